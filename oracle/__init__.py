@@ -1,0 +1,252 @@
+"""CPU fp64 oracle — TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, obviously-correct implementations of what the hot path computes
+(paper Sec. III-A layer computations on a depth slab; Sec. III-C passes FP/BD/BF).
+The arithmetic lives in `h3d_oracle.c` (direct loop nests, fp64) and, for the
+index-only and library-primitive steps, in numpy below.  Nothing here imports
+or is imported by the HIP package; only tests, the smoke check and the bench's
+CPU-baseline leg may use it.
+
+Pins (tests/test_oracle_*.py): brute force against an independently written
+definition, a library cross-check (torch CPU float64 + autograd), the
+delta-input identity, closed forms for constant inputs, linearity, the adjoint
+identity, finite differences, bit-exact shard consistency, the conv-FLOP and
+parameter counts printed in Table I.  Unpinned by the paper itself: every
+numeric layer output (the paper prints no worked example).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libh3d_oracle.so")
+_SRC = os.path.join(_HERE, "h3d_oracle.c")
+
+ACT_NONE, ACT_RELU, ACT_LEAKY = 0, 1, 2
+POOL_AVG, POOL_MAX = 0, 1
+FACE_D_LO, FACE_D_HI = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _SO, _SRC, "-lm"])
+    return _SO
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+@dataclass
+class Slab:
+    """A depth slab of an N,C,D,H,W tensor; `a` is float64 [N, C, halo_lo+d+halo_hi, H, W]."""
+    a: np.ndarray
+    halo_lo: int = 0
+    halo_hi: int = 0
+    d_offset: int = 0
+    d_global: int | None = None
+
+    def __post_init__(self):
+        self.a = np.ascontiguousarray(self.a, dtype=np.float64)
+        assert self.a.ndim == 5
+        if self.d_global is None:
+            self.d_global = self.d
+        assert self.d >= 0
+
+    @property
+    def d(self) -> int:
+        return self.a.shape[2] - self.halo_lo - self.halo_hi
+
+    @property
+    def interior(self) -> np.ndarray:
+        return self.a[:, :, self.halo_lo:self.halo_lo + self.d]
+
+    def geom(self):
+        n, c, _, h, w = self.a.shape
+        return (ctypes.c_int64 * 9)(n, c, self.d, h, w, self.halo_lo, self.halo_hi, self.d_offset, self.d_global)
+
+    def like(self, channels: int, halo_lo: int = 0, halo_hi: int = 0, fill: float = np.nan) -> "Slab":
+        n, _, _, h, w = self.a.shape
+        a = np.full((n, channels, halo_lo + self.d + halo_hi, h, w), fill, dtype=np.float64)
+        return Slab(a, halo_lo, halo_hi, self.d_offset, self.d_global)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _chk(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: status {rc}")
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def conv3d_fwd(x: Slab, w, bias, cout_halo=(0, 0), act=ACT_NONE, alpha=0.0) -> Slab:
+    """z = act(b + w (*) x~), 3x3x3, stride 1, zero padding 1 (Table I caption; Sec. III-A)."""
+    w = _f64(w)
+    bias = _f64(bias)
+    assert w.shape[1:] == (x.a.shape[1], 3, 3, 3)
+    z = x.like(w.shape[0], cout_halo[0], cout_halo[1])
+    _chk(_L().orc_conv3d_fwd(_p(x.a), x.geom(), _p(w), _p(bias), _p(z.a), z.geom(), int(act),
+                             ctypes.c_double(alpha)), "conv3d_fwd")
+    return z
+
+
+def conv3d_bwd_data(dz: Slab, z: Slab | None, w, dx_halo=(0, 0), act=ACT_NONE, alpha=0.0) -> Slab:
+    """BD pass (Sec. III-C): dx = sum_{co,k} w[co,ci,k] * (dz*act'(z))~[q-k+1]."""
+    w = _f64(w)
+    assert w.shape[0] == dz.a.shape[1] and w.shape[2:] == (3, 3, 3)
+    dx = dz.like(w.shape[1], dx_halo[0], dx_halo[1])
+    _chk(_L().orc_conv3d_bwd_data(_p(dz.a), dz.geom(), _p(z.a) if z is not None else None,
+                                  z.geom() if z is not None else None, _p(w), _p(dx.a), dx.geom(), int(act),
+                                  ctypes.c_double(alpha)), "conv3d_bwd_data")
+    return dx
+
+
+def conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, act=ACT_NONE, alpha=0.0):
+    """BF pass (Sec. III-C): the shard's partial dw [cout,cin,3,3,3] and db [cout]."""
+    cin, cout = x.a.shape[1], dz.a.shape[1]
+    dw = np.zeros((cout, cin, 3, 3, 3), dtype=np.float64)
+    db = np.zeros((cout,), dtype=np.float64)
+    _chk(_L().orc_conv3d_bwd_filter(_p(x.a), x.geom(), _p(dz.a), dz.geom(), _p(z.a) if z is not None else None,
+                                    z.geom() if z is not None else None, _p(dw), _p(db), int(act),
+                                    ctypes.c_double(alpha)), "conv3d_bwd_filter")
+    return dw, db
+
+
+def pool3d_fwd(x: Slab, mode: int, y_halo=(0, 0)) -> Slab:
+    """2x2x2 stride-2 pooling of the interior (Table I: stride-2 pooling)."""
+    n, c, _, h, w = x.a.shape
+    y = Slab(np.zeros((n, c, y_halo[0] + x.d // 2 + y_halo[1], h // 2, w // 2)), y_halo[0], y_halo[1],
+             x.d_offset // 2, x.d_global // 2)
+    _chk(_L().orc_pool3d_fwd(_p(x.a), x.geom(), _p(y.a), y.geom(), int(mode)), "pool3d_fwd")
+    return y
+
+
+def pool3d_bwd(dy: Slab, x: Slab | None, mode: int, dx_halo=(0, 0)) -> Slab:
+    n, c, _, h, w = dy.a.shape
+    dx = Slab(np.zeros((n, c, dx_halo[0] + 2 * dy.d + dx_halo[1], 2 * h, 2 * w)), dx_halo[0], dx_halo[1],
+              dy.d_offset * 2, dy.d_global * 2)
+    _chk(_L().orc_pool3d_bwd(_p(dy.a), dy.geom(), _p(x.a) if x is not None else None,
+                             x.geom() if x is not None else None, _p(dx.a), dx.geom(), int(mode)), "pool3d_bwd")
+    return dx
+
+
+def deconv2_fwd(x: Slab, w, bias) -> Slab:
+    """2x2x2 stride-2 transposed convolution, w [cin][cout][2][2][2] (U-Net up-sampling, Sec. II-C)."""
+    w = _f64(w)
+    bias = _f64(bias)
+    n, c, _, h, ww = x.a.shape
+    assert w.shape == (c, w.shape[1], 2, 2, 2)
+    y = Slab(np.zeros((n, w.shape[1], 2 * x.d, 2 * h, 2 * ww)), 0, 0, 2 * x.d_offset, 2 * x.d_global)
+    xi = Slab(x.interior, 0, 0, x.d_offset, x.d_global)
+    _chk(_L().orc_deconv2_fwd(_p(xi.a), xi.geom(), _p(w), _p(bias), _p(y.a), y.geom()), "deconv2_fwd")
+    return y
+
+
+def deconv2_bwd_data(dy: Slab, w) -> Slab:
+    w = _f64(w)
+    n, c, _, h, ww = dy.a.shape
+    dyi = Slab(dy.interior, 0, 0, dy.d_offset, dy.d_global)
+    dx = Slab(np.zeros((n, w.shape[0], dy.d // 2, h // 2, ww // 2)), 0, 0, dy.d_offset // 2, dy.d_global // 2)
+    _chk(_L().orc_deconv2_bwd_data(_p(dyi.a), dyi.geom(), _p(w), _p(dx.a), dx.geom()), "deconv2_bwd_data")
+    return dx
+
+
+def deconv2_bwd_filter(x: Slab, dy: Slab):
+    xi = Slab(x.interior, 0, 0, x.d_offset, x.d_global)
+    dyi = Slab(dy.interior, 0, 0, dy.d_offset, dy.d_global)
+    cin, cout = xi.a.shape[1], dyi.a.shape[1]
+    dw = np.zeros((cin, cout, 2, 2, 2))
+    db = np.zeros((cout,))
+    _chk(_L().orc_deconv2_bwd_filter(_p(xi.a), xi.geom(), _p(dyi.a), dyi.geom(), _p(dw), _p(db)), "deconv2_bwd_filter")
+    return dw, db
+
+
+# ------------------------------------------------------------ index-only steps (numpy slicing)
+
+def halo_pack(t: Slab, face: int, width: int) -> np.ndarray:
+    """The `width` outermost INTERIOR planes next to `face`, as [n][c][width][h][w] (Sec. III-A pack kernels)."""
+    assert 0 < width <= t.d
+    lo = t.halo_lo if face == FACE_D_LO else t.halo_lo + t.d - width
+    return t.a[:, :, lo:lo + width].copy()
+
+
+def halo_unpack(buf: np.ndarray | None, t: Slab, face: int, width: int) -> None:
+    """Write `buf` (or zeros: global boundary) into the `width` HALO planes adjacent to the interior at `face`."""
+    if face == FACE_D_LO:
+        assert width <= t.halo_lo
+        lo = t.halo_lo - width
+    else:
+        assert width <= t.halo_hi
+        lo = t.halo_lo + t.d
+    t.a[:, :, lo:lo + width] = 0.0 if buf is None else buf
+
+
+def concat_c(a: Slab, b: Slab) -> Slab:
+    """Channel concat of the interiors, `a` first (skip connection of the U-Net, Sec. III-A)."""
+    return Slab(np.concatenate([a.interior, b.interior], axis=1), 0, 0, a.d_offset, a.d_global)
+
+
+def split_c(g: Slab, ca: int):
+    gi = g.interior
+    return (Slab(gi[:, :ca].copy(), 0, 0, g.d_offset, g.d_global), Slab(gi[:, ca:].copy(), 0, 0, g.d_offset, g.d_global))
+
+
+# ------------------------------------------------------------ dense / loss (library matmul as the step)
+
+def _act(y, act, alpha):
+    if act == ACT_NONE:
+        return y
+    s = alpha if act == ACT_LEAKY else 0.0
+    return np.where(y > 0, y, s * y)
+
+
+def dense_fwd(x, w, b, act=ACT_NONE, alpha=0.0):
+    """y = act(x W^T + b); x [m,k], W [n,k] (fully-connected layers of Table I)."""
+    y = _f64(x) @ _f64(w).T
+    if b is not None:
+        y = y + _f64(b)
+    return _act(y, act, alpha)
+
+
+def dense_bwd(x, w, y, dy, act=ACT_NONE, alpha=0.0):
+    """Returns dx [m,k], dW [n,k], db [n]; `y` is the saved activated output."""
+    g = _f64(dy)
+    if act != ACT_NONE:
+        s = alpha if act == ACT_LEAKY else 0.0
+        g = g * np.where(_f64(y) > 0, 1.0, s)
+    return g @ _f64(w), g.T @ _f64(x), g.sum(axis=0)
+
+
+def mse_fwd_bwd(pred, target):
+    """Mean squared error over all entries (Sec. IV: loss) and its gradient."""
+    p, t = _f64(pred), _f64(target)
+    diff = p - t
+    return float(np.mean(diff * diff)), 2.0 * diff / diff.size
+
+
+def num_threads() -> int:
+    return int(_L().orc_num_threads())
+
+
+# ------------------------------------------------------------ bookkeeping pinned by Table I
+
+def conv_flops(cin: int, cout: int, out_voxels: int, k: int = 3) -> int:
+    """2 * k^3 * Cin * Cout per output voxel (convention fixed by Table I's conv-op counts)."""
+    return 2 * k ** 3 * cin * cout * out_voxels

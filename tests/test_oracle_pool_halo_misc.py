@@ -1,0 +1,181 @@
+"""Pins for the oracle's pooling, halo pack/unpack, 2x2x2 transposed conv, concat, dense and loss (no GPU)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as orc
+from oracle import Slab
+
+RNG = np.random.default_rng(2007)
+
+
+def rand(*shape):
+    return RNG.uniform(-1.0, 1.0, size=shape)
+
+
+# ---------------------------------------------------------------- pooling
+
+@pytest.mark.parametrize("mode", [orc.POOL_AVG, orc.POOL_MAX])
+def test_pool_constant_and_sums(mode):
+    x = Slab(np.full((2, 3, 4, 6, 8), 0.75))
+    y = orc.pool3d_fwd(x, mode)
+    assert y.a.shape == (2, 3, 2, 3, 4) and np.all(y.a == 0.75)
+    dy = Slab(rand(2, 3, 2, 3, 4))
+    xr = Slab(rand(2, 3, 4, 6, 8))
+    dx = orc.pool3d_bwd(dy, xr, mode)
+    assert abs(dx.a.sum() - dy.a.sum()) < 1e-12
+    # per-window sums are preserved too
+    win = dx.a.reshape(2, 3, 2, 2, 3, 2, 4, 2).sum(axis=(3, 5, 7))
+    np.testing.assert_allclose(win, dy.a, atol=1e-15)
+
+
+def test_pool_definition_by_reshape():
+    x = rand(1, 2, 4, 4, 6)
+    blocks = x.reshape(1, 2, 2, 2, 2, 2, 3, 2)
+    assert np.allclose(orc.pool3d_fwd(Slab(x), orc.POOL_AVG).a, blocks.mean(axis=(3, 5, 7)), atol=1e-15)
+    assert np.array_equal(orc.pool3d_fwd(Slab(x), orc.POOL_MAX).a, blocks.max(axis=(3, 5, 7)))
+
+
+def test_avg_pool_adjoint():
+    x, g = rand(1, 2, 4, 4, 4), rand(1, 2, 2, 2, 2)
+    lhs = np.sum(orc.pool3d_fwd(Slab(x), orc.POOL_AVG).a * g)
+    rhs = np.sum(x * orc.pool3d_bwd(Slab(g), None, orc.POOL_AVG).a)
+    assert abs(lhs - rhs) < 1e-13
+
+
+def test_max_pool_tie_goes_to_first_in_row_major_order():
+    x = np.zeros((1, 1, 2, 2, 4))
+    x[0, 0, :, :, 2:] = [[[1.0, 5.0], [5.0, 2.0]], [[5.0, 0.0], [0.0, 5.0]]]
+    dy = np.array([3.0, 7.0]).reshape(1, 1, 1, 1, 2)
+    dx = orc.pool3d_bwd(Slab(dy), Slab(x), orc.POOL_MAX).a
+    expect = np.zeros_like(x)
+    expect[0, 0, 0, 0, 0] = 3.0      # all-equal window: k = (0,0,0)
+    expect[0, 0, 0, 0, 3] = 7.0      # first of the four 5.0 in (kd,kh,kw) order is (0,0,1)
+    assert np.array_equal(dx, expect)
+
+
+def test_pool_against_torch():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    x = rand(2, 3, 4, 6, 8)
+    g = rand(2, 3, 2, 3, 4)
+    for mode, fn in [(orc.POOL_AVG, F.avg_pool3d), (orc.POOL_MAX, F.max_pool3d)]:
+        tx = torch.tensor(x, requires_grad=True)
+        ty = fn(tx, 2, 2)
+        ty.backward(torch.tensor(g))
+        np.testing.assert_allclose(orc.pool3d_fwd(Slab(x), mode).a, ty.detach().numpy(), atol=1e-15)
+        np.testing.assert_allclose(orc.pool3d_bwd(Slab(g), Slab(x), mode).a, tx.grad.numpy(), atol=1e-15)
+
+
+def test_pool_on_slab_touches_interior_only_and_matches_full():
+    full = rand(1, 2, 8, 4, 4)
+    yf = orc.pool3d_fwd(Slab(full), orc.POOL_MAX)
+    a = np.full((1, 2, 6, 4, 4), np.nan)
+    a[:, :, 1:5] = full[:, :, 4:8]
+    ys = orc.pool3d_fwd(Slab(a, 1, 1, 4, 8), orc.POOL_MAX, y_halo=(1, 1))
+    assert (ys.d_offset, ys.d_global) == (2, 4)
+    assert np.array_equal(ys.interior, yf.a[:, :, 2:4])
+    assert not ys.a[:, :, 0].any() and not ys.a[:, :, -1].any()
+    with pytest.raises(ValueError):
+        orc.pool3d_fwd(Slab(a[:, :, 1:4], 0, 0, 4, 8), orc.POOL_AVG)    # odd depth: window would straddle a face
+
+
+# ---------------------------------------------------------------- halo pack / unpack
+
+def test_halo_exchange_between_neighbouring_shards_reproduces_full_volume():
+    full = rand(2, 3, 12, 4, 5)
+    shards = []
+    for s in range(3):
+        a = np.full((2, 3, 4 + 4, 4, 5), 777.0)     # canary everywhere but the interior
+        a[:, :, 2:6] = full[:, :, 4 * s:4 * s + 4]
+        shards.append(Slab(a, 2, 2, 4 * s, 12))
+    for width in (1, 2):
+        for s in range(3):
+            lo_buf = orc.halo_pack(shards[s - 1], orc.FACE_D_HI, width) if s > 0 else None
+            hi_buf = orc.halo_pack(shards[s + 1], orc.FACE_D_LO, width) if s < 2 else None
+            orc.halo_unpack(lo_buf, shards[s], orc.FACE_D_LO, width)
+            orc.halo_unpack(hi_buf, shards[s], orc.FACE_D_HI, width)
+        for s in range(3):
+            t = shards[s]
+            for i, g in enumerate(range(4 * s - 2, 4 * s + 6)):
+                plane = t.a[:, :, i]
+                dist = (4 * s - g) if g < 4 * s else (g - (4 * s + 3) if g > 4 * s + 3 else 0)
+                if dist > width:
+                    assert np.all(plane == 777.0)           # not addressed: untouched
+                elif 0 <= g < 12:
+                    assert np.array_equal(plane, full[:, :, g])
+                else:
+                    assert not plane.any()                   # global boundary: zero fill
+
+
+def test_pack_layout_and_roundtrip():
+    t = Slab(np.arange(2 * 2 * 5 * 2 * 3, dtype=np.float64).reshape(2, 2, 5, 2, 3), 1, 1)
+    lo, hi = orc.halo_pack(t, orc.FACE_D_LO, 1), orc.halo_pack(t, orc.FACE_D_HI, 1)
+    assert lo.shape == (2, 2, 1, 2, 3)
+    assert np.array_equal(lo[:, :, 0], t.a[:, :, 1]) and np.array_equal(hi[:, :, 0], t.a[:, :, 3])
+    u = Slab(np.zeros_like(t.a), 1, 1)
+    orc.halo_unpack(lo, u, orc.FACE_D_HI, 1)
+    assert np.array_equal(orc.halo_pack(Slab(u.a[:, :, 2:], 0, 0), orc.FACE_D_HI, 1), lo)
+
+
+# ---------------------------------------------------------------- 2x2x2 stride-2 transposed convolution
+
+def test_deconv_is_adjoint_of_stride2_correlation_and_closed_form():
+    Ci, Co = 3, 2
+    x, w, y = rand(1, Ci, 2, 3, 2), rand(Ci, Co, 2, 2, 2), rand(1, Co, 4, 6, 4)
+    up = orc.deconv2_fwd(Slab(x), w, None)
+    # stride-2 correlation written out independently
+    conv = np.zeros_like(x)
+    for ci, q, h, v in itertools.product(range(Ci), range(2), range(3), range(2)):
+        conv[0, ci, q, h, v] = np.sum(w[ci] * y[0, :, 2 * q:2 * q + 2, 2 * h:2 * h + 2, 2 * v:2 * v + 2])
+    assert abs(np.sum(up.a * y) - np.sum(x * conv)) < 1e-12
+    np.testing.assert_allclose(orc.deconv2_bwd_data(Slab(y), w).a, conv, atol=1e-13)
+    ones = orc.deconv2_fwd(Slab(np.ones((1, Ci, 2, 2, 2))), np.ones((Ci, Co, 2, 2, 2)), np.full(Co, 0.5))
+    assert np.all(ones.a == Ci + 0.5)
+
+
+def test_deconv_against_torch():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    Ci, Co = 3, 4
+    x, w, b, g = rand(2, Ci, 2, 3, 2), rand(Ci, Co, 2, 2, 2), rand(Co), rand(2, Co, 4, 6, 4)
+    tx, tw, tb = (torch.tensor(v, requires_grad=True) for v in (x, w, b))
+    ty = F.conv_transpose3d(tx, tw, tb, stride=2)
+    ty.backward(torch.tensor(g))
+    np.testing.assert_allclose(orc.deconv2_fwd(Slab(x), w, b).a, ty.detach().numpy(), atol=1e-13)
+    np.testing.assert_allclose(orc.deconv2_bwd_data(Slab(g), w).a, tx.grad.numpy(), atol=1e-13)
+    dw, db = orc.deconv2_bwd_filter(Slab(x), Slab(g))
+    np.testing.assert_allclose(dw, tw.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(db, tb.grad.numpy(), atol=1e-12)
+
+
+def test_concat_split():
+    a, b = Slab(rand(1, 2, 3, 2, 2)), Slab(rand(1, 3, 3, 2, 2))
+    c = orc.concat_c(a, b)
+    assert np.array_equal(c.a[:, :2], a.a) and np.array_equal(c.a[:, 2:], b.a)
+    ga, gb = orc.split_c(c, 2)
+    assert np.array_equal(ga.a, a.a) and np.array_equal(gb.a, b.a)
+
+
+# ---------------------------------------------------------------- dense + loss
+
+def test_dense_and_mse_against_torch_and_finite_differences():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    x, w, b, t = rand(4, 7), rand(5, 7), rand(5), rand(4, 5)
+    tx, tw, tb = (torch.tensor(v, requires_grad=True) for v in (x, w, b))
+    ty = F.leaky_relu(F.linear(tx, tw, tb), 0.01)
+    loss = F.mse_loss(ty, torch.tensor(t))
+    loss.backward()
+    y = orc.dense_fwd(x, w, b, orc.ACT_LEAKY, 0.01)
+    L, dy = orc.mse_fwd_bwd(y, t)
+    dx, dw, db = orc.dense_bwd(x, w, y, dy, orc.ACT_LEAKY, 0.01)
+    assert abs(L - loss.item()) < 1e-14
+    np.testing.assert_allclose(y, ty.detach().numpy(), atol=1e-14)
+    np.testing.assert_allclose(dx, tx.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(dw, tw.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(db, tb.grad.numpy(), atol=1e-14)
+    # closed form: pred = target + 1 everywhere -> loss 1, gradient 2/size
+    L1, g1 = orc.mse_fwd_bwd(t + 1.0, t)
+    assert abs(L1 - 1.0) < 1e-15 and np.allclose(g1, 2.0 / t.size)
