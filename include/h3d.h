@@ -1,0 +1,164 @@
+/*
+ * h3d — per-GPU hot path of spatially-partitioned ("hybrid-parallel") 3-D CNN
+ * training on AMD MI355X (gfx950): dense 3x3x3 convolution forward /
+ * backward-data / backward-filter with fused bias and (leaky-)ReLU, 2x2x2
+ * pooling, and halo pack/unpack, on one GPU's depth slab of an N,C,D,H,W
+ * sample (paper Sec. II-B "spatial partitioning", Sec. III-A, Sec. III-C).
+ *
+ * Plain C ABI.  No C++ types, no exceptions, no torch types.
+ *
+ * POINTERS.  Every `data`, weight, bias, gradient, buffer and workspace pointer
+ * is a DEVICE pointer owned by the caller (for instance a torch tensor's
+ * data_ptr()).  Descriptor structs (`h3d_tensor`) and the handle are HOST memory.
+ * The library never allocates or frees device memory; scratch space is passed
+ * in as a workspace whose size is queried with h3d_*_workspace_bytes.
+ *
+ * ASYNCHRONY.  Every compute call only enqueues kernels on `stream`
+ * (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *
+ * ERRORS.  Every call returns an h3d_status.  Argument violations are found on
+ * the host BEFORE anything is launched; nothing aborts or throws.
+ * h3d_last_error(handle) gives a human-readable reason for the last failure
+ * on that handle.
+ *
+ * TENSORS.  N,C,D,H,W, fully packed, W fastest (paper Sec. III "Notation").
+ * A slab stores halo_lo + d + halo_hi depth planes per (n,c).  Interior plane
+ * p in [0,d) is global plane d_offset + p of a sample whose unsharded depth is
+ * d_global; halo plane p in [-halo_lo,0) or [d,d+halo_hi) holds the
+ * neighbouring shard's boundary data (Sec. II-B: halo exchange).  Everything
+ * outside the global volume [0,d_global) x [0,h) x [0,w) is zero ("same"
+ * padding, Table I caption) and is never read, whatever the halo planes there
+ * contain.  An unsharded tensor is the case halo 0, d_offset 0, d_global = d.
+ * H and W are not partitioned (the paper evaluates depth partitioning, Sec. V).
+ */
+#ifndef H3D_H
+#define H3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { H3D_F32 = 0, H3D_BF16 = 1 } h3d_dtype;
+
+typedef enum {
+  H3D_OK = 0,
+  H3D_EINVAL = -1,       /* NULL pointer, shape/dtype mismatch, bad enum            */
+  H3D_EUNSUPPORTED = -2, /* valid request this build has no kernel for              */
+  H3D_EWORKSPACE = -3,   /* workspace NULL or smaller than h3d_*_workspace_bytes    */
+  H3D_EHALO = -4,        /* a needed plane inside the global volume is not stored   */
+  H3D_EHIP = -5          /* HIP runtime error on launch                             */
+} h3d_status;
+
+typedef enum { H3D_ACT_NONE = 0, H3D_ACT_RELU = 1, H3D_ACT_LEAKY = 2 } h3d_act;
+typedef enum { H3D_POOL_AVG = 0, H3D_POOL_MAX = 1 } h3d_pool;
+typedef enum { H3D_FACE_D_LO = 0, H3D_FACE_D_HI = 1 } h3d_face;
+typedef enum { H3D_OP_FWD = 0, H3D_OP_BWD_DATA = 1, H3D_OP_BWD_FILTER = 2 } h3d_conv_op;
+
+typedef struct {
+  void* data;               /* DEVICE pointer to [n][c][halo_lo+d+halo_hi][h][w]          */
+  int32_t dtype;            /* h3d_dtype                                                   */
+  int32_t n, c;             /* samples, channels                                           */
+  int32_t d, h, w;          /* INTERIOR extents of this shard                              */
+  int32_t halo_lo, halo_hi; /* stored halo planes below / above the interior              */
+  int64_t d_offset;         /* global depth index of interior plane 0                      */
+  int64_t d_global;         /* depth of the unsharded sample                               */
+} h3d_tensor;
+
+/* Handle: host object caching device properties and the last error text.
+ * Not thread-safe; use one per host thread.  Bound to the device current at creation. */
+h3d_status h3d_create(void** handle);
+h3d_status h3d_destroy(void* handle);
+const char* h3d_last_error(void* handle); /* handle-owned string, valid until the next call */
+
+/* ---- 3x3x3 convolution, stride 1, zero padding 1 (Table I caption; FP/BD/BF of Sec. III-C) ----
+ *
+ * Weights w: [cout][cin][3][3][3] packed, same dtype as the activations.
+ * bias: fp32 [cout] or NULL (the paper's CosmoFlow variant drops conv biases, Sec. IV).
+ * act/alpha: z = y > 0 ? y : slope*y with slope = alpha (LEAKY), 0 (RELU), 1 (NONE).
+ *
+ * Workspace bytes needed by `op` for these shapes (0 is possible).  Returns 0 on bad arguments. */
+size_t h3d_conv3d_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* z);
+
+/* Forward: z[n,co,p] = act(bias[co] + sum_{ci,kd,kh,kw} w[co,ci,kd,kh,kw] * x~[n,ci,p+k-1])
+ * (cross-correlation) for every stored plane p of z, i.e. p in [-z.halo_lo, d+z.halo_hi):
+ * a z with halos asks for "halo recompute" and needs x to store one plane more on that side.
+ * Planes of z outside the global volume are written as ZERO (they are the next layer's padding).
+ * x and z must agree in n,d,h,w,d_offset,d_global,dtype.  H3D_EHALO if x lacks a needed plane. */
+h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias,
+                          h3d_tensor* z, int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward-data: g = dz * (z > 0 ? 1 : slope) with z the saved forward OUTPUT
+ * (z == NULL or act NONE: g = dz);  dx[n,ci,q] = sum_{co,k} w[co,ci,k] * g~[n,co,q-k+1]
+ * for every stored plane q of dx.  dz (and z) must store the planes q-1..q+1 that lie inside
+ * the volume (their halos come from the neighbours by halo exchange), else H3D_EHALO. */
+h3d_status h3d_conv3d_bwd_data(void* handle, const h3d_tensor* dz, const h3d_tensor* z, const void* w,
+                               h3d_tensor* dx, int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward-filter: dw[co,ci,k] = sum_n sum_{p in interior} g[n,co,p] * x~[n,ci,p+k-1], db[co] = sum g.
+ * dw fp32 [cout][cin][3][3][3] and db fp32 [cout] (or NULL) are OVERWRITTEN with this shard's
+ * partial gradient (the sum over shards and data-parallel replicas is the allreduce of Sec. III-A,
+ * outside this library).  Deterministic: a fixed split of the voxel range and a fixed-order second
+ * stage, so two calls with the same inputs return identical bits. */
+h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z,
+                                 float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
+                                 void* stream);
+
+/* ---- 2x2x2 stride-2 pooling of the shard interior (Table I: stride-2 pooling; Sec. III-A) ----
+ * y interior extents are x's halved; d, h, w and d_offset of x must be even so that no window
+ * straddles a shard face (else H3D_EUNSUPPORTED).  Halo planes of x and y are neither read nor
+ * written.  AVG: mean of 8.  MAX: maximum of 8. */
+h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tensor* y, int mode, void* stream);
+/* AVG: dx[2q+k] = dy[q]/8.  MAX: dy[q] goes to the FIRST maximal element of the window of x (the
+ * forward input, required) in (kd,kh,kw) row-major order, zero to the other seven. */
+h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, h3d_tensor* dx, int mode,
+                          void* stream);
+
+/* ---- halo pack / unpack of the depth faces (Sec. III-A: packing/unpacking kernels for the
+ *      neighbour communication of boundary regions) ---- bit-exact copies.
+ * Face buffer layout: [n][c][width][h][w] packed, same dtype as t. */
+size_t h3d_halo_bytes(const h3d_tensor* t, int width);
+/* pack: copy the `width` outermost INTERIOR planes at `face` into buf (what the neighbour needs). */
+h3d_status h3d_halo_pack(void* handle, const h3d_tensor* t, int face, int width, void* buf, void* stream);
+/* unpack: write buf into the `width` HALO planes adjacent to the interior at `face`
+ * (width <= that halo); buf == NULL zero-fills them (global boundary). */
+h3d_status h3d_halo_unpack(void* handle, const void* buf, h3d_tensor* t, int face, int width, void* stream);
+
+/* ---- 2x2x2 stride-2 transposed convolution (U-Net up-sampling "deconvolution", Sec. III-A) ----
+ * w: [cin][cout][2][2][2]; y[n,co,2q+k] = bias[co] + sum_ci w[ci,co,k] * x[n,ci,q].  Interiors only;
+ * y interior extents are twice x's. */
+size_t h3d_deconv2_workspace_bytes(void* handle, int op /* h3d_conv_op */, const h3d_tensor* x, const h3d_tensor* y);
+h3d_status h3d_deconv2_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* y,
+                           void* ws, size_t ws_bytes, void* stream);
+/* dx[n,ci,q] = sum_{co,k} w[ci,co,k] * dy[n,co,2q+k] */
+h3d_status h3d_deconv2_bwd_data(void* handle, const h3d_tensor* dy, const void* w, h3d_tensor* dx, void* ws,
+                                size_t ws_bytes, void* stream);
+/* dw[ci,co,k] = sum_{n,q} x[n,ci,q] * dy[n,co,2q+k], db[co] = sum dy: dw fp32 [cin][cout][2][2][2] and
+ * db fp32 [cout] (or NULL) are overwritten; deterministic (fixed split + fixed-order second stage). */
+h3d_status h3d_deconv2_bwd_filter(void* handle, const h3d_tensor* x, const h3d_tensor* dy, float* dw, float* db,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/* ---- channel concat / split of interiors (U-Net skip connections, Sec. III-A) ---- bit-exact.
+ * out channels [0,a.c) = a, [a.c, a.c+b.c) = b.  split is the inverse (the backward of concat). */
+h3d_status h3d_concat_c(void* handle, const h3d_tensor* a, const h3d_tensor* b, h3d_tensor* out, void* stream);
+h3d_status h3d_split_c(void* handle, const h3d_tensor* in, h3d_tensor* a, h3d_tensor* b, void* stream);
+
+/* ---- fully-connected layers and the MSE loss that close the CosmoFlow stack (Table I, Sec. IV) ----
+ * x [m][k], w [n][k] (dtype of x), bias fp32 [n] or NULL, y [m][n] (dtype of x): y = act(x w^T + bias).
+ * m <= 8 rows per call (the per-GPU sample count after the spatial layers), else H3D_EUNSUPPORTED. */
+h3d_status h3d_dense_fwd(void* handle, const void* x, const void* w, const float* bias, void* y, int dtype, int m,
+                         int n, int k, int act, float alpha, void* stream);
+/* dy [m][n], y saved output; dx [m][k] (dtype) or NULL, dw fp32 [n][k], db fp32 [n] or NULL; overwritten. */
+h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, const void* y, const void* dy, void* dx,
+                         float* dw, float* db, int dtype, int m, int n, int k, int act, float alpha, void* stream);
+/* loss[0] (fp32, device) = mean over all `count` entries of (pred-target)^2; dpred = 2 (pred-target)/count
+ * (dtype of pred); target fp32.  count <= 65536. */
+h3d_status h3d_mse_fwd_bwd(void* handle, const void* pred, const float* target, float* loss, void* dpred, int dtype,
+                           int count, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* H3D_H */

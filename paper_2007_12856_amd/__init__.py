@@ -1,0 +1,306 @@
+"""Python binding of libh3d (the C ABI declared in include/h3d.h).
+
+Argument marshalling only: every function here builds the C descriptors and
+calls the entry point of the same name; all arithmetic runs in the HIP kernels.
+PyTorch is used for device memory (`tensor.data_ptr()`) and the current stream.
+There is no CPU or PyTorch fallback: if libh3d.so is missing or a call fails,
+an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libh3d.so")
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_LEAKY = 0, 1, 2
+POOL_AVG, POOL_MAX = 0, 1
+FACE_D_LO, FACE_D_HI = 0, 1
+OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
+STATUS = {0: "H3D_OK", -1: "H3D_EINVAL", -2: "H3D_EUNSUPPORTED", -3: "H3D_EWORKSPACE", -4: "H3D_EHALO", -5: "H3D_EHIP"}
+
+
+class H3DError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS.get(status, status)}: {msg}")
+        self.status = status
+
+
+class h3d_tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("n", ctypes.c_int32), ("c", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("h", ctypes.c_int32), ("w", ctypes.c_int32), ("halo_lo", ctypes.c_int32),
+                ("halo_hi", ctypes.c_int32), ("d_offset", ctypes.c_int64), ("d_global", ctypes.c_int64)]
+
+
+_lib = None
+_P = ctypes.c_void_p
+_T = ctypes.POINTER(h3d_tensor)
+_SIGNATURES = {
+    "h3d_create": (ctypes.c_int, [ctypes.POINTER(_P)]),
+    "h3d_destroy": (ctypes.c_int, [_P]),
+    "h3d_last_error": (ctypes.c_char_p, [_P]),
+    "h3d_conv3d_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
+    "h3d_conv3d_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_conv3d_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_conv3d_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
+    "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
+    "h3d_halo_bytes": (ctypes.c_size_t, [_T, ctypes.c_int]),
+    "h3d_halo_pack": (ctypes.c_int, [_P, _T, ctypes.c_int, ctypes.c_int, _P, _P]),
+    "h3d_halo_unpack": (ctypes.c_int, [_P, _P, _T, ctypes.c_int, ctypes.c_int, _P]),
+    "h3d_deconv2_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
+    "h3d_deconv2_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, _P, ctypes.c_size_t, _P]),
+    "h3d_deconv2_bwd_data": (ctypes.c_int, [_P, _T, _P, _T, _P, ctypes.c_size_t, _P]),
+    "h3d_deconv2_bwd_filter": (ctypes.c_int, [_P, _T, _T, _P, _P, _P, ctypes.c_size_t, _P]),
+    "h3d_concat_c": (ctypes.c_int, [_P, _T, _T, _T, _P]),
+    "h3d_split_c": (ctypes.c_int, [_P, _T, _T, _T, _P]),
+    "h3d_dense_fwd": (ctypes.c_int, [_P, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_float, _P]),
+    "h3d_dense_bwd": (ctypes.c_int, [_P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
+    "h3d_mse_fwd_bwd": (ctypes.c_int, [_P, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, _P]),
+}
+
+
+def lib():
+    """The loaded C library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2007_12856_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+_handle = None
+
+
+def h3d_create():
+    """A new library handle (host object; bound to the current device)."""
+    h = _P()
+    st = lib().h3d_create(ctypes.byref(h))
+    if st != 0:
+        raise H3DError(st, "h3d_create failed")
+    return h
+
+
+def h3d_destroy(h) -> None:
+    st = lib().h3d_destroy(h)
+    if st != 0:
+        raise H3DError(st, "h3d_destroy failed")
+
+
+def h3d_last_error(h=None) -> str:
+    return (lib().h3d_last_error(h if h is not None else handle()) or b"").decode()
+
+
+def handle():
+    """The module-wide handle the wrappers below use."""
+    global _handle
+    if _handle is None:
+        _handle = h3d_create()
+    return _handle
+
+
+def _check(st: int):
+    if st != 0:
+        raise H3DError(st, h3d_last_error())
+
+
+def _stream():
+    import torch
+    return _P(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else _P(t.data_ptr())
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+@dataclass
+class Slab:
+    """A depth slab: `t` is a contiguous device tensor [N, C, halo_lo + d + halo_hi, H, W]."""
+    t: object
+    halo_lo: int = 0
+    halo_hi: int = 0
+    d_offset: int = 0
+    d_global: int | None = None
+
+    def __post_init__(self):
+        assert self.t.dim() == 5 and self.t.is_contiguous()
+        if self.d_global is None:
+            self.d_global = self.d
+
+    @property
+    def d(self) -> int:
+        return self.t.shape[2] - self.halo_lo - self.halo_hi
+
+    @property
+    def interior(self):
+        return self.t[:, :, self.halo_lo:self.halo_lo + self.d]
+
+    def desc(self) -> h3d_tensor:
+        n, c, _, h, w = self.t.shape
+        return h3d_tensor(self.t.data_ptr(), _dtype_code(self.t), n, c, self.d, h, w, self.halo_lo, self.halo_hi,
+                          self.d_offset, self.d_global)
+
+    def like(self, channels: int, halo_lo: int = 0, halo_hi: int = 0, d: int | None = None, h: int | None = None,
+             w: int | None = None, d_offset: int | None = None, d_global: int | None = None) -> "Slab":
+        import torch
+        n, _, _, hh, ww = self.t.shape
+        d = self.d if d is None else d
+        t = torch.empty((n, channels, halo_lo + d + halo_hi, hh if h is None else h, ww if w is None else w),
+                        dtype=self.t.dtype, device=self.t.device)
+        return Slab(t, halo_lo, halo_hi, self.d_offset if d_offset is None else d_offset,
+                    self.d_global if d_global is None else d_global)
+
+
+class Workspace:
+    """A caller-owned, growable device scratch buffer handed to the calls that need one."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes: int):
+        import torch
+        if nbytes <= 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")
+        return _P(self.buf.data_ptr()), int(self.buf.numel())
+
+
+_ws = Workspace()
+
+
+# ---------------------------------------------------------------- entry points (same names as the C ABI)
+
+def h3d_conv3d_workspace_bytes(op: int, x: Slab, z: Slab) -> int:
+    return int(lib().h3d_conv3d_workspace_bytes(handle(), op, ctypes.byref(x.desc()), ctypes.byref(z.desc())))
+
+
+def h3d_conv3d_fwd(x: Slab, w, bias, z: Slab, act: int = ACT_NONE, alpha: float = 0.0, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_workspace_bytes(OP_FWD, x, z))
+    _check(lib().h3d_conv3d_fwd(handle(), ctypes.byref(x.desc()), _ptr(w), _ptr(bias), ctypes.byref(z.desc()), act,
+                                alpha, p, n, _stream()))
+    return z
+
+
+def h3d_conv3d_bwd_data(dz: Slab, z: Slab | None, w, dx: Slab, act: int = ACT_NONE, alpha: float = 0.0,
+                        ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_workspace_bytes(OP_BWD_DATA, dz, dx))
+    _check(lib().h3d_conv3d_bwd_data(handle(), ctypes.byref(dz.desc()), ctypes.byref(z.desc()) if z is not None else None,
+                                     _ptr(w), ctypes.byref(dx.desc()), act, alpha, p, n, _stream()))
+    return dx
+
+
+def h3d_conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, dw, db, act: int = ACT_NONE, alpha: float = 0.0,
+                          ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_workspace_bytes(OP_BWD_FILTER, x, dz))
+    _check(lib().h3d_conv3d_bwd_filter(handle(), ctypes.byref(x.desc()), ctypes.byref(dz.desc()),
+                                       ctypes.byref(z.desc()) if z is not None else None, _ptr(dw), _ptr(db), act, alpha,
+                                       p, n, _stream()))
+    return dw, db
+
+
+def h3d_pool3d_fwd(x: Slab, y: Slab, mode: int):
+    _check(lib().h3d_pool3d_fwd(handle(), ctypes.byref(x.desc()), ctypes.byref(y.desc()), mode, _stream()))
+    return y
+
+
+def h3d_pool3d_bwd(dy: Slab, x: Slab | None, dx: Slab, mode: int):
+    _check(lib().h3d_pool3d_bwd(handle(), ctypes.byref(dy.desc()), ctypes.byref(x.desc()) if x is not None else None,
+                                ctypes.byref(dx.desc()), mode, _stream()))
+    return dx
+
+
+def h3d_halo_bytes(t: Slab, width: int) -> int:
+    return int(lib().h3d_halo_bytes(ctypes.byref(t.desc()), width))
+
+
+def h3d_halo_pack(t: Slab, face: int, width: int, buf):
+    _check(lib().h3d_halo_pack(handle(), ctypes.byref(t.desc()), face, width, _ptr(buf), _stream()))
+    return buf
+
+
+def h3d_halo_unpack(buf, t: Slab, face: int, width: int):
+    _check(lib().h3d_halo_unpack(handle(), _ptr(buf), ctypes.byref(t.desc()), face, width, _stream()))
+    return t
+
+
+def h3d_deconv2_workspace_bytes(op: int, x: Slab, y: Slab) -> int:
+    return int(lib().h3d_deconv2_workspace_bytes(handle(), op, ctypes.byref(x.desc()), ctypes.byref(y.desc())))
+
+
+def h3d_deconv2_fwd(x: Slab, w, bias, y: Slab, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_deconv2_workspace_bytes(OP_FWD, x, y))
+    _check(lib().h3d_deconv2_fwd(handle(), ctypes.byref(x.desc()), _ptr(w), _ptr(bias), ctypes.byref(y.desc()), p, n, _stream()))
+    return y
+
+
+def h3d_deconv2_bwd_data(dy: Slab, w, dx: Slab, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_deconv2_workspace_bytes(OP_BWD_DATA, dx, dy))
+    _check(lib().h3d_deconv2_bwd_data(handle(), ctypes.byref(dy.desc()), _ptr(w), ctypes.byref(dx.desc()), p, n, _stream()))
+    return dx
+
+
+def h3d_deconv2_bwd_filter(x: Slab, dy: Slab, dw, db, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_deconv2_workspace_bytes(OP_BWD_FILTER, x, dy))
+    _check(lib().h3d_deconv2_bwd_filter(handle(), ctypes.byref(x.desc()), ctypes.byref(dy.desc()), _ptr(dw), _ptr(db), p, n, _stream()))
+    return dw, db
+
+
+def h3d_concat_c(a: Slab, b: Slab, out: Slab):
+    _check(lib().h3d_concat_c(handle(), ctypes.byref(a.desc()), ctypes.byref(b.desc()), ctypes.byref(out.desc()), _stream()))
+    return out
+
+
+def h3d_split_c(inp: Slab, a: Slab, b: Slab):
+    _check(lib().h3d_split_c(handle(), ctypes.byref(inp.desc()), ctypes.byref(a.desc()), ctypes.byref(b.desc()), _stream()))
+    return a, b
+
+
+def h3d_dense_fwd(x, w, bias, y, act: int = ACT_NONE, alpha: float = 0.0):
+    m, k = x.shape
+    n = w.shape[0]
+    assert w.shape[1] == k and tuple(y.shape) == (m, n)
+    _check(lib().h3d_dense_fwd(handle(), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _dtype_code(x), m, n, k, act, alpha, _stream()))
+    return y
+
+
+def h3d_dense_bwd(x, w, y, dy, dx, dw, db, act: int = ACT_NONE, alpha: float = 0.0):
+    m, k = x.shape
+    n = w.shape[0]
+    _check(lib().h3d_dense_bwd(handle(), _ptr(x), _ptr(w), _ptr(y), _ptr(dy), _ptr(dx), _ptr(dw), _ptr(db), _dtype_code(x),
+                               m, n, k, act, alpha, _stream()))
+    return dx, dw, db
+
+
+def h3d_mse_fwd_bwd(pred, target, loss, dpred):
+    _check(lib().h3d_mse_fwd_bwd(handle(), _ptr(pred), _ptr(target), _ptr(loss), _ptr(dpred), _dtype_code(pred),
+                                 pred.numel(), _stream()))
+    return loss, dpred
+
+
+# short aliases
+conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
+pool3d_fwd, pool3d_bwd = h3d_pool3d_fwd, h3d_pool3d_bwd
+halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
+deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
+concat_c, split_c = h3d_concat_c, h3d_split_c
+dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd

@@ -1,0 +1,77 @@
+// Internal definitions shared by the HIP translation units of libh3d (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "h3d.h"
+
+namespace h3d {
+
+struct Handle {
+  int device = 0;
+  int num_cu = 256;
+  char err[512] = {0};
+};
+
+// Slab geometry as the kernels see it (element strides, not bytes).
+struct Geo {
+  int n, c, d, h, w, hlo, hhi;
+  int ds;            // stored planes = hlo + d + hhi
+  int64_t doff, dglob;
+  int64_t plane;     // h*w
+  int64_t cstride;   // ds*h*w
+  int64_t nstride;   // c*ds*h*w
+};
+
+inline Geo make_geo(const h3d_tensor* t) {
+  Geo g;
+  g.n = t->n; g.c = t->c; g.d = t->d; g.h = t->h; g.w = t->w; g.hlo = t->halo_lo; g.hhi = t->halo_hi;
+  g.ds = t->halo_lo + t->d + t->halo_hi;
+  g.doff = t->d_offset; g.dglob = t->d_global;
+  g.plane = (int64_t)t->h * t->w;
+  g.cstride = g.plane * g.ds;
+  g.nstride = g.cstride * t->c;
+  return g;
+}
+
+inline size_t elt_size(int dtype) { return dtype == H3D_F32 ? 4 : 2; }
+
+h3d_status fail(void* handle, h3d_status st, const char* fmt, ...);
+h3d_status check_tensor(void* handle, const h3d_tensor* t, const char* name);
+// every needed in-volume input plane for output planes [lo,hi) (local indices) must be stored
+bool halo_covers(const h3d_tensor* in, int64_t lo, int64_t hi);
+bool same_shard(const h3d_tensor* a, const h3d_tensor* b);
+h3d_status launch_status(void* handle, const char* what);
+
+inline float act_slope(int act, float alpha) { return act == H3D_ACT_LEAKY ? alpha : (act == H3D_ACT_RELU ? 0.f : 1.f); }
+
+// ---- bf16 storage helpers (device) -------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even; NaN stays NaN
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+template <typename T> struct dtype_of;
+template <> struct dtype_of<float> { static constexpr int value = H3D_F32; };
+template <> struct dtype_of<bf16_t> { static constexpr int value = H3D_BF16; };
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace h3d
+
+#define H3D_TRY(expr)                       \
+  do {                                      \
+    h3d_status _s = (expr);                 \
+    if (_s != H3D_OK) return _s;            \
+  } while (0)

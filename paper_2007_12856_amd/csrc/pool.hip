@@ -1,0 +1,218 @@
+// 2x2x2 stride-2 average / max pooling of a slab interior, forward and backward.
+// Pure streaming kernels (HBM-bound: 8 elements read per element written, or the reverse):
+// each thread produces VEC consecutive outputs along W from four input rows read with 16-byte
+// loads, so a wavefront covers whole 128-byte lines of every row it touches.
+#include "common.h"
+
+namespace h3d {
+
+template <typename T, int N>
+struct alignas(sizeof(T) * N) Vec {
+  T v[N];
+};
+
+struct PoolArgs {
+  Geo x, y;            // x: the big tensor (fwd input / bwd output), y: the pooled one
+  int64_t total;       // threads needed = n*c*yd*yh*(yw/VEC)
+  int wv;              // yw / VEC
+};
+
+template <typename T, int VEC>
+__device__ __forceinline__ void decode(const PoolArgs& a, int64_t t, int64_t& xoff, int64_t& yoff) {
+  int wv = (int)(t % a.wv); t /= a.wv;
+  int ho = (int)(t % a.y.h); t /= a.y.h;
+  int q = (int)(t % a.y.d); t /= a.y.d;
+  int c = (int)(t % a.y.c);
+  int n = (int)(t / a.y.c);
+  yoff = n * a.y.nstride + c * a.y.cstride + (int64_t)(q + a.y.hlo) * a.y.plane + (int64_t)ho * a.y.w + wv * VEC;
+  xoff = n * a.x.nstride + c * a.x.cstride + (int64_t)(2 * q + a.x.hlo) * a.x.plane + (int64_t)(2 * ho) * a.x.w +
+         wv * VEC * 2;
+}
+
+template <typename T, int VEC, int MODE>
+__global__ void __launch_bounds__(256) pool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, PoolArgs a) {
+  int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.total) return;
+  int64_t xoff, yoff;
+  decode<T, VEC>(a, t, xoff, yoff);
+  Vec<T, 2 * VEC> r[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    r[k] = *reinterpret_cast<const Vec<T, 2 * VEC>*>(x + xoff + (k >> 1) * a.x.plane + (k & 1) * a.x.w);
+  Vec<T, VEC> o;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) {
+    if (MODE == H3D_POOL_AVG) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s += ld(&r[k].v[2 * i]) + ld(&r[k].v[2 * i + 1]);
+      st(&o.v[i], s * 0.125f);
+    } else {
+      T best = r[0].v[2 * i];
+      float m = ld(&best);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          float e = ld(&r[k].v[2 * i + j]);
+          if (e > m) { m = e; best = r[k].v[2 * i + j]; }
+        }
+      o.v[i] = best;
+    }
+  }
+  *reinterpret_cast<Vec<T, VEC>*>(y + yoff) = o;
+}
+
+template <typename T, int VEC, int MODE>
+__global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                       T* __restrict__ dx, PoolArgs a, Geo xin) {
+  int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.total) return;
+  int64_t dxoff, yoff;
+  decode<T, VEC>(a, t, dxoff, yoff);
+  Vec<T, VEC> g = *reinterpret_cast<const Vec<T, VEC>*>(dy + yoff);
+  Vec<T, 2 * VEC> o[4];
+  if (MODE == H3D_POOL_AVG) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      T v;
+      st(&v, ld(&g.v[i]) * 0.125f);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k].v[2 * i] = o[k].v[2 * i + 1] = v;
+    }
+  } else {
+    // same (n,c,q,ho,wv) decode against the forward input's own geometry (its halos may differ)
+    PoolArgs b = a;
+    b.x = xin;
+    int64_t xoff, dummy;
+    decode<T, VEC>(b, t, xoff, dummy);
+    Vec<T, 2 * VEC> r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      r[k] = *reinterpret_cast<const Vec<T, 2 * VEC>*>(x + xoff + (k >> 1) * xin.plane + (k & 1) * xin.w);
+    T zero;
+    st(&zero, 0.f);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float m = ld(&r[0].v[2 * i]);
+      int best = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          float e = ld(&r[k].v[2 * i + j]);
+          if (e > m) { m = e; best = k * 2 + j; }   // strict: ties keep the first in (kd,kh,kw) order
+        }
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) o[k].v[2 * i + j] = (best == k * 2 + j) ? g.v[i] : zero;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    *reinterpret_cast<Vec<T, 2 * VEC>*>(dx + dxoff + (k >> 1) * a.x.plane + (k & 1) * a.x.w) = o[k];
+}
+
+static h3d_status pool_check(void* handle, const h3d_tensor* big, const h3d_tensor* small, const char* what) {
+  if (big->dtype != small->dtype || big->n != small->n || big->c != small->c)
+    return fail(handle, H3D_EINVAL, "%s: n/c/dtype mismatch", what);
+  if ((big->d & 1) || (big->h & 1) || (big->w & 1) || (big->d_offset & 1) || (big->d_global & 1))
+    return fail(handle, H3D_EUNSUPPORTED, "%s: d,h,w,d_offset,d_global must be even (a window would straddle a face)", what);
+  if (small->d * 2 != big->d || small->h * 2 != big->h || small->w * 2 != big->w ||
+      small->d_offset * 2 != big->d_offset || small->d_global * 2 != big->d_global)
+    return fail(handle, H3D_EINVAL, "%s: pooled extents/offsets must be half of the input's", what);
+  return H3D_OK;
+}
+
+template <typename T>
+static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_tensor* extra) {
+  // widest VEC (outputs per thread) such that every row start is aligned for the vector accesses
+  const int cand = 16 / (2 * (int)sizeof(T)) * 2;  // bf16: 8, fp32: 4  (two 16-byte loads per input row)
+  for (int v = cand; v > 1; v >>= 1) {
+    bool ok = small->w % v == 0 && ((uintptr_t)small->data % (v * sizeof(T))) == 0 &&
+              ((uintptr_t)big->data % (2 * v * sizeof(T))) == 0 &&
+              (!extra || ((uintptr_t)extra->data % (2 * v * sizeof(T))) == 0);
+    if (ok) return v;
+  }
+  return 0;  // scalar: VEC = 1 needs pairs aligned to 2 elements
+}
+
+template <typename T, int MODE>
+static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, const h3d_tensor* small,
+                              const h3d_tensor* xin, hipStream_t stream) {
+  PoolArgs a;
+  a.x = make_geo(big);
+  a.y = make_geo(small);
+  int vec = pick_vec<T>(big, small, xin);
+  if (vec == 0) {
+    bool ok = ((uintptr_t)big->data % (2 * sizeof(T))) == 0 && (!xin || ((uintptr_t)xin->data % (2 * sizeof(T))) == 0);
+    if (!ok) return fail(handle, H3D_EUNSUPPORTED, "pool3d: data pointers must be aligned to two elements");
+    vec = 1;
+  }
+  a.wv = small->w / vec;
+  a.total = (int64_t)small->n * small->c * small->d * small->h * a.wv;
+  if (a.total == 0) return H3D_OK;
+  int64_t grid = cdiv(a.total, 256);
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "pool3d: too many blocks");
+  Geo gx = xin ? make_geo(xin) : a.x;
+  const T* bigp = (const T*)big->data;
+  const T* smallp = (const T*)small->data;
+#define H3D_POOL_CASE(V)                                                                                           \
+  case V:                                                                                                          \
+    if (fwd)                                                                                                       \
+      hipLaunchKernelGGL((pool_fwd_kernel<T, V, MODE>), dim3((unsigned)grid), dim3(256), 0, stream, bigp,          \
+                         (T*)small->data, a);                                                                      \
+    else                                                                                                           \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE>), dim3((unsigned)grid), dim3(256), 0, stream, smallp,        \
+                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx);                               \
+    break;
+  switch (vec) {
+    H3D_POOL_CASE(8)
+    H3D_POOL_CASE(4)
+    H3D_POOL_CASE(2)
+    H3D_POOL_CASE(1)
+  }
+#undef H3D_POOL_CASE
+  return launch_status(handle, fwd ? "pool3d_fwd" : "pool3d_bwd");
+}
+
+}  // namespace h3d
+
+using namespace h3d;
+
+extern "C" h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tensor* y, int mode, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  H3D_TRY(check_tensor(handle, x, "x"));
+  H3D_TRY(check_tensor(handle, y, "y"));
+  if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_fwd: bad mode %d", mode);
+  H3D_TRY(pool_check(handle, x, y, "pool3d_fwd"));
+  hipStream_t s = (hipStream_t)stream;
+  if (x->dtype == H3D_F32)
+    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, true, x, y, nullptr, s)
+                                : pool_launch<float, H3D_POOL_MAX>(handle, true, x, y, nullptr, s);
+  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, true, x, y, nullptr, s)
+                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, true, x, y, nullptr, s);
+}
+
+extern "C" h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, h3d_tensor* dx, int mode,
+                                     void* stream) {
+  if (!handle) return H3D_EINVAL;
+  H3D_TRY(check_tensor(handle, dy, "dy"));
+  H3D_TRY(check_tensor(handle, dx, "dx"));
+  if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_bwd: bad mode %d", mode);
+  H3D_TRY(pool_check(handle, dx, dy, "pool3d_bwd"));
+  if (mode == H3D_POOL_MAX) {
+    if (!x) return fail(handle, H3D_EINVAL, "pool3d_bwd: max pooling needs the forward input x");
+    H3D_TRY(check_tensor(handle, x, "x"));
+    if (!same_shard(x, dx) || x->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd: x and dx shapes differ");
+  } else {
+    x = nullptr;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (dx->dtype == H3D_F32)
+    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, false, dx, dy, x, s)
+                                : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s);
+  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s)
+                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s);
+}

@@ -1,0 +1,203 @@
+"""GPU parity of the three convolution passes against the CPU oracle, element by element, on
+seeded inputs at sizes the oracle finishes in seconds: several tiles, ragged tails, odd channel
+counts, boundary and interior shards, halo recompute.  All calls go through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import synth
+from helpers import TOL, cut, dev_like, from_dev, quantize, rel_l2, slab_pair, to_dev
+
+pytestmark = pytest.mark.gpu
+SEED = synth.BASE_SEED
+
+# (N, Cin, Cout, Dg, H, W)
+SHAPES = [
+    (1, 4, 16, 32, 32, 32),      # the single-layer fp32 configuration's shape
+    (2, 3, 5, 6, 7, 9),          # nothing divides anything
+    (1, 1, 32, 8, 20, 70),       # single input channel (U-Net first layer), W spans two 64-wide tiles raggedly
+    (1, 17, 4, 5, 9, 33),
+    (2, 16, 32, 8, 12, 40),
+    (1, 32, 64, 6, 10, 36),
+    (1, 64, 16, 4, 6, 66),
+    (1, 8, 8, 1, 1, 1),          # degenerate volume
+]
+
+
+def _weights(cin, cout, dtype, stream):
+    b = np.sqrt(3.0 / (27 * cin))
+    w = quantize(synth.flat("uniform", SEED, stream, (cout, cin, 3, 3, 3), -b, b), dtype)
+    bias = synth.round_f32(synth.flat("uniform", SEED, stream + 1, (cout,), -0.1, 0.1)).astype(np.float64)
+    return w, bias
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_conv3d_three_passes_unsharded(shape, dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, D, H, W = shape
+    alpha = 0.01
+    w, bias = _weights(Ci, Co, dtype, 10)
+    xo, xg = slab_pair(synth.flat("uniform", SEED, 1, (N, Ci, D, H, W)), dtype)
+    wd, bd = to_dev(w, dtype), to_dev(bias, "f32")
+    # forward
+    zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=alpha)
+    zg = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, dtype), h3d.ACT_LEAKY, alpha)
+    assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+    # backward passes take the ORACLE's z (rounded to storage) as the saved output on both sides
+    zq_o, zq_g = slab_pair(zo.a, dtype)
+    dzo, dzg = slab_pair(synth.flat("uniform", SEED, 2, (N, Co, D, H, W)), dtype)
+    dxo = orc.conv3d_bwd_data(dzo, zq_o, w, act=orc.ACT_LEAKY, alpha=alpha)
+    dxg = h3d.conv3d_bwd_data(dzg, zq_g, wd, dev_like(dxo, dtype), h3d.ACT_LEAKY, alpha)
+    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, zq_o, act=orc.ACT_LEAKY, alpha=alpha)
+    dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
+    db = torch.full((Co,), 777.0, device="cuda")
+    h3d.conv3d_bwd_filter(xg, dzg, zq_g, dw, db, h3d.ACT_LEAKY, alpha)
+    tol_w = 1e-5 if dtype == "f32" else 2e-2
+    assert rel_l2(from_dev(dw), dwo) <= tol_w
+    assert rel_l2(from_dev(db), dbo) <= tol_w
+    # deterministic split-spatial reduction: a second call returns identical bits
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    h3d.conv3d_bwd_filter(xg, dzg, zq_g, dw2, db2, h3d.ACT_LEAKY, alpha)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("act", [orc.ACT_NONE, orc.ACT_RELU])
+def test_conv3d_no_bias_and_other_activations(dtype, act):
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, D, H, W = 1, 8, 16, 4, 6, 20
+    w, _ = _weights(Ci, Co, dtype, 20)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 3, (N, Ci, D, H, W)), dtype)
+    zo = orc.conv3d_fwd(xo, w, None, act=act)
+    zg = h3d.conv3d_fwd(xg, to_dev(w, dtype), None, dev_like(zo, dtype), act, 0.0)
+    assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 4, (N, Co, D, H, W)), dtype)
+    zq_o, zq_g = slab_pair(zo.a, dtype)
+    dxo = orc.conv3d_bwd_data(dzo, zq_o, w, act=act)
+    dxg = h3d.conv3d_bwd_data(dzg, zq_g, to_dev(w, dtype), dev_like(dxo, dtype), act, 0.0)
+    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cin,cout", [(4, 16), (3, 5), (16, 32)])
+def test_conv3d_sharded_matches_oracle_and_unsharded_gpu(dtype, cin, cout):
+    """Boundary and interior shards; halo planes outside the volume hold a canary that must not be read;
+    the concatenated shard outputs equal the unsharded GPU output bit for bit (the accumulation
+    order of a voxel does not depend on the slab it is computed in)."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Dg, H, W, nshard = 2, 12, 10, 34, 3
+    d = Dg // nshard
+    full = (N, cin, Dg, H, W)
+    w, bias = _weights(cin, cout, dtype, 30)
+    wd, bd = to_dev(w, dtype), to_dev(bias, "f32")
+    xfo, xfg = slab_pair(synth.slab("cosmo", SEED, 5, full, 0, Dg), dtype)
+    zfo = orc.conv3d_fwd(xfo, w, bias, act=orc.ACT_LEAKY, alpha=0.01)
+    zfg = h3d.conv3d_fwd(xfg, wd, bd, dev_like(zfo, dtype), h3d.ACT_LEAKY, 0.01)
+    dzf = synth.slab("normal", SEED, 6, (N, cout, Dg, H, W), 0, Dg)
+    dzfo, dzfg = slab_pair(dzf, dtype)
+    zqo, zqg = slab_pair(zfo.a, dtype)
+    dxfg = h3d.conv3d_bwd_data(dzfg, zqg, wd, dev_like(xfo, dtype), h3d.ACT_LEAKY, 0.01)
+    dwf = torch.empty((cout, cin, 3, 3, 3), device="cuda")
+    dbf = torch.empty((cout,), device="cuda")
+    h3d.conv3d_bwd_filter(xfg, dzfg, zqg, dwf, dbf, h3d.ACT_LEAKY, 0.01)
+    dw_sum = torch.zeros_like(dwf, dtype=torch.float64)
+    db_sum = torch.zeros_like(dbf, dtype=torch.float64)
+    dwo_sum = 0.0
+    for s in range(nshard):
+        off = s * d
+        xs = cut("cosmo", SEED, 5, full, off, d, (1, 1))
+        for pl, g in enumerate(range(off - 1, off + d + 1)):
+            if g < 0 or g >= Dg:
+                xs[:, :, pl] = 999.0          # canary outside the volume
+        xo, xg = slab_pair(xs, dtype, (1, 1), off, Dg)
+        zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=0.01)
+        zg = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, dtype), h3d.ACT_LEAKY, 0.01)
+        assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+        assert torch.equal(zg.t, zfg.t[:, :, off:off + d])
+        # backward-data: dz and z carry the exchanged halo
+        zs = np.full((N, cout, d + 2, H, W), 999.0)
+        dzs = np.full((N, cout, d + 2, H, W), 999.0)
+        for pl, g in enumerate(range(off - 1, off + d + 1)):
+            if 0 <= g < Dg:
+                zs[:, :, pl], dzs[:, :, pl] = zfo.a[:, :, g], dzf[:, :, g]
+        zso, zsg = slab_pair(zs, dtype, (1, 1), off, Dg)
+        dzo, dzg = slab_pair(dzs, dtype, (1, 1), off, Dg)
+        dxo = orc.conv3d_bwd_data(dzo, zso, w, act=orc.ACT_LEAKY, alpha=0.01)
+        dxg = h3d.conv3d_bwd_data(dzg, zsg, wd, dev_like(dxo, dtype), h3d.ACT_LEAKY, 0.01)
+        assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+        assert torch.equal(dxg.t, dxfg.t[:, :, off:off + d])
+        # backward-filter partial of this shard
+        dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, zso, act=orc.ACT_LEAKY, alpha=0.01)
+        dw, db = torch.empty_like(dwf), torch.empty_like(dbf)
+        h3d.conv3d_bwd_filter(xg, dzg, zsg, dw, db, h3d.ACT_LEAKY, 0.01)
+        assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+        dw_sum += dw.double()
+        db_sum += db.double()
+        dwo_sum = dwo_sum + dwo
+    assert rel_l2(dw_sum.cpu().numpy(), from_dev(dwf)) <= 1e-5
+    assert rel_l2(db_sum.cpu().numpy(), from_dev(dbf)) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_halo_recompute_two_stacked_convs(dtype):
+    """A 2-plane halo serves two stacked convolutions (U-Net-shaped level): the first also produces
+    its output's halo plane; beyond the global boundary that plane must be zero, not act(bias)."""
+    import paper_2007_12856_amd as h3d
+    Ci, Cm, Co, Dg, H, W, d = 1, 8, 16, 8, 12, 20, 4
+    wa, ba = _weights(Ci, Cm, dtype, 40)
+    wb, bb = _weights(Cm, Co, dtype, 42)
+    for off in (0, 4):
+        xs = cut("normal", SEED, 7, (1, Ci, Dg, H, W), off, d, (2, 2))
+        xo, xg = slab_pair(xs, dtype, (2, 2), off, Dg)
+        ao = orc.conv3d_fwd(xo, wa, ba, cout_halo=(1, 1), act=orc.ACT_RELU)
+        ag = h3d.conv3d_fwd(xg, to_dev(wa, dtype), to_dev(ba, "f32"), dev_like(ao, dtype), h3d.ACT_RELU, 0.0)
+        assert rel_l2(from_dev(ag.t), ao.a) <= TOL[dtype]
+        outside = 0 if off == 0 else -1
+        assert not from_dev(ag.t)[:, :, outside].any()
+        aqo, aqg = slab_pair(ao.a, dtype, (1, 1), off, Dg)
+        bo = orc.conv3d_fwd(aqo, wb, bb, act=orc.ACT_RELU)
+        bg = h3d.conv3d_fwd(aqg, to_dev(wb, dtype), to_dev(bb, "f32"), dev_like(bo, dtype), h3d.ACT_RELU, 0.0)
+        assert rel_l2(from_dev(bg.t), bo.a) <= TOL[dtype]
+
+
+def test_error_paths_do_not_launch():
+    import torch
+    import paper_2007_12856_amd as h3d
+    x = h3d.Slab(torch.zeros((1, 2, 4, 4, 4), device="cuda"), 0, 0, 4, 16)      # interior shard without halo
+    z = x.like(3)
+    w = torch.zeros((3, 2, 3, 3, 3), device="cuda")
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.conv3d_fwd(x, w, None, z)
+    assert e.value.status == -4
+    zbad = h3d.Slab(torch.zeros((1, 3, 4, 4, 5), device="cuda"), 0, 0, 4, 16)
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.conv3d_fwd(x, w, None, zbad)
+    assert e.value.status == -1
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.conv3d_fwd(h3d.Slab(torch.zeros((1, 2, 4, 4, 4), device="cuda")), w, None,
+                       h3d.Slab(torch.zeros((1, 3, 4, 4, 4), device="cuda")), act=7)
+    assert e.value.status == -1
+    # workspace too small is reported, not overrun
+    import ctypes
+    xd, zd = h3d.Slab(torch.zeros((1, 2, 4, 4, 4), device="cuda")), h3d.Slab(torch.zeros((1, 3, 4, 4, 4), device="cuda"))
+    st = h3d.lib().h3d_conv3d_fwd(h3d.handle(), ctypes.byref(xd.desc()), ctypes.c_void_p(w.data_ptr()), None,
+                                  ctypes.byref(zd.desc()), 0, 0.0, None, 0, None)
+    assert st == -3
+
+
+def test_empty_shard():
+    import torch
+    import paper_2007_12856_amd as h3d
+    x = h3d.Slab(torch.zeros((0, 2, 4, 4, 4), device="cuda"))
+    z = h3d.Slab(torch.zeros((0, 3, 4, 4, 4), device="cuda"))
+    w = torch.ones((3, 2, 3, 3, 3), device="cuda")
+    h3d.conv3d_fwd(x, w, None, z)
+    dw = torch.full((3, 2, 3, 3, 3), 5.0, device="cuda")
+    db = torch.full((3,), 5.0, device="cuda")
+    h3d.conv3d_bwd_filter(x, z, None, dw, db)
+    torch.cuda.synchronize()
+    assert not dw.any() and not db.any()

@@ -1,0 +1,181 @@
+"""GPU parity of pooling, halo pack/unpack (bit-exact), transposed conv, concat, dense and MSE."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import synth
+from helpers import TOL, dev_like, from_dev, quantize, rel_l2, slab_pair, to_dev
+
+pytestmark = pytest.mark.gpu
+SEED = synth.BASE_SEED + 1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [orc.POOL_AVG, orc.POOL_MAX])
+@pytest.mark.parametrize("shape,halo", [((2, 3, 4, 6, 32), (0, 0)), ((1, 2, 6, 10, 12), (1, 1)),
+                                        ((1, 5, 2, 4, 70), (2, 1)), ((1, 1, 8, 8, 2), (0, 0)),
+                                        ((1, 16, 8, 32, 64), (1, 1))])
+def test_pool_fwd_bwd(shape, halo, mode, dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = shape
+    a = synth.flat("normal", SEED, 1, (N, C, halo[0] + d + halo[1], H, W))
+    if mode == orc.POOL_MAX:
+        a = np.maximum(a, 0.0)          # post-ReLU input: all-zero windows make ties common
+    xo, xg = slab_pair(a, dtype, halo, 4, 4 + d + 6)
+    yo = orc.pool3d_fwd(xo, mode, y_halo=(1, 0))
+    yg = dev_like(yo, dtype)
+    h3d.pool3d_fwd(xg, yg, mode)
+    got = from_dev(yg.t)
+    if mode == orc.POOL_MAX:
+        assert np.array_equal(got[:, :, 1:], yo.interior)
+    else:
+        assert rel_l2(got[:, :, 1:], yo.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+    assert np.all(got[:, :, 0] == 12345.0 if dtype == "f32" else got[:, :, 0] == quantize(12345.0, "bf16"))
+    dyo, dyg = slab_pair(synth.flat("normal", SEED, 2, yo.a.shape), dtype, (1, 0), yo.d_offset, yo.d_global)
+    dxo = orc.pool3d_bwd(dyo, xo, mode, dx_halo=halo)
+    dxg = h3d.Slab(torch.full(xo.a.shape, 7.0, dtype=xg.t.dtype, device="cuda"), halo[0], halo[1], xo.d_offset, xo.d_global)
+    h3d.pool3d_bwd(dyg, xg if mode == orc.POOL_MAX else None, dxg, mode)
+    got = from_dev(dxg.interior)
+    if mode == orc.POOL_MAX:
+        assert np.array_equal(got, dxo.interior)     # routing is exact, ties included
+    else:
+        assert rel_l2(got, dxo.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+    if halo[0]:
+        assert np.all(from_dev(dxg.t)[:, :, :halo[0]] == 7.0)
+
+
+def test_pool_rejects_odd_extents():
+    import torch
+    import paper_2007_12856_amd as h3d
+    x = h3d.Slab(torch.zeros((1, 1, 3, 4, 4), device="cuda"))
+    y = h3d.Slab(torch.zeros((1, 1, 1, 2, 2), device="cuda"))
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.pool3d_fwd(x, y, h3d.POOL_AVG)
+    assert e.value.status == -2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 4, 4, 5), (1, 4, 6, 16, 32), (1, 1, 2, 3, 3)])
+def test_halo_exchange_is_bit_exact(shape, dtype):
+    """Three shards of one volume on one GPU exchange faces: pack the neighbour's edge, unpack into
+    the halo (zero fill at the global boundary).  Every byte must equal the full volume's."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = shape
+    Dg = 3 * d
+    full = quantize(synth.flat("normal", SEED, 3, (N, C, Dg, H, W)), dtype)
+    for width in (1, 2):
+        if width > d:
+            continue
+        shards_o, shards_g = [], []
+        for s in range(3):
+            a = np.full((N, C, d + 4, H, W), 777.0)
+            a[:, :, 2:2 + d] = full[:, :, s * d:(s + 1) * d]
+            o, g = slab_pair(a, dtype, (2, 2), s * d, Dg)
+            shards_o.append(o)
+            shards_g.append(g)
+        for s in range(3):
+            for face, nb, nb_face in ((orc.FACE_D_LO, s - 1, orc.FACE_D_HI), (orc.FACE_D_HI, s + 1, orc.FACE_D_LO)):
+                if 0 <= nb < 3:
+                    bo = orc.halo_pack(shards_o[nb], nb_face, width)
+                    nbytes = h3d.halo_bytes(shards_g[nb], width)
+                    assert nbytes == bo.size * (4 if dtype == "f32" else 2)
+                    bg = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                    h3d.halo_pack(shards_g[nb], nb_face, width, bg)
+                    view = bg.view(torch.float32 if dtype == "f32" else torch.bfloat16).view(bo.shape)
+                    assert np.array_equal(from_dev(view), bo)
+                    orc.halo_unpack(bo, shards_o[s], face, width)
+                    h3d.halo_unpack(bg, shards_g[s], face, width)
+                else:
+                    orc.halo_unpack(None, shards_o[s], face, width)
+                    h3d.halo_unpack(None, shards_g[s], face, width)
+        for s in range(3):
+            assert np.array_equal(from_dev(shards_g[s].t), shards_o[s].a)   # canaries included
+
+
+def test_halo_width_errors():
+    import torch
+    import paper_2007_12856_amd as h3d
+    t = h3d.Slab(torch.zeros((1, 1, 4, 2, 2), device="cuda"), 1, 1)
+    buf = torch.zeros(64, device="cuda")
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.halo_unpack(buf, t, h3d.FACE_D_LO, 2)
+    assert e.value.status == -4
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.halo_pack(t, h3d.FACE_D_LO, 3, buf)
+    assert e.value.status == -1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cin,cout,shape", [(3, 5, (2, 2, 3, 5)), (16, 8, (1, 4, 6, 34)), (128, 64, (1, 2, 4, 16))])
+def test_deconv2(cin, cout, shape, dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, d, H, W = shape
+    b = np.sqrt(3.0 / (8 * cin))
+    w = quantize(synth.flat("uniform", SEED, 4, (cin, cout, 2, 2, 2), -b, b), dtype)
+    bias = synth.round_f32(synth.flat("uniform", SEED, 5, (cout,), -0.1, 0.1)).astype(np.float64)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 6, (N, cin, d, H, W)), dtype, (0, 0), 2, 2 + d + 2)
+    yo = orc.deconv2_fwd(xo, w, bias)
+    yg = h3d.deconv2_fwd(xg, to_dev(w, dtype), to_dev(bias, "f32"), dev_like(yo, dtype))
+    assert rel_l2(from_dev(yg.t), yo.a) <= TOL[dtype]
+    dyo, dyg = slab_pair(synth.flat("normal", SEED, 7, yo.a.shape), dtype, (0, 0), yo.d_offset, yo.d_global)
+    dxo = orc.deconv2_bwd_data(dyo, w)
+    dxg = h3d.deconv2_bwd_data(dyg, to_dev(w, dtype), dev_like(dxo, dtype))
+    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    dwo, dbo = orc.deconv2_bwd_filter(xo, dyo)
+    dw = torch.empty((cin, cout, 2, 2, 2), device="cuda")
+    db = torch.empty((cout,), device="cuda")
+    h3d.deconv2_bwd_filter(xg, dyg, dw, db)
+    assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    h3d.deconv2_bwd_filter(xg, dyg, dw2, db2)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_concat_split_bit_exact(dtype):
+    import paper_2007_12856_amd as h3d
+    ao, ag = slab_pair(synth.flat("normal", SEED, 8, (2, 3, 6, 5, 7)), dtype, (1, 1), 4, 12)
+    bo, bg = slab_pair(synth.flat("normal", SEED, 9, (2, 5, 4, 5, 7)), dtype, (0, 0), 4, 12)
+    co = orc.concat_c(ao, bo)
+    cg = h3d.concat_c(ag, bg, dev_like(co, dtype))
+    assert np.array_equal(from_dev(cg.t), co.a)
+    a2, b2 = dev_like(orc.Slab(ao.interior, 0, 0, 4, 12), dtype), dev_like(bo, dtype)
+    h3d.split_c(cg, a2, b2)
+    assert np.array_equal(from_dev(a2.t), ao.interior) and np.array_equal(from_dev(b2.t), bo.a)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m,n,k,act", [(4, 64, 512, orc.ACT_LEAKY), (3, 7, 33, orc.ACT_NONE), (8, 300, 1000, orc.ACT_RELU),
+                                       (4, 4, 256, orc.ACT_NONE), (1, 130, 2048, orc.ACT_LEAKY)])
+def test_dense_and_mse(m, n, k, act, dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    b = np.sqrt(3.0 / k)
+    x = quantize(synth.flat("normal", SEED, 10, (m, k)), dtype)
+    w = quantize(synth.flat("uniform", SEED, 11, (n, k), -b, b), dtype)
+    bias = synth.round_f32(synth.flat("uniform", SEED, 12, (n,), -0.1, 0.1)).astype(np.float64)
+    yo = orc.dense_fwd(x, w, bias, act, 0.01)
+    y = torch.empty((m, n), dtype=td, device="cuda")
+    h3d.dense_fwd(to_dev(x, dtype), to_dev(w, dtype), to_dev(bias, "f32"), y, act, 0.01)
+    assert rel_l2(from_dev(y), yo) <= TOL[dtype]
+    yq = quantize(yo, dtype)
+    dy = quantize(synth.flat("normal", SEED, 13, (m, n)), dtype)
+    dxo, dwo, dbo = orc.dense_bwd(x, w, yq, dy, act, 0.01)
+    dx = torch.empty((m, k), dtype=td, device="cuda")
+    dw = torch.empty((n, k), device="cuda")
+    db = torch.empty((n,), device="cuda")
+    h3d.dense_bwd(to_dev(x, dtype), to_dev(w, dtype), to_dev(yq, dtype), to_dev(dy, dtype), dx, dw, db, act, 0.01)
+    assert rel_l2(from_dev(dx), dxo) <= TOL[dtype]
+    assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+    # loss
+    t = synth.round_f32(synth.flat("uniform", SEED, 14, (m, n))).astype(np.float64)
+    Lo, go = orc.mse_fwd_bwd(yq, t)
+    loss = torch.empty((1,), device="cuda")
+    dp = torch.empty((m, n), dtype=td, device="cuda")
+    h3d.mse_fwd_bwd(to_dev(yq, dtype), to_dev(t, "f32"), loss, dp)
+    assert abs(loss.item() - Lo) <= 1e-5 * abs(Lo)
+    assert rel_l2(from_dev(dp), go) <= TOL[dtype]
