@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv3d hot path on one MI355X.
+
+Workload (default): the CosmoFlow-shaped network step — N=4 samples of 4x128^3, five
+conv3d 3x3x3 + leaky-ReLU + 2x2x2 avg-pool stages (16..256 channels), dense 16384-2048-256-4,
+MSE; bf16 storage, fp32 accumulation; forward + backward (BD and BF of every layer).
+A step = one pass of that whole path over one synthetic batch already resident in HBM.
+
+Prints ONE JSON line: conv3d fwd+bwd TFLOP/s of the step (conv flops by Table I's convention,
+2*27*Cin*Cout per output voxel and pass, divided by the whole step time), voxels/s, a per-call
+table, the roofline of the dominant call (timed with HIP events inside the timed region) and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_FP32_VALU_TFLOPS = 157.3
+RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+
+
+def cpu_baseline(seed):
+    """The oracle, as it stands, on a bounded sample: stage 2 of the stack (16->32 channels on 64^3),
+    one sample, all three passes (FP, BD, BF)."""
+    import numpy as np
+    import oracle as orc
+    import synth
+    from synth import recipes
+    w, b = recipes.conv_params(seed, 102, 16, 32)
+    w = synth.round_bf16(w).astype(np.float64)
+    x = orc.Slab(synth.round_bf16(synth.slab("cosmo", seed, 7, (1, 16, 64, 64, 64), 0, 64)).astype(np.float64))
+    dz = orc.Slab(synth.round_bf16(synth.slab("normal", seed, 8, (1, 32, 64, 64, 64), 0, 64)).astype(np.float64))
+    t0 = time.time()
+    z = orc.conv3d_fwd(x, w, b, act=orc.ACT_LEAKY, alpha=0.01)
+    orc.conv3d_bwd_data(dz, z, w, act=orc.ACT_LEAKY, alpha=0.01)
+    orc.conv3d_bwd_filter(x, dz, z, act=orc.ACT_LEAKY, alpha=0.01)
+    dt = time.time() - t0
+    flops = 3 * orc.conv_flops(16, 32, 64 ** 3)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "stage-2 conv (16->32 ch, 64^3, 1 sample) fwd+bwd_data+bwd_filter, fp64 direct loops",
+            "seconds": round(dt, 2), "voxels_per_s": 64 ** 3 / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=4)
+    ap.add_argument("--width", type=int, default=128)
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the per-GPU share of the spatially-partitioned path); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    import synth
+    from synth import recipes
+    import paper_2007_12856_amd as h3d
+    from paper_2007_12856_amd.nets import CosmoFlowStack
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    h3d.lib()   # fail loudly if the HIP library is not built
+    seed = synth.BASE_SEED if args.seed is None else args.seed
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+
+    def dev(a, dt=td):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+
+    P = recipes.cosmoflow_params(seed, args.width)
+    x, t = recipes.cosmoflow_batch(seed, args.batch, args.width)
+    net = CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), dev(b, torch.float32)) for w, b in P["conv"]],
+                         [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]])
+    del P, x
+    stream = torch.cuda.current_stream()
+
+    # warm-up; the last warm-up step also times every call on its own to find the dominant one
+    for _ in range(max(args.warmup - 1, 0)):
+        net.step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in net.ops]
+    for op, (e0, e1) in zip(net.ops, evs):
+        e0.record(stream)
+        op["fn"]()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    per_call = []
+    for op, (e0, e1) in zip(net.ops, evs):
+        ms = e0.elapsed_time(e1)
+        per_call.append({"name": op["name"], "ms": round(ms, 4),
+                         "tflops": round(op["flops"] / ms / 1e9, 2) if op["flops"] and op["name"].startswith("conv") else None,
+                         "gbs": round(op["bytes"] / ms / 1e6, 1) if op["bytes"] else None})
+    dom = max(range(len(net.ops)), key=lambda i: per_call[i]["ms"])
+
+    # timed region: exactly K steps; one HIP-event pair per step around the dominant call
+    # (events are recorded on the stream the kernels are launched on)
+    dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for i, op in enumerate(net.ops):
+            if i == dom:
+                dom_ev[k][0].record(stream)
+                op["fn"]()
+                dom_ev[k][1].record(stream)
+            else:
+                op["fn"]()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    dom_ms = sum(a.elapsed_time(b) for a, b in dom_ev) / args.steps
+
+    flops = net.conv_flops()
+    voxels = args.batch * args.width ** 3
+    op = net.ops[dom]
+    intensity = op["flops"] / max(op["bytes"], 1)
+    if op["flops"] and intensity >= RIDGE:
+        roof = {"bound": "mfma", "achieved": op["flops"] / dom_ms / 1e9, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": op["bytes"] / dom_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = op["name"]
+    roof["ms"] = round(dom_ms, 4)
+    roof["algorithmic_bytes"] = op["bytes"]
+    roof["algorithmic_flops"] = op["flops"]
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roof["traffic"] = json.load(open(tpath)).get(op["name"])
+        except Exception:
+            roof["traffic"] = None
+
+    out = {
+        "metric": "conv3d fwd+bwd TFLOP/s", "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"CosmoFlow-shaped stack fwd+bwd: N={args.batch} x 4x{args.width}^3, conv 16-32-64-128-256 "
+                               f"+ leaky-ReLU + avg-pool, dense 2048-256-4, MSE",
+                   "global_batch": args.batch, "input": [4, args.width, args.width, args.width]},
+        "voxels_per_s": voxels / (ms_per_step * 1e-3),
+        "conv_gflop_per_step": flops / 1e9,
+        "pct_of_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+        "roofline": roof,
+        "per_call": per_call,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,18 +1,350 @@
-// bf16 MFMA implicit-GEMM convolution kernels (placeholder until the matrix-core path lands:
-// every shape currently takes the direct kernels).
+// bf16 MFMA implicit-GEMM kernels for the 3x3x3 convolution passes on gfx950.
+//
+// Forward / backward-data (one kernel; backward-data is the forward correlation of
+// g = dz * act'(z) with the weights transposed and reversed, Sec. III-C "BD"):
+//   D[co][voxel] = sum_{tap, ci} Wp[co][tap, ci] * X[tap, ci][voxel]
+//   * output channels sit on the MFMA rows (A operand = weights), voxels on the columns
+//     (B operand = input patches), so one accumulator register of a wavefront covers 32
+//     consecutive W positions of one channel: stores along W are contiguous;
+//   * the contraction index is ordered (tap, ci) with ci fastest: the 8 bf16 a lane feeds to
+//     v_mfma_f32_32x32x16_bf16 are 8 consecutive input channels of ONE voxel.  NCDHW keeps
+//     channels a whole volume apart, so the input tile (with its halo) is transposed on its way
+//     into LDS: 16-byte units of 8 channels, laid out [ci-group][d][h][w], read back with
+//     conflict-free ds_read_b128 at the 27 shifted offsets;
+//   * weights are pre-packed in exact fragment order ([co-block][ci-chunk][tap][lane][8]) and go
+//     global -> registers (fully coalesced 1 KB per fragment, L1/L2 resident), prefetched one
+//     (kd,kw) step ahead; they never touch LDS;
+//   * a workgroup is 8 wavefronts: NCB blocks of 32 output channels x ND depth planes; each
+//     wavefront owns 32 channels x 128 voxels (4 MFMA column blocks = 4 groups of h rows).  For a
+//     fixed (kd,kw) the 12 (block, kh) products need only 3*RPB+3 distinct row fragments, so LDS
+//     read traffic is about half of one fragment per MFMA;
+//   * the ci loop runs in chunks of 16 channels with two LDS buffers: the global loads of chunk
+//     c+1 are in flight while chunk c is multiplied.
+#include <algorithm>
+
 #include "common.h"
 
 namespace h3d {
-bool mfma_fwd_supported(const h3d_tensor*, const h3d_tensor*) { return false; }
-size_t mfma_fwd_ws_bytes(const h3d_tensor*, const h3d_tensor*) { return 0; }
-h3d_status conv3d_mfma(void* handle, const h3d_tensor*, const h3d_tensor*, const void*, const float*, h3d_tensor*, bool, float,
-                       float, void*, size_t, hipStream_t) {
-  return fail(handle, H3D_EUNSUPPORTED, "conv3d_mfma: not built");
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int CI_CHUNK = 16;
+constexpr int WG_THREADS = 512;
+
+// wp: [co_blk][chunk][tap][lane][8] bf16; lane l, element e: co_k = 32*co_blk + l%32, ci_k = 16*chunk + 8*(l/32) + e
+__global__ void pack_w_mfma_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int cin, int cout, int transpose,
+                                   int nchunks, int ncoblk) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int64_t total = (int64_t)ncoblk * nchunks * 27 * 512;
+  if (i >= total) return;
+  int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  int64_t r = i >> 9;
+  int tap = (int)(r % 27); r /= 27;
+  int chunk = (int)(r % nchunks);
+  int cb = (int)(r / nchunks);
+  int co_k = cb * 32 + (lane & 31), ci_k = chunk * CI_CHUNK + (lane >> 5) * 8 + e;
+  int cin_k = transpose ? cout : cin, cout_k = transpose ? cin : cout;
+  bf16_t v = 0;
+  if (co_k < cout_k && ci_k < cin_k)
+    v = transpose ? w[((int64_t)ci_k * cin + co_k) * 27 + (26 - tap)] : w[((int64_t)co_k * cin + ci_k) * 27 + tap];
+  wp[i] = v;
 }
+
+struct MfmaArgs {
+  Geo in, mask, out;
+  int cin_k, cout_k, nchunks, ncoblk;
+  int tiles_w, tiles_h, tiles_d;
+  float out_slope, mask_slope;
+  int vec_ok;  // rows start 4-byte aligned: pairs of bf16 are loaded as one dword
+};
+
+__device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t m, float slope) {
+  // per bf16 half: keep v where the mask value is > 0, else v * slope (rounded to bf16)
+  float v0 = __uint_as_float(v << 16), v1 = __uint_as_float(v & 0xffff0000u);
+  float m0 = __uint_as_float(m << 16), m1 = __uint_as_float(m & 0xffff0000u);
+  if (!(m0 > 0.f)) v0 *= slope;
+  if (!(m1 > 0.f)) v1 *= slope;
+  return (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+}
+
+template <int NCB, int ND, int TWC, bool MASKED>
+__global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ mask,
+                                                                 const uint4* __restrict__ wp, const float* __restrict__ bias,
+                                                                 bf16_t* __restrict__ out, MfmaArgs a) {
+  static_assert(NCB * ND == 8, "8 wavefronts per workgroup");
+  constexpr int RPB = 32 / TWC;        // h rows per MFMA column block
+  constexpr int TH = 4 * RPB, TW = TWC;
+  constexpr int TD2 = ND + 2, TH2 = TH + 2;
+  constexpr int P = TWC == 32 ? 36 : 20;   // LDS row pitch in 16-byte units: w in [w0-2, w0+TW+2)
+  constexpr int PAIRS = (TW + 4) / 2;
+  constexpr int CIG_UNITS = TD2 * TH2 * P;
+  constexpr int BUF_UNITS = 2 * CIG_UNITS;
+  constexpr int NITEMS = 2 * TD2 * TH2 * PAIRS;
+  constexpr int ROUNDS = (NITEMS + WG_THREADS - 1) / WG_THREADS;
+  constexpr int NFRAG = 3 * RPB + 3;   // distinct start rows b*RPB + kh
+  extern __shared__ uint4 lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cbw = wave / ND, wd = wave % ND;
+  int t = blockIdx.x;
+  const int tw = t % a.tiles_w; t /= a.tiles_w;
+  const int th = t % a.tiles_h; t /= a.tiles_h;
+  const int td = t % a.tiles_d;
+  const int n = t / a.tiles_d;
+  const int w0 = tw * TW, h0 = th * TH, ps0 = td * ND;
+  const int co_blk = blockIdx.y * NCB + cbw;
+  const int W = a.in.w, H = a.in.h;
+
+  // ---- per-thread staging plan (the same for every ci chunk)
+  int lds_unit[ROUNDS];
+  int goff[ROUNDS], moff[ROUNDS];
+  int flags[ROUNDS];   // bit0/bit1: element valid; bits 4..: ci-group
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    int item = tid + r * WG_THREADS;
+    int pair = item % PAIRS;
+    int x = item / PAIRS;
+    int hy = x % TH2; x /= TH2;
+    int dz = x % TD2;
+    int cig = x / TD2;
+    lds_unit[r] = (cig * TD2 + dz) * (TH2 * P) + hy * P + 2 * pair;
+    int p_in = ps0 - a.out.hlo + dz - 1;        // local interior index of the input plane
+    int64_t gq = a.in.doff + p_in;
+    int sp = p_in + a.in.hlo;
+    bool ok = item < NITEMS && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds;
+    int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
+    ok = ok && h >= 0 && h < H;
+    int f = 0;
+    if (ok && w >= 0 && w < W) f |= 1;
+    if (ok && w + 1 >= 0 && w + 1 < W) f |= 2;
+    if (item >= NITEMS) f = 0, cig = 2;   // cig 2: never matches a channel below
+    flags[r] = f | (cig << 4);
+    goff[r] = sp * (int)a.in.plane + h * W + w;
+    moff[r] = MASKED ? (p_in + a.mask.hlo) * (int)a.mask.plane + h * W + w : 0;
+  }
+  const bf16_t* in_n = in + n * a.in.nstride;
+  const bf16_t* mask_n = MASKED ? mask + n * a.mask.nstride : nullptr;
+
+  uint32_t v[ROUNDS][8];
+  uint32_t mv[MASKED ? ROUNDS : 1][8];
+
+  auto load_chunk = [&](int c) {
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int f = flags[r] & 3, cig = flags[r] >> 4;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int ci = c * CI_CHUNK + cig * 8 + e;
+        uint32_t val = 0, mval = 0x3f803f80u;   // mask default: 1.0 (keeps the zero)
+        if (f && ci < a.cin_k && cig < 2) {
+          const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + goff[r];
+          if (a.vec_ok) {
+            val = *reinterpret_cast<const uint32_t*>(p);
+          } else {
+            if (f & 1) val = p[0];
+            if (f & 2) val |= (uint32_t)p[1] << 16;
+          }
+          if (MASKED) {
+            const bf16_t* q = mask_n + (int64_t)ci * a.mask.cstride + moff[r];
+            if (a.vec_ok) {
+              mval = *reinterpret_cast<const uint32_t*>(q);
+            } else {
+              mval = 0;
+              if (f & 1) mval = q[0];
+              if (f & 2) mval |= (uint32_t)q[1] << 16;
+            }
+          }
+        }
+        v[r][e] = val;
+        if (MASKED) mv[r][e] = mval;
+      }
+    }
+  };
+
+  auto store_chunk = [&](int buf) {
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      if ((flags[r] >> 4) >= 2) continue;
+      uint32_t g[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[e] = MASKED ? mask_pair(v[r][e], mv[r][e], a.mask_slope) : v[r][e];
+      uint4 u0, u1;   // unit of w (low halves) and of w+1 (high halves): 8 channels each
+      u0.x = __builtin_amdgcn_perm(g[1], g[0], 0x05040100); u1.x = __builtin_amdgcn_perm(g[1], g[0], 0x07060302);
+      u0.y = __builtin_amdgcn_perm(g[3], g[2], 0x05040100); u1.y = __builtin_amdgcn_perm(g[3], g[2], 0x07060302);
+      u0.z = __builtin_amdgcn_perm(g[5], g[4], 0x05040100); u1.z = __builtin_amdgcn_perm(g[5], g[4], 0x07060302);
+      u0.w = __builtin_amdgcn_perm(g[7], g[6], 0x05040100); u1.w = __builtin_amdgcn_perm(g[7], g[6], 0x07060302);
+      uint4* dst = lds + buf * BUF_UNITS + lds_unit[r];
+      dst[0] = u0;
+      dst[1] = u1;
+    }
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+
+  const bool wave_active = co_blk < a.ncoblk;
+  const int j = lane & 31;
+  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2 + j / TWC) * P + (j % TWC) + 1;
+  const uint4* wp_blk = wp + (int64_t)(wave_active ? co_blk : 0) * a.nchunks * 27 * 64 + lane;
+
+  auto load_a = [&](int c, int step, uint4 (&dst)[3]) {
+    const int kd = step / 3, kw = step % 3;
+    const uint4* p = wp_blk + (int64_t)c * 27 * 64;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh) dst[kh] = p[(kd * 9 + kh * 3 + kw) * 64];
+  };
+
+  auto compute_chunk = [&](int c, int buf) {
+    const uint4* base = lds + buf * BUF_UNITS + lane_unit;
+    uint4 a_cur[3], a_nxt[3];
+    load_a(c, 0, a_cur);
+#pragma unroll
+    for (int step = 0; step < 9; ++step) {
+      const int kd = step / 3, kw = step % 3;
+      if (step + 1 < 9) load_a(c, step + 1, a_nxt);
+#pragma unroll
+      for (int s = 0; s < NFRAG; ++s) {
+        const uint4 fr = base[(kd * TH2 + s) * P + kw];
+        const bf16x8 B = __builtin_bit_cast(bf16x8, fr);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+          // the block whose start row b*RPB + kh equals s
+          if (s - kh >= 0 && (s - kh) % RPB == 0 && (s - kh) / RPB < 4) {
+            const int b = (s - kh) / RPB;
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_cur[kh]), B, acc[b], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh) a_cur[kh] = a_nxt[kh];
+    }
+  };
+
+  // ---- main loop over ci chunks, two LDS buffers
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  for (int c = 0; c < a.nchunks; ++c) {
+    const bool more = c + 1 < a.nchunks;
+    if (more) load_chunk(c + 1);
+    if (wave_active) compute_chunk(c, c & 1);
+    if (more) store_chunk((c + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: bias + activation, bf16 store; output planes outside the global volume are zero
+  if (!wave_active) return;
+  const int ps = ps0 + wd;
+  if (ps >= a.out.ds) return;
+  const int64_t gp = a.out.doff + ps - a.out.hlo;
+  const bool inside = gp >= 0 && gp < a.out.dglob;
+  bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
+    if (h >= H || w >= W) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = co_blk * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+      if (co < a.cout_k) {
+        float val = acc[b][r] + (bias ? bias[co] : 0.f);
+        if (!(val > 0.f)) val *= a.out_slope;
+        out_n[(int64_t)co * a.out.cstride + h * W + w] = f32_to_bf16(inside ? val : 0.f);
+      }
+    }
+  }
+}
+
+bool mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
+  if (in->dtype != H3D_BF16) return false;
+  if (in->c < 1 || out->c < 1) return false;
+  // 32-bit in-sample offsets inside the kernel
+  int64_t in_sample = (int64_t)(in->halo_lo + in->d + in->halo_hi) * in->h * in->w;
+  int64_t out_sample = (int64_t)(out->halo_lo + out->d + out->halo_hi) * out->h * out->w;
+  return in_sample < ((int64_t)1 << 30) && out_sample < ((int64_t)1 << 30);
+}
+
+static void wp_dims(int cin_k, int cout_k, int* nchunks, int* ncoblk) {
+  *nchunks = (int)cdiv(cin_k, CI_CHUNK);
+  *ncoblk = (int)cdiv(cout_k, 32);
+}
+
+size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
+  int nchunks, ncoblk;
+  wp_dims(in->c, out->c, &nchunks, &ncoblk);
+  return (size_t)ncoblk * nchunks * 27 * 512 * sizeof(bf16_t);
+}
+
+template <int NCB, int ND, int TWC, bool MASKED>
+static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
+                                 bf16_t* out, MfmaArgs a, int n, hipStream_t stream) {
+  constexpr int RPB = 32 / TWC, TH = 4 * RPB;
+  constexpr int P = TWC == 32 ? 36 : 20;
+  constexpr size_t lds_bytes = (size_t)2 * 2 * (ND + 2) * (TH + 2) * P * 16;
+  a.tiles_w = (int)cdiv(a.out.w, TWC);
+  a.tiles_h = (int)cdiv(a.out.h, TH);
+  a.tiles_d = (int)cdiv(a.out.ds, ND);
+  int64_t gx = (int64_t)n * a.tiles_d * a.tiles_h * a.tiles_w;
+  int64_t gy = cdiv(a.ncoblk, NCB);
+  if (gx >= ((int64_t)1 << 31) || gy > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED>;
+  static bool attr_set = false;   // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(WG_THREADS), lds_bytes, stream, in, mask, wp, bias, out, a);
+  return launch_status(handle, "conv3d_mfma");
+}
+
+template <bool MASKED>
+static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
+                               bf16_t* out, const MfmaArgs& a, int n, hipStream_t s) {
+  const bool wide = a.out.w > 16;
+  const bool two_cb = a.cout_k > 32;
+  if (wide) {
+    return two_cb ? launch_variant<2, 4, 32, MASKED>(handle, in, mask, wp, bias, out, a, n, s)
+                  : launch_variant<1, 8, 32, MASKED>(handle, in, mask, wp, bias, out, a, n, s);
+  }
+  return two_cb ? launch_variant<2, 4, 16, MASKED>(handle, in, mask, wp, bias, out, a, n, s)
+                : launch_variant<1, 8, 16, MASKED>(handle, in, mask, wp, bias, out, a, n, s);
+}
+
+h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
+                       h3d_tensor* out, bool transpose, float out_slope, float mask_slope, void* ws, size_t ws_bytes,
+                       hipStream_t stream) {
+  MfmaArgs a;
+  a.in = make_geo(in);
+  a.mask = mask ? make_geo(mask) : a.in;
+  a.out = make_geo(out);
+  a.cin_k = in->c; a.cout_k = out->c;
+  wp_dims(a.cin_k, a.cout_k, &a.nchunks, &a.ncoblk);
+  a.out_slope = out_slope; a.mask_slope = mask_slope;
+  if ((int64_t)out->n * a.out.ds * out->h * out->w == 0) return H3D_OK;
+  if (!ws || ws_bytes < mfma_fwd_ws_bytes(in, out)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
+  if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace must be 16-byte aligned");
+  a.vec_ok = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && (!mask || (uintptr_t)mask->data % 4 == 0);
+  const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
+  int64_t total = (int64_t)a.ncoblk * a.nchunks * 27 * 512;
+  hipLaunchKernelGGL(pack_w_mfma_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin,
+                     cout, transpose ? 1 : 0, a.nchunks, a.ncoblk);
+  const bf16_t* ip = (const bf16_t*)in->data;
+  const bf16_t* mp = mask ? (const bf16_t*)mask->data : nullptr;
+  if (mask) return pick_variant<true>(handle, ip, mp, (const uint4*)ws, bias, (bf16_t*)out->data, a, out->n, stream);
+  return pick_variant<false>(handle, ip, mp, (const uint4*)ws, bias, (bf16_t*)out->data, a, out->n, stream);
+}
+
+// ---- backward-filter on the matrix cores: not built yet, the direct two-stage kernel serves every shape
 bool mfma_bf_supported(const h3d_tensor*, const h3d_tensor*) { return false; }
 size_t mfma_bf_ws_bytes(const h3d_tensor*, const h3d_tensor*) { return 0; }
 h3d_status bwd_filter_mfma(void* handle, const h3d_tensor*, const h3d_tensor*, const h3d_tensor*, float*, float*, float, void*,
                            size_t, hipStream_t) {
   return fail(handle, H3D_EUNSUPPORTED, "bwd_filter_mfma: not built");
 }
+
 }  // namespace h3d
