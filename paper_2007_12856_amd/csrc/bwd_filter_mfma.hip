@@ -1,0 +1,355 @@
+// Backward-filter (BF pass, Sec. III-C) on the matrix cores, bf16 in / fp32 accumulate.
+//
+//   dW[co][ci,kd,kh,kw] = sum over voxels v of g[co][v] * x~[ci][v + (kd,kh,kw) - 1]
+//
+// is a GEMM whose contraction runs over VOXELS: with v_mfma_f32_16x16x32_bf16 a lane feeds 8
+// consecutive voxels along W of one row (A: a channel of g) or one column (B: a shifted channel of
+// x) — contiguous 16 bytes in NCDHW, so both operands keep their natural layout (no transpose).
+//   * rows    = output channels, in blocks of 16;
+//   * columns = (ci, kd, kh) combinations, ci slowest, in blocks of 16; the three kw taps of a
+//     combination are three MFMAs fed from ONE aligned 16-byte LDS read: the kw = 0 / 2 operands are
+//     that block shifted by one element, completed with the neighbouring lane group's edge dword
+//     (ds_bpermute) or, at the ends of a row segment, one dword read from the tile's halo;
+//   * LDS pitches of the x tile are chosen so that the 16 combinations of a column block fall into
+//     16 distinct 16-byte bank groups (row pitch r odd, plane pitch = 3r, channel pitch = 9r mod 16);
+//   * a workgroup = 3 wavefronts x 3 column blocks = the 144 combinations of 16 input channels,
+//     times RBW row blocks; it streams a fixed chunk of voxel tiles through LDS and keeps the whole
+//     dW tile in accumulators;
+//   * db[co] = sum g comes from one extra MFMA per A fragment against an all-ones operand.
+// Determinism: the split of the voxel range into chunks and tiles is fixed by the shape; every
+// workgroup writes its partial tile; a second kernel adds the chunk partials in chunk order.
+#include <algorithm>
+
+#include "common.h"
+
+namespace h3d {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int cmod_ge(int lo, int target_mod16) {  // smallest v >= lo with v % 16 == target_mod16
+  int v = lo;
+  while (v % 16 != target_mod16) ++v;
+  return v;
+}
+
+template <int TW, int TH>
+struct BfTile {
+  static constexpr int GW = TW >= 32 ? 4 : TW / 8;        // lane groups (of 8 voxels) side by side in a row
+  static constexpr int RPK = TW >= 32 ? 1 : 32 / TW;      // rows per K-step of 32 voxels
+  static constexpr int KS_PER_ROW = TW >= 32 ? TW / 32 : 1;
+  static constexpr int KSTEPS = TH * TW / 32;
+  static constexpr int XU = TW / 8 + 2;                   // x row: w in [w0-8, w0+TW+8)
+  static constexpr int PR = XU | 1;
+  static constexpr int PD = cmod_ge((TH + 2) * PR, (3 * PR) % 16);
+  static constexpr int PC = cmod_ge(3 * PD, (9 * PR) % 16);
+  static constexpr int GU = TW / 8;
+  static constexpr int PG = (TH * GU) | 1;
+  static constexpr int X_UNITS = 16 * PC;
+};
+
+struct BfmArgs {
+  Geo x, g, z;
+  int cin, cout;
+  int tiles_w, tiles_h;       // tiles per plane
+  int64_t ntiles;             // n * d * tiles_h * tiles_w
+  int tiles_per_chunk, nchunks;
+  float mask_slope;
+  int vec_ok;                 // W % 8 == 0 and 16-byte aligned bases: whole units are loaded at once
+};
+
+__device__ __forceinline__ uint4 load_unit(const bf16_t* base, int w, int W, bool row_ok, bool vec) {
+  // 8 elements at w..w+7 of a row starting at `base`; zero where outside [0,W) or the row is invalid
+  uint4 u = {0, 0, 0, 0};
+  if (!row_ok) return u;
+  if (vec) {
+    if (w >= 0 && w + 8 <= W) u = *reinterpret_cast<const uint4*>(base + w);
+    return u;
+  }
+  uint32_t e[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? base[w + i] : 0;
+  u.x = e[0] | (e[1] << 16); u.y = e[2] | (e[3] << 16); u.z = e[4] | (e[5] << 16); u.w = e[6] | (e[7] << 16);
+  return u;
+}
+
+__device__ __forceinline__ uint32_t mask2(uint32_t v, uint32_t m, float slope) {
+  float v0 = __uint_as_float(v << 16), v1 = __uint_as_float(v & 0xffff0000u);
+  float m0 = __uint_as_float(m << 16), m1 = __uint_as_float(m & 0xffff0000u);
+  if (!(m0 > 0.f)) v0 *= slope;
+  if (!(m1 > 0.f)) v1 *= slope;
+  return (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+}
+
+template <int RBW, int TW, int TH, bool MASKED>
+__global__ void __launch_bounds__(192) bwd_filter_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
+                                                              const bf16_t* __restrict__ z, float* __restrict__ part,
+                                                              BfmArgs a) {
+  using T = BfTile<TW, TH>;
+  constexpr int NT = 192;
+  constexpr int CO_WG = 16 * RBW;
+  extern __shared__ uint4 lds[];
+  uint4* xl = lds;                    // [16 ci][3 kd][TH+2 rows][PR units]  (pitches PC, PD, PR)
+  uint4* gl = lds + T::X_UNITS;       // [CO_WG][TH rows][GU units]          (pitch PG)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lg = lane >> 4, lc = lane & 15;
+  const int chunk = blockIdx.x, co0 = blockIdx.y * CO_WG, ci0 = blockIdx.z * 16;
+  const int W = a.x.w, H = a.x.h, D = a.x.d;
+
+  // ---- this lane's three column blocks: combination q = (3*wave + cbi)*16 + lc = ci_local*9 + kd*3 + kh
+  int xb[3];
+#pragma unroll
+  for (int cbi = 0; cbi < 3; ++cbi) {
+    int q = (3 * wave + cbi) * 16 + lc;
+    int cil = q / 9, kd = (q % 9) / 3, kh = q % 3;
+    xb[cbi] = cil * T::PC + kd * T::PD + kh * T::PR + 1 + (T::GW == 4 ? lg : lg % T::GW) + (lg / T::GW) * T::PR;
+  }
+  const int ga_off = lc * T::PG + (T::GW == 4 ? lg : (lg / T::GW) * T::GU + lg % T::GW);
+  const bool edge_lo = (lg % T::GW) == 0, edge_hi = (lg % T::GW) == T::GW - 1;
+  const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
+  const bool do_db = (wave == 0) && (blockIdx.z == 0);
+
+  f32x4 acc[RBW][3][3];
+  f32x4 accdb[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    accdb[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cbi = 0; cbi < 3; ++cbi)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) acc[rb][cbi][kw] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
+
+  const int64_t t_begin = (int64_t)chunk * a.tiles_per_chunk;
+  const int64_t t_end = min(t_begin + a.tiles_per_chunk, a.ntiles);
+  for (int64_t tile = t_begin; tile < t_end; ++tile) {
+    int64_t r = tile;
+    const int tw = (int)(r % a.tiles_w); r /= a.tiles_w;
+    const int th = (int)(r % a.tiles_h); r /= a.tiles_h;
+    const int p = (int)(r % D);
+    const int n = (int)(r / D);
+    const int w0 = tw * TW, h0 = th * TH;
+
+    __syncthreads();   // everyone is done reading the previous tile
+    // ---- stage x: 16 channels x 3 planes x (TH+2) rows x XU units
+    constexpr int XITEMS = 16 * 3 * (TH + 2) * T::XU;
+    for (int item = tid; item < XITEMS; item += NT) {
+      int u = item % T::XU;
+      int q = item / T::XU;
+      int row = q % (TH + 2); q /= (TH + 2);
+      int kd = q % 3;
+      int cil = q / 3;
+      int ci = ci0 + cil, h = h0 + row - 1, pp = p + kd - 1;
+      int64_t gq = a.x.doff + pp;
+      bool ok = ci < a.cin && h >= 0 && h < H && gq >= 0 && gq < a.x.dglob;
+      const bf16_t* base = x + n * a.x.nstride + (int64_t)ci * a.x.cstride + (int64_t)(pp + a.x.hlo) * a.x.plane + (int64_t)h * W;
+      xl[cil * T::PC + kd * T::PD + row * T::PR + u] = load_unit(base, w0 - 8 + 8 * u, W, ok, a.vec_ok);
+    }
+    // ---- stage g (= dz, masked by the saved output if asked): CO_WG channels x TH rows x GU units
+    constexpr int GITEMS = CO_WG * TH * T::GU;
+    for (int item = tid; item < GITEMS; item += NT) {
+      int u = item % T::GU;
+      int q = item / T::GU;
+      int row = q % TH;
+      int col = q / TH;
+      int co = co0 + col, h = h0 + row;
+      bool ok = co < a.cout && h < H;
+      const bf16_t* base = dz + n * a.g.nstride + (int64_t)co * a.g.cstride + (int64_t)(p + a.g.hlo) * a.g.plane + (int64_t)h * W;
+      uint4 v = load_unit(base, w0 + 8 * u, W, ok, a.vec_ok);
+      if (MASKED) {
+        const bf16_t* mb = z + n * a.z.nstride + (int64_t)co * a.z.cstride + (int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)h * W;
+        uint4 m = load_unit(mb, w0 + 8 * u, W, ok, a.vec_ok);
+        v.x = mask2(v.x, m.x, a.mask_slope); v.y = mask2(v.y, m.y, a.mask_slope);
+        v.z = mask2(v.z, m.z, a.mask_slope); v.w = mask2(v.w, m.w, a.mask_slope);
+      }
+      gl[col * T::PG + row * T::GU + u] = v;
+    }
+    __syncthreads();
+
+    // ---- K-steps of 32 voxels
+#pragma unroll
+    for (int ks = 0; ks < T::KSTEPS; ++ks) {
+      // position of this K-step inside the tile: row (first row of the step) and unit offset
+      const int row = T::GW == 4 ? ks / T::KS_PER_ROW : ks * T::RPK;
+      const int uo = T::GW == 4 ? (ks % T::KS_PER_ROW) * 4 : 0;
+      bf16x8 A[RBW];
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) A[rb] = __builtin_bit_cast(bf16x8, gl[rb * 16 * T::PG + ga_off + row * T::GU + uo]);
+      if (do_db) {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) accdb[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb], ones, accdb[rb], 0, 0, 0);
+      }
+#pragma unroll
+      for (int cbi = 0; cbi < 3; ++cbi) {
+        const int ua = xb[cbi] + row * T::PR + uo;
+        const uint4 blk = xl[ua];
+        uint32_t pv = __builtin_amdgcn_ds_bpermute(bp_prev, blk.w);
+        uint32_t nx = __builtin_amdgcn_ds_bpermute(bp_next, blk.x);
+        const uint32_t* xw = reinterpret_cast<const uint32_t*>(xl);
+        if (edge_lo) pv = xw[(ua - 1) * 4 + 3];
+        if (edge_hi) nx = xw[(ua + 1) * 4];
+        const uint32_t s0 = __builtin_amdgcn_alignbit(blk.x, pv, 16);
+        const uint32_t s1 = __builtin_amdgcn_alignbit(blk.y, blk.x, 16);
+        const uint32_t s2 = __builtin_amdgcn_alignbit(blk.z, blk.y, 16);
+        const uint32_t s3 = __builtin_amdgcn_alignbit(blk.w, blk.z, 16);
+        const uint32_t s4 = __builtin_amdgcn_alignbit(nx, blk.w, 16);
+        const uint4 f0 = {s0, s1, s2, s3}, f2 = {s1, s2, s3, s4};
+        const bf16x8 B0 = __builtin_bit_cast(bf16x8, f0), B1 = __builtin_bit_cast(bf16x8, blk), B2 = __builtin_bit_cast(bf16x8, f2);
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+          acc[rb][cbi][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb], B0, acc[rb][cbi][0], 0, 0, 0);
+          acc[rb][cbi][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb], B1, acc[rb][cbi][1], 0, 0, 0);
+          acc[rb][cbi][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb], B2, acc[rb][cbi][2], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- partial tile -> workspace [chunk][cout][cin][27] (+ [chunk][cout] for the bias partial behind it)
+  float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
+#pragma unroll
+  for (int cbi = 0; cbi < 3; ++cbi) {
+    const int q = (3 * wave + cbi) * 16 + lc;
+    const int ci = ci0 + q / 9, kdkh = q % 9;
+    if (ci >= a.cin) continue;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + rb * 16 + 4 * lg + rr;
+        if (co < a.cout) {
+          float* o = pw + ((int64_t)co * a.cin + ci) * 27 + kdkh * 3;
+          o[0] = acc[rb][cbi][0][rr];
+          o[1] = acc[rb][cbi][1][rr];
+          o[2] = acc[rb][cbi][2][rr];
+        }
+      }
+  }
+  if (do_db && lc == 0) {
+    float* pb = part + (int64_t)a.nchunks * a.cout * a.cin * 27 + (int64_t)chunk * a.cout;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + rb * 16 + 4 * lg + rr;
+        if (co < a.cout) pb[co] = accdb[rb][rr];
+      }
+  }
+}
+
+// dw[i] = sum over chunks (in order) of part[chunk][i]; db likewise
+__global__ void bfm_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, float* __restrict__ db, int64_t nw,
+                                  int cout, int nchunks) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < nw) {
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * nw + i];
+    dw[i] = s;
+  } else if (db && i < nw + cout) {
+    const float* pb = part + (int64_t)nchunks * nw;
+    int co = (int)(i - nw);
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c) s += pb[(int64_t)c * cout + co];
+    db[co] = s;
+  }
+}
+
+struct BfPlan {
+  int tw, th, rbw;
+  int tiles_w, tiles_h;
+  int64_t ntiles;
+  int tiles_per_chunk, nchunks;
+};
+
+static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout) {
+  BfPlan p;
+  if (x->w > 32) { p.tw = 64; p.th = 2; }
+  else if (x->w > 16) { p.tw = 32; p.th = 4; }
+  else { p.tw = 16; p.th = 4; }
+  p.rbw = cout <= 16 ? 1 : (cout <= 32 ? 2 : 4);
+  p.tiles_w = (int)cdiv(x->w, p.tw);
+  p.tiles_h = (int)cdiv(x->h, p.th);
+  p.ntiles = (int64_t)x->n * x->d * p.tiles_h * p.tiles_w;
+  int64_t groups = cdiv(cout, 16 * p.rbw) * cdiv(x->c, 16);
+  // enough workgroups to fill the chip a few times over, few enough that the partials stay small
+  int64_t want = std::max<int64_t>(1, std::min<int64_t>(4096 / groups, 2048));
+  int64_t per_chunk_bytes = (int64_t)cout * x->c * 27 * 4;
+  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)512 << 20) / std::max<int64_t>(per_chunk_bytes, 1)));
+  p.tiles_per_chunk = (int)std::max<int64_t>(1, cdiv(p.ntiles, want));
+  p.nchunks = (int)std::max<int64_t>(1, cdiv(p.ntiles, p.tiles_per_chunk));
+  return p;
+}
+
+bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
+  if (x->dtype != H3D_BF16 || x->c < 1 || dz->c < 1) return false;
+  return true;
+}
+
+size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
+  BfPlan p = bf_plan_mfma(x, dz->c);
+  return (size_t)p.nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
+}
+
+template <int RBW, int TW, int TH, bool MASKED>
+static h3d_status bf_launch(void* handle, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part, const BfmArgs& a,
+                            dim3 grid, hipStream_t stream) {
+  using T = BfTile<TW, TH>;
+  constexpr size_t lds_bytes = (size_t)(T::X_UNITS + 16 * RBW * T::PG) * 16;
+  auto kern = bwd_filter_mfma_kernel<RBW, TW, TH, MASKED>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(192), lds_bytes, stream, x, dz, z, part, a);
+  return H3D_OK;
+}
+
+template <int RBW, bool MASKED>
+static h3d_status bf_pick_tile(void* handle, const BfPlan& p, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part,
+                               const BfmArgs& a, dim3 grid, hipStream_t s) {
+  if (p.tw == 64) return bf_launch<RBW, 64, 2, MASKED>(handle, x, dz, z, part, a, grid, s);
+  if (p.tw == 32) return bf_launch<RBW, 32, 4, MASKED>(handle, x, dz, z, part, a, grid, s);
+  return bf_launch<RBW, 16, 4, MASKED>(handle, x, dz, z, part, a, grid, s);
+}
+
+template <bool MASKED>
+static h3d_status bf_pick(void* handle, const BfPlan& p, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part,
+                          const BfmArgs& a, dim3 grid, hipStream_t s) {
+  if (p.rbw == 1) return bf_pick_tile<1, MASKED>(handle, p, x, dz, z, part, a, grid, s);
+  if (p.rbw == 2) return bf_pick_tile<2, MASKED>(handle, p, x, dz, z, part, a, grid, s);
+  return bf_pick_tile<4, MASKED>(handle, p, x, dz, z, part, a, grid, s);
+}
+
+h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw, float* db,
+                           float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
+  BfPlan p = bf_plan_mfma(x, dz->c);
+  if (!ws || ws_bytes < mfma_bf_ws_bytes(x, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
+  if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace must be 16-byte aligned");
+  BfmArgs a;
+  a.x = make_geo(x); a.g = make_geo(dz); a.z = z ? make_geo(z) : a.g;
+  a.cin = x->c; a.cout = dz->c;
+  a.tiles_w = p.tiles_w; a.tiles_h = p.tiles_h; a.ntiles = p.ntiles;
+  a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
+  a.mask_slope = mask_slope;
+  a.vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
+  int64_t gy = cdiv(a.cout, 16 * p.rbw), gz = cdiv(a.cin, 16);
+  if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
+  dim3 grid((unsigned)p.nchunks, (unsigned)gy, (unsigned)gz);
+  const bf16_t* xp = (const bf16_t*)x->data;
+  const bf16_t* gp = (const bf16_t*)dz->data;
+  const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
+  h3d_status st = z ? bf_pick<true>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream)
+                    : bf_pick<false>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream);
+  if (st != H3D_OK) return st;
+  int64_t nw = (int64_t)a.cout * a.cin * 27;
+  hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
+                     a.cout, a.nchunks);
+  return launch_status(handle, "conv3d_bwd_filter_mfma");
+}
+
+}  // namespace h3d

@@ -339,12 +339,4 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   return pick_variant<false>(handle, ip, mp, (const uint4*)ws, bias, (bf16_t*)out->data, a, out->n, stream);
 }
 
-// ---- backward-filter on the matrix cores: not built yet, the direct two-stage kernel serves every shape
-bool mfma_bf_supported(const h3d_tensor*, const h3d_tensor*) { return false; }
-size_t mfma_bf_ws_bytes(const h3d_tensor*, const h3d_tensor*) { return 0; }
-h3d_status bwd_filter_mfma(void* handle, const h3d_tensor*, const h3d_tensor*, const h3d_tensor*, float*, float*, float, void*,
-                           size_t, hipStream_t) {
-  return fail(handle, H3D_EUNSUPPORTED, "bwd_filter_mfma: not built");
-}
-
 }  // namespace h3d

@@ -55,7 +55,8 @@ def test_conv3d_three_passes_unsharded(shape, dtype):
     dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
     db = torch.full((Co,), 777.0, device="cuda")
     h3d.conv3d_bwd_filter(xg, dzg, zq_g, dw, db, h3d.ACT_LEAKY, alpha)
-    tol_w = 1e-5 if dtype == "f32" else 2e-2
+    # dW stays fp32: with exact bf16 products and fp32 accumulation the error is far below the bf16 bar
+    tol_w = 1e-5 if dtype == "f32" else 2e-4
     assert rel_l2(from_dev(dw), dwo) <= tol_w
     assert rel_l2(from_dev(db), dbo) <= tol_w
     # deterministic split-spatial reduction: a second call returns identical bits
