@@ -106,6 +106,14 @@ h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, const h3d_te
                                  float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
                                  void* stream);
 
+/* ---- activation backward as a separate pass (Sec. IV: leaky-ReLU after every conv; U-Net: ReLU) ----
+ * g = (dz + dz2) * (z > 0 ? 1 : slope) on the shard INTERIOR; dz2 may be NULL (it merges the two
+ * gradient branches of a skip connection).  z is the saved forward output.  Halo planes of g are
+ * not written: they are filled by the backward halo exchange, after which the backward
+ * convolutions are called with act NONE.  All tensors agree in n,c,d,h,w,offsets,dtype; halos may differ. */
+h3d_status h3d_act_bwd(void* handle, const h3d_tensor* dz, const h3d_tensor* dz2, const h3d_tensor* z,
+                       h3d_tensor* g, int act, float alpha, void* stream);
+
 /* ---- 2x2x2 stride-2 pooling of the shard interior (Table I: stride-2 pooling; Sec. III-A) ----
  * y interior extents are x's halved; d, h, w and d_offset of x must be even so that no window
  * straddles a shard face (else H3D_EUNSUPPORTED).  Halo planes of x and y are neither read nor

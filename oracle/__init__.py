@@ -129,6 +129,15 @@ def conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, act=ACT_NONE, alpha=0.0
     return dw, db
 
 
+def act_bwd(dz: Slab, dz2: Slab | None, z: Slab, act: int, alpha: float = 0.0, g_halo=(0, 0)) -> Slab:
+    """g = (dz + dz2) * (z > 0 ? 1 : slope) on the interior (activation derivative, Sec. IV); halo planes of g are zero."""
+    slope = alpha if act == ACT_LEAKY else (0.0 if act == ACT_RELU else 1.0)
+    t = dz.interior + (dz2.interior if dz2 is not None else 0.0)
+    g = dz.like(dz.a.shape[1], g_halo[0], g_halo[1], fill=0.0)
+    g.interior[...] = t * np.where(z.interior > 0, 1.0, slope)
+    return g
+
+
 def pool3d_fwd(x: Slab, mode: int, y_halo=(0, 0)) -> Slab:
     """2x2x2 stride-2 pooling of the interior (Table I: stride-2 pooling)."""
     n, c, _, h, w = x.a.shape

@@ -46,6 +46,7 @@ _SIGNATURES = {
     "h3d_conv3d_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_act_bwd": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
     "h3d_halo_bytes": (ctypes.c_size_t, [_T, ctypes.c_int]),
@@ -218,6 +219,12 @@ def h3d_conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, dw, db, act: int = 
     return dw, db
 
 
+def h3d_act_bwd(dz: Slab, dz2: Slab | None, z: Slab, g: Slab, act: int, alpha: float = 0.0):
+    _check(lib().h3d_act_bwd(handle(), ctypes.byref(dz.desc()), ctypes.byref(dz2.desc()) if dz2 is not None else None,
+                             ctypes.byref(z.desc()), ctypes.byref(g.desc()), act, alpha, _stream()))
+    return g
+
+
 def h3d_pool3d_fwd(x: Slab, y: Slab, mode: int):
     _check(lib().h3d_pool3d_fwd(handle(), ctypes.byref(x.desc()), ctypes.byref(y.desc()), mode, _stream()))
     return y
@@ -299,7 +306,7 @@ def h3d_mse_fwd_bwd(pred, target, loss, dpred):
 
 # short aliases
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
-pool3d_fwd, pool3d_bwd = h3d_pool3d_fwd, h3d_pool3d_bwd
+pool3d_fwd, pool3d_bwd, act_bwd = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c

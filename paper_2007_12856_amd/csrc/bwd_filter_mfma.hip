@@ -58,17 +58,19 @@ struct BfmArgs {
   int vec_ok;                 // W % 8 == 0 and 16-byte aligned bases: whole units are loaded at once
 };
 
-__device__ __forceinline__ uint4 load_unit(const bf16_t* base, int w, int W, bool row_ok, bool vec) {
-  // 8 elements at w..w+7 of a row starting at `base`; zero where outside [0,W) or the row is invalid
+__device__ __forceinline__ uint4 load_unit(const bf16_t* base, int w, int W, bool row_ok, bool vec, int w0) {
+  // 8 elements at absolute columns w..w+7 of a row; `base` points at column w0 of that row.
+  // Zero where outside [0,W) or the row is invalid.
   uint4 u = {0, 0, 0, 0};
   if (!row_ok) return u;
+  base += w - w0;
   if (vec) {
-    if (w >= 0 && w + 8 <= W) u = *reinterpret_cast<const uint4*>(base + w);
+    if (w >= 0 && w + 8 <= W) u = *reinterpret_cast<const uint4*>(base);
     return u;
   }
   uint32_t e[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? base[w + i] : 0;
+  for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? base[i] : 0;
   u.x = e[0] | (e[1] << 16); u.y = e[2] | (e[3] << 16); u.z = e[4] | (e[5] << 16); u.w = e[6] | (e[7] << 16);
   return u;
 }
@@ -81,34 +83,70 @@ __device__ __forceinline__ uint32_t mask2(uint32_t v, uint32_t m, float slope) {
   return (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
 }
 
-template <int RBW, int TW, int TH, bool MASKED>
-__global__ void __launch_bounds__(192) bwd_filter_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
-                                                              const bf16_t* __restrict__ z, float* __restrict__ part,
-                                                              BfmArgs a) {
+// SMALLCI (Cin <= 5: the first layer of both networks): the 48 columns 0..47 hold every (ci,kd,kh)
+// combination, so instead of splitting columns the four wavefronts of a workgroup split the K-steps
+// of each tile and their accumulators are added in wavefront order at the end.
+template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI>
+__global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_kernel(const bf16_t* __restrict__ x,
+                                                                              const bf16_t* __restrict__ dz,
+                                                                              const bf16_t* __restrict__ z,
+                                                                              float* __restrict__ part, BfmArgs a) {
   using T = BfTile<TW, TH>;
-  constexpr int NT = 192;
-  constexpr int CO_WG = 16 * RBW;
+  static_assert(!SMALLCI || NRG == 1, "row groups only in the column-split mode");
+  constexpr int NW = SMALLCI ? 4 : 3 * NRG;   // NRG groups of three wavefronts, each group owns RBW row blocks
+  constexpr int NT = 64 * NW;
+  constexpr int CI_WG = SMALLCI ? 6 : 16;     // channels staged per workgroup
+  constexpr int CO_WG = 16 * RBW * NRG;
   extern __shared__ uint4 lds[];
-  uint4* xl = lds;                    // [16 ci][3 kd][TH+2 rows][PR units]  (pitches PC, PD, PR)
-  uint4* gl = lds + T::X_UNITS;       // [CO_WG][TH rows][GU units]          (pitch PG)
+  uint4* xl = lds;                    // [CI_WG][3 kd][TH+2 rows][PR units]  (pitches PC, PD, PR)
+  uint4* gl = lds + CI_WG * T::PC;    // [CO_WG][TH rows][GU units]          (pitch PG)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
   const int chunk = blockIdx.x, co0 = blockIdx.y * CO_WG, ci0 = blockIdx.z * 16;
   const int W = a.x.w, H = a.x.h, D = a.x.d;
+  const int rg = SMALLCI ? 0 : wave / 3;       // row group of this wavefront
+  const int cb0 = SMALLCI ? 0 : 3 * (wave % 3);  // first of this wavefront's three column blocks
 
-  // ---- this lane's three column blocks: combination q = (3*wave + cbi)*16 + lc = ci_local*9 + kd*3 + kh
+  // ---- this lane's three column blocks: combination q = (cb0 + cbi)*16 + lc = ci_local*9 + kd*3 + kh
   int xb[3];
 #pragma unroll
   for (int cbi = 0; cbi < 3; ++cbi) {
-    int q = (3 * wave + cbi) * 16 + lc;
+    int q = (cb0 + cbi) * 16 + lc;
     int cil = q / 9, kd = (q % 9) / 3, kh = q % 3;
     xb[cbi] = cil * T::PC + kd * T::PD + kh * T::PR + 1 + (T::GW == 4 ? lg : lg % T::GW) + (lg / T::GW) * T::PR;
   }
-  const int ga_off = lc * T::PG + (T::GW == 4 ? lg : (lg / T::GW) * T::GU + lg % T::GW);
+  const int ga_off = (rg * 16 * RBW + lc) * T::PG + (T::GW == 4 ? lg : (lg / T::GW) * T::GU + lg % T::GW);
   const bool edge_lo = (lg % T::GW) == 0, edge_hi = (lg % T::GW) == T::GW - 1;
   const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
-  const bool do_db = (wave == 0) && (blockIdx.z == 0);
+  const bool do_db = (SMALLCI || wave % 3 == 0) && (blockIdx.z == 0);
+
+  // ---- staging plan (tile-invariant part): which units this thread copies
+  constexpr int XITEMS = CI_WG * 3 * (TH + 2) * T::XU;
+  constexpr int XR = (XITEMS + NT - 1) / NT;
+  constexpr int GITEMS = CO_WG * TH * T::GU;
+  constexpr int GR = (GITEMS + NT - 1) / NT;
+  int x_meta[XR];     // row | kd << 8 | u << 12 | cil << 20 | valid << 28
+  int g_meta[GR];     // row | u << 8 | col << 16 | valid << 28
+#pragma unroll
+  for (int r = 0; r < XR; ++r) {
+    int item = tid + r * NT;
+    int u = item % T::XU;
+    int q = item / T::XU;
+    int row = q % (TH + 2); q /= (TH + 2);
+    int kd = q % 3;
+    int cil = q / 3;
+    x_meta[r] = item < XITEMS ? (row | (kd << 8) | (u << 12) | (cil << 20) | ((ci0 + cil < a.cin ? 1 : 0) << 28)) : -1;
+  }
+#pragma unroll
+  for (int r = 0; r < GR; ++r) {
+    int item = tid + r * NT;
+    int u = item % T::GU;
+    int q = item / T::GU;
+    int row = q % TH;
+    int col = q / TH;
+    g_meta[r] = item < GITEMS ? (row | (u << 8) | (col << 16) | ((co0 + col < a.cout ? 1 : 0) << 28)) : -1;
+  }
 
   f32x4 acc[RBW][3][3];
   f32x4 accdb[RBW];
@@ -133,45 +171,53 @@ __global__ void __launch_bounds__(192) bwd_filter_mfma_kernel(const bf16_t* __re
     const int n = (int)(r / D);
     const int w0 = tw * TW, h0 = th * TH;
 
-    __syncthreads();   // everyone is done reading the previous tile
-    // ---- stage x: 16 channels x 3 planes x (TH+2) rows x XU units
-    constexpr int XITEMS = 16 * 3 * (TH + 2) * T::XU;
-    for (int item = tid; item < XITEMS; item += NT) {
-      int u = item % T::XU;
-      int q = item / T::XU;
-      int row = q % (TH + 2); q /= (TH + 2);
-      int kd = q % 3;
-      int cil = q / 3;
-      int ci = ci0 + cil, h = h0 + row - 1, pp = p + kd - 1;
-      int64_t gq = a.x.doff + pp;
-      bool ok = ci < a.cin && h >= 0 && h < H && gq >= 0 && gq < a.x.dglob;
-      const bf16_t* base = x + n * a.x.nstride + (int64_t)ci * a.x.cstride + (int64_t)(pp + a.x.hlo) * a.x.plane + (int64_t)h * W;
-      xl[cil * T::PC + kd * T::PD + row * T::PR + u] = load_unit(base, w0 - 8 + 8 * u, W, ok, a.vec_ok);
+    // ---- global -> registers for this tile (issued before the barrier so they overlap the
+    //      other wavefronts' last K-steps), then registers -> LDS
+    uint4 xv[XR], gv[GR], mvv[MASKED ? GR : 1];
+    const bf16_t* xt = x + n * a.x.nstride + (int64_t)(p + a.x.hlo - 1) * a.x.plane + (int64_t)(h0 - 1) * W + w0;
+#pragma unroll
+    for (int i = 0; i < XR; ++i) {
+      const int m = x_meta[i];
+      const int row = m & 0xff, kd = (m >> 8) & 0xf, u = (m >> 12) & 0xff, cil = (m >> 20) & 0xff;
+      const int h = h0 + row - 1;
+      const int64_t gq = a.x.doff + p + kd - 1;
+      const bool ok = m >= 0 && (m >> 28) && h >= 0 && h < H && gq >= 0 && gq < a.x.dglob;
+      xv[i] = load_unit(xt + (int64_t)(ci0 + cil) * a.x.cstride + (int64_t)kd * a.x.plane + row * W, w0 + 8 * u - 8, W, ok,
+                        a.vec_ok, w0);
     }
-    // ---- stage g (= dz, masked by the saved output if asked): CO_WG channels x TH rows x GU units
-    constexpr int GITEMS = CO_WG * TH * T::GU;
-    for (int item = tid; item < GITEMS; item += NT) {
-      int u = item % T::GU;
-      int q = item / T::GU;
-      int row = q % TH;
-      int col = q / TH;
-      int co = co0 + col, h = h0 + row;
-      bool ok = co < a.cout && h < H;
-      const bf16_t* base = dz + n * a.g.nstride + (int64_t)co * a.g.cstride + (int64_t)(p + a.g.hlo) * a.g.plane + (int64_t)h * W;
-      uint4 v = load_unit(base, w0 + 8 * u, W, ok, a.vec_ok);
+    const bf16_t* gt = dz + n * a.g.nstride + (int64_t)(p + a.g.hlo) * a.g.plane + (int64_t)h0 * W + w0;
+    const bf16_t* zt = MASKED ? z + n * a.z.nstride + (int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)h0 * W + w0 : nullptr;
+#pragma unroll
+    for (int i = 0; i < GR; ++i) {
+      const int m = g_meta[i];
+      const int row = m & 0xff, u = (m >> 8) & 0xff, col = (m >> 16) & 0xfff;
+      const bool ok = m >= 0 && (m >> 28) && h0 + row < H;
+      gv[i] = load_unit(gt + (int64_t)(co0 + col) * a.g.cstride + row * W, w0 + 8 * u, W, ok, a.vec_ok, w0);
+      if (MASKED) mvv[i] = load_unit(zt + (int64_t)(co0 + col) * a.z.cstride + row * W, w0 + 8 * u, W, ok, a.vec_ok, w0);
+    }
+    __syncthreads();   // everyone is done reading the previous tile
+#pragma unroll
+    for (int i = 0; i < XR; ++i) {
+      const int m = x_meta[i];
+      if (m >= 0) xl[((m >> 20) & 0xff) * T::PC + ((m >> 8) & 0xf) * T::PD + (m & 0xff) * T::PR + ((m >> 12) & 0xff)] = xv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < GR; ++i) {
+      const int m = g_meta[i];
+      if (m < 0) continue;
+      uint4 v = gv[i];
       if (MASKED) {
-        const bf16_t* mb = z + n * a.z.nstride + (int64_t)co * a.z.cstride + (int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)h * W;
-        uint4 m = load_unit(mb, w0 + 8 * u, W, ok, a.vec_ok);
-        v.x = mask2(v.x, m.x, a.mask_slope); v.y = mask2(v.y, m.y, a.mask_slope);
-        v.z = mask2(v.z, m.z, a.mask_slope); v.w = mask2(v.w, m.w, a.mask_slope);
+        v.x = mask2(v.x, mvv[i].x, a.mask_slope); v.y = mask2(v.y, mvv[i].y, a.mask_slope);
+        v.z = mask2(v.z, mvv[i].z, a.mask_slope); v.w = mask2(v.w, mvv[i].w, a.mask_slope);
       }
-      gl[col * T::PG + row * T::GU + u] = v;
+      gl[((m >> 16) & 0xfff) * T::PG + (m & 0xff) * T::GU + ((m >> 8) & 0xff)] = v;
     }
     __syncthreads();
 
     // ---- K-steps of 32 voxels
 #pragma unroll
     for (int ks = 0; ks < T::KSTEPS; ++ks) {
+      if (SMALLCI && (ks % NW) != wave) continue;
       // position of this K-step inside the tile: row (first row of the step) and unit offset
       const int row = T::GW == 4 ? ks / T::KS_PER_ROW : ks * T::RPK;
       const int uo = T::GW == 4 ? (ks % T::KS_PER_ROW) * 4 : 0;
@@ -208,18 +254,38 @@ __global__ void __launch_bounds__(192) bwd_filter_mfma_kernel(const bf16_t* __re
     }
   }
 
+  if (SMALLCI) {
+    // add the four wavefronts' accumulators in wavefront order (fixed, so the result is reproducible)
+    f32x4* red = reinterpret_cast<f32x4*>(lds);     // [3][64] slots, reused for every accumulator
+    auto wave_sum = [&](f32x4& v) {
+      __syncthreads();
+      if (wave > 0) red[(wave - 1) * 64 + lane] = v;
+      __syncthreads();
+      if (wave == 0) v = ((v + red[lane]) + red[64 + lane]) + red[128 + lane];
+    };
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      wave_sum(accdb[rb]);
+#pragma unroll
+      for (int cbi = 0; cbi < 3; ++cbi)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wave_sum(acc[rb][cbi][kw]);
+    }
+    if (wave > 0) return;
+  }
+
   // ---- partial tile -> workspace [chunk][cout][cin][27] (+ [chunk][cout] for the bias partial behind it)
   float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
 #pragma unroll
   for (int cbi = 0; cbi < 3; ++cbi) {
-    const int q = (3 * wave + cbi) * 16 + lc;
+    const int q = (cb0 + cbi) * 16 + lc;
     const int ci = ci0 + q / 9, kdkh = q % 9;
     if (ci >= a.cin) continue;
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const int co = co0 + rb * 16 + 4 * lg + rr;
+        const int co = co0 + (rg * RBW + rb) * 16 + 4 * lg + rr;
         if (co < a.cout) {
           float* o = pw + ((int64_t)co * a.cin + ci) * 27 + kdkh * 3;
           o[0] = acc[rb][cbi][0][rr];
@@ -234,31 +300,43 @@ __global__ void __launch_bounds__(192) bwd_filter_mfma_kernel(const bf16_t* __re
     for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const int co = co0 + rb * 16 + 4 * lg + rr;
+        const int co = co0 + (rg * RBW + rb) * 16 + 4 * lg + rr;
         if (co < a.cout) pb[co] = accdb[rb][rr];
       }
   }
 }
 
-// dw[i] = sum over chunks (in order) of part[chunk][i]; db likewise
-__global__ void bfm_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, float* __restrict__ db, int64_t nw,
-                                  int cout, int nchunks) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < nw) {
-    float s = 0.f;
-    for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * nw + i];
-    dw[i] = s;
-  } else if (db && i < nw + cout) {
-    const float* pb = part + (int64_t)nchunks * nw;
-    int co = (int)(i - nw);
-    float s = 0.f;
-    for (int c = 0; c < nchunks; ++c) s += pb[(int64_t)c * cout + co];
-    db[co] = s;
+// Second stage: out[i] = sum over chunks of part[chunk][i] in a FIXED order.  A block takes 16
+// consecutive outputs; 16 thread groups each add every 16th chunk in increasing order, then the 16
+// group sums are added in group order.  (dw and the bias partials share the kernel: the bias
+// partials are stored behind the dw partials.)
+__global__ void __launch_bounds__(256) bfm_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                         float* __restrict__ db, int64_t nw, int cout, int nchunks) {
+  __shared__ float red[16][17];
+  const int o = threadIdx.x & 15, cg = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + o;
+  const int64_t nout = nw + cout;
+  float s = 0.f;
+  if (i < nout) {
+    const bool is_w = i < nw;
+    const float* base = is_w ? part + i : part + (int64_t)nchunks * nw + (i - nw);
+    const int64_t stride = is_w ? nw : cout;
+    for (int c = cg; c < nchunks; c += 16) s += base[(int64_t)c * stride];
+  }
+  red[cg][o] = s;
+  __syncthreads();
+  if (cg == 0 && i < nout) {
+    float t = red[0][o];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) t += red[k][o];
+    if (i < nw) dw[i] = t;
+    else if (db) db[i - nw] = t;
   }
 }
 
 struct BfPlan {
-  int tw, th, rbw;
+  int tw, th, rbw, nrg;
+  bool smallci;
   int tiles_w, tiles_h;
   int64_t ntiles;
   int tiles_per_chunk, nchunks;
@@ -269,15 +347,19 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout) {
   if (x->w > 32) { p.tw = 64; p.th = 2; }
   else if (x->w > 16) { p.tw = 32; p.th = 4; }
   else { p.tw = 16; p.th = 4; }
-  p.rbw = cout <= 16 ? 1 : (cout <= 32 ? 2 : 4);
+  p.smallci = x->c <= 5;
+  p.rbw = cout <= 16 ? 1 : 2;
+  p.nrg = (cout > 32 && !p.smallci) ? 2 : 1;
   p.tiles_w = (int)cdiv(x->w, p.tw);
   p.tiles_h = (int)cdiv(x->h, p.th);
   p.ntiles = (int64_t)x->n * x->d * p.tiles_h * p.tiles_w;
-  int64_t groups = cdiv(cout, 16 * p.rbw) * cdiv(x->c, 16);
-  // enough workgroups to fill the chip a few times over, few enough that the partials stay small
-  int64_t want = std::max<int64_t>(1, std::min<int64_t>(4096 / groups, 2048));
-  int64_t per_chunk_bytes = (int64_t)cout * x->c * 27 * 4;
-  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)512 << 20) / std::max<int64_t>(per_chunk_bytes, 1)));
+  int64_t groups = cdiv(cout, 16 * p.rbw * p.nrg) * cdiv(x->c, 16);
+  // Number of voxel chunks: enough workgroups to fill 256 CUs several times over, at least 4 tiles
+  // per workgroup, and partials (chunks x Cout x Cin x 27 floats) that stay small next to the tensors.
+  int64_t per_chunk_bytes = std::max<int64_t>(1, (int64_t)cout * x->c * 27 * 4);
+  int64_t want = std::max<int64_t>(1, 1024 / groups);
+  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)48 << 20) / per_chunk_bytes));
+  want = std::min<int64_t>(want, std::max<int64_t>(1, p.ntiles / 4));
   p.tiles_per_chunk = (int)std::max<int64_t>(1, cdiv(p.ntiles, want));
   p.nchunks = (int)std::max<int64_t>(1, cdiv(p.ntiles, p.tiles_per_chunk));
   return p;
@@ -285,7 +367,8 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout) {
 
 bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
   if (x->dtype != H3D_BF16 || x->c < 1 || dz->c < 1) return false;
-  return true;
+  int64_t sample = (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w;
+  return sample < ((int64_t)1 << 30);
 }
 
 size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
@@ -293,36 +376,41 @@ size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
   return (size_t)p.nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
 }
 
-template <int RBW, int TW, int TH, bool MASKED>
+template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI>
 static h3d_status bf_launch(void* handle, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part, const BfmArgs& a,
                             dim3 grid, hipStream_t stream) {
   using T = BfTile<TW, TH>;
-  constexpr size_t lds_bytes = (size_t)(T::X_UNITS + 16 * RBW * T::PG) * 16;
-  auto kern = bwd_filter_mfma_kernel<RBW, TW, TH, MASKED>;
+  constexpr size_t tile_bytes = (size_t)((SMALLCI ? 6 : 16) * T::PC + 16 * RBW * NRG * T::PG) * 16;
+  constexpr size_t lds_bytes = tile_bytes < 3 * 64 * 16 ? 3 * 64 * 16 : tile_bytes;
+  auto kern = bwd_filter_mfma_kernel<RBW, NRG, TW, TH, MASKED, SMALLCI>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return fail(handle, H3D_EHIP, "conv3d_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(192), lds_bytes, stream, x, dz, z, part, a);
+  hipLaunchKernelGGL(kern, grid, dim3(SMALLCI ? 256 : 192 * NRG), lds_bytes, stream, x, dz, z, part, a);
   return H3D_OK;
 }
 
-template <int RBW, bool MASKED>
+template <int RBW, int NRG, bool MASKED, bool SMALLCI>
 static h3d_status bf_pick_tile(void* handle, const BfPlan& p, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part,
                                const BfmArgs& a, dim3 grid, hipStream_t s) {
-  if (p.tw == 64) return bf_launch<RBW, 64, 2, MASKED>(handle, x, dz, z, part, a, grid, s);
-  if (p.tw == 32) return bf_launch<RBW, 32, 4, MASKED>(handle, x, dz, z, part, a, grid, s);
-  return bf_launch<RBW, 16, 4, MASKED>(handle, x, dz, z, part, a, grid, s);
+  if (p.tw == 64) return bf_launch<RBW, NRG, 64, 2, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
+  if (p.tw == 32) return bf_launch<RBW, NRG, 32, 4, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
+  return bf_launch<RBW, NRG, 16, 4, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
 }
 
 template <bool MASKED>
 static h3d_status bf_pick(void* handle, const BfPlan& p, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part,
                           const BfmArgs& a, dim3 grid, hipStream_t s) {
-  if (p.rbw == 1) return bf_pick_tile<1, MASKED>(handle, p, x, dz, z, part, a, grid, s);
-  if (p.rbw == 2) return bf_pick_tile<2, MASKED>(handle, p, x, dz, z, part, a, grid, s);
-  return bf_pick_tile<4, MASKED>(handle, p, x, dz, z, part, a, grid, s);
+  if (p.smallci) {
+    if (p.rbw == 1) return bf_pick_tile<1, 1, MASKED, true>(handle, p, x, dz, z, part, a, grid, s);
+    return bf_pick_tile<2, 1, MASKED, true>(handle, p, x, dz, z, part, a, grid, s);
+  }
+  if (p.rbw == 1) return bf_pick_tile<1, 1, MASKED, false>(handle, p, x, dz, z, part, a, grid, s);
+  if (p.nrg == 1) return bf_pick_tile<2, 1, MASKED, false>(handle, p, x, dz, z, part, a, grid, s);
+  return bf_pick_tile<2, 2, MASKED, false>(handle, p, x, dz, z, part, a, grid, s);
 }
 
 h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw, float* db,
@@ -337,7 +425,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
   a.mask_slope = mask_slope;
   a.vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
-  int64_t gy = cdiv(a.cout, 16 * p.rbw), gz = cdiv(a.cin, 16);
+  int64_t gy = cdiv(a.cout, 16 * p.rbw * p.nrg), gz = cdiv(a.cin, 16);
   if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
   dim3 grid((unsigned)p.nchunks, (unsigned)gy, (unsigned)gz);
   const bf16_t* xp = (const bf16_t*)x->data;
@@ -347,7 +435,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
                     : bf_pick<false>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream);
   if (st != H3D_OK) return st;
   int64_t nw = (int64_t)a.cout * a.cin * 27;
-  hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
+  hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
                      a.cout, a.nchunks);
   return launch_status(handle, "conv3d_bwd_filter_mfma");
 }

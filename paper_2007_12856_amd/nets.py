@@ -111,3 +111,101 @@ class CosmoFlowStack:
 
     def conv_flops(self) -> int:
         return sum(op["flops"] for op in self.ops if op["name"].startswith("conv"))
+
+
+class UNetLevel:
+    """One encoder/decoder level of a 3D U-Net on a depth shard (Sec. II-C, III-A): two 3x3x3
+    conv+ReLU (the first also produces its output's halo plane from the 2-plane input halo), 2x2x2
+    max-pool, two conv+ReLU one level down, 2x2x2 stride-2 transposed conv back up, channel concat
+    with the skip tensor, conv+ReLU.  Halos that cannot be recomputed locally arrive as face
+    buffers (what the neighbour's halo_pack produced) and go in through halo_unpack.  Backward:
+    activation-backward passes produce g tensors whose halos are exchanged the same way."""
+
+    def __init__(self, x: Slab, params: dict, dout: torch.Tensor, faces: dict):
+        from . import (ACT_RELU, FACE_D_HI, FACE_D_LO, POOL_MAX, act_bwd, concat_c, deconv2_bwd_data, deconv2_bwd_filter,
+                       deconv2_fwd, halo_unpack, split_c)
+        self.ws = Workspace()
+        self.x, self.P, self.faces = x, params, faces
+        dt, dev = x.t.dtype, x.t.device
+        n, _, _, H, W = x.t.shape
+        d, off, dg = x.d, x.d_offset, x.d_global
+        ws, R, NONE = self.ws, ACT_RELU, ACT_NONE
+
+        def slab(c, halo, level=1):
+            s = 2 if level == 2 else 1
+            t = torch.zeros((n, c, d // s + 2 * halo, H // s, W // s), dtype=dt, device=dev)
+            return Slab(t, halo, halo, off // s, dg // s)
+
+        def grads(name):
+            w, b = params[name]
+            return torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev)
+
+        T = self.T = {"a1": slab(32, 1), "a2": slab(64, 0), "p": slab(64, 2, 2), "b1": slab(64, 1, 2), "b2": slab(128, 0, 2),
+                      "up": slab(64, 0), "cat": slab(128, 1), "out": slab(64, 0)}
+        G = self.G = {"dout": Slab(dout, 0, 0, off, dg), "g6": slab(64, 1), "dcat": slab(128, 0), "d_skip": slab(64, 0),
+                      "d_up": slab(64, 0), "d_b2": slab(128, 0, 2), "g4": slab(128, 1, 2), "d_b1": slab(64, 0, 2),
+                      "g3": slab(64, 1, 2), "d_p": slab(64, 0, 2), "d_a2": slab(64, 0), "g2": slab(64, 1), "d_a1": slab(32, 0),
+                      "g1": slab(32, 1), "dx": slab(1, 0)}
+        self.dP = {k: grads(k) for k in params}
+        self.ops = []
+
+        def op(name, fn, flops=0):
+            self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": 0})
+
+        def cflops(name, out):   # 2*27*Cin*Cout per produced output voxel
+            w = params[name][0]
+            return 2 * 27 * w.shape[0] * w.shape[1] * out.t.numel() // out.t.shape[1]
+
+        def exchange(name, t, width):
+            lo, hi = faces[name]
+            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, width), halo_unpack(hi, t, FACE_D_HI, width)))
+
+        P = params
+        op("c1_fwd", lambda: conv3d_fwd(x, *P["c1"], T["a1"], R, 0.0, ws), cflops("c1", T["a1"]))
+        op("c2_fwd", lambda: conv3d_fwd(T["a1"], *P["c2"], T["a2"], R, 0.0, ws), cflops("c2", T["a2"]))
+        op("pool_fwd", lambda: pool3d_fwd(T["a2"], T["p"], POOL_MAX))
+        exchange("p", T["p"], 2)
+        op("c3_fwd", lambda: conv3d_fwd(T["p"], *P["c3"], T["b1"], R, 0.0, ws), cflops("c3", T["b1"]))
+        op("c4_fwd", lambda: conv3d_fwd(T["b1"], *P["c4"], T["b2"], R, 0.0, ws), cflops("c4", T["b2"]))
+        op("up_fwd", lambda: deconv2_fwd(T["b2"], *P["up"], T["up"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
+        op("concat", lambda: concat_c(T["a2"], T["up"], T["cat"]))
+        exchange("cat", T["cat"], 1)
+        op("c6_fwd", lambda: conv3d_fwd(T["cat"], *P["c6"], T["out"], R, 0.0, ws), cflops("c6", T["out"]))
+        self.n_fwd_ops = len(self.ops)
+        # ---- backward
+        dP = self.dP
+        op("act_bwd_out", lambda: act_bwd(G["dout"], None, T["out"], G["g6"], R))
+        exchange("g6", G["g6"], 1)
+        op("c6_bwd_filter", lambda: conv3d_bwd_filter(T["cat"], G["g6"], None, *dP["c6"], NONE, 0.0, ws), cflops("c6", T["out"]))
+        op("c6_bwd_data", lambda: conv3d_bwd_data(G["g6"], None, P["c6"][0], G["dcat"], NONE, 0.0, ws), cflops("c6", T["out"]))
+        op("split", lambda: split_c(G["dcat"], G["d_skip"], G["d_up"]))
+        op("up_bwd_filter", lambda: deconv2_bwd_filter(T["b2"], G["d_up"], *dP["up"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
+        op("up_bwd_data", lambda: deconv2_bwd_data(G["d_up"], P["up"][0], G["d_b2"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
+        op("act_bwd_b2", lambda: act_bwd(G["d_b2"], None, T["b2"], G["g4"], R))
+        exchange("g4", G["g4"], 1)
+        op("c4_bwd_filter", lambda: conv3d_bwd_filter(T["b1"], G["g4"], None, *dP["c4"], NONE, 0.0, ws), cflops("c4", T["b2"]))
+        op("c4_bwd_data", lambda: conv3d_bwd_data(G["g4"], None, P["c4"][0], G["d_b1"], NONE, 0.0, ws), cflops("c4", T["b2"]))
+        op("act_bwd_b1", lambda: act_bwd(G["d_b1"], None, T["b1"], G["g3"], R))
+        exchange("g3", G["g3"], 1)
+        op("c3_bwd_filter", lambda: conv3d_bwd_filter(T["p"], G["g3"], None, *dP["c3"], NONE, 0.0, ws), cflops("c3", G["d_b1"]))
+        op("c3_bwd_data", lambda: conv3d_bwd_data(G["g3"], None, P["c3"][0], G["d_p"], NONE, 0.0, ws), cflops("c3", G["d_b1"]))
+        op("pool_bwd", lambda: pool3d_bwd(G["d_p"], T["a2"], G["d_a2"], POOL_MAX))
+        op("act_bwd_a2", lambda: act_bwd(G["d_a2"], G["d_skip"], T["a2"], G["g2"], R))
+        exchange("g2", G["g2"], 1)
+        op("c2_bwd_filter", lambda: conv3d_bwd_filter(T["a1"], G["g2"], None, *dP["c2"], NONE, 0.0, ws), cflops("c2", T["a2"]))
+        op("c2_bwd_data", lambda: conv3d_bwd_data(G["g2"], None, P["c2"][0], G["d_a1"], NONE, 0.0, ws), cflops("c2", T["a2"]))
+        op("act_bwd_a1", lambda: act_bwd(G["d_a1"], None, T["a1"], G["g1"], R))
+        exchange("g1", G["g1"], 1)
+        op("c1_bwd_filter", lambda: conv3d_bwd_filter(x, G["g1"], None, *dP["c1"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
+        op("c1_bwd_data", lambda: conv3d_bwd_data(G["g1"], None, P["c1"][0], G["dx"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
+
+    def forward(self):
+        for o in self.ops[:self.n_fwd_ops]:
+            o["fn"]()
+
+    def step(self):
+        for o in self.ops:
+            o["fn"]()
+
+    def conv_flops(self) -> int:
+        return sum(o["flops"] for o in self.ops)

@@ -40,3 +40,31 @@ def cosmoflow_batch(seed=BASE_SEED, n=4, width=128, cin=4, nout=4):
     x = slab("cosmo", seed, 1, (n, cin, width, width, width), 0, width)
     t = flat("uniform", seed, 2, (n, nout), -1.0, 1.0)
     return x, t
+
+
+UNET_WIDTHS = {"c1": (1, 32), "c2": (32, 64), "c3": (64, 64), "c4": (64, 128), "up": (128, 64), "c6": (128, 64)}
+
+
+def unet_level_inputs(seed=BASE_SEED, d_global=256, d=64, d_offset=64, hw=256):
+    """Inputs of one U-Net-shaped encoder/decoder level on a depth shard: the input slab with a
+    2-plane halo cut from the seeded volume, the six layers' parameters, the upstream gradient, and
+    the stand-in faces that a halo exchange with the two depth neighbours would deliver for the
+    tensors whose halo cannot be recomputed locally (None at a global boundary)."""
+    x = slab("normal", seed, 300, (1, 1, d_global, hw, hw), d_offset - 2, d_offset + d + 2)
+    params = {}
+    for i, (name, (ci, co)) in enumerate(UNET_WIDTHS.items()):
+        params[name] = conv_params(seed, 310 + 2 * i, ci, co, taps=8 if name == "up" else 27, transposed=(name == "up"))
+    dout = slab("normal", seed, 330, (1, 64, d_global, hw, hw), d_offset, d_offset + d)
+    has_lo, has_hi = d_offset > 0, d_offset + d < d_global
+    faces = {}
+    spec = {"p": (64, 2, 2, True), "cat": (128, 1, 1, True), "g6": (64, 1, 1, False), "g4": (128, 1, 2, False),
+            "g3": (64, 1, 2, False), "g2": (64, 1, 1, False), "g1": (32, 1, 1, False)}
+    for k, (name, (c, width, level, nonneg)) in enumerate(spec.items()):
+        s = hw // level
+        lo = flat("normal", seed, 340 + 2 * k, (1, c, width, s, s)) if has_lo else None
+        hi = flat("normal", seed, 341 + 2 * k, (1, c, width, s, s)) if has_hi else None
+        if nonneg:   # these stand in for post-ReLU activations
+            lo = None if lo is None else np.maximum(lo, 0.0)
+            hi = None if hi is None else np.maximum(hi, 0.0)
+        faces[name] = (lo, hi)
+    return x, params, dout, faces

@@ -49,3 +49,54 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         dconv[i] = orc.conv3d_bwd_filter(xin, dz, zs[i], act=orc.ACT_LEAKY, alpha=alpha)
         dp = qs(orc.conv3d_bwd_data(dz, zs[i], conv_params[i][0], act=orc.ACT_LEAKY, alpha=alpha))
     return {"z": zs, "p": ps, "y": ys, "loss": loss, "dfc": dfc, "dconv": dconv, "dz": dzs, "dx": dp}
+
+
+def unet_level_oracle(x, halo, d_offset, d_global, P, dout, faces, q=None):
+    """The U-Net-shaped level (same graph as paper_2007_12856_amd.nets.UNetLevel) with the oracle.
+    x: [1,1,d+2*halo,H,W] float64; P: name -> (w, b); faces: name -> (lo, hi) arrays or None."""
+    if q is None:
+        q = lambda a: a
+    R, NONE = orc.ACT_RELU, orc.ACT_NONE
+    qs = lambda s: orc.Slab(q(s.a), s.halo_lo, s.halo_hi, s.d_offset, s.d_global)
+
+    def with_halo(s, name, width):
+        """re-home the interior of `s` in a slab with `width` halo planes filled by the exchange"""
+        n, c, _, h, w = s.a.shape
+        t = orc.Slab(np.zeros((n, c, s.d + 2 * width, h, w)), width, width, s.d_offset, s.d_global)
+        t.interior[...] = s.interior
+        lo, hi = faces[name]
+        orc.halo_unpack(lo, t, orc.FACE_D_LO, width)
+        orc.halo_unpack(hi, t, orc.FACE_D_HI, width)
+        return t
+
+    xs = orc.Slab(x, halo, halo, d_offset, d_global)
+    T, G, dP = {}, {}, {}
+    T["a1"] = qs(orc.conv3d_fwd(xs, *P["c1"], cout_halo=(1, 1), act=R))
+    T["a2"] = qs(orc.conv3d_fwd(T["a1"], *P["c2"], act=R))
+    T["p"] = with_halo(qs(orc.pool3d_fwd(T["a2"], orc.POOL_MAX)), "p", 2)
+    T["b1"] = qs(orc.conv3d_fwd(T["p"], *P["c3"], cout_halo=(1, 1), act=R))
+    T["b2"] = qs(orc.conv3d_fwd(T["b1"], *P["c4"], act=R))
+    T["up"] = qs(orc.deconv2_fwd(T["b2"], *P["up"]))
+    T["cat"] = with_halo(orc.concat_c(T["a2"], T["up"]), "cat", 1)
+    T["out"] = qs(orc.conv3d_fwd(T["cat"], *P["c6"], act=R))
+    dsl = orc.Slab(dout, 0, 0, d_offset, d_global)
+    G["g6"] = with_halo(qs(orc.act_bwd(dsl, None, T["out"], R)), "g6", 1)
+    dP["c6"] = orc.conv3d_bwd_filter(T["cat"], G["g6"], None)
+    G["dcat"] = qs(orc.conv3d_bwd_data(G["g6"], None, P["c6"][0]))
+    G["d_skip"], G["d_up"] = orc.split_c(G["dcat"], 64)
+    dP["up"] = orc.deconv2_bwd_filter(T["b2"], G["d_up"])
+    G["d_b2"] = qs(orc.deconv2_bwd_data(G["d_up"], P["up"][0]))
+    G["g4"] = with_halo(qs(orc.act_bwd(G["d_b2"], None, T["b2"], R)), "g4", 1)
+    dP["c4"] = orc.conv3d_bwd_filter(T["b1"], G["g4"], None)
+    G["d_b1"] = qs(orc.conv3d_bwd_data(G["g4"], None, P["c4"][0]))
+    G["g3"] = with_halo(qs(orc.act_bwd(G["d_b1"], None, T["b1"], R)), "g3", 1)
+    dP["c3"] = orc.conv3d_bwd_filter(T["p"], G["g3"], None)
+    G["d_p"] = qs(orc.conv3d_bwd_data(G["g3"], None, P["c3"][0]))
+    G["d_a2"] = qs(orc.pool3d_bwd(G["d_p"], T["a2"], orc.POOL_MAX))
+    G["g2"] = with_halo(qs(orc.act_bwd(G["d_a2"], G["d_skip"], T["a2"], R)), "g2", 1)
+    dP["c2"] = orc.conv3d_bwd_filter(T["a1"], G["g2"], None)
+    G["d_a1"] = qs(orc.conv3d_bwd_data(G["g2"], None, P["c2"][0]))
+    G["g1"] = with_halo(qs(orc.act_bwd(G["d_a1"], None, T["a1"], R)), "g1", 1)
+    dP["c1"] = orc.conv3d_bwd_filter(xs, G["g1"], None)
+    G["dx"] = qs(orc.conv3d_bwd_data(G["g1"], None, P["c1"][0]))
+    return T, G, dP

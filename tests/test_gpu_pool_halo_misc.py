@@ -179,3 +179,20 @@ def test_dense_and_mse(m, n, k, act, dtype):
     h3d.mse_fwd_bwd(to_dev(yq, dtype), to_dev(t, "f32"), loss, dp)
     assert abs(loss.item() - Lo) <= 1e-5 * abs(Lo)
     assert rel_l2(from_dev(dp), go) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 7), (1, 8, 4, 6, 16)])
+def test_act_bwd(shape, dtype):
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = shape
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 20, (N, C, d + 2, H, W)), dtype, (1, 1), 4, 16)
+    d2o, d2g = slab_pair(synth.flat("normal", SEED, 21, (N, C, d, H, W)), dtype, (0, 0), 4, 16)
+    zo, zg = slab_pair(synth.flat("normal", SEED, 22, (N, C, d + 1, H, W)), dtype, (0, 1), 4, 16)
+    for act, two in [(orc.ACT_LEAKY, False), (orc.ACT_RELU, True), (orc.ACT_NONE, True)]:
+        go = orc.act_bwd(dzo, d2o if two else None, zo, act, 0.01, g_halo=(2, 0))
+        gg = dev_like(go, dtype)
+        h3d.act_bwd(dzg, d2g if two else None, zg, gg, act, 0.01)
+        got = from_dev(gg.t)
+        assert rel_l2(got[:, :, 2:], go.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+        assert np.all(got[:, :, :2] == quantize(12345.0, dtype))      # halo planes untouched

@@ -44,3 +44,34 @@ def test_cosmoflow_stack_miniature(dtype, tol):
         assert rel_l2(from_dev(net.dconv[i][0]), ref["dconv"][i][0]) <= 2 * tol, f"dw{i}"
         assert rel_l2(from_dev(net.dconv[i][1]), ref["dconv"][i][1]) <= 2 * tol, f"db{i}"
     assert rel_l2(from_dev(net.dx.t), ref["dx"].a) <= 2 * tol
+
+
+@pytest.mark.parametrize("dg,d,d_offset,hw", [(32, 8, 0, 32), (32, 8, 8, 32), (32, 8, 24, 32), (64, 16, 16, 64)])
+def test_unet_level_miniature(dg, d, d_offset, hw):
+    """The U-Net-shaped level on linearly reduced shards (8x32x32 of a 32^3 volume: first, interior and
+    last shard; 16x64x64 of a 64^3 volume = the 4x reduction of the real shard), 2-plane halo, full
+    oracle, forward and backward, bf16."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    from paper_2007_12856_amd.nets import UNetLevel
+    from oracle_nets import unet_level_oracle
+    dtype, tol = "bf16", 2e-2
+    x, P, dout, faces = recipes.unet_level_inputs(synth.BASE_SEED + 9, d_global=dg, d=d, d_offset=d_offset, hw=hw)
+    qz = lambda v: quantize(v, dtype)
+    xq, doutq = qz(x), qz(dout)
+    Pq = {k: (qz(w), synth.round_f32(b).astype(np.float64)) for k, (w, b) in P.items()}
+    fq = {k: tuple(None if f is None else qz(f) for f in pair) for k, pair in faces.items()}
+    Pd = {k: (to_dev(w, dtype), to_dev(b, "f32")) for k, (w, b) in Pq.items()}
+    fd = {k: tuple(None if f is None else to_dev(f, dtype) for f in pair) for k, pair in fq.items()}
+    net = UNetLevel(h3d.Slab(to_dev(xq, dtype), 2, 2, d_offset, dg), Pd, to_dev(doutq, dtype), fd)
+    net.step()
+    torch.cuda.synchronize()
+    T, G, dP = unet_level_oracle(xq, 2, d_offset, dg, Pq, doutq, fq, q=qz)
+    for k in ("a1", "a2", "p", "b1", "b2", "up", "cat", "out"):
+        assert rel_l2(from_dev(net.T[k].t), T[k].a) <= tol, k
+    assert np.array_equal(from_dev(net.T["cat"].t)[:, :, [0, -1]], T["cat"].a[:, :, [0, -1]])     # exchanged halo: bit-exact
+    for k in ("g6", "dcat", "d_b2", "g4", "d_b1", "g3", "d_p", "d_a2", "g2", "d_a1", "g1", "dx"):
+        assert rel_l2(from_dev(net.G[k].t), G[k].a) <= tol, k
+    for k in dP:
+        assert rel_l2(from_dev(net.dP[k][0]), dP[k][0]) <= tol, f"dw {k}"
+        assert rel_l2(from_dev(net.dP[k][1]), dP[k][1]) <= tol, f"db {k}"

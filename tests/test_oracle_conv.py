@@ -317,3 +317,18 @@ def test_table1_conv_ops_and_parameters():
         assert f"{3 * fwd / 1e9:.4g}" == f"{printed['total_gflop'][col]:.4g}"
     params = sum(27 * ci * co for ci, co, _ in conv) + sum(i * o + o for i, o in fc)
     assert f"{params / 1e6:.2f}" == f"{printed['params_1e6'][0]:.2f}"
+
+
+def test_act_bwd_equals_the_fused_mask():
+    """The separate activation-backward pass followed by an unmasked BD/BF equals the fused form."""
+    x, w, b = rand(1, 2, 4, 4, 5), rand(3, 2, 3, 3, 3), rand(3)
+    dz, dz2 = rand(1, 3, 4, 4, 5), rand(1, 3, 4, 4, 5)
+    z = orc.conv3d_fwd(Slab(x), w, b, act=orc.ACT_LEAKY, alpha=0.2)
+    g = orc.act_bwd(Slab(dz), None, z, orc.ACT_LEAKY, 0.2)
+    assert np.array_equal(orc.conv3d_bwd_data(g, None, w).a, orc.conv3d_bwd_data(Slab(dz), z, w, act=orc.ACT_LEAKY, alpha=0.2).a)
+    dw_a, db_a = orc.conv3d_bwd_filter(Slab(x), g, None)
+    dw_b, db_b = orc.conv3d_bwd_filter(Slab(x), Slab(dz), z, act=orc.ACT_LEAKY, alpha=0.2)
+    assert np.array_equal(dw_a, dw_b) and np.array_equal(db_a, db_b)
+    g2 = orc.act_bwd(Slab(dz), Slab(dz2), z, orc.ACT_RELU)
+    assert np.array_equal(g2.a, (dz + dz2) * (z.a > 0))
+    assert np.array_equal(orc.act_bwd(Slab(dz), None, z, orc.ACT_NONE).a, dz)
