@@ -59,6 +59,10 @@ def main():
     ap.add_argument("--width", type=int, default=128)
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default=None, help="after warm-up, time only this call of the step (name as in per_call); "
+                    "used to profile one kernel under rocprofv3")
+    ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
+                    "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,6 +79,23 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     h3d.lib()   # fail loudly if the HIP library is not built
+    if args.copy_ref:
+        t = h3d.Slab(torch.randn((1, 16, 64, 512, 512), device="cuda").to(torch.bfloat16))
+        buf = torch.empty_like(t.t)
+        for _ in range(args.warmup):
+            h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        nbytes = 2 * t.t.numel() * 2
+        print(json.dumps({"metric": "copy GB/s", "value": nbytes / ms / 1e6, "unit": "GB/s", "ms": ms, "bytes": nbytes,
+                          "kernel": "copy_runs_kernel (halo_pack of a whole interior)"}))
+        return
     seed = synth.BASE_SEED if args.seed is None else args.seed
     td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
 
@@ -105,6 +126,24 @@ def main():
                          "tflops": round(op["flops"] / ms / 1e9, 2) if op["flops"] and op["name"].startswith("conv") else None,
                          "gbs": round(op["bytes"] / ms / 1e6, 1) if op["bytes"] else None})
     dom = max(range(len(net.ops)), key=lambda i: per_call[i]["ms"])
+    if args.only:
+        names = [o["name"] for o in net.ops]
+        if args.only not in names:
+            sys.exit(f"bench.py: --only must be one of {names}")
+        dom = names.index(args.only)
+        op = net.ops[dom]
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            op["fn"]()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"metric": "single call", "kernel": op["name"], "ms": ms, "steps": args.steps,
+                          "tflops": op["flops"] / ms / 1e9, "gbs": op["bytes"] / ms / 1e6,
+                          "algorithmic_bytes": op["bytes"], "algorithmic_flops": op["flops"]}))
+        return
 
     # timed region: exactly K steps; one HIP-event pair per step around the dominant call
     # (events are recorded on the stream the kernels are launched on)

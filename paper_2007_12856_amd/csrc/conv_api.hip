@@ -15,6 +15,11 @@ h3d_status conv3d_direct(void* handle, const h3d_tensor* in, const h3d_tensor* m
 template <typename T>
 h3d_status bwd_filter_direct(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw,
                              float* db, float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream);
+// conv_small_cin.hip
+bool c4_fwd_supported(const h3d_tensor* in, const h3d_tensor* out);
+size_t c4_fwd_ws_bytes(const h3d_tensor* out);
+h3d_status conv3d_fwd_c4(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, float out_slope,
+                         void* ws, size_t ws_bytes, hipStream_t stream);
 // conv_mfma.hip
 bool mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out);
 size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out);
@@ -49,8 +54,10 @@ extern "C" size_t h3d_conv3d_workspace_bytes(void* handle, int op, const h3d_ten
   size_t b = 0;
   switch (op) {
     case H3D_OP_FWD:       // x: input, z: output
+      if (c4_fwd_supported(x, z)) b = c4_fwd_ws_bytes(z);
+      [[fallthrough]];
     case H3D_OP_BWD_DATA:  // x: dz (input of the correlation), z: dx
-      b = direct_fwd_ws_bytes(x->c, z->c);
+      b = std::max(b, direct_fwd_ws_bytes(x->c, z->c));
       if (mfma_fwd_supported(x, z)) b = std::max(b, mfma_fwd_ws_bytes(x, z));
       break;
     case H3D_OP_BWD_FILTER:  // x: activations, z: dz
@@ -73,6 +80,7 @@ extern "C" h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const vo
   H3D_TRY(check_pair(handle, x, z, "conv3d_fwd"));
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
+  if (c4_fwd_supported(x, z)) return conv3d_fwd_c4(handle, x, w, bias, z, slope, ws, ws_bytes, s);
   if (mfma_fwd_supported(x, z)) return conv3d_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return conv3d_direct<float>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   return conv3d_direct<bf16_t>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);

@@ -1,0 +1,232 @@
+// Forward 3x3x3 convolution for the FIRST layer of both networks: Cin <= 4 input channels
+// (4 redshift channels of the CosmoFlow cubes, 1 CT channel of the U-Net), Cout <= 32, bf16.
+//
+// With so few input channels the layer is bound by HBM (40 bytes per output voxel against 3456
+// flops for 4 -> 16), so the kernel is built around the data path, not the matrix cores:
+//   * the haloed input tile is staged in LDS channel-interleaved, 8 bytes per voxel (4 bf16
+//     channels), from 16-byte loads along W;
+//   * the contraction index is (tap, ci): K = 27*4 = 108, padded to 128 = four
+//     v_mfma_f32_16x16x32_bf16 steps.  A lane's 16-byte B operand is TWO taps of one voxel, fetched
+//     with two 8-byte LDS reads at per-lane tap offsets; the four lane groups of a wavefront cover
+//     8 taps per step.  Output channels are the MFMA rows; the packed weights (16 x 128 per row
+//     block) stay in registers for the whole kernel;
+//   * the accumulators (one output row of 64 voxels x Cout at a time) are transposed through LDS so
+//     that every lane stores 16 contiguous bytes along W: whole 128-byte lines per channel row.
+// Bias, (leaky-)ReLU and the zeroing of output planes beyond the global volume are fused.
+#include <algorithm>
+
+#include "common.h"
+
+namespace h3d {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace c4 {
+constexpr int TD = 4, TH = 4, TW = 64;
+constexpr int XW = TW + 16;                 // staged row: w in [w0-8, w0+TW+8)
+constexpr int PRV = XW + 2;                 // row pitch in voxels (8 bytes each)
+constexpr int PDV = (TH + 2) * PRV + 6;     // plane pitch in voxels
+constexpr int XS_VOX = (TD + 2) * PDV;
+constexpr int OTP = TW + 8;                 // epilogue transpose pitch (bf16 elements)
+}  // namespace c4
+
+// wA: [rb][m][lane][8] bf16: row co = 16*rb + lane%16; element e of lane group g = lane/16 in step m is
+// tap slot s = 2*(4m+g) + e/4, channel e%4 (zero for s >= 27, ci >= cin, co >= cout)
+__global__ void pack_w_c4_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wA, int cin, int cout, int nrb) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= nrb * 4 * 512) return;
+  int e = i & 7, lane = (i >> 3) & 63, m = (i >> 9) & 3, rb = i >> 11;
+  int co = rb * 16 + (lane & 15), s = 2 * (4 * m + (lane >> 4)) + (e >> 2), ci = e & 3;
+  bf16_t v = 0;
+  if (co < cout && s < 27 && ci < cin) v = w[((int64_t)co * cin + ci) * 27 + s];
+  wA[i] = v;
+}
+
+struct C4Args {
+  Geo in, out;
+  int cin, cout;
+  int tiles_w, tiles_h, tiles_d;
+  float out_slope;
+  int vec_ok;
+};
+
+template <int RB>
+__global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wA,
+                                                            const float* __restrict__ bias, bf16_t* __restrict__ out, C4Args a) {
+  using namespace c4;
+  __shared__ uint2 xs[XS_VOX];
+  __shared__ __attribute__((aligned(16))) bf16_t ot[4][16 * RB][OTP];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lg = lane >> 4, lj = lane & 15;
+  int t = blockIdx.x;
+  const int tw = t % a.tiles_w; t /= a.tiles_w;
+  const int th = t % a.tiles_h; t /= a.tiles_h;
+  const int td = t % a.tiles_d;
+  const int n = t / a.tiles_d;
+  const int w0 = tw * TW, h0 = th * TH, ps0 = td * TD;
+  const int W = a.in.w, H = a.in.h;
+
+  // ---- weights: registers for the whole kernel
+  bf16x8 A[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int m = 0; m < 4; ++m) A[rb][m] = __builtin_bit_cast(bf16x8, wA[(rb * 4 + m) * 64 + lane]);
+
+  // ---- per-lane tap offsets (in voxels) of the two taps this lane group feeds in each step
+  int offA[4], offB[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    int s0 = 2 * (4 * m + lg), s1 = s0 + 1;
+    offA[m] = s0 < 27 ? (s0 / 9) * PDV + ((s0 % 9) / 3) * PRV + s0 % 3 : 0;
+    offB[m] = s1 < 27 ? (s1 / 9) * PDV + ((s1 % 9) / 3) * PRV + s1 % 3 : 0;
+  }
+
+  // ---- stage the input tile: items = (plane, row, group of 8 w), 4 channels each
+  const bf16_t* in_n = in + n * a.in.nstride;
+  constexpr int NGRP = XW / 8;
+  constexpr int NITEMS = (TD + 2) * (TH + 2) * NGRP;
+  for (int item = tid; item < NITEMS; item += 256) {
+    const int grp = item % NGRP;
+    int q = item / NGRP;
+    const int hy = q % (TH + 2), dz = q / (TH + 2);
+    const int p_in = ps0 - a.out.hlo + dz - 1;
+    const int64_t gq = a.in.doff + p_in;
+    const int sp = p_in + a.in.hlo;
+    const int h = h0 + hy - 1, w = w0 - 8 + 8 * grp;
+    const bool row_ok = gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H;
+    uint4 c[4];
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) {
+      c[ci] = uint4{0, 0, 0, 0};
+      if (row_ok && ci < a.cin) {
+        const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + (int64_t)sp * a.in.plane + (int64_t)h * W + w;
+        if (a.vec_ok) {
+          if (w >= 0 && w + 8 <= W) c[ci] = *reinterpret_cast<const uint4*>(p);
+        } else {
+          uint32_t e[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? p[i] : 0;
+          c[ci] = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+        }
+      }
+    }
+    uint4* dst = reinterpret_cast<uint4*>(&xs[dz * PDV + hy * PRV + 8 * grp]);
+    const uint32_t c0[4] = {c[0].x, c[0].y, c[0].z, c[0].w}, c1[4] = {c[1].x, c[1].y, c[1].z, c[1].w};
+    const uint32_t c2[4] = {c[2].x, c[2].y, c[2].z, c[2].w}, c3[4] = {c[3].x, c[3].y, c[3].z, c[3].w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {   // voxels 2k and 2k+1 of the group
+      uint4 u;
+      u.x = __builtin_amdgcn_perm(c1[k], c0[k], 0x05040100);
+      u.y = __builtin_amdgcn_perm(c3[k], c2[k], 0x05040100);
+      u.z = __builtin_amdgcn_perm(c1[k], c0[k], 0x07060302);
+      u.w = __builtin_amdgcn_perm(c3[k], c2[k], 0x07060302);
+      dst[k] = u;
+    }
+  }
+  __syncthreads();
+
+  // ---- this wavefront's depth plane, one output row (64 voxels) at a time
+  const int ps = ps0 + wave;
+  const int64_t gp = a.out.doff + ps - a.out.hlo;
+  const bool inside = gp >= 0 && gp < a.out.dglob;
+  const bool plane_ok = ps < a.out.ds;
+  float bv[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int co = rb * 16 + 4 * lg + r;
+      bv[rb][r] = (bias && co < a.cout) ? bias[co] : 0.f;
+    }
+  bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
+  for (int hl = 0; hl < TH; ++hl) {
+    f32x4 acc[4][RB];
+#pragma unroll
+    for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int vrow = wave * PDV + hl * PRV + 7 + lj;   // tap (0,0,0) of this lane's voxel in block 0
+#pragma unroll
+    for (int vb = 0; vb < 4; ++vb) {
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const uint2 lo = xs[vrow + vb * 16 + offA[m]], hi = xs[vrow + vb * 16 + offB[m]];
+        const uint4 b = {lo.x, lo.y, hi.x, hi.y};
+        const bf16x8 B = __builtin_bit_cast(bf16x8, b);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb][m], B, acc[vb][rb], 0, 0, 0);
+      }
+    }
+    // bias + activation, transpose through LDS: ot[wave][co][w]
+    __syncthreads();   // previous row's readers are done
+#pragma unroll
+    for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = acc[vb][rb][r] + bv[rb][r];
+          if (!(v > 0.f)) v *= a.out_slope;
+          ot[wave][rb * 16 + 4 * lg + r][vb * 16 + lj] = f32_to_bf16(inside ? v : 0.f);
+        }
+    __syncthreads();
+    const int h = h0 + hl;
+    if (plane_ok && h < H) {
+#pragma unroll
+      for (int i = 0; i < 2 * RB; ++i) {
+        const int u = lane + 64 * i;
+        const int co = u >> 3, wu = u & 7;
+        const int w = w0 + 8 * wu;
+        if (co < a.cout && w < W) {
+          const uint4 v = *reinterpret_cast<const uint4*>(&ot[wave][co][8 * wu]);
+          bf16_t* o = out_n + (int64_t)co * a.out.cstride + (int64_t)h * W + w;
+          if (a.vec_ok && w + 8 <= W) {
+            *reinterpret_cast<uint4*>(o) = v;
+          } else {
+            const uint32_t e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+              if (w + k < W) o[k] = (bf16_t)(e[k >> 1] >> (16 * (k & 1)));
+          }
+        }
+      }
+    }
+  }
+}
+
+bool c4_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
+  if (in->dtype != H3D_BF16 || in->c < 1 || in->c > 4 || out->c < 1 || out->c > 32) return false;
+  int64_t in_sample = (int64_t)(in->halo_lo + in->d + in->halo_hi) * in->h * in->w;
+  return in_sample < ((int64_t)1 << 30);
+}
+
+size_t c4_fwd_ws_bytes(const h3d_tensor* out) { return (size_t)cdiv(out->c, 16) * 4 * 512 * sizeof(bf16_t); }
+
+h3d_status conv3d_fwd_c4(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, float out_slope,
+                         void* ws, size_t ws_bytes, hipStream_t stream) {
+  using namespace c4;
+  C4Args a;
+  a.in = make_geo(in); a.out = make_geo(out);
+  a.cin = in->c; a.cout = out->c; a.out_slope = out_slope;
+  if ((int64_t)out->n * a.out.ds * out->h * out->w == 0) return H3D_OK;
+  const int nrb = (int)cdiv(out->c, 16);
+  if (!ws || ws_bytes < c4_fwd_ws_bytes(out)) return fail(handle, H3D_EWORKSPACE, "conv3d_fwd: workspace too small");
+  if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d_fwd: workspace must be 16-byte aligned");
+  a.vec_ok = (in->w % 8 == 0) && ((uintptr_t)in->data % 16 == 0) && ((uintptr_t)out->data % 16 == 0);
+  a.tiles_w = (int)cdiv(out->w, TW); a.tiles_h = (int)cdiv(out->h, TH); a.tiles_d = (int)cdiv(a.out.ds, TD);
+  int64_t grid = (int64_t)out->n * a.tiles_d * a.tiles_h * a.tiles_w;
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_fwd: too many workgroups");
+  hipLaunchKernelGGL(pack_w_c4_kernel, dim3((unsigned)cdiv(nrb * 4 * 512, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws,
+                     a.cin, a.cout, nrb);
+  if (nrb == 1)
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<1>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+                       (const uint4*)ws, bias, (bf16_t*)out->data, a);
+  else
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<2>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+                       (const uint4*)ws, bias, (bf16_t*)out->data, a);
+  return launch_status(handle, "conv3d_fwd_c4");
+}
+
+}  // namespace h3d

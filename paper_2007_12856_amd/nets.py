@@ -105,6 +105,11 @@ class CosmoFlowStack:
         for op in self.ops[self.n_fwd_ops:]:
             op["fn"]()
 
+    def backward_after_loss(self):
+        """Backward from a loss gradient already present in self.dy[-1] (skips the MSE call)."""
+        for op in self.ops[self.n_fwd_ops + 1:]:
+            op["fn"]()
+
     def step(self):
         for op in self.ops:
             op["fn"]()

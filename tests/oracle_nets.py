@@ -34,6 +34,7 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
     if count is not None:
         loss, g = loss * target.size / count, g * target.size / count
     g = q(g)
+    dpred = g
     dfc = [None] * len(fc_params)
     for i in range(last, -1, -1):
         g, dw, db = orc.dense_bwd(hs[i], fc_params[i][0], ys[i], g, orc.ACT_NONE if i == last else orc.ACT_LEAKY, alpha)
@@ -48,7 +49,7 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         xin = xs if i == 0 else ps[i - 1]
         dconv[i] = orc.conv3d_bwd_filter(xin, dz, zs[i], act=orc.ACT_LEAKY, alpha=alpha)
         dp = qs(orc.conv3d_bwd_data(dz, zs[i], conv_params[i][0], act=orc.ACT_LEAKY, alpha=alpha))
-    return {"z": zs, "p": ps, "y": ys, "loss": loss, "dfc": dfc, "dconv": dconv, "dz": dzs, "dx": dp}
+    return {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "dfc": dfc, "dconv": dconv, "dz": dzs, "dx": dp}
 
 
 def unet_level_oracle(x, halo, d_offset, d_global, P, dout, faces, q=None):

@@ -35,8 +35,15 @@ def test_cosmoflow_stack_miniature(dtype, tol):
     for i in range(len(convq)):
         assert rel_l2(from_dev(net.z[i].t), ref["z"][i].a) <= tol, f"z{i}"
     assert rel_l2(from_dev(net.y[-1]), ref["y"][-1]) <= tol
-    assert abs(net.loss.item() - ref["loss"]) <= tol * abs(ref["loss"]) * 4
-    # gradients: the masks are taken from each side's own z, so a few voxels near zero flip sign;
+    assert abs(net.loss.item() - ref["loss"]) <= 4 * tol * abs(ref["loss"])
+    # The loss gradient 2(pred - target)/count amplifies a one-ulp difference in pred by
+    # |pred| / |pred - target|, and every gradient below is linear in it: the backward chain is
+    # therefore started from the oracle's loss gradient on both sides (the MSE call itself is
+    # compared on identical inputs in test_dense_and_mse).
+    net.dy[-1].copy_(to_dev(ref["dpred"], dtype))
+    net.backward_after_loss()
+    torch.cuda.synchronize()
+    # the masks are taken from each side's own z, so a few voxels near zero flip sign;
     # with slope 0.01 that perturbs the gradient norm far below the bar
     for i in range(len(fcq)):
         assert rel_l2(from_dev(net.dfc[i][0]), ref["dfc"][i][0]) <= 2 * tol, f"dfc{i}"
