@@ -124,6 +124,14 @@ h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tensor* y, int 
 h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, h3d_tensor* dx, int mode,
                           void* stream);
 
+/* Pooling backward fused with the activation backward of the layer below it:
+ * g = pool3d_bwd(dy) * (z > 0 ? 1 : slope), z the saved output of the conv+activation that fed the
+ * pooling (same shape as g; its halos may differ).  One streaming pass; the backward convolutions are
+ * then called on g with act NONE.  With bf16 storage g is rounded once (the unfused sequence rounds
+ * the pooled gradient first). */
+h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z,
+                              h3d_tensor* g, int mode, int act, float alpha, void* stream);
+
 /* ---- halo pack / unpack of the depth faces (Sec. III-A: packing/unpacking kernels for the
  *      neighbour communication of boundary regions) ---- bit-exact copies.
  * Face buffer layout: [n][c][width][h][w] packed, same dtype as t. */

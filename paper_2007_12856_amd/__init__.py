@@ -49,6 +49,7 @@ _SIGNATURES = {
     "h3d_act_bwd": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
+    "h3d_pool3d_bwd_act": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_halo_bytes": (ctypes.c_size_t, [_T, ctypes.c_int]),
     "h3d_halo_pack": (ctypes.c_int, [_P, _T, ctypes.c_int, ctypes.c_int, _P, _P]),
     "h3d_halo_unpack": (ctypes.c_int, [_P, _P, _T, ctypes.c_int, ctypes.c_int, _P]),
@@ -236,6 +237,12 @@ def h3d_pool3d_bwd(dy: Slab, x: Slab | None, dx: Slab, mode: int):
     return dx
 
 
+def h3d_pool3d_bwd_act(dy: Slab, x: Slab | None, z: Slab, g: Slab, mode: int, act: int, alpha: float = 0.0):
+    _check(lib().h3d_pool3d_bwd_act(handle(), ctypes.byref(dy.desc()), ctypes.byref(x.desc()) if x is not None else None,
+                                    ctypes.byref(z.desc()), ctypes.byref(g.desc()), mode, act, alpha, _stream()))
+    return g
+
+
 def h3d_halo_bytes(t: Slab, width: int) -> int:
     return int(lib().h3d_halo_bytes(ctypes.byref(t.desc()), width))
 
@@ -306,7 +313,7 @@ def h3d_mse_fwd_bwd(pred, target, loss, dpred):
 
 # short aliases
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
-pool3d_fwd, pool3d_bwd, act_bwd = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd
+pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c

@@ -63,9 +63,13 @@ __global__ void __launch_bounds__(256) pool_fwd_kernel(const T* __restrict__ x, 
   *reinterpret_cast<Vec<T, VEC>*>(y + yoff) = o;
 }
 
-template <typename T, int VEC, int MODE>
+// ACT: also multiply by the activation derivative taken from the saved output z of the layer that
+// produced the pooled tensor (g = pool_bwd(dy) * (z > 0 ? 1 : slope)): one pass instead of a pooling
+// backward followed by an activation backward.
+template <typename T, int VEC, int MODE, bool ACT>
 __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                       T* __restrict__ dx, PoolArgs a, Geo xin) {
+                                                       T* __restrict__ dx, PoolArgs a, Geo xin, const T* __restrict__ z,
+                                                       Geo zg, float slope) {
   int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= a.total) return;
   int64_t dxoff, yoff;
@@ -109,6 +113,19 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy,
         for (int j = 0; j < 2; ++j) o[k].v[2 * i + j] = (best == k * 2 + j) ? g.v[i] : zero;
     }
   }
+  if (ACT) {
+    PoolArgs b = a;
+    b.x = zg;
+    int64_t zoff, dummy;
+    decode<T, VEC>(b, t, zoff, dummy);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      Vec<T, 2 * VEC> m = *reinterpret_cast<const Vec<T, 2 * VEC>*>(z + zoff + (k >> 1) * zg.plane + (k & 1) * zg.w);
+#pragma unroll
+      for (int i = 0; i < 2 * VEC; ++i)
+        if (!(ld(&m.v[i]) > 0.f)) st(&o[k].v[i], ld(&o[k].v[i]) * slope);
+    }
+  }
 #pragma unroll
   for (int k = 0; k < 4; ++k)
     *reinterpret_cast<Vec<T, 2 * VEC>*>(dx + dxoff + (k >> 1) * a.x.plane + (k & 1) * a.x.w) = o[k];
@@ -126,13 +143,14 @@ static h3d_status pool_check(void* handle, const h3d_tensor* big, const h3d_tens
 }
 
 template <typename T>
-static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_tensor* extra) {
+static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_tensor* extra, const h3d_tensor* extra2 = nullptr) {
   // widest VEC (outputs per thread) such that every row start is aligned for the vector accesses
   const int cand = 16 / (2 * (int)sizeof(T)) * 2;  // bf16: 8, fp32: 4  (two 16-byte loads per input row)
   for (int v = cand; v > 1; v >>= 1) {
     bool ok = small->w % v == 0 && ((uintptr_t)small->data % (v * sizeof(T))) == 0 &&
               ((uintptr_t)big->data % (2 * v * sizeof(T))) == 0 &&
-              (!extra || ((uintptr_t)extra->data % (2 * v * sizeof(T))) == 0);
+              (!extra || ((uintptr_t)extra->data % (2 * v * sizeof(T))) == 0) &&
+              (!extra2 || ((uintptr_t)extra2->data % (2 * v * sizeof(T))) == 0);
     if (ok) return v;
   }
   return 0;  // scalar: VEC = 1 needs pairs aligned to 2 elements
@@ -140,13 +158,14 @@ static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_te
 
 template <typename T, int MODE>
 static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, const h3d_tensor* small,
-                              const h3d_tensor* xin, hipStream_t stream) {
+                              const h3d_tensor* xin, hipStream_t stream, const h3d_tensor* zt = nullptr, float slope = 1.f) {
   PoolArgs a;
   a.x = make_geo(big);
   a.y = make_geo(small);
-  int vec = pick_vec<T>(big, small, xin);
+  int vec = pick_vec<T>(big, small, xin, zt);
   if (vec == 0) {
-    bool ok = ((uintptr_t)big->data % (2 * sizeof(T))) == 0 && (!xin || ((uintptr_t)xin->data % (2 * sizeof(T))) == 0);
+    bool ok = ((uintptr_t)big->data % (2 * sizeof(T))) == 0 && (!xin || ((uintptr_t)xin->data % (2 * sizeof(T))) == 0) &&
+              (!zt || ((uintptr_t)zt->data % (2 * sizeof(T))) == 0);
     if (!ok) return fail(handle, H3D_EUNSUPPORTED, "pool3d: data pointers must be aligned to two elements");
     vec = 1;
   }
@@ -156,6 +175,8 @@ static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, con
   int64_t grid = cdiv(a.total, 256);
   if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "pool3d: too many blocks");
   Geo gx = xin ? make_geo(xin) : a.x;
+  Geo gz = zt ? make_geo(zt) : a.x;
+  const T* zp = zt ? (const T*)zt->data : nullptr;
   const T* bigp = (const T*)big->data;
   const T* smallp = (const T*)small->data;
 #define H3D_POOL_CASE(V)                                                                                           \
@@ -163,9 +184,12 @@ static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, con
     if (fwd)                                                                                                       \
       hipLaunchKernelGGL((pool_fwd_kernel<T, V, MODE>), dim3((unsigned)grid), dim3(256), 0, stream, bigp,          \
                          (T*)small->data, a);                                                                      \
+    else if (zt)                                                                                                   \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, true>), dim3((unsigned)grid), dim3(256), 0, stream, smallp,  \
+                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope);                \
     else                                                                                                           \
-      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE>), dim3((unsigned)grid), dim3(256), 0, stream, smallp,        \
-                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx);                               \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, false>), dim3((unsigned)grid), dim3(256), 0, stream, smallp, \
+                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope);                \
     break;
   switch (vec) {
     H3D_POOL_CASE(8)
@@ -195,9 +219,30 @@ extern "C" h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tens
                               : pool_launch<bf16_t, H3D_POOL_MAX>(handle, true, x, y, nullptr, s);
 }
 
+static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, h3d_tensor* dx,
+                                int mode, float slope, void* stream);
+
 extern "C" h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, h3d_tensor* dx, int mode,
                                      void* stream) {
+  return pool_bwd_impl(handle, dy, x, nullptr, dx, mode, 1.f, stream);
+}
+
+extern "C" h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z,
+                                         h3d_tensor* g, int mode, int act, float alpha, void* stream) {
   if (!handle) return H3D_EINVAL;
+  if (act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: bad activation");
+  if (act == H3D_ACT_NONE) z = nullptr;
+  else if (!z) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: the saved output z is required");
+  return pool_bwd_impl(handle, dy, x, z, g, mode, act_slope(act, alpha), stream);
+}
+
+static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, h3d_tensor* dx,
+                                int mode, float slope, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (z) {
+    H3D_TRY(check_tensor(handle, z, "z"));
+    if (!dx || !same_shard(z, dx) || z->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: z and g shapes differ");
+  }
   H3D_TRY(check_tensor(handle, dy, "dy"));
   H3D_TRY(check_tensor(handle, dx, "dx"));
   if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_bwd: bad mode %d", mode);
@@ -211,8 +256,8 @@ extern "C" h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h
   }
   hipStream_t s = (hipStream_t)stream;
   if (dx->dtype == H3D_F32)
-    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, false, dx, dy, x, s)
-                                : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s);
-  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s)
-                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s);
+    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope)
+                                : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
+  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope)
+                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
 }

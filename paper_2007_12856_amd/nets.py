@@ -10,7 +10,7 @@ from __future__ import annotations
 import torch
 
 from . import (ACT_LEAKY, ACT_NONE, POOL_AVG, Slab, Workspace, conv3d_bwd_data, conv3d_bwd_filter, conv3d_fwd,
-               dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_fwd)
+               dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_fwd)
 
 
 class CosmoFlowStack:
@@ -40,7 +40,7 @@ class CosmoFlowStack:
         self.dfc = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
                     for w, b in fc_params]
         self.dp = [Slab(torch.empty_like(p.t)) for p in self.p]
-        self.dz = [Slab(torch.empty_like(z.t)) for z in self.z]
+        self.g = [Slab(torch.empty_like(z.t)) for z in self.z]     # g = dz * act'(z), pre-activation gradient
         self.dx = Slab(torch.empty_like(x))
         self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
                       for w, b in conv_params]
@@ -85,16 +85,18 @@ class CosmoFlowStack:
                 4 * xin.shape[0] * w.numel(), w.numel() * es + w.numel() * 4)
         for i in range(nconv - 1, -1, -1):
             w = self.conv[i][0]
-            z, dz, dp = self.z[i], self.dz[i], self.dp[i]
+            z, g, dp = self.z[i], self.g[i], self.dp[i]
             xin = self.x if i == 0 else self.p[i - 1]
             dxin = self.dx if i == 0 else self.dp[i - 1]
             fl = 2 * 27 * w.shape[1] * w.shape[0] * z.t.numel() // w.shape[0]
-            self._op(f"pool{i + 1}_bwd", lambda dp=dp, dz=dz: pool3d_bwd(dp, None, dz, POOL_AVG), 0, (dp.t.numel() + dz.t.numel()) * es)
-            self._op(f"conv{i + 1}_bwd_filter", lambda xin=xin, dz=dz, z=z, i=i: conv3d_bwd_filter(
-                xin, dz, z, self.dconv[i][0], self.dconv[i][1], ACT_LEAKY, al, ws), fl,
-                (xin.t.numel() + dz.t.numel() + z.t.numel()) * es + w.numel() * 4)
-            self._op(f"conv{i + 1}_bwd_data", lambda dz=dz, z=z, w=w, dxin=dxin: conv3d_bwd_data(dz, z, w, dxin, ACT_LEAKY, al, ws),
-                     fl, (dz.t.numel() + z.t.numel() + dxin.t.numel() + w.numel()) * es)
+            # pooling backward and activation backward in one pass; BF and BD then run unmasked on g
+            self._op(f"pool{i + 1}_bwd_act", lambda dp=dp, z=z, g=g: pool3d_bwd_act(dp, None, z, g, POOL_AVG, ACT_LEAKY, al), 0,
+                     (dp.t.numel() + z.t.numel() + g.t.numel()) * es)
+            self._op(f"conv{i + 1}_bwd_filter", lambda xin=xin, g=g, i=i: conv3d_bwd_filter(
+                xin, g, None, self.dconv[i][0], self.dconv[i][1], ACT_NONE, 0.0, ws), fl,
+                (xin.t.numel() + g.t.numel()) * es + w.numel() * 4)
+            self._op(f"conv{i + 1}_bwd_data", lambda g=g, w=w, dxin=dxin: conv3d_bwd_data(g, None, w, dxin, ACT_NONE, 0.0, ws),
+                     fl, (g.t.numel() + dxin.t.numel() + w.numel()) * es)
 
     def forward(self):
         for op in self.ops[:self.n_fwd_ops]:

@@ -42,14 +42,15 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         g = q(g)
     dp = orc.Slab(g.reshape(ps[-1].a.shape))
     dconv = [None] * len(conv_params)
-    dzs = [None] * len(conv_params)
+    gs = [None] * len(conv_params)
     for i in range(len(conv_params) - 1, -1, -1):
-        dz = qs(orc.pool3d_bwd(dp, None, orc.POOL_AVG))
-        dzs[i] = dz
+        # pooling backward and activation backward form one stored tensor g (rounded once)
+        g = qs(orc.act_bwd(orc.pool3d_bwd(dp, None, orc.POOL_AVG), None, zs[i], orc.ACT_LEAKY, alpha))
+        gs[i] = g
         xin = xs if i == 0 else ps[i - 1]
-        dconv[i] = orc.conv3d_bwd_filter(xin, dz, zs[i], act=orc.ACT_LEAKY, alpha=alpha)
-        dp = qs(orc.conv3d_bwd_data(dz, zs[i], conv_params[i][0], act=orc.ACT_LEAKY, alpha=alpha))
-    return {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "dfc": dfc, "dconv": dconv, "dz": dzs, "dx": dp}
+        dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
+        dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
+    return {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "dfc": dfc, "dconv": dconv, "g": gs, "dx": dp}
 
 
 def unet_level_oracle(x, halo, d_offset, d_global, P, dout, faces, q=None):

@@ -156,7 +156,7 @@ def test_cfg2_cosmoflow_stack_full_size():
     net.backward_after_loss()
     torch.cuda.synchronize()
     for i in range(5):
-        assert rel_l2(from_dev(net.dz[i].t[:1]), ref["dz"][i].a) <= TOL[BF], f"dz{i}"
+        assert rel_l2(from_dev(net.g[i].t[:1]), ref["g"][i].a) <= TOL[BF], f"g{i}"
     assert rel_l2(from_dev(net.dx.t[:1]), ref["dx"].a) <= TOL[BF]
     # weight gradients: per-sample runs
     from paper_2007_12856_amd.nets import CosmoFlowStack

@@ -196,3 +196,19 @@ def test_act_bwd(shape, dtype):
         got = from_dev(gg.t)
         assert rel_l2(got[:, :, 2:], go.interior) <= (1e-6 if dtype == "f32" else 4e-3)
         assert np.all(got[:, :, :2] == quantize(12345.0, dtype))      # halo planes untouched
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [orc.POOL_AVG, orc.POOL_MAX])
+def test_pool_bwd_fused_with_activation_backward(mode, dtype):
+    """g = pool_bwd(dy) * act'(z) in one pass equals the two oracle steps (one rounding of g)."""
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = 2, 3, 4, 6, 16
+    xo, xg = slab_pair(np.maximum(synth.flat("normal", SEED, 30, (N, C, d, H, W)), 0), dtype, (0, 0), 8, 32)
+    zo, zg = slab_pair(synth.flat("normal", SEED, 31, (N, C, d + 2, H, W)), dtype, (1, 1), 8, 32)
+    dyo, dyg = slab_pair(synth.flat("normal", SEED, 32, (N, C, d // 2, H // 2, W // 2)), dtype, (0, 0), 4, 16)
+    for act in (orc.ACT_LEAKY, orc.ACT_RELU):
+        ref = orc.act_bwd(orc.pool3d_bwd(dyo, xo, mode), None, zo, act, 0.01)
+        gg = dev_like(ref, dtype)
+        h3d.pool3d_bwd_act(dyg, xg if mode == orc.POOL_MAX else None, zg, gg, mode, act, 0.01)
+        assert rel_l2(from_dev(gg.t), ref.a) <= (1e-6 if dtype == "f32" else 4e-3)
