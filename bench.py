@@ -50,6 +50,70 @@ def cpu_baseline(seed):
             "seconds": round(dt, 2), "voxels_per_s": 64 ** 3 / dt}
 
 
+def side_workload(args, seed):
+    """Per-call tables for the other configurations (not the headline line)."""
+    import numpy as np
+    import torch
+    import synth
+    from synth import recipes
+    import paper_2007_12856_amd as h3d
+    from paper_2007_12856_amd.nets import SingleLayer, UNetLevel
+    bf = torch.bfloat16
+    if args.workload == "shard512":
+        net = SingleLayer(1, 4, 16, 64, 512, 64, 512, seed=seed)
+        name = "one 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky + avg-pool, halo faces"
+    elif args.workload == "late256":
+        net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
+        name = "late layer N=8, 256->256, 16^3 bf16"
+    else:
+        dev = lambda a, dt=bf: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+        x, P, dout, faces = recipes.unet_level_inputs(seed, 256, 64, 64, 256)
+        net = UNetLevel(h3d.Slab(dev(x), 2, 2, 64, 256), {k: (dev(w), dev(b, torch.float32)) for k, (w, b) in P.items()},
+                        dev(dout), {k: tuple(None if f is None else dev(f) for f in pr) for k, pr in faces.items()})
+        name = "U-Net-shaped level on a 64x256x256 shard of a 256^3 volume (halo 2), bf16, fwd+bwd"
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        net.step()
+    torch.cuda.synchronize()
+    if args.only:
+        sel = [o for o in net.ops if o["name"] == args.only]
+        if not sel:
+            sys.exit(f"bench.py: --only must be one of {[o['name'] for o in net.ops]}")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            sel[0]["fn"]()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"metric": "single call", "kernel": args.only, "ms": ms, "steps": args.steps,
+                          "tflops": sel[0]["flops"] / ms / 1e9, "config": {"workload": name}}))
+        return
+    tot = {o["name"]: 0.0 for o in net.ops}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        evs = []
+        for o in net.ops:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            o["fn"]()
+            e1.record(stream)
+            evs.append((o, e0, e1))
+        torch.cuda.synchronize()
+        for o, e0, e1 in evs:
+            tot[o["name"]] += e0.elapsed_time(e1)
+    dt = time.perf_counter() - t0
+    per_call = []
+    for o in net.ops:
+        ms = tot[o["name"]] / args.steps
+        per_call.append({"name": o["name"], "ms": round(ms, 4), "tflops": round(o["flops"] / ms / 1e9, 1) if o["flops"] else None,
+                         "gbs": round(o["bytes"] / ms / 1e6, 1) if o["bytes"] else None})
+    ms_step = sum(tot.values()) / args.steps
+    print(json.dumps({"metric": "conv3d fwd+bwd TFLOP/s", "value": net.conv_flops() / ms_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": name}, "per_call": per_call}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +128,9 @@ def main():
     ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "shard512", "unet", "late256"],
+                    help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
+                         "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the per-GPU share of the spatially-partitioned path); "
@@ -98,6 +165,8 @@ def main():
         return
     seed = synth.BASE_SEED if args.seed is None else args.seed
     td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    if args.workload != "cosmoflow":
+        return side_workload(args, seed)
 
     def dev(a, dt=td):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)

@@ -54,7 +54,7 @@ __global__ void pack_w_mfma_kernel(const bf16_t* __restrict__ w, bf16_t* __restr
 struct MfmaArgs {
   Geo in, mask, out;
   int cin_k, cout_k, nchunks, ncoblk;
-  int tiles_w, tiles_h, tiles_d;
+  int tiles_w, tiles_h, tiles_d, ntiles;
   float out_slope, mask_slope;
   int vec_ok;  // rows start 4-byte aligned: pairs of bf16 are loaded as one dword
 };
@@ -87,19 +87,11 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cbw = wave / ND, wd = wave % ND;
-  int t = blockIdx.x;
-  const int tw = t % a.tiles_w; t /= a.tiles_w;
-  const int th = t % a.tiles_h; t /= a.tiles_h;
-  const int td = t % a.tiles_d;
-  const int n = t / a.tiles_d;
-  const int w0 = tw * TW, h0 = th * TH, ps0 = td * ND;
   const int co_blk = blockIdx.y * NCB + cbw;
   const int W = a.in.w, H = a.in.h;
 
-  // ---- per-thread staging plan (the same for every ci chunk)
-  int lds_unit[ROUNDS];
-  int goff[ROUNDS], moff[ROUNDS];
-  int flags[ROUNDS];   // bit0/bit1: element valid; bits 4..: ci-group
+  // ---- tile-invariant part of the staging plan: which units this thread fills
+  int lds_unit[ROUNDS], item_meta[ROUNDS];   // meta: pair | hy << 8 | dz << 16 | cig << 24 (cig 2: no item)
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
     int item = tid + r * WG_THREADS;
@@ -107,24 +99,41 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     int x = item / PAIRS;
     int hy = x % TH2; x /= TH2;
     int dz = x % TD2;
-    int cig = x / TD2;
+    int cig = item < NITEMS ? x / TD2 : 2;
     lds_unit[r] = (cig * TD2 + dz) * (TH2 * P) + hy * P + 2 * pair;
-    int p_in = ps0 - a.out.hlo + dz - 1;        // local interior index of the input plane
-    int64_t gq = a.in.doff + p_in;
-    int sp = p_in + a.in.hlo;
-    bool ok = item < NITEMS && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds;
-    int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
-    ok = ok && h >= 0 && h < H;
-    int f = 0;
-    if (ok && w >= 0 && w < W) f |= 1;
-    if (ok && w + 1 >= 0 && w + 1 < W) f |= 2;
-    if (item >= NITEMS) f = 0, cig = 2;   // cig 2: never matches a channel below
-    flags[r] = f | (cig << 4);
-    goff[r] = sp * (int)a.in.plane + h * W + w;
-    moff[r] = MASKED ? (p_in + a.mask.hlo) * (int)a.mask.plane + h * W + w : 0;
+    item_meta[r] = pair | (hy << 8) | (dz << 16) | (cig << 24);
   }
-  const bf16_t* in_n = in + n * a.in.nstride;
-  const bf16_t* mask_n = MASKED ? mask + n * a.mask.nstride : nullptr;
+
+  // ---- per-tile part: global offsets and validity
+  int goff[ROUNDS], moff[ROUNDS], flags[ROUNDS];   // flags bit0/bit1: element valid
+  const bf16_t* in_n = nullptr;
+  const bf16_t* mask_n = nullptr;
+  auto plan_tile = [&](int tile) {
+    int t = tile;
+    const int tw = t % a.tiles_w; t /= a.tiles_w;
+    const int th = t % a.tiles_h; t /= a.tiles_h;
+    const int td = t % a.tiles_d;
+    const int n = t / a.tiles_d;
+    const int w0 = tw * TW, h0 = th * TH, ps0 = td * ND;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int m = item_meta[r];
+      const int pair = m & 0xff, hy = (m >> 8) & 0xff, dz = (m >> 16) & 0xff, cig = m >> 24;
+      const int p_in = ps0 - a.out.hlo + dz - 1;        // local interior index of the input plane
+      const int64_t gq = a.in.doff + p_in;
+      const int sp = p_in + a.in.hlo;
+      const int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
+      const bool ok = cig < 2 && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H;
+      int f = 0;
+      if (ok && w >= 0 && w < W) f |= 1;
+      if (ok && w + 1 >= 0 && w + 1 < W) f |= 2;
+      flags[r] = f;
+      goff[r] = sp * (int)a.in.plane + h * W + w;
+      moff[r] = MASKED ? (p_in + a.mask.hlo) * (int)a.mask.plane + h * W + w : 0;
+    }
+    in_n = in + n * a.in.nstride;
+    mask_n = MASKED ? mask + n * a.mask.nstride : nullptr;
+  };
 
   uint32_t v[ROUNDS][8];
   uint32_t mv[MASKED ? ROUNDS : 1][8];
@@ -132,12 +141,12 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   auto load_chunk = [&](int c) {
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      const int f = flags[r] & 3, cig = flags[r] >> 4;
+      const int f = flags[r], cig = item_meta[r] >> 24;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int ci = c * CI_CHUNK + cig * 8 + e;
         uint32_t val = 0, mval = 0x3f803f80u;   // mask default: 1.0 (keeps the zero)
-        if (f && ci < a.cin_k && cig < 2) {
+        if (f && ci < a.cin_k) {
           const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + goff[r];
           if (a.vec_ok) {
             val = *reinterpret_cast<const uint32_t*>(p);
@@ -165,7 +174,7 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   auto store_chunk = [&](int buf) {
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      if ((flags[r] >> 4) >= 2) continue;
+      if ((item_meta[r] >> 24) >= 2) continue;
       uint32_t g[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) g[e] = MASKED ? mask_pair(v[r][e], mv[r][e], a.mask_slope) : v[r][e];
@@ -181,10 +190,13 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   };
 
   f32x16 acc[4];
+  auto zero_acc = [&]() {
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+  };
+  zero_acc();
 
   const bool wave_active = co_blk < a.ncoblk;
   const int j = lane & 31;
@@ -224,38 +236,62 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     }
   };
 
-  // ---- main loop over ci chunks, two LDS buffers
+  // bias + activation, bf16 store; output planes outside the global volume are zero
+  auto epilogue = [&](int tile) {
+    int t = tile;
+    const int tw = t % a.tiles_w; t /= a.tiles_w;
+    const int th = t % a.tiles_h; t /= a.tiles_h;
+    const int td = t % a.tiles_d;
+    const int n = t / a.tiles_d;
+    const int w0 = tw * TW, h0 = th * TH, ps = td * ND + wd;
+    if (!wave_active || ps >= a.out.ds) return;
+    const int64_t gp = a.out.doff + ps - a.out.hlo;
+    const bool inside = gp >= 0 && gp < a.out.dglob;
+    bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
+      if (h >= H || w >= W) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int co = co_blk * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        if (co < a.cout_k) {
+          float val = acc[b][r] + (bias ? bias[co] : 0.f);
+          if (!(val > 0.f)) val *= a.out_slope;
+          out_n[(int64_t)co * a.out.cstride + h * W + w] = f32_to_bf16(inside ? val : 0.f);
+        }
+      }
+    }
+  };
+
+  // ---- persistent loop: this workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the
+  //      (tile, ci-chunk) stages alternate between two LDS buffers, and the global loads of the next
+  //      stage — the next chunk, or chunk 0 of the NEXT TILE — are in flight while this one is multiplied
+  int tile = blockIdx.x;
+  if (tile >= a.ntiles) return;
+  plan_tile(tile);
   load_chunk(0);
   store_chunk(0);
   __syncthreads();
-  for (int c = 0; c < a.nchunks; ++c) {
-    const bool more = c + 1 < a.nchunks;
-    if (more) load_chunk(c + 1);
-    if (wave_active) compute_chunk(c, c & 1);
-    if (more) store_chunk((c + 1) & 1);
-    __syncthreads();
-  }
-
-  // ---- epilogue: bias + activation, bf16 store; output planes outside the global volume are zero
-  if (!wave_active) return;
-  const int ps = ps0 + wd;
-  if (ps >= a.out.ds) return;
-  const int64_t gp = a.out.doff + ps - a.out.hlo;
-  const bool inside = gp >= 0 && gp < a.out.dglob;
-  bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
-#pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
-    if (h >= H || w >= W) continue;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int co = co_blk * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-      if (co < a.cout_k) {
-        float val = acc[b][r] + (bias ? bias[co] : 0.f);
-        if (!(val > 0.f)) val *= a.out_slope;
-        out_n[(int64_t)co * a.out.cstride + h * W + w] = f32_to_bf16(inside ? val : 0.f);
+  int buf = 0;
+  while (true) {
+    for (int c = 0; c < a.nchunks; ++c) {
+      const bool last_chunk = c + 1 == a.nchunks;
+      const int next_tile = tile + gridDim.x;
+      const bool more = !last_chunk || next_tile < a.ntiles;
+      if (more) {
+        if (last_chunk) plan_tile(next_tile);
+        load_chunk(last_chunk ? 0 : c + 1);
       }
+      if (wave_active) compute_chunk(c, buf);
+      if (more) store_chunk(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
     }
+    epilogue(tile);
+    zero_acc();
+    tile += gridDim.x;
+    if (tile >= a.ntiles) break;
   }
 }
 
@@ -288,9 +324,13 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   a.tiles_w = (int)cdiv(a.out.w, TWC);
   a.tiles_h = (int)cdiv(a.out.h, TH);
   a.tiles_d = (int)cdiv(a.out.ds, ND);
-  int64_t gx = (int64_t)n * a.tiles_d * a.tiles_h * a.tiles_w;
+  int64_t ntiles = (int64_t)n * a.tiles_d * a.tiles_h * a.tiles_w;
   int64_t gy = cdiv(a.ncoblk, NCB);
-  if (gx >= ((int64_t)1 << 31) || gy > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  if (ntiles >= ((int64_t)1 << 31) || gy > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  a.ntiles = (int)ntiles;
+  // one resident workgroup per CU (LDS-limited), spread over the output-channel groups
+  const int num_cu = static_cast<Handle*>(handle)->num_cu;
+  int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / gy));
   auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {

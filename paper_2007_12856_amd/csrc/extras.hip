@@ -210,15 +210,27 @@ __global__ void __launch_bounds__(256) dense_fwd_kernel(const T* __restrict__ x,
   constexpr int V = 16 / sizeof(T);
   const bool vec = (a.k % V == 0) && ((uintptr_t)w % 16 == 0) && ((uintptr_t)x % 16 == 0);
   if (vec) {
-    for (int k0 = lane * V; k0 < a.k; k0 += 64 * V) {
-      struct alignas(16) Pk { T v[V]; };
-      Pk wv = *reinterpret_cast<const Pk*>(wr + k0);
+    struct alignas(16) Pk { T v[V]; };
+    constexpr int UN = 4;   // weight loads in flight per lane
+    for (int k0 = lane * V; k0 < a.k; k0 += 64 * V * UN) {
+      Pk wv[UN];
 #pragma unroll
-      for (int i = 0; i < DM; ++i) {
-        if (i < a.m) {
-          Pk xv = *reinterpret_cast<const Pk*>(x + (int64_t)i * a.k + k0);
+      for (int u = 0; u < UN; ++u) {
+        const int kk = k0 + u * 64 * V;
+        if (kk < a.k) wv[u] = *reinterpret_cast<const Pk*>(wr + kk);
+      }
 #pragma unroll
-          for (int e = 0; e < V; ++e) acc[i] = fmaf(ld(&wv.v[e]), ld(&xv.v[e]), acc[i]);
+      for (int u = 0; u < UN; ++u) {
+        const int kk = k0 + u * 64 * V;
+        if (kk < a.k) {
+#pragma unroll
+          for (int i = 0; i < DM; ++i) {
+            if (i < a.m) {
+              Pk xv = *reinterpret_cast<const Pk*>(x + (int64_t)i * a.k + kk);
+#pragma unroll
+              for (int e = 0; e < V; ++e) acc[i] = fmaf(ld(&wv[u].v[e]), ld(&xv.v[e]), acc[i]);
+            }
+          }
         }
       }
     }
@@ -254,30 +266,55 @@ __device__ __forceinline__ float dense_g(const T* dy, const T* y, int64_t idx, c
   return g;
 }
 
-// dx[i][c] = sum_j g[i][j] w[j][c]: block = 1024 threads = 16 wavefronts over one tile of 64 columns x ... ;
-// wavefront r takes rows j = r, r+16, ...; partial sums meet in LDS and are added in wavefront order.
+// dx[i][c] = sum_j g[i][j] w[j][c].  Weight-streaming: a block of 1024 threads = 16 wavefronts covers
+// 128 columns (two per lane, one 4-byte load for bf16); wavefront r takes rows j = r, r+16, ... with
+// four rows in flight per iteration; the 16 partial sums meet in LDS and are added in wavefront order.
 template <typename T>
 __global__ void __launch_bounds__(1024) dense_bwd_dx_kernel(const T* __restrict__ w, const T* __restrict__ y,
                                                             const T* __restrict__ dy, T* __restrict__ dx, DenseArgs a) {
-  constexpr int CW = 4;  // columns per lane
+  constexpr int CW = 2;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int c0 = (blockIdx.x * 64 + lane) * CW;
+  const bool pair_ok = (a.k % CW == 0) && c0 + CW <= a.k && ((uintptr_t)w % (CW * sizeof(T)) == 0);
   float acc[DM][CW];
 #pragma unroll
   for (int i = 0; i < DM; ++i)
 #pragma unroll
     for (int e = 0; e < CW; ++e) acc[i][e] = 0.f;
-  for (int j = wave; j < a.n; j += 16) {
-    float wv[CW];
+  constexpr int UN = 4;
+  for (int j0 = wave; j0 < a.n; j0 += 16 * UN) {
+    float wv[UN][CW];
 #pragma unroll
-    for (int e = 0; e < CW; ++e) wv[e] = (c0 + e < a.k) ? ld(w + (int64_t)j * a.k + c0 + e) : 0.f;
+    for (int u = 0; u < UN; ++u) {
+      const int j = j0 + 16 * u;
 #pragma unroll
-    for (int i = 0; i < DM; ++i)
-      if (i < a.m) {
-        float g = dense_g(dy, y, (int64_t)i * a.n + j, a);
+      for (int e = 0; e < CW; ++e) wv[u][e] = 0.f;
+      if (j < a.n) {
+        if (pair_ok) {
+          struct alignas(CW * sizeof(T)) P2 { T v[CW]; };
+          P2 p = *reinterpret_cast<const P2*>(w + (int64_t)j * a.k + c0);
 #pragma unroll
-        for (int e = 0; e < CW; ++e) acc[i][e] = fmaf(g, wv[e], acc[i][e]);
+          for (int e = 0; e < CW; ++e) wv[u][e] = ld(&p.v[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < CW; ++e)
+            if (c0 + e < a.k) wv[u][e] = ld(w + (int64_t)j * a.k + c0 + e);
+        }
       }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int j = j0 + 16 * u;
+      if (j < a.n) {
+#pragma unroll
+        for (int i = 0; i < DM; ++i)
+          if (i < a.m) {
+            const float g = dense_g(dy, y, (int64_t)i * a.n + j, a);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) acc[i][e] = fmaf(g, wv[u][e], acc[i][e]);
+          }
+      }
+    }
   }
   __shared__ float red[16][64 * CW + 1];
   for (int i = 0; i < a.m; ++i) {
@@ -300,7 +337,8 @@ __global__ void __launch_bounds__(1024) dense_bwd_dx_kernel(const T* __restrict_
   }
 }
 
-// dw[j][c] = sum_i g[i][j] x[i][c];  db[j] = sum_i g[i][j]
+// dw[j][c] = sum_i g[i][j] x[i][c];  db[j] = sum_i g[i][j].  Output-bound (fp32 dw): four columns per
+// thread, 16-byte stores.
 template <typename T>
 __global__ void __launch_bounds__(256) dense_bwd_dw_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, float* __restrict__ dw,
@@ -315,12 +353,28 @@ __global__ void __launch_bounds__(256) dense_bwd_dw_kernel(const T* __restrict__
     for (int i = 0; i < DM; ++i) s += g[i];
     db[j] = s;
   }
-  for (int c = blockIdx.x * 256 + threadIdx.x; c < a.k; c += gridDim.x * 256) {
-    float s = 0.f;
+  const bool vec = (a.k % 4 == 0) && ((uintptr_t)x % (4 * sizeof(T)) == 0) && ((uintptr_t)dw % 16 == 0);
+  if (vec) {
+    for (int c = (blockIdx.x * 256 + threadIdx.x) * 4; c < a.k; c += gridDim.x * 1024) {
+      float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < DM; ++i)
-      if (i < a.m) s = fmaf(g[i], ld(x + (int64_t)i * a.k + c), s);
-    dw[(int64_t)j * a.k + c] = s;
+      for (int i = 0; i < DM; ++i)
+        if (i < a.m) {
+          struct alignas(4 * sizeof(T)) P4 { T v[4]; };
+          P4 p = *reinterpret_cast<const P4*>(x + (int64_t)i * a.k + c);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[e] = fmaf(g[i], ld(&p.v[e]), s[e]);
+        }
+      *reinterpret_cast<float4*>(dw + (int64_t)j * a.k + c) = float4{s[0], s[1], s[2], s[3]};
+    }
+  } else {
+    for (int c = blockIdx.x * 256 + threadIdx.x; c < a.k; c += gridDim.x * 256) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < DM; ++i)
+        if (i < a.m) s = fmaf(g[i], ld(x + (int64_t)i * a.k + c), s);
+      dw[(int64_t)j * a.k + c] = s;
+    }
   }
 }
 
@@ -469,7 +523,7 @@ extern "C" h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, 
   if (!x || !w || !dy || !dw || (act != H3D_ACT_NONE && !y)) return fail(handle, H3D_EINVAL, "dense_bwd: NULL pointer");
   DenseArgs a{m, n, k, act_slope(act, alpha), act};
   hipStream_t s = (hipStream_t)stream;
-  dim3 gdx((unsigned)cdiv(k, 256)), gdw((unsigned)std::min<int64_t>(cdiv(k, 256), 64), (unsigned)n);
+  dim3 gdx((unsigned)cdiv(k, 128)), gdw((unsigned)std::min<int64_t>(cdiv(k, 1024), 64), (unsigned)n);
   if (n > 65535) return fail(handle, H3D_EINVAL, "dense_bwd: n too large");
   if (dtype == H3D_F32) {
     if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<float>), gdx, dim3(1024), 0, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);

@@ -216,3 +216,56 @@ class UNetLevel:
 
     def conv_flops(self) -> int:
         return sum(o["flops"] for o in self.ops)
+
+
+class SingleLayer:
+    """One conv3d layer on a depth shard with its pooling and halo traffic, as a list of calls:
+    halo_unpack of both D faces, conv fwd (+bias+act), pool fwd, halo_pack of the input faces;
+    pool bwd fused with the activation backward, BF and BD on g (g carries a 1-plane halo)."""
+
+    def __init__(self, n, cin, cout, d, hw, d_offset, d_global, pool=True, act=ACT_LEAKY, alpha=0.01, dtype=torch.bfloat16, seed=0):
+        from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
+        dev = "cuda"
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(seed)
+        rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dtype)
+        self.ws = Workspace()
+        ws, es = self.ws, 2 if dtype == torch.bfloat16 else 4
+        x = self.x = Slab(rnd(n, cin, d + 2, hw, hw), 1, 1, d_offset, d_global)
+        bound = (3.0 / (27 * cin)) ** 0.5
+        w = self.w = ((torch.rand((cout, cin, 3, 3, 3), generator=gen, device=dev) * 2 - 1) * bound).to(dtype)
+        b = self.b = (torch.rand((cout,), generator=gen, device=dev) * 0.2 - 0.1)
+        z = self.z = Slab(torch.empty((n, cout, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
+        g = self.g = Slab(rnd(n, cout, d + 2, hw, hw), 1, 1, d_offset, d_global)
+        dx = self.dx = Slab(torch.empty((n, cin, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
+        self.dw = torch.empty((cout, cin, 3, 3, 3), device=dev)
+        self.db = torch.empty((cout,), device=dev)
+        faces = [torch.empty(halo_bytes(x, 1) // es, dtype=dtype, device=dev) for _ in range(2)]
+        gfaces = [torch.empty(halo_bytes(g, 1) // es, dtype=dtype, device=dev) for _ in range(2)]
+        self.ops = []
+        fl = 2 * 27 * cin * cout * n * d * hw * hw
+        vox = n * d * hw * hw
+
+        def op(name, fn, flops=0, nbytes=0):
+            self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": int(nbytes)})
+
+        op("halo_pack_x", lambda: (halo_pack(x, FACE_D_LO, 1, faces[0]), halo_pack(x, FACE_D_HI, 1, faces[1])), 0, 4 * faces[0].numel() * es)
+        op("halo_unpack_x", lambda: (halo_unpack(faces[1], x, FACE_D_LO, 1), halo_unpack(faces[0], x, FACE_D_HI, 1)), 0, 4 * faces[0].numel() * es)
+        op("conv_fwd", lambda: conv3d_fwd(x, w, b, z, act, alpha, ws), fl, (x.t.numel() + z.t.numel() + w.numel()) * es)
+        if pool:
+            p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
+            dp = self.dp = Slab(rnd(n, cout, d // 2, hw // 2, hw // 2), 0, 0, d_offset // 2, d_global // 2)
+            op("pool_fwd", lambda: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
+            op("pool_bwd_act", lambda: pool3d_bwd_act(dp, None, z, g, POOL_AVG, act, alpha), 0, (dp.t.numel() + 2 * z.t.numel()) * es)
+        op("halo_pack_g", lambda: (halo_pack(g, FACE_D_LO, 1, gfaces[0]), halo_pack(g, FACE_D_HI, 1, gfaces[1])), 0, 4 * gfaces[0].numel() * es)
+        op("halo_unpack_g", lambda: (halo_unpack(gfaces[1], g, FACE_D_LO, 1), halo_unpack(gfaces[0], g, FACE_D_HI, 1)), 0, 4 * gfaces[0].numel() * es)
+        op("conv_bwd_filter", lambda: conv3d_bwd_filter(x, g, None, self.dw, self.db, ACT_NONE, 0.0, ws), fl,
+           (x.t.numel() + vox * cout) * es + w.numel() * 4)
+        op("conv_bwd_data", lambda: conv3d_bwd_data(g, None, w, dx, ACT_NONE, 0.0, ws), fl, (g.t.numel() + dx.t.numel() + w.numel()) * es)
+
+    def step(self):
+        for o in self.ops:
+            o["fn"]()
+
+    def conv_flops(self):
+        return sum(o["flops"] for o in self.ops)
