@@ -56,7 +56,6 @@ struct MfmaArgs {
   int cin_k, cout_k, nchunks, ncoblk;
   int tiles_w, tiles_h, tiles_d, ntiles;
   float out_slope, mask_slope;
-  int vec_ok;  // rows start 4-byte aligned: pairs of bf16 are loaded as one dword
 };
 
 __device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t m, float slope) {
@@ -68,7 +67,21 @@ __device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t m, float slop
   return (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
 }
 
-template <int NCB, int ND, int TWC, bool MASKED>
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int BUF_OOB = (int)0x80000000;   // byte offset beyond every buffer: such a lane reads zero
+
+// The descriptor must live in scalar registers: the pointer is passed through readfirstlane so the
+// compiler knows it is wave-uniform (otherwise every load becomes a waterfall loop).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  void* q = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(q, 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+// VEC: rows start 4-byte aligned and W is even, so a pair of bf16 is one dword load (the normal case);
+// otherwise the two elements of a pair are fetched by two 2-byte loads with their own validity.
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC>
 __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ mask,
                                                                  const uint4* __restrict__ wp, const float* __restrict__ bias,
                                                                  bf16_t* __restrict__ out, MfmaArgs a) {
@@ -104,10 +117,13 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     item_meta[r] = pair | (hy << 8) | (dz << 16) | (cig << 24);
   }
 
-  // ---- per-tile part: global offsets and validity
-  int goff[ROUNDS], moff[ROUNDS], flags[ROUNDS];   // flags bit0/bit1: element valid
-  const bf16_t* in_n = nullptr;
-  const bf16_t* mask_n = nullptr;
+  // ---- per-tile part: byte offsets of this thread's items inside the sample (ci-group included),
+  //      BUF_OOB where the item lies outside the volume: a buffer load then returns zero without
+  //      any branch or select.  The channel inside the chunk is added as a scalar offset.
+  constexpr int NV = VEC ? 1 : 2;
+  int voff[ROUNDS][NV], moffb[MASKED ? ROUNDS : 1][NV];
+  int n_plan = 0;   // sample index of the planned tile (wave-uniform)
+  const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wp, (uint32_t)a.ncoblk * a.nchunks * 27 * 1024);
   auto plan_tile = [&](int tile) {
     int t = tile;
     const int tw = t % a.tiles_w; t /= a.tiles_w;
@@ -124,49 +140,58 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
       const int sp = p_in + a.in.hlo;
       const int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
       const bool ok = cig < 2 && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H;
-      int f = 0;
-      if (ok && w >= 0 && w < W) f |= 1;
-      if (ok && w + 1 >= 0 && w + 1 < W) f |= 2;
-      flags[r] = f;
-      goff[r] = sp * (int)a.in.plane + h * W + w;
-      moff[r] = MASKED ? (p_in + a.mask.hlo) * (int)a.mask.plane + h * W + w : 0;
+      const int base = 2 * (cig * 8 * (int)a.in.cstride + sp * (int)a.in.plane + h * W + w);
+      const int mbase = MASKED ? 2 * (cig * 8 * (int)a.mask.cstride + (p_in + a.mask.hlo) * (int)a.mask.plane + h * W + w) : 0;
+#pragma unroll
+      for (int e2 = 0; e2 < NV; ++e2) {
+        const bool okw = VEC ? (ok && w >= 0 && w + 1 < W) : (ok && w + e2 >= 0 && w + e2 < W);
+        voff[r][e2] = okw ? base + 2 * e2 : BUF_OOB;
+        if (MASKED) moffb[r][e2] = okw ? mbase + 2 * e2 : BUF_OOB;
+      }
     }
-    in_n = in + n * a.in.nstride;
-    mask_n = MASKED ? mask + n * a.mask.nstride : nullptr;
+    n_plan = n;
   };
 
   uint32_t v[ROUNDS][8];
   uint32_t mv[MASKED ? ROUNDS : 1][8];
 
-  auto load_chunk = [&](int c) {
+  // `live` = false turns every load into an out-of-range (zero, no traffic) one: the last stage of a
+  // workgroup has nothing to prefetch, but keeping the load count identical on every path lets the
+  // compiler use exact s_waitcnt counts for the weight fragments instead of waiting for everything.
+  auto load_chunk = [&](int c, bool live) {
+    const bool full = (c + 1) * CI_CHUNK <= a.cin_k;   // uniform: no channel of this chunk is beyond Cin
+    const __amdgpu_buffer_rsrc_t rs_in = make_rsrc(in + n_plan * a.in.nstride, (uint32_t)a.in.nstride * 2);
+    const __amdgpu_buffer_rsrc_t rs_mask = make_rsrc(MASKED ? mask + n_plan * a.mask.nstride : in, (uint32_t)a.mask.nstride * 2);
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int f = flags[r], cig = item_meta[r] >> 24;
+    for (int e = 0; e < 8; ++e) {
+      const int soff = __builtin_amdgcn_readfirstlane(2 * (c * CI_CHUNK + e) * (int)a.in.cstride);
+      const int smoff = MASKED ? __builtin_amdgcn_readfirstlane(2 * (c * CI_CHUNK + e) * (int)a.mask.cstride) : 0;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int ci = c * CI_CHUNK + cig * 8 + e;
-        uint32_t val = 0, mval = 0x3f803f80u;   // mask default: 1.0 (keeps the zero)
-        if (f && ci < a.cin_k) {
-          const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + goff[r];
-          if (a.vec_ok) {
-            val = *reinterpret_cast<const uint32_t*>(p);
-          } else {
-            if (f & 1) val = p[0];
-            if (f & 2) val |= (uint32_t)p[1] << 16;
-          }
-          if (MASKED) {
-            const bf16_t* q = mask_n + (int64_t)ci * a.mask.cstride + moff[r];
-            if (a.vec_ok) {
-              mval = *reinterpret_cast<const uint32_t*>(q);
-            } else {
-              mval = 0;
-              if (f & 1) mval = q[0];
-              if (f & 2) mval |= (uint32_t)q[1] << 16;
-            }
+      for (int r = 0; r < ROUNDS; ++r) {
+        int vo[NV], mo[NV];
+#pragma unroll
+        for (int e2 = 0; e2 < NV; ++e2) {
+          vo[e2] = live ? voff[r][e2] : BUF_OOB;
+          mo[e2] = MASKED ? (live ? moffb[r][e2] : BUF_OOB) : 0;
+          if (!full) {
+            const bool chan_ok = c * CI_CHUNK + (item_meta[r] >> 24) * 8 + e < a.cin_k;
+            vo[e2] = chan_ok ? vo[e2] : BUF_OOB;
+            mo[e2] = chan_ok ? mo[e2] : BUF_OOB;
           }
         }
-        v[r][e] = val;
-        if (MASKED) mv[r][e] = mval;
+        if (VEC) {
+          v[r][e] = __builtin_amdgcn_raw_buffer_load_b32(rs_in, vo[0], soff, 0);
+          if (MASKED) mv[r][e] = __builtin_amdgcn_raw_buffer_load_b32(rs_mask, mo[0], smoff, 0);
+        } else {
+          const uint32_t lo = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_in, vo[0], soff, 0);
+          const uint32_t hi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_in, vo[NV - 1], soff, 0);
+          v[r][e] = lo | (hi << 16);
+          if (MASKED) {
+            const uint32_t ml = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_mask, mo[0], smoff, 0);
+            const uint32_t mh = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_mask, mo[NV - 1], smoff, 0);
+            mv[r][e] = ml | (mh << 16);
+          }
+        }
       }
     }
   };
@@ -189,54 +214,78 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     }
   };
 
-  f32x16 acc[4];
-  auto zero_acc = [&]() {
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
-  };
-  zero_acc();
-
   const bool wave_active = co_blk < a.ncoblk;
   const int j = lane & 31;
-  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2 + j / TWC) * P + (j % TWC) + 1;
-  const uint4* wp_blk = wp + (int64_t)(wave_active ? co_blk : 0) * a.nchunks * 27 * 64 + lane;
+  // accumulators start from the bias of their output channel (row 8*(r/4) + 4*(lane/32) + r%4 of the block)
+  f32x16 acc[4];
+  auto init_acc = [&]() {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = co_blk * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+      const float bv = (bias && co < a.cout_k) ? bias[co] : 0.f;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) acc[b][r] = bv;
+    }
+  };
+  init_acc();
 
+  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2 + j / TWC) * P + (j % TWC) + 1;
+
+  const int a_voff = ((wave_active ? co_blk : 0) * a.nchunks * 27 * 64 + lane) * 16;
   auto load_a = [&](int c, int step, uint4 (&dst)[3]) {
     const int kd = step / 3, kw = step % 3;
-    const uint4* p = wp_blk + (int64_t)c * 27 * 64;
 #pragma unroll
-    for (int kh = 0; kh < 3; ++kh) dst[kh] = p[(kd * 9 + kh * 3 + kw) * 64];
+    for (int kh = 0; kh < 3; ++kh) {
+      const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, __builtin_amdgcn_readfirstlane((c * 27 + kd * 9 + kh * 3 + kw) * 1024), 0);
+      dst[kh] = uint4{t.x, t.y, t.z, t.w};
+    }
   };
 
-  auto compute_chunk = [&](int c, int buf) {
+  // One chunk = 9 (kd,kw) steps of 12 MFMAs.  Vector-memory loads return in order, so a wait for a
+  // weight fragment also waits for every load issued before it.  The weight fragments of the first
+  // APRE steps are therefore requested BEFORE the (long-latency) input loads of the next stage are
+  // issued (`issue_next`), and the remaining ones only once those have had several steps to land.
+  constexpr int APRE = 5;
+  auto compute_chunk = [&](int c, int buf, auto&& issue_next) {
     const uint4* base = lds + buf * BUF_UNITS + lane_unit;
-    uint4 a_cur[3], a_nxt[3];
-    load_a(c, 0, a_cur);
+    uint4 afr[9][3];
+    uint4 bfr[2][NFRAG];     // row fragments of the current and of the next (kd,kw) step
+    auto load_b = [&](int step, uint4 (&dst)[NFRAG]) {
+      const int kd = step / 3, kw = step % 3;
+#pragma unroll
+      for (int s = 0; s < NFRAG; ++s) dst[s] = base[(kd * TH2 + s) * P + kw];
+    };
+#pragma unroll
+    for (int step = 0; step < APRE; ++step) load_a(c, step, afr[step]);
+    load_b(0, bfr[0]);
+    __builtin_amdgcn_sched_barrier(0);   // keep the weight requests ahead of the input loads ...
+    issue_next();
+    __builtin_amdgcn_sched_barrier(0);   // ... and the input loads ahead of the MFMA steps (not sunk below them)
 #pragma unroll
     for (int step = 0; step < 9; ++step) {
-      const int kd = step / 3, kw = step % 3;
-      if (step + 1 < 9) load_a(c, step + 1, a_nxt);
+      if (step + 1 < 9) load_b(step + 1, bfr[(step + 1) & 1]);     // in flight during this step's MFMAs
+      if (step == APRE - 1) {
+#pragma unroll
+        for (int s2 = APRE; s2 < 9; ++s2) load_a(c, s2, afr[s2]);
+      }
 #pragma unroll
       for (int s = 0; s < NFRAG; ++s) {
-        const uint4 fr = base[(kd * TH2 + s) * P + kw];
-        const bf16x8 B = __builtin_bit_cast(bf16x8, fr);
+        const bf16x8 B = __builtin_bit_cast(bf16x8, bfr[step & 1][s]);
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh) {
           // the block whose start row b*RPB + kh equals s
           if (s - kh >= 0 && (s - kh) % RPB == 0 && (s - kh) / RPB < 4) {
             const int b = (s - kh) / RPB;
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_cur[kh]), B, acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afr[step][kh]), B, acc[b], 0, 0, 0);
           }
         }
       }
-#pragma unroll
-      for (int kh = 0; kh < 3; ++kh) a_cur[kh] = a_nxt[kh];
     }
   };
 
-  // bias + activation, bf16 store; output planes outside the global volume are zero
+  // activation, bf16 store (the bias is already in the accumulators); output planes outside the global
+  // volume are zero.  Buffer stores: the lane's voxel offset (BUF_OOB where the voxel is beyond H or W:
+  // such a store is dropped) plus a scalar channel offset — no branches, no 64-bit address arithmetic.
   auto epilogue = [&](int tile) {
     int t = tile;
     const int tw = t % a.tiles_w; t /= a.tiles_w;
@@ -247,19 +296,20 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     if (!wave_active || ps >= a.out.ds) return;
     const int64_t gp = a.out.doff + ps - a.out.hlo;
     const bool inside = gp >= 0 && gp < a.out.dglob;
-    bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
+    const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
+    const int row_ch = 4 * (lane >> 5);   // this lane's accumulator rows are channels 8*(r/4) + row_ch + r%4 of the block
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
-      if (h >= H || w >= W) continue;
+      const int vo = (h < H && w < W) ? 2 * (row_ch * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int co = co_blk * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-        if (co < a.cout_k) {
-          float val = acc[b][r] + (bias ? bias[co] : 0.f);
-          if (!(val > 0.f)) val *= a.out_slope;
-          out_n[(int64_t)co * a.out.cstride + h * W + w] = f32_to_bf16(inside ? val : 0.f);
-        }
+        const int co_u = co_blk * 32 + 8 * (r / 4) + (r % 4);            // wave-uniform part of the channel
+        const bool ch_ok = co_u + row_ch < a.cout_k;
+        float val = acc[b][r];
+        if (!(val > 0.f)) val *= a.out_slope;
+        __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(inside ? val : 0.f), rs_out, ch_ok ? vo : BUF_OOB,
+                                              __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
       }
     }
   };
@@ -267,30 +317,34 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   // ---- persistent loop: this workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the
   //      (tile, ci-chunk) stages alternate between two LDS buffers, and the global loads of the next
   //      stage — the next chunk, or chunk 0 of the NEXT TILE — are in flight while this one is multiplied
-  int tile = blockIdx.x;
+  // consecutive workgroup ids land on different XCDs (each with its own L2): remap so that the
+  // workgroups of one XCD work on neighbouring tiles and share the halo lines in that L2
+  const int G = gridDim.x;
+  int tile = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
   if (tile >= a.ntiles) return;
   plan_tile(tile);
-  load_chunk(0);
+  load_chunk(0, true);
   store_chunk(0);
   __syncthreads();
   int buf = 0;
   while (true) {
     for (int c = 0; c < a.nchunks; ++c) {
       const bool last_chunk = c + 1 == a.nchunks;
-      const int next_tile = tile + gridDim.x;
+      const int next_tile = tile + G;
       const bool more = !last_chunk || next_tile < a.ntiles;
-      if (more) {
-        if (last_chunk) plan_tile(next_tile);
-        load_chunk(last_chunk ? 0 : c + 1);
-      }
-      if (wave_active) compute_chunk(c, buf);
+      auto issue_next = [&]() {
+        if (last_chunk && more) plan_tile(next_tile);
+        load_chunk(last_chunk ? 0 : c + 1, more);
+      };
+      if (wave_active) compute_chunk(c, buf, issue_next);
+      else issue_next();
       if (more) store_chunk(buf ^ 1);
       __syncthreads();
       buf ^= 1;
     }
     epilogue(tile);
-    zero_acc();
-    tile += gridDim.x;
+    init_acc();
+    tile += G;
     if (tile >= a.ntiles) break;
   }
 }
@@ -301,7 +355,8 @@ bool mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
   // 32-bit in-sample offsets inside the kernel
   int64_t in_sample = (int64_t)(in->halo_lo + in->d + in->halo_hi) * in->h * in->w;
   int64_t out_sample = (int64_t)(out->halo_lo + out->d + out->halo_hi) * out->h * out->w;
-  return in_sample < ((int64_t)1 << 30) && out_sample < ((int64_t)1 << 30);
+  // buffer loads address a whole sample (all channels) with 31-bit byte offsets
+  return in_sample * in->c < ((int64_t)1 << 30) && out_sample * out->c < ((int64_t)1 << 30);
 }
 
 static void wp_dims(int cin_k, int cout_k, int* nchunks, int* ncoblk) {
@@ -315,7 +370,7 @@ size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   return (size_t)ncoblk * nchunks * 27 * 512 * sizeof(bf16_t);
 }
 
-template <int NCB, int ND, int TWC, bool MASKED>
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC>
 static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
                                  bf16_t* out, MfmaArgs a, int n, hipStream_t stream) {
   constexpr int RPB = 32 / TWC, TH = 4 * RPB;
@@ -331,7 +386,7 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   // one resident workgroup per CU (LDS-limited), spread over the output-channel groups
   const int num_cu = static_cast<Handle*>(handle)->num_cu;
   int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / gy));
-  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED>;
+  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED, VEC>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
@@ -342,17 +397,17 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   return launch_status(handle, "conv3d_mfma");
 }
 
-template <bool MASKED>
+template <bool MASKED, bool VEC>
 static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
                                bf16_t* out, const MfmaArgs& a, int n, hipStream_t s) {
   const bool wide = a.out.w > 16;
   const bool two_cb = a.cout_k > 32;
   if (wide) {
-    return two_cb ? launch_variant<2, 4, 32, MASKED>(handle, in, mask, wp, bias, out, a, n, s)
-                  : launch_variant<1, 8, 32, MASKED>(handle, in, mask, wp, bias, out, a, n, s);
+    return two_cb ? launch_variant<2, 4, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s)
+                  : launch_variant<1, 8, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
   }
-  return two_cb ? launch_variant<2, 4, 16, MASKED>(handle, in, mask, wp, bias, out, a, n, s)
-                : launch_variant<1, 8, 16, MASKED>(handle, in, mask, wp, bias, out, a, n, s);
+  return two_cb ? launch_variant<2, 4, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s)
+                : launch_variant<1, 8, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
 }
 
 h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
@@ -368,15 +423,19 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   if ((int64_t)out->n * a.out.ds * out->h * out->w == 0) return H3D_OK;
   if (!ws || ws_bytes < mfma_fwd_ws_bytes(in, out)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace must be 16-byte aligned");
-  a.vec_ok = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && (!mask || (uintptr_t)mask->data % 4 == 0);
+  const bool vec = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && (!mask || (uintptr_t)mask->data % 4 == 0);
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
   int64_t total = (int64_t)a.ncoblk * a.nchunks * 27 * 512;
   hipLaunchKernelGGL(pack_w_mfma_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin,
                      cout, transpose ? 1 : 0, a.nchunks, a.ncoblk);
   const bf16_t* ip = (const bf16_t*)in->data;
   const bf16_t* mp = mask ? (const bf16_t*)mask->data : nullptr;
-  if (mask) return pick_variant<true>(handle, ip, mp, (const uint4*)ws, bias, (bf16_t*)out->data, a, out->n, stream);
-  return pick_variant<false>(handle, ip, mp, (const uint4*)ws, bias, (bf16_t*)out->data, a, out->n, stream);
+  bf16_t* op = (bf16_t*)out->data;
+  const uint4* wq = (const uint4*)ws;
+  if (mask) return vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
+                       : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
+  return vec ? pick_variant<false, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
+             : pick_variant<false, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
 }
 
 }  // namespace h3d
