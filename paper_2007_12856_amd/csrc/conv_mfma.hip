@@ -298,18 +298,44 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     const bool inside = gp >= 0 && gp < a.out.dglob;
     const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
     const int row_ch = 4 * (lane >> 5);   // this lane's accumulator rows are channels 8*(r/4) + row_ch + r%4 of the block
+    if (VEC) {
+      // Two adjacent voxels live in adjacent lanes.  Lane pairs swap one value (DPP quad_perm [1,0,3,2])
+      // so that the even lane holds both voxels of channel row r and the odd lane both voxels of row
+      // r+1: every lane then stores ONE dword (two bf16) instead of two shorts.
+      const bool odd = lane & 1;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
-      const int vo = (h < H && w < W) ? 2 * (row_ch * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
+      for (int b = 0; b < 4; ++b) {
+        const int h = h0 + b * RPB + j / TWC, w = w0 + (j % TWC) - (odd ? 1 : 0);
+        const int vo = (h < H && w < W)
+                           ? 2 * ((row_ch + (odd ? 1 : 0)) * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int co_u = co_blk * 32 + 8 * (r / 4) + (r % 4);            // wave-uniform part of the channel
-        const bool ch_ok = co_u + row_ch < a.cout_k;
-        float val = acc[b][r];
-        if (!(val > 0.f)) val *= a.out_slope;
-        __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(inside ? val : 0.f), rs_out, ch_ok ? vo : BUF_OOB,
-                                              __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
+        for (int r = 0; r < 16; r += 2) {
+          const int co_u = co_blk * 32 + 8 * (r / 4) + (r % 4);          // wave-uniform part of the even lane's channel
+          const bool ch_ok = co_u + row_ch + (odd ? 1 : 0) < a.cout_k;
+          float v0 = acc[b][r], v1 = acc[b][r + 1];
+          if (!(v0 > 0.f)) v0 *= a.out_slope;
+          if (!(v1 > 0.f)) v1 *= a.out_slope;
+          const float give = odd ? v0 : v1;
+          const float got = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(give), 0xB1, 0xF, 0xF, true));
+          const uint32_t pk = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
+          __builtin_amdgcn_raw_buffer_store_b32(inside ? pk : 0u, rs_out, ch_ok ? vo : BUF_OOB,
+                                                __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
+        const int vo = (h < H && w < W) ? 2 * (row_ch * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int co_u = co_blk * 32 + 8 * (r / 4) + (r % 4);            // wave-uniform part of the channel
+          const bool ch_ok = co_u + row_ch < a.cout_k;
+          float val = acc[b][r];
+          if (!(val > 0.f)) val *= a.out_slope;
+          __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(inside ? val : 0.f), rs_out, ch_ok ? vo : BUF_OOB,
+                                                __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
+        }
       }
     }
   };
@@ -423,7 +449,8 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   if ((int64_t)out->n * a.out.ds * out->h * out->w == 0) return H3D_OK;
   if (!ws || ws_bytes < mfma_fwd_ws_bytes(in, out)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace must be 16-byte aligned");
-  const bool vec = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && (!mask || (uintptr_t)mask->data % 4 == 0);
+  const bool vec = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && ((uintptr_t)out->data % 4 == 0) &&
+                   (!mask || (uintptr_t)mask->data % 4 == 0);
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
   int64_t total = (int64_t)a.ncoblk * a.nchunks * 27 * 512;
   hipLaunchKernelGGL(pack_w_mfma_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin,
