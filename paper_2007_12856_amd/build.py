@@ -42,6 +42,9 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    # a shared library links with undefined symbols: load it once so a missing kernel stub fails the build
+    import ctypes
+    ctypes.CDLL(LIB, mode=ctypes.RTLD_GLOBAL if hasattr(ctypes, "RTLD_GLOBAL") else 0)
     if verbose:
         print("built", LIB)
     return LIB

@@ -27,6 +27,20 @@ namespace h3d {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int BF_OOB = (int)0x80000000;   // byte offset beyond every buffer: such a lane transfers zeros
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t bf_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                           (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+// 64 lanes x 16 bytes from per-lane buffer offsets straight into 1 KB of LDS at `lds_dst` (wave-uniform)
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rs, uint4* lds_dst, int voff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds_dst, 16, voff, 0, 0, 0);
+}
+
 constexpr int cmod_ge(int lo, int target_mod16) {  // smallest v >= lo with v % 16 == target_mod16
   int v = lo;
   while (v % 16 != target_mod16) ++v;
@@ -54,8 +68,10 @@ struct BfmArgs {
   int tiles_w, tiles_h;       // tiles per plane
   int64_t ntiles;             // n * d * tiles_h * tiles_w
   int tiles_per_chunk, nchunks;
+  int gy, gz;                 // output-channel groups and input-channel groups of the grid
   float mask_slope;
   int vec_ok;                 // W % 8 == 0 and 16-byte aligned bases: whole units are loaded at once
+  int dma_ok;                 // every sample fits 31-bit byte offsets: tiles can be moved by buffer loads into LDS
 };
 
 __device__ __forceinline__ uint4 load_unit(const bf16_t* base, int w, int W, bool row_ok, bool vec, int w0) {
@@ -86,8 +102,11 @@ __device__ __forceinline__ uint32_t mask2(uint32_t v, uint32_t m, float slope) {
 // SMALLCI (Cin <= 5: the first layer of both networks): the 48 columns 0..47 hold every (ci,kd,kh)
 // combination, so instead of splitting columns the four wavefronts of a workgroup split the K-steps
 // of each tile and their accumulators are added in wavefront order at the end.
-template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI>
-__global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_kernel(const bf16_t* __restrict__ x,
+// DMA: the tiles go global -> LDS directly (buffer_load ... lds, 16 bytes per lane, no registers and no
+// VALU in between; lanes whose unit is padding or lies outside the volume use an out-of-range offset
+// and deposit zeros).  Needs whole 16-byte units (W % 8 == 0, aligned bases) and no fused mask.
+template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI, bool DMA>
+__global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG, DMA ? 3 : 1) bwd_filter_mfma_kernel(const bf16_t* __restrict__ x,
                                                                               const bf16_t* __restrict__ dz,
                                                                               const bf16_t* __restrict__ z,
                                                                               float* __restrict__ part, BfmArgs a) {
@@ -97,13 +116,27 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_ker
   constexpr int NT = 64 * NW;
   constexpr int CI_WG = SMALLCI ? 6 : 16;     // channels staged per workgroup
   constexpr int CO_WG = 16 * RBW * NRG;
+  static_assert(!(DMA && MASKED), "the mask needs the register path");
+  constexpr int XPAD = (CI_WG * T::PC + 63) / 64 * 64;     // x region rounded up to whole 64-unit DMA chunks
+  constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64;
   extern __shared__ uint4 lds[];
   uint4* xl = lds;                    // [CI_WG][3 kd][TH+2 rows][PR units]  (pitches PC, PD, PR)
-  uint4* gl = lds + CI_WG * T::PC;    // [CO_WG][TH rows][GU units]          (pitch PG)
+  uint4* gl = lds + XPAD;             // [CO_WG][TH rows][GU units]          (pitch PG)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
-  const int chunk = blockIdx.x, co0 = blockIdx.y * CO_WG, ci0 = blockIdx.z * 16;
+  // Workgroups that stream the SAME voxel chunk (all ci groups, all co groups) are made neighbours in
+  // time and placed on the same XCD, so the tiles they share are served by that XCD's L2: the linear
+  // block id is (chunk / 8, group, chunk % 8) and consecutive ids go to the 8 XCDs round-robin.
+  const int ngrp = a.gy * a.gz;
+  int chunk, grp;
+  {
+    const int b = blockIdx.x, full = (a.nchunks / 8) * 8 * ngrp;
+    if (b < full) { chunk = (b / (8 * ngrp)) * 8 + b % 8; grp = (b / 8) % ngrp; }
+    else { const int r = b - full, rem = a.nchunks % 8; chunk = (a.nchunks / 8) * 8 + r % rem; grp = r / rem; }
+  }
+  const int zi = grp % a.gz;
+  const int co0 = (grp / a.gz) * CO_WG, ci0 = zi * 16;
   const int W = a.x.w, H = a.x.h, D = a.x.d;
   const int rg = SMALLCI ? 0 : wave / 3;       // row group of this wavefront
   const int cb0 = SMALLCI ? 0 : 3 * (wave % 3);  // first of this wavefront's three column blocks
@@ -119,7 +152,7 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_ker
   const int ga_off = (rg * 16 * RBW + lc) * T::PG + (T::GW == 4 ? lg : (lg / T::GW) * T::GU + lg % T::GW);
   const bool edge_lo = (lg % T::GW) == 0, edge_hi = (lg % T::GW) == T::GW - 1;
   const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
-  const bool do_db = (SMALLCI || wave % 3 == 0) && (blockIdx.z == 0);
+  const bool do_db = (SMALLCI || wave % 3 == 0) && (zi == 0);
 
   // ---- staging plan (tile-invariant part): which units this thread copies
   constexpr int XITEMS = CI_WG * 3 * (TH + 2) * T::XU;
@@ -148,6 +181,33 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_ker
     g_meta[r] = item < GITEMS ? (row | (u << 8) | (col << 16) | ((co0 + col < a.cout ? 1 : 0) << 28)) : -1;
   }
 
+  // ---- DMA plan: wavefront w owns the 64-unit LDS chunks w, w+NW, ...; lane l fills unit 64*chunk + l
+  constexpr int NCHX = XPAD / 64, NCHG = GPAD / 64;
+  constexpr int CXW = DMA ? (NCHX + NW - 1) / NW : 1, CGW = DMA ? (NCHG + NW - 1) / NW : 1;
+  int dx_rel[CXW], dx_meta[CXW];    // byte offset relative to (plane p, row h0, column w0) of channel ci0; meta: row | kd<<8 | w8<<12, -1 = never valid
+  int dg_rel[CGW], dg_meta[CGW];
+  if (DMA) {
+#pragma unroll
+    for (int i = 0; i < CXW; ++i) {
+      const int ul = 64 * (wave + NW * i) + lane;
+      const int cil = ul / T::PC, r1 = ul % T::PC;
+      const int kd = r1 / T::PD, r2 = r1 % T::PD;
+      const int row = r2 / T::PR, u = r2 % T::PR;
+      const bool ok = wave + NW * i < NCHX && cil < CI_WG && kd < 3 && row < TH + 2 && u < T::XU && ci0 + cil < a.cin;
+      dx_meta[i] = ok ? (row | (kd << 8) | (u << 12)) : -1;
+      dx_rel[i] = 2 * ((ci0 + cil) * (int)a.x.cstride + (kd - 1 + a.x.hlo) * (int)a.x.plane + (row - 1) * W + 8 * u - 8);
+    }
+#pragma unroll
+    for (int i = 0; i < CGW; ++i) {
+      const int ul = 64 * (wave + NW * i) + lane;
+      const int col = ul / T::PG, r1 = ul % T::PG;
+      const int row = r1 / T::GU, u = r1 % T::GU;
+      const bool ok = wave + NW * i < NCHG && col < CO_WG && r1 < TH * T::GU && co0 + col < a.cout;
+      dg_meta[i] = ok ? (row | (u << 12)) : -1;
+      dg_rel[i] = 2 * ((co0 + col) * (int)a.g.cstride + a.g.hlo * (int)a.g.plane + row * W + 8 * u);
+    }
+  }
+
   f32x4 acc[RBW][3][3];
   f32x4 accdb[RBW];
 #pragma unroll
@@ -161,16 +221,49 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_ker
   const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
   const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
 
-  const int64_t t_begin = (int64_t)chunk * a.tiles_per_chunk;
-  const int64_t t_end = min(t_begin + a.tiles_per_chunk, a.ntiles);
-  for (int64_t tile = t_begin; tile < t_end; ++tile) {
-    int64_t r = tile;
-    const int tw = (int)(r % a.tiles_w); r /= a.tiles_w;
-    const int th = (int)(r % a.tiles_h); r /= a.tiles_h;
-    const int p = (int)(r % D);
-    const int n = (int)(r / D);
+  // tile coordinates are decoded once and then advanced incrementally (no divisions in the loop)
+  const int t_begin = chunk * a.tiles_per_chunk;
+  const int t_end = min(t_begin + a.tiles_per_chunk, (int)a.ntiles);
+  int tw, th, p, n;
+  {
+    int r = t_begin;
+    tw = r % a.tiles_w; r /= a.tiles_w;
+    th = r % a.tiles_h; r /= a.tiles_h;
+    p = r % D;
+    n = r / D;
+  }
+  for (int tile = t_begin; tile < t_end; ++tile, ++tw) {
+    if (tw == a.tiles_w) { tw = 0; ++th; }
+    if (th == a.tiles_h) { th = 0; ++p; }
+    if (p == D) { p = 0; ++n; }
     const int w0 = tw * TW, h0 = th * TH;
 
+    if (DMA) {
+      __syncthreads();   // everyone is done reading the previous tile
+      const __amdgpu_buffer_rsrc_t rs_x = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+      const __amdgpu_buffer_rsrc_t rs_g = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+      const int tx = 2 * (p * (int)a.x.plane + h0 * W + w0), tg = 2 * (p * (int)a.g.plane + h0 * W + w0);
+#pragma unroll
+      for (int i = 0; i < CXW; ++i) {
+        const int m = dx_meta[i];
+        const int row = m & 0xff, kd = (m >> 8) & 0xf, w = w0 + 8 * ((m >> 12) & 0xff) - 8;
+        const int h = h0 + row - 1;
+        const int64_t gq = a.x.doff + p + kd - 1;
+        const bool ok = m >= 0 && h >= 0 && h < H && gq >= 0 && gq < a.x.dglob && w >= 0 && w + 8 <= W;
+        if (wave + NW * i < NCHX)
+          dma16(rs_x, xl + 64 * (wave + NW * i), ok ? tx + dx_rel[i] : BF_OOB);
+      }
+#pragma unroll
+      for (int i = 0; i < CGW; ++i) {
+        const int m = dg_meta[i];
+        const int row = m & 0xff, w = w0 + 8 * ((m >> 12) & 0xff);
+        const bool ok = m >= 0 && h0 + row < H && w + 8 <= W;
+        if (wave + NW * i < NCHG)
+          dma16(rs_g, gl + 64 * (wave + NW * i), ok ? tg + dg_rel[i] : BF_OOB);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    } else {
     // ---- global -> registers for this tile (issued before the barrier so they overlap the
     //      other wavefronts' last K-steps), then registers -> LDS
     uint4 xv[XR], gv[GR], mvv[MASKED ? GR : 1];
@@ -213,6 +306,8 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG) bwd_filter_mfma_ker
       gl[((m >> 16) & 0xfff) * T::PG + (m & 0xff) * T::GU + ((m >> 8) & 0xff)] = v;
     }
     __syncthreads();
+
+    }
 
     // ---- K-steps of 32 voxels
 #pragma unroll
@@ -376,13 +471,13 @@ size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
   return (size_t)p.nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
 }
 
-template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI>
+template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI, bool DMA>
 static h3d_status bf_launch(void* handle, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part, const BfmArgs& a,
                             dim3 grid, hipStream_t stream) {
   using T = BfTile<TW, TH>;
-  constexpr size_t tile_bytes = (size_t)((SMALLCI ? 6 : 16) * T::PC + 16 * RBW * NRG * T::PG) * 16;
+  constexpr size_t tile_bytes = (size_t)(((SMALLCI ? 6 : 16) * T::PC + 63) / 64 * 64 + (16 * RBW * NRG * T::PG + 63) / 64 * 64) * 16;
   constexpr size_t lds_bytes = tile_bytes < 3 * 64 * 16 ? 3 * 64 * 16 : tile_bytes;
-  auto kern = bwd_filter_mfma_kernel<RBW, NRG, TW, TH, MASKED, SMALLCI>;
+  auto kern = bwd_filter_mfma_kernel<RBW, NRG, TW, TH, MASKED, SMALLCI, DMA>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
@@ -396,9 +491,16 @@ static h3d_status bf_launch(void* handle, const bf16_t* x, const bf16_t* dz, con
 template <int RBW, int NRG, bool MASKED, bool SMALLCI>
 static h3d_status bf_pick_tile(void* handle, const BfPlan& p, const bf16_t* x, const bf16_t* dz, const bf16_t* z, float* part,
                                const BfmArgs& a, dim3 grid, hipStream_t s) {
-  if (p.tw == 64) return bf_launch<RBW, NRG, 64, 2, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
-  if (p.tw == 32) return bf_launch<RBW, NRG, 32, 4, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
-  return bf_launch<RBW, NRG, 16, 4, MASKED, SMALLCI>(handle, x, dz, z, part, a, grid, s);
+  if constexpr (!MASKED) {
+    if (a.vec_ok && a.dma_ok) {
+      if (p.tw == 64) return bf_launch<RBW, NRG, 64, 2, false, SMALLCI, true>(handle, x, dz, z, part, a, grid, s);
+      if (p.tw == 32) return bf_launch<RBW, NRG, 32, 4, false, SMALLCI, true>(handle, x, dz, z, part, a, grid, s);
+      return bf_launch<RBW, NRG, 16, 4, false, SMALLCI, true>(handle, x, dz, z, part, a, grid, s);
+    }
+  }
+  if (p.tw == 64) return bf_launch<RBW, NRG, 64, 2, MASKED, SMALLCI, false>(handle, x, dz, z, part, a, grid, s);
+  if (p.tw == 32) return bf_launch<RBW, NRG, 32, 4, MASKED, SMALLCI, false>(handle, x, dz, z, part, a, grid, s);
+  return bf_launch<RBW, NRG, 16, 4, MASKED, SMALLCI, false>(handle, x, dz, z, part, a, grid, s);
 }
 
 template <bool MASKED>
@@ -424,10 +526,14 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   a.tiles_w = p.tiles_w; a.tiles_h = p.tiles_h; a.ntiles = p.ntiles;
   a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
   a.mask_slope = mask_slope;
+  a.dma_ok = (int64_t)a.x.nstride * 2 < ((int64_t)1 << 31) && (int64_t)a.g.nstride * 2 < ((int64_t)1 << 31);
   a.vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
   int64_t gy = cdiv(a.cout, 16 * p.rbw * p.nrg), gz = cdiv(a.cin, 16);
   if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
-  dim3 grid((unsigned)p.nchunks, (unsigned)gy, (unsigned)gz);
+  if (p.ntiles >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many tiles");
+  a.gy = (int)gy; a.gz = (int)gz;
+  if ((int64_t)p.nchunks * gy * gz >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many workgroups");
+  dim3 grid((unsigned)((int64_t)p.nchunks * gy * gz));
   const bf16_t* xp = (const bf16_t*)x->data;
   const bf16_t* gp = (const bf16_t*)dz->data;
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
