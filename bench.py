@@ -114,6 +114,20 @@ def side_workload(args, seed):
                       "config": {"workload": name}, "per_call": per_call}))
 
 
+def measured_traffic(workload, call):
+    """HBM bytes per launch of `call`, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the
+    plain-copy factors; read from the 'TRAFFIC <call> <bytes>' lines of profiles/<workload>_step_hbm_traffic.txt.
+    None when no measurement of that call is on record."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_step_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 3 and f[0] == "TRAFFIC" and f[1] == call:
+            return int(f[2])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,13 +259,7 @@ def main():
     roof["ms"] = round(dom_ms, 4)
     roof["algorithmic_bytes"] = op["bytes"]
     roof["algorithmic_flops"] = op["flops"]
-    roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            roof["traffic"] = json.load(open(tpath)).get(op["name"])
-        except Exception:
-            roof["traffic"] = None
+    roof["traffic"] = measured_traffic(args.workload, op["name"])
 
     out = {
         "metric": "conv3d fwd+bwd TFLOP/s", "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
