@@ -401,6 +401,252 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG, DMA ? 3 : 1) bwd_fi
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Row-rolling variant for the wide layers (W >= 32, whole 16-byte units, no fused mask).
+//
+// Same GEMM, different split of the 27 taps: a column block is the 16 input channels of ONE kd plane
+// (a wavefront per kd), and the kh taps are not columns but ROWS: the operand built from x row r pairs
+// with g row r - kh.  So one aligned 16-byte LDS read of an x row segment (plus its two edge dwords)
+// feeds 9 x RBW MFMAs (3 kh x 3 kw), and each g row fragment is read once and kept in registers while
+// three x rows pass.  LDS traffic per MFMA is less than half that of the column-per-(ci,kd,kh) kernel
+// above, and nothing in the inner loop depends on a branch: the edge dwords of a row segment are read
+// by all lanes of a column from one address (a broadcast) and selected against the neighbouring lane
+// group's dword (ds_bpermute) afterwards.  The row loop is software-pipelined three deep (LDS reads two
+// rows ahead, cross-lane exchange one row ahead).
+template <int TH>
+struct RollTile {
+  static constexpr int TW = 32;
+  static constexpr int XU = TW / 8 + 2;            // x row: w in [w0-8, w0+TW+8)
+  static constexpr int PR = XU;
+  static constexpr int PD = (TH + 2) * PR;
+  static constexpr int PC = (3 * PD) | 1;          // odd channel pitch: the 16 channels of a column block hit 16 bank groups
+  static constexpr int GU = TW / 8;
+  static constexpr int PG = (TH * GU) | 1;
+};
+
+template <int RBW, int NRG, int TH>
+__global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf16_t* __restrict__ x,
+                                                                                    const bf16_t* __restrict__ dz,
+                                                                                    float* __restrict__ part, BfmArgs a) {
+  using T = RollTile<TH>;
+  constexpr int NW = 3 * NRG;
+  constexpr int CO_WG = 16 * RBW * NRG;
+  constexpr int XPAD = (16 * T::PC + 63) / 64 * 64;
+  constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64;
+  constexpr int NCHX = XPAD / 64, NCHG = GPAD / 64;
+  constexpr int CXW = (NCHX + NW - 1) / NW, CGW = (NCHG + NW - 1) / NW;
+  extern __shared__ uint4 lds[];
+  uint4* xl = lds;                    // [16 ci][3 kd][TH+2 rows][6 units]  (pitches PC, PD, PR)
+  uint4* gl = lds + XPAD;             // [CO_WG][TH rows][4 units]          (pitch PG)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lg = lane >> 4, lc = lane & 15;
+  const int ngrp = a.gy * a.gz;
+  int chunk, grp;
+  {
+    const int b = blockIdx.x, full = (a.nchunks / 8) * 8 * ngrp;
+    if (b < full) { chunk = (b / (8 * ngrp)) * 8 + b % 8; grp = (b / 8) % ngrp; }
+    else { const int r = b - full, rem = a.nchunks % 8; chunk = (a.nchunks / 8) * 8 + r % rem; grp = r / rem; }
+  }
+  const int zi = grp % a.gz;
+  const int co0 = (grp / a.gz) * CO_WG, ci0 = zi * 16;
+  const int W = a.x.w, H = a.x.h, D = a.x.d;
+  const int rg = wave / 3, kd = wave % 3;
+  const bool edge_lo = lg == 0, edge_hi = lg == 3;
+  const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
+  const bool do_db = kd == 0 && zi == 0;
+  // per-lane LDS byte addresses; rows and row blocks are compile-time offsets on top
+  const char* xb_p = reinterpret_cast<const char*>(xl) + 16 * (lc * T::PC + kd * T::PD + 1 + lg);
+  const char* pe_p = reinterpret_cast<const char*>(xl) + 16 * (lc * T::PC + kd * T::PD) + 12;   // last dword of unit 0
+  const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * ((rg * 16 * RBW + lc) * T::PG + lg);
+
+  // staging plan: wavefront w fills the 64-unit LDS chunks w, w + NW, ...; lane l fills unit 64 * chunk + l
+  int dx_meta[CXW];    // row | kd << 8 | u << 12 | ci << 16, -1 = padding or channel out of range
+  int dg_meta[CGW];    // row | u << 12 | co << 16
+#pragma unroll
+  for (int i = 0; i < CXW; ++i) {
+    const int ul = 64 * (wave + NW * i) + lane;
+    const int cil = ul / T::PC, r1 = ul % T::PC;
+    const int pk = r1 / T::PD, r2 = r1 % T::PD;
+    const int row = r2 / T::PR, u = r2 % T::PR;
+    const bool ok = wave + NW * i < NCHX && cil < 16 && pk < 3 && ci0 + cil < a.cin;
+    dx_meta[i] = ok ? (row | (pk << 8) | (u << 12) | ((ci0 + cil) << 16)) : -1;
+  }
+#pragma unroll
+  for (int i = 0; i < CGW; ++i) {
+    const int ul = 64 * (wave + NW * i) + lane;
+    const int col = ul / T::PG, r1 = ul % T::PG;
+    const int row = r1 / T::GU, u = r1 % T::GU;
+    const bool ok = wave + NW * i < NCHG && col < CO_WG && r1 < TH * T::GU && co0 + col < a.cout;
+    dg_meta[i] = ok ? (row | (u << 12) | ((co0 + col) << 16)) : -1;
+  }
+
+  f32x4 acc[RBW][3][3];   // [row block][kh][kw]
+  f32x4 accdb[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    accdb[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) acc[rb][kh][kw] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
+
+  const int t_begin = chunk * a.tiles_per_chunk;
+  const int t_end = min(t_begin + a.tiles_per_chunk, (int)a.ntiles);
+  int tw, th, p, n;
+  {
+    int r = t_begin;
+    tw = r % a.tiles_w; r /= a.tiles_w;
+    th = r % a.tiles_h; r /= a.tiles_h;
+    p = r % D;
+    n = r / D;
+  }
+  for (int tile = t_begin; tile < t_end; ++tile, ++tw) {
+    if (tw == a.tiles_w) { tw = 0; ++th; }
+    if (th == a.tiles_h) { th = 0; ++p; }
+    if (p == D) { p = 0; ++n; }
+    const int w0 = tw * T::TW, h0 = th * TH;
+
+    __syncthreads();   // everyone is done reading the previous tile
+    {
+      const __amdgpu_buffer_rsrc_t rs_x = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+      const __amdgpu_buffer_rsrc_t rs_g = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+      const int tx = (p - 1 + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
+      const int tg = (p + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
+      int kdmask = 0;     // which of the three planes p-1, p, p+1 exist in the global volume
+#pragma unroll
+      for (int pk = 0; pk < 3; ++pk) {
+        const int64_t gq = a.x.doff + p + pk - 1;
+        if (gq >= 0 && gq < a.x.dglob) kdmask |= 1 << pk;
+      }
+#pragma unroll
+      for (int i = 0; i < CXW; ++i) {
+        int m = dx_meta[i];
+        // opaque to the optimiser: otherwise every field of every plan entry is unpacked once, kept in a
+        // register of its own across the tile loop, and the accumulators are spilled to make room
+        asm volatile("" : "+v"(m));
+        const int row = m & 0xff, pk = (m >> 8) & 0xf, u8 = 8 * ((m >> 12) & 0xf), ci = m >> 16;
+        const int w = w0 + u8 - 8, h = h0 + row - 1;
+        const bool ok = m >= 0 && h >= 0 && h < H && ((kdmask >> pk) & 1) && w >= 0 && w + 8 <= W;
+        if (wave + NW * i < NCHX)
+          dma16(rs_x, xl + 64 * (wave + NW * i),
+                ok ? 2 * (tx + ci * (int)a.x.cstride + pk * (int)a.x.plane + row * W + u8) : BF_OOB);
+      }
+#pragma unroll
+      for (int i = 0; i < CGW; ++i) {
+        int m = dg_meta[i];
+        asm volatile("" : "+v"(m));
+        const int row = m & 0xff, u8 = 8 * ((m >> 12) & 0xf), co = m >> 16;
+        const bool ok = m >= 0 && h0 + row < H && w0 + u8 + 8 <= W;
+        if (wave + NW * i < NCHG)
+          dma16(rs_g, gl + 64 * (wave + NW * i), ok ? 2 * (tg + co * (int)a.g.cstride + row * W + u8) : BF_OOB);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+
+    // Row loop.  Per x row r: B(r) = {row r shifted by -1, 0, +1}; MFMA groups in the order kh = 2, 1, 0
+    // (g rows r-2, r-1, r), so the register slot of g row r-2 is free after the first group and takes g
+    // row r+1, which is first needed at the END of the next iteration.  The LDS reads of x row r+1 are
+    // issued at the top of iteration r; its cross-lane exchange sits between the first two MFMA groups.
+    uint4 blk[2];
+    uint32_t pe, ne, pv, nx;
+    bf16x8 A[3][RBW];
+    bf16x8 B0, B1, B2;
+    auto read_x = [&](int r) {      // x row r: aligned block + the two edge dwords of the row segment
+      const int off = 16 * T::PR * r;
+      blk[r & 1] = *reinterpret_cast<const uint4*>(xb_p + off);
+      pe = *reinterpret_cast<const uint32_t*>(pe_p + off);
+      ne = *reinterpret_cast<const uint32_t*>(pe_p + off + 16 * (T::XU - 1) - 12);
+    };
+    auto read_g = [&](int r) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb)
+        A[r % 3][rb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ga_p + 16 * (rb * 16 * T::PG + r * T::GU)));
+    };
+    auto exchange = [&](int r) {
+      // The dword before / after this lane's block.  Lane group 3's last dword is wanted by nobody (its
+      // "next" group is group 0 by wrap-around), so it hands the segment's low edge dword to group 0
+      // instead; likewise group 0 hands the high edge dword to group 3.
+      pv = __builtin_amdgcn_ds_bpermute(bp_prev, edge_hi ? pe : blk[r & 1].w);
+      nx = __builtin_amdgcn_ds_bpermute(bp_next, edge_lo ? ne : blk[r & 1].x);
+    };
+    auto build_B = [&](int r) {
+      const uint4 b = blk[r & 1];
+      const uint32_t s0 = __builtin_amdgcn_alignbit(b.x, pv, 16);
+      const uint32_t s1 = __builtin_amdgcn_alignbit(b.y, b.x, 16);
+      const uint32_t s2 = __builtin_amdgcn_alignbit(b.z, b.y, 16);
+      const uint32_t s3 = __builtin_amdgcn_alignbit(b.w, b.z, 16);
+      const uint32_t s4 = __builtin_amdgcn_alignbit(nx, b.w, 16);
+      const uint4 f0 = {s0, s1, s2, s3}, f2 = {s1, s2, s3, s4};
+      B0 = __builtin_bit_cast(bf16x8, f0); B1 = __builtin_bit_cast(bf16x8, b); B2 = __builtin_bit_cast(bf16x8, f2);
+    };
+    auto mfma_group = [&](int r, int kh) {   // x row r meets g row r - kh under tap row kh
+      const int gr = r - kh;
+      if (gr < 0 || gr >= TH) return;
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        acc[rb][kh][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B0, acc[rb][kh][0], 0, 0, 0);
+        acc[rb][kh][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B1, acc[rb][kh][1], 0, 0, 0);
+        acc[rb][kh][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B2, acc[rb][kh][2], 0, 0, 0);
+      }
+    };
+    read_x(0);
+    read_g(0);
+    exchange(0);
+#pragma unroll
+    for (int r = 0; r < TH + 2; ++r) {
+      build_B(r);
+      if (r + 1 < TH + 2) read_x(r + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(r, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      if (r + 1 < TH) read_g(r + 1);
+      if (r + 1 < TH + 2) exchange(r + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(r, 1);
+      mfma_group(r, 0);
+      if (r < TH && do_db) {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) accdb[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[r % 3][rb], ones, accdb[rb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- partial tile -> workspace [chunk][cout][cin][27] (+ [chunk][cout] for the bias partial behind it)
+  float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
+  const int ci = ci0 + lc;
+  if (ci < a.cin) {
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + (rg * RBW + rb) * 16 + 4 * lg + rr;
+        if (co < a.cout) {
+          float* o = pw + ((int64_t)co * a.cin + ci) * 27 + kd * 9;
+#pragma unroll
+          for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) o[kh * 3 + kw] = acc[rb][kh][kw][rr];
+        }
+      }
+  }
+  if (do_db && lc == 0) {
+    float* pb = part + (int64_t)a.nchunks * a.cout * a.cin * 27 + (int64_t)chunk * a.cout;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + (rg * RBW + rb) * 16 + 4 * lg + rr;
+        if (co < a.cout) pb[co] = accdb[rb][rr];
+      }
+  }
+}
+
 // Second stage: out[i] = sum over chunks of part[chunk][i] in a FIXED order.  A block takes 16
 // consecutive outputs; 16 thread groups each add every 16th chunk in increasing order, then the 16
 // group sums are added in group order.  (dw and the bias partials share the kernel: the bias
@@ -437,14 +683,18 @@ struct BfPlan {
   int tiles_per_chunk, nchunks;
 };
 
-static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout) {
+// The row-rolling kernel takes the wide layers with more than a handful of input channels.
+static bool bf_roll_shape(const h3d_tensor* x) { return x->w >= 32 && x->c > 5; }
+
+static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   BfPlan p;
-  if (x->w > 32) { p.tw = 64; p.th = 2; }
-  else if (x->w > 16) { p.tw = 32; p.th = 4; }
-  else { p.tw = 16; p.th = 4; }
   p.smallci = x->c <= 5;
   p.rbw = cout <= 16 ? 1 : 2;
   p.nrg = (cout > 32 && !p.smallci) ? 2 : 1;
+  if (roll) { p.tw = 32; p.th = p.nrg == 2 ? 8 : 4; }
+  else if (x->w > 32) { p.tw = 64; p.th = 2; }
+  else if (x->w > 16) { p.tw = 32; p.th = 4; }
+  else { p.tw = 16; p.th = 4; }
   p.tiles_w = (int)cdiv(x->w, p.tw);
   p.tiles_h = (int)cdiv(x->h, p.th);
   p.ntiles = (int64_t)x->n * x->d * p.tiles_h * p.tiles_w;
@@ -467,8 +717,26 @@ bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
 }
 
 size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
-  BfPlan p = bf_plan_mfma(x, dz->c);
-  return (size_t)p.nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
+  // which kernel runs also depends on alignment and on the fused mask, unknown here: size for either
+  int nchunks = bf_plan_mfma(x, dz->c, false).nchunks;
+  if (bf_roll_shape(x)) nchunks = std::max(nchunks, bf_plan_mfma(x, dz->c, true).nchunks);
+  return (size_t)nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
+}
+
+template <int RBW, int NRG, int TH>
+static h3d_status bf_roll_launch(void* handle, const bf16_t* x, const bf16_t* dz, float* part, const BfmArgs& a, dim3 grid,
+                                 hipStream_t stream) {
+  using T = RollTile<TH>;
+  constexpr size_t lds_bytes = (size_t)((16 * T::PC + 63) / 64 * 64 + (16 * RBW * NRG * T::PG + 63) / 64 * 64) * 16;
+  auto kern = bwd_filter_roll_kernel<RBW, NRG, TH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(192 * NRG), lds_bytes, stream, x, dz, part, a);
+  return H3D_OK;
 }
 
 template <int RBW, int NRG, int TW, int TH, bool MASKED, bool SMALLCI, bool DMA>
@@ -517,7 +785,11 @@ static h3d_status bf_pick(void* handle, const BfPlan& p, const bf16_t* x, const 
 
 h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw, float* db,
                            float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
-  BfPlan p = bf_plan_mfma(x, dz->c);
+  const bool vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
+  const bool dma_ok = (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w * x->c * 2 < ((int64_t)1 << 31) &&
+                      (int64_t)(dz->halo_lo + dz->d + dz->halo_hi) * dz->h * dz->w * dz->c * 2 < ((int64_t)1 << 31);
+  const bool roll = !z && vec_ok && dma_ok && bf_roll_shape(x);
+  BfPlan p = bf_plan_mfma(x, dz->c, roll);
   if (!ws || ws_bytes < mfma_bf_ws_bytes(x, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace must be 16-byte aligned");
   BfmArgs a;
@@ -526,8 +798,8 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   a.tiles_w = p.tiles_w; a.tiles_h = p.tiles_h; a.ntiles = p.ntiles;
   a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
   a.mask_slope = mask_slope;
-  a.dma_ok = (int64_t)a.x.nstride * 2 < ((int64_t)1 << 31) && (int64_t)a.g.nstride * 2 < ((int64_t)1 << 31);
-  a.vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
+  a.dma_ok = dma_ok;
+  a.vec_ok = vec_ok;
   int64_t gy = cdiv(a.cout, 16 * p.rbw * p.nrg), gz = cdiv(a.cin, 16);
   if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
   if (p.ntiles >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many tiles");
@@ -537,8 +809,15 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   const bf16_t* xp = (const bf16_t*)x->data;
   const bf16_t* gp = (const bf16_t*)dz->data;
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
-  h3d_status st = z ? bf_pick<true>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream)
-                    : bf_pick<false>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream);
+  h3d_status st;
+  if (roll) {
+    if (p.nrg == 2) st = bf_roll_launch<2, 2, 8>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else if (p.rbw == 2) st = bf_roll_launch<2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else st = bf_roll_launch<1, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+  } else {
+    st = z ? bf_pick<true>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream)
+           : bf_pick<false>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream);
+  }
   if (st != H3D_OK) return st;
   int64_t nw = (int64_t)a.cout * a.cin * 27;
   hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
