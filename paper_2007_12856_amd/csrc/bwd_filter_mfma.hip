@@ -404,40 +404,42 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG, DMA ? 3 : 1) bwd_fi
 // ---------------------------------------------------------------------------------------------------
 // Row-rolling variant for the wide layers (W >= 32, whole 16-byte units, no fused mask).
 //
-// Same GEMM, different split of the 27 taps: a column block is the 16 input channels of ONE kd plane
-// (a wavefront per kd), and the kh taps are not columns but ROWS: the operand built from x row r pairs
+// Same GEMM, different split of the 27 taps: a column block is 16 input channels of ONE kd plane (a
+// wavefront per kd), and the kh taps are not columns but ROWS: the operand built from x row r pairs
 // with g row r - kh.  So one aligned 16-byte LDS read of an x row segment (plus its two edge dwords)
 // feeds 9 x RBW MFMAs (3 kh x 3 kw), and each g row fragment is read once and kept in registers while
-// three x rows pass.  LDS traffic per MFMA is less than half that of the column-per-(ci,kd,kh) kernel
-// above, and nothing in the inner loop depends on a branch: the edge dwords of a row segment are read
-// by all lanes of a column from one address (a broadcast) and selected against the neighbouring lane
-// group's dword (ds_bpermute) afterwards.  The row loop is software-pipelined three deep (LDS reads two
-// rows ahead, cross-lane exchange one row ahead).
+// three x rows pass.  Nothing in the inner loop depends on a branch: the edge dwords of a row segment
+// are read by all lanes of a column from one address (a broadcast) and travel to the lane group that
+// needs them inside the same ds_bpermute that exchanges the neighbours' dwords.
+//
+// Tiles are walked along DEPTH first.  The x planes live in a ring of four LDS slots (plane q in slot
+// q mod 4): a step in depth brings in ONE new plane, the other two are already there.  While a tile is
+// being multiplied, the next tile's plane and g tile are on their way into the free slot / the other g
+// buffer (buffer_load ... lds), so a tile costs one barrier and the copies overlap the MFMAs.
+// A workgroup = 3 kd x CIB channel blocks x NRG row groups of wavefronts.
 template <int TH>
 struct RollTile {
   static constexpr int TW = 32;
   static constexpr int XU = TW / 8 + 2;            // x row: w in [w0-8, w0+TW+8)
-  static constexpr int PR = XU;
-  static constexpr int PD = (TH + 2) * PR;
-  static constexpr int PC = (3 * PD) | 1;          // odd channel pitch: the 16 channels of a column block hit 16 bank groups
+  static constexpr int PCI = ((TH + 2) * XU) | 1;  // odd channel pitch: the 16 channels of a column block hit 16 bank groups
   static constexpr int GU = TW / 8;
   static constexpr int PG = (TH * GU) | 1;
 };
 
-template <int RBW, int NRG, int TH>
-__global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf16_t* __restrict__ x,
-                                                                                    const bf16_t* __restrict__ dz,
-                                                                                    float* __restrict__ part, BfmArgs a) {
+template <int RBW, int NRG, int CIB, int TH>
+__global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(const bf16_t* __restrict__ x,
+                                                                           const bf16_t* __restrict__ dz,
+                                                                           float* __restrict__ part, BfmArgs a) {
   using T = RollTile<TH>;
-  constexpr int NW = 3 * NRG;
-  constexpr int CO_WG = 16 * RBW * NRG;
-  constexpr int XPAD = (16 * T::PC + 63) / 64 * 64;
+  constexpr int NW = 3 * NRG * CIB;
+  constexpr int CO_WG = 16 * RBW * NRG, CI_WG = 16 * CIB;
+  constexpr int SLOTP = (CI_WG * T::PCI + 63) / 64 * 64;      // one plane of the x tile, whole 64-unit copy chunks
   constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64;
-  constexpr int NCHX = XPAD / 64, NCHG = GPAD / 64;
+  constexpr int NCHX = SLOTP / 64, NCHG = GPAD / 64;
   constexpr int CXW = (NCHX + NW - 1) / NW, CGW = (NCHG + NW - 1) / NW;
   extern __shared__ uint4 lds[];
-  uint4* xl = lds;                    // [16 ci][3 kd][TH+2 rows][6 units]  (pitches PC, PD, PR)
-  uint4* gl = lds + XPAD;             // [CO_WG][TH rows][4 units]          (pitch PG)
+  uint4* xl = lds;                    // [4 slots][CI_WG][TH+2 rows][6 units]  (pitches SLOTP, PCI, XU)
+  uint4* gl = lds + 4 * SLOTP;        // [2 buffers][CO_WG][TH rows][4 units]  (pitches GPAD, PG, GU)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
@@ -449,37 +451,71 @@ __global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf1
     else { const int r = b - full, rem = a.nchunks % 8; chunk = (a.nchunks / 8) * 8 + r % rem; grp = r / rem; }
   }
   const int zi = grp % a.gz;
-  const int co0 = (grp / a.gz) * CO_WG, ci0 = zi * 16;
+  const int co0 = (grp / a.gz) * CO_WG, ci0 = zi * CI_WG;
   const int W = a.x.w, H = a.x.h, D = a.x.d;
-  const int rg = wave / 3, kd = wave % 3;
+  const int kd = wave % 3, cib = (wave / 3) % CIB, rg = wave / (3 * CIB);
   const bool edge_lo = lg == 0, edge_hi = lg == 3;
   const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
-  const bool do_db = kd == 0 && zi == 0;
-  // per-lane LDS byte addresses; rows and row blocks are compile-time offsets on top
-  const char* xb_p = reinterpret_cast<const char*>(xl) + 16 * (lc * T::PC + kd * T::PD + 1 + lg);
-  const char* pe_p = reinterpret_cast<const char*>(xl) + 16 * (lc * T::PC + kd * T::PD) + 12;   // last dword of unit 0
-  const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * ((rg * 16 * RBW + lc) * T::PG + lg);
+  const bool do_db = kd == 0 && cib == 0 && zi == 0;
+  // per-lane LDS byte offsets inside a slot / a g buffer; rows and row blocks are compile-time offsets on top
+  const int xb_o = 16 * ((cib * 16 + lc) * T::PCI + 1 + lg);
+  const int pe_o = 16 * ((cib * 16 + lc) * T::PCI) + 12;       // last dword of unit 0 of the row
+  const int ga_o = 16 * ((rg * 16 * RBW + lc) * T::PG + lg);
 
-  // staging plan: wavefront w fills the 64-unit LDS chunks w, w + NW, ...; lane l fills unit 64 * chunk + l
-  int dx_meta[CXW];    // row | kd << 8 | u << 12 | ci << 16, -1 = padding or channel out of range
-  int dg_meta[CGW];    // row | u << 12 | co << 16
+  // copy plan: wavefront w fills the 64-unit chunks w, w + NW, ... of a slot (or g buffer); lane l fills unit 64 * chunk + l
+  int dx_meta[CXW];    // row | u << 8 | ci << 16, -1 = padding or channel out of range
+  int dg_meta[CGW];    // row | u << 8 | co << 16
 #pragma unroll
   for (int i = 0; i < CXW; ++i) {
     const int ul = 64 * (wave + NW * i) + lane;
-    const int cil = ul / T::PC, r1 = ul % T::PC;
-    const int pk = r1 / T::PD, r2 = r1 % T::PD;
-    const int row = r2 / T::PR, u = r2 % T::PR;
-    const bool ok = wave + NW * i < NCHX && cil < 16 && pk < 3 && ci0 + cil < a.cin;
-    dx_meta[i] = ok ? (row | (pk << 8) | (u << 12) | ((ci0 + cil) << 16)) : -1;
+    const int cil = ul / T::PCI, r1 = ul % T::PCI;
+    const int row = r1 / T::XU, u = r1 % T::XU;
+    const bool ok = wave + NW * i < NCHX && cil < CI_WG && row < TH + 2 && ci0 + cil < a.cin;
+    dx_meta[i] = ok ? (row | (u << 8) | ((ci0 + cil) << 16)) : -1;
   }
 #pragma unroll
   for (int i = 0; i < CGW; ++i) {
     const int ul = 64 * (wave + NW * i) + lane;
     const int col = ul / T::PG, r1 = ul % T::PG;
     const int row = r1 / T::GU, u = r1 % T::GU;
-    const bool ok = wave + NW * i < NCHG && col < CO_WG && r1 < TH * T::GU && co0 + col < a.cout;
-    dg_meta[i] = ok ? (row | (u << 12) | ((co0 + col) << 16)) : -1;
+    const bool ok = wave + NW * i < NCHG && col < CO_WG && row < TH && co0 + col < a.cout;
+    dg_meta[i] = ok ? (row | (u << 8) | ((co0 + col) << 16)) : -1;
   }
+
+  // plane q (relative to the slab's first owned plane) of sample n, rows h0-1.., columns w0-8.. -> slot q mod 4
+  auto load_plane = [&](int n, int q, int h0, int w0) {
+    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const int64_t gq = a.x.doff + q;
+    const bool plane_ok = gq >= 0 && gq < a.x.dglob;
+    const int t0 = (q + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
+    uint4* dst = xl + ((q + 4) & 3) * SLOTP;
+#pragma unroll
+    for (int i = 0; i < CXW; ++i) {
+      int m = dx_meta[i];
+      // opaque to the optimiser: otherwise every field of every plan entry is unpacked once, kept in a
+      // register of its own across the tile loop, and the accumulators are spilled to make room
+      asm volatile("" : "+v"(m));
+      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), ci = m >> 16;
+      const int w = w0 + u8 - 8, h = h0 + row - 1;
+      const bool ok = m >= 0 && plane_ok && h >= 0 && h < H && w >= 0 && w + 8 <= W;
+      if (wave + NW * i < NCHX)
+        dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + ci * (int)a.x.cstride + row * W + u8) : BF_OOB);
+    }
+  };
+  auto load_g = [&](int n, int q, int h0, int w0, int buf) {
+    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+    const int t0 = (q + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
+    uint4* dst = gl + buf * GPAD;
+#pragma unroll
+    for (int i = 0; i < CGW; ++i) {
+      int m = dg_meta[i];
+      asm volatile("" : "+v"(m));
+      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), co = m >> 16;
+      const bool ok = m >= 0 && h0 + row < H && w0 + u8 + 8 <= W;
+      if (wave + NW * i < NCHG)
+        dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + co * (int)a.g.cstride + row * W + u8) : BF_OOB);
+    }
+  };
 
   f32x4 acc[RBW][3][3];   // [row block][kh][kw]
   f32x4 accdb[RBW];
@@ -494,59 +530,44 @@ __global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf1
   const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
   const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
 
+  // tile order: depth fastest, then columns, rows, samples
   const int t_begin = chunk * a.tiles_per_chunk;
   const int t_end = min(t_begin + a.tiles_per_chunk, (int)a.ntiles);
   int tw, th, p, n;
   {
     int r = t_begin;
+    p = r % D; r /= D;
     tw = r % a.tiles_w; r /= a.tiles_w;
-    th = r % a.tiles_h; r /= a.tiles_h;
-    p = r % D;
-    n = r / D;
+    th = r % a.tiles_h;
+    n = r / a.tiles_h;
   }
-  for (int tile = t_begin; tile < t_end; ++tile, ++tw) {
-    if (tw == a.tiles_w) { tw = 0; ++th; }
-    if (th == a.tiles_h) { th = 0; ++p; }
-    if (p == D) { p = 0; ++n; }
-    const int w0 = tw * T::TW, h0 = th * TH;
-
-    __syncthreads();   // everyone is done reading the previous tile
-    {
-      const __amdgpu_buffer_rsrc_t rs_x = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
-      const __amdgpu_buffer_rsrc_t rs_g = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
-      const int tx = (p - 1 + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
-      const int tg = (p + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
-      int kdmask = 0;     // which of the three planes p-1, p, p+1 exist in the global volume
-#pragma unroll
-      for (int pk = 0; pk < 3; ++pk) {
-        const int64_t gq = a.x.doff + p + pk - 1;
-        if (gq >= 0 && gq < a.x.dglob) kdmask |= 1 << pk;
-      }
-#pragma unroll
-      for (int i = 0; i < CXW; ++i) {
-        int m = dx_meta[i];
-        // opaque to the optimiser: otherwise every field of every plan entry is unpacked once, kept in a
-        // register of its own across the tile loop, and the accumulators are spilled to make room
-        asm volatile("" : "+v"(m));
-        const int row = m & 0xff, pk = (m >> 8) & 0xf, u8 = 8 * ((m >> 12) & 0xf), ci = m >> 16;
-        const int w = w0 + u8 - 8, h = h0 + row - 1;
-        const bool ok = m >= 0 && h >= 0 && h < H && ((kdmask >> pk) & 1) && w >= 0 && w + 8 <= W;
-        if (wave + NW * i < NCHX)
-          dma16(rs_x, xl + 64 * (wave + NW * i),
-                ok ? 2 * (tx + ci * (int)a.x.cstride + pk * (int)a.x.plane + row * W + u8) : BF_OOB);
-      }
-#pragma unroll
-      for (int i = 0; i < CGW; ++i) {
-        int m = dg_meta[i];
-        asm volatile("" : "+v"(m));
-        const int row = m & 0xff, u8 = 8 * ((m >> 12) & 0xf), co = m >> 16;
-        const bool ok = m >= 0 && h0 + row < H && w0 + u8 + 8 <= W;
-        if (wave + NW * i < NCHG)
-          dma16(rs_g, gl + 64 * (wave + NW * i), ok ? 2 * (tg + co * (int)a.g.cstride + row * W + u8) : BF_OOB);
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+  if (t_begin < t_end) {
+    load_plane(n, p - 1, th * TH, tw * T::TW);
+    load_plane(n, p, th * TH, tw * T::TW);
+    load_plane(n, p + 1, th * TH, tw * T::TW);
+    load_g(n, p, th * TH, tw * T::TW, 0);
+  }
+  int buf = 0;
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    // this tile's copies have landed (each wavefront waits for its own, the barrier collects them all),
+    // and everyone is done with the previous tile, whose g buffer and oldest plane are now free
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    int tw2 = tw, th2 = th, p2 = p + 1, n2 = n;
+    if (p2 == D) { p2 = 0; ++tw2; }
+    if (tw2 == a.tiles_w) { tw2 = 0; ++th2; }
+    if (th2 == a.tiles_h) { th2 = 0; ++n2; }
+    const bool has_next = tile + 1 < t_end;
+    const bool jump = has_next && p2 == 0;      // the next tile starts a new column of tiles: none of its planes is here
+    if (has_next) {
+      load_g(n2, p2, th2 * TH, tw2 * T::TW, buf ^ 1);
+      if (!jump) load_plane(n2, p2 + 1, th2 * TH, tw2 * T::TW);
+    }
+
+    const char* xs = reinterpret_cast<const char*>(xl) + 16 * SLOTP * ((p + kd + 3) & 3);   // plane p + kd - 1
+    const char* xb_p = xs + xb_o;
+    const char* pe_p = xs + pe_o;
+    const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * GPAD * buf + ga_o;
 
     // Row loop.  Per x row r: B(r) = {row r shifted by -1, 0, +1}; MFMA groups in the order kh = 2, 1, 0
     // (g rows r-2, r-1, r), so the register slot of g row r-2 is free after the first group and takes g
@@ -557,7 +578,7 @@ __global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf1
     bf16x8 A[3][RBW];
     bf16x8 B0, B1, B2;
     auto read_x = [&](int r) {      // x row r: aligned block + the two edge dwords of the row segment
-      const int off = 16 * T::PR * r;
+      const int off = 16 * T::XU * r;
       blk[r & 1] = *reinterpret_cast<const uint4*>(xb_p + off);
       pe = *reinterpret_cast<const uint32_t*>(pe_p + off);
       ne = *reinterpret_cast<const uint32_t*>(pe_p + off + 16 * (T::XU - 1) - 12);
@@ -615,11 +636,20 @@ __global__ void __launch_bounds__(192 * NRG, 3) bwd_filter_roll_kernel(const bf1
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+
+    if (jump) {
+      __syncthreads();    // three of the four slots are about to be rewritten: everyone must be done with this tile
+      load_plane(n2, -1, th2 * TH, tw2 * T::TW);
+      load_plane(n2, 0, th2 * TH, tw2 * T::TW);
+      load_plane(n2, 1, th2 * TH, tw2 * T::TW);
+    }
+    tw = tw2; th = th2; p = p2; n = n2;
+    buf ^= 1;
   }
 
   // ---- partial tile -> workspace [chunk][cout][cin][27] (+ [chunk][cout] for the bias partial behind it)
   float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
-  const int ci = ci0 + lc;
+  const int ci = ci0 + cib * 16 + lc;
   if (ci < a.cin) {
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb)
@@ -676,7 +706,7 @@ __global__ void __launch_bounds__(256) bfm_reduce_kernel(const float* __restrict
 }
 
 struct BfPlan {
-  int tw, th, rbw, nrg;
+  int tw, th, rbw, nrg, cib;
   bool smallci;
   int tiles_w, tiles_h;
   int64_t ntiles;
@@ -691,14 +721,21 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   p.smallci = x->c <= 5;
   p.rbw = cout <= 16 ? 1 : 2;
   p.nrg = (cout > 32 && !p.smallci) ? 2 : 1;
-  if (roll) { p.tw = 32; p.th = p.nrg == 2 ? 8 : 4; }
+  p.cib = 1;
+  if (roll) {
+    // workgroup = 3 kd x cib channel blocks x nrg row groups of wavefronts; Cout in steps of 16 * rbw * nrg
+    p.tw = 32; p.th = 4;
+    p.rbw = cout > 32 ? 2 : 1;
+    p.nrg = cout > 16 ? 2 : 1;
+    p.cib = x->c > 16 ? 2 : 1;
+  }
   else if (x->w > 32) { p.tw = 64; p.th = 2; }
   else if (x->w > 16) { p.tw = 32; p.th = 4; }
   else { p.tw = 16; p.th = 4; }
   p.tiles_w = (int)cdiv(x->w, p.tw);
   p.tiles_h = (int)cdiv(x->h, p.th);
   p.ntiles = (int64_t)x->n * x->d * p.tiles_h * p.tiles_w;
-  int64_t groups = cdiv(cout, 16 * p.rbw * p.nrg) * cdiv(x->c, 16);
+  int64_t groups = cdiv(cout, 16 * p.rbw * p.nrg) * cdiv(x->c, 16 * p.cib);
   // Number of voxel chunks: enough workgroups to fill 256 CUs several times over, at least 4 tiles
   // per workgroup, and partials (chunks x Cout x Cin x 27 floats) that stay small next to the tensors.
   int64_t per_chunk_bytes = std::max<int64_t>(1, (int64_t)cout * x->c * 27 * 4);
@@ -723,19 +760,20 @@ size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
   return (size_t)nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
 }
 
-template <int RBW, int NRG, int TH>
+template <int RBW, int NRG, int CIB, int TH>
 static h3d_status bf_roll_launch(void* handle, const bf16_t* x, const bf16_t* dz, float* part, const BfmArgs& a, dim3 grid,
                                  hipStream_t stream) {
   using T = RollTile<TH>;
-  constexpr size_t lds_bytes = (size_t)((16 * T::PC + 63) / 64 * 64 + (16 * RBW * NRG * T::PG + 63) / 64 * 64) * 16;
-  auto kern = bwd_filter_roll_kernel<RBW, NRG, TH>;
+  // four plane slots of the x tile and two g buffers
+  constexpr size_t lds_bytes = (size_t)(4 * ((16 * CIB * T::PCI + 63) / 64 * 64) + 2 * ((16 * RBW * NRG * T::PG + 63) / 64 * 64)) * 16;
+  auto kern = bwd_filter_roll_kernel<RBW, NRG, CIB, TH>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return fail(handle, H3D_EHIP, "conv3d_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(192 * NRG), lds_bytes, stream, x, dz, part, a);
+  hipLaunchKernelGGL(kern, grid, dim3(192 * NRG * CIB), lds_bytes, stream, x, dz, part, a);
   return H3D_OK;
 }
 
@@ -800,7 +838,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   a.mask_slope = mask_slope;
   a.dma_ok = dma_ok;
   a.vec_ok = vec_ok;
-  int64_t gy = cdiv(a.cout, 16 * p.rbw * p.nrg), gz = cdiv(a.cin, 16);
+  int64_t gy = cdiv(a.cout, 16 * p.rbw * p.nrg), gz = cdiv(a.cin, 16 * p.cib);
   if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
   if (p.ntiles >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many tiles");
   a.gy = (int)gy; a.gz = (int)gz;
@@ -811,9 +849,15 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
   h3d_status st;
   if (roll) {
-    if (p.nrg == 2) st = bf_roll_launch<2, 2, 8>(handle, xp, gp, (float*)ws, a, grid, stream);
-    else if (p.rbw == 2) st = bf_roll_launch<2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
-    else st = bf_roll_launch<1, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+    if (p.cib == 2) {
+      if (p.rbw == 2) st = bf_roll_launch<2, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else if (p.nrg == 2) st = bf_roll_launch<1, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else st = bf_roll_launch<1, 1, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+    } else {
+      if (p.rbw == 2) st = bf_roll_launch<2, 2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else if (p.nrg == 2) st = bf_roll_launch<1, 2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else st = bf_roll_launch<1, 1, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+    }
   } else {
     st = z ? bf_pick<true>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream)
            : bf_pick<false>(handle, p, xp, gp, zp, (float*)ws, a, grid, stream);
