@@ -724,10 +724,11 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   p.cib = 1;
   if (roll) {
     // workgroup = 3 kd x cib channel blocks x nrg row groups of wavefronts; Cout in steps of 16 * rbw * nrg
-    p.tw = 32; p.th = 4;
+    p.tw = 32;
     p.rbw = cout > 32 ? 2 : 1;
     p.nrg = cout > 16 ? 2 : 1;
     p.cib = x->c > 16 ? 2 : 1;
+    p.th = (p.rbw == 2 && p.cib == 2 && x->h >= 48) ? 6 : 4;
   }
   else if (x->w > 32) { p.tw = 64; p.th = 2; }
   else if (x->w > 16) { p.tw = 32; p.th = 4; }
@@ -850,7 +851,8 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   h3d_status st;
   if (roll) {
     if (p.cib == 2) {
-      if (p.rbw == 2) st = bf_roll_launch<2, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      if (p.rbw == 2 && p.th == 6) st = bf_roll_launch<2, 2, 2, 6>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else if (p.rbw == 2) st = bf_roll_launch<2, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
       else if (p.nrg == 2) st = bf_roll_launch<1, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
       else st = bf_roll_launch<1, 1, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
     } else {

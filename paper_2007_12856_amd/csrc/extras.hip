@@ -337,6 +337,84 @@ __global__ void __launch_bounds__(1024) dense_bwd_dx_kernel(const T* __restrict_
   }
 }
 
+// dx for 16-byte-aligned rows (k a multiple of 16 / sizeof(T)): a block owns 8 lanes' worth of columns
+// (8 x 16 bytes = one 128-byte line per weight row) and walks ALL n rows: a wavefront is 8 rows x 8
+// lanes, 16 wavefronts take 128 rows per step with four steps in flight, so every weight byte is read
+// once, in whole lines, with k / (8 V) blocks in flight.  g = dy (.) act'(y) is staged once in LDS as
+// [j][m].  The 8 x 16 partial sums of a column meet in a fixed order (row lanes by butterfly, then
+// wavefronts in order), so the result does not depend on scheduling.
+template <typename T>
+__global__ void __launch_bounds__(1024) dense_bwd_dx_vec_kernel(const T* __restrict__ w, const T* __restrict__ y,
+                                                                const T* __restrict__ dy, T* __restrict__ dx, DenseArgs a) {
+  constexpr int V = 16 / sizeof(T);
+  struct alignas(16) Pk { T v[V]; };
+  extern __shared__ float g_lds[];      // [n][DM]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  for (int idx = tid; idx < a.n * DM; idx += 1024) {
+    const int j = idx / DM, i = idx % DM;
+    g_lds[idx] = i < a.m ? dense_g(dy, y, (int64_t)i * a.n + j, a) : 0.f;
+  }
+  __syncthreads();
+  const int rl = lane >> 3, cl = lane & 7;
+  const int c0 = (blockIdx.x * 8 + cl) * V;
+  const bool col_ok = c0 < a.k;
+  float acc[DM][V];
+#pragma unroll
+  for (int i = 0; i < DM; ++i)
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[i][e] = 0.f;
+  constexpr int UN = 4;
+  for (int j0 = wave * 8 + rl; j0 < a.n; j0 += 128 * UN) {
+    Pk wv[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int j = j0 + 128 * u;
+      if (j < a.n && col_ok) wv[u] = *reinterpret_cast<const Pk*>(w + (int64_t)j * a.k + c0);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int j = j0 + 128 * u;
+      if (j < a.n && col_ok) {
+        const float4 ga = *reinterpret_cast<const float4*>(g_lds + j * DM), gb = *reinterpret_cast<const float4*>(g_lds + j * DM + 4);
+        const float gv[DM] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float wf = ld(&wv[u].v[e]);
+#pragma unroll
+          for (int i = 0; i < DM; ++i) acc[i][e] = fmaf(gv[i], wf, acc[i][e]);
+        }
+      }
+    }
+  }
+  // rows of the wavefront: butterfly over the row lanes (bits 3..5 of the lane id)
+#pragma unroll
+  for (int i = 0; i < DM; ++i)
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float v = acc[i][e];
+      v += __shfl_xor(v, 8, 64);
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      acc[i][e] = v;
+    }
+  __syncthreads();                       // g_lds is reused for the wavefront partials: [16][DM][8 V]
+  float* red = g_lds;
+  if (rl == 0) {
+#pragma unroll
+    for (int i = 0; i < DM; ++i)
+#pragma unroll
+      for (int e = 0; e < V; ++e) red[(wave * DM + i) * 8 * V + cl * V + e] = acc[i][e];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < a.m * 8 * V; idx += 1024) {
+    const int i = idx / (8 * V), c = idx % (8 * V);
+    float s = 0.f;
+    for (int r = 0; r < 16; ++r) s += red[(r * DM + i) * 8 * V + c];
+    const int col = blockIdx.x * 8 * V + c;
+    if (col < a.k) st(dx + (int64_t)i * a.k + col, s);
+  }
+}
+
 // dw[j][c] = sum_i g[i][j] x[i][c];  db[j] = sum_i g[i][j].  Output-bound (fp32 dw): four columns per
 // thread, 16-byte stores.
 template <typename T>
@@ -525,11 +603,17 @@ extern "C" h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, 
   hipStream_t s = (hipStream_t)stream;
   dim3 gdx((unsigned)cdiv(k, 128)), gdw((unsigned)std::min<int64_t>(cdiv(k, 1024), 64), (unsigned)n);
   if (n > 65535) return fail(handle, H3D_EINVAL, "dense_bwd: n too large");
+  // line-wide dx kernel: whole 16-byte units per row and g (n x 8 floats) within 64 KB of LDS
+  const int vw = dtype == H3D_F32 ? 4 : 8;
+  const size_t dx_lds = std::max<size_t>((size_t)n * DM * sizeof(float), (size_t)16 * DM * 8 * vw * sizeof(float));
+  const bool dx_vec = dx && k % vw == 0 && (uintptr_t)w % 16 == 0 && dx_lds <= 65536;
   if (dtype == H3D_F32) {
-    if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<float>), gdx, dim3(1024), 0, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);
+    if (dx && dx_vec) hipLaunchKernelGGL((dense_bwd_dx_vec_kernel<float>), dim3((unsigned)cdiv(k, 32)), dim3(1024), dx_lds, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);
+    else if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<float>), gdx, dim3(1024), 0, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);
     hipLaunchKernelGGL((dense_bwd_dw_kernel<float>), gdw, dim3(256), 0, s, (const float*)x, (const float*)y, (const float*)dy, dw, db, a);
   } else {
-    if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<bf16_t>), gdx, dim3(1024), 0, s, (const bf16_t*)w, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dx, a);
+    if (dx && dx_vec) hipLaunchKernelGGL((dense_bwd_dx_vec_kernel<bf16_t>), dim3((unsigned)cdiv(k, 64)), dim3(1024), dx_lds, s, (const bf16_t*)w, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dx, a);
+    else if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<bf16_t>), gdx, dim3(1024), 0, s, (const bf16_t*)w, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dx, a);
     hipLaunchKernelGGL((dense_bwd_dw_kernel<bf16_t>), gdw, dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)y, (const bf16_t*)dy, dw, db, a);
   }
   return launch_status(handle, "dense_bwd");
