@@ -677,6 +677,276 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
   }
 }
 
+// Row-rolling kernel for the first layer of a network (Cin <= 4).  One column block holds every
+// (ci, kd) combination (column = 3 ci + kd), so a single wavefront covers all 27 taps: kd through the
+// lane's plane slot, kh through the rolling g rows, kw through the shifted operands.  The NW wavefronts
+// of a workgroup share the staged tile and split its rows into bands of RB (each band reads RB + 2 x
+// rows); their accumulators are added in wavefront order at the end.  Pitches: channel pitch = 1 and
+// slot pitch = 4 (mod 16), so the 16 columns of a block read 16 distinct bank groups.
+template <int TH>
+struct RollSmallTile {
+  static constexpr int TW = 32, XU = 6, GU = 4;
+  static constexpr int PCI = cmod_ge((TH + 2) * XU, 1);
+  static constexpr int NCHX = (4 * PCI + 63) / 64;            // 64-unit copy chunks of one plane (4 channels)
+  static constexpr int SLOTP = cmod_ge(NCHX * 64, 4);
+  static constexpr int PG = (TH * GU) | 1;
+};
+
+template <int RBW, int NW, int RB>
+__global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const bf16_t* __restrict__ x,
+                                                                         const bf16_t* __restrict__ dz,
+                                                                         float* __restrict__ part, BfmArgs a) {
+  constexpr int TH = NW * RB;
+  using T = RollSmallTile<TH>;
+  constexpr int CO_WG = 16 * RBW;
+  constexpr int SLOTP = T::SLOTP, NCHX = T::NCHX;
+  constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64, NCHG = GPAD / 64;
+  constexpr int CXW = (NCHX + NW - 1) / NW, CGW = (NCHG + NW - 1) / NW;
+  extern __shared__ uint4 lds[];
+  uint4* xl = lds;                    // [4 slots][4 ci][TH+2 rows][6 units]  (pitches SLOTP, PCI, XU)
+  uint4* gl = lds + 4 * SLOTP;        // [2 buffers][CO_WG][TH rows][4 units]  (pitches GPAD, PG, GU)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lg = lane >> 4, lc = lane & 15;
+  int chunk, grp;
+  {
+    const int ngrp = a.gy;
+    const int b = blockIdx.x, full = (a.nchunks / 8) * 8 * ngrp;
+    if (b < full) { chunk = (b / (8 * ngrp)) * 8 + b % 8; grp = (b / 8) % ngrp; }
+    else { const int r = b - full, rem = a.nchunks % 8; chunk = (a.nchunks / 8) * 8 + r % rem; grp = r / rem; }
+  }
+  const int co0 = grp * CO_WG;
+  const int W = a.x.w, H = a.x.h, D = a.x.d;
+  const int cil = lc / 3, kdl = lc % 3;
+  const bool col_ok = cil < a.cin;              // columns beyond 3 Cin compute on channel 0 and are dropped
+  const bool edge_lo = lg == 0, edge_hi = lg == 3;
+  const int bp_prev = ((lane - 16) & 63) * 4, bp_next = ((lane + 16) & 63) * 4;
+  const int row0 = wave * RB;                   // this wavefront's band of the tile
+  const int xb_o = 16 * ((col_ok ? cil : 0) * T::PCI + row0 * T::XU + 1 + lg);
+  const int pe_o = 16 * ((col_ok ? cil : 0) * T::PCI + row0 * T::XU) + 12;
+  const int ga_o = 16 * (lc * T::PG + row0 * T::GU + lg);
+
+  int dx_meta[CXW];    // row | u << 8 | ci << 16, -1 = padding or channel out of range
+  int dg_meta[CGW];    // row | u << 8 | co << 16
+#pragma unroll
+  for (int i = 0; i < CXW; ++i) {
+    const int ul = 64 * (wave + NW * i) + lane;
+    const int ci = ul / T::PCI, r1 = ul % T::PCI;
+    const int row = r1 / T::XU, u = r1 % T::XU;
+    const bool ok = wave + NW * i < NCHX && ci < 4 && row < TH + 2 && ci < a.cin;
+    dx_meta[i] = ok ? (row | (u << 8) | (ci << 16)) : -1;
+  }
+#pragma unroll
+  for (int i = 0; i < CGW; ++i) {
+    const int ul = 64 * (wave + NW * i) + lane;
+    const int col = ul / T::PG, r1 = ul % T::PG;
+    const int row = r1 / T::GU, u = r1 % T::GU;
+    const bool ok = wave + NW * i < NCHG && col < CO_WG && row < TH && co0 + col < a.cout;
+    dg_meta[i] = ok ? (row | (u << 8) | ((co0 + col) << 16)) : -1;
+  }
+
+  auto load_plane = [&](int n, int q, int h0, int w0) {
+    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const int64_t gq = a.x.doff + q;
+    const bool plane_ok = gq >= 0 && gq < a.x.dglob;
+    const int t0 = (q + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
+    uint4* dst = xl + ((q + 4) & 3) * SLOTP;
+#pragma unroll
+    for (int i = 0; i < CXW; ++i) {
+      int m = dx_meta[i];
+      asm volatile("" : "+v"(m));     // keeps the unpacked fields from being hoisted into registers of their own
+      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), ci = m >> 16;
+      const int w = w0 + u8 - 8, h = h0 + row - 1;
+      const bool ok = m >= 0 && plane_ok && h >= 0 && h < H && w >= 0 && w + 8 <= W;
+      if (wave + NW * i < NCHX)
+        dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + ci * (int)a.x.cstride + row * W + u8) : BF_OOB);
+    }
+  };
+  auto load_g = [&](int n, int q, int h0, int w0, int buf) {
+    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+    const int t0 = (q + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
+    uint4* dst = gl + buf * GPAD;
+#pragma unroll
+    for (int i = 0; i < CGW; ++i) {
+      int m = dg_meta[i];
+      asm volatile("" : "+v"(m));
+      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), co = m >> 16;
+      const bool ok = m >= 0 && h0 + row < H && w0 + u8 + 8 <= W;
+      if (wave + NW * i < NCHG)
+        dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + co * (int)a.g.cstride + row * W + u8) : BF_OOB);
+    }
+  };
+
+  f32x4 acc[RBW][3][3];   // [row block][kh][kw]
+  f32x4 accdb[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    accdb[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) acc[rb][kh][kw] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
+
+  const int t_begin = chunk * a.tiles_per_chunk;
+  const int t_end = min(t_begin + a.tiles_per_chunk, (int)a.ntiles);
+  int tw, th, p, n;
+  {
+    int r = t_begin;
+    p = r % D; r /= D;
+    tw = r % a.tiles_w; r /= a.tiles_w;
+    th = r % a.tiles_h;
+    n = r / a.tiles_h;
+  }
+  if (t_begin < t_end) {
+    load_plane(n, p - 1, th * TH, tw * T::TW);
+    load_plane(n, p, th * TH, tw * T::TW);
+    load_plane(n, p + 1, th * TH, tw * T::TW);
+    load_g(n, p, th * TH, tw * T::TW, 0);
+  }
+  int buf = 0;
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int tw2 = tw, th2 = th, p2 = p + 1, n2 = n;
+    if (p2 == D) { p2 = 0; ++tw2; }
+    if (tw2 == a.tiles_w) { tw2 = 0; ++th2; }
+    if (th2 == a.tiles_h) { th2 = 0; ++n2; }
+    const bool has_next = tile + 1 < t_end;
+    const bool jump = has_next && p2 == 0;
+    if (has_next) {
+      load_g(n2, p2, th2 * TH, tw2 * T::TW, buf ^ 1);
+      if (!jump) load_plane(n2, p2 + 1, th2 * TH, tw2 * T::TW);
+    }
+
+    const char* xs = reinterpret_cast<const char*>(xl) + 16 * SLOTP * ((p + kdl + 3) & 3);   // this lane's plane p + kd - 1
+    const char* xb_p = xs + xb_o;
+    const char* pe_p = xs + pe_o;
+    const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * GPAD * buf + ga_o;
+
+    uint4 blk[2];
+    uint32_t pe, ne, pv, nx;
+    bf16x8 A[3][RBW];
+    bf16x8 B0, B1, B2;
+    auto read_x = [&](int r) {
+      const int off = 16 * T::XU * r;
+      blk[r & 1] = *reinterpret_cast<const uint4*>(xb_p + off);
+      pe = *reinterpret_cast<const uint32_t*>(pe_p + off);
+      ne = *reinterpret_cast<const uint32_t*>(pe_p + off + 16 * (T::XU - 1) - 12);
+    };
+    auto read_g = [&](int r) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb)
+        A[r % 3][rb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ga_p + 16 * (rb * 16 * T::PG + r * T::GU)));
+    };
+    auto exchange = [&](int r) {
+      pv = __builtin_amdgcn_ds_bpermute(bp_prev, edge_hi ? pe : blk[r & 1].w);
+      nx = __builtin_amdgcn_ds_bpermute(bp_next, edge_lo ? ne : blk[r & 1].x);
+    };
+    auto build_B = [&](int r) {
+      const uint4 b = blk[r & 1];
+      const uint32_t s0 = __builtin_amdgcn_alignbit(b.x, pv, 16);
+      const uint32_t s1 = __builtin_amdgcn_alignbit(b.y, b.x, 16);
+      const uint32_t s2 = __builtin_amdgcn_alignbit(b.z, b.y, 16);
+      const uint32_t s3 = __builtin_amdgcn_alignbit(b.w, b.z, 16);
+      const uint32_t s4 = __builtin_amdgcn_alignbit(nx, b.w, 16);
+      const uint4 f0 = {s0, s1, s2, s3}, f2 = {s1, s2, s3, s4};
+      B0 = __builtin_bit_cast(bf16x8, f0); B1 = __builtin_bit_cast(bf16x8, b); B2 = __builtin_bit_cast(bf16x8, f2);
+    };
+    auto mfma_group = [&](int r, int kh) {
+      const int gr = r - kh;
+      if (gr < 0 || gr >= RB) return;
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        acc[rb][kh][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B0, acc[rb][kh][0], 0, 0, 0);
+        acc[rb][kh][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B1, acc[rb][kh][1], 0, 0, 0);
+        acc[rb][kh][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[gr % 3][rb], B2, acc[rb][kh][2], 0, 0, 0);
+      }
+    };
+    read_x(0);
+    read_g(0);
+    exchange(0);
+#pragma unroll
+    for (int r = 0; r < RB + 2; ++r) {
+      build_B(r);
+      if (r + 1 < RB + 2) read_x(r + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(r, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      if (r + 1 < RB) read_g(r + 1);
+      if (r + 1 < RB + 2) exchange(r + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(r, 1);
+      mfma_group(r, 0);
+      if (r < RB) {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) accdb[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[r % 3][rb], ones, accdb[rb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    if (jump) {
+      __syncthreads();
+      load_plane(n2, -1, th2 * TH, tw2 * T::TW);
+      load_plane(n2, 0, th2 * TH, tw2 * T::TW);
+      load_plane(n2, 1, th2 * TH, tw2 * T::TW);
+    }
+    tw = tw2; th = th2; p = p2; n = n2;
+    buf ^= 1;
+  }
+
+  // add the wavefronts' accumulators in wavefront order (fixed, so the result is reproducible)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  f32x4* red = reinterpret_cast<f32x4*>(lds);     // [NW-1][64] slots, reused for every accumulator
+  auto wave_sum = [&](f32x4& v) {
+    __syncthreads();
+    if (wave > 0) red[(wave - 1) * 64 + lane] = v;
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int wv = 0; wv < NW - 1; ++wv) v = v + red[wv * 64 + lane];
+    }
+  };
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    wave_sum(accdb[rb]);
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) wave_sum(acc[rb][kh][kw]);
+  }
+  if (wave > 0) return;
+
+  float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
+  if (col_ok && lc < 15) {
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + rb * 16 + 4 * lg + rr;
+        if (co < a.cout) {
+          float* o = pw + ((int64_t)co * a.cin + cil) * 27 + kdl * 9;
+#pragma unroll
+          for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) o[kh * 3 + kw] = acc[rb][kh][kw][rr];
+        }
+      }
+  }
+  if (lc == 0) {
+    float* pb = part + (int64_t)a.nchunks * a.cout * a.cin * 27 + (int64_t)chunk * a.cout;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int co = co0 + rb * 16 + 4 * lg + rr;
+        if (co < a.cout) pb[co] = accdb[rb][rr];
+      }
+  }
+}
+
 // Second stage: out[i] = sum over chunks of part[chunk][i] in a FIXED order.  A block takes 16
 // consecutive outputs; 16 thread groups each add every 16th chunk in increasing order, then the 16
 // group sums are added in group order.  (dw and the bias partials share the kernel: the bias
@@ -714,7 +984,7 @@ struct BfPlan {
 };
 
 // The row-rolling kernel takes the wide layers with more than a handful of input channels.
-static bool bf_roll_shape(const h3d_tensor* x) { return x->w >= 32 && x->c > 5; }
+static bool bf_roll_shape(const h3d_tensor* x) { return x->w >= 32 && (x->c > 5 || (x->c <= 4 && x->h >= 16)); }
 
 static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   BfPlan p;
@@ -729,6 +999,12 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
     p.nrg = cout > 16 ? 2 : 1;
     p.cib = x->c > 16 ? 2 : 1;
     p.th = (p.rbw == 2 && p.cib == 2 && x->h >= 48) ? 6 : 4;
+    if (x->c <= 4) {    // first-layer kernel: one wavefront covers all taps, 8 wavefronts split the tile's rows
+      p.smallci = false;
+      p.rbw = cout > 16 ? 2 : 1;
+      p.nrg = 1;
+      p.th = p.rbw == 2 ? 16 : 32;
+    }
   }
   else if (x->w > 32) { p.tw = 64; p.th = 2; }
   else if (x->w > 16) { p.tw = 32; p.th = 4; }
@@ -740,7 +1016,9 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   // Number of voxel chunks: enough workgroups to fill 256 CUs several times over, at least 4 tiles
   // per workgroup, and partials (chunks x Cout x Cin x 27 floats) that stay small next to the tensors.
   int64_t per_chunk_bytes = std::max<int64_t>(1, (int64_t)cout * x->c * 27 * 4);
-  int64_t want = std::max<int64_t>(1, 1024 / groups);
+  // (the first-layer kernel keeps one 8-wavefront workgroup per CU and pays a cross-wavefront reduction per
+  //  workgroup: one round of workgroups)
+  int64_t want = std::max<int64_t>(1, ((roll && x->c <= 4) ? 256 : 1024) / groups);
   want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)48 << 20) / per_chunk_bytes));
   want = std::min<int64_t>(want, std::max<int64_t>(1, p.ntiles / 4));
   p.tiles_per_chunk = (int)std::max<int64_t>(1, cdiv(p.ntiles, want));
@@ -775,6 +1053,22 @@ static h3d_status bf_roll_launch(void* handle, const bf16_t* x, const bf16_t* dz
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(192 * NRG * CIB), lds_bytes, stream, x, dz, part, a);
+  return H3D_OK;
+}
+
+template <int RBW, int NW, int RB>
+static h3d_status bf_roll_small_launch(void* handle, const bf16_t* x, const bf16_t* dz, float* part, const BfmArgs& a, dim3 grid,
+                                       hipStream_t stream) {
+  using T = RollSmallTile<NW * RB>;
+  constexpr size_t lds_bytes = (size_t)(4 * T::SLOTP + 2 * ((16 * RBW * T::PG + 63) / 64 * 64)) * 16;
+  auto kern = bwd_filter_roll_small_kernel<RBW, NW, RB>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds_bytes, stream, x, dz, part, a);
   return H3D_OK;
 }
 
@@ -849,7 +1143,10 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   const bf16_t* gp = (const bf16_t*)dz->data;
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
   h3d_status st;
-  if (roll) {
+  if (roll && x->c <= 4) {
+    if (p.rbw == 2) st = bf_roll_small_launch<2, 8, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else st = bf_roll_small_launch<1, 8, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+  } else if (roll) {
     if (p.cib == 2) {
       if (p.rbw == 2 && p.th == 6) st = bf_roll_launch<2, 2, 2, 6>(handle, xp, gp, (float*)ws, a, grid, stream);
       else if (p.rbw == 2) st = bf_roll_launch<2, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);

@@ -82,6 +82,44 @@ def test_conv3d_no_bias_and_other_activations(dtype, act):
     assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
 
 
+# (N, Cin, Cout, D, H, W, halo): unmasked filter gradients (the activation's mask already applied upstream), shapes
+# chosen to reach every workgroup layout of the matrix-core kernels: first-layer (Cin <= 4) with one and two
+# row blocks, 16- and 32-channel workgroups, one and two row groups, 4- and 6-row tiles, ragged H / W / channels
+BF_SHAPES = [
+    (1, 4, 16, 3, 36, 40, 1),
+    (2, 3, 24, 2, 20, 64, 0),
+    (1, 1, 40, 3, 33, 32, 1),
+    (1, 16, 32, 3, 12, 40, 1),
+    (1, 12, 16, 2, 9, 32, 0),
+    (1, 32, 64, 3, 50, 32, 1),
+    (1, 48, 80, 2, 10, 72, 1),
+    (1, 20, 16, 2, 8, 96, 0),
+    (1, 24, 24, 5, 7, 33, 1),
+]
+
+
+@pytest.mark.parametrize("shape", BF_SHAPES)
+def test_conv3d_bwd_filter_unmasked_bf16(shape):
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, D, H, W, halo = shape
+    dtype = "bf16"
+    # with halo: the middle slab of a volume two planes taller (the halo planes hold real neighbours);
+    # without: the whole volume, zero beyond both ends
+    Dg, off = (D + 2, 1) if halo else (D, 0)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 30, (N, Ci, D + 2 * halo, H, W)), dtype, (halo, halo), off, Dg)
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 31, (N, Co, D, H, W)), dtype, (0, 0), off, Dg)
+    dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, None, act=orc.ACT_NONE)
+    dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
+    db = torch.full((Co,), 777.0, device="cuda")
+    h3d.conv3d_bwd_filter(xg, dzg, None, dw, db, h3d.ACT_NONE, 0.0)
+    assert rel_l2(from_dev(dw), dwo) <= 2e-4
+    assert rel_l2(from_dev(db), dbo) <= 2e-4
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    h3d.conv3d_bwd_filter(xg, dzg, None, dw2, db2, h3d.ACT_NONE, 0.0)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("cin,cout", [(4, 16), (3, 5), (16, 32)])
 def test_conv3d_sharded_matches_oracle_and_unsharded_gpu(dtype, cin, cout):
