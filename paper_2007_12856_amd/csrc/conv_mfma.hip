@@ -436,6 +436,10 @@ static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mas
                 : launch_variant<1, 8, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
 }
 
+bool conv3d_thin_supported(const h3d_tensor* in, const h3d_tensor* out);
+h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, bool transpose,
+                       float out_slope, void* ws, hipStream_t stream);
+
 h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
                        h3d_tensor* out, bool transpose, float out_slope, float mask_slope, void* ws, size_t ws_bytes,
                        hipStream_t stream) {
@@ -449,6 +453,8 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   if ((int64_t)out->n * a.out.ds * out->h * out->w == 0) return H3D_OK;
   if (!ws || ws_bytes < mfma_fwd_ws_bytes(in, out)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace must be 16-byte aligned");
+  // a handful of output channels from at most 16 input channels: the tap-row-folding kernel
+  if (!mask && conv3d_thin_supported(in, out)) return conv3d_thin(handle, in, w, bias, out, transpose, out_slope, ws, stream);
   const bool vec = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && ((uintptr_t)out->data % 4 == 0) &&
                    (!mask || (uintptr_t)mask->data % 4 == 0);
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;

@@ -1,0 +1,229 @@
+// 3x3x3 convolution with very few OUTPUT channels (at most 8) and at most 16 input channels, bf16 on the
+// matrix cores: the backward-data pass of a network's first layer (Sec. III-C "BD": dx of a 4-channel
+// input from a 16-channel g), or a forward pass onto a handful of channels.
+//
+// With so few output channels the 32 rows of v_mfma_f32_32x32x16_bf16 would be almost empty, so the kh
+// taps are folded into them: row 8 kh + m of the A operand holds the weights of output channel m under
+// tap row kh.  One MFMA per (kd, kw) on an INPUT row then yields that row's contribution to three output
+// rows at once; the accumulator slides down one tap row per input row (kh = 0 -> 1 -> 2) and the kh = 2
+// quarter leaves as a finished output row.  9 MFMAs per input row instead of 27 per output row, and the
+// nine weight fragments stay in registers for the whole workgroup.
+//   * accumulator layout: lanes 0..31 hold rows 0-3, 8-11, 16-19 (kh = 0,1,2 of channels 0..3), lanes 32..63
+//     rows 4-7, 12-15, 20-23 (channels 4..7): the slide is a register move, no cross-lane traffic;
+//   * the input tile is transposed into LDS as 16-byte units of 8 channels, [ci-group][plane][row][w], as
+//     in the general kernel, so the B operand of tap (kd, kw) is one ds_read_b128 per lane;
+//   * a workgroup = 4 wavefronts = 4 output planes x 4 rows x 64 columns (two MFMA column blocks per
+//     wavefront: two independent accumulator chains).
+#include <algorithm>
+
+#include "common.h"
+
+namespace h3d {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int T_TD = 4, T_TH = 4, T_TW = 64;
+constexpr int T_P = 68;                                   // LDS row pitch in units: w in [w0-2, w0+66)
+constexpr int T_PAIRS = T_P / 2;
+constexpr int T_CIG_UNITS = (T_TD + 2) * (T_TH + 2) * T_P;
+constexpr int T_ITEMS = 2 * (T_TD + 2) * (T_TH + 2) * T_PAIRS;
+constexpr int T_THREADS = 256;
+constexpr int T_ROUNDS = (T_ITEMS + T_THREADS - 1) / T_THREADS;
+constexpr int T_OOB = (int)0x80000000;
+
+struct ThinArgs {
+  Geo in, out;
+  int cin_k, cout_k;
+  int tiles_w, tiles_h, tiles_d;
+  float out_slope;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t thin_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                           (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+// wp: [step = kd*3+kw][lane][8] bf16; lane l, element e: row 8 kh + m = l % 32 (kh < 3), input channel 8 (l/32) + e
+__global__ void pack_w_thin_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int cin, int cout, int transpose) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 9 * 512) return;
+  const int e = i & 7, lane = (i >> 3) & 63, step = i >> 9;
+  const int kd = step / 3, kw = step % 3;
+  const int row = lane & 31, kh = row >> 3, m = row & 7, c = (lane >> 5) * 8 + e;
+  const int cin_k = transpose ? cout : cin, cout_k = transpose ? cin : cout;
+  bf16_t v = 0;
+  if (kh < 3 && m < cout_k && c < cin_k) {
+    const int tap = kd * 9 + kh * 3 + kw;
+    v = transpose ? w[((int64_t)c * cin + m) * 27 + (26 - tap)] : w[((int64_t)m * cin + c) * 27 + tap];
+  }
+  wp[i] = v;
+}
+
+__global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
+                                                                   const float* __restrict__ bias, bf16_t* __restrict__ out,
+                                                                   ThinArgs a) {
+  extern __shared__ uint4 lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wd = tid >> 6;
+  const int W = a.in.w, H = a.in.h;
+  int t = blockIdx.x;
+  const int tw = t % a.tiles_w; t /= a.tiles_w;
+  const int th = t % a.tiles_h; t /= a.tiles_h;
+  const int td = t % a.tiles_d;
+  const int n = t / a.tiles_d;
+  const int w0 = tw * T_TW, h0 = th * T_TH, ps0 = td * T_TD;
+
+  // ---- weights: nine fragments, resident in registers
+  bf16x8 A[9];
+#pragma unroll
+  for (int s = 0; s < 9; ++s) A[s] = __builtin_bit_cast(bf16x8, wp[s * 64 + lane]);
+
+  // ---- input tile -> LDS, transposed to units of 8 channels.  An item = (ci-group, plane, row, pair of
+  //      columns): 8 dword loads (one per channel, two voxels each), 8 byte-permutes, two 16-byte LDS stores.
+  {
+    const __amdgpu_buffer_rsrc_t rs_in = thin_rsrc(in + n * a.in.nstride, (uint32_t)a.in.nstride * 2);
+    constexpr int HALF = (T_ROUNDS + 1) / 2;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      uint32_t v[HALF][8];
+      int unit[HALF];
+#pragma unroll
+      for (int rr = 0; rr < HALF; ++rr) {
+        const int r = half * HALF + rr;
+        const int item = tid + r * T_THREADS;
+        const int pair = item % T_PAIRS;
+        int q = item / T_PAIRS;
+        const int hy = q % (T_TH + 2); q /= (T_TH + 2);
+        const int dz = q % (T_TD + 2);
+        const int cig = q / (T_TD + 2);
+        const bool item_ok = r < T_ROUNDS && item < T_ITEMS;
+        unit[rr] = item_ok ? (cig * (T_TD + 2) + dz) * ((T_TH + 2) * T_P) + hy * T_P + 2 * pair : -1;
+        const int p_in = ps0 - a.out.hlo + dz - 1;        // local interior index of the input plane
+        const int64_t gq = a.in.doff + p_in;
+        const int sp = p_in + a.in.hlo;
+        const int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
+        const bool ok = item_ok && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H && w >= 0 && w + 1 < W;
+        const int base = 2 * (cig * 8 * (int)a.in.cstride + sp * (int)a.in.plane + h * W + w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const bool chan_ok = cig * 8 + e < a.cin_k;
+          v[rr][e] = __builtin_amdgcn_raw_buffer_load_b32(rs_in, (ok && chan_ok) ? base : T_OOB,
+                                                         __builtin_amdgcn_readfirstlane(2 * e * (int)a.in.cstride), 0);
+        }
+      }
+#pragma unroll
+      for (int rr = 0; rr < HALF; ++rr) {
+        if (unit[rr] < 0) continue;
+        const uint32_t* g = v[rr];
+        uint4 u0, u1;   // unit of w (low halves) and of w+1 (high halves): 8 channels each
+        u0.x = __builtin_amdgcn_perm(g[1], g[0], 0x05040100); u1.x = __builtin_amdgcn_perm(g[1], g[0], 0x07060302);
+        u0.y = __builtin_amdgcn_perm(g[3], g[2], 0x05040100); u1.y = __builtin_amdgcn_perm(g[3], g[2], 0x07060302);
+        u0.z = __builtin_amdgcn_perm(g[5], g[4], 0x05040100); u1.z = __builtin_amdgcn_perm(g[5], g[4], 0x07060302);
+        u0.w = __builtin_amdgcn_perm(g[7], g[6], 0x05040100); u1.w = __builtin_amdgcn_perm(g[7], g[6], 0x07060302);
+        lds[unit[rr]] = u0;
+        lds[unit[rr] + 1] = u1;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- this wavefront: output plane ps0 + wd, rows h0 .. h0+3, columns w0 .. w0+63
+  const int ps = ps0 + wd;
+  const int half = lane >> 5, col = lane & 31;
+  const bool plane_stored = ps < a.out.ds;
+  const int64_t gp = a.out.doff + ps - a.out.hlo;
+  const bool inside = gp >= 0 && gp < a.out.dglob;          // planes outside the global volume are written as zeros
+  const __amdgpu_buffer_rsrc_t rs_out = thin_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
+  float bv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) bv[i] = (bias && 4 * half + i < a.cout_k) ? bias[4 * half + i] : 0.f;
+
+  const uint4* base = lds + half * T_CIG_UNITS + wd * ((T_TH + 2) * T_P) + col + 1;
+  f32x16 acc[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+#pragma unroll
+  for (int hi = 0; hi < T_TH + 2; ++hi) {
+    // slide: what was accumulated under tap row kh now waits for tap row kh + 1 of the next input row
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[cb][8 + i] = acc[cb][4 + i];
+        acc[cb][4 + i] = acc[cb][i];
+        acc[cb][i] = 0.f;
+      }
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const bf16x8 B = __builtin_bit_cast(bf16x8, base[(kd * (T_TH + 2) + hi) * T_P + cb * 32 + kw]);
+          acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[kd * 3 + kw], B, acc[cb], 0, 0, 0);
+        }
+    if (hi >= 2 && plane_stored) {
+      const int h = h0 + hi - 2;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const int w = w0 + cb * 32 + col;
+        const int vo = (h < H && w < W) ? 2 * (4 * half * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : T_OOB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float val = acc[cb][8 + i] + bv[i];
+          if (!(val > 0.f)) val *= a.out_slope;
+          const bool ch_ok = 4 * half + i < a.cout_k;
+          __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(inside ? val : 0.f), rs_out, ch_ok ? vo : T_OOB,
+                                                __builtin_amdgcn_readfirstlane(2 * i * (int)a.out.cstride), 0);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool conv3d_thin_supported(const h3d_tensor* in, const h3d_tensor* out) {
+  return in->dtype == H3D_BF16 && in->c >= 1 && in->c <= 16 && out->c >= 1 && out->c <= 8 && out->w >= 32 && in->w % 2 == 0 &&
+         (uintptr_t)in->data % 4 == 0;
+}
+
+// Caller guarantees conv3d_thin_supported(), 31-bit in-sample byte offsets and a 16-byte-aligned workspace
+// of at least 9 KB.
+h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, bool transpose,
+                       float out_slope, void* ws, hipStream_t stream) {
+  ThinArgs a;
+  a.in = make_geo(in);
+  a.out = make_geo(out);
+  a.cin_k = in->c; a.cout_k = out->c;
+  a.out_slope = out_slope;
+  a.tiles_w = (int)cdiv(out->w, T_TW);
+  a.tiles_h = (int)cdiv(out->h, T_TH);
+  a.tiles_d = (int)cdiv(a.out.ds, T_TD);
+  const int64_t ntiles = (int64_t)out->n * a.tiles_d * a.tiles_h * a.tiles_w;
+  if (ntiles == 0) return H3D_OK;
+  if (ntiles >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
+  hipLaunchKernelGGL(pack_w_thin_kernel, dim3(18), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin, cout, transpose ? 1 : 0);
+  constexpr size_t lds_bytes = (size_t)2 * T_CIG_UNITS * 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(conv3d_thin_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(conv3d_thin_kernel, dim3((unsigned)ntiles), dim3(T_THREADS), lds_bytes, stream, (const bf16_t*)in->data,
+                     (const uint4*)ws, bias, (bf16_t*)out->data, a);
+  return launch_status(handle, "conv3d_thin");
+}
+
+}  // namespace h3d

@@ -120,6 +120,36 @@ def test_conv3d_bwd_filter_unmasked_bf16(shape):
     assert torch.equal(dw, dw2) and torch.equal(db, db2)
 
 
+# (N, Cin, Cout, D, H, W, halo): layers with a handful of channels on one side and at most 16 on the other, wide
+# enough for the tap-row-folding kernel: backward-data onto <= 8 channels (no fused mask), forward onto <= 8
+THIN_SHAPES = [
+    (1, 4, 16, 5, 9, 40, 1),
+    (2, 3, 12, 3, 6, 66, 0),
+    (1, 8, 16, 6, 10, 32, 1),
+    (1, 1, 7, 2, 5, 130, 0),
+]
+
+
+@pytest.mark.parametrize("shape", THIN_SHAPES)
+def test_conv3d_few_channels_bf16(shape):
+    import paper_2007_12856_amd as h3d
+    N, Cs, Cl, D, H, W, halo = shape      # Cs: the small channel count, Cl: the larger one
+    dtype = "bf16"
+    Dg, off = (D + 2, 1) if halo else (D, 0)
+    # backward-data of a Cs -> Cl layer: dz has Cl channels and a halo, dx has Cs channels
+    w, bias = _weights(Cs, Cl, dtype, 40)
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 41, (N, Cl, D + 2 * halo, H, W)), dtype, (halo, halo), off, Dg)
+    dxo = orc.conv3d_bwd_data(dzo, None, w, act=orc.ACT_NONE)
+    dxg = h3d.conv3d_bwd_data(dzg, None, to_dev(w, dtype), dev_like(dxo, dtype), h3d.ACT_NONE, 0.0)
+    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    # forward of a Cl -> Cs layer with bias and leaky ReLU
+    w2, bias2 = _weights(Cl, Cs, dtype, 42)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 43, (N, Cl, D + 2 * halo, H, W)), dtype, (halo, halo), off, Dg)
+    zo = orc.conv3d_fwd(xo, w2, bias2, act=orc.ACT_LEAKY, alpha=0.01)
+    zg = h3d.conv3d_fwd(xg, to_dev(w2, dtype), to_dev(bias2, "f32"), dev_like(zo, dtype), h3d.ACT_LEAKY, 0.01)
+    assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("cin,cout", [(4, 16), (3, 5), (16, 32)])
 def test_conv3d_sharded_matches_oracle_and_unsharded_gpu(dtype, cin, cout):
