@@ -27,8 +27,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int T_TD = 4, T_TH = 4, T_TW = 64;
-constexpr int T_P = 68;                                   // LDS row pitch in units: w in [w0-2, w0+66)
-constexpr int T_PAIRS = T_P / 2;
+constexpr int T_NU = 68;                                  // units of a row: unit u holds column w0 - 2 + u; 1..66 are used
+// A row is stored as 8 interleaved sub-rows: unit u sits at t_pos(u + 1) = ((u + 1) % 8) * 9 + (u + 1) / 8.  The
+// staging threads, which own whole groups of 8 columns, then write consecutive positions (no bank conflicts:
+// lanes run over the column groups of a row, then over planes, whose pitch 6 * 71 = 10 (mod 16) continues the
+// sequence), and the 16 lanes of a ds_read_b128 pass, which want consecutive units starting at u + 1 = 2..4
+// (mod 8), still hit 16 distinct bank groups.  71 positions per row: two workgroups fill the CU's 160 KB exactly.
+constexpr int T_P = 71;
+__host__ __device__ constexpr int t_pos(int v) { return (v & 7) * 9 + (v >> 3); }
+constexpr int T_PAIRS = T_NU / 2;
 constexpr int T_CIG_UNITS = (T_TD + 2) * (T_TH + 2) * T_P;
 constexpr int T_ITEMS = 2 * (T_TD + 2) * (T_TH + 2) * T_PAIRS;
 constexpr int T_THREADS = 256;
@@ -65,13 +72,17 @@ __global__ void pack_w_thin_kernel(const bf16_t* __restrict__ w, bf16_t* __restr
   wp[i] = v;
 }
 
+template <bool VEC8>
 __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
                                                                    const float* __restrict__ bias, bf16_t* __restrict__ out,
                                                                    ThinArgs a) {
   extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63, wd = tid >> 6;
   const int W = a.in.w, H = a.in.h;
-  int t = blockIdx.x;
+  // consecutive workgroup ids go to different XCDs (each with its own L2): hand every XCD a contiguous run
+  // of tiles, so that tiles sharing halo rows and planes meet in one L2
+  const int G = gridDim.x;
+  int t = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
   const int tw = t % a.tiles_w; t /= a.tiles_w;
   const int th = t % a.tiles_h; t /= a.tiles_h;
   const int td = t % a.tiles_d;
@@ -83,15 +94,70 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
 #pragma unroll
   for (int s = 0; s < 9; ++s) A[s] = __builtin_bit_cast(bf16x8, wp[s * 64 + lane]);
 
-  // ---- input tile -> LDS, transposed to units of 8 channels.  An item = (ci-group, plane, row, pair of
-  //      columns): 8 dword loads (one per channel, two voxels each), 8 byte-permutes, two 16-byte LDS stores.
-  {
+  // ---- input tile -> LDS, transposed to units of 8 channels.
+  if (VEC8) {
+    // An item = (ci-group, plane, row, group of 8 columns): 8 loads of 16 bytes (one per channel), an 8 x 8
+    // transpose by byte-permutes, up to eight 16-byte LDS stores.  Groups 0 and 9 only contribute the two
+    // columns next to the tile (w0-2, w0-1 and w0+64, w0+65).
+    const __amdgpu_buffer_rsrc_t rs_in = thin_rsrc(in + n * a.in.nstride, (uint32_t)a.in.nstride * 2);
+    constexpr int NG = T_TW / 8 + 2;
+    constexpr int ITEMS8 = 2 * (T_TD + 2) * (T_TH + 2) * NG;
+    constexpr int ROUNDS8 = (ITEMS8 + T_THREADS - 1) / T_THREADS;
+    // every load of the tile is issued before the first transpose, so one memory latency covers them all
+    u32x4 v[ROUNDS8][8];
+#pragma unroll
+    for (int r = 0; r < ROUNDS8; ++r) {
+      const int item = tid + r * T_THREADS;
+      const int grp = item % NG;
+      int q = item / NG;
+      const int dz = q % (T_TD + 2); q /= (T_TD + 2);
+      const int hy = q % (T_TH + 2);
+      const int cig = q / (T_TH + 2);
+      const int p_in = ps0 - a.out.hlo + dz - 1;
+      const int64_t gq = a.in.doff + p_in;
+      const int sp = p_in + a.in.hlo;
+      const int h = h0 + hy - 1, w = w0 - 8 + 8 * grp;
+      const bool ok = item < ITEMS8 && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H && w >= 0 && w + 8 <= W;
+      const int base = 2 * (cig * 8 * (int)a.in.cstride + sp * (int)a.in.plane + h * W + w);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const bool chan_ok = cig * 8 + e < a.cin_k;
+        v[r][e] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (ok && chan_ok) ? base : T_OOB,
+                                                        __builtin_amdgcn_readfirstlane(2 * e * (int)a.in.cstride), 0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < ROUNDS8; ++r) {
+      const int item = tid + r * T_THREADS;
+      if (item >= ITEMS8) continue;
+      const int grp = item % NG;
+      int q = item / NG;
+      const int dz = q % (T_TD + 2); q /= (T_TD + 2);
+      const int hy = q % (T_TH + 2);
+      const int cig = q / (T_TH + 2);
+      // this group's column c is unit u = 8 grp - 6 + c, and u + 1 = 8 (grp - 1) + (c + 3)
+      uint4* dst = lds + (cig * (T_TD + 2) + dz) * ((T_TH + 2) * T_P) + hy * T_P + grp - 1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {       // dword j of each channel = columns 2j, 2j+1 of the group
+        uint4 u0, u1;
+        u0.x = __builtin_amdgcn_perm(v[r][1][j], v[r][0][j], 0x05040100); u1.x = __builtin_amdgcn_perm(v[r][1][j], v[r][0][j], 0x07060302);
+        u0.y = __builtin_amdgcn_perm(v[r][3][j], v[r][2][j], 0x05040100); u1.y = __builtin_amdgcn_perm(v[r][3][j], v[r][2][j], 0x07060302);
+        u0.z = __builtin_amdgcn_perm(v[r][5][j], v[r][4][j], 0x05040100); u1.z = __builtin_amdgcn_perm(v[r][5][j], v[r][4][j], 0x07060302);
+        u0.w = __builtin_amdgcn_perm(v[r][7][j], v[r][6][j], 0x05040100); u1.w = __builtin_amdgcn_perm(v[r][7][j], v[r][6][j], 0x07060302);
+        const int u = 8 * grp - 6 + 2 * j;
+        if (u >= 1 && u <= T_NU - 2) dst[t_pos(2 * j + 3)] = u0;
+        if (u + 1 >= 1 && u + 1 <= T_NU - 2) dst[t_pos(2 * j + 4)] = u1;
+      }
+    }
+  } else {
+    // An item = (ci-group, plane, row, pair of columns): 8 dword loads (one per channel, two voxels each),
+    // 8 byte-permutes, two 16-byte LDS stores.
     const __amdgpu_buffer_rsrc_t rs_in = thin_rsrc(in + n * a.in.nstride, (uint32_t)a.in.nstride * 2);
     constexpr int HALF = (T_ROUNDS + 1) / 2;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       uint32_t v[HALF][8];
-      int unit[HALF];
+      int unit[HALF], upair[HALF];   // LDS row base and first unit of the pair
 #pragma unroll
       for (int rr = 0; rr < HALF; ++rr) {
         const int r = half * HALF + rr;
@@ -102,7 +168,8 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
         const int dz = q % (T_TD + 2);
         const int cig = q / (T_TD + 2);
         const bool item_ok = r < T_ROUNDS && item < T_ITEMS;
-        unit[rr] = item_ok ? (cig * (T_TD + 2) + dz) * ((T_TH + 2) * T_P) + hy * T_P + 2 * pair : -1;
+        unit[rr] = item_ok ? (cig * (T_TD + 2) + dz) * ((T_TH + 2) * T_P) + hy * T_P : -1;
+        upair[rr] = 2 * pair;
         const int p_in = ps0 - a.out.hlo + dz - 1;        // local interior index of the input plane
         const int64_t gq = a.in.doff + p_in;
         const int sp = p_in + a.in.hlo;
@@ -125,8 +192,8 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
         u0.y = __builtin_amdgcn_perm(g[3], g[2], 0x05040100); u1.y = __builtin_amdgcn_perm(g[3], g[2], 0x07060302);
         u0.z = __builtin_amdgcn_perm(g[5], g[4], 0x05040100); u1.z = __builtin_amdgcn_perm(g[5], g[4], 0x07060302);
         u0.w = __builtin_amdgcn_perm(g[7], g[6], 0x05040100); u1.w = __builtin_amdgcn_perm(g[7], g[6], 0x07060302);
-        lds[unit[rr]] = u0;
-        lds[unit[rr] + 1] = u1;
+        if (upair[rr] >= 1) lds[unit[rr] + t_pos(upair[rr] + 1)] = u0;
+        if (upair[rr] + 1 <= T_NU - 2) lds[unit[rr] + t_pos(upair[rr] + 2)] = u1;
       }
     }
   }
@@ -143,13 +210,27 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
 #pragma unroll
   for (int i = 0; i < 4; ++i) bv[i] = (bias && 4 * half + i < a.cout_k) ? bias[4 * half + i] : 0.f;
 
-  const uint4* base = lds + half * T_CIG_UNITS + wd * ((T_TH + 2) * T_P) + col + 1;
+  const uint4* base = lds + half * T_CIG_UNITS + wd * ((T_TH + 2) * T_P);
+  int lane_pos[3];      // position of unit u = col + 1 + kw inside a row (column block 1 lies 4 positions on)
+#pragma unroll
+  for (int kw = 0; kw < 3; ++kw) lane_pos[kw] = t_pos(col + 2 + kw);
   f32x16 acc[2];
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
+  // B fragments are read two (kd, kw) steps ahead of the MFMAs that use them
+  constexpr int NSTEP = (T_TH + 2) * 9;
+  auto frag = [&](int step, int cb) {
+    const int hi = step / 9, kd = (step % 9) / 3, kw = step % 3;
+    return base[(kd * (T_TH + 2) + hi) * T_P + cb * 4 + lane_pos[kw]];
+  };
+  uint4 bq[3][2];
+#pragma unroll
+  for (int s0 = 0; s0 < 2; ++s0)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) bq[s0][cb] = frag(s0, cb);
 #pragma unroll
   for (int hi = 0; hi < T_TH + 2; ++hi) {
     // slide: what was accumulated under tap row kh now waits for tap row kh + 1 of the next input row
@@ -162,14 +243,18 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
         acc[cb][i] = 0.f;
       }
 #pragma unroll
-    for (int kd = 0; kd < 3; ++kd)
+    for (int k9 = 0; k9 < 9; ++k9) {
+      const int step = hi * 9 + k9;
+      if (step + 2 < NSTEP) {
 #pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
+        for (int cb = 0; cb < 2; ++cb) bq[(step + 2) % 3][cb] = frag(step + 2, cb);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const bf16x8 B = __builtin_bit_cast(bf16x8, base[(kd * (T_TH + 2) + hi) * T_P + cb * 32 + kw]);
-          acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[kd * 3 + kw], B, acc[cb], 0, 0, 0);
-        }
+      for (int cb = 0; cb < 2; ++cb)
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[k9], __builtin_bit_cast(bf16x8, bq[step % 3][cb]), acc[cb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (hi >= 2 && plane_stored) {
       const int h = h0 + hi - 2;
 #pragma unroll
@@ -214,15 +299,18 @@ h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const 
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
   hipLaunchKernelGGL(pack_w_thin_kernel, dim3(18), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin, cout, transpose ? 1 : 0);
   constexpr size_t lds_bytes = (size_t)2 * T_CIG_UNITS * 16;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(conv3d_thin_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
+  // whole 16-byte column groups: faster staging (a quarter of the load instructions)
+  const bool vec8 = in->w % 8 == 0 && (uintptr_t)in->data % 16 == 0;
+  auto kern = vec8 ? conv3d_thin_kernel<true> : conv3d_thin_kernel<false>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[vec8]) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
+        hipSuccess)
       return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
-    attr_set = true;
+    attr_set[vec8] = true;
   }
-  hipLaunchKernelGGL(conv3d_thin_kernel, dim3((unsigned)ntiles), dim3(T_THREADS), lds_bytes, stream, (const bf16_t*)in->data,
-                     (const uint4*)ws, bias, (bf16_t*)out->data, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(T_THREADS), lds_bytes, stream, (const bf16_t*)in->data, (const uint4*)ws,
+                     bias, (bf16_t*)out->data, a);
   return launch_status(handle, "conv3d_thin");
 }
 
