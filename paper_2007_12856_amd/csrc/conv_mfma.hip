@@ -56,6 +56,10 @@ struct MfmaArgs {
   int cin_k, cout_k, nchunks, ncoblk;
   int tiles_w, tiles_h, tiles_d, ntiles;
   float out_slope, mask_slope;
+  // split of the input-channel chunks over blockIdx.z (small volumes with many channels would otherwise
+  // occupy a handful of CUs): each split writes fp32 partial sums, a second kernel adds them in order
+  int csplit, chunks_per_split;
+  float* part;      // [csplit][n][cout][stored planes][h][w], used when csplit > 1
 };
 
 __device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t m, float slope) {
@@ -81,7 +85,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // VEC: rows start 4-byte aligned and W is even, so a pair of bf16 is one dword load (the normal case);
 // otherwise the two elements of a pair are fetched by two 2-byte loads with their own validity.
-template <int NCB, int ND, int TWC, bool MASKED, bool VEC>
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT>
 __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ mask,
                                                                  const uint4* __restrict__ wp, const float* __restrict__ bias,
                                                                  bf16_t* __restrict__ out, MfmaArgs a) {
@@ -296,8 +300,22 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     if (!wave_active || ps >= a.out.ds) return;
     const int64_t gp = a.out.doff + ps - a.out.hlo;
     const bool inside = gp >= 0 && gp < a.out.dglob;
-    const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
     const int row_ch = 4 * (lane >> 5);   // this lane's accumulator rows are channels 8*(r/4) + row_ch + r%4 of the block
+    if (SPLIT) {
+      float* pp = a.part + ((int64_t)blockIdx.z * a.out.n + n) * a.out.nstride + (int64_t)ps * a.out.plane;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
+        if (h >= H || w >= W) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int co = co_blk * 32 + 8 * (r / 4) + row_ch + (r % 4);
+          if (co < a.cout_k) pp[(int64_t)co * a.out.cstride + h * W + w] = acc[b][r];
+        }
+      }
+      return;
+    }
+    const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
     if (VEC) {
       // Two adjacent voxels live in adjacent lanes.  Lane pairs swap one value (DPP quad_perm [1,0,3,2])
       // so that the even lane holds both voxels of channel row r and the odd lane both voxels of row
@@ -348,19 +366,21 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   const int G = gridDim.x;
   int tile = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
   if (tile >= a.ntiles) return;
+  const int c_begin = SPLIT ? blockIdx.z * a.chunks_per_split : 0;
+  const int c_end = SPLIT ? min(a.nchunks, c_begin + a.chunks_per_split) : a.nchunks;
   plan_tile(tile);
-  load_chunk(0, true);
+  load_chunk(c_begin, true);
   store_chunk(0);
   __syncthreads();
   int buf = 0;
   while (true) {
-    for (int c = 0; c < a.nchunks; ++c) {
-      const bool last_chunk = c + 1 == a.nchunks;
+    for (int c = c_begin; c < c_end; ++c) {
+      const bool last_chunk = c + 1 == c_end;
       const int next_tile = tile + G;
       const bool more = !last_chunk || next_tile < a.ntiles;
       auto issue_next = [&]() {
         if (last_chunk && more) plan_tile(next_tile);
-        load_chunk(last_chunk ? 0 : c + 1, more);
+        load_chunk(last_chunk ? c_begin : c + 1, more);
       };
       if (wave_active) compute_chunk(c, buf, issue_next);
       else issue_next();
@@ -373,6 +393,36 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     tile += G;
     if (tile >= a.ntiles) break;
   }
+}
+
+// out = act(bias + sum over splits of part[split]) in split order; planes outside the global volume are zero
+__global__ void __launch_bounds__(256) conv_split_reduce_kernel(const float* __restrict__ part, const float* __restrict__ bias,
+                                                                bf16_t* __restrict__ out, Geo g, int splits, float slope) {
+  const int64_t total = (int64_t)g.n * g.nstride;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  float s = 0.f;
+  for (int sp = 0; sp < splits; ++sp) s += part[sp * total + i];
+  const int co = (int)((i / g.cstride) % g.c), ps = (int)((i / g.plane) % g.ds);
+  const int64_t gp = g.doff + ps - g.hlo;
+  float v = s + (bias ? bias[co] : 0.f);
+  if (!(v > 0.f)) v *= slope;
+  out[i] = f32_to_bf16((gp >= 0 && gp < g.dglob) ? v : 0.f);
+}
+
+// How many ways the input-channel chunks are split: 1 unless the tiles alone would leave most CUs idle.
+static int mfma_splits(const h3d_tensor* in, const h3d_tensor* out) {
+  const int nchunks = (int)cdiv(in->c, CI_CHUNK), ncoblk = (int)cdiv(out->c, 32);
+  const bool wide = out->w > 16, two_cb = out->c > 32;
+  const int twc = wide ? 32 : 16, ncb = two_cb ? 2 : 1, nd = 8 / ncb, th = 4 * (32 / twc);
+  const int64_t ds = out->halo_lo + out->d + out->halo_hi;
+  const int64_t wgs = (int64_t)out->n * cdiv(ds, nd) * cdiv(out->h, th) * cdiv(out->w, twc) * cdiv(ncoblk, ncb);
+  if (wide || wgs == 0 || wgs >= 64 || nchunks < 2) return 1;    // (only the narrow-volume variants come in a split form)
+  int s = (int)std::min<int64_t>(nchunks, cdiv(256, wgs));
+  const int64_t out_elems = (int64_t)out->n * out->c * ds * out->h * out->w;
+  while (s > 1 && s * out_elems * 4 > ((int64_t)20 << 20)) --s;   // the partials cost a write and a read
+  const int cps = (int)cdiv(nchunks, s);
+  return (int)cdiv(nchunks, cps);
 }
 
 bool mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
@@ -390,13 +440,20 @@ static void wp_dims(int cin_k, int cout_k, int* nchunks, int* ncoblk) {
   *ncoblk = (int)cdiv(cout_k, 32);
 }
 
-size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
+static size_t mfma_wp_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   int nchunks, ncoblk;
   wp_dims(in->c, out->c, &nchunks, &ncoblk);
-  return (size_t)ncoblk * nchunks * 27 * 512 * sizeof(bf16_t);
+  return ((size_t)ncoblk * nchunks * 27 * 512 * sizeof(bf16_t) + 255) & ~(size_t)255;
 }
 
-template <int NCB, int ND, int TWC, bool MASKED, bool VEC>
+size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
+  size_t b = mfma_wp_bytes(in, out);
+  const int s = mfma_splits(in, out);
+  if (s > 1) b += (size_t)s * out->n * out->c * (out->halo_lo + out->d + out->halo_hi) * out->h * out->w * sizeof(float);
+  return b;
+}
+
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT = false>
 static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
                                  bf16_t* out, MfmaArgs a, int n, hipStream_t stream) {
   constexpr int RPB = 32 / TWC, TH = 4 * RPB;
@@ -411,15 +468,16 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   a.ntiles = (int)ntiles;
   // one resident workgroup per CU (LDS-limited), spread over the output-channel groups
   const int num_cu = static_cast<Handle*>(handle)->num_cu;
-  int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / gy));
-  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED, VEC>;
+  int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / (gy * a.csplit)));
+  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED, VEC, SPLIT>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(WG_THREADS), lds_bytes, stream, in, mask, wp, bias, out, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy, (unsigned)a.csplit), dim3(WG_THREADS), lds_bytes, stream, in, mask, wp,
+                     a.csplit > 1 ? nullptr : bias, out, a);
   return launch_status(handle, "conv3d_mfma");
 }
 
@@ -432,6 +490,9 @@ static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mas
     return two_cb ? launch_variant<2, 4, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s)
                   : launch_variant<1, 8, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
   }
+  if (a.csplit > 1)
+    return two_cb ? launch_variant<2, 4, 16, MASKED, VEC, true>(handle, in, mask, wp, bias, out, a, n, s)
+                  : launch_variant<1, 8, 16, MASKED, VEC, true>(handle, in, mask, wp, bias, out, a, n, s);
   return two_cb ? launch_variant<2, 4, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s)
                 : launch_variant<1, 8, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
 }
@@ -465,10 +526,19 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   const bf16_t* mp = mask ? (const bf16_t*)mask->data : nullptr;
   bf16_t* op = (bf16_t*)out->data;
   const uint4* wq = (const uint4*)ws;
-  if (mask) return vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
-                       : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
-  return vec ? pick_variant<false, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
-             : pick_variant<false, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
+  a.csplit = mfma_splits(in, out);
+  a.chunks_per_split = (int)cdiv(a.nchunks, a.csplit);
+  a.part = a.csplit > 1 ? reinterpret_cast<float*>(static_cast<char*>(ws) + mfma_wp_bytes(in, out)) : nullptr;
+  h3d_status st;
+  if (mask) st = vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
+                     : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
+  else st = vec ? pick_variant<false, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
+                : pick_variant<false, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
+  if (st != H3D_OK || a.csplit == 1) return st;
+  const int64_t out_total = (int64_t)out->n * a.out.nstride;
+  hipLaunchKernelGGL(conv_split_reduce_kernel, dim3((unsigned)cdiv(out_total, 256)), dim3(256), 0, stream, (const float*)a.part, bias, op,
+                     a.out, a.csplit, out_slope);
+  return launch_status(handle, "conv3d_split_reduce");
 }
 
 }  // namespace h3d
