@@ -999,6 +999,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
     p.nrg = cout > 16 ? 2 : 1;
     p.cib = x->c > 16 ? 2 : 1;
     p.th = (p.rbw == 2 && p.cib == 2 && x->h >= 48) ? 6 : 4;
+    if (p.cib == 1 && cout > 16 && cout <= 32) { p.rbw = 2; p.nrg = 1; p.th = 6; }   // one 3-wavefront row group, taller tiles
     if (x->c <= 4) {    // first-layer kernel: one wavefront covers all taps, 8 wavefronts split the tile's rows
       p.smallci = false;
       p.rbw = cout > 16 ? 2 : 1;
@@ -1016,10 +1017,17 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   // Number of voxel chunks: enough workgroups to fill 256 CUs several times over, at least 4 tiles
   // per workgroup, and partials (chunks x Cout x Cin x 27 floats) that stay small next to the tensors.
   int64_t per_chunk_bytes = std::max<int64_t>(1, (int64_t)cout * x->c * 27 * 4);
-  // (the first-layer kernel keeps one 8-wavefront workgroup per CU and pays a cross-wavefront reduction per
-  //  workgroup: one round of workgroups)
-  int64_t want = std::max<int64_t>(1, ((roll && x->c <= 4) ? 256 : 1024) / groups);
-  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)48 << 20) / per_chunk_bytes));
+  int64_t want = std::max<int64_t>(1, 1024 / groups);
+  int64_t cap_bytes = (int64_t)48 << 20;
+  if (roll) {
+    // the rolling kernels hold one to three workgroups per CU (LDS-bound): one round of resident workgroups,
+    // which keeps the fp32 partials (written once, read once by the reduction) small next to the tensors
+    int per_cu = 1;
+    if (x->c > 4) per_cu = (p.cib == 2) ? 1 : (p.rbw * p.nrg == 1 ? 3 : 2);
+    want = std::max<int64_t>(1, cdiv(256 * per_cu, groups));
+    cap_bytes = (int64_t)96 << 20;
+  }
+  want = std::min<int64_t>(want, std::max<int64_t>(1, cap_bytes / per_chunk_bytes));
   want = std::min<int64_t>(want, std::max<int64_t>(1, p.ntiles / 4));
   p.tiles_per_chunk = (int)std::max<int64_t>(1, cdiv(p.ntiles, want));
   p.nchunks = (int)std::max<int64_t>(1, cdiv(p.ntiles, p.tiles_per_chunk));
@@ -1153,8 +1161,8 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
       else if (p.nrg == 2) st = bf_roll_launch<1, 2, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
       else st = bf_roll_launch<1, 1, 2, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
     } else {
-      if (p.rbw == 2) st = bf_roll_launch<2, 2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
-      else if (p.nrg == 2) st = bf_roll_launch<1, 2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+      if (p.rbw == 2 && p.nrg == 1) st = bf_roll_launch<2, 1, 1, 6>(handle, xp, gp, (float*)ws, a, grid, stream);
+      else if (p.rbw == 2) st = bf_roll_launch<2, 2, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
       else st = bf_roll_launch<1, 1, 1, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
     }
   } else {
