@@ -1,0 +1,279 @@
+// Filter gradient of the 2x2x2 stride-2 transposed convolution (the U-Net's up-sampling layer) on the
+// matrix cores, bf16 in / fp32 accumulate:
+//
+//   dW[ci][co][a,b,c] = sum over coarse voxels v = (d,h,w) of x[ci][v] * dy[co][2d+a][2h+b][2w+c]
+//
+// a GEMM whose contraction runs over the coarse voxels.  With v_mfma_f32_16x16x32_bf16 a lane feeds 8
+// consecutive voxels along W:
+//   * rows    = input channels: the A operand is 16 contiguous bytes of x, staged through LDS
+//     (buffer_load ... lds, double-buffered) because all 8 wavefronts of a workgroup need the same x tile;
+//   * columns = (co, c) pairs, 8 output channels x 2 parities, for one (a,b): the B operand is every
+//     second element of 32 contiguous bytes of a dy row, loaded straight from global memory (each dy
+//     element is needed by exactly one wavefront) and de-interleaved with four byte-permutes;
+//   * a workgroup = 8 wavefronts = 16 output channels x the four (a,b); each wavefront keeps
+//     16*MRB input channels x 16 columns in accumulators;
+//   * db[co] = sum dy: one extra MFMA per B fragment against an all-ones A operand.
+// The voxel range is cut into chunks by shape alone; every workgroup writes its partial sums and a second
+// kernel adds the chunks in order, so the result is reproducible.
+#include <algorithm>
+
+#include "common.h"
+
+namespace h3d {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int DB_OOB = (int)0x80000000;
+constexpr int DB_R = 4;                       // rows of 32 coarse voxels per tile
+constexpr int DB_PCI = (4 * DB_R) | 1;        // LDS pitch of a channel in 16-byte units (odd: 16 channels -> 16 bank groups)
+constexpr int DB_NW = 8;
+
+struct DbfArgs {
+  Geo x, y;
+  int cin, cout;
+  int tiles_w, tiles_h;
+  int ntiles, tiles_per_chunk, nchunks;
+  int gco, gci;       // groups of 16 output channels / of 16*MRB input channels
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t db_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                           (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+__device__ __forceinline__ void db_dma16(__amdgpu_buffer_rsrc_t rs, uint4* lds_dst, int voff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds_dst, 16, voff, 0, 0, 0);
+}
+
+template <int MRB>
+__global__ void __launch_bounds__(64 * DB_NW, 4) deconv_bf_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+                                                                     float* __restrict__ part, DbfArgs a) {
+  constexpr int CI_WG = 16 * MRB;
+  constexpr int XPAD = (CI_WG * DB_PCI + 63) / 64 * 64;
+  constexpr int NCHX = XPAD / 64;
+  constexpr int CXW = (NCHX + DB_NW - 1) / DB_NW;
+  extern __shared__ uint4 lds[];      // [2 buffers][CI_WG][DB_R rows][4 units]  (pitches XPAD, DB_PCI, 4)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lg = lane >> 4, lc = lane & 15;
+  const int chunk = blockIdx.x;
+  const int co0 = (blockIdx.y % a.gco) * 16, ci0 = (blockIdx.y / a.gco) * CI_WG;
+  const int ab = wave & 3, cob = wave >> 2;                // this wavefront: (a,b) and which 8 of the 16 output channels
+  const int ta = ab >> 1, tb = ab & 1;
+  const int co = co0 + cob * 8 + (lc >> 1), par = lc & 1;  // this lane's column: output channel and parity c
+  const bool col_ok = co < a.cout;
+  const uint32_t sel = par ? 0x07060302u : 0x05040100u;    // picks the odd / even halves of two dwords
+  const int Wc = a.x.w, Hc = a.x.h, Dc = a.x.d, Wf = a.y.w;
+
+  int dx_meta[CXW];    // row | u << 8 | ci << 16, -1 = padding or channel out of range
+#pragma unroll
+  for (int i = 0; i < CXW; ++i) {
+    const int ul = 64 * (wave + DB_NW * i) + lane;
+    const int cil = ul / DB_PCI, r1 = ul % DB_PCI;
+    const bool ok = wave + DB_NW * i < NCHX && cil < CI_WG && r1 < 4 * DB_R && ci0 + cil < a.cin;
+    dx_meta[i] = ok ? ((r1 >> 2) | ((r1 & 3) << 8) | ((ci0 + cil) << 16)) : -1;
+  }
+  auto load_x = [&](int n, int d, int h0, int w0, int buf) {
+    const __amdgpu_buffer_rsrc_t rs = db_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const int t0 = (d + a.x.hlo) * (int)a.x.plane + h0 * Wc + w0;
+#pragma unroll
+    for (int i = 0; i < CXW; ++i) {
+      int m = dx_meta[i];
+      asm volatile("" : "+v"(m));     // keeps the unpacked fields from being hoisted into registers of their own
+      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), ci = m >> 16;
+      const bool ok = m >= 0 && h0 + row < Hc && w0 + u8 + 8 <= Wc;
+      if (wave + DB_NW * i < NCHX)
+        db_dma16(rs, lds + buf * XPAD + 64 * (wave + DB_NW * i), ok ? 2 * (t0 + ci * (int)a.x.cstride + row * Wc + u8) : DB_OOB);
+    }
+  };
+
+  f32x4 acc[MRB];
+  f32x4 accdb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int rb = 0; rb < MRB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
+  const bool do_db = ci0 == 0;
+
+  // tile order: columns fastest, then row blocks, planes, samples
+  const int t_begin = chunk * a.tiles_per_chunk;
+  const int t_end = min(t_begin + a.tiles_per_chunk, a.ntiles);
+  int tw, th, d, n;
+  {
+    int r = t_begin;
+    tw = r % a.tiles_w; r /= a.tiles_w;
+    th = r % a.tiles_h; r /= a.tiles_h;
+    d = r % Dc;
+    n = r / Dc;
+  }
+  if (t_begin < t_end) load_x(n, d, th * DB_R, tw * 32, 0);
+  int buf = 0;
+  const char* a_base = reinterpret_cast<const char*>(lds) + 16 * (lc * DB_PCI + lg);
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int h0 = th * DB_R, w0 = tw * 32;
+    // ---- this tile's dy fragments: 32 contiguous bytes per lane and row, straight from global memory
+    const __amdgpu_buffer_rsrc_t rs_y = db_rsrc(dy + n * a.y.nstride, (uint32_t)a.y.nstride * 2);
+    u32x4 braw[DB_R][2];
+    {
+      const int yb = co * (int)a.y.cstride + (2 * d + ta + a.y.hlo) * (int)a.y.plane + (2 * h0 + tb) * Wf + 2 * (w0 + 8 * lg);
+#pragma unroll
+      for (int r = 0; r < DB_R; ++r) {
+        const bool ok = col_ok && h0 + r < Hc && w0 + 8 * lg + 8 <= Wc;
+        const int off = ok ? 2 * (yb + 2 * r * Wf) : DB_OOB;
+        braw[r][0] = __builtin_amdgcn_raw_buffer_load_b128(rs_y, off, 0, 0);
+        braw[r][1] = __builtin_amdgcn_raw_buffer_load_b128(rs_y, ok ? off + 16 : DB_OOB, 0, 0);
+      }
+    }
+    // the x tile of this step has landed (issued one step ago); everyone is done with the other buffer
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DB_R) : "memory");
+    __syncthreads();
+    int tw2 = tw + 1, th2 = th, d2 = d, n2 = n;
+    if (tw2 == a.tiles_w) { tw2 = 0; ++th2; }
+    if (th2 == a.tiles_h) { th2 = 0; ++d2; }
+    if (d2 == Dc) { d2 = 0; ++n2; }
+    if (tile + 1 < t_end) load_x(n2, d2, th2 * DB_R, tw2 * 32, buf ^ 1);
+
+    const char* ap = a_base + 16 * XPAD * buf;
+#pragma unroll
+    for (int r = 0; r < DB_R; ++r) {
+      bf16x8 A[MRB];
+#pragma unroll
+      for (int rb = 0; rb < MRB; ++rb) A[rb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ap + 16 * (rb * 16 * DB_PCI + 4 * r)));
+      uint4 bf;
+      bf.x = __builtin_amdgcn_perm(braw[r][0][1], braw[r][0][0], sel);
+      bf.y = __builtin_amdgcn_perm(braw[r][0][3], braw[r][0][2], sel);
+      bf.z = __builtin_amdgcn_perm(braw[r][1][1], braw[r][1][0], sel);
+      bf.w = __builtin_amdgcn_perm(braw[r][1][3], braw[r][1][2], sel);
+      const bf16x8 B = __builtin_bit_cast(bf16x8, bf);
+#pragma unroll
+      for (int rb = 0; rb < MRB; ++rb) acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb], B, acc[rb], 0, 0, 0);
+      if (do_db) accdb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, B, accdb, 0, 0, 0);
+    }
+    tw = tw2; th = th2; d = d2; n = n2;
+    buf ^= 1;
+  }
+
+  // ---- partial sums -> workspace [chunk][cin][cout][8] (+ [chunk][cout][8] for the bias partial behind it)
+  const int k = ab * 2 + par;
+  if (col_ok) {
+    float* pw = part + (int64_t)chunk * a.cin * a.cout * 8;
+#pragma unroll
+    for (int rb = 0; rb < MRB; ++rb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int ci = ci0 + rb * 16 + 4 * lg + rr;
+        if (ci < a.cin) pw[((int64_t)ci * a.cout + co) * 8 + k] = acc[rb][rr];
+      }
+    if (do_db && lg == 0) {
+      float* pb = part + (int64_t)a.nchunks * a.cin * a.cout * 8 + (int64_t)chunk * a.cout * 8;
+      pb[co * 8 + k] = accdb[0];
+    }
+  }
+}
+
+// dw[i] = sum over chunks of part[chunk][i] (chunk order); db[co] = sum over chunks, then over the 8 taps
+__global__ void __launch_bounds__(256) deconv_bf_mfma_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                                    float* __restrict__ db, int64_t nw, int cout, int nchunks) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < nw) {
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * nw + i];
+    dw[i] = s;
+  } else if (db && i < nw + cout) {
+    const int co = (int)(i - nw);
+    const float* pb = part + (int64_t)nchunks * nw;
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c)
+      for (int k = 0; k < 8; ++k) s += pb[((int64_t)c * cout + co) * 8 + k];
+    db[co] = s;
+  }
+}
+
+struct DbfPlan {
+  int mrb, tiles_w, tiles_h, ntiles, tiles_per_chunk, nchunks, gco, gci;
+};
+
+DbfPlan dbf_plan(const h3d_tensor* x, const h3d_tensor* dy) {
+  DbfPlan p;
+  p.mrb = x->c > 64 ? 8 : (x->c > 32 ? 4 : 2);
+  p.tiles_w = (int)cdiv(x->w, 32);
+  p.tiles_h = (int)cdiv(x->h, DB_R);
+  p.ntiles = (int)((int64_t)x->n * x->d * p.tiles_h * p.tiles_w);
+  p.gco = (int)cdiv(dy->c, 16);
+  p.gci = (int)cdiv(x->c, 16 * p.mrb);
+  const int64_t groups = (int64_t)p.gco * p.gci;
+  const int64_t per_chunk_bytes = std::max<int64_t>(1, ((int64_t)x->c * dy->c + dy->c) * 8 * 4);
+  int64_t want = std::max<int64_t>(1, 512 / groups);
+  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)64 << 20) / per_chunk_bytes));
+  want = std::min<int64_t>(want, std::max<int64_t>(1, p.ntiles / 4));
+  p.tiles_per_chunk = (int)std::max<int64_t>(1, cdiv(p.ntiles, want));
+  p.nchunks = (int)std::max<int64_t>(1, cdiv(p.ntiles, p.tiles_per_chunk));
+  return p;
+}
+
+template <int MRB>
+h3d_status dbf_launch(void* handle, const bf16_t* x, const bf16_t* dy, float* part, const DbfArgs& a, hipStream_t stream) {
+  constexpr size_t lds_bytes = (size_t)2 * ((16 * MRB * DB_PCI + 63) / 64 * 64) * 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(deconv_bf_mfma_kernel<MRB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "deconv2_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((deconv_bf_mfma_kernel<MRB>), dim3((unsigned)a.nchunks, (unsigned)(a.gco * a.gci)), dim3(64 * DB_NW), lds_bytes,
+                     stream, x, dy, part, a);
+  return H3D_OK;
+}
+
+}  // namespace
+
+bool deconv_bf_mfma_supported(const h3d_tensor* x, const h3d_tensor* dy) {
+  if (x->dtype != H3D_BF16 || x->c < 1 || dy->c < 1 || x->w % 8 != 0) return false;
+  if ((uintptr_t)x->data % 16 != 0 || (uintptr_t)dy->data % 16 != 0) return false;
+  const int64_t xs = (int64_t)x->c * (x->halo_lo + x->d + x->halo_hi) * x->h * x->w * 2;
+  const int64_t ys = (int64_t)dy->c * (dy->halo_lo + dy->d + dy->halo_hi) * dy->h * dy->w * 2;
+  const int64_t ntiles = (int64_t)x->n * x->d * cdiv(x->h, DB_R) * cdiv(x->w, 32);
+  return xs < ((int64_t)1 << 31) && ys < ((int64_t)1 << 31) && ntiles < ((int64_t)1 << 30) && cdiv(dy->c, 16) * cdiv(x->c, 32) < 65536;
+}
+
+size_t deconv_bf_mfma_ws_bytes(const h3d_tensor* x, const h3d_tensor* dy) {
+  const DbfPlan p = dbf_plan(x, dy);
+  return (size_t)p.nchunks * ((size_t)x->c * dy->c + dy->c) * 8 * sizeof(float);
+}
+
+h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dy, float* dw, float* db, void* ws, size_t ws_bytes,
+                          hipStream_t stream) {
+  const DbfPlan p = dbf_plan(x, dy);
+  if (!ws || ws_bytes < deconv_bf_mfma_ws_bytes(x, dy)) return fail(handle, H3D_EWORKSPACE, "deconv2_bwd_filter: workspace too small");
+  DbfArgs a;
+  a.x = make_geo(x); a.y = make_geo(dy);
+  a.cin = x->c; a.cout = dy->c;
+  a.tiles_w = p.tiles_w; a.tiles_h = p.tiles_h; a.ntiles = p.ntiles;
+  a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
+  a.gco = p.gco; a.gci = p.gci;
+  const int64_t nw = (int64_t)a.cin * a.cout * 8;
+  if (p.ntiles == 0) {
+    hipMemsetAsync(dw, 0, nw * sizeof(float), stream);
+    if (db) hipMemsetAsync(db, 0, a.cout * sizeof(float), stream);
+    return launch_status(handle, "deconv2_bwd_filter");
+  }
+  const bf16_t* xp = (const bf16_t*)x->data;
+  const bf16_t* yp = (const bf16_t*)dy->data;
+  h3d_status st;
+  if (p.mrb == 8) st = dbf_launch<8>(handle, xp, yp, (float*)ws, a, stream);
+  else if (p.mrb == 4) st = dbf_launch<4>(handle, xp, yp, (float*)ws, a, stream);
+  else st = dbf_launch<2>(handle, xp, yp, (float*)ws, a, stream);
+  if (st != H3D_OK) return st;
+  hipLaunchKernelGGL(deconv_bf_mfma_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw,
+                     db, nw, a.cout, a.nchunks);
+  return launch_status(handle, "deconv2_bwd_filter_mfma");
+}
+
+}  // namespace h3d

@@ -506,6 +506,11 @@ static h3d_status deconv_bwd_data_t(void* handle, const h3d_tensor* dy, const vo
   return launch_status(handle, "deconv2_bwd_data");
 }
 
+bool deconv_bf_mfma_supported(const h3d_tensor* x, const h3d_tensor* dy);
+size_t deconv_bf_mfma_ws_bytes(const h3d_tensor* x, const h3d_tensor* dy);
+h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dy, float* dw, float* db, void* ws, size_t ws_bytes,
+                          hipStream_t stream);
+
 template <typename T>
 static h3d_status deconv_bwd_filter_t(void* handle, const h3d_tensor* x, const h3d_tensor* dy, float* dw, float* db, void* ws,
                                       size_t ws_bytes, hipStream_t s) {
@@ -513,6 +518,7 @@ static h3d_status deconv_bwd_filter_t(void* handle, const h3d_tensor* x, const h
   a.x = make_geo(x); a.y = make_geo(dy); a.cin = x->c; a.cout = dy->c;
   a.voxels = (int64_t)x->n * x->d * x->h * x->w;
   if (a.cin == 0 || a.cout == 0) return H3D_OK;
+  if (deconv_bf_mfma_supported(x, dy)) return deconv_bf_mfma(handle, x, dy, dw, db, ws, ws_bytes, s);
   df_plan(a.voxels, a.cin, a.cout, &a.chunk, &a.nchunks);
   int cog = (int)cdiv(a.cout, DF_COT);
   size_t need = (size_t)a.nchunks * cog * DF_COT * a.cin * 9 * 4;
@@ -539,6 +545,7 @@ extern "C" size_t h3d_deconv2_workspace_bytes(void* handle, int op, const h3d_te
     int64_t chunk; int nchunks;
     df_plan((int64_t)x->n * x->d * x->h * x->w, x->c, y->c, &chunk, &nchunks);
     b = (size_t)nchunks * cdiv(y->c, DF_COT) * DF_COT * x->c * 9 * 4;
+    if (deconv_bf_mfma_supported(x, y)) b = std::max(b, deconv_bf_mfma_ws_bytes(x, y));
   }
   return (b + 255) & ~(size_t)255;
 }
