@@ -277,3 +277,186 @@ h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* d
 }
 
 }  // namespace h3d
+
+// ---------------------------------------------------------------------------------------------------
+// Data gradient of the transposed convolution:
+//
+//   dx[ci][v] = sum over co and the 8 taps k = (a,b,c) of W[ci][co][k] * dy[co][2d+a][2h+b][2w+c]
+//
+// a GEMM whose contraction index (co, k) needs no re-layout on either side: with
+// v_mfma_f32_32x32x16_bf16 a lane feeds the 8 taps of ONE output channel — for the B operand the
+// 2x2x2 block of dy above its coarse voxel (four dword loads, consecutive lanes = consecutive dwords),
+// for the A operand 16 contiguous bytes of W[ci][co][0..8).  Rows = input channels, columns = 32 coarse
+// voxels along W, one K-step = two output channels.  W^T sits in LDS for the whole (persistent)
+// workgroup, as [co][ci] units with an odd pitch; every dy element is loaded exactly once.
+namespace h3d {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int DD_NW = 8;
+constexpr int DD_BATCH = 8;      // K-steps (pairs of output channels) whose dy loads are in flight together
+
+struct DbdArgs {
+  Geo x, y;          // x: coarse tensor (dx), y: fine tensor (dy)
+  int cin, cout;
+  int wblks;         // 32-voxel column blocks per coarse row
+  int64_t ncb;       // column blocks in total
+};
+
+template <int MRB>
+__global__ void __launch_bounds__(64 * DD_NW, 2) deconv_bd_mfma_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
+                                                                     bf16_t* __restrict__ dx, DbdArgs a) {
+  constexpr int CP = (32 * MRB) | 1;          // LDS pitch of an output channel in 16-byte units
+  extern __shared__ uint4 lds[];              // [cout rounded up to even][CP]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int nks = (a.cout + 1) / 2;
+
+  // ---- W[ci][co][8] -> LDS [co][ci]; rows of a padding channel are zero (their dy operand is zero too)
+  {
+    const uint4* wu = reinterpret_cast<const uint4*>(w);
+    const int total = a.cin * a.cout;
+    for (int i = tid; i < total; i += 64 * DD_NW) {
+      const int ci = i / a.cout, co = i % a.cout;
+      lds[co * CP + ci] = wu[i];
+    }
+    if (a.cout & 1)
+      for (int i = tid; i < CP; i += 64 * DD_NW) lds[a.cout * CP + i] = uint4{0, 0, 0, 0};
+  }
+  __syncthreads();
+
+  const int Wc = a.x.w, Hc = a.x.h, Dc = a.x.d, Wf = a.y.w;
+  const char* a_base = reinterpret_cast<const char*>(lds) + 16 * (half * CP + col);
+  for (int64_t cb = (int64_t)blockIdx.x * DD_NW + wave; cb < a.ncb; cb += (int64_t)gridDim.x * DD_NW) {
+    int64_t r = cb;
+    const int wb = (int)(r % a.wblks); r /= a.wblks;
+    const int h = (int)(r % Hc); r /= Hc;
+    const int d = (int)(r % Dc);
+    const int n = (int)(r / Dc);
+    const int wv = wb * 32 + col;
+    const __amdgpu_buffer_rsrc_t rs_y = db_rsrc(dy + n * a.y.nstride, (uint32_t)a.y.nstride * 2);
+    const int vbase = wv < Wc ? 2 * (half * (int)a.y.cstride + (2 * d + a.y.hlo) * (int)a.y.plane + 2 * h * Wf + 2 * wv) : DB_OOB;
+
+    f32x16 acc[MRB];
+#pragma unroll
+    for (int rb = 0; rb < MRB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
+
+    uint32_t bqa[DD_BATCH][4], bqb[DD_BATCH][4];     // two batches of dy operands: one in flight, one being multiplied
+    auto load_batch = [&](int s0, uint32_t (&dst)[DD_BATCH][4]) {
+#pragma unroll
+      for (int j = 0; j < DD_BATCH; ++j) {
+        const int s = s0 + j;
+        // the channel pair of this K-step is a scalar offset; lanes of a missing channel read nothing
+        const int vo = (s < nks && 2 * s + half < a.cout) ? vbase : DB_OOB;
+        const int so = __builtin_amdgcn_readfirstlane(2 * (2 * s) * (int)a.y.cstride);
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab)
+          dst[j][ab] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, vo, so + 2 * ((ab >> 1) * (int)a.y.plane + (ab & 1) * Wf), 0);
+      }
+    };
+    auto read_a = [&](int s, uint4 (&dst)[MRB]) {
+#pragma unroll
+      for (int rb = 0; rb < MRB; ++rb) dst[rb] = *reinterpret_cast<const uint4*>(a_base + 16 * (2 * s * CP + rb * 32));
+    };
+    auto mul_batch = [&](int s0, const uint32_t (&src)[DD_BATCH][4]) {
+      uint4 af[2][MRB];       // weight fragments of this K-step and of the next
+      if (s0 < nks) read_a(s0, af[0]);
+#pragma unroll
+      for (int j = 0; j < DD_BATCH; ++j) {
+        const int s = s0 + j;
+        if (s < nks) {
+          if (s + 1 < nks && j + 1 < DD_BATCH) read_a(s + 1, af[(j + 1) & 1]);
+          __builtin_amdgcn_sched_barrier(0);
+          const uint4 bu = {src[j][0], src[j][1], src[j][2], src[j][3]};
+          const bf16x8 B = __builtin_bit_cast(bf16x8, bu);
+#pragma unroll
+          for (int rb = 0; rb < MRB; ++rb)
+            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[j & 1][rb]), B, acc[rb], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
+    load_batch(0, bqa);
+    for (int s0 = 0; s0 < nks; s0 += 2 * DD_BATCH) {
+      load_batch(s0 + DD_BATCH, bqb);
+      mul_batch(s0, bqa);
+      load_batch(s0 + 2 * DD_BATCH, bqa);
+      mul_batch(s0 + DD_BATCH, bqb);
+    }
+
+    // ---- dx[ci][d][h][wv]: accumulator register r of row block rb is channel 32 rb + 8 (r/4) + 4 half + r % 4
+    // (buffer stores: the lane's voxel offset plus a scalar channel offset; a store to a channel beyond Cin or a
+    //  column beyond W gets an out-of-range offset and is dropped)
+    {
+      const __amdgpu_buffer_rsrc_t rs_x = db_rsrc(dx + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+      const int vo = wv < Wc ? 2 * (4 * half * (int)a.x.cstride + (d + a.x.hlo) * (int)a.x.plane + h * Wc + wv) : DB_OOB;
+#pragma unroll
+      for (int rb = 0; rb < MRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int ci_u = rb * 32 + 8 * (i / 4) + (i % 4);      // wave-uniform part of the channel
+          const bool ch_ok = ci_u + 4 * half < a.cin;
+          __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(acc[rb][i]), rs_x, ch_ok ? vo : DB_OOB,
+                                                __builtin_amdgcn_readfirstlane(2 * ci_u * (int)a.x.cstride), 0);
+        }
+    }
+  }
+}
+
+template <int MRB>
+h3d_status dbd_launch(void* handle, const bf16_t* dy, const bf16_t* w, bf16_t* dx, const DbdArgs& a, size_t lds_bytes,
+                      hipStream_t stream) {
+  static size_t attr_bytes = 0;
+  if (lds_bytes > attr_bytes) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(deconv_bd_mfma_kernel<MRB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "deconv2_bwd_data: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_bytes = lds_bytes;
+  }
+  const int num_cu = static_cast<Handle*>(handle)->num_cu;
+  const int64_t grid = std::max<int64_t>(1, std::min<int64_t>(num_cu, cdiv(a.ncb, DD_NW)));
+  hipLaunchKernelGGL((deconv_bd_mfma_kernel<MRB>), dim3((unsigned)grid), dim3(64 * DD_NW), lds_bytes, stream, dy, w, dx, a);
+  return H3D_OK;
+}
+
+size_t dbd_lds_bytes(int cin, int cout) {
+  const int mrb = (int)cdiv(cin, 32);
+  return (size_t)((cout + 1) / 2 * 2) * ((32 * mrb) | 1) * 16;
+}
+
+}  // namespace
+
+bool deconv_bd_mfma_supported(const h3d_tensor* dx, const h3d_tensor* dy, const void* w) {
+  if (dx->dtype != H3D_BF16 || dx->c < 1 || dx->c > 128 || dy->c < 1) return false;
+  if ((uintptr_t)dy->data % 4 != 0 || (uintptr_t)w % 16 != 0) return false;
+  if (dbd_lds_bytes(dx->c, dy->c) > 160 * 1024) return false;
+  const int64_t ys = (int64_t)dy->c * (dy->halo_lo + dy->d + dy->halo_hi) * dy->h * dy->w * 2;
+  const int64_t xs = (int64_t)dx->c * (dx->halo_lo + dx->d + dx->halo_hi) * dx->h * dx->w * 2;
+  return ys < ((int64_t)1 << 31) && xs < ((int64_t)1 << 31);
+}
+
+h3d_status deconv_bd_mfma(void* handle, const h3d_tensor* dy, const void* w, h3d_tensor* dx, hipStream_t stream) {
+  DbdArgs a;
+  a.x = make_geo(dx); a.y = make_geo(dy);
+  a.cin = dx->c; a.cout = dy->c;
+  a.wblks = (int)cdiv(dx->w, 32);
+  a.ncb = (int64_t)dx->n * dx->d * dx->h * a.wblks;
+  if (a.ncb == 0) return H3D_OK;
+  const size_t lds_bytes = dbd_lds_bytes(a.cin, a.cout);
+  const int mrb = (int)cdiv(a.cin, 32);
+  const bf16_t* yp = (const bf16_t*)dy->data;
+  const bf16_t* wp = (const bf16_t*)w;
+  bf16_t* xp = (bf16_t*)dx->data;
+  h3d_status st;
+  if (mrb == 4) st = dbd_launch<4>(handle, yp, wp, xp, a, lds_bytes, stream);
+  else if (mrb == 3) st = dbd_launch<3>(handle, yp, wp, xp, a, lds_bytes, stream);
+  else if (mrb == 2) st = dbd_launch<2>(handle, yp, wp, xp, a, lds_bytes, stream);
+  else st = dbd_launch<1>(handle, yp, wp, xp, a, lds_bytes, stream);
+  if (st != H3D_OK) return st;
+  return launch_status(handle, "deconv2_bwd_data_mfma");
+}
+
+}  // namespace h3d

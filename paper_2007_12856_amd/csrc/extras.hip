@@ -490,6 +490,9 @@ static h3d_status deconv_fwd_t(void* handle, const h3d_tensor* x, const void* w,
   return launch_status(handle, "deconv2_fwd");
 }
 
+bool deconv_bd_mfma_supported(const h3d_tensor* dx, const h3d_tensor* dy, const void* w);
+h3d_status deconv_bd_mfma(void* handle, const h3d_tensor* dy, const void* w, h3d_tensor* dx, hipStream_t stream);
+
 template <typename T>
 static h3d_status deconv_bwd_data_t(void* handle, const h3d_tensor* dy, const void* w, h3d_tensor* dx, void* ws, size_t ws_bytes,
                                     hipStream_t s) {
@@ -498,6 +501,7 @@ static h3d_status deconv_bwd_data_t(void* handle, const h3d_tensor* dy, const vo
   a.pad = (int)cdiv(a.cin, DC_COT) * DC_COT;
   a.total = (int64_t)dx->n * dx->d * dx->h * dx->w;
   if (a.total == 0 || a.cin == 0) return H3D_OK;
+  if (deconv_bd_mfma_supported(dx, dy, w)) return deconv_bd_mfma(handle, dy, w, dx, s);
   size_t need = (size_t)a.cout * 8 * a.pad * 4;
   if (need && (!ws || ws_bytes < need)) return fail(handle, H3D_EWORKSPACE, "deconv2_bwd_data: workspace too small");
   if (need) hipLaunchKernelGGL((deconv_pack_kernel<T>), dim3((unsigned)cdiv(need / 4, 256)), dim3(256), 0, s, (const T*)w, (float*)ws, a.cin, a.cout, a.pad, 1);
