@@ -460,3 +460,224 @@ h3d_status deconv_bd_mfma(void* handle, const h3d_tensor* dy, const void* w, h3d
 }
 
 }  // namespace h3d
+
+// ---------------------------------------------------------------------------------------------------
+// Forward of the transposed convolution:
+//
+//   y[co][2d+a][2h+b][2w+c] = bias[co] + sum over ci of W[ci][co][a,b,c] * x[ci][d,h,w]
+//
+// a GEMM with rows (co, k = (a,b,c)), columns = coarse voxels and the contraction over ci.  NCDHW keeps
+// channels a whole volume apart, so (as in the 3x3x3 kernels) the x tile is transposed on its way into
+// LDS: 16-byte units of 8 channels, [ci-group][voxel].  Eight wavefronts share the staged tile; wavefront
+// w owns the row blocks w, w+8, ... and keeps their weight fragments (pre-packed in fragment order) in
+// registers for the whole persistent workgroup.  In an accumulator the two parities c of a (co,a,b) are
+// adjacent registers of one lane, so every lane stores whole dwords and consecutive lanes write
+// consecutive dwords of a fine row.
+namespace h3d {
+namespace {
+
+constexpr int DF_NW = 8;
+constexpr int DF_CBI = 8;        // 32-voxel column blocks staged per iteration (one per wavefront)
+
+struct DfwArgs {
+  Geo x, y;
+  int cin, cout;
+  int wblks;
+  int64_t ncb;
+};
+
+// wp: [row block][K-step][lane][8] bf16; lane l, element e: row 32 rb + l % 32 = 8 co + k, channel 16 ks + 8 (l/32) + e
+__global__ void deconv_fw_pack_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int cin, int cout, int nrb, int ks) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)nrb * ks * 512) return;
+  const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  int64_t r = i >> 9;
+  const int s = (int)(r % ks), rb = (int)(r / ks);
+  const int row = rb * 32 + (lane & 31), co = row >> 3, k = row & 7, ci = s * 16 + (lane >> 5) * 8 + e;
+  wp[i] = (co < cout && ci < cin) ? w[((int64_t)ci * cout + co) * 8 + k] : (bf16_t)0;
+}
+
+template <int RBW, int KS>
+__global__ void __launch_bounds__(64 * DF_NW, 2) deconv_fw_mfma_kernel(const bf16_t* __restrict__ x, const uint4* __restrict__ wp,
+                                                                     const float* __restrict__ bias, bf16_t* __restrict__ y,
+                                                                     DfwArgs a) {
+  constexpr int NCIG = 2 * KS;                     // groups of 8 input channels
+  constexpr int CBU = NCIG * 32 + 4;               // LDS units of one column block: [ci-group][32 voxels] (+4: staggers the blocks)
+  extern __shared__ uint4 lds[];                   // [2 buffers][DF_CBI][CBU]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int Wc = a.x.w, Hc = a.x.h, Dc = a.x.d, Wf = a.y.w;
+  const int nrb = (8 * a.cout + 31) / 32;
+
+  // ---- this wavefront's weight fragments
+  uint4 A[RBW][KS];
+#pragma unroll
+  for (int j = 0; j < RBW; ++j) {
+    const int rb = wave + DF_NW * j;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) A[j][s] = rb < nrb ? wp[((int64_t)rb * KS + s) * 64 + lane] : uint4{0, 0, 0, 0};
+  }
+
+  float bv[RBW][4];
+#pragma unroll
+  for (int j = 0; j < RBW; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int co = 4 * (wave + DF_NW * j) + q;
+      bv[j][q] = (bias && co < a.cout) ? bias[co] : 0.f;
+    }
+
+  const int ncb = (int)a.ncb;
+  const int it0 = blockIdx.x * DF_CBI, it_stride = gridDim.x * DF_CBI;
+  auto decode = [&](int cb, int& n, int& d, int& h, int& w0) {
+    int r = cb;
+    w0 = (r % a.wblks) * 32; r /= a.wblks;
+    h = r % Hc; r /= Hc;
+    d = r % Dc;
+    n = r / Dc;
+  };
+  // staging: a lane takes one (ci-group, group of 8 voxels) item of its wavefront's column block per round
+  constexpr int SROUNDS = (NCIG * 4 + 63) / 64;
+  u32x4 sv[SROUNDS][8];
+  auto stage_load = [&](int cb0) {
+    const int cb = cb0 + wave;
+    int n, d, h, w0;
+    decode(cb < ncb ? cb : 0, n, d, h, w0);
+    const __amdgpu_buffer_rsrc_t rs = db_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+#pragma unroll
+    for (int r = 0; r < SROUNDS; ++r) {
+      const int item = lane + 64 * r, cig = item >> 2, vg = item & 3;
+      const int wv = w0 + 8 * vg;
+      const bool ok = cb < ncb && cig < NCIG && wv + 8 <= Wc;
+      const int base = 2 * (cig * 8 * (int)a.x.cstride + (d + a.x.hlo) * (int)a.x.plane + h * Wc + wv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        sv[r][e] = __builtin_amdgcn_raw_buffer_load_b128(rs, (ok && cig * 8 + e < a.cin) ? base : DB_OOB,
+                                                         __builtin_amdgcn_readfirstlane(2 * e * (int)a.x.cstride), 0);
+    }
+  };
+  auto stage_store = [&](int buf) {
+    uint4* dst0 = lds + (buf * DF_CBI + wave) * CBU;
+#pragma unroll
+    for (int r = 0; r < SROUNDS; ++r) {
+      const int item = lane + 64 * r, cig = item >> 2, vg = item & 3;
+      if (cig >= NCIG) continue;
+      uint4* dst = dst0 + cig * 32 + 8 * vg;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {       // dword j of each channel = voxels 2j, 2j+1 of the group
+        uint4 u0, u1;
+        u0.x = __builtin_amdgcn_perm(sv[r][1][j], sv[r][0][j], 0x05040100); u1.x = __builtin_amdgcn_perm(sv[r][1][j], sv[r][0][j], 0x07060302);
+        u0.y = __builtin_amdgcn_perm(sv[r][3][j], sv[r][2][j], 0x05040100); u1.y = __builtin_amdgcn_perm(sv[r][3][j], sv[r][2][j], 0x07060302);
+        u0.z = __builtin_amdgcn_perm(sv[r][5][j], sv[r][4][j], 0x05040100); u1.z = __builtin_amdgcn_perm(sv[r][5][j], sv[r][4][j], 0x07060302);
+        u0.w = __builtin_amdgcn_perm(sv[r][7][j], sv[r][6][j], 0x05040100); u1.w = __builtin_amdgcn_perm(sv[r][7][j], sv[r][6][j], 0x07060302);
+        dst[2 * j] = u0;
+        dst[2 * j + 1] = u1;
+      }
+    }
+  };
+
+  if (it0 < ncb) { stage_load(it0); stage_store(0); }
+  __syncthreads();
+  int buf = 0;
+  for (int cb0 = it0; cb0 < ncb; cb0 += it_stride, buf ^= 1) {
+    const bool more = cb0 + it_stride < ncb;
+    if (more) stage_load(cb0 + it_stride);       // in flight during this iteration's MFMAs
+#pragma unroll 1
+    for (int c = 0; c < DF_CBI; ++c) {
+      const int cb = cb0 + c;
+      if (cb >= ncb) break;
+      int n, d, h, w0;
+      decode(cb, n, d, h, w0);
+      const uint4* bp = lds + (buf * DF_CBI + c) * CBU + half * 32 + col;
+      f32x16 acc[RBW];
+#pragma unroll
+      for (int j = 0; j < RBW; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bf16x8 B = __builtin_bit_cast(bf16x8, bp[s * 64]);
+#pragma unroll
+        for (int j = 0; j < RBW; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[j][s]), B, acc[j], 0, 0, 0);
+      }
+      // ---- rows 32 rb + 8 (i/4) + 4 half + i % 4 = 8 co + k: co = 4 rb + i / 4, a = half, b = (i % 4) / 2, c = i % 2
+      const __amdgpu_buffer_rsrc_t rs_y = db_rsrc(y + n * a.y.nstride, (uint32_t)a.y.nstride * 2);
+      const int wv = w0 + col;
+      const int vo = wv < Wc ? 2 * ((2 * d + half + a.y.hlo) * (int)a.y.plane + 2 * h * Wf + 2 * wv) : DB_OOB;
+#pragma unroll
+      for (int j = 0; j < RBW; ++j) {
+        const int rb = wave + DF_NW * j;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int co = 4 * rb + q;
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const uint32_t pk = pack_bf16x2(acc[j][4 * q + 2 * b] + bv[j][q], acc[j][4 * q + 2 * b + 1] + bv[j][q]);
+            __builtin_amdgcn_raw_buffer_store_b32(pk, rs_y, co < a.cout ? vo : DB_OOB,
+                                                  __builtin_amdgcn_readfirstlane(2 * (co * (int)a.y.cstride + b * Wf)), 0);
+          }
+        }
+      }
+    }
+    if (more) stage_store(buf ^ 1);
+    __syncthreads();
+  }
+}
+
+template <int RBW, int KS>
+h3d_status dfw_launch(void* handle, const bf16_t* x, const uint4* wp, const float* bias, bf16_t* y, const DfwArgs& a,
+                      hipStream_t stream) {
+  constexpr size_t lds_bytes = (size_t)2 * DF_CBI * (2 * KS * 32 + 4) * 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(deconv_fw_mfma_kernel<RBW, KS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "deconv2_fwd: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  const int num_cu = static_cast<Handle*>(handle)->num_cu;
+  const int64_t grid = std::max<int64_t>(1, std::min<int64_t>(num_cu, cdiv(a.ncb, DF_CBI)));
+  hipLaunchKernelGGL((deconv_fw_mfma_kernel<RBW, KS>), dim3((unsigned)grid), dim3(64 * DF_NW), lds_bytes, stream, x, wp, bias, y, a);
+  return H3D_OK;
+}
+
+}  // namespace
+
+bool deconv_fw_mfma_supported(const h3d_tensor* x, const h3d_tensor* y) {
+  if (x->dtype != H3D_BF16 || x->c < 1 || x->c > 128 || y->c < 1 || y->c > 64 || x->w % 8 != 0) return false;
+  if ((uintptr_t)x->data % 16 != 0 || (uintptr_t)y->data % 4 != 0) return false;
+  const int64_t xs = (int64_t)x->c * (x->halo_lo + x->d + x->halo_hi) * x->h * x->w * 2;
+  const int64_t ys = (int64_t)y->c * (y->halo_lo + y->d + y->halo_hi) * y->h * y->w * 2;
+  const int64_t ncb = (int64_t)x->n * x->d * x->h * cdiv(x->w, 32);
+  return xs < ((int64_t)1 << 31) && ys < ((int64_t)1 << 31) && ncb < ((int64_t)1 << 30);
+}
+
+size_t deconv_fw_mfma_ws_bytes(const h3d_tensor* x, const h3d_tensor* y) {
+  const int ks = x->c > 64 ? 8 : 4, nrb = (int)cdiv(8 * (int64_t)y->c, 32);
+  return (size_t)nrb * ks * 1024;
+}
+
+h3d_status deconv_fw_mfma(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* y, void* ws,
+                          size_t ws_bytes, hipStream_t stream) {
+  DfwArgs a;
+  a.x = make_geo(x); a.y = make_geo(y);
+  a.cin = x->c; a.cout = y->c;
+  a.wblks = (int)cdiv(x->w, 32);
+  a.ncb = (int64_t)x->n * x->d * x->h * a.wblks;
+  if (a.ncb == 0) return H3D_OK;
+  if (!ws || ws_bytes < deconv_fw_mfma_ws_bytes(x, y) || (uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "deconv2_fwd: workspace too small or misaligned");
+  const int ks = a.cin > 64 ? 8 : 4, nrb = (int)cdiv(8 * (int64_t)a.cout, 32), rbw = (int)cdiv(nrb, DF_NW);
+  hipLaunchKernelGGL(deconv_fw_pack_kernel, dim3((unsigned)cdiv((int64_t)nrb * ks * 512, 256)), dim3(256), 0, stream, (const bf16_t*)w,
+                     (bf16_t*)ws, a.cin, a.cout, nrb, ks);
+  const bf16_t* xp = (const bf16_t*)x->data;
+  bf16_t* yp = (bf16_t*)y->data;
+  const uint4* wq = (const uint4*)ws;
+  h3d_status st;
+  if (ks == 8) st = rbw == 2 ? dfw_launch<2, 8>(handle, xp, wq, bias, yp, a, stream) : dfw_launch<1, 8>(handle, xp, wq, bias, yp, a, stream);
+  else st = rbw == 2 ? dfw_launch<2, 4>(handle, xp, wq, bias, yp, a, stream) : dfw_launch<1, 4>(handle, xp, wq, bias, yp, a, stream);
+  if (st != H3D_OK) return st;
+  return launch_status(handle, "deconv2_fwd_mfma");
+}
+
+}  // namespace h3d

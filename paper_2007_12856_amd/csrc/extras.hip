@@ -474,6 +474,11 @@ __global__ void __launch_bounds__(256) mse_kernel(const T* __restrict__ pred, co
   if (threadIdx.x == 0) loss[0] = (red[0] + red[1] + red[2] + red[3]) * inv;
 }
 
+bool deconv_fw_mfma_supported(const h3d_tensor* x, const h3d_tensor* y);
+size_t deconv_fw_mfma_ws_bytes(const h3d_tensor* x, const h3d_tensor* y);
+h3d_status deconv_fw_mfma(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* y, void* ws,
+                          size_t ws_bytes, hipStream_t stream);
+
 template <typename T>
 static h3d_status deconv_fwd_t(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* y, void* ws,
                                size_t ws_bytes, hipStream_t s) {
@@ -482,6 +487,7 @@ static h3d_status deconv_fwd_t(void* handle, const h3d_tensor* x, const void* w,
   a.pad = (int)cdiv(a.cout, DC_COT) * DC_COT;
   a.total = (int64_t)x->n * x->d * x->h * x->w;
   if (a.total == 0 || a.cout == 0) return H3D_OK;
+  if (deconv_fw_mfma_supported(x, y)) return deconv_fw_mfma(handle, x, w, bias, y, ws, ws_bytes, s);
   size_t need = (size_t)a.cin * a.pad * 8 * 4;
   if (need && (!ws || ws_bytes < need)) return fail(handle, H3D_EWORKSPACE, "deconv2_fwd: workspace too small");
   if (need) hipLaunchKernelGGL((deconv_pack_kernel<T>), dim3((unsigned)cdiv(need / 4, 256)), dim3(256), 0, s, (const T*)w, (float*)ws, a.cin, a.cout, a.pad, 0);
@@ -543,7 +549,10 @@ using namespace h3d;
 extern "C" size_t h3d_deconv2_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* y) {
   if (!handle || !x || !y) return 0;
   size_t b = 0;
-  if (op == H3D_OP_FWD) b = (size_t)x->c * cdiv(y->c, DC_COT) * DC_COT * 8 * 4;
+  if (op == H3D_OP_FWD) {
+    b = (size_t)x->c * cdiv(y->c, DC_COT) * DC_COT * 8 * 4;
+    if (deconv_fw_mfma_supported(x, y)) b = std::max(b, deconv_fw_mfma_ws_bytes(x, y));
+  }
   else if (op == H3D_OP_BWD_DATA) b = (size_t)y->c * 8 * cdiv(x->c, DC_COT) * DC_COT * 4;
   else if (op == H3D_OP_BWD_FILTER) {
     int64_t chunk; int nchunks;

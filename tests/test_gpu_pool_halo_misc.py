@@ -109,7 +109,8 @@ def test_halo_width_errors():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("cin,cout,shape", [(3, 5, (2, 2, 3, 5)), (16, 8, (1, 4, 6, 34)), (128, 64, (1, 2, 4, 16)),
-                                            (40, 24, (2, 3, 5, 40)), (20, 70, (1, 2, 9, 64)), (136, 16, (1, 1, 4, 32))])
+                                            (40, 24, (2, 3, 5, 40)), (20, 70, (1, 2, 9, 64)), (136, 16, (1, 1, 4, 32)),
+                                            (48, 40, (1, 2, 3, 24)), (100, 21, (1, 1, 2, 16))])
 def test_deconv2(cin, cout, shape, dtype):
     import torch
     import paper_2007_12856_amd as h3d
