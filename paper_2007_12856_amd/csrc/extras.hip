@@ -259,6 +259,64 @@ __global__ void __launch_bounds__(256) dense_fwd_kernel(const T* __restrict__ x,
   }
 }
 
+// Forward for inputs that fit the LDS (m * k elements <= 128 KB, k a multiple of 16 / sizeof(T)): x is staged once
+// per (persistent) workgroup, every weight row is then streamed from HBM exactly once by one wavefront and
+// meets x in LDS, so the L2 sees the weights only.  Eight wavefronts per workgroup, rows handed out round-robin.
+template <typename T>
+__global__ void __launch_bounds__(512) dense_fwd_lds_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                            const float* __restrict__ bias, T* __restrict__ y, DenseArgs a) {
+  constexpr int V = 16 / sizeof(T);
+  struct alignas(16) Pk { T v[V]; };
+  extern __shared__ uint4 x_lds[];      // [m][k / V] units
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int ku = a.k / V;
+  for (int i = tid; i < a.m * ku; i += 512) x_lds[i] = reinterpret_cast<const uint4*>(x)[i];
+  __syncthreads();
+  for (int j = blockIdx.x * 8 + wave; j < a.n; j += gridDim.x * 8) {
+    float acc[DM];
+#pragma unroll
+    for (int i = 0; i < DM; ++i) acc[i] = 0.f;
+    const uint4* wr = reinterpret_cast<const uint4*>(w + (int64_t)j * a.k);
+    constexpr int UN = 4;   // weight loads in flight per lane
+    for (int u0 = lane; u0 < ku; u0 += 64 * UN) {
+      uint4 wv[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u)
+        if (u0 + 64 * u < ku) wv[u] = wr[u0 + 64 * u];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int uu = u0 + 64 * u;
+        if (uu < ku) {
+          const Pk wp = __builtin_bit_cast(Pk, wv[u]);
+#pragma unroll
+          for (int i = 0; i < DM; ++i) {
+            if (i < a.m) {
+              const Pk xp = __builtin_bit_cast(Pk, x_lds[i * ku + uu]);
+#pragma unroll
+              for (int e = 0; e < V; ++e) acc[i] = fmaf(ld(&wp.v[e]), ld(&xp.v[e]), acc[i]);
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < DM; ++i) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) acc[i] += __shfl_xor(acc[i], off, 64);
+    }
+    if (lane == 0) {
+      const float b = bias ? bias[j] : 0.f;
+#pragma unroll
+      for (int i = 0; i < DM; ++i)
+        if (i < a.m) {
+          float r = acc[i] + b;
+          if (!(r > 0.f)) r *= a.slope;
+          st(y + (int64_t)i * a.n + j, r);
+        }
+    }
+  }
+}
+
 template <typename T>
 __device__ __forceinline__ float dense_g(const T* dy, const T* y, int64_t idx, const DenseArgs& a) {
   float g = ld(dy + idx);
@@ -415,43 +473,57 @@ __global__ void __launch_bounds__(1024) dense_bwd_dx_vec_kernel(const T* __restr
   }
 }
 
-// dw[j][c] = sum_i g[i][j] x[i][c];  db[j] = sum_i g[i][j].  Output-bound (fp32 dw): four columns per
-// thread, 16-byte stores.
+// dw[j][c] = sum_i g[i][j] x[i][c];  db[j] = sum_i g[i][j].  Output-bound (fp32 dw): a thread keeps its four
+// columns of x (all m rows) in registers and walks DW_ROWS output rows, one 16-byte store per row.
+constexpr int DW_ROWS = 16;
 template <typename T>
 __global__ void __launch_bounds__(256) dense_bwd_dw_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, float* __restrict__ dw,
                                                            float* __restrict__ db, DenseArgs a) {
-  const int j = blockIdx.y;
-  float g[DM];
-#pragma unroll
-  for (int i = 0; i < DM; ++i) g[i] = i < a.m ? dense_g(dy, y, (int64_t)i * a.n + j, a) : 0.f;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && db) {
+  const int j0 = blockIdx.y * DW_ROWS;
+  if (blockIdx.x == 0 && threadIdx.x < DW_ROWS && j0 + threadIdx.x < a.n && db) {
+    const int j = j0 + threadIdx.x;
     float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < DM; ++i) s += g[i];
+    for (int i = 0; i < a.m; ++i) s += dense_g(dy, y, (int64_t)i * a.n + j, a);
     db[j] = s;
   }
   const bool vec = (a.k % 4 == 0) && ((uintptr_t)x % (4 * sizeof(T)) == 0) && ((uintptr_t)dw % 16 == 0);
   if (vec) {
     for (int c = (blockIdx.x * 256 + threadIdx.x) * 4; c < a.k; c += gridDim.x * 1024) {
-      float s[4] = {0.f, 0.f, 0.f, 0.f};
+      float xv[DM][4];
 #pragma unroll
-      for (int i = 0; i < DM; ++i)
+      for (int i = 0; i < DM; ++i) {
+        struct alignas(4 * sizeof(T)) P4 { T v[4]; };
         if (i < a.m) {
-          struct alignas(4 * sizeof(T)) P4 { T v[4]; };
-          P4 p = *reinterpret_cast<const P4*>(x + (int64_t)i * a.k + c);
+          const P4 p = *reinterpret_cast<const P4*>(x + (int64_t)i * a.k + c);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) s[e] = fmaf(g[i], ld(&p.v[e]), s[e]);
+          for (int e = 0; e < 4; ++e) xv[i][e] = ld(&p.v[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) xv[i][e] = 0.f;
         }
-      *reinterpret_cast<float4*>(dw + (int64_t)j * a.k + c) = float4{s[0], s[1], s[2], s[3]};
+      }
+      for (int jj = 0; jj < DW_ROWS && j0 + jj < a.n; ++jj) {
+        const int j = j0 + jj;
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < DM; ++i)
+          if (i < a.m) {
+            const float g = dense_g(dy, y, (int64_t)i * a.n + j, a);     // wave-uniform address: a scalar load
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] = fmaf(g, xv[i][e], s[e]);
+          }
+        *reinterpret_cast<float4*>(dw + (int64_t)j * a.k + c) = float4{s[0], s[1], s[2], s[3]};
+      }
     }
   } else {
-    for (int c = blockIdx.x * 256 + threadIdx.x; c < a.k; c += gridDim.x * 256) {
-      float s = 0.f;
-#pragma unroll
-      for (int i = 0; i < DM; ++i)
-        if (i < a.m) s = fmaf(g[i], ld(x + (int64_t)i * a.k + c), s);
-      dw[(int64_t)j * a.k + c] = s;
+    for (int jj = 0; jj < DW_ROWS && j0 + jj < a.n; ++jj) {
+      const int j = j0 + jj;
+      for (int c = blockIdx.x * 256 + threadIdx.x; c < a.k; c += gridDim.x * 256) {
+        float s = 0.f;
+        for (int i = 0; i < a.m; ++i) s = fmaf(dense_g(dy, y, (int64_t)i * a.n + j, a), ld(x + (int64_t)i * a.k + c), s);
+        dw[(int64_t)j * a.k + c] = s;
+      }
     }
   }
 }
@@ -606,6 +678,26 @@ extern "C" h3d_status h3d_dense_fwd(void* handle, const void* x, const void* w, 
   if (!y || (k > 0 && (!x || !w))) return fail(handle, H3D_EINVAL, "dense_fwd: NULL pointer");
   DenseArgs a{m, n, k, act_slope(act, alpha), act};
   dim3 g((unsigned)cdiv(n, 4));
+  // x resident in LDS: whole 16-byte units and at most 128 KB of input
+  const int vw = dtype == H3D_F32 ? 4 : 8;
+  const size_t x_bytes = (size_t)m * k * (dtype == H3D_F32 ? 4 : 2);
+  if (k % vw == 0 && (uintptr_t)x % 16 == 0 && (uintptr_t)w % 16 == 0 && x_bytes <= 128 * 1024 && n >= 256) {
+    const int num_cu = static_cast<Handle*>(handle)->num_cu;
+    dim3 gl((unsigned)std::min<int64_t>(num_cu, cdiv(n, 8)));
+    static bool attr_set[2] = {false, false};
+    const int di = dtype == H3D_F32 ? 0 : 1;
+    if (!attr_set[di]) {
+      const void* fn = di == 0 ? reinterpret_cast<const void*>(dense_fwd_lds_kernel<float>) : reinterpret_cast<const void*>(dense_fwd_lds_kernel<bf16_t>);
+      if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess)
+        return fail(handle, H3D_EHIP, "dense_fwd: cannot raise the dynamic LDS limit");
+      attr_set[di] = true;
+    }
+    if (dtype == H3D_F32)
+      hipLaunchKernelGGL((dense_fwd_lds_kernel<float>), gl, dim3(512), x_bytes, (hipStream_t)stream, (const float*)x, (const float*)w, bias, (float*)y, a);
+    else
+      hipLaunchKernelGGL((dense_fwd_lds_kernel<bf16_t>), gl, dim3(512), x_bytes, (hipStream_t)stream, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, a);
+    return launch_status(handle, "dense_fwd");
+  }
   if (dtype == H3D_F32)
     hipLaunchKernelGGL((dense_fwd_kernel<float>), g, dim3(256), 0, (hipStream_t)stream, (const float*)x, (const float*)w, bias, (float*)y, a);
   else
@@ -621,7 +713,7 @@ extern "C" h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, 
   if (!x || !w || !dy || !dw || (act != H3D_ACT_NONE && !y)) return fail(handle, H3D_EINVAL, "dense_bwd: NULL pointer");
   DenseArgs a{m, n, k, act_slope(act, alpha), act};
   hipStream_t s = (hipStream_t)stream;
-  dim3 gdx((unsigned)cdiv(k, 128)), gdw((unsigned)std::min<int64_t>(cdiv(k, 1024), 64), (unsigned)n);
+  dim3 gdx((unsigned)cdiv(k, 128)), gdw((unsigned)std::min<int64_t>(cdiv(k, 1024), 64), (unsigned)cdiv(n, DW_ROWS));
   if (n > 65535) return fail(handle, H3D_EINVAL, "dense_bwd: n too large");
   // line-wide dx kernel: whole 16-byte units per row and g (n x 8 floats) within 64 KB of LDS
   const int vw = dtype == H3D_F32 ? 4 : 8;
