@@ -65,6 +65,16 @@ typedef struct {
   int32_t halo_lo, halo_hi; /* stored halo planes below / above the interior              */
   int64_t d_offset;         /* global depth index of interior plane 0                      */
   int64_t d_global;         /* depth of the unsharded sample                               */
+  /* Elements between consecutive channels / samples.  0 = packed: (halo_lo+d+halo_hi)*h*w and c times that.
+   * Non-zero strides describe a RUN OF PLANES inside a taller stored slab, i.e. the main / halo sub-domains
+   * of Sec. III-C (D_main = planes that need no halo, D_halo = the strips that do): `data` points at the
+   * run's first stored plane, d / halo_* / d_offset describe the run, the strides are the parent's.  Only
+   * the three convolution passes accept such a view; every other entry point returns H3D_EUNSUPPORTED.
+   * Forward / backward-data on views that tile a slab give the whole-slab call's result bit for bit, except
+   * where the whole-slab call is small enough to take the channel-split kernel (bf16, W <= 16, fewer than 64
+   * workgroups): views are never split, so the fp32 summation order of the two differs there. */
+  int64_t c_stride;
+  int64_t n_stride;
 } h3d_tensor;
 
 /* Handle: host object caching device properties and the last error text.

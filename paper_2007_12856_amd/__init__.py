@@ -32,7 +32,8 @@ class H3DError(RuntimeError):
 class h3d_tensor(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("n", ctypes.c_int32), ("c", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("h", ctypes.c_int32), ("w", ctypes.c_int32), ("halo_lo", ctypes.c_int32),
-                ("halo_hi", ctypes.c_int32), ("d_offset", ctypes.c_int64), ("d_global", ctypes.c_int64)]
+                ("halo_hi", ctypes.c_int32), ("d_offset", ctypes.c_int64), ("d_global", ctypes.c_int64),
+                ("c_stride", ctypes.c_int64), ("n_stride", ctypes.c_int64)]
 
 
 _lib = None
@@ -136,7 +137,8 @@ def _dtype_code(t) -> int:
 
 @dataclass
 class Slab:
-    """A depth slab: `t` is a contiguous device tensor [N, C, halo_lo + d + halo_hi, H, W]."""
+    """A depth slab: `t` is a device tensor [N, C, halo_lo + d + halo_hi, H, W], either contiguous or a run of planes
+    sliced out of a taller contiguous slab (`planes()`: the convolution passes accept such views)."""
     t: object
     halo_lo: int = 0
     halo_hi: int = 0
@@ -144,7 +146,9 @@ class Slab:
     d_global: int | None = None
 
     def __post_init__(self):
-        assert self.t.dim() == 5 and self.t.is_contiguous()
+        assert self.t.dim() == 5
+        n, c, ds, h, w = self.t.shape
+        assert self.t.is_contiguous() or self.t.stride()[2:] == (h * w, w, 1), "only whole planes can be sliced"
         if self.d_global is None:
             self.d_global = self.d
 
@@ -158,8 +162,16 @@ class Slab:
 
     def desc(self) -> h3d_tensor:
         n, c, _, h, w = self.t.shape
+        cs, ns = (0, 0) if self.t.is_contiguous() else (self.t.stride(1), self.t.stride(0))
         return h3d_tensor(self.t.data_ptr(), _dtype_code(self.t), n, c, self.d, h, w, self.halo_lo, self.halo_hi,
-                          self.d_offset, self.d_global)
+                          self.d_offset, self.d_global, cs, ns)
+
+    def planes(self, p0: int, p1: int, halo_lo: int = 0, halo_hi: int = 0) -> "Slab":
+        """The interior planes [p0, p1) of this slab (indices relative to its first interior plane; they may reach
+        into its halo) as a view with the given halo widths: no copy, same memory."""
+        a, b = self.halo_lo + p0 - halo_lo, self.halo_lo + p1 + halo_hi
+        assert 0 <= a <= b <= self.t.shape[2]
+        return Slab(self.t[:, :, a:b], halo_lo, halo_hi, self.d_offset + p0, self.d_global)
 
     def like(self, channels: int, halo_lo: int = 0, halo_hi: int = 0, d: int | None = None, h: int | None = None,
              w: int | None = None, d_offset: int | None = None, d_global: int | None = None) -> "Slab":

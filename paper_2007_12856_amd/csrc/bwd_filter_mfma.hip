@@ -1036,8 +1036,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
 
 bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
   if (x->dtype != H3D_BF16 || x->c < 1 || dz->c < 1) return false;
-  int64_t sample = (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w;
-  return sample < ((int64_t)1 << 30);
+  return sample_span(x) < ((int64_t)1 << 40) && (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w < ((int64_t)1 << 30);
 }
 
 size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
@@ -1127,8 +1126,7 @@ static h3d_status bf_pick(void* handle, const BfPlan& p, const bf16_t* x, const 
 h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw, float* db,
                            float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
   const bool vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
-  const bool dma_ok = (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w * x->c * 2 < ((int64_t)1 << 31) &&
-                      (int64_t)(dz->halo_lo + dz->d + dz->halo_hi) * dz->h * dz->w * dz->c * 2 < ((int64_t)1 << 31);
+  const bool dma_ok = sample_span(x) * 2 < ((int64_t)1 << 31) && sample_span(dz) * 2 < ((int64_t)1 << 31);
   const bool roll = !z && vec_ok && dma_ok && bf_roll_shape(x);
   BfPlan p = bf_plan_mfma(x, dz->c, roll);
   if (!ws || ws_bytes < mfma_bf_ws_bytes(x, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");

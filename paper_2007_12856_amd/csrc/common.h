@@ -31,15 +31,23 @@ inline Geo make_geo(const h3d_tensor* t) {
   g.ds = t->halo_lo + t->d + t->halo_hi;
   g.doff = t->d_offset; g.dglob = t->d_global;
   g.plane = (int64_t)t->h * t->w;
-  g.cstride = g.plane * g.ds;
-  g.nstride = g.cstride * t->c;
+  g.cstride = t->c_stride ? t->c_stride : g.plane * g.ds;
+  g.nstride = t->n_stride ? t->n_stride : g.cstride * t->c;
   return g;
+}
+
+inline bool is_packed(const h3d_tensor* t) { return t->c_stride == 0 && t->n_stride == 0; }
+// elements spanned by one sample (all channels), with the tensor's real strides
+inline int64_t sample_span(const h3d_tensor* t) {
+  const int64_t cs = t->c_stride ? t->c_stride : (int64_t)(t->halo_lo + t->d + t->halo_hi) * t->h * t->w;
+  return t->n_stride ? t->n_stride : cs * t->c;
 }
 
 inline size_t elt_size(int dtype) { return dtype == H3D_F32 ? 4 : 2; }
 
 h3d_status fail(void* handle, h3d_status st, const char* fmt, ...);
-h3d_status check_tensor(void* handle, const h3d_tensor* t, const char* name);
+h3d_status check_tensor(void* handle, const h3d_tensor* t, const char* name);          // strided plane runs allowed
+h3d_status check_tensor_packed(void* handle, const h3d_tensor* t, const char* name);   // packed tensors only
 // every needed in-volume input plane for output planes [lo,hi) (local indices) must be stored
 bool halo_covers(const h3d_tensor* in, int64_t lo, int64_t hi);
 bool same_shard(const h3d_tensor* a, const h3d_tensor* b);

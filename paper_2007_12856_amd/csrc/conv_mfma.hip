@@ -417,7 +417,7 @@ static int mfma_splits(const h3d_tensor* in, const h3d_tensor* out) {
   const int twc = wide ? 32 : 16, ncb = two_cb ? 2 : 1, nd = 8 / ncb, th = 4 * (32 / twc);
   const int64_t ds = out->halo_lo + out->d + out->halo_hi;
   const int64_t wgs = (int64_t)out->n * cdiv(ds, nd) * cdiv(out->h, th) * cdiv(out->w, twc) * cdiv(ncoblk, ncb);
-  if (wide || wgs == 0 || wgs >= 64 || nchunks < 2) return 1;    // (only the narrow-volume variants come in a split form)
+  if (wide || wgs == 0 || wgs >= 64 || nchunks < 2 || !is_packed(out)) return 1;    // (only the narrow-volume variants come in a split form)
   int s = (int)std::min<int64_t>(nchunks, cdiv(256, wgs));
   const int64_t out_elems = (int64_t)out->n * out->c * ds * out->h * out->w;
   while (s > 1 && s * out_elems * 4 > ((int64_t)20 << 20)) --s;   // the partials cost a write and a read
@@ -429,10 +429,8 @@ bool mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
   if (in->dtype != H3D_BF16) return false;
   if (in->c < 1 || out->c < 1) return false;
   // 32-bit in-sample offsets inside the kernel
-  int64_t in_sample = (int64_t)(in->halo_lo + in->d + in->halo_hi) * in->h * in->w;
-  int64_t out_sample = (int64_t)(out->halo_lo + out->d + out->halo_hi) * out->h * out->w;
   // buffer loads address a whole sample (all channels) with 31-bit byte offsets
-  return in_sample * in->c < ((int64_t)1 << 30) && out_sample * out->c < ((int64_t)1 << 30);
+  return sample_span(in) < ((int64_t)1 << 30) && sample_span(out) < ((int64_t)1 << 30);
 }
 
 static void wp_dims(int cin_k, int cout_k, int* nchunks, int* ncoblk) {

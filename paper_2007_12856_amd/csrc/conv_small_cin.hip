@@ -198,8 +198,7 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
 
 bool c4_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
   if (in->dtype != H3D_BF16 || in->c < 1 || in->c > 4 || out->c < 1 || out->c > 32) return false;
-  int64_t in_sample = (int64_t)(in->halo_lo + in->d + in->halo_hi) * in->h * in->w;
-  return in_sample < ((int64_t)1 << 30);
+  return sample_span(in) < ((int64_t)1 << 30);
 }
 
 size_t c4_fwd_ws_bytes(const h3d_tensor* out) { return (size_t)cdiv(out->c, 16) * 4 * 512 * sizeof(bf16_t); }

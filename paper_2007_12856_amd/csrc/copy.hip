@@ -97,7 +97,7 @@ extern "C" size_t h3d_halo_bytes(const h3d_tensor* t, int width) {
 }
 
 static h3d_status face_args(void* handle, const h3d_tensor* t, int face, int width, bool pack, RunCopy* a) {
-  H3D_TRY(check_tensor(handle, t, "t"));
+  H3D_TRY(check_tensor_packed(handle, t, "t"));
   if (face != H3D_FACE_D_LO && face != H3D_FACE_D_HI) return fail(handle, H3D_EINVAL, "halo: bad face %d", face);
   if (width <= 0) return fail(handle, H3D_EINVAL, "halo: width must be positive");
   int64_t first;  // first stored plane of the face region
@@ -145,9 +145,9 @@ extern "C" h3d_status h3d_halo_unpack(void* handle, const void* buf, h3d_tensor*
 }
 
 static h3d_status cat_check(void* handle, const h3d_tensor* a, const h3d_tensor* b, const h3d_tensor* o) {
-  H3D_TRY(check_tensor(handle, a, "a"));
-  H3D_TRY(check_tensor(handle, b, "b"));
-  H3D_TRY(check_tensor(handle, o, "out"));
+  H3D_TRY(check_tensor_packed(handle, a, "a"));
+  H3D_TRY(check_tensor_packed(handle, b, "b"));
+  H3D_TRY(check_tensor_packed(handle, o, "out"));
   if (!same_shard(a, b) || !same_shard(a, o) || o->c != a->c + b->c)
     return fail(handle, H3D_EINVAL, "concat/split: shapes do not match (need same n,d,h,w,offsets,dtype and c = ca+cb)");
   return H3D_OK;

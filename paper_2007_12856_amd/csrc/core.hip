@@ -32,6 +32,20 @@ h3d_status check_tensor(void* handle, const h3d_tensor* t, const char* name) {
   if (elems >= ((int64_t)1 << 40)) return fail(handle, H3D_EINVAL, "%s: tensor too large", name);
   if ((int64_t)t->h * t->w >= ((int64_t)1 << 30)) return fail(handle, H3D_EINVAL, "%s: plane too large", name);
   if (((uintptr_t)t->data) % elt_size(t->dtype)) return fail(handle, H3D_EINVAL, "%s: misaligned data pointer", name);
+  if (t->c_stride < 0 || t->n_stride < 0) return fail(handle, H3D_EINVAL, "%s: negative stride", name);
+  if (!is_packed(t)) {
+    const int64_t run = (int64_t)(t->halo_lo + t->d + t->halo_hi) * t->h * t->w;
+    const int64_t cs = t->c_stride ? t->c_stride : run;
+    const int64_t ns = t->n_stride ? t->n_stride : cs * t->c;
+    if (cs < run || ns < cs * t->c) return fail(handle, H3D_EINVAL, "%s: strides smaller than the run of planes they address", name);
+    if (ns >= ((int64_t)1 << 40)) return fail(handle, H3D_EINVAL, "%s: tensor too large", name);
+  }
+  return H3D_OK;
+}
+
+h3d_status check_tensor_packed(void* handle, const h3d_tensor* t, const char* name) {
+  H3D_TRY(check_tensor(handle, t, name));
+  if (!is_packed(t)) return fail(handle, H3D_EUNSUPPORTED, "%s: strided plane runs are accepted by the convolution passes only", name);
   return H3D_OK;
 }
 

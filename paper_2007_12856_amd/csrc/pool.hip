@@ -207,8 +207,8 @@ using namespace h3d;
 
 extern "C" h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tensor* y, int mode, void* stream) {
   if (!handle) return H3D_EINVAL;
-  H3D_TRY(check_tensor(handle, x, "x"));
-  H3D_TRY(check_tensor(handle, y, "y"));
+  H3D_TRY(check_tensor_packed(handle, x, "x"));
+  H3D_TRY(check_tensor_packed(handle, y, "y"));
   if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_fwd: bad mode %d", mode);
   H3D_TRY(pool_check(handle, x, y, "pool3d_fwd"));
   hipStream_t s = (hipStream_t)stream;
@@ -240,16 +240,16 @@ static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_te
                                 int mode, float slope, void* stream) {
   if (!handle) return H3D_EINVAL;
   if (z) {
-    H3D_TRY(check_tensor(handle, z, "z"));
+    H3D_TRY(check_tensor_packed(handle, z, "z"));
     if (!dx || !same_shard(z, dx) || z->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: z and g shapes differ");
   }
-  H3D_TRY(check_tensor(handle, dy, "dy"));
-  H3D_TRY(check_tensor(handle, dx, "dx"));
+  H3D_TRY(check_tensor_packed(handle, dy, "dy"));
+  H3D_TRY(check_tensor_packed(handle, dx, "dx"));
   if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_bwd: bad mode %d", mode);
   H3D_TRY(pool_check(handle, dx, dy, "pool3d_bwd"));
   if (mode == H3D_POOL_MAX) {
     if (!x) return fail(handle, H3D_EINVAL, "pool3d_bwd: max pooling needs the forward input x");
-    H3D_TRY(check_tensor(handle, x, "x"));
+    H3D_TRY(check_tensor_packed(handle, x, "x"));
     if (!same_shard(x, dx) || x->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd: x and dx shapes differ");
   } else {
     x = nullptr;

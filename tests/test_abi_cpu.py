@@ -31,8 +31,8 @@ def test_header_symbols_are_exported_and_bound():
 def test_descriptor_layout_matches_header():
     import paper_2007_12856_amd as h3d
     # void* + 8 x int32 + 2 x int64 with natural alignment
-    assert ctypes.sizeof(h3d.h3d_tensor) == 8 + 8 * 4 + 2 * 8
-    assert h3d.h3d_tensor.d_offset.offset == 40 and h3d.h3d_tensor.dtype.offset == 8
+    assert ctypes.sizeof(h3d.h3d_tensor) == 8 + 8 * 4 + 4 * 8
+    assert h3d.h3d_tensor.d_offset.offset == 40 and h3d.h3d_tensor.dtype.offset == 8 and h3d.h3d_tensor.c_stride.offset == 56
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -212,6 +212,62 @@ def test_conv3d_sharded_matches_oracle_and_unsharded_gpu(dtype, cin, cout):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cin,cout,W,exact", [(4, 16, 40, True), (16, 32, 32, True), (24, 8, 36, True), (64, 128, 40, True),
+                                              (64, 128, 8, False)])
+def test_main_halo_split_is_bit_exact(dtype, cin, cout, W, exact):
+    """Sec. III-C: the planes that need no halo (main) and the two strips that do are computed by separate
+    calls on plane-run views of the same buffers; together they must reproduce the whole-slab call bit for bit."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, D, H = 2, 9, 10
+    w, bias = _weights(cin, cout, dtype, 50)
+    wd, bd = to_dev(w, dtype), to_dev(bias, "f32")
+    xo, xg = slab_pair(synth.flat("normal", SEED, 51, (N, cin, D + 2, H, W)), dtype, (1, 1), 3, D + 6)
+    zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=0.01)
+    whole = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, dtype), h3d.ACT_LEAKY, 0.01)
+    assert rel_l2(from_dev(whole.t), zo.a) <= TOL[dtype]
+    parts = dev_like(zo, dtype)
+    for p0, p1 in [(1, D - 1), (0, 1), (D - 1, D)]:          # main first, then the two strips
+        h3d.conv3d_fwd(xg.planes(p0, p1, 1, 1), wd, bd, parts.planes(p0, p1), h3d.ACT_LEAKY, 0.01)
+    if exact or dtype == "f32":
+        assert torch.equal(parts.t, whole.t)
+    else:
+        assert rel_l2(from_dev(parts.t), zo.a) <= TOL[dtype]
+    # backward-data on the same split
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 52, (N, cout, D + 2, H, W)), dtype, (1, 1), 3, D + 6)
+    dxo = orc.conv3d_bwd_data(dzo, None, w, act=orc.ACT_NONE)
+    dx_whole = h3d.conv3d_bwd_data(dzg, None, wd, dev_like(dxo, dtype), h3d.ACT_NONE, 0.0)
+    assert rel_l2(from_dev(dx_whole.t), dxo.a) <= TOL[dtype]
+    dx_parts = dev_like(dxo, dtype)
+    for p0, p1 in [(2, D - 2), (0, 2), (D - 2, D)]:
+        h3d.conv3d_bwd_data(dzg.planes(p0, p1, 1, 1), None, wd, dx_parts.planes(p0, p1), h3d.ACT_NONE, 0.0)
+    if exact or dtype == "f32":
+        assert torch.equal(dx_parts.t, dx_whole.t)
+    else:
+        assert rel_l2(from_dev(dx_parts.t), dxo.a) <= TOL[dtype]
+    # backward-filter: the strips' partial gradients add up to the whole slab's (different summation order)
+    go, gg = slab_pair(synth.flat("normal", SEED, 53, (N, cout, D, H, W)), dtype, (0, 0), 3, D + 6)
+    dwo, dbo = orc.conv3d_bwd_filter(xo, go, None, act=orc.ACT_NONE)
+    dw = torch.zeros((cout, cin, 3, 3, 3), device="cuda")
+    db = torch.zeros((cout,), device="cuda")
+    for p0, p1 in [(1, D - 1), (0, 1), (D - 1, D)]:
+        dwp, dbp = torch.empty_like(dw), torch.empty_like(db)
+        h3d.conv3d_bwd_filter(xg.planes(p0, p1, 1, 1), gg.planes(p0, p1), None, dwp, dbp, h3d.ACT_NONE, 0.0)
+        dw += dwp
+        db += dbp
+    tol_w = 1e-5 if dtype == "f32" else 2e-4
+    assert rel_l2(from_dev(dw), dwo) <= tol_w and rel_l2(from_dev(db), dbo) <= tol_w
+
+
+def test_plane_run_views_are_rejected_elsewhere():
+    import paper_2007_12856_amd as h3d
+    _, xg = slab_pair(synth.flat("normal", SEED, 54, (1, 2, 6, 4, 8)), "bf16")
+    _, yg = slab_pair(np.zeros((1, 2, 3, 2, 4)), "bf16")
+    with pytest.raises(h3d.H3DError):
+        h3d.pool3d_fwd(xg.planes(0, 4), yg.planes(0, 2), h3d.POOL_AVG)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_halo_recompute_two_stacked_convs(dtype):
     """A 2-plane halo serves two stacked convolutions (U-Net-shaped level): the first also produces
     its output's halo plane; beyond the global boundary that plane must be zero, not act(bias)."""
