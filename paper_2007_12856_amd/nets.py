@@ -223,7 +223,8 @@ class SingleLayer:
     halo_unpack of both D faces, conv fwd (+bias+act), pool fwd, halo_pack of the input faces;
     pool bwd fused with the activation backward, BF and BD on g (g carries a 1-plane halo)."""
 
-    def __init__(self, n, cin, cout, d, hw, d_offset, d_global, pool=True, act=ACT_LEAKY, alpha=0.01, dtype=torch.bfloat16, seed=0):
+    def __init__(self, n, cin, cout, d, hw, d_offset, d_global, pool=True, act=ACT_LEAKY, alpha=0.01, dtype=torch.bfloat16, seed=0,
+                 split=False):
         from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
         dev = "cuda"
         gen = torch.Generator(device=dev)
@@ -252,6 +253,14 @@ class SingleLayer:
         op("halo_pack_x", lambda: (halo_pack(x, FACE_D_LO, 1, faces[0]), halo_pack(x, FACE_D_HI, 1, faces[1])), 0, 4 * faces[0].numel() * es)
         op("halo_unpack_x", lambda: (halo_unpack(faces[1], x, FACE_D_LO, 1), halo_unpack(faces[0], x, FACE_D_HI, 1)), 0, 4 * faces[0].numel() * es)
         op("conv_fwd", lambda: conv3d_fwd(x, w, b, z, act, alpha, ws), fl, (x.t.numel() + z.t.numel() + w.numel()) * es)
+        if split and d >= 3:
+            # the same forward as main planes (no halo needed) + the two one-plane strips (Sec. III-C), on plane-run views
+            pl = n * hw * hw
+            op("conv_fwd_main", lambda: conv3d_fwd(x.planes(1, d - 1, 1, 1), w, b, z.planes(1, d - 1), act, alpha, ws),
+               fl * (d - 2) // d, (pl * (d * cin + (d - 2) * cout) + w.numel()) * es)
+            op("conv_fwd_strips", lambda: (conv3d_fwd(x.planes(0, 1, 1, 1), w, b, z.planes(0, 1), act, alpha, ws),
+                                           conv3d_fwd(x.planes(d - 1, d, 1, 1), w, b, z.planes(d - 1, d), act, alpha, ws)),
+               fl * 2 // d, (pl * 2 * (3 * cin + cout) + 2 * w.numel()) * es)
         if pool:
             p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
             dp = self.dp = Slab(rnd(n, cout, d // 2, hw // 2, hw // 2), 0, 0, d_offset // 2, d_global // 2)
