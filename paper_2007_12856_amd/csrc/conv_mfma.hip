@@ -85,14 +85,17 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // VEC: rows start 4-byte aligned and W is even, so a pair of bf16 is one dword load (the normal case);
 // otherwise the two elements of a pair are fetched by two 2-byte loads with their own validity.
-template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT>
+// FLAT: for outputs of one or two planes (the halo strips of a main / halo split) the ND wavefronts of a
+// channel block take ND groups of rows of ONE plane instead of ND planes, so no wavefront runs empty.
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT, bool FLAT>
 __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ mask,
                                                                  const uint4* __restrict__ wp, const float* __restrict__ bias,
                                                                  bf16_t* __restrict__ out, MfmaArgs a) {
   static_assert(NCB * ND == 8, "8 wavefronts per workgroup");
   constexpr int RPB = 32 / TWC;        // h rows per MFMA column block
-  constexpr int TH = 4 * RPB, TW = TWC;
-  constexpr int TD2 = ND + 2, TH2 = TH + 2;
+  constexpr int TH = 4 * RPB, TW = TWC;   // rows per wavefront
+  constexpr int TDP = FLAT ? 1 : ND, THT = FLAT ? TH * ND : TH;   // planes and rows of the workgroup's tile
+  constexpr int TD2 = TDP + 2, TH2 = THT + 2;
   constexpr int P = TWC == 32 ? 36 : 20;   // LDS row pitch in 16-byte units: w in [w0-2, w0+TW+2)
   constexpr int PAIRS = (TW + 4) / 2;
   constexpr int CIG_UNITS = TD2 * TH2 * P;
@@ -134,7 +137,7 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     const int th = t % a.tiles_h; t /= a.tiles_h;
     const int td = t % a.tiles_d;
     const int n = t / a.tiles_d;
-    const int w0 = tw * TW, h0 = th * TH, ps0 = td * ND;
+    const int w0 = tw * TW, h0 = th * THT, ps0 = td * TDP;
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
       const int m = item_meta[r];
@@ -233,7 +236,7 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   };
   init_acc();
 
-  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2 + j / TWC) * P + (j % TWC) + 1;
+  const int lane_unit = (lane >> 5) * CIG_UNITS + ((FLAT ? 0 : wd) * TH2 + (FLAT ? wd * TH : 0) + j / TWC) * P + (j % TWC) + 1;
 
   const int a_voff = ((wave_active ? co_blk : 0) * a.nchunks * 27 * 64 + lane) * 16;
   auto load_a = [&](int c, int step, uint4 (&dst)[3]) {
@@ -296,7 +299,7 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     const int th = t % a.tiles_h; t /= a.tiles_h;
     const int td = t % a.tiles_d;
     const int n = t / a.tiles_d;
-    const int w0 = tw * TW, h0 = th * TH, ps = td * ND + wd;
+    const int w0 = tw * TW, h0 = th * THT + (FLAT ? wd * TH : 0), ps = td * TDP + (FLAT ? 0 : wd);
     if (!wave_active || ps >= a.out.ds) return;
     const int64_t gp = a.out.doff + ps - a.out.hlo;
     const bool inside = gp >= 0 && gp < a.out.dglob;
@@ -451,15 +454,16 @@ size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   return b;
 }
 
-template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT = false>
+template <int NCB, int ND, int TWC, bool MASKED, bool VEC, bool SPLIT = false, bool FLAT = false>
 static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* mask, const uint4* wp, const float* bias,
                                  bf16_t* out, MfmaArgs a, int n, hipStream_t stream) {
   constexpr int RPB = 32 / TWC, TH = 4 * RPB;
   constexpr int P = TWC == 32 ? 36 : 20;
-  constexpr size_t lds_bytes = (size_t)2 * 2 * (ND + 2) * (TH + 2) * P * 16;
+  constexpr int TDP = FLAT ? 1 : ND, THT = FLAT ? TH * ND : TH;
+  constexpr size_t lds_bytes = (size_t)2 * 2 * (TDP + 2) * (THT + 2) * P * 16;
   a.tiles_w = (int)cdiv(a.out.w, TWC);
-  a.tiles_h = (int)cdiv(a.out.h, TH);
-  a.tiles_d = (int)cdiv(a.out.ds, ND);
+  a.tiles_h = (int)cdiv(a.out.h, THT);
+  a.tiles_d = (int)cdiv(a.out.ds, TDP);
   int64_t ntiles = (int64_t)n * a.tiles_d * a.tiles_h * a.tiles_w;
   int64_t gy = cdiv(a.ncoblk, NCB);
   if (ntiles >= ((int64_t)1 << 31) || gy > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
@@ -467,7 +471,7 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   // one resident workgroup per CU (LDS-limited), spread over the output-channel groups
   const int num_cu = static_cast<Handle*>(handle)->num_cu;
   int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / (gy * a.csplit)));
-  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED, VEC, SPLIT>;
+  auto kern = conv3d_mfma_kernel<NCB, ND, TWC, MASKED, VEC, SPLIT, FLAT>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
@@ -484,6 +488,10 @@ static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mas
                                bf16_t* out, const MfmaArgs& a, int n, hipStream_t s) {
   const bool wide = a.out.w > 16;
   const bool two_cb = a.cout_k > 32;
+  // one- or two-plane outputs with more than 32 channels and enough rows: the row-group layout
+  const bool flat = two_cb && a.out.ds <= 2 && a.csplit == 1;
+  if (flat && wide && a.out.h >= 16) return launch_variant<2, 4, 32, MASKED, VEC, false, true>(handle, in, mask, wp, bias, out, a, n, s);
+  if (flat && !wide && a.out.h >= 32) return launch_variant<2, 4, 16, MASKED, VEC, false, true>(handle, in, mask, wp, bias, out, a, n, s);
   if (wide) {
     return two_cb ? launch_variant<2, 4, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s)
                   : launch_variant<1, 8, 32, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);

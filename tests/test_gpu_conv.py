@@ -219,7 +219,7 @@ def test_main_halo_split_is_bit_exact(dtype, cin, cout, W, exact):
     calls on plane-run views of the same buffers; together they must reproduce the whole-slab call bit for bit."""
     import torch
     import paper_2007_12856_amd as h3d
-    N, D, H = 2, 9, 10
+    N, D, H = 2, 9, 18
     w, bias = _weights(cin, cout, dtype, 50)
     wd, bd = to_dev(w, dtype), to_dev(bias, "f32")
     xo, xg = slab_pair(synth.flat("normal", SEED, 51, (N, cin, D + 2, H, W)), dtype, (1, 1), 3, D + 6)
