@@ -250,6 +250,49 @@ def mse_fwd_bwd(pred, target):
     return float(np.mean(diff * diff)), 2.0 * diff / diff.size
 
 
+# ------------------------------------------------------------ batch normalisation, the local parts (Sec. II-B, III-C)
+# Distributed batch normalisation = per-shard partial sums, an allreduce over the shards (not part of this
+# code), then a per-channel affine map.  "Local" means: sums over the interior planes of THIS slab only.
+
+def bn_stats(x: Slab):
+    """Per-channel partial statistics of the slab's interior: (sum x, sum x^2), each [C]."""
+    a = _f64(x.interior)
+    return a.sum(axis=(0, 2, 3, 4)), (a * a).sum(axis=(0, 2, 3, 4))
+
+
+def bn_finalize(s, sq, count: int, eps: float):
+    """Mean and 1/sqrt(var + eps) (biased variance, as in training) from the summed statistics of `count` voxels."""
+    mean = _f64(s) / count
+    var = _f64(sq) / count - mean * mean
+    return mean, 1.0 / np.sqrt(var + eps)
+
+
+def bn_fwd(x: Slab, mean, invstd, gamma, beta) -> Slab:
+    """y = gamma * (x - mean) * invstd + beta on the interior; halo planes of y are left zero."""
+    y = x.like(x.a.shape[1], 0, 0)
+    sh = (1, -1, 1, 1, 1)
+    y.a[...] = _f64(gamma).reshape(sh) * (_f64(x.interior) - _f64(mean).reshape(sh)) * _f64(invstd).reshape(sh) + _f64(beta).reshape(sh)
+    return y
+
+
+def bn_bwd_stats(dy: Slab, x: Slab, mean, invstd):
+    """Per-channel partial sums of the backward pass: (sum dy, sum dy * xhat) = (dbeta, dgamma) partials."""
+    sh = (1, -1, 1, 1, 1)
+    g = _f64(dy.interior)
+    xhat = (_f64(x.interior) - _f64(mean).reshape(sh)) * _f64(invstd).reshape(sh)
+    return g.sum(axis=(0, 2, 3, 4)), (g * xhat).sum(axis=(0, 2, 3, 4))
+
+
+def bn_bwd(dy: Slab, x: Slab, mean, invstd, gamma, sum_dy, sum_dy_xhat, count: int) -> Slab:
+    """dx = gamma * invstd * (dy - sum_dy / count - xhat * sum_dy_xhat / count), sums taken over all shards."""
+    sh = (1, -1, 1, 1, 1)
+    xhat = (_f64(x.interior) - _f64(mean).reshape(sh)) * _f64(invstd).reshape(sh)
+    dx = x.like(x.a.shape[1], 0, 0)
+    dx.a[...] = (_f64(gamma) * _f64(invstd)).reshape(sh) * (
+        _f64(dy.interior) - (_f64(sum_dy) / count).reshape(sh) - xhat * (_f64(sum_dy_xhat) / count).reshape(sh))
+    return dx
+
+
 def num_threads() -> int:
     return int(_L().orc_num_threads())
 
