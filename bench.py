@@ -65,6 +65,10 @@ def side_workload(args, seed):
     elif args.workload == "split256":
         net = SingleLayer(1, 64, 64, 32, 256, 32, 256, pool=False, seed=seed, split=True)
         name = "one 8-way depth shard of a 64-channel 256^3 sample: conv 64->64 whole, and as main planes + two 1-plane strips"
+    elif args.workload == "bn":
+        from paper_2007_12856_amd.nets import BatchNormLayer
+        net = BatchNormLayer(4, 16, 128, 128, seed=seed)
+        name = "local batch-normalisation passes on the first convolution's output: 4 x 16 x 128^3 bf16"
     elif args.workload == "late256":
         net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
         name = "late layer N=8, 256->256, 16^3 bf16"
@@ -145,7 +149,7 @@ def main():
     ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "shard512", "unet", "late256", "split256"],
+    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
                          "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
     args = ap.parse_args()

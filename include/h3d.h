@@ -184,6 +184,30 @@ h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, const void*
 h3d_status h3d_mse_fwd_bwd(void* handle, const void* pred, const float* target, float* loss, void* dpred, int dtype,
                            int count, void* stream);
 
+/* ---- batch normalisation, the parts local to a shard (Sec. II-B: partial statistics per partition are aggregated
+ * with an allreduce; Sec. III-C: a batch-normalisation layer costs this computation plus the allreduce of the
+ * per-channel sum and squared sum).  The allreduce itself is the caller's.  All per-channel arrays are fp32
+ * device memory of x->c entries; sums run over the INTERIOR planes of the slab only, in a fixed order (the
+ * same inputs give the same bits); halo planes are neither read nor written.  Packed tensors only.
+ * Workspace: h3d_bn_workspace_bytes(x) bytes for every call below that takes one. */
+size_t h3d_bn_workspace_bytes(void* handle, const h3d_tensor* x);
+/* sum[c] = sum of x, sqsum[c] = sum of x^2 over n, d, h, w of this shard. */
+h3d_status h3d_bn_stats(void* handle, const h3d_tensor* x, float* sum, float* sqsum, void* ws, size_t ws_bytes, void* stream);
+/* mean = sum / count, invstd = 1 / sqrt(sqsum / count - mean^2 + eps) (biased variance, clamped at 0), from the
+ * statistics summed over all shards; count = voxels per channel over all shards and samples. */
+h3d_status h3d_bn_finalize(void* handle, const float* sum, const float* sqsum, int channels, int64_t count, float eps,
+                           float* mean, float* invstd, void* stream);
+/* y = gamma * (x - mean) * invstd + beta on the interior (gamma / beta NULL = 1 / 0); y: same shard as x. */
+h3d_status h3d_bn_fwd(void* handle, const h3d_tensor* x, const float* mean, const float* invstd, const float* gamma,
+                      const float* beta, h3d_tensor* y, void* ws, size_t ws_bytes, void* stream);
+/* sum_dy[c] = sum of dy (the shard's part of dbeta), sum_dy_xhat[c] = sum of dy * (x - mean) * invstd (of dgamma). */
+h3d_status h3d_bn_bwd_stats(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const float* mean, const float* invstd,
+                            float* sum_dy, float* sum_dy_xhat, void* ws, size_t ws_bytes, void* stream);
+/* dx = gamma * invstd * (dy - sum_dy / count - xhat * sum_dy_xhat / count), with the two sums taken over all shards. */
+h3d_status h3d_bn_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const float* mean, const float* invstd,
+                      const float* gamma, const float* sum_dy, const float* sum_dy_xhat, int64_t count, h3d_tensor* dx,
+                      void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

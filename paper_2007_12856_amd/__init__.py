@@ -65,6 +65,12 @@ _SIGNATURES = {
     "h3d_dense_bwd": (ctypes.c_int, [_P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_mse_fwd_bwd": (ctypes.c_int, [_P, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, _P]),
+    "h3d_bn_workspace_bytes": (ctypes.c_size_t, [_P, _T]),
+    "h3d_bn_stats": (ctypes.c_int, [_P, _T, _P, _P, _P, ctypes.c_size_t, _P]),
+    "h3d_bn_finalize": (ctypes.c_int, [_P, _P, _P, ctypes.c_int, ctypes.c_int64, ctypes.c_float, _P, _P, _P]),
+    "h3d_bn_fwd": (ctypes.c_int, [_P, _T, _P, _P, _P, _P, _T, _P, ctypes.c_size_t, _P]),
+    "h3d_bn_bwd_stats": (ctypes.c_int, [_P, _T, _T, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]),
+    "h3d_bn_bwd": (ctypes.c_int, [_P, _T, _T, _P, _P, _P, _P, _P, ctypes.c_int64, _T, _P, ctypes.c_size_t, _P]),
 }
 
 
@@ -323,7 +329,44 @@ def h3d_mse_fwd_bwd(pred, target, loss, dpred):
     return loss, dpred
 
 
+def h3d_bn_workspace_bytes(x: Slab) -> int:
+    return int(lib().h3d_bn_workspace_bytes(handle(), ctypes.byref(x.desc())))
+
+
+def h3d_bn_stats(x: Slab, s, sq, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_bn_workspace_bytes(x))
+    _check(lib().h3d_bn_stats(handle(), ctypes.byref(x.desc()), _ptr(s), _ptr(sq), p, n, _stream()))
+    return s, sq
+
+
+def h3d_bn_finalize(s, sq, count: int, eps: float, mean, invstd):
+    _check(lib().h3d_bn_finalize(handle(), _ptr(s), _ptr(sq), s.numel(), int(count), float(eps), _ptr(mean), _ptr(invstd), _stream()))
+    return mean, invstd
+
+
+def h3d_bn_fwd(x: Slab, mean, invstd, gamma, beta, y: Slab, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_bn_workspace_bytes(x))
+    _check(lib().h3d_bn_fwd(handle(), ctypes.byref(x.desc()), _ptr(mean), _ptr(invstd), _ptr(gamma), _ptr(beta),
+                            ctypes.byref(y.desc()), p, n, _stream()))
+    return y
+
+
+def h3d_bn_bwd_stats(dy: Slab, x: Slab, mean, invstd, sum_dy, sum_dy_xhat, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_bn_workspace_bytes(x))
+    _check(lib().h3d_bn_bwd_stats(handle(), ctypes.byref(dy.desc()), ctypes.byref(x.desc()), _ptr(mean), _ptr(invstd),
+                                  _ptr(sum_dy), _ptr(sum_dy_xhat), p, n, _stream()))
+    return sum_dy, sum_dy_xhat
+
+
+def h3d_bn_bwd(dy: Slab, x: Slab, mean, invstd, gamma, sum_dy, sum_dy_xhat, count: int, dx: Slab, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_bn_workspace_bytes(x))
+    _check(lib().h3d_bn_bwd(handle(), ctypes.byref(dy.desc()), ctypes.byref(x.desc()), _ptr(mean), _ptr(invstd), _ptr(gamma),
+                            _ptr(sum_dy), _ptr(sum_dy_xhat), int(count), ctypes.byref(dx.desc()), p, n, _stream()))
+    return dx
+
+
 # short aliases
+bn_stats, bn_finalize, bn_fwd, bn_bwd_stats, bn_bwd = h3d_bn_stats, h3d_bn_finalize, h3d_bn_fwd, h3d_bn_bwd_stats, h3d_bn_bwd
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
 pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack

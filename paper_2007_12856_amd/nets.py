@@ -278,3 +278,41 @@ class SingleLayer:
 
     def conv_flops(self):
         return sum(o["flops"] for o in self.ops)
+
+
+class BatchNormLayer:
+    """The local passes of one distributed batch-normalisation layer on a slab, as a list of calls (the allreduce of
+    the per-channel sums between them is the caller's and is not part of this list)."""
+
+    def __init__(self, n, c, d, hw, dtype=torch.bfloat16, seed=0):
+        from . import bn_bwd, bn_bwd_stats, bn_finalize, bn_fwd, bn_stats
+        dev = "cuda"
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(seed)
+        rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dtype)
+        self.ws = Workspace()
+        ws, es = self.ws, 2 if dtype == torch.bfloat16 else 4
+        x, dy = Slab(rnd(n, c, d, hw, hw)), Slab(rnd(n, c, d, hw, hw))
+        y, dx = Slab(torch.empty_like(x.t)), Slab(torch.empty_like(x.t))
+        vec = lambda: torch.empty(c, device=dev)
+        s, sq, mean, invstd, sdy, sdx = vec(), vec(), vec(), vec(), vec(), vec()
+        gamma, beta = torch.ones(c, device=dev), torch.zeros(c, device=dev)
+        count, nb = n * d * hw * hw, x.t.numel() * es
+        self.keep = (x, dy, y, dx)
+        self.ops = []
+
+        def op(name, fn, nbytes):
+            self.ops.append({"name": name, "fn": fn, "flops": 0, "bytes": int(nbytes)})
+
+        op("bn_stats", lambda: bn_stats(x, s, sq, ws), nb)
+        op("bn_finalize", lambda: bn_finalize(s, sq, count, 1e-5, mean, invstd), 0)
+        op("bn_fwd", lambda: bn_fwd(x, mean, invstd, gamma, beta, y, ws), 2 * nb)
+        op("bn_bwd_stats", lambda: bn_bwd_stats(dy, x, mean, invstd, sdy, sdx, ws), 2 * nb)
+        op("bn_bwd", lambda: bn_bwd(dy, x, mean, invstd, gamma, sdy, sdx, count, dx, ws), 3 * nb)
+
+    def step(self):
+        for o in self.ops:
+            o["fn"]()
+
+    def conv_flops(self):
+        return 0
