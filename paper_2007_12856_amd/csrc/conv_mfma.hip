@@ -305,17 +305,13 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
     const bool inside = gp >= 0 && gp < a.out.dglob;
     const int row_ch = 4 * (lane >> 5);   // this lane's accumulator rows are channels 8*(r/4) + row_ch + r%4 of the block
     if (SPLIT) {
-      float* pp = a.part + ((int64_t)blockIdx.z * a.out.n + n) * a.out.nstride + (int64_t)ps * a.out.plane;
+      // the accumulators go out as they are, [split][tile][channel block][plane of the tile][b*16 + r][lane]: every
+      // store instruction writes 256 contiguous bytes; the reduction kernel undoes the mapping
+      float* pp = a.part + (((((int64_t)blockIdx.z * a.ntiles + tile) * a.ncoblk + co_blk) * ND + wd) * 64) * 64 + lane;
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const int h = h0 + b * RPB + j / TWC, w = w0 + j % TWC;
-        if (h >= H || w >= W) continue;
+      for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int co = co_blk * 32 + 8 * (r / 4) + row_ch + (r % 4);
-          if (co < a.cout_k) pp[(int64_t)co * a.out.cstride + h * W + w] = acc[b][r];
-        }
-      }
+        for (int r = 0; r < 16; ++r) pp[(b * 16 + r) * 64] = acc[b][r];
       return;
     }
     const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
@@ -398,15 +394,32 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   }
 }
 
-// out = act(bias + sum over splits of part[split]) in split order; planes outside the global volume are zero
+// out = act(bias + sum over splits of part[split]) in split order; planes outside the global volume are zero.
+// part holds raw accumulator tiles (see the SPLIT epilogue): an output element (n, co, ps, h, w) is register
+// b*16 + r of lane `lane` of the wavefront (channel block co/32, plane ps % ND) of tile (n, ps/ND, h/TH, w/TW).
+struct SplitGeo {
+  int nd, twc, rpb, ncoblk, tiles_w, tiles_h, tiles_d, ntiles;
+};
 __global__ void __launch_bounds__(256) conv_split_reduce_kernel(const float* __restrict__ part, const float* __restrict__ bias,
-                                                                bf16_t* __restrict__ out, Geo g, int splits, float slope) {
+                                                                bf16_t* __restrict__ out, Geo g, SplitGeo q, int splits, float slope) {
   const int64_t total = (int64_t)g.n * g.nstride;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= total) return;
+  int64_t t = i;
+  const int w = (int)(t % g.w); t /= g.w;
+  const int h = (int)(t % g.h); t /= g.h;
+  const int ps = (int)(t % g.ds); t /= g.ds;
+  const int co = (int)(t % g.c);
+  const int n = (int)(t / g.c);
+  const int th_rows = 4 * q.rpb;
+  const int tile = ((n * q.tiles_d + ps / q.nd) * q.tiles_h + h / th_rows) * q.tiles_w + w / q.twc;
+  const int hl = h % th_rows, wl = w % q.twc, c32 = co % 32;
+  const int b = hl / q.rpb, j = (hl % q.rpb) * q.twc + wl;
+  const int r = 4 * (c32 / 8) + c32 % 4, lane = ((c32 / 4) % 2) * 32 + j;
+  const int64_t slot = ((((int64_t)tile * q.ncoblk + co / 32) * q.nd + ps % q.nd) * 64 + (b * 16 + r)) * 64 + lane;
+  const int64_t per_split = (int64_t)q.ntiles * q.ncoblk * q.nd * 4096;
   float s = 0.f;
-  for (int sp = 0; sp < splits; ++sp) s += part[sp * total + i];
-  const int co = (int)((i / g.cstride) % g.c), ps = (int)((i / g.plane) % g.ds);
+  for (int sp = 0; sp < splits; ++sp) s += part[sp * per_split + slot];
   const int64_t gp = g.doff + ps - g.hlo;
   float v = s + (bias ? bias[co] : 0.f);
   if (!(v > 0.f)) v *= slope;
@@ -423,7 +436,11 @@ static int mfma_splits(const h3d_tensor* in, const h3d_tensor* out) {
   if (wide || wgs == 0 || wgs >= 64 || nchunks < 2 || !is_packed(out)) return 1;    // (only the narrow-volume variants come in a split form)
   int s = (int)std::min<int64_t>(nchunks, cdiv(256, wgs));
   const int64_t out_elems = (int64_t)out->n * out->c * ds * out->h * out->w;
-  while (s > 1 && s * out_elems * 4 > ((int64_t)20 << 20)) --s;   // the partials cost a write and a read
+  (void)out_elems;
+  {
+    const int64_t padded = (int64_t)out->n * cdiv(ds, nd) * cdiv(out->h, 8) * cdiv(out->w, 16) * ncoblk * nd * 4096;
+    while (s > 1 && s * padded * 4 > ((int64_t)24 << 20)) --s;   // the partials cost a write and a read
+  }
   const int cps = (int)cdiv(nchunks, s);
   return (int)cdiv(nchunks, cps);
 }
@@ -441,6 +458,13 @@ static void wp_dims(int cin_k, int cout_k, int* nchunks, int* ncoblk) {
   *ncoblk = (int)cdiv(cout_k, 32);
 }
 
+// floats of ONE split's partial tiles: the split kernels are the narrow-volume instances (16-column blocks, 8 rows)
+static size_t split_part_floats(const h3d_tensor* out) {
+  const int ncoblk = (int)cdiv(out->c, 32), nd = out->c > 32 ? 4 : 8;
+  const int64_t ds = out->halo_lo + out->d + out->halo_hi;
+  return (size_t)((int64_t)out->n * cdiv(ds, nd) * cdiv(out->h, 8) * cdiv(out->w, 16)) * ncoblk * nd * 4096;
+}
+
 static size_t mfma_wp_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   int nchunks, ncoblk;
   wp_dims(in->c, out->c, &nchunks, &ncoblk);
@@ -450,7 +474,7 @@ static size_t mfma_wp_bytes(const h3d_tensor* in, const h3d_tensor* out) {
 size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   size_t b = mfma_wp_bytes(in, out);
   const int s = mfma_splits(in, out);
-  if (s > 1) b += (size_t)s * out->n * out->c * (out->halo_lo + out->d + out->halo_hi) * out->h * out->w * sizeof(float);
+  if (s > 1) b += (size_t)s * split_part_floats(out) * sizeof(float);
   return b;
 }
 
@@ -542,8 +566,12 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
                 : pick_variant<false, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
   if (st != H3D_OK || a.csplit == 1) return st;
   const int64_t out_total = (int64_t)out->n * a.out.nstride;
+  SplitGeo q;
+  q.nd = a.cout_k > 32 ? 4 : 8; q.twc = 16; q.rpb = 2; q.ncoblk = a.ncoblk;
+  q.tiles_w = (int)cdiv(a.out.w, 16); q.tiles_h = (int)cdiv(a.out.h, 8); q.tiles_d = (int)cdiv(a.out.ds, q.nd);
+  q.ntiles = out->n * q.tiles_d * q.tiles_h * q.tiles_w;
   hipLaunchKernelGGL(conv_split_reduce_kernel, dim3((unsigned)cdiv(out_total, 256)), dim3(256), 0, stream, (const float*)a.part, bias, op,
-                     a.out, a.csplit, out_slope);
+                     a.out, q, a.csplit, out_slope);
   return launch_status(handle, "conv3d_split_reduce");
 }
 
