@@ -975,6 +975,27 @@ __global__ void __launch_bounds__(256) bfm_reduce_kernel(const float* __restrict
   }
 }
 
+// Same sum for many outputs and few chunks (the late, channel-rich layers): one thread per output adds the chunks
+// in increasing order, so every chunk row is read in whole contiguous kilobytes.
+__global__ void __launch_bounds__(256) bfm_reduce_wide_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                              float* __restrict__ db, int64_t nw, int cout, int nchunks) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nw + cout) return;
+  const bool is_w = i < nw;
+  const float* base = is_w ? part + i : part + (int64_t)nchunks * nw + (i - nw);
+  const int64_t stride = is_w ? nw : cout;
+  float s = 0.f;
+  int c = 0;
+  for (; c + 4 <= nchunks; c += 4) {
+    const float a0 = base[(int64_t)c * stride], a1 = base[(int64_t)(c + 1) * stride];
+    const float a2 = base[(int64_t)(c + 2) * stride], a3 = base[(int64_t)(c + 3) * stride];
+    s = (((s + a0) + a1) + a2) + a3;
+  }
+  for (; c < nchunks; ++c) s += base[(int64_t)c * stride];
+  if (is_w) dw[i] = s;
+  else if (db) db[i - nw] = s;
+}
+
 struct BfPlan {
   int tw, th, rbw, nrg, cib;
   bool smallci;
@@ -1169,8 +1190,12 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   }
   if (st != H3D_OK) return st;
   int64_t nw = (int64_t)a.cout * a.cin * 27;
-  hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
-                     a.cout, a.nchunks);
+  if (nw >= 65536 && a.nchunks <= 16)
+    hipLaunchKernelGGL(bfm_reduce_wide_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw, db,
+                       nw, a.cout, a.nchunks);
+  else
+    hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
+                       a.cout, a.nchunks);
   return launch_status(handle, "conv3d_bwd_filter_mfma");
 }
 
