@@ -683,21 +683,23 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
 // of a workgroup share the staged tile and split its rows into bands of RB (each band reads RB + 2 x
 // rows); their accumulators are added in wavefront order at the end.  Pitches: channel pitch = 1 and
 // slot pitch = 4 (mod 16), so the 16 columns of a block read 16 distinct bank groups.
-template <int TH>
+// NSEG segments of 32 columns per row: with NSEG = 2 a row of the tile is a whole 128-byte line of the tensors,
+// so no line is fetched by two workgroups at two different times.
+template <int TH, int NSEG>
 struct RollSmallTile {
-  static constexpr int TW = 32, XU = 6, GU = 4;
+  static constexpr int TW = 32 * NSEG, XU = 4 * NSEG + 2, GU = 4 * NSEG;
   static constexpr int PCI = cmod_ge((TH + 2) * XU, 1);
   static constexpr int NCHX = (4 * PCI + 63) / 64;            // 64-unit copy chunks of one plane (4 channels)
   static constexpr int SLOTP = cmod_ge(NCHX * 64, 4);
   static constexpr int PG = (TH * GU) | 1;
 };
 
-template <int RBW, int NW, int RB>
+template <int RBW, int NW, int RB, int NSEG>
 __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const bf16_t* __restrict__ x,
                                                                          const bf16_t* __restrict__ dz,
                                                                          float* __restrict__ part, BfmArgs a) {
   constexpr int TH = NW * RB;
-  using T = RollSmallTile<TH>;
+  using T = RollSmallTile<TH, NSEG>;
   constexpr int CO_WG = 16 * RBW;
   constexpr int SLOTP = T::SLOTP, NCHX = T::NCHX;
   constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64, NCHG = GPAD / 64;
@@ -822,9 +824,11 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     }
 
     const char* xs = reinterpret_cast<const char*>(xl) + 16 * SLOTP * ((p + kdl + 3) & 3);   // this lane's plane p + kd - 1
-    const char* xb_p = xs + xb_o;
-    const char* pe_p = xs + pe_o;
-    const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * GPAD * buf + ga_o;
+#pragma unroll
+    for (int seg = 0; seg < NSEG; ++seg) {
+    const char* xb_p = xs + xb_o + 64 * seg;
+    const char* pe_p = xs + pe_o + 64 * seg;
+    const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * GPAD * buf + ga_o + 64 * seg;
 
     uint4 blk[2];
     uint32_t pe, ne, pv, nx;
@@ -834,7 +838,7 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
       const int off = 16 * T::XU * r;
       blk[r & 1] = *reinterpret_cast<const uint4*>(xb_p + off);
       pe = *reinterpret_cast<const uint32_t*>(pe_p + off);
-      ne = *reinterpret_cast<const uint32_t*>(pe_p + off + 16 * (T::XU - 1) - 12);
+      ne = *reinterpret_cast<const uint32_t*>(pe_p + off + 16 * 5 - 12);
     };
     auto read_g = [&](int r) {
 #pragma unroll
@@ -885,6 +889,7 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
         for (int rb = 0; rb < RBW; ++rb) accdb[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[r % 3][rb], ones, accdb[rb], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
     }
 
     if (jump) {
@@ -1026,6 +1031,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
       p.rbw = cout > 16 ? 2 : 1;
       p.nrg = 1;
       p.th = p.rbw == 2 ? 16 : 32;
+      if (p.rbw == 1 && x->w >= 64) { p.tw = 64; p.th = 16; }     // whole 128-byte lines per tile row
     }
   }
   else if (x->w > 32) { p.tw = 64; p.th = 2; }
@@ -1084,12 +1090,12 @@ static h3d_status bf_roll_launch(void* handle, const bf16_t* x, const bf16_t* dz
   return H3D_OK;
 }
 
-template <int RBW, int NW, int RB>
+template <int RBW, int NW, int RB, int NSEG>
 static h3d_status bf_roll_small_launch(void* handle, const bf16_t* x, const bf16_t* dz, float* part, const BfmArgs& a, dim3 grid,
                                        hipStream_t stream) {
-  using T = RollSmallTile<NW * RB>;
+  using T = RollSmallTile<NW * RB, NSEG>;
   constexpr size_t lds_bytes = (size_t)(4 * T::SLOTP + 2 * ((16 * RBW * T::PG + 63) / 64 * 64)) * 16;
-  auto kern = bwd_filter_roll_small_kernel<RBW, NW, RB>;
+  auto kern = bwd_filter_roll_small_kernel<RBW, NW, RB, NSEG>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
@@ -1171,8 +1177,9 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
   h3d_status st;
   if (roll && x->c <= 4) {
-    if (p.rbw == 2) st = bf_roll_small_launch<2, 8, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
-    else st = bf_roll_small_launch<1, 8, 4>(handle, xp, gp, (float*)ws, a, grid, stream);
+    if (p.rbw == 2) st = bf_roll_small_launch<2, 8, 2, 1>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else if (p.tw == 64) st = bf_roll_small_launch<1, 8, 2, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else st = bf_roll_small_launch<1, 8, 4, 1>(handle, xp, gp, (float*)ws, a, grid, stream);
   } else if (roll) {
     if (p.cib == 2) {
       if (p.rbw == 2 && p.th == 6) st = bf_roll_launch<2, 2, 2, 6>(handle, xp, gp, (float*)ws, a, grid, stream);

@@ -95,6 +95,8 @@ BF_SHAPES = [
     (1, 48, 80, 2, 10, 72, 1),
     (1, 20, 16, 2, 8, 96, 0),
     (1, 24, 24, 5, 7, 33, 1),
+    (1, 4, 16, 2, 20, 72, 1),
+    (1, 2, 10, 3, 17, 128, 0),
 ]
 
 
