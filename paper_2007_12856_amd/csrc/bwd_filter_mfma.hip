@@ -69,6 +69,9 @@ struct BfmArgs {
   int64_t ntiles;             // n * d * tiles_h * tiles_w
   int tiles_per_chunk, nchunks;
   int gy, gz;                 // output-channel groups and input-channel groups of the grid
+  int wpair;                  // rolling kernel: 2 = the two 32-column tiles that share 128-byte lines go to two
+                              // neighbouring workgroups (same XCD, same time), which write separate partials
+  int npart;                  // partial tiles in the workspace = nchunks * wpair
   float mask_slope;
   int vec_ok;                 // W % 8 == 0 and 16-byte aligned bases: whole units are loaded at once
   int dma_ok;                 // every sample fits 31-bit byte offsets: tiles can be moved by buffer loads into LDS
@@ -443,13 +446,15 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
-  const int ngrp = a.gy * a.gz;
+  const int ngrp = a.gy * a.gz * a.wpair;
   int chunk, grp;
   {
     const int b = blockIdx.x, full = (a.nchunks / 8) * 8 * ngrp;
     if (b < full) { chunk = (b / (8 * ngrp)) * 8 + b % 8; grp = (b / 8) % ngrp; }
     else { const int r = b - full, rem = a.nchunks % 8; chunk = (a.nchunks / 8) * 8 + r % rem; grp = r / rem; }
   }
+  const int par = grp % a.wpair;      // which of the two 32-column tiles of a 64-column pair
+  grp /= a.wpair;
   const int zi = grp % a.gz;
   const int co0 = (grp / a.gz) * CO_WG, ci0 = zi * CI_WG;
   const int W = a.x.w, H = a.x.h, D = a.x.d;
@@ -542,10 +547,10 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
     n = r / a.tiles_h;
   }
   if (t_begin < t_end) {
-    load_plane(n, p - 1, th * TH, tw * T::TW);
-    load_plane(n, p, th * TH, tw * T::TW);
-    load_plane(n, p + 1, th * TH, tw * T::TW);
-    load_g(n, p, th * TH, tw * T::TW, 0);
+    load_plane(n, p - 1, th * TH, (tw * a.wpair + par) * T::TW);
+    load_plane(n, p, th * TH, (tw * a.wpair + par) * T::TW);
+    load_plane(n, p + 1, th * TH, (tw * a.wpair + par) * T::TW);
+    load_g(n, p, th * TH, (tw * a.wpair + par) * T::TW, 0);
   }
   int buf = 0;
   for (int tile = t_begin; tile < t_end; ++tile) {
@@ -560,8 +565,8 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
     const bool has_next = tile + 1 < t_end;
     const bool jump = has_next && p2 == 0;      // the next tile starts a new column of tiles: none of its planes is here
     if (has_next) {
-      load_g(n2, p2, th2 * TH, tw2 * T::TW, buf ^ 1);
-      if (!jump) load_plane(n2, p2 + 1, th2 * TH, tw2 * T::TW);
+      load_g(n2, p2, th2 * TH, (tw2 * a.wpair + par) * T::TW, buf ^ 1);
+      if (!jump) load_plane(n2, p2 + 1, th2 * TH, (tw2 * a.wpair + par) * T::TW);
     }
 
     const char* xs = reinterpret_cast<const char*>(xl) + 16 * SLOTP * ((p + kd + 3) & 3);   // plane p + kd - 1
@@ -639,16 +644,17 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
 
     if (jump) {
       __syncthreads();    // three of the four slots are about to be rewritten: everyone must be done with this tile
-      load_plane(n2, -1, th2 * TH, tw2 * T::TW);
-      load_plane(n2, 0, th2 * TH, tw2 * T::TW);
-      load_plane(n2, 1, th2 * TH, tw2 * T::TW);
+      load_plane(n2, -1, th2 * TH, (tw2 * a.wpair + par) * T::TW);
+      load_plane(n2, 0, th2 * TH, (tw2 * a.wpair + par) * T::TW);
+      load_plane(n2, 1, th2 * TH, (tw2 * a.wpair + par) * T::TW);
     }
     tw = tw2; th = th2; p = p2; n = n2;
     buf ^= 1;
   }
 
   // ---- partial tile -> workspace [chunk][cout][cin][27] (+ [chunk][cout] for the bias partial behind it)
-  float* pw = part + (int64_t)chunk * a.cout * a.cin * 27;
+  const int pchunk = chunk * a.wpair + par;
+  float* pw = part + (int64_t)pchunk * a.cout * a.cin * 27;
   const int ci = ci0 + cib * 16 + lc;
   if (ci < a.cin) {
 #pragma unroll
@@ -666,7 +672,7 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
       }
   }
   if (do_db && lc == 0) {
-    float* pb = part + (int64_t)a.nchunks * a.cout * a.cin * 27 + (int64_t)chunk * a.cout;
+    float* pb = part + (int64_t)a.npart * a.cout * a.cin * 27 + (int64_t)pchunk * a.cout;
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
@@ -1002,7 +1008,7 @@ __global__ void __launch_bounds__(256) bfm_reduce_wide_kernel(const float* __res
 }
 
 struct BfPlan {
-  int tw, th, rbw, nrg, cib;
+  int tw, th, rbw, nrg, cib, wpair;
   bool smallci;
   int tiles_w, tiles_h;
   int64_t ntiles;
@@ -1038,9 +1044,13 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   else if (x->w > 16) { p.tw = 32; p.th = 4; }
   else { p.tw = 16; p.th = 4; }
   p.tiles_w = (int)cdiv(x->w, p.tw);
+  // rolling kernel, 32-column tiles: neighbouring tiles share 128-byte lines, so they are walked as pairs by two
+  // workgroups side by side (the pair index counts as a workgroup group, not as tiles)
+  p.wpair = (roll && x->c > 4 && p.tiles_w >= 2) ? 2 : 1;
+  p.tiles_w = (int)cdiv(p.tiles_w, p.wpair);
   p.tiles_h = (int)cdiv(x->h, p.th);
   p.ntiles = (int64_t)x->n * x->d * p.tiles_h * p.tiles_w;
-  int64_t groups = cdiv(cout, 16 * p.rbw * p.nrg) * cdiv(x->c, 16 * p.cib);
+  int64_t groups = cdiv(cout, 16 * p.rbw * p.nrg) * cdiv(x->c, 16 * p.cib) * p.wpair;
   // Number of voxel chunks: enough workgroups to fill 256 CUs several times over, at least 4 tiles
   // per workgroup, and partials (chunks x Cout x Cin x 27 floats) that stay small next to the tensors.
   int64_t per_chunk_bytes = std::max<int64_t>(1, (int64_t)cout * x->c * 27 * 4);
@@ -1069,7 +1079,10 @@ bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
 size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
   // which kernel runs also depends on alignment and on the fused mask, unknown here: size for either
   int nchunks = bf_plan_mfma(x, dz->c, false).nchunks;
-  if (bf_roll_shape(x)) nchunks = std::max(nchunks, bf_plan_mfma(x, dz->c, true).nchunks);
+  if (bf_roll_shape(x)) {
+    const BfPlan pr = bf_plan_mfma(x, dz->c, true);
+    nchunks = std::max(nchunks, pr.nchunks * pr.wpair);
+  }
   return (size_t)nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
 }
 
@@ -1163,6 +1176,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   a.cin = x->c; a.cout = dz->c;
   a.tiles_w = p.tiles_w; a.tiles_h = p.tiles_h; a.ntiles = p.ntiles;
   a.tiles_per_chunk = p.tiles_per_chunk; a.nchunks = p.nchunks;
+  a.wpair = p.wpair; a.npart = p.nchunks * p.wpair;
   a.mask_slope = mask_slope;
   a.dma_ok = dma_ok;
   a.vec_ok = vec_ok;
@@ -1170,8 +1184,8 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   if (gy > 65535 || gz > 65535) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many channels");
   if (p.ntiles >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many tiles");
   a.gy = (int)gy; a.gz = (int)gz;
-  if ((int64_t)p.nchunks * gy * gz >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many workgroups");
-  dim3 grid((unsigned)((int64_t)p.nchunks * gy * gz));
+  if ((int64_t)p.nchunks * gy * gz * p.wpair >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_bwd_filter: too many workgroups");
+  dim3 grid((unsigned)((int64_t)p.nchunks * gy * gz * p.wpair));
   const bf16_t* xp = (const bf16_t*)x->data;
   const bf16_t* gp = (const bf16_t*)dz->data;
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
@@ -1197,12 +1211,12 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   }
   if (st != H3D_OK) return st;
   int64_t nw = (int64_t)a.cout * a.cin * 27;
-  if (nw >= 65536 && a.nchunks <= 16)
+  if (nw >= 65536 && a.npart <= 16)
     hipLaunchKernelGGL(bfm_reduce_wide_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw, db,
-                       nw, a.cout, a.nchunks);
+                       nw, a.cout, a.npart);
   else
     hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
-                       a.cout, a.nchunks);
+                       a.cout, a.npart);
   return launch_status(handle, "conv3d_bwd_filter_mfma");
 }
 
