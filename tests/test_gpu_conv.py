@@ -129,6 +129,12 @@ THIN_SHAPES = [
     (2, 3, 12, 3, 6, 66, 0),
     (1, 8, 16, 6, 10, 32, 1),
     (1, 1, 7, 2, 5, 130, 0),
+    # at most 4 channels, W a multiple of 8, H >= 8: the row-streaming variant (several depth tiles with a ragged
+    # last one, several row segments, one to three column tiles)
+    (2, 4, 16, 7, 33, 136, 1),
+    (1, 2, 9, 9, 8, 64, 0),
+    (1, 3, 16, 4, 20, 72, 1),
+    (1, 4, 12, 2, 70, 32, 1),
 ]
 
 
