@@ -279,23 +279,39 @@ __global__ void __launch_bounds__(T_THREADS, 2) conv3d_thin_kernel(const bf16_t*
 // Row-streaming variant for at most 4 output channels (the first layer's backward-data pass).
 //
 // The tap-row folding makes the accumulator walk down the rows by itself, so a workgroup does not need a
-// tile of rows at all: it owns 4 output planes x 64 columns and streams along H.  Per input row it keeps the
-// six planes of that row in an LDS ring of three rows (41 KB: three workgroups per CU), computes on row t
-// while row t+2 is being transposed into the ring and the global loads of rows t+3, t+4 are in flight.
+// tile of rows at all: it owns 4 output planes x 64 or 128 columns and streams along H.  Per input row it keeps
+// the six planes of that row in an LDS ring of three rows, computes on row t while row t+2 is being transposed
+// into the ring and the global loads of the rows after it are in flight.
 //   * no row halo: every input row is staged once per workgroup and its 9-tap MFMAs are issued once;
 //   * with <= 4 output channels the 32 MFMA rows hold TWO output planes: row 8 kh + 4 o + m is channel m of
 //     plane o under tap row kh, and the A fragment of input plane dz carries tap kd = dz - o in the rows of
-//     plane o.  A wavefront = 2 planes x 32 columns, 12 MFMAs (4 input planes x 3 kw) per row, and the two
-//     lane halves of the accumulator are the two planes, so every lane stores in the epilogue;
-//   * wavefront pairs take turns staging: pair j owns the rows t = j (mod 2), one item (ci-group, plane,
-//     group of 8 columns: 8 loads, 32 byte-permutes, 8 LDS stores) per lane.
-constexpr int R_TD = 4;
-constexpr int R_NPL = R_TD + 2;
-constexpr int R_SLOT = 2 * R_NPL * T_P;        // 16-byte units of one ring slot: [ci-group][plane][position]
+//     plane o.  A wavefront = 2 planes x 64 columns: two accumulator chains of 12 MFMAs (4 input planes x 3 kw)
+//     per row, and the two lane halves of an accumulator are the two planes;
+//   * staging: one item per lane and row = (ci-group, plane, 8 columns): 8 loads of 16 bytes (one per channel),
+//     an 8 x 8 transpose by 32 byte-permutes, eight 16-byte LDS stores.  Few, wide vector-memory instructions:
+//     what the memory pipeline of a CU charges for is their number, not their bytes;
+//   * for the same reason a finished output row does not leave as 2-byte stores: the wavefront transposes it
+//     through 1 KB of LDS of its own and every lane stores 8 consecutive columns of one channel (16 bytes).
 constexpr int R_RING = 3;
-constexpr int R_NG = T_TW / 8 + 2;
-constexpr int R_ITEMS = 2 * R_NPL * R_NG;      // staging items of a row
-static_assert(R_ITEMS <= 128, "one item per lane of a wavefront pair");
+template <int TD, int CB>
+struct RollCfg {
+  static constexpr int TW = 32 * CB;                          // tile columns: CB MFMA column blocks, two per wavefront
+  // a row of the ring: TW + 2 units (16 bytes: 8 channels of one voxel) in column order, unit x = column w0 - 1 + x:
+  // the 8 consecutive lanes of a ds_read_b128 phase read 8 consecutive units, 8 distinct 16-byte bank groups.  With
+  // an odd row pitch the staging stores (8 consecutive lanes = 2 neighbouring column groups x 4 rows) meet two by two.
+  static constexpr int P = (TW + 2) | 1;
+  static constexpr int NPL = TD + 2;
+  static constexpr int SLOT = 2 * NPL * P;                    // 16-byte units of one ring slot: [ci-group][plane][unit]
+  static constexpr int GROUPS = TW / 8;
+  static constexpr int INNER = 2 * NPL * GROUPS;              // staging items of a row: whole column groups of the tile
+  static constexpr int ITEMS = INNER + 2 * NPL * 2;           // .. and the groups left and right of it
+  static constexpr int WAVES = (TD / 2) * (CB / 2);
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int OSTAGE = 72;                           // 16-byte units per wavefront: 2 planes x (32 + 4 pad)
+  static constexpr size_t LDS_BYTES = ((size_t)R_RING * SLOT + WAVES * OSTAGE) * 16;
+  static_assert(ITEMS <= THREADS, "one item per lane");
+  static_assert(CB % 2 == 0 && TD % 2 == 0 && (2 * NPL) % 4 == 0 && GROUPS % 2 == 0, "tile shape");
+};
 
 struct ThinRollArgs {
   Geo in, out;
@@ -326,9 +342,12 @@ __global__ void pack_w_thin_roll_kernel(const bf16_t* __restrict__ w, bf16_t* __
 // the rows ahead stay in flight across the barrier.)
 __device__ __forceinline__ void ring_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-__global__ void __launch_bounds__(256, 3) conv3d_thin_roll_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
-                                                                  const float* __restrict__ bias, bf16_t* __restrict__ out,
-                                                                  ThinRollArgs a) {
+template <int TD, int CB, int NSET, int WPS>
+__global__ void __launch_bounds__((RollCfg<TD, CB>::THREADS), WPS) conv3d_thin_roll_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
+                                                                       const float* __restrict__ bias, bf16_t* __restrict__ out,
+                                                                       ThinRollArgs a) {
+  using Cfg = RollCfg<TD, CB>;
+  constexpr int NPL = Cfg::NPL, SLOT = Cfg::SLOT, INNER = Cfg::INNER, ITEMS = Cfg::ITEMS, GROUPS = Cfg::GROUPS, P = Cfg::P;
   extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63, wd = tid >> 6;
   const int W = a.in.w, H = a.in.h;
@@ -338,7 +357,7 @@ __global__ void __launch_bounds__(256, 3) conv3d_thin_roll_kernel(const bf16_t* 
   const int seg = t0 % a.segs; t0 /= a.segs;
   const int td = t0 % a.tiles_d;
   const int n = t0 / a.tiles_d;
-  const int w0 = tw * T_TW, ps0 = td * R_TD;
+  const int w0 = tw * Cfg::TW, ps0 = td * TD;
   const int ha = seg * a.seg_rows, hb = min(H, ha + a.seg_rows);
   const int nsteps = hb - ha + 2;         // input rows ha-1 .. hb
 
@@ -346,11 +365,23 @@ __global__ void __launch_bounds__(256, 3) conv3d_thin_roll_kernel(const bf16_t* 
 #pragma unroll
   for (int s = 0; s < 12; ++s) A[s] = __builtin_bit_cast(bf16x8, wp[s * 64 + lane]);
 
-  // ---- staging role of this lane
-  const int pair = wd >> 1;
-  const int item = (wd & 1) * 64 + lane;
-  const int grp = item % R_NG;
-  const int dzs = (item / R_NG) % R_NPL, cig = item / (R_NG * R_NPL);
+  // ---- staging role of this lane.  The first INNER items are the column groups of the tile (8 consecutive lanes =
+  // 2 neighbouring groups x 4 rows, "row" = ci-group * NPL + plane), the rest the groups left and right of it,
+  // which only contribute the column next to the tile.
+  const int item = tid;
+  const bool inner = item < INNER;
+  const bool edge = !inner && item < ITEMS;
+  const bool left = item - INNER < 2 * NPL;
+  int grp, rowid;
+  if (inner) {
+    const int q = item >> 3;                         // (row group of 4, pair of column groups)
+    grp = 2 * (q % (GROUPS / 2)) + (item & 1);
+    rowid = 4 * (q / (GROUPS / 2)) + ((item >> 1) & 3);
+  } else {
+    grp = left ? -1 : GROUPS;
+    rowid = (item - INNER) % (2 * NPL);
+  }
+  const int dzs = rowid % NPL, cig = rowid / NPL;
   const __amdgpu_buffer_rsrc_t rs_in = thin_rsrc(in + n * a.in.nstride, (uint32_t)a.in.nstride * 2);
   bool st_ok;
   int st_base;
@@ -358,100 +389,187 @@ __global__ void __launch_bounds__(256, 3) conv3d_thin_roll_kernel(const bf16_t* 
     const int p_in = ps0 - a.out.hlo + dzs - 1;       // local interior index of the input plane
     const int64_t gq = a.in.doff + p_in;
     const int sp = p_in + a.in.hlo;
-    const int wc = w0 - 8 + 8 * grp;
-    st_ok = item < R_ITEMS && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && wc >= 0 && wc + 8 <= W;
+    const int wc = w0 + 8 * grp;
+    st_ok = item < ITEMS && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && wc >= 0 && wc + 8 <= W;
     st_base = 2 * (cig * 8 * (int)a.in.cstride + sp * (int)a.in.plane + wc);
   }
   const int nch = a.cin_k - cig * 8;
-  const int st_dst = (cig * R_NPL + dzs) * T_P + grp - 1;
-  u32x4 v[8];
-  auto issue = [&](int t) {      // global loads of input row ha - 1 + t
+  // column w0 + 8 grp + c is unit 8 grp + 1 + c of its row; the left group's last column is unit 0, the right group's
+  // first column unit TW + 1
+  const int st_p0 = rowid * P + (inner ? 8 * grp + 1 : (left ? 0 : Cfg::TW + 1));
+  auto issue = [&](u32x4 (&v)[8], int t) {      // global loads of input row ha - 1 + t
     const int h = ha - 1 + t;
     const int vo = (st_ok && h >= 0 && h < H && t < nsteps) ? st_base + 2 * h * W : T_OOB;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       v[e] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, e < nch ? vo : T_OOB, __builtin_amdgcn_readfirstlane(2 * e * (int)a.in.cstride), 0);
   };
-  auto write = [&](int slot) {   // 8 x 8 transpose into the ring
-    if (item >= R_ITEMS) return;
-    uint4* dst = lds + slot * R_SLOT + st_dst;
+  auto write = [&](const u32x4 (&v)[8], int slot) {   // 8 x 8 transpose into the ring
+    uint4* dst = lds + slot * SLOT + st_p0;
+    if (inner) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint4 u0, u1;
-      u0.x = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x05040100); u1.x = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x07060302);
-      u0.y = __builtin_amdgcn_perm(v[3][j], v[2][j], 0x05040100); u1.y = __builtin_amdgcn_perm(v[3][j], v[2][j], 0x07060302);
-      u0.z = __builtin_amdgcn_perm(v[5][j], v[4][j], 0x05040100); u1.z = __builtin_amdgcn_perm(v[5][j], v[4][j], 0x07060302);
-      u0.w = __builtin_amdgcn_perm(v[7][j], v[6][j], 0x05040100); u1.w = __builtin_amdgcn_perm(v[7][j], v[6][j], 0x07060302);
-      const int u = 8 * grp - 6 + 2 * j;
-      if (u >= 1 && u <= T_NU - 2) dst[t_pos(2 * j + 3)] = u0;
-      if (u + 1 >= 1 && u + 1 <= T_NU - 2) dst[t_pos(2 * j + 4)] = u1;
+      for (int j = 0; j < 4; ++j) {       // dword j of each channel = columns 2j, 2j+1 of the group
+        uint4 u0, u1;
+        u0.x = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x05040100); u1.x = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x07060302);
+        u0.y = __builtin_amdgcn_perm(v[3][j], v[2][j], 0x05040100); u1.y = __builtin_amdgcn_perm(v[3][j], v[2][j], 0x07060302);
+        u0.z = __builtin_amdgcn_perm(v[5][j], v[4][j], 0x05040100); u1.z = __builtin_amdgcn_perm(v[5][j], v[4][j], 0x07060302);
+        u0.w = __builtin_amdgcn_perm(v[7][j], v[6][j], 0x05040100); u1.w = __builtin_amdgcn_perm(v[7][j], v[6][j], 0x07060302);
+        dst[2 * j] = u0;
+        dst[2 * j + 1] = u1;
+      }
+    } else if (edge) {
+      // left group: its last column (high half of dword 3) is unit 0; right group: its first column is unit TW + 1
+      const uint32_t sel = left ? 0x07060302 : 0x05040100;
+      uint4 u;
+      u.x = __builtin_amdgcn_perm(left ? v[1][3] : v[1][0], left ? v[0][3] : v[0][0], sel);
+      u.y = __builtin_amdgcn_perm(left ? v[3][3] : v[3][0], left ? v[2][3] : v[2][0], sel);
+      u.z = __builtin_amdgcn_perm(left ? v[5][3] : v[5][0], left ? v[4][3] : v[4][0], sel);
+      u.w = __builtin_amdgcn_perm(left ? v[7][3] : v[7][0], left ? v[6][3] : v[6][0], sel);
+      dst[0] = u;
     }
   };
 
-  // ---- compute role: planes ps0 + 2 pp + {0, 1}, columns w0 + 32 cb ..
-  const int pp = wd >> 1, cb = wd & 1;
+  // ---- compute role: planes ps0 + 2 pp + {0, 1}, columns w0 + 64 cp .. + 63 (column blocks 2 cp and 2 cp + 1)
+  const int pp = wd / (CB / 2), cp = wd % (CB / 2);
   const int half = lane >> 5, col = lane & 31;
-  const int ps = ps0 + 2 * pp + half;
-  const int64_t gp = a.out.doff + ps - a.out.hlo;
-  const bool inside = gp >= 0 && gp < a.out.dglob;          // planes outside the global volume are written as zeros
-  const __amdgpu_buffer_rsrc_t rs_out = thin_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
   float bv[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) bv[i] = (bias && i < a.cout_k) ? bias[i] : 0.f;
-  const int wq = w0 + cb * 32 + col;
-  const int out_base = (ps < a.out.ds && wq < W) ? 2 * (ps * (int)a.out.plane + wq) : T_OOB;
-  int lane_off[3];
+  const bool inside = [&] {          // planes outside the global volume are written as zeros
+    const int64_t gp = a.out.doff + (ps0 + 2 * pp + half) - a.out.hlo;
+    return gp >= 0 && gp < a.out.dglob;
+  }();
+  // output transpose: [plane o][channel i][64 columns] bf16, planes 36 units apart; lane j then owns the unit
+  // (o, i, column group g) = 8 consecutive columns of one channel
+  bf16_t* ost_w = reinterpret_cast<bf16_t*>(lds + R_RING * SLOT + wd * Cfg::OSTAGE + half * 36) + col;
+  const uint4* ost_r = lds + R_RING * SLOT + wd * Cfg::OSTAGE + (lane >> 5) * 36 + (lane & 31);
+  const __amdgpu_buffer_rsrc_t rs_out = thin_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
+  int out_base;
+  {
+    const int o = lane >> 5, i = (lane >> 3) & 3, g = lane & 7;
+    const int ps = ps0 + 2 * pp + o, wq = w0 + 64 * cp + 8 * g;
+    out_base = (ps < a.out.ds && wq < W && i < a.cout_k) ? 2 * (i * (int)a.out.cstride + ps * (int)a.out.plane + wq) : T_OOB;
+  }
+  const int lane_off = (half * NPL + 2 * pp) * P + cp * 64 + col;      // unit of column w0 + 64 cp + col - 1 (tap kw = 0)
+  f32x16 acc[2];
 #pragma unroll
-  for (int kw = 0; kw < 3; ++kw) lane_off[kw] = (half * R_NPL + 2 * pp) * T_P + cb * 4 + t_pos(col + 2 + kw);
-  f32x16 acc;
+  for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
-  // ---- prologue: rows 0 and 1 into the ring, rows 2 and 3 in flight
-  issue(pair);
-  write(pair);
-  issue(pair + 2);
+  // ---- prologue: rows 0 and 1 into the ring, rows 2 .. 1 + NSET in flight (row r waits in register set r % NSET)
+  u32x4 v[NSET][8];
+  {
+    u32x4 v1[8];
+    issue(v[0], 0);
+    issue(v1, 1);
+    write(v[0], 0);
+    write(v1, 1);
+  }
+#pragma unroll
+  for (int r = 2; r < 2 + NSET; ++r) issue(v[r % NSET], r);
   ring_barrier();
 
+  // B fragments are read R_AHEAD (dz, kw) steps ahead, across the row boundary: row t + 1 is complete in its slot
+  // before row t's barrier (it was written during row t - 1), so the queue never drains between rows
+  constexpr int R_AHEAD = 3;
+  static_assert(12 % R_AHEAD == 0, "fragment s lives in queue entry s % R_AHEAD in every row");
+  const uint4* fp = lds + lane_off;
+  uint4 bq[R_AHEAD][2];
+#pragma unroll
+  for (int s = 0; s < R_AHEAD; ++s)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) bq[s][cb] = fp[(s / 3) * P + s % 3 + 32 * cb];
+
   int slot = 0;
-  for (int t = 0; t < nsteps; ++t) {
-    const uint4* rowbase = lds + slot * R_SLOT;
-    const uint4* fp[3] = {rowbase + lane_off[0], rowbase + lane_off[1], rowbase + lane_off[2]};
-    uint4 bq[3];
-    bq[0] = fp[0][0];
-    bq[1] = fp[1][0];
+  for (int t0s = 0; t0s < nsteps; t0s += NSET) {
+#pragma unroll
+  for (int k = 0; k < NSET; ++k) {
+    const int t = t0s + k;
+    if (t >= nsteps) break;
     // slide: what was accumulated under tap row kh now waits for tap row kh + 1 of the next input row
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[8 + i] = acc[4 + i];
-      acc[4 + i] = acc[i];
-      acc[i] = 0.f;
-    }
-#pragma unroll
-    for (int s = 0; s < 12; ++s) {
-      if (s + 2 < 12) bq[(s + 2) % 3] = fp[(s + 2) % 3][((s + 2) / 3) * T_P];
-      __builtin_amdgcn_sched_barrier(0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], __builtin_bit_cast(bf16x8, bq[s % 3]), acc, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // staging turn: row t + 2 into the slot that row t - 1 has just left, then the loads of row t + 4
-    if ((t & 1) == pair) {
-      if (t + 2 < nsteps) write(slot == 0 ? 2 : slot - 1);
-      if (t + 4 < nsteps) issue(t + 4);
-    }
-    if (t >= 2) {
-      const int vo = out_base == T_OOB ? T_OOB : out_base + 2 * (ha + t - 2) * W;
+    for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float val = acc[8 + i] + bv[i];
-        if (!(val > 0.f)) val *= a.out_slope;
-        __builtin_amdgcn_raw_buffer_store_b16((short)pack_bf16x2(inside ? val : 0.f, 0.f), rs_out, i < a.cout_k ? vo : T_OOB,
-                                              __builtin_amdgcn_readfirstlane(2 * i * (int)a.out.cstride), 0);
+        acc[cb][8 + i] = acc[cb][4 + i];
+        acc[cb][4 + i] = acc[cb][i];
+        acc[cb][i] = 0.f;
       }
+#pragma unroll
+    for (int s = 0; s < 12; ++s) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], __builtin_bit_cast(bf16x8, bq[s % R_AHEAD][cb]), acc[cb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + R_AHEAD == 12) fp += (slot == R_RING - 1 ? -(R_RING - 1) : 1) * SLOT;      // the queue moves on to the next row's slot
+      const int f = (s + R_AHEAD) % 12;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) bq[s % R_AHEAD][cb] = fp[(f / 3) * P + f % 3 + 32 * cb];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // row t + 2 goes into the slot that row t - 1 has just left; then the loads of row t + 2 + NSET
+    if (t + 2 < nsteps) write(v[(k + 2) % NSET], slot == 0 ? 2 : slot - 1);
+    if (t + 2 + NSET < nsteps) issue(v[(k + 2) % NSET], t + 2 + NSET);
+    if (t >= 2) {
+      // finished output row ha + t - 2: bias, activation, bf16, transposed through this wavefront's LDS patch
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float val = acc[cb][8 + i] + bv[i];
+          if (!(val > 0.f)) val *= a.out_slope;
+          ost_w[i * 64 + cb * 32] = (bf16_t)pack_bf16x2(inside ? val : 0.f, 0.f);
+        }
+      asm volatile("" ::: "memory");     // the 16-byte read below aliases the 2-byte writes above
+      const uint4 o4 = *ost_r;
+      const int vo = out_base == T_OOB ? T_OOB : out_base + 2 * (ha + t - 2) * W;
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o4), rs_out, vo, 0, 0);
     }
     ring_barrier();
     slot = slot == R_RING - 1 ? 0 : slot + 1;
   }
+  }
+}
+
+template <int TD, int CB, int NSET, int WPS>
+h3d_status launch_thin_roll(void* handle, const h3d_tensor* in, const float* bias, h3d_tensor* out, const ThinArgs& a, float out_slope,
+                            const void* wp, hipStream_t stream) {
+  using Cfg = RollCfg<TD, CB>;
+  auto kern = conv3d_thin_roll_kernel<TD, CB, NSET, WPS>;
+  static int wgs_per_cu = 0;
+  if (wgs_per_cu == 0) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES) !=
+        hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", Cfg::LDS_BYTES);
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, Cfg::THREADS, Cfg::LDS_BYTES) != hipSuccess || nb < 1) nb = 1;
+    wgs_per_cu = nb;
+    if (getenv("H3D_DEBUG")) fprintf(stderr, "thin_roll<%d,%d>: %d workgroups per CU\n", TD, CB, nb);
+  }
+  ThinRollArgs r;
+  r.in = a.in; r.out = a.out; r.cin_k = a.cin_k; r.cout_k = a.cout_k; r.out_slope = out_slope;
+  r.tiles_w = (int)cdiv(out->w, Cfg::TW);
+  r.tiles_d = (int)cdiv(a.out.ds, TD);
+  // pick the number of row segments that fills the chip's workgroup slots in the fewest rounds (a segment pays for
+  // 2 extra rows and the pipeline fill)
+  const int64_t base = (int64_t)out->n * r.tiles_d * r.tiles_w;
+  const int64_t slots = (int64_t)wgs_per_cu * static_cast<Handle*>(handle)->num_cu;
+  int best = 1;
+  int64_t best_cost = -1;
+  for (int s = 1; s <= out->h / 8; ++s) {
+    const int64_t cost = cdiv(base * s, slots) * (cdiv(out->h, s) + 5);
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = s; }
+  }
+  if (getenv("H3D_SEGS") && atoi(getenv("H3D_SEGS")) > 0) best = atoi(getenv("H3D_SEGS"));
+  r.seg_rows = (int)cdiv(out->h, best);
+  r.segs = (int)cdiv(out->h, r.seg_rows);
+  const int64_t nwg = base * r.segs;
+  if (nwg >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, (const bf16_t*)in->data, (const uint4*)wp, bias,
+                     (bf16_t*)out->data, r);
+  return launch_status(handle, "conv3d_thin_roll");
 }
 
 }  // namespace
@@ -479,29 +597,12 @@ h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const 
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;
   // whole 16-byte column groups: faster staging (a quarter of the load instructions)
   const bool vec8 = in->w % 8 == 0 && (uintptr_t)in->data % 16 == 0;
-  if (vec8 && a.cout_k <= 4 && out->h >= 8) {
-    // row streaming: pick the number of row segments that fills the chip's 3 workgroup slots per CU in the
-    // fewest rounds (a segment pays for 2 extra rows and the pipeline fill)
-    ThinRollArgs r;
-    r.in = a.in; r.out = a.out; r.cin_k = a.cin_k; r.cout_k = a.cout_k; r.out_slope = out_slope;
-    r.tiles_w = a.tiles_w;
-    r.tiles_d = (int)cdiv(a.out.ds, R_TD);
-    const int64_t base = (int64_t)out->n * r.tiles_d * r.tiles_w;
-    const int64_t slots = 3 * (int64_t)static_cast<Handle*>(handle)->num_cu;
-    int best = 1;
-    int64_t best_cost = -1;
-    for (int s = 1; s <= out->h / 8; ++s) {
-      const int64_t cost = cdiv(base * s, slots) * (cdiv(out->h, s) + 5);
-      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = s; }
-    }
-    r.seg_rows = (int)cdiv(out->h, best);
-    r.segs = (int)cdiv(out->h, r.seg_rows);
-    const int64_t nwg = base * r.segs;
-    if (nwg >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  if (vec8 && a.cout_k <= 4 && out->h >= 8 && (uintptr_t)out->data % 16 == 0) {
     hipLaunchKernelGGL(pack_w_thin_roll_kernel, dim3(24), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin, cout, transpose ? 1 : 0);
-    hipLaunchKernelGGL(conv3d_thin_roll_kernel, dim3((unsigned)nwg), dim3(256), (size_t)R_RING * R_SLOT * 16, stream,
-                       (const bf16_t*)in->data, (const uint4*)ws, bias, (bf16_t*)out->data, r);
-    return launch_status(handle, "conv3d_thin_roll");
+    // wide rows: 128-column tiles (a 64-column tile also pulls in the neighbouring 128-byte line of every row for
+    // the one column next to it)
+    if (out->w > 64) return launch_thin_roll<4, 4, 1, 2>(handle, in, bias, out, a, out_slope, ws, stream);
+    return launch_thin_roll<4, 2, 1, 2>(handle, in, bias, out, a, out_slope, ws, stream);
   }
   hipLaunchKernelGGL(pack_w_thin_kernel, dim3(18), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws, cin, cout, transpose ? 1 : 0);
   constexpr size_t lds_bytes = (size_t)2 * T_CIG_UNITS * 16;
