@@ -159,19 +159,24 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
         for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb][m], B, acc[vb][rb], 0, 0, 0);
       }
     }
-    // bias + activation, transpose through LDS: ot[wave][co][w]
-    __syncthreads();   // previous row's readers are done
+    // bias + activation, transpose through LDS: ot[wave][co][w].  The patch belongs to this wavefront alone and a
+    // wavefront's LDS accesses execute in order, so no barrier is needed (and none that would wait for the global
+    // stores of the previous row): only the compiler must keep the 2-byte writes and 16-byte reads in order.
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int vb = 0; vb < 4; ++vb)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float v = acc[vb][rb][r] + bv[rb][r];
-          if (!(v > 0.f)) v *= a.out_slope;
-          ot[wave][rb * 16 + 4 * lg + r][vb * 16 + lj] = f32_to_bf16(inside ? v : 0.f);
+        for (int r = 0; r < 4; r += 2) {
+          float v0 = acc[vb][rb][r] + bv[rb][r], v1 = acc[vb][rb][r + 1] + bv[rb][r + 1];
+          if (!(v0 > 0.f)) v0 *= a.out_slope;
+          if (!(v1 > 0.f)) v1 *= a.out_slope;
+          const uint32_t pk = inside ? pack_bf16x2(v0, v1) : 0u;      // one conversion for two channels
+          ot[wave][rb * 16 + 4 * lg + r][vb * 16 + lj] = (bf16_t)pk;
+          ot[wave][rb * 16 + 4 * lg + r + 1][vb * 16 + lj] = (bf16_t)(pk >> 16);
         }
-    __syncthreads();
+    asm volatile("" ::: "memory");
     const int h = h0 + hl;
     if (plane_ok && h < H) {
 #pragma unroll
