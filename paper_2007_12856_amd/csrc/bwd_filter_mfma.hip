@@ -1037,7 +1037,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
       p.rbw = cout > 16 ? 2 : 1;
       p.nrg = 1;
       p.th = p.rbw == 2 ? 16 : 32;
-      if (p.rbw == 1 && x->w >= 64) { p.tw = 64; p.th = 16; }     // whole 128-byte lines per tile row
+      if (p.rbw == 1 && x->w >= 64) { p.tw = 64; p.th = 8; }     // whole 128-byte lines per tile row; 4 wavefronts, two workgroups per CU
     }
   }
   else if (x->w > 32) { p.tw = 64; p.th = 2; }
@@ -1061,6 +1061,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
     // which keeps the fp32 partials (written once, read once by the reduction) small next to the tensors
     int per_cu = 1;
     if (x->c > 4) per_cu = (p.cib == 2) ? 1 : (p.rbw * p.nrg == 1 ? 3 : 2);
+    else if (p.tw == 64) per_cu = 2;     // two workgroups of 68 KB: one computes while the other waits for its next tile
     want = std::max<int64_t>(1, cdiv(256 * per_cu, groups));
     cap_bytes = (int64_t)96 << 20;
   }
@@ -1192,7 +1193,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   h3d_status st;
   if (roll && x->c <= 4) {
     if (p.rbw == 2) st = bf_roll_small_launch<2, 8, 2, 1>(handle, xp, gp, (float*)ws, a, grid, stream);
-    else if (p.tw == 64) st = bf_roll_small_launch<1, 8, 2, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
+    else if (p.tw == 64) st = bf_roll_small_launch<1, 4, 2, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
     else st = bf_roll_small_launch<1, 8, 4, 1>(handle, xp, gp, (float*)ws, a, grid, stream);
   } else if (roll) {
     if (p.cib == 2) {

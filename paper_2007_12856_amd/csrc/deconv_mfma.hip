@@ -248,6 +248,11 @@ size_t deconv_bf_mfma_ws_bytes(const h3d_tensor* x, const h3d_tensor* dy) {
   return (size_t)p.nchunks * ((size_t)x->c * dy->c + dy->c) * 8 * sizeof(float);
 }
 
+__global__ void deconv_zero_kernel(float* __restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
 h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dy, float* dw, float* db, void* ws, size_t ws_bytes,
                           hipStream_t stream) {
   const DbfPlan p = dbf_plan(x, dy);
@@ -260,8 +265,9 @@ h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* d
   a.gco = p.gco; a.gci = p.gci;
   const int64_t nw = (int64_t)a.cin * a.cout * 8;
   if (p.ntiles == 0) {
-    hipMemsetAsync(dw, 0, nw * sizeof(float), stream);
-    if (db) hipMemsetAsync(db, 0, a.cout * sizeof(float), stream);
+    // a fill kernel, not a memset: the call may be recorded into a graph by the caller
+    hipLaunchKernelGGL(deconv_zero_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, dw, nw);
+    if (db) hipLaunchKernelGGL(deconv_zero_kernel, dim3((unsigned)cdiv(a.cout, 256)), dim3(256), 0, stream, db, (int64_t)a.cout);
     return launch_status(handle, "deconv2_bwd_filter");
   }
   const bf16_t* xp = (const bf16_t*)x->data;
