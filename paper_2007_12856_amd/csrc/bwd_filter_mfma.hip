@@ -1258,7 +1258,7 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   if (nw >= 65536 && a.npart <= 16)
     hipLaunchKernelGGL(bfm_reduce_wide_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw, db,
                        nw, a.cout, a.npart);
-  else if (nw % 4 == 0 && (uintptr_t)ws % 16 == 0 && (uintptr_t)dw % 16 == 0)
+  else if (nw >= 32768 && nw % 4 == 0 && (uintptr_t)ws % 16 == 0 && (uintptr_t)dw % 16 == 0)     // (few weights: more, smaller workgroups)
     hipLaunchKernelGGL(bfm_reduce4_kernel, dim3((unsigned)(cdiv(nw / 4, 16) + cdiv(a.cout, 16))), dim3(256), 0, stream, (const float*)ws, dw,
                        db, nw, a.cout, a.npart);
   else

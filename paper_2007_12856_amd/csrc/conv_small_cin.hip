@@ -10,8 +10,11 @@
 //     with two 8-byte LDS reads at per-lane tap offsets; the four lane groups of a wavefront cover
 //     8 taps per step.  Output channels are the MFMA rows; the packed weights (16 x 128 per row
 //     block) stay in registers for the whole kernel;
-//   * the accumulators (one output row of 64 voxels x Cout at a time) are transposed through LDS so
-//     that every lane stores 16 contiguous bytes along W: whole 128-byte lines per channel row.
+//   * the input patches are the A operand and the weights the B operand, so an accumulator holds FOUR
+//     consecutive voxels of one output channel per lane: bias, activation and bf16 packing stay in the
+//     lane (one bias value, packed conversions), and the row (64 voxels x Cout) goes through a per-wavefront
+//     LDS patch as 8-byte pieces so that every lane stores 16 contiguous bytes along W: whole 128-byte
+//     lines per channel row.
 // Bias, (leaky-)ReLU and the zeroing of output planes beyond the global volume are fused.
 #include <algorithm>
 
@@ -132,14 +135,9 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   const int64_t gp = a.out.doff + ps - a.out.hlo;
   const bool inside = gp >= 0 && gp < a.out.dglob;
   const bool plane_ok = ps < a.out.ds;
-  float bv[RB][4];
+  float bv[RB];      // this lane's output channel of row block rb: 16 rb + lj
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int co = rb * 16 + 4 * lg + r;
-      bv[rb][r] = (bias && co < a.cout) ? bias[co] : 0.f;
-    }
+  for (int rb = 0; rb < RB; ++rb) bv[rb] = (bias && rb * 16 + lj < a.cout) ? bias[rb * 16 + lj] : 0.f;
   bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
   for (int hl = 0; hl < TH; ++hl) {
     f32x4 acc[4][RB];
@@ -156,26 +154,27 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
         const uint4 b = {lo.x, lo.y, hi.x, hi.y};
         const bf16x8 B = __builtin_bit_cast(bf16x8, b);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[rb][m], B, acc[vb][rb], 0, 0, 0);
+        for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(B, A[rb][m], acc[vb][rb], 0, 0, 0);
       }
     }
-    // bias + activation, transpose through LDS: ot[wave][co][w].  The patch belongs to this wavefront alone and a
-    // wavefront's LDS accesses execute in order, so no barrier is needed (and none that would wait for the global
-    // stores of the previous row): only the compiler must keep the 2-byte writes and 16-byte reads in order.
+    // bias + activation: accumulator register r of block vb is voxel w0 + 16 vb + 4 lg + r of channel 16 rb + lj.
+    // Transposed through ot[wave][co][w]: the patch belongs to this wavefront alone and a wavefront's LDS accesses
+    // execute in order, so no barrier is needed (and none that would wait for the global stores of the previous
+    // row): only the compiler must keep the 8-byte writes and 16-byte reads in order.
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int vb = 0; vb < 4; ++vb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
+      for (int vb = 0; vb < 4; ++vb) {
+        float v[4];
 #pragma unroll
-        for (int r = 0; r < 4; r += 2) {
-          float v0 = acc[vb][rb][r] + bv[rb][r], v1 = acc[vb][rb][r + 1] + bv[rb][r + 1];
-          if (!(v0 > 0.f)) v0 *= a.out_slope;
-          if (!(v1 > 0.f)) v1 *= a.out_slope;
-          const uint32_t pk = inside ? pack_bf16x2(v0, v1) : 0u;      // one conversion for two channels
-          ot[wave][rb * 16 + 4 * lg + r][vb * 16 + lj] = (bf16_t)pk;
-          ot[wave][rb * 16 + 4 * lg + r + 1][vb * 16 + lj] = (bf16_t)(pk >> 16);
+        for (int r = 0; r < 4; ++r) {
+          v[r] = acc[vb][rb][r] + bv[rb];
+          if (!(v[r] > 0.f)) v[r] *= a.out_slope;
         }
+        const uint2 pk = inside ? uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])} : uint2{0u, 0u};
+        *reinterpret_cast<uint2*>(&ot[wave][rb * 16 + lj][vb * 16 + 4 * lg]) = pk;
+      }
     asm volatile("" ::: "memory");
     const int h = h0 + hl;
     if (plane_ok && h < H) {
