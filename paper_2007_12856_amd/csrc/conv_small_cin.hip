@@ -62,7 +62,16 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   __shared__ __attribute__((aligned(16))) bf16_t ot[4][16 * RB][OTP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lj = lane & 15;
+  // consecutive workgroup ids go to different XCDs (each with its own L2): XCD x takes the depth slabs x, x + 8, ...
+  // whole, so that the tiles of a slab, which share halo rows and columns, meet in one L2 (neighbouring slabs, in
+  // different XCDs, still fetch the two shared planes twice: spreading every XCD over the whole volume keeps its
+  // requests spread over the memory channels, which one contiguous run per XCD does not)
+  const int per_slab = a.tiles_w * a.tiles_h, nslab = (int)gridDim.x / per_slab;
   int t = blockIdx.x;
+  if (nslab % 8 == 0) {
+    const int x = t % 8, i = t / 8;
+    t = ((i / per_slab) * 8 + x) * per_slab + i % per_slab;
+  }
   const int tw = t % a.tiles_w; t /= a.tiles_w;
   const int th = t % a.tiles_h; t /= a.tiles_h;
   const int td = t % a.tiles_d;
@@ -90,31 +99,7 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   const bf16_t* in_n = in + n * a.in.nstride;
   constexpr int NGRP = XW / 8;
   constexpr int NITEMS = (TD + 2) * (TH + 2) * NGRP;
-  for (int item = tid; item < NITEMS; item += 256) {
-    const int grp = item % NGRP;
-    int q = item / NGRP;
-    const int hy = q % (TH + 2), dz = q / (TH + 2);
-    const int p_in = ps0 - a.out.hlo + dz - 1;
-    const int64_t gq = a.in.doff + p_in;
-    const int sp = p_in + a.in.hlo;
-    const int h = h0 + hy - 1, w = w0 - 8 + 8 * grp;
-    const bool row_ok = gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H;
-    uint4 c[4];
-#pragma unroll
-    for (int ci = 0; ci < 4; ++ci) {
-      c[ci] = uint4{0, 0, 0, 0};
-      if (row_ok && ci < a.cin) {
-        const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + (int64_t)sp * a.in.plane + (int64_t)h * W + w;
-        if (a.vec_ok) {
-          if (w >= 0 && w + 8 <= W) c[ci] = *reinterpret_cast<const uint4*>(p);
-        } else {
-          uint32_t e[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? p[i] : 0;
-          c[ci] = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-        }
-      }
-    }
+  auto transpose_store = [&](const uint4 (&c)[4], int dz, int hy, int grp) {
     uint4* dst = reinterpret_cast<uint4*>(&xs[dz * PDV + hy * PRV + 8 * grp]);
     const uint32_t c0[4] = {c[0].x, c[0].y, c[0].z, c[0].w}, c1[4] = {c[1].x, c[1].y, c[1].z, c[1].w};
     const uint32_t c2[4] = {c[2].x, c[2].y, c[2].z, c[2].w}, c3[4] = {c[3].x, c[3].y, c[3].z, c[3].w};
@@ -126,6 +111,72 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
       u.z = __builtin_amdgcn_perm(c1[k], c0[k], 0x07060302);
       u.w = __builtin_amdgcn_perm(c3[k], c2[k], 0x07060302);
       dst[k] = u;
+    }
+  };
+  if (a.vec_ok) {
+    // whole 16-byte groups: buffer loads whose offset is pushed out of range where the group lies outside the
+    // volume (they return zeros: no branches), all rounds issued before the first transpose
+    constexpr int ROUNDS = (NITEMS + 255) / 256;
+    constexpr int OOB = (int)0x80000000;
+    // (the two halves of the pointer go through unsigned temporaries: readfirstlane returns a signed int, and a
+    // sign-extended low half would overwrite the high half)
+    const uint64_t pbase = reinterpret_cast<uint64_t>(in_n);
+    const uint32_t p_lo = __builtin_amdgcn_readfirstlane((uint32_t)pbase), p_hi = __builtin_amdgcn_readfirstlane((uint32_t)(pbase >> 32));
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(((uint64_t)p_hi << 32) | p_lo), 0, (int)__builtin_amdgcn_readfirstlane((uint32_t)a.in.nstride * 2),
+        0x00020000);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 c[ROUNDS][4];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int item = tid + 256 * r;
+      const int grp = item % NGRP;
+      const int q = item / NGRP;
+      const int hy = q % (TH + 2), dz = q / (TH + 2);
+      const int p_in = ps0 - a.out.hlo + dz - 1;
+      const int64_t gq = a.in.doff + p_in;
+      const int sp = p_in + a.in.hlo;
+      const int h = h0 + hy - 1, w = w0 - 8 + 8 * grp;
+      const bool ok = item < NITEMS && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H && w >= 0 && w + 8 <= W;
+      const int vo = ok ? 2 * (sp * (int)a.in.plane + h * W + w) : OOB;
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci)
+        c[r][ci] = __builtin_amdgcn_raw_buffer_load_b128(rs, ci < a.cin ? vo : OOB, __builtin_amdgcn_readfirstlane(2 * ci * (int)a.in.cstride), 0);
+    }
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int item = tid + 256 * r;
+      if (item < NITEMS) {
+        const int grp = item % NGRP;
+        const int q = item / NGRP;
+        const uint4 cc[4] = {uint4{c[r][0][0], c[r][0][1], c[r][0][2], c[r][0][3]}, uint4{c[r][1][0], c[r][1][1], c[r][1][2], c[r][1][3]},
+                             uint4{c[r][2][0], c[r][2][1], c[r][2][2], c[r][2][3]}, uint4{c[r][3][0], c[r][3][1], c[r][3][2], c[r][3][3]}};
+        transpose_store(cc, q / (TH + 2), q % (TH + 2), grp);
+      }
+    }
+  } else {
+    for (int item = tid; item < NITEMS; item += 256) {
+      const int grp = item % NGRP;
+      int q = item / NGRP;
+      const int hy = q % (TH + 2), dz = q / (TH + 2);
+      const int p_in = ps0 - a.out.hlo + dz - 1;
+      const int64_t gq = a.in.doff + p_in;
+      const int sp = p_in + a.in.hlo;
+      const int h = h0 + hy - 1, w = w0 - 8 + 8 * grp;
+      const bool row_ok = gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H;
+      uint4 c[4];
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        c[ci] = uint4{0, 0, 0, 0};
+        if (row_ok && ci < a.cin) {
+          const bf16_t* p = in_n + (int64_t)ci * a.in.cstride + (int64_t)sp * a.in.plane + (int64_t)h * W + w;
+          uint32_t e[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) e[i] = (w + i >= 0 && w + i < W) ? p[i] : 0;
+          c[ci] = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+        }
+      }
+      transpose_store(c, dz, hy, grp);
     }
   }
   __syncthreads();
