@@ -701,18 +701,16 @@ struct RollSmallTile {
 };
 
 template <int RBW, int NW, int RB, int NSEG>
-__global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const bf16_t* __restrict__ x,
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 4 : 2) bwd_filter_roll_small_kernel(const bf16_t* __restrict__ x,
                                                                          const bf16_t* __restrict__ dz,
                                                                          float* __restrict__ part, BfmArgs a) {
   constexpr int TH = NW * RB;
   using T = RollSmallTile<TH, NSEG>;
   constexpr int CO_WG = 16 * RBW;
   constexpr int SLOTP = T::SLOTP, NCHX = T::NCHX;
-  constexpr int GPAD = (CO_WG * T::PG + 63) / 64 * 64, NCHG = GPAD / 64;
-  constexpr int CXW = (NCHX + NW - 1) / NW, CGW = (NCHG + NW - 1) / NW;
+  constexpr int CXW = (NCHX + NW - 1) / NW;
   extern __shared__ uint4 lds[];
   uint4* xl = lds;                    // [4 slots][4 ci][TH+2 rows][6 units]  (pitches SLOTP, PCI, XU)
-  uint4* gl = lds + 4 * SLOTP;        // [2 buffers][CO_WG][TH rows][4 units]  (pitches GPAD, PG, GU)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
@@ -732,10 +730,8 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
   const int row0 = wave * RB;                   // this wavefront's band of the tile
   const int xb_o = 16 * ((col_ok ? cil : 0) * T::PCI + row0 * T::XU + 1 + lg);
   const int pe_o = 16 * ((col_ok ? cil : 0) * T::PCI + row0 * T::XU) + 12;
-  const int ga_o = 16 * (lc * T::PG + row0 * T::GU + lg);
 
   int dx_meta[CXW];    // row | u << 8 | ci << 16, -1 = padding or channel out of range
-  int dg_meta[CGW];    // row | u << 8 | co << 16
 #pragma unroll
   for (int i = 0; i < CXW; ++i) {
     const int ul = 64 * (wave + NW * i) + lane;
@@ -744,15 +740,6 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     const bool ok = wave + NW * i < NCHX && ci < 4 && row < TH + 2 && ci < a.cin;
     dx_meta[i] = ok ? (row | (u << 8) | (ci << 16)) : -1;
   }
-#pragma unroll
-  for (int i = 0; i < CGW; ++i) {
-    const int ul = 64 * (wave + NW * i) + lane;
-    const int col = ul / T::PG, r1 = ul % T::PG;
-    const int row = r1 / T::GU, u = r1 % T::GU;
-    const bool ok = wave + NW * i < NCHG && col < CO_WG && row < TH && co0 + col < a.cout;
-    dg_meta[i] = ok ? (row | (u << 8) | ((co0 + col) << 16)) : -1;
-  }
-
   auto load_plane = [&](int n, int q, int h0, int w0) {
     const __amdgpu_buffer_rsrc_t rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
     const int64_t gq = a.x.doff + q;
@@ -770,19 +757,23 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
         dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + ci * (int)a.x.cstride + row * W + u8) : BF_OOB);
     }
   };
-  auto load_g = [&](int n, int q, int h0, int w0, int buf) {
+  // The g rows of a wavefront's band are used by that wavefront alone, and 8 consecutive voxels of one channel are
+  // 16 contiguous bytes: they go straight from global memory into the A-operand registers (lane (lc, lg): channel
+  // co0 + 16 rb + lc, voxels 8 lg .. 8 lg + 7 of the 32-column segment), one tile ahead, without touching LDS.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  auto load_g = [&](u32x4 (&G)[RB][NSEG][RBW], int n, int q, int h0, int w0) {
     const __amdgpu_buffer_rsrc_t rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
-    const int t0 = (q + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
-    uint4* dst = gl + buf * GPAD;
+    const int t0 = (q + a.g.hlo) * (int)a.g.plane + (h0 + row0) * W + w0 + 8 * lg;
 #pragma unroll
-    for (int i = 0; i < CGW; ++i) {
-      int m = dg_meta[i];
-      asm volatile("" : "+v"(m));
-      const int row = m & 0xff, u8 = 8 * ((m >> 8) & 0xff), co = m >> 16;
-      const bool ok = m >= 0 && h0 + row < H && w0 + u8 + 8 <= W;
-      if (wave + NW * i < NCHG)
-        dma16(rs, dst + 64 * (wave + NW * i), ok ? 2 * (t0 + co * (int)a.g.cstride + row * W + u8) : BF_OOB);
-    }
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+      for (int seg = 0; seg < NSEG; ++seg)
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+          const int co = co0 + 16 * rb + lc;
+          const bool ok = co < a.cout && h0 + row0 + r < H && w0 + 32 * seg + 8 * lg + 8 <= W;
+          G[r][seg][rb] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? 2 * (t0 + co * (int)a.g.cstride + r * W + 32 * seg) : BF_OOB, 0, 0);
+        }
   };
 
   f32x4 acc[RBW][3][3];   // [row block][kh][kw]
@@ -808,14 +799,14 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     th = r % a.tiles_h;
     n = r / a.tiles_h;
   }
+  u32x4 G0[RB][NSEG][RBW], G1[RB][NSEG][RBW];     // this tile's g rows and the next tile's
   if (t_begin < t_end) {
     load_plane(n, p - 1, th * TH, tw * T::TW);
     load_plane(n, p, th * TH, tw * T::TW);
     load_plane(n, p + 1, th * TH, tw * T::TW);
-    load_g(n, p, th * TH, tw * T::TW, 0);
+    load_g(G0, n, p, th * TH, tw * T::TW);
   }
-  int buf = 0;
-  for (int tile = t_begin; tile < t_end; ++tile) {
+  auto tile_step = [&](u32x4 (&Gc)[RB][NSEG][RBW], u32x4 (&Gn)[RB][NSEG][RBW], int tile) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     int tw2 = tw, th2 = th, p2 = p + 1, n2 = n;
@@ -825,7 +816,7 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     const bool has_next = tile + 1 < t_end;
     const bool jump = has_next && p2 == 0;
     if (has_next) {
-      load_g(n2, p2, th2 * TH, tw2 * T::TW, buf ^ 1);
+      load_g(Gn, n2, p2, th2 * TH, tw2 * T::TW);
       if (!jump) load_plane(n2, p2 + 1, th2 * TH, tw2 * T::TW);
     }
 
@@ -834,7 +825,6 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     for (int seg = 0; seg < NSEG; ++seg) {
     const char* xb_p = xs + xb_o + 64 * seg;
     const char* pe_p = xs + pe_o + 64 * seg;
-    const char* ga_p = reinterpret_cast<const char*>(gl) + 16 * GPAD * buf + ga_o + 64 * seg;
 
     uint4 blk[2];
     uint32_t pe, ne, pv, nx;
@@ -848,8 +838,7 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
     };
     auto read_g = [&](int r) {
 #pragma unroll
-      for (int rb = 0; rb < RBW; ++rb)
-        A[r % 3][rb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ga_p + 16 * (rb * 16 * T::PG + r * T::GU)));
+      for (int rb = 0; rb < RBW; ++rb) A[r % 3][rb] = __builtin_bit_cast(bf16x8, Gc[r][seg][rb]);
     };
     auto exchange = [&](int r) {
       pv = __builtin_amdgcn_ds_bpermute(bp_prev, edge_hi ? pe : blk[r & 1].w);
@@ -905,7 +894,10 @@ __global__ void __launch_bounds__(64 * NW, 2) bwd_filter_roll_small_kernel(const
       load_plane(n2, 1, th2 * TH, tw2 * T::TW);
     }
     tw = tw2; th = th2; p = p2; n = n2;
-    buf ^= 1;
+  };
+  for (int tile = t_begin; tile < t_end; tile += 2) {
+    tile_step(G0, G1, tile);
+    if (tile + 1 < t_end) tile_step(G1, G0, tile + 1);
   }
 
   // add the wavefronts' accumulators in wavefront order (fixed, so the result is reproducible)
@@ -1104,7 +1096,7 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
     // which keeps the fp32 partials (written once, read once by the reduction) small next to the tensors
     int per_cu = 1;
     if (x->c > 4) per_cu = (p.cib == 2) ? 1 : (p.rbw * p.nrg == 1 ? 3 : 2);
-    else if (p.tw == 64) per_cu = 2;     // two workgroups of 68 KB: one computes while the other waits for its next tile
+    else if (p.tw == 64) per_cu = 2;     // two workgroups of 4 wavefronts per CU (measured: more of them only compete for the memory system)
     want = std::max<int64_t>(1, cdiv(256 * per_cu, groups));
     cap_bytes = (int64_t)96 << 20;
   }
@@ -1151,7 +1143,8 @@ template <int RBW, int NW, int RB, int NSEG>
 static h3d_status bf_roll_small_launch(void* handle, const bf16_t* x, const bf16_t* dz, float* part, const BfmArgs& a, dim3 grid,
                                        hipStream_t stream) {
   using T = RollSmallTile<NW * RB, NSEG>;
-  constexpr size_t lds_bytes = (size_t)(4 * T::SLOTP + 2 * ((16 * RBW * T::PG + 63) / 64 * 64)) * 16;
+  constexpr size_t lds_bytes = (size_t)4 * T::SLOTP * 16;      // four plane slots; the wavefront sums at the end reuse them
+  static_assert(lds_bytes >= (size_t)(NW - 1) * 64 * 16, "room for the accumulator exchange");
   auto kern = bwd_filter_roll_small_kernel<RBW, NW, RB, NSEG>;
   static bool attr_set = false;
   if (!attr_set) {
