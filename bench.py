@@ -60,8 +60,8 @@ def side_workload(args, seed):
     from paper_2007_12856_amd.nets import SingleLayer, UNetLevel
     bf = torch.bfloat16
     if args.workload == "shard512":
-        net = SingleLayer(1, 4, 16, 64, 512, 64, 512, seed=seed)
-        name = "one 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky + avg-pool, halo faces"
+        net = SingleLayer(1, 4, 16, 64, 512, 64, 512, seed=seed, faces_hw=True)
+        name = "one 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky + avg-pool, D halo faces; H and W faces of g"
     elif args.workload == "split256":
         net = SingleLayer(1, 64, 64, 32, 256, 32, 256, pool=False, seed=seed, split=True)
         name = "one 8-way depth shard of a 64-channel 256^3 sample: conv 64->64 whole, and as main planes + two 1-plane strips"

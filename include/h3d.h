@@ -152,6 +152,27 @@ h3d_status h3d_halo_pack(void* handle, const h3d_tensor* t, int face, int width,
  * (width <= that halo); buf == NULL zero-fills them (global boundary). */
 h3d_status h3d_halo_unpack(void* handle, const void* buf, h3d_tensor* t, int face, int width, void* stream);
 
+/* ---- general faces (Sec. II-B: the spatial domain may be partitioned in any of its three dimensions;
+ *      Sec. III-A: packing / unpacking kernels of the boundary exchange for 3^3 and 5^3 filters, i.e. faces
+ *      one or two voxels wide) ---- bit-exact copies.
+ * t: DEVICE pointer to a packed tensor [n][c][D][H][W] of `dtype`; D, H, W are its STORED extents (the
+ * caller decides which planes, rows and columns of it are halo).  box: origin (d0,h0,w0) and extents
+ * (bd,bh,bw) of the face inside every (n,c) volume; buf: DEVICE pointer to [n][c][bd][bh][bw] packed.
+ * Nothing is allocated or owned; a box that does not lie inside the tensor is H3D_EINVAL before any launch;
+ * an empty box is a no-op. */
+typedef struct {
+  int32_t d0, h0, w0;   /* origin of the box */
+  int32_t bd, bh, bw;   /* extents of the box */
+} h3d_box;
+size_t h3d_box_bytes(int dtype, int n, int c, const h3d_box* box);
+/* pack: buf <- box of t. */
+h3d_status h3d_box_pack(void* handle, const void* t, int dtype, int n, int c, int D, int H, int W,
+                        const h3d_box* box, void* buf, void* stream);
+/* unpack: box of t <- buf; buf == NULL writes zeros (a face on the global boundary).  Elements of t
+ * outside the box are not touched. */
+h3d_status h3d_box_unpack(void* handle, const void* buf, void* t, int dtype, int n, int c, int D, int H, int W,
+                          const h3d_box* box, void* stream);
+
 /* ---- 2x2x2 stride-2 transposed convolution (U-Net up-sampling "deconvolution", Sec. III-A) ----
  * w: [cin][cout][2][2][2]; y[n,co,2q+k] = bias[co] + sum_ci w[ci,co,k] * x[n,ci,q].  Interiors only;
  * y interior extents are twice x's. */

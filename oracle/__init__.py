@@ -207,6 +207,29 @@ def halo_unpack(buf: np.ndarray | None, t: Slab, face: int, width: int) -> None:
     t.a[:, :, lo:lo + width] = 0.0 if buf is None else buf
 
 
+def box_pack(a: np.ndarray, box) -> np.ndarray:
+    """General face (Sec. II-B partitioning in any spatial dimension, Sec. III-A pack kernels): the box
+    (d0, h0, w0, bd, bh, bw) of every (n, c) volume of the packed array a[n][c][D][H][W], as [n][c][bd][bh][bw]."""
+    d0, h0, w0, bd, bh, bw = box
+    assert a.ndim == 5 and 0 <= d0 and d0 + bd <= a.shape[2] and 0 <= h0 and h0 + bh <= a.shape[3] and 0 <= w0 and w0 + bw <= a.shape[4]
+    out = np.empty((a.shape[0], a.shape[1], bd, bh, bw), dtype=a.dtype)
+    for d in range(bd):
+        for h in range(bh):
+            for w in range(bw):
+                out[:, :, d, h, w] = a[:, :, d0 + d, h0 + h, w0 + w]
+    return out
+
+
+def box_unpack(buf: np.ndarray | None, a: np.ndarray, box) -> None:
+    """Write buf[n][c][bd][bh][bw] (or zeros: a face on the global boundary) into the box of a; the rest of a stays."""
+    d0, h0, w0, bd, bh, bw = box
+    assert a.ndim == 5 and 0 <= d0 and d0 + bd <= a.shape[2] and 0 <= h0 and h0 + bh <= a.shape[3] and 0 <= w0 and w0 + bw <= a.shape[4]
+    for d in range(bd):
+        for h in range(bh):
+            for w in range(bw):
+                a[:, :, d0 + d, h0 + h, w0 + w] = 0.0 if buf is None else buf[:, :, d, h, w]
+
+
 def concat_c(a: Slab, b: Slab) -> Slab:
     """Channel concat of the interiors, `a` first (skip connection of the U-Net, Sec. III-A)."""
     return Slab(np.concatenate([a.interior, b.interior], axis=1), 0, 0, a.d_offset, a.d_global)

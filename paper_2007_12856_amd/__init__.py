@@ -36,9 +36,15 @@ class h3d_tensor(ctypes.Structure):
                 ("c_stride", ctypes.c_int64), ("n_stride", ctypes.c_int64)]
 
 
+class h3d_box(ctypes.Structure):
+    _fields_ = [("d0", ctypes.c_int32), ("h0", ctypes.c_int32), ("w0", ctypes.c_int32),
+                ("bd", ctypes.c_int32), ("bh", ctypes.c_int32), ("bw", ctypes.c_int32)]
+
+
 _lib = None
 _P = ctypes.c_void_p
 _T = ctypes.POINTER(h3d_tensor)
+_B = ctypes.POINTER(h3d_box)
 _SIGNATURES = {
     "h3d_create": (ctypes.c_int, [ctypes.POINTER(_P)]),
     "h3d_destroy": (ctypes.c_int, [_P]),
@@ -54,6 +60,11 @@ _SIGNATURES = {
     "h3d_halo_bytes": (ctypes.c_size_t, [_T, ctypes.c_int]),
     "h3d_halo_pack": (ctypes.c_int, [_P, _T, ctypes.c_int, ctypes.c_int, _P, _P]),
     "h3d_halo_unpack": (ctypes.c_int, [_P, _P, _T, ctypes.c_int, ctypes.c_int, _P]),
+    "h3d_box_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_int, ctypes.c_int, _B]),
+    "h3d_box_pack": (ctypes.c_int, [_P, _P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    _B, _P, _P]),
+    "h3d_box_unpack": (ctypes.c_int, [_P, _P, _P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, _B, _P]),
     "h3d_deconv2_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
     "h3d_deconv2_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, _P, ctypes.c_size_t, _P]),
     "h3d_deconv2_bwd_data": (ctypes.c_int, [_P, _T, _P, _T, _P, ctypes.c_size_t, _P]),
@@ -275,6 +286,33 @@ def h3d_halo_unpack(buf, t: Slab, face: int, width: int):
     return t
 
 
+def _box_args(t, box):
+    """t: contiguous 5-D torch tensor [n][c][D][H][W] (stored extents); box = (d0, h0, w0, bd, bh, bw)."""
+    import torch
+    if t.dim() != 5 or not t.is_contiguous():
+        raise ValueError("box_pack/unpack: a contiguous 5-D tensor is required")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[t.dtype]
+    n, c, D, H, W = (int(v) for v in t.shape)
+    return dt, n, c, D, H, W, h3d_box(*[int(v) for v in box])
+
+
+def h3d_box_bytes(t, box) -> int:
+    dt, n, c, D, H, W, b = _box_args(t, box)
+    return int(lib().h3d_box_bytes(dt, n, c, ctypes.byref(b)))
+
+
+def h3d_box_pack(t, box, buf):
+    dt, n, c, D, H, W, b = _box_args(t, box)
+    _check(lib().h3d_box_pack(handle(), _ptr(t), dt, n, c, D, H, W, ctypes.byref(b), _ptr(buf), _stream()))
+    return buf
+
+
+def h3d_box_unpack(buf, t, box):
+    dt, n, c, D, H, W, b = _box_args(t, box)
+    _check(lib().h3d_box_unpack(handle(), _ptr(buf), _ptr(t), dt, n, c, D, H, W, ctypes.byref(b), _stream()))
+    return t
+
+
 def h3d_deconv2_workspace_bytes(op: int, x: Slab, y: Slab) -> int:
     return int(lib().h3d_deconv2_workspace_bytes(handle(), op, ctypes.byref(x.desc()), ctypes.byref(y.desc())))
 
@@ -370,6 +408,7 @@ bn_stats, bn_finalize, bn_fwd, bn_bwd_stats, bn_bwd = h3d_bn_stats, h3d_bn_final
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
 pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
+box_bytes, box_pack, box_unpack = h3d_box_bytes, h3d_box_pack, h3d_box_unpack
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c
 dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd

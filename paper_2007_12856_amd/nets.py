@@ -224,7 +224,7 @@ class SingleLayer:
     pool bwd fused with the activation backward, BF and BD on g (g carries a 1-plane halo)."""
 
     def __init__(self, n, cin, cout, d, hw, d_offset, d_global, pool=True, act=ACT_LEAKY, alpha=0.01, dtype=torch.bfloat16, seed=0,
-                 split=False):
+                 split=False, faces_hw=False):
         from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
         dev = "cuda"
         gen = torch.Generator(device=dev)
@@ -268,6 +268,22 @@ class SingleLayer:
             op("pool_bwd_act", lambda: pool3d_bwd_act(dp, None, z, g, POOL_AVG, act, alpha), 0, (dp.t.numel() + 2 * z.t.numel()) * es)
         op("halo_pack_g", lambda: (halo_pack(g, FACE_D_LO, 1, gfaces[0]), halo_pack(g, FACE_D_HI, 1, gfaces[1])), 0, 4 * gfaces[0].numel() * es)
         op("halo_unpack_g", lambda: (halo_unpack(gfaces[1], g, FACE_D_LO, 1), halo_unpack(gfaces[0], g, FACE_D_HI, 1)), 0, 4 * gfaces[0].numel() * es)
+        if faces_hw:
+            # H and W faces of the activation gradient (a partitioning in H or W as well, Sec. II-B): one and two
+            # voxels wide, pack and unpack of both ends; bytes = face read + face written
+            from . import box_pack, box_unpack
+            ds, H, W = g.t.shape[2], g.t.shape[3], g.t.shape[4]
+            for wd_ in (1, 2):
+                hb = [torch.empty((n, cout, ds, wd_, W), dtype=dtype, device=dev) for _ in range(2)]
+                wb = [torch.empty((n, cout, ds, H, wd_), dtype=dtype, device=dev) for _ in range(2)]
+                op(f"face_pack_h{wd_}", lambda hb=hb, k=wd_: (box_pack(g.t, (0, 0, 0, ds, k, W), hb[0]), box_pack(g.t, (0, H - k, 0, ds, k, W), hb[1])),
+                   0, 4 * hb[0].numel() * es)
+                op(f"face_unpack_h{wd_}", lambda hb=hb, k=wd_: (box_unpack(hb[1], g.t, (0, 0, 0, ds, k, W)), box_unpack(hb[0], g.t, (0, H - k, 0, ds, k, W))),
+                   0, 4 * hb[0].numel() * es)
+                op(f"face_pack_w{wd_}", lambda wb=wb, k=wd_: (box_pack(g.t, (0, 0, 0, ds, H, k), wb[0]), box_pack(g.t, (0, 0, W - k, ds, H, k), wb[1])),
+                   0, 4 * wb[0].numel() * es)
+                op(f"face_unpack_w{wd_}", lambda wb=wb, k=wd_: (box_unpack(wb[1], g.t, (0, 0, 0, ds, H, k)), box_unpack(wb[0], g.t, (0, 0, W - k, ds, H, k))),
+                   0, 4 * wb[0].numel() * es)
         op("conv_bwd_filter", lambda: conv3d_bwd_filter(x, g, None, self.dw, self.db, ACT_NONE, 0.0, ws), fl,
            (x.t.numel() + vox * cout) * es + w.numel() * 4)
         op("conv_bwd_data", lambda: conv3d_bwd_data(g, None, w, dx, ACT_NONE, 0.0, ws), fl, (g.t.numel() + dx.t.numel() + w.numel()) * es)

@@ -119,6 +119,66 @@ def test_pack_layout_and_roundtrip():
     assert np.array_equal(orc.halo_pack(Slab(u.a[:, :, 2:], 0, 0), orc.FACE_D_HI, 1), lo)
 
 
+def test_general_faces_of_a_2x2x2_partition_reproduce_the_full_volume():
+    """Sec. II-B partitions the domain in any spatial dimension.  A 2x2x2 grid of sub-domains with a one-voxel halo
+    on every side: after every sub-domain has packed its six faces (as wide as the neighbour's halo box needs them,
+    in D, then H including the fresh D halos, then W including both: the usual three-phase exchange that also
+    fills edges and corners) and the neighbours have unpacked them, each padded block equals the zero-padded full
+    volume cut at its place; what no box addresses keeps its canary."""
+    N, C, S = 2, 2, 4                     # sub-domain edge
+    full = rand(N, C, 2 * S, 2 * S, 2 * S)
+    padded = np.zeros((N, C, 2 * S + 2, 2 * S + 2, 2 * S + 2))
+    padded[:, :, 1:-1, 1:-1, 1:-1] = full
+    blocks = {}
+    for bd in range(2):
+        for bh in range(2):
+            for bw in range(2):
+                a = np.full((N, C, S + 2, S + 2, S + 2), 777.0)
+                a[:, :, 1:-1, 1:-1, 1:-1] = full[:, :, bd * S:(bd + 1) * S, bh * S:(bh + 1) * S, bw * S:(bw + 1) * S]
+                blocks[bd, bh, bw] = a
+    E = S + 2
+    for axis in range(3):                 # phase 0: D faces of the interior; 1: H faces over the filled D extent; 2: W faces
+        for key, a in blocks.items():
+            for side in (0, 1):
+                nb = list(key)
+                nb[axis] += 1 if side else -1
+                # the halo box on `side` of this block, and the neighbour's matching interior slice
+                lo = [1, 1, 1]; ext = [S, S, S]
+                for prev in range(axis):
+                    lo[prev], ext[prev] = 0, E
+                dst = list(lo); dst_ext = list(ext)
+                dst[axis] = E - 1 if side else 0
+                dst_ext[axis] = 1
+                src = list(lo)
+                src[axis] = 1 if side else S
+                box_dst = (dst[0], dst[1], dst[2], dst_ext[0], dst_ext[1], dst_ext[2])
+                if 0 <= nb[axis] < 2:
+                    box_src = (src[0], src[1], src[2], dst_ext[0], dst_ext[1], dst_ext[2])
+                    orc.box_unpack(orc.box_pack(blocks[tuple(nb)], box_src), a, box_dst)
+                else:
+                    orc.box_unpack(None, a, box_dst)
+    for (bd, bh, bw), a in blocks.items():
+        want = padded[:, :, bd * S:bd * S + E, bh * S:bh * S + E, bw * S:bw * S + E]
+        assert np.array_equal(a, want)
+
+
+def test_box_pack_layout_roundtrip_and_untouched_rest():
+    a = np.arange(2 * 3 * 4 * 5 * 6, dtype=np.float64).reshape(2, 3, 4, 5, 6)
+    box = (1, 2, 3, 2, 3, 2)
+    b = orc.box_pack(a, box)
+    assert b.shape == (2, 3, 2, 3, 2)
+    assert np.array_equal(b, a[:, :, 1:3, 2:5, 3:5])                   # the library slicing of the same box
+    assert b[1, 2, 1, 2, 1] == a[1, 2, 2, 4, 4]
+    u = np.full_like(a, -1.0)
+    orc.box_unpack(b, u, box)
+    assert np.array_equal(orc.box_pack(u, box), b)
+    mask = np.ones(a.shape, dtype=bool)
+    mask[:, :, 1:3, 2:5, 3:5] = False
+    assert np.all(u[mask] == -1.0)
+    orc.box_unpack(None, u, (0, 0, 0, 4, 5, 1))                        # a W face on the global boundary
+    assert not u[..., 0].any() and np.all(u[..., 1][mask[..., 1]] == -1.0)
+
+
 # ---------------------------------------------------------------- 2x2x2 stride-2 transposed convolution
 
 def test_deconv_is_adjoint_of_stride2_correlation_and_closed_form():
