@@ -142,6 +142,27 @@ h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* 
 h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z,
                               h3d_tensor* g, int mode, int act, float alpha, void* stream);
 
+/* ---- convolution forward fused with the 2x2x2 average pooling that follows it, and the matching backward step ----
+ * (Sec. III-A: operations that are "normally considered cheap" - pooling, activations - dominate once the tensors
+ * are large; here the unpooled activation never has to travel to memory and back.)
+ * y = avgpool(act(b + W * x)): the pooled tensor of the same shard (extents and offsets half of z's, halos allowed,
+ * interior written).  z describes the unpooled output; z->data == NULL means it is not stored (only where a fused
+ * kernel exists: bf16, Cin <= 4, Cout <= 32, z without halos, even d and h, w a multiple of 8; otherwise
+ * H3D_EUNSUPPORTED) - with z->data set the call works for every shape h3d_conv3d_fwd and h3d_pool3d_fwd accept.
+ * mask (DEVICE, h3d_act_mask_bytes(z) bytes, or NULL): one bit per unpooled voxel, set where the stored output is
+ * > 0; bit k of byte j of a row is voxel 8 j + k, rows packed [n][c][interior plane][h][w/8].  It replaces z in
+ * the backward pass (1/16 of its bytes). */
+size_t h3d_act_mask_bytes(const h3d_tensor* z);                       /* 0 if w is not a multiple of 8 */
+h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z,
+                               h3d_tensor* y, void* mask, int act, float alpha,
+                               void* ws, size_t ws_bytes, void* stream);
+/* mask of a stored output z (what the fused call writes by itself). */
+h3d_status h3d_act_mask(void* handle, const h3d_tensor* z, void* mask, void* stream);
+/* g = avgpool_bwd(dy) * (bit ? 1 : slope): h3d_pool3d_bwd_act with the mask in place of z; same bits in g.
+ * bf16, w a multiple of 16, act RELU or LEAKY. */
+h3d_status h3d_pool3d_bwd_mask(void* handle, const h3d_tensor* dy, const void* mask, h3d_tensor* g, int act, float alpha,
+                               void* stream);
+
 /* ---- halo pack / unpack of the depth faces (Sec. III-A: packing/unpacking kernels for the
  *      neighbour communication of boundary regions) ---- bit-exact copies.
  * Face buffer layout: [n][c][width][h][w] packed, same dtype as t. */

@@ -207,6 +207,17 @@ def halo_unpack(buf: np.ndarray | None, t: Slab, face: int, width: int) -> None:
     t.a[:, :, lo:lo + width] = 0.0 if buf is None else buf
 
 
+def act_mask(z: Slab) -> np.ndarray:
+    """Sign mask of a saved activation output (the derivative of ReLU / leaky ReLU only needs z > 0, Sec. IV-A's
+    activations): uint8 [n][c][d][h][w/8] over the interior planes, bit k of byte j of a row = (z[8 j + k] > 0)."""
+    zi = z.interior
+    assert zi.shape[4] % 8 == 0
+    out = np.zeros(zi.shape[:4] + (zi.shape[4] // 8,), dtype=np.uint8)
+    for k in range(8):
+        out |= (zi[..., k::8] > 0).astype(np.uint8) << k
+    return out
+
+
 def box_pack(a: np.ndarray, box) -> np.ndarray:
     """General face (Sec. II-B partitioning in any spatial dimension, Sec. III-A pack kernels): the box
     (d0, h0, w0, bd, bh, bw) of every (n, c) volume of the packed array a[n][c][D][H][W], as [n][c][bd][bh][bw]."""

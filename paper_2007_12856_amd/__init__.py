@@ -57,6 +57,10 @@ _SIGNATURES = {
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd_act": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
+    "h3d_act_mask_bytes": (ctypes.c_size_t, [_T]),
+    "h3d_conv3d_fwd_pool": (ctypes.c_int, [_P, _T, _P, _P, _T, _T, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_act_mask": (ctypes.c_int, [_P, _T, _P, _P]),
+    "h3d_pool3d_bwd_mask": (ctypes.c_int, [_P, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_halo_bytes": (ctypes.c_size_t, [_T, ctypes.c_int]),
     "h3d_halo_pack": (ctypes.c_int, [_P, _T, ctypes.c_int, ctypes.c_int, _P, _P]),
     "h3d_halo_unpack": (ctypes.c_int, [_P, _P, _T, ctypes.c_int, ctypes.c_int, _P]),
@@ -230,6 +234,37 @@ def h3d_conv3d_fwd(x: Slab, w, bias, z: Slab, act: int = ACT_NONE, alpha: float 
     _check(lib().h3d_conv3d_fwd(handle(), ctypes.byref(x.desc()), _ptr(w), _ptr(bias), ctypes.byref(z.desc()), act,
                                 alpha, p, n, _stream()))
     return z
+
+
+def _z_desc(x: Slab, z) -> h3d_tensor:
+    """Descriptor of the unpooled output: a Slab, or its shape (n, c, d, h, w) alone when it is not to be stored."""
+    if isinstance(z, Slab):
+        return z.desc()
+    n, c, d, h, w = (int(v) for v in z)
+    return h3d_tensor(None, _dtype_code(x.t), n, c, d, h, w, 0, 0, x.d_offset, x.d_global, 0, 0)
+
+
+def h3d_act_mask_bytes(x: Slab, z) -> int:
+    return int(lib().h3d_act_mask_bytes(ctypes.byref(_z_desc(x, z))))
+
+
+def h3d_conv3d_fwd_pool(x: Slab, w, bias, z, y: Slab, mask, act: int = ACT_NONE, alpha: float = 0.0, ws: Workspace | None = None):
+    zd = _z_desc(x, z)
+    nbytes = int(lib().h3d_conv3d_workspace_bytes(handle(), OP_FWD, ctypes.byref(x.desc()), ctypes.byref(zd)))
+    p, n = (ws or _ws).get(nbytes)
+    _check(lib().h3d_conv3d_fwd_pool(handle(), ctypes.byref(x.desc()), _ptr(w), _ptr(bias), ctypes.byref(zd), ctypes.byref(y.desc()),
+                                     _ptr(mask), act, alpha, p, n, _stream()))
+    return y
+
+
+def h3d_act_mask(z: Slab, mask):
+    _check(lib().h3d_act_mask(handle(), ctypes.byref(z.desc()), _ptr(mask), _stream()))
+    return mask
+
+
+def h3d_pool3d_bwd_mask(dy: Slab, mask, g: Slab, act: int, alpha: float = 0.0):
+    _check(lib().h3d_pool3d_bwd_mask(handle(), ctypes.byref(dy.desc()), _ptr(mask), ctypes.byref(g.desc()), act, alpha, _stream()))
+    return g
 
 
 def h3d_conv3d_bwd_data(dz: Slab, z: Slab | None, w, dx: Slab, act: int = ACT_NONE, alpha: float = 0.0,
@@ -409,6 +444,7 @@ conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_
 pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
 box_bytes, box_pack, box_unpack = h3d_box_bytes, h3d_box_pack, h3d_box_unpack
+conv3d_fwd_pool, act_mask, act_mask_bytes, pool3d_bwd_mask = h3d_conv3d_fwd_pool, h3d_act_mask, h3d_act_mask_bytes, h3d_pool3d_bwd_mask
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c
 dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd

@@ -17,6 +17,10 @@ h3d_status bwd_filter_direct(void* handle, const h3d_tensor* x, const h3d_tensor
                              float* db, float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream);
 // conv_small_cin.hip
 bool c4_fwd_supported(const h3d_tensor* in, const h3d_tensor* out);
+bool c4_fwd_pool_supported(const h3d_tensor* in, const h3d_tensor* z, const h3d_tensor* y);
+h3d_status conv3d_fwd_c4_pool(void* handle, const h3d_tensor* in, const void* w, const float* bias, const h3d_tensor* z, h3d_tensor* y,
+                              void* mask, float out_slope, void* ws, size_t ws_bytes, hipStream_t stream);
+h3d_status pool_shapes_check(void* handle, const h3d_tensor* big, const h3d_tensor* small, const char* what);
 size_t c4_fwd_ws_bytes(const h3d_tensor* out);
 h3d_status conv3d_fwd_c4(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, float out_slope,
                          void* ws, size_t ws_bytes, hipStream_t stream);
@@ -84,6 +88,30 @@ extern "C" h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const vo
   if (mfma_fwd_supported(x, z)) return conv3d_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return conv3d_direct<float>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   return conv3d_direct<bf16_t>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
+}
+
+extern "C" h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z,
+                                          h3d_tensor* y, void* mask, int act, float alpha, void* ws, size_t ws_bytes, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (!z || !y) return fail(handle, H3D_EINVAL, "conv3d_fwd_pool: NULL descriptor");
+  h3d_tensor zc = *z;                    // z may be shape-only (data == NULL: the unpooled output is not stored)
+  if (!zc.data) zc.data = y->data;
+  H3D_TRY(check_tensor(handle, x, "x"));
+  H3D_TRY(check_tensor(handle, &zc, "z"));
+  H3D_TRY(check_tensor_packed(handle, y, "y"));
+  H3D_TRY(check_act(handle, act));
+  if (!w && x->c * z->c > 0) return fail(handle, H3D_EINVAL, "conv3d_fwd_pool: NULL weights");
+  H3D_TRY(check_pair(handle, x, &zc, "conv3d_fwd_pool"));
+  H3D_TRY(pool_shapes_check(handle, &zc, y, "conv3d_fwd_pool"));
+  const float slope = act_slope(act, alpha);
+  hipStream_t s = (hipStream_t)stream;
+  if (c4_fwd_pool_supported(x, z, y)) return conv3d_fwd_c4_pool(handle, x, w, bias, z, y, mask, slope, ws, ws_bytes, s);
+  // other shapes: the three passes one after the other (the unpooled output must then be stored)
+  if (!z->data) return fail(handle, H3D_EUNSUPPORTED, "conv3d_fwd_pool: this shape has no fused kernel, z must be stored");
+  H3D_TRY(h3d_conv3d_fwd(handle, x, w, bias, z, act, alpha, ws, ws_bytes, stream));
+  H3D_TRY(h3d_pool3d_fwd(handle, z, y, H3D_POOL_AVG, stream));
+  if (mask) H3D_TRY(h3d_act_mask(handle, z, mask, stream));
+  return H3D_OK;
 }
 
 extern "C" h3d_status h3d_conv3d_bwd_data(void* handle, const h3d_tensor* dz, const h3d_tensor* z, const void* w,

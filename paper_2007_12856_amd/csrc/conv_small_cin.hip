@@ -52,14 +52,20 @@ struct C4Args {
   int tiles_w, tiles_h, tiles_d;
   float out_slope;
   int vec_ok;
+  // fused 2x2x2 average pooling (POOL kernels): pooled output, optional sign mask (one bit per unpooled voxel, 8 voxels
+  // of a row per byte, rows packed [n][c][plane][h][w/8]); `out` may then be NULL (the unpooled tensor is not stored)
+  Geo yp;
+  bf16_t* ypool;
+  uint8_t* mask;
 };
 
-template <int RB>
+template <int RB, bool POOL>
 __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wA,
                                                             const float* __restrict__ bias, bf16_t* __restrict__ out, C4Args a) {
   using namespace c4;
   __shared__ uint2 xs[XS_VOX];
   __shared__ __attribute__((aligned(16))) bf16_t ot[4][16 * RB][OTP];
+  __shared__ float px[POOL ? 2 : 1][POOL ? 2 : 1][POOL ? RB * 8 : 1][64];   // pooling: partial sums of the odd planes, [row pair][plane pair][value][lane]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lj = lane & 15;
   // consecutive workgroup ids go to different XCDs (each with its own L2): XCD x takes the depth slabs x, x + 8, ...
@@ -189,7 +195,9 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   float bv[RB];      // this lane's output channel of row block rb: 16 rb + lj
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) bv[rb] = (bias && rb * 16 + lj < a.cout) ? bias[rb * 16 + lj] : 0.f;
-  bf16_t* out_n = out + n * a.out.nstride + (int64_t)ps * a.out.plane;
+  bf16_t* out_n = out ? out + n * a.out.nstride + (int64_t)ps * a.out.plane : nullptr;
+  const bool keep_row = !POOL || out || a.mask;     // the row goes through the LDS patch only if z or the mask is stored
+  float psum[RB][4][2];                              // POOL: sums over this plane's row pair, per pooled voxel
   for (int hl = 0; hl < TH; ++hl) {
     f32x4 acc[4][RB];
 #pragma unroll
@@ -224,11 +232,18 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
           if (!(v[r] > 0.f)) v[r] *= a.out_slope;
         }
         const uint2 pk = inside ? uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])} : uint2{0u, 0u};
-        *reinterpret_cast<uint2*>(&ot[wave][rb * 16 + lj][vb * 16 + 4 * lg]) = pk;
+        if (keep_row) *reinterpret_cast<uint2*>(&ot[wave][rb * 16 + lj][vb * 16 + 4 * lg]) = pk;
+        if (POOL) {
+          // the pooling reads the values as they are stored (rounded to bf16), pairs along W first
+          const float s0 = __uint_as_float(pk.x << 16) + __uint_as_float(pk.x & 0xffff0000u);
+          const float s1 = __uint_as_float(pk.y << 16) + __uint_as_float(pk.y & 0xffff0000u);
+          if (hl & 1) { psum[rb][vb][0] += s0; psum[rb][vb][1] += s1; }
+          else { psum[rb][vb][0] = s0; psum[rb][vb][1] = s1; }
+        }
       }
     asm volatile("" ::: "memory");
     const int h = h0 + hl;
-    if (plane_ok && h < H) {
+    if (keep_row && plane_ok && h < H) {
 #pragma unroll
       for (int i = 0; i < 2 * RB; ++i) {
         const int u = lane + 64 * i;
@@ -236,14 +251,55 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
         const int w = w0 + 8 * wu;
         if (co < a.cout && w < W) {
           const uint4 v = *reinterpret_cast<const uint4*>(&ot[wave][co][8 * wu]);
-          bf16_t* o = out_n + (int64_t)co * a.out.cstride + (int64_t)h * W + w;
-          if (a.vec_ok && w + 8 <= W) {
-            *reinterpret_cast<uint4*>(o) = v;
-          } else {
-            const uint32_t e[4] = {v.x, v.y, v.z, v.w};
+          if (out_n) {
+            bf16_t* o = out_n + (int64_t)co * a.out.cstride + (int64_t)h * W + w;
+            if (a.vec_ok && w + 8 <= W) {
+              *reinterpret_cast<uint4*>(o) = v;
+            } else {
+              const uint32_t e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-              if (w + k < W) o[k] = (bf16_t)(e[k >> 1] >> (16 * (k & 1)));
+              for (int k = 0; k < 8; ++k)
+                if (w + k < W) o[k] = (bf16_t)(e[k >> 1] >> (16 * (k & 1)));
+            }
+          }
+          if (POOL && a.mask) {
+            // bit k of the byte: stored value of voxel w + k is > 0 (bf16 as a signed 16-bit integer: positive, not zero)
+            const uint32_t e[4] = {v.x, v.y, v.z, v.w};
+            uint32_t bits = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              bits |= ((int)(e[k] << 16) > 0 ? 1u : 0u) << (2 * k);
+              bits |= ((int)(e[k] & 0xffff0000u) > 0 ? 1u : 0u) << (2 * k + 1);
+            }
+            a.mask[((((int64_t)n * a.cout + co) * a.out.ds + ps) * H + h) * (W / 8) + (w >> 3)] = (uint8_t)bits;
+          }
+        }
+      }
+    }
+    if (POOL && (hl & 1)) {
+      // planes meet: the odd plane of a pair hands its sums over through LDS, the even plane adds, scales and stores
+      const int rp = hl >> 1, pp = wave >> 1;
+      if (wave & 1) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int vb = 0; vb < 4; ++vb) {
+            px[rp][pp][(rb * 4 + vb) * 2][lane] = psum[rb][vb][0];
+            px[rp][pp][(rb * 4 + vb) * 2 + 1][lane] = psum[rb][vb][1];
+          }
+      }
+      __syncthreads();
+      if (!(wave & 1) && plane_ok && h < H) {
+        bf16_t* yo = a.ypool + n * a.yp.nstride + (int64_t)((ps >> 1) + a.yp.hlo) * a.yp.plane + (int64_t)(h >> 1) * (W >> 1) + (w0 >> 1) + 2 * lg;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          const int co = rb * 16 + lj;
+#pragma unroll
+          for (int vb = 0; vb < 4; ++vb) {
+            const float q0 = (psum[rb][vb][0] + px[rp][pp][(rb * 4 + vb) * 2][lane]) * 0.125f;
+            const float q1 = (psum[rb][vb][1] + px[rp][pp][(rb * 4 + vb) * 2 + 1][lane]) * 0.125f;
+            if (co < a.cout && w0 + 16 * vb + 4 * lg < W)
+              *reinterpret_cast<uint32_t*>(yo + (int64_t)co * a.yp.cstride + 8 * vb) = pack_bf16x2(q0, q1);
           }
         }
       }
@@ -275,12 +331,48 @@ h3d_status conv3d_fwd_c4(void* handle, const h3d_tensor* in, const void* w, cons
   hipLaunchKernelGGL(pack_w_c4_kernel, dim3((unsigned)cdiv(nrb * 4 * 512, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws,
                      a.cin, a.cout, nrb);
   if (nrb == 1)
-    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<1>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<1, false>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
                        (const uint4*)ws, bias, (bf16_t*)out->data, a);
   else
-    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<2>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<2, false>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
                        (const uint4*)ws, bias, (bf16_t*)out->data, a);
   return launch_status(handle, "conv3d_fwd_c4");
+}
+
+// Fused forward + 2x2x2 average pooling (+ sign mask): z without halos, even extents, W a multiple of 8, 16-byte
+// aligned tensors; y = the pooled tensor of the same shard (halos allowed, only its interior is written).
+bool c4_fwd_pool_supported(const h3d_tensor* in, const h3d_tensor* z, const h3d_tensor* y) {
+  if (!c4_fwd_supported(in, z) || y->dtype != H3D_BF16) return false;
+  if (z->halo_lo || z->halo_hi || z->d % 2 || z->h % 2 || z->w % 8 || !is_packed(z) || !is_packed(y)) return false;
+  if (y->n != z->n || y->c != z->c || y->d != z->d / 2 || y->h != z->h / 2 || y->w != z->w / 2) return false;
+  if ((uintptr_t)in->data % 16 || (z->data && (uintptr_t)z->data % 16) || (uintptr_t)y->data % 4) return false;
+  return true;
+}
+
+h3d_status conv3d_fwd_c4_pool(void* handle, const h3d_tensor* in, const void* w, const float* bias, const h3d_tensor* z, h3d_tensor* y,
+                              void* mask, float out_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
+  using namespace c4;
+  C4Args a;
+  a.in = make_geo(in); a.out = make_geo(z); a.yp = make_geo(y);
+  a.cin = in->c; a.cout = z->c; a.out_slope = out_slope;
+  a.ypool = (bf16_t*)y->data; a.mask = (uint8_t*)mask;
+  if ((int64_t)z->n * a.out.ds * z->h * z->w == 0) return H3D_OK;
+  const int nrb = (int)cdiv(z->c, 16);
+  if (!ws || ws_bytes < c4_fwd_ws_bytes(z)) return fail(handle, H3D_EWORKSPACE, "conv3d_fwd_pool: workspace too small");
+  if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d_fwd_pool: workspace must be 16-byte aligned");
+  a.vec_ok = 1;
+  a.tiles_w = (int)cdiv(z->w, TW); a.tiles_h = (int)cdiv(z->h, TH); a.tiles_d = (int)cdiv(a.out.ds, TD);
+  int64_t grid = (int64_t)z->n * a.tiles_d * a.tiles_h * a.tiles_w;
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "conv3d_fwd_pool: too many workgroups");
+  hipLaunchKernelGGL(pack_w_c4_kernel, dim3((unsigned)cdiv(nrb * 4 * 512, 256)), dim3(256), 0, stream, (const bf16_t*)w, (bf16_t*)ws,
+                     a.cin, a.cout, nrb);
+  if (nrb == 1)
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<1, true>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+                       (const uint4*)ws, bias, (bf16_t*)z->data, a);
+  else
+    hipLaunchKernelGGL((conv3d_fwd_c4_kernel<2, true>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t*)in->data,
+                       (const uint4*)ws, bias, (bf16_t*)z->data, a);
+  return launch_status(handle, "conv3d_fwd_c4_pool");
 }
 
 }  // namespace h3d

@@ -131,6 +131,57 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy,
     *reinterpret_cast<Vec<T, 2 * VEC>*>(dx + dxoff + (k >> 1) * a.x.plane + (k & 1) * a.x.w) = o[k];
 }
 
+// Sign mask of a saved activation output: bit k of byte j of a row = (z[8 j + k] > 0); rows packed
+// [n][c][interior plane][h][w/8].  One thread per byte.
+template <typename T>
+__global__ void __launch_bounds__(256) act_mask_kernel(const T* __restrict__ z, uint8_t* __restrict__ mask, Geo g, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  int64_t t = i;
+  const int wb = (int)(t % (g.w / 8)); t /= g.w / 8;
+  const int h = (int)(t % g.h); t /= g.h;
+  const int p = (int)(t % g.d); t /= g.d;
+  const int c = (int)(t % g.c);
+  const int64_t n = t / g.c;
+  const T* src = z + n * g.nstride + c * g.cstride + (int64_t)(p + g.hlo) * g.plane + (int64_t)h * g.w + 8 * wb;
+  uint32_t bits = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) bits |= (ld(src + k) > 0.f ? 1u : 0u) << k;
+  mask[i] = (uint8_t)bits;
+}
+
+// Average-pooling backward fused with the activation derivative read from the sign mask instead of the saved
+// output: g = dy / 8 (rounded to storage) where the bit is set, that value times slope (rounded again) elsewhere —
+// bit for bit what pool_bwd_kernel<.., ACT> writes from z itself, for 1/16 of its mask traffic.
+__global__ void __launch_bounds__(256) pool_bwd_mask_kernel(const bf16_t* __restrict__ dy, const uint8_t* __restrict__ mask,
+                                                            bf16_t* __restrict__ g, PoolArgs a, float slope) {
+  constexpr int VEC = 8;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.total) return;
+  int64_t goff, yoff;
+  decode<bf16_t, VEC>(a, t, goff, yoff);
+  int64_t r = t;
+  const int wv = (int)(r % a.wv); r /= a.wv;
+  const int ho = (int)(r % a.y.h); r /= a.y.h;
+  const int q = (int)(r % a.y.d); r /= a.y.d;      // r = n * C + c
+  const Vec<bf16_t, VEC> gy = *reinterpret_cast<const Vec<bf16_t, VEC>*>(dy + yoff);
+  bf16_t v[VEC], vs[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) {
+    v[i] = f32_to_bf16(bf16_to_f32(gy.v[i]) * 0.125f);
+    vs[i] = f32_to_bf16(bf16_to_f32(v[i]) * slope);
+  }
+  const int64_t mrow = ((r * a.x.d + 2 * q) * a.x.h + 2 * ho) * (a.x.w / 8) + 2 * wv;   // byte of the first of the four rows
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t m = *reinterpret_cast<const uint16_t*>(mask + mrow + ((int64_t)(k >> 1) * a.x.h + (k & 1)) * (a.x.w / 8));
+    Vec<bf16_t, 2 * VEC> o;
+#pragma unroll
+    for (int i = 0; i < 2 * VEC; ++i) o.v[i] = ((m >> i) & 1u) ? v[i >> 1] : vs[i >> 1];
+    *reinterpret_cast<Vec<bf16_t, 2 * VEC>*>(g + goff + (k >> 1) * a.x.plane + (k & 1) * a.x.w) = o;
+  }
+}
+
 static h3d_status pool_check(void* handle, const h3d_tensor* big, const h3d_tensor* small, const char* what) {
   if (big->dtype != small->dtype || big->n != small->n || big->c != small->c)
     return fail(handle, H3D_EINVAL, "%s: n/c/dtype mismatch", what);
@@ -140,6 +191,10 @@ static h3d_status pool_check(void* handle, const h3d_tensor* big, const h3d_tens
       small->d_offset * 2 != big->d_offset || small->d_global * 2 != big->d_global)
     return fail(handle, H3D_EINVAL, "%s: pooled extents/offsets must be half of the input's", what);
   return H3D_OK;
+}
+
+h3d_status pool_shapes_check(void* handle, const h3d_tensor* big, const h3d_tensor* small, const char* what) {
+  return pool_check(handle, big, small, what);
 }
 
 template <typename T>
@@ -260,4 +315,49 @@ static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_te
                                 : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
   return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope)
                               : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
+}
+
+extern "C" size_t h3d_act_mask_bytes(const h3d_tensor* z) {
+  if (!z || z->w % 8 || z->n <= 0 || z->c <= 0 || z->d <= 0 || z->h <= 0) return 0;
+  return (size_t)z->n * z->c * z->d * z->h * (z->w / 8);
+}
+
+extern "C" h3d_status h3d_act_mask(void* handle, const h3d_tensor* z, void* mask, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  H3D_TRY(check_tensor_packed(handle, z, "z"));
+  if (z->w % 8) return fail(handle, H3D_EUNSUPPORTED, "act_mask: w must be a multiple of 8");
+  const int64_t total = (int64_t)h3d_act_mask_bytes(z);
+  if (total == 0) return H3D_OK;
+  if (!mask) return fail(handle, H3D_EINVAL, "act_mask: NULL mask");
+  const Geo g = make_geo(z);
+  const int64_t grid = cdiv(total, 256);
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "act_mask: too many blocks");
+  if (z->dtype == H3D_F32)
+    hipLaunchKernelGGL((act_mask_kernel<float>), dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const float*)z->data, (uint8_t*)mask, g, total);
+  else
+    hipLaunchKernelGGL((act_mask_kernel<bf16_t>), dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)z->data, (uint8_t*)mask, g, total);
+  return launch_status(handle, "act_mask");
+}
+
+extern "C" h3d_status h3d_pool3d_bwd_mask(void* handle, const h3d_tensor* dy, const void* mask, h3d_tensor* g, int act, float alpha,
+                                          void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (act != H3D_ACT_RELU && act != H3D_ACT_LEAKY) return fail(handle, H3D_EINVAL, "pool3d_bwd_mask: activation must be RELU or LEAKY");
+  H3D_TRY(check_tensor_packed(handle, dy, "dy"));
+  H3D_TRY(check_tensor_packed(handle, g, "g"));
+  H3D_TRY(pool_check(handle, g, dy, "pool3d_bwd_mask"));
+  if (g->dtype != H3D_BF16 || g->w % 16 || (uintptr_t)g->data % 32 || (uintptr_t)dy->data % 16 || (uintptr_t)mask % 2)
+    return fail(handle, H3D_EUNSUPPORTED, "pool3d_bwd_mask: bf16, w a multiple of 16 and aligned tensors only");
+  PoolArgs a;
+  a.x = make_geo(g);
+  a.y = make_geo(dy);
+  a.wv = dy->w / 8;
+  a.total = (int64_t)dy->n * dy->c * dy->d * dy->h * a.wv;
+  if (a.total == 0) return H3D_OK;
+  if (!mask) return fail(handle, H3D_EINVAL, "pool3d_bwd_mask: NULL mask");
+  const int64_t grid = cdiv(a.total, 256);
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "pool3d_bwd_mask: too many blocks");
+  hipLaunchKernelGGL(pool_bwd_mask_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)dy->data,
+                     (const uint8_t*)mask, (bf16_t*)g->data, a, act_slope(act, alpha));
+  return launch_status(handle, "pool3d_bwd_mask");
 }
