@@ -148,6 +148,8 @@ def main():
                     "used to profile one kernel under rocprofv3")
     ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
+    ap.add_argument("--unfused", action="store_true", help="store the first stage's unpooled activation (separate conv, pool and "
+                    "pool-backward calls) instead of the fused forward + sign mask")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
@@ -195,7 +197,7 @@ def main():
     P = recipes.cosmoflow_params(seed, args.width)
     x, t = recipes.cosmoflow_batch(seed, args.batch, args.width)
     net = CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), dev(b, torch.float32)) for w, b in P["conv"]],
-                         [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]])
+                         [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused)
     del P, x
     stream = torch.cuda.current_stream()
 

@@ -65,7 +65,6 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   using namespace c4;
   __shared__ uint2 xs[XS_VOX];
   __shared__ __attribute__((aligned(16))) bf16_t ot[4][16 * RB][OTP];
-  __shared__ float px[POOL ? 2 : 1][POOL ? 2 : 1][POOL ? RB * 8 : 1][64];   // pooling: partial sums of the odd planes, [row pair][plane pair][value][lane]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lj = lane & 15;
   // consecutive workgroup ids go to different XCDs (each with its own L2): XCD x takes the depth slabs x, x + 8, ...
@@ -187,24 +186,27 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
   }
   __syncthreads();
 
-  // ---- this wavefront's depth plane, one output row (64 voxels) at a time
-  const int ps = ps0 + wave;
-  const int64_t gp = a.out.doff + ps - a.out.hlo;
-  const bool inside = gp >= 0 && gp < a.out.dglob;
-  const bool plane_ok = ps < a.out.ds;
+  // ---- this wavefront's share of the tile, one output row (64 voxels) at a time: a depth plane and its four rows;
+  //      with pooling, a PAIR of planes and a pair of rows, so that every 2x2x2 window is summed inside one lane
   float bv[RB];      // this lane's output channel of row block rb: 16 rb + lj
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) bv[rb] = (bias && rb * 16 + lj < a.cout) ? bias[rb * 16 + lj] : 0.f;
-  bf16_t* out_n = out ? out + n * a.out.nstride + (int64_t)ps * a.out.plane : nullptr;
   const bool keep_row = !POOL || out || a.mask;     // the row goes through the LDS patch only if z or the mask is stored
-  float psum[RB][4][2];                              // POOL: sums over this plane's row pair, per pooled voxel
-  for (int hl = 0; hl < TH; ++hl) {
+  float psum[RB][4][2];                              // POOL: sums over the window's planes and rows, per pooled voxel
+  for (int it = 0; it < TH; ++it) {
+    const int pl = POOL ? 2 * (wave >> 1) + (it >> 1) : wave;      // plane and row of the tile
+    const int hl = POOL ? 2 * (wave & 1) + (it & 1) : it;
+    const int ps = ps0 + pl;
+    const int64_t gp = a.out.doff + ps - a.out.hlo;
+    const bool inside = gp >= 0 && gp < a.out.dglob;
+    const bool plane_ok = ps < a.out.ds;
+    bf16_t* out_n = out ? out + n * a.out.nstride + (int64_t)ps * a.out.plane : nullptr;
     f32x4 acc[4][RB];
 #pragma unroll
     for (int vb = 0; vb < 4; ++vb)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) acc[vb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int vrow = wave * PDV + hl * PRV + 7 + lj;   // tap (0,0,0) of this lane's voxel in block 0
+    const int vrow = pl * PDV + hl * PRV + 7 + lj;   // tap (0,0,0) of this lane's voxel in block 0
 #pragma unroll
     for (int vb = 0; vb < 4; ++vb) {
 #pragma unroll
@@ -237,7 +239,7 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
           // the pooling reads the values as they are stored (rounded to bf16), pairs along W first
           const float s0 = __uint_as_float(pk.x << 16) + __uint_as_float(pk.x & 0xffff0000u);
           const float s1 = __uint_as_float(pk.y << 16) + __uint_as_float(pk.y & 0xffff0000u);
-          if (hl & 1) { psum[rb][vb][0] += s0; psum[rb][vb][1] += s1; }
+          if (it) { psum[rb][vb][0] += s0; psum[rb][vb][1] += s1; }
           else { psum[rb][vb][0] = s0; psum[rb][vb][1] = s1; }
         }
       }
@@ -276,32 +278,16 @@ __global__ void __launch_bounds__(256) conv3d_fwd_c4_kernel(const bf16_t* __rest
         }
       }
     }
-    if (POOL && (hl & 1)) {
-      // planes meet: the odd plane of a pair hands its sums over through LDS, the even plane adds, scales and stores
-      const int rp = hl >> 1, pp = wave >> 1;
-      if (wave & 1) {
+    if (POOL && it == TH - 1 && plane_ok && h < H) {
+      // the window is complete (this was its last plane and row): scale, round, 4-byte stores of two pooled voxels
+      bf16_t* yo = a.ypool + n * a.yp.nstride + (int64_t)((ps >> 1) + a.yp.hlo) * a.yp.plane + (int64_t)(h >> 1) * (W >> 1) + (w0 >> 1) + 2 * lg;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+      for (int rb = 0; rb < RB; ++rb) {
+        const int co = rb * 16 + lj;
 #pragma unroll
-          for (int vb = 0; vb < 4; ++vb) {
-            px[rp][pp][(rb * 4 + vb) * 2][lane] = psum[rb][vb][0];
-            px[rp][pp][(rb * 4 + vb) * 2 + 1][lane] = psum[rb][vb][1];
-          }
-      }
-      __syncthreads();
-      if (!(wave & 1) && plane_ok && h < H) {
-        bf16_t* yo = a.ypool + n * a.yp.nstride + (int64_t)((ps >> 1) + a.yp.hlo) * a.yp.plane + (int64_t)(h >> 1) * (W >> 1) + (w0 >> 1) + 2 * lg;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          const int co = rb * 16 + lj;
-#pragma unroll
-          for (int vb = 0; vb < 4; ++vb) {
-            const float q0 = (psum[rb][vb][0] + px[rp][pp][(rb * 4 + vb) * 2][lane]) * 0.125f;
-            const float q1 = (psum[rb][vb][1] + px[rp][pp][(rb * 4 + vb) * 2 + 1][lane]) * 0.125f;
-            if (co < a.cout && w0 + 16 * vb + 4 * lg < W)
-              *reinterpret_cast<uint32_t*>(yo + (int64_t)co * a.yp.cstride + 8 * vb) = pack_bf16x2(q0, q1);
-          }
-        }
+        for (int vb = 0; vb < 4; ++vb)
+          if (co < a.cout && w0 + 16 * vb + 4 * lg < W)
+            *reinterpret_cast<uint32_t*>(yo + (int64_t)co * a.yp.cstride + 8 * vb) = pack_bf16x2(psum[rb][vb][0] * 0.125f, psum[rb][vb][1] * 0.125f);
       }
     }
   }

@@ -10,24 +10,32 @@ from __future__ import annotations
 import torch
 
 from . import (ACT_LEAKY, ACT_NONE, POOL_AVG, Slab, Workspace, conv3d_bwd_data, conv3d_bwd_filter, conv3d_fwd,
-               dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_fwd)
+               conv3d_fwd_pool, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd)
 
 
 class CosmoFlowStack:
-    def __init__(self, x: torch.Tensor, target: torch.Tensor, conv_params, fc_params, alpha: float = 0.01):
+    def __init__(self, x: torch.Tensor, target: torch.Tensor, conv_params, fc_params, alpha: float = 0.01, fuse_pool: bool = False):
         """x [N,C,D,H,W] device tensor; conv_params/fc_params: lists of (w, bias) device tensors
         (w in x's dtype, bias fp32); target fp32 [N, nout]."""
         self.alpha = alpha
         self.ws = Workspace()
         dt, dev = x.dtype, x.device
+        # fuse_pool: stages whose convolution has a fused forward (first layer: Cin <= 4) never store the unpooled
+        # activation: the forward writes the pooled tensor and a sign mask, the backward reads the mask
+        self.fused = [bool(fuse_pool) and dt == torch.bfloat16 and w.shape[1] <= 4 and w.shape[0] <= 32 for w, _ in conv_params]
         self.x = Slab(x)
         self.target = target
         self.conv, self.fc = conv_params, fc_params
         n = x.shape[0]
         self.z, self.p = [], []
         cur = self.x
-        for w, _ in conv_params:
-            z = cur.like(w.shape[0])
+        self.mask = []
+        for i, (w, _) in enumerate(conv_params):
+            fused = self.fused[i] and cur.d % 2 == 0 and cur.t.shape[3] % 2 == 0 and cur.t.shape[4] % 16 == 0
+            self.fused[i] = fused
+            z = None if fused else cur.like(w.shape[0])
+            self.mask.append(torch.empty((n * w.shape[0] * cur.d * cur.t.shape[3] * cur.t.shape[4] // 8,), dtype=torch.uint8, device=dev)
+                             if fused else None)
             p = Slab(torch.empty((n, w.shape[0], cur.d // 2, cur.t.shape[3] // 2, cur.t.shape[4] // 2), dtype=dt, device=dev))
             self.z.append(z)
             self.p.append(p)
@@ -40,7 +48,8 @@ class CosmoFlowStack:
         self.dfc = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
                     for w, b in fc_params]
         self.dp = [Slab(torch.empty_like(p.t)) for p in self.p]
-        self.g = [Slab(torch.empty_like(z.t)) for z in self.z]     # g = dz * act'(z), pre-activation gradient
+        self.g = [Slab(torch.empty((n, w.shape[0], 2 * p.d, 2 * p.t.shape[3], 2 * p.t.shape[4]), dtype=dt, device=dev))
+                  for (w, _), p in zip(conv_params, self.p)]     # g = dz * act'(z), pre-activation gradient
         self.dx = Slab(torch.empty_like(x))
         self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
                       for w, b in conv_params]
@@ -61,10 +70,16 @@ class CosmoFlowStack:
         cur = self.x
         for i, (w, b) in enumerate(self.conv):
             z, p = self.z[i], self.p[i]
-            fl = 2 * 27 * w.shape[1] * w.shape[0] * z.t.numel() // w.shape[0]
-            io = (cur.t.numel() + z.t.numel() + w.numel()) * es
-            self._op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z: conv3d_fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl, io)
-            self._op(f"pool{i + 1}_fwd", lambda z=z, p=p: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
+            zvox = self.g[i].t.numel() // w.shape[0]
+            fl = 2 * 27 * w.shape[1] * w.shape[0] * zvox
+            if self.fused[i]:
+                zshape, mask = tuple(self.g[i].t.shape), self.mask[i]
+                self._op(f"conv{i + 1}_fwd_pool", lambda cur=cur, w=w, b=b, zshape=zshape, p=p, mask=mask: conv3d_fwd_pool(
+                    cur, w, b, zshape, p, mask, ACT_LEAKY, al, ws), fl, (cur.t.numel() + p.t.numel() + w.numel()) * es + mask.numel())
+            else:
+                io = (cur.t.numel() + z.t.numel() + w.numel()) * es
+                self._op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z: conv3d_fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl, io)
+                self._op(f"pool{i + 1}_fwd", lambda z=z, p=p: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
             cur = p
         h = self.flat
         for i, (w, b) in enumerate(self.fc):
@@ -88,10 +103,15 @@ class CosmoFlowStack:
             z, g, dp = self.z[i], self.g[i], self.dp[i]
             xin = self.x if i == 0 else self.p[i - 1]
             dxin = self.dx if i == 0 else self.dp[i - 1]
-            fl = 2 * 27 * w.shape[1] * w.shape[0] * z.t.numel() // w.shape[0]
+            fl = 2 * 27 * w.shape[1] * g.t.numel()
             # pooling backward and activation backward in one pass; BF and BD then run unmasked on g
-            self._op(f"pool{i + 1}_bwd_act", lambda dp=dp, z=z, g=g: pool3d_bwd_act(dp, None, z, g, POOL_AVG, ACT_LEAKY, al), 0,
-                     (dp.t.numel() + z.t.numel() + g.t.numel()) * es)
+            if self.fused[i]:
+                mask = self.mask[i]
+                self._op(f"pool{i + 1}_bwd_mask", lambda dp=dp, mask=mask, g=g: pool3d_bwd_mask(dp, mask, g, ACT_LEAKY, al), 0,
+                         (dp.t.numel() + g.t.numel()) * es + mask.numel())
+            else:
+                self._op(f"pool{i + 1}_bwd_act", lambda dp=dp, z=z, g=g: pool3d_bwd_act(dp, None, z, g, POOL_AVG, ACT_LEAKY, al), 0,
+                         (dp.t.numel() + z.t.numel() + g.t.numel()) * es)
             self._op(f"conv{i + 1}_bwd_filter", lambda xin=xin, g=g, i=i: conv3d_bwd_filter(
                 xin, g, None, self.dconv[i][0], self.dconv[i][1], ACT_NONE, 0.0, ws), fl,
                 (xin.t.numel() + g.t.numel()) * es + w.numel() * 4)

@@ -11,7 +11,7 @@ from oracle_nets import cosmoflow_oracle
 pytestmark = pytest.mark.gpu
 
 
-def build(dtype, n, width, channels, fc, seed):
+def build(dtype, n, width, channels, fc, seed, fuse_pool=False):
     import paper_2007_12856_amd as h3d
     from paper_2007_12856_amd.nets import CosmoFlowStack
     P = recipes.cosmoflow_params(seed, width, channels, fc)
@@ -20,7 +20,7 @@ def build(dtype, n, width, channels, fc, seed):
     fcq = [(quantize(w, dtype), synth.round_f32(b).astype(np.float64)) for w, b in P["fc"]]
     xq, tq = quantize(x, dtype), synth.round_f32(t).astype(np.float64)
     net = CosmoFlowStack(to_dev(xq, dtype), to_dev(tq, "f32"), [(to_dev(w, dtype), to_dev(b, "f32")) for w, b in convq],
-                         [(to_dev(w, dtype), to_dev(b, "f32")) for w, b in fcq])
+                         [(to_dev(w, dtype), to_dev(b, "f32")) for w, b in fcq], fuse_pool=fuse_pool)
     return net, xq, tq, convq, fcq
 
 
@@ -47,6 +47,29 @@ def test_cosmoflow_stack_miniature(dtype, tol):
     # with slope 0.01 that perturbs the gradient norm far below the bar
     for i in range(len(fcq)):
         assert rel_l2(from_dev(net.dfc[i][0]), ref["dfc"][i][0]) <= 2 * tol, f"dfc{i}"
+    for i in range(len(convq)):
+        assert rel_l2(from_dev(net.dconv[i][0]), ref["dconv"][i][0]) <= 2 * tol, f"dw{i}"
+        assert rel_l2(from_dev(net.dconv[i][1]), ref["dconv"][i][1]) <= 2 * tol, f"db{i}"
+    assert rel_l2(from_dev(net.dx.t), ref["dx"].a) <= 2 * tol
+
+
+def test_cosmoflow_stack_miniature_with_fused_first_stage():
+    """The same miniature with the first stage's unpooled activation never stored (fused conv + pool forward, sign mask,
+    pooling backward from the mask): same bars against the oracle; the first stage has no z to compare."""
+    import torch
+    dtype, tol = "bf16", 2e-2
+    net, xq, tq, convq, fcq = build(dtype, 2, 32, (4, 16, 32, 64), (128, 32, 4), synth.BASE_SEED + 5, fuse_pool=True)
+    assert net.fused == [True, False, False] and net.z[0] is None
+    assert [o["name"] for o in net.ops][:3] == ["conv1_fwd_pool", "conv2_fwd", "pool2_fwd"]
+    net.step()
+    torch.cuda.synchronize()
+    ref = cosmoflow_oracle(xq, tq, convq, fcq, q=lambda v: quantize(v, dtype))
+    for i in range(1, len(convq)):
+        assert rel_l2(from_dev(net.z[i].t), ref["z"][i].a) <= tol, f"z{i}"
+    assert rel_l2(from_dev(net.y[-1]), ref["y"][-1]) <= tol
+    net.dy[-1].copy_(to_dev(ref["dpred"], dtype))
+    net.backward_after_loss()
+    torch.cuda.synchronize()
     for i in range(len(convq)):
         assert rel_l2(from_dev(net.dconv[i][0]), ref["dconv"][i][0]) <= 2 * tol, f"dw{i}"
         assert rel_l2(from_dev(net.dconv[i][1]), ref["dconv"][i][1]) <= 2 * tol, f"db{i}"
