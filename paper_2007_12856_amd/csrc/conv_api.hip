@@ -21,6 +21,10 @@ bool c4_fwd_pool_supported(const h3d_tensor* in, const h3d_tensor* z, const h3d_
 h3d_status conv3d_fwd_c4_pool(void* handle, const h3d_tensor* in, const void* w, const float* bias, const h3d_tensor* z, h3d_tensor* y,
                               void* mask, float out_slope, void* ws, size_t ws_bytes, hipStream_t stream);
 h3d_status pool_shapes_check(void* handle, const h3d_tensor* big, const h3d_tensor* small, const char* what);
+bool c4_roll_supported(const h3d_tensor* in, const h3d_tensor* z);
+size_t c4_roll_ws_bytes();
+h3d_status conv3d_fwd_c4_roll(void* handle, const h3d_tensor* in, const void* w, const float* bias, const h3d_tensor* z, const h3d_tensor* y,
+                              void* mask, float out_slope, void* ws, size_t ws_bytes, hipStream_t stream);
 size_t c4_fwd_ws_bytes(const h3d_tensor* out);
 h3d_status conv3d_fwd_c4(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, float out_slope,
                          void* ws, size_t ws_bytes, hipStream_t stream);
@@ -58,7 +62,7 @@ extern "C" size_t h3d_conv3d_workspace_bytes(void* handle, int op, const h3d_ten
   size_t b = 0;
   switch (op) {
     case H3D_OP_FWD:       // x: input, z: output
-      if (c4_fwd_supported(x, z)) b = c4_fwd_ws_bytes(z);
+      if (c4_fwd_supported(x, z)) b = std::max(c4_fwd_ws_bytes(z), c4_roll_ws_bytes());
       [[fallthrough]];
     case H3D_OP_BWD_DATA:  // x: dz (input of the correlation), z: dx
       b = std::max(b, direct_fwd_ws_bytes(x->c, z->c));
@@ -84,6 +88,7 @@ extern "C" h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const vo
   H3D_TRY(check_pair(handle, x, z, "conv3d_fwd"));
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
+  if (c4_roll_supported(x, z) && !getenv("H3D_NO_C4_ROLL")) return conv3d_fwd_c4_roll(handle, x, w, bias, z, nullptr, nullptr, slope, ws, ws_bytes, s);
   if (c4_fwd_supported(x, z)) return conv3d_fwd_c4(handle, x, w, bias, z, slope, ws, ws_bytes, s);
   if (mfma_fwd_supported(x, z)) return conv3d_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return conv3d_direct<float>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
@@ -105,6 +110,8 @@ extern "C" h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, con
   H3D_TRY(pool_shapes_check(handle, &zc, y, "conv3d_fwd_pool"));
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
+  if (c4_fwd_pool_supported(x, z, y) && c4_roll_supported(x, z) && !getenv("H3D_NO_C4_ROLL"))
+    return conv3d_fwd_c4_roll(handle, x, w, bias, z, y, mask, slope, ws, ws_bytes, s);
   if (c4_fwd_pool_supported(x, z, y)) return conv3d_fwd_c4_pool(handle, x, w, bias, z, y, mask, slope, ws, ws_bytes, s);
   // other shapes: the three passes one after the other (the unpooled output must then be stored)
   if (!z->data) return fail(handle, H3D_EUNSUPPORTED, "conv3d_fwd_pool: this shape has no fused kernel, z must be stored");

@@ -29,7 +29,10 @@ def _mask_from_stored(z_stored: np.ndarray) -> np.ndarray:
 # several tiles in every direction, ragged last tiles, two row blocks of output channels), then shapes that take
 # the three-pass route (more input channels; odd multiple of 8 is fine, W = 12 is not a multiple of 8: no mask)
 FUSED = [(1, 4, 16, 4, 4, 64, 0), (2, 4, 16, 6, 10, 72, 0), (1, 1, 32, 8, 6, 136, 0), (1, 3, 20, 2, 2, 8, 0),
-         (1, 4, 16, 4, 8, 64, 1)]
+         (1, 4, 16, 4, 8, 64, 1),
+         # at most 16 output channels and at least 8 rows: the row-streaming kernel (several row segments, ragged plane
+         # quads, one and two column tiles, fewer than 4 input channels)
+         (1, 4, 16, 8, 20, 136, 0), (2, 3, 12, 6, 8, 128, 0), (1, 2, 5, 2, 16, 8, 0), (1, 4, 16, 4, 64, 256, 0)]
 UNFUSED = [(1, 8, 16, 4, 6, 16, 0), (1, 16, 8, 2, 4, 40, 0)]
 
 
