@@ -129,6 +129,45 @@ def conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, act=ACT_NONE, alpha=0.0
     return dw, db
 
 
+def _s2_out(x: Slab, channels: int, halo_lo: int = 0, halo_hi: int = 0, fill: float = np.nan) -> Slab:
+    n, _, _, h, w = x.a.shape
+    a = np.full((n, channels, halo_lo + x.d // 2 + halo_hi, (h + 1) // 2, (w + 1) // 2), fill, dtype=np.float64)
+    return Slab(a, halo_lo, halo_hi, x.d_offset // 2, x.d_global // 2)
+
+
+def conv3d_s2_fwd(x: Slab, w, bias, act=ACT_NONE, alpha=0.0) -> Slab:
+    """Stride-2 3x3x3 convolution (Table I, fourth convolution): y[p] = act(b + sum_k w[k] x~[2p+k-1])."""
+    w = _f64(w)
+    bias = _f64(bias)
+    assert w.shape[1:] == (x.a.shape[1], 3, 3, 3)
+    y = _s2_out(x, w.shape[0])
+    _chk(_L().orc_conv3d_s2_fwd(_p(x.a), x.geom(), _p(w), _p(bias), _p(y.a), y.geom(), int(act),
+                                ctypes.c_double(alpha)), "conv3d_s2_fwd")
+    return y
+
+
+def conv3d_s2_bwd_data(dy: Slab, y: Slab | None, w, x_like: Slab, act=ACT_NONE, alpha=0.0) -> Slab:
+    """dx of the stride-2 convolution on the interior of the input shard described by `x_like`."""
+    w = _f64(w)
+    assert w.shape[0] == dy.a.shape[1] and w.shape[2:] == (3, 3, 3)
+    dx = x_like.like(w.shape[1])
+    _chk(_L().orc_conv3d_s2_bwd_data(_p(dy.a), dy.geom(), _p(y.a) if y is not None else None,
+                                     y.geom() if y is not None else None, _p(w), _p(dx.a), dx.geom(), int(act),
+                                     ctypes.c_double(alpha)), "conv3d_s2_bwd_data")
+    return dx
+
+
+def conv3d_s2_bwd_filter(x: Slab, dy: Slab, y: Slab | None, act=ACT_NONE, alpha=0.0):
+    """The shard's partial dw [cout,cin,3,3,3] and db [cout] of the stride-2 convolution."""
+    cin, cout = x.a.shape[1], dy.a.shape[1]
+    dw = np.zeros((cout, cin, 3, 3, 3), dtype=np.float64)
+    db = np.zeros((cout,), dtype=np.float64)
+    _chk(_L().orc_conv3d_s2_bwd_filter(_p(x.a), x.geom(), _p(dy.a), dy.geom(), _p(y.a) if y is not None else None,
+                                       y.geom() if y is not None else None, _p(dw), _p(db), int(act),
+                                       ctypes.c_double(alpha)), "conv3d_s2_bwd_filter")
+    return dw, db
+
+
 def act_bwd(dz: Slab, dz2: Slab | None, z: Slab, act: int, alpha: float = 0.0, g_halo=(0, 0)) -> Slab:
     """g = (dz + dz2) * (z > 0 ? 1 : slope) on the interior (activation derivative, Sec. IV); halo planes of g are zero."""
     slope = alpha if act == ACT_LEAKY else (0.0 if act == ACT_RELU else 1.0)

@@ -206,6 +206,144 @@ int orc_conv3d_bwd_filter(const double* x, const int64_t* xg, const double* dz, 
   return 0;
 }
 
+/* ------------------------------------------------- stride-2 convolution */
+/* The fourth convolution of the CosmoFlow network has a stride of 2 (Table I); "same" padding
+ * is read as one zero voxel on every side, as for the stride-1 layers, so that an even extent is
+ * halved (odd: rounded up):
+ *   y[n,co,p] = act(b[co] + sum_{ci,k} w[co,ci,k] * x~[n,ci,2p+k-1]).
+ * Slab form: x has even d, d_offset, d_global; y is the shard with all three halved and no halo
+ * planes; output plane p reads input planes 2p-1..2p+1, so x needs its LOWER halo plane only. */
+static int s2_shapes(const int64_t* xg, const int64_t* yg) {
+  if (xg[G_D] % 2 || xg[G_DOFF] % 2 || xg[G_DGLOB] % 2) return 0;
+  return yg[G_N] == xg[G_N] && yg[G_D] == xg[G_D] / 2 && yg[G_H] == (xg[G_H] + 1) / 2 && yg[G_W] == (xg[G_W] + 1) / 2 &&
+         yg[G_DOFF] == xg[G_DOFF] / 2 && yg[G_DGLOB] == xg[G_DGLOB] / 2;
+}
+
+int orc_conv3d_s2_fwd(const double* x, const int64_t* xg, const double* w, const double* bias, double* y,
+                      const int64_t* yg, int act, double alpha) {
+  if (!s2_shapes(xg, yg) || yg[G_HLO] || yg[G_HHI]) return -1;
+  const int64_t N = xg[G_N], Ci = xg[G_C], Co = yg[G_C], H = xg[G_H], W = xg[G_W];
+  const int64_t Do = yg[G_D], Ho = yg[G_H], Wo = yg[G_W];
+  if (Do > 0 && in_volume(xg, -1) && !stored(xg, -1)) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(3) schedule(dynamic, 1)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t co = 0; co < Co; ++co)
+      for (int64_t p = 0; p < Do; ++p)
+        for (int64_t h = 0; h < Ho; ++h)
+          for (int64_t v = 0; v < Wo; ++v) {
+            double acc = bias ? bias[co] : 0.0;
+            for (int64_t ci = 0; ci < Ci; ++ci)
+              for (int kd = 0; kd < 3; ++kd) {
+                const int64_t pp = 2 * p + kd - 1;
+                if (!in_volume(xg, pp)) continue;
+                for (int kh = 0; kh < 3; ++kh) {
+                  const int64_t hh = 2 * h + kh - 1;
+                  if (hh < 0 || hh >= H) continue;
+                  for (int kw = 0; kw < 3; ++kw) {
+                    const int64_t ww = 2 * v + kw - 1;
+                    if (ww < 0 || ww >= W) continue;
+                    acc += w[(((co * Ci + ci) * 3 + kd) * 3 + kh) * 3 + kw] * x[at5(xg, n, ci, pp, hh, ww)];
+                  }
+                }
+              }
+            if (!(acc > 0.0)) acc *= slope;
+            y[at5(yg, n, co, p, h, v)] = acc;
+          }
+  return 0;
+}
+
+/* g = dy * (y > 0 ? 1 : slope);  dx[n,ci,q] = sum over (co,k,p) with 2p+k-1 = q of w[co,ci,k] * g[n,co,p]
+ * for the interior planes q of the input shard.  Plane q = d-1 takes a term from output plane d/2, the
+ * first plane of the shard above: dy (and y) need their UPPER halo plane when it is inside the volume. */
+int orc_conv3d_s2_bwd_data(const double* dy, const int64_t* yg, const double* y, const int64_t* ysg, const double* w,
+                           double* dx, const int64_t* xg, int act, double alpha) {
+  if (!s2_shapes(xg, yg) || xg[G_HLO] || xg[G_HHI]) return -1;
+  const int masked = (y != NULL && act != ACT_NONE);
+  if (masked && (!same_shard(ysg, yg) || ysg[G_C] != yg[G_C])) return -1;
+  const int64_t N = xg[G_N], Ci = xg[G_C], Co = yg[G_C], D = xg[G_D], H = xg[G_H], W = xg[G_W];
+  const int64_t Do = yg[G_D], Ho = yg[G_H], Wo = yg[G_W];
+  if (Do > 0 && in_volume(yg, Do) && (!stored(yg, Do) || (masked && !stored(ysg, Do)))) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(3) schedule(dynamic, 1)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t ci = 0; ci < Ci; ++ci)
+      for (int64_t q = 0; q < D; ++q)
+        for (int64_t h = 0; h < H; ++h)
+          for (int64_t v = 0; v < W; ++v) {
+            double acc = 0.0;
+            for (int64_t co = 0; co < Co; ++co)
+              for (int kd = 0; kd < 3; ++kd) {
+                const int64_t t = q + 1 - kd;            /* = 2p */
+                if (t % 2 != 0 || !in_volume(yg, t / 2)) continue;
+                for (int kh = 0; kh < 3; ++kh) {
+                  const int64_t th = h + 1 - kh;
+                  if (th % 2 != 0 || th < 0 || th / 2 >= Ho) continue;
+                  for (int kw = 0; kw < 3; ++kw) {
+                    const int64_t tw = v + 1 - kw;
+                    if (tw % 2 != 0 || tw < 0 || tw / 2 >= Wo) continue;
+                    double g = dy[at5(yg, n, co, t / 2, th / 2, tw / 2)];
+                    if (masked && !(y[at5(ysg, n, co, t / 2, th / 2, tw / 2)] > 0.0)) g *= slope;
+                    acc += w[(((co * Ci + ci) * 3 + kd) * 3 + kh) * 3 + kw] * g;
+                  }
+                }
+              }
+            dx[at5(xg, n, ci, q, h, v)] = acc;
+          }
+  return 0;
+}
+
+/* dw[co,ci,k] = sum_n sum_{p in the output shard} g[n,co,p] * x~[n,ci,2p+k-1]; db[co] = sum g: the shard's partial. */
+int orc_conv3d_s2_bwd_filter(const double* x, const int64_t* xg, const double* dy, const int64_t* yg, const double* y,
+                             const int64_t* ysg, double* dw, double* db, int act, double alpha) {
+  if (!s2_shapes(xg, yg)) return -1;
+  const int masked = (y != NULL && act != ACT_NONE);
+  if (masked && (!same_shard(ysg, yg) || ysg[G_C] != yg[G_C])) return -1;
+  const int64_t N = xg[G_N], Ci = xg[G_C], Co = yg[G_C], H = xg[G_H], W = xg[G_W];
+  const int64_t Do = yg[G_D], Ho = yg[G_H], Wo = yg[G_W];
+  if (Do > 0 && in_volume(xg, -1) && !stored(xg, -1)) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int64_t co = 0; co < Co; ++co)
+    for (int64_t cik = 0; cik < Ci * 27; ++cik) {
+      const int64_t ci = cik / 27;
+      const int kd = (int)(cik % 27) / 9, kh = (int)(cik % 9) / 3, kw = (int)(cik % 3);
+      double acc = 0.0;
+      for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < Do; ++p) {
+          const int64_t pp = 2 * p + kd - 1;
+          if (!in_volume(xg, pp)) continue;
+          for (int64_t h = 0; h < Ho; ++h) {
+            const int64_t hh = 2 * h + kh - 1;
+            if (hh < 0 || hh >= H) continue;
+            for (int64_t v = 0; v < Wo; ++v) {
+              const int64_t ww = 2 * v + kw - 1;
+              if (ww < 0 || ww >= W) continue;
+              double g = dy[at5(yg, n, co, p, h, v)];
+              if (masked && !(y[at5(ysg, n, co, p, h, v)] > 0.0)) g *= slope;
+              acc += g * x[at5(xg, n, ci, pp, hh, ww)];
+            }
+          }
+        }
+      dw[co * Ci * 27 + cik] = acc;
+    }
+  if (db) {
+    for (int64_t co = 0; co < Co; ++co) {
+      double acc = 0.0;
+      for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < Do; ++p)
+          for (int64_t h = 0; h < Ho; ++h)
+            for (int64_t v = 0; v < Wo; ++v) {
+              double g = dy[at5(yg, n, co, p, h, v)];
+              if (masked && !(y[at5(ysg, n, co, p, h, v)] > 0.0)) g *= slope;
+              acc += g;
+            }
+      db[co] = acc;
+    }
+  }
+  return 0;
+}
+
 /* ------------------------------------------------------------------ pooling */
 /* 2x2x2, stride 2, non-overlapping windows over the shard INTERIOR (Sec. III-A:
  * pooling is the other layer with a spatial dependency; with even d and even
