@@ -116,6 +116,32 @@ h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, const h3d_te
                                  float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
                                  void* stream);
 
+/* ---- 3x3x3 convolution with a stride of 2 (Table I: the fourth convolution of the CosmoFlow network) ----
+ * "Same" padding is read as one zero voxel on every side, as for the stride-1 layers, so an even extent is halved
+ * (an odd h or w is rounded up):  y[n,co,p] = act(bias[co] + sum_{ci,k} w[co,ci,k] * x~[n,ci,2p+k-1]).
+ * x: the input shard, d, d_offset and d_global even (else H3D_EUNSUPPORTED: an output voxel would belong to two
+ * shards); y: the output shard, n equal, d/2, ceil(h/2), ceil(w/2), d_offset/2, d_global/2.  Packed tensors only;
+ * weights, bias, dw, db, act as for the stride-1 calls.  Interiors are written; halo planes of the OUTPUT argument
+ * of each call are neither read nor written.  Which halo planes are READ differs by direction:
+ *   forward, backward-filter: output plane p reads input planes 2p-1 .. 2p+1, so x needs its LOWER halo plane
+ *     (when inside the volume), never the upper one;
+ *   backward-data: input plane d-1 receives a term from output plane d/2, so dy (and y, when act is not NONE)
+ *     need their UPPER halo plane, never the lower one.                                  H3D_EHALO otherwise.
+ * Workspace: h3d_conv3d_s2_workspace_bytes(handle, op, x, y) with x / y the input-side / output-side descriptors
+ * for every op; 256-byte aligned.  The call rewrites the problem as a stride-1 convolution over the eight parity
+ * sub-lattices of x and runs the stride-1 kernels; the workspace holds the rearranged tensors. */
+size_t h3d_conv3d_s2_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* y);
+h3d_status h3d_conv3d_s2_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* y,
+                             int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+/* g = dy * (y > 0 ? 1 : slope);  dx[n,ci,q] = sum over (co,k,p) with 2p+k-1 = q of w[co,ci,k] * g[n,co,p]. */
+h3d_status h3d_conv3d_s2_bwd_data(void* handle, const h3d_tensor* dy, const h3d_tensor* y, const void* w,
+                                  h3d_tensor* dx, int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+/* dw[co,ci,k] = sum_n sum_{p in the output shard} g[n,co,p] * x~[n,ci,2p+k-1], db[co] = sum g; overwritten;
+ * deterministic like h3d_conv3d_bwd_filter. */
+h3d_status h3d_conv3d_s2_bwd_filter(void* handle, const h3d_tensor* x, const h3d_tensor* dy, const h3d_tensor* y,
+                                    float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
+                                    void* stream);
+
 /* ---- activation backward as a separate pass (Sec. IV: leaky-ReLU after every conv; U-Net: ReLU) ----
  * g = (dz + dz2) * (z > 0 ? 1 : slope) on the shard INTERIOR; dz2 may be NULL (it merges the two
  * gradient branches of a skip connection).  z is the saved forward output.  Halo planes of g are
