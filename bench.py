@@ -69,6 +69,28 @@ def side_workload(args, seed):
         from paper_2007_12856_amd.nets import BatchNormLayer
         net = BatchNormLayer(4, 16, 128, 128, seed=seed)
         name = "local batch-normalisation passes on the first convolution's output: 4 x 16 x 128^3 bf16"
+    elif args.workload == "table1":
+        # the seven convolutions of Table I (fourth one with a stride of 2, no convolution biases, pooling until the
+        # volume is 2^3), dense head 2048-256-4, on whole samples of --width^3 (128 or 256)
+        from paper_2007_12856_amd.nets import CosmoFlowStack
+        dev = lambda a, dt=bf: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+        channels, strides, pools, flat_w = recipes.table1_layout(args.width)
+        P = recipes.cosmoflow_params(seed, args.width, channels, recipes.COSMO_FC, flat_w)
+        x, t = recipes.cosmoflow_batch(seed, args.batch, args.width)
+        net = CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), None) for w, _ in P["conv"]],
+                             [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused,
+                             strides=strides, pools=pools)
+        name = (f"network of Table I for {args.width}^3 inputs, N={args.batch}: conv 16-32-64-128(stride 2)-256-256-256, no conv biases, "
+                f"leaky-ReLU, avg-pool, dense 2048-256-4, MSE; fwd+bwd; {net.conv_flops() / args.batch / 1e9:.2f} conv GFlop per sample")
+    elif args.workload == "chain512":
+        # the spatially-partitioned front of Table I's 512^3 network on one interior shard of an 8-way depth partition
+        from paper_2007_12856_amd.nets import CosmoFlowShardChain
+        dev = lambda a, dt=bf: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+        x, conv, dout, faces = recipes.shard_chain_inputs(seed, 512, 64, 64, 512, n=args.batch)
+        net = CosmoFlowShardChain(h3d.Slab(dev(x), 1, 1, 64, 512), [(dev(w), None) for w, _ in conv], dev(dout),
+                                  {k: (dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
+        name = (f"conv1-pool1 .. conv3-pool3 of Table I's 512^3 network on one interior shard of an 8-way depth partition "
+                f"(N={args.batch} x 4x(64+2)x512x512 bf16), halo faces packed and unpacked per stage, fwd+bwd")
     elif args.workload == "late256":
         net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
         name = "late layer N=8, 256->256, 16^3 bf16"
@@ -151,7 +173,7 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="store the first stage's unpooled activation (separate conv, pool and "
                     "pool-backward calls) instead of the fused forward + sign mask")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "shard512", "unet", "late256", "split256", "bn"],
+    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
                          "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
     args = ap.parse_args()

@@ -10,36 +10,55 @@ from __future__ import annotations
 import torch
 
 from . import (ACT_LEAKY, ACT_NONE, POOL_AVG, Slab, Workspace, conv3d_bwd_data, conv3d_bwd_filter, conv3d_fwd,
-               conv3d_fwd_pool, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd)
+               conv3d_fwd_pool, conv3d_s2_bwd_data, conv3d_s2_bwd_filter, conv3d_s2_fwd, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd)
 
 
 class CosmoFlowStack:
-    def __init__(self, x: torch.Tensor, target: torch.Tensor, conv_params, fc_params, alpha: float = 0.01, fuse_pool: bool = False):
+    def __init__(self, x: torch.Tensor, target: torch.Tensor, conv_params, fc_params, alpha: float = 0.01, fuse_pool: bool = False,
+                 strides=None, pools=None):
         """x [N,C,D,H,W] device tensor; conv_params/fc_params: lists of (w, bias) device tensors
-        (w in x's dtype, bias fp32); target fp32 [N, nout]."""
+        (w in x's dtype, bias fp32 or None: the paper's variant drops the convolution biases, Sec. IV);
+        target fp32 [N, nout].  strides[i] in (1, 2): stride of convolution i (Table I: the fourth has 2);
+        pools[i]: whether a 2x2x2 average pooling follows it (Table I: the last layers of the small inputs
+        have none, their volume is already 2^3).  Defaults: stride 1, pooling everywhere."""
         self.alpha = alpha
         self.ws = Workspace()
         dt, dev = x.dtype, x.device
+        nconv = len(conv_params)
+        self.strides = list(strides) if strides is not None else [1] * nconv
+        self.pools = list(pools) if pools is not None else [True] * nconv
         # fuse_pool: stages whose convolution has a fused forward (first layer: Cin <= 4) never store the unpooled
         # activation: the forward writes the pooled tensor and a sign mask, the backward reads the mask
-        self.fused = [bool(fuse_pool) and dt == torch.bfloat16 and w.shape[1] <= 4 and w.shape[0] <= 32 for w, _ in conv_params]
+        self.fused = [bool(fuse_pool) and dt == torch.bfloat16 and w.shape[1] <= 4 and w.shape[0] <= 32 and self.strides[i] == 1
+                      and self.pools[i] for i, (w, _) in enumerate(conv_params)]
         self.x = Slab(x)
         self.target = target
         self.conv, self.fc = conv_params, fc_params
         n = x.shape[0]
-        self.z, self.p = [], []
+        self.z, self.p, self.mask, self.g, self.dp = [], [], [], [], []
         cur = self.x
-        self.mask = []
         for i, (w, _) in enumerate(conv_params):
-            fused = self.fused[i] and cur.d % 2 == 0 and cur.t.shape[3] % 2 == 0 and cur.t.shape[4] % 16 == 0
+            st = self.strides[i]
+            zd, zh, zw = cur.d // st, (cur.t.shape[3] + st - 1) // st, (cur.t.shape[4] + st - 1) // st
+            fused = self.fused[i] and zd % 2 == 0 and zh % 2 == 0 and zw % 16 == 0
             self.fused[i] = fused
-            z = None if fused else cur.like(w.shape[0])
-            self.mask.append(torch.empty((n * w.shape[0] * cur.d * cur.t.shape[3] * cur.t.shape[4] // 8,), dtype=torch.uint8, device=dev)
-                             if fused else None)
-            p = Slab(torch.empty((n, w.shape[0], cur.d // 2, cur.t.shape[3] // 2, cur.t.shape[4] // 2), dtype=dt, device=dev))
+            zshape = (n, w.shape[0], zd, zh, zw)
+            z = None if fused else Slab(torch.empty(zshape, dtype=dt, device=dev))
+            self.mask.append(torch.empty((n * w.shape[0] * zd * zh * zw // 8,), dtype=torch.uint8, device=dev) if fused else None)
+            # g: gradient at the convolution's output; after a pooling it is already multiplied by the activation
+            # derivative (pooling backward and activation backward are one call), else it is the raw dz
+            self.g.append(Slab(torch.empty(zshape, dtype=dt, device=dev)))
+            if self.pools[i]:
+                p = Slab(torch.empty((n, w.shape[0], zd // 2, zh // 2, zw // 2), dtype=dt, device=dev))
+                self.dp.append(Slab(torch.empty_like(p.t)))
+            else:
+                p = None
+                self.dp.append(None)
             self.z.append(z)
             self.p.append(p)
-            cur = p
+            cur = p if p is not None else z
+        self.out = [p if p is not None else z for p, z in zip(self.p, self.z)]            # what the next layer reads
+        self.dout = [dp if dp is not None else g for dp, g in zip(self.dp, self.g)]       # where its gradient arrives
         self.flat = cur.t.view(n, -1)
         self.y = [torch.empty((n, w.shape[0]), dtype=dt, device=dev) for w, _ in fc_params]
         self.loss = torch.empty((1,), dtype=torch.float32, device=dev)
@@ -47,12 +66,9 @@ class CosmoFlowStack:
         self.dy = [torch.empty_like(y) for y in self.y]
         self.dfc = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
                     for w, b in fc_params]
-        self.dp = [Slab(torch.empty_like(p.t)) for p in self.p]
-        self.g = [Slab(torch.empty((n, w.shape[0], 2 * p.d, 2 * p.t.shape[3], 2 * p.t.shape[4]), dtype=dt, device=dev))
-                  for (w, _), p in zip(conv_params, self.p)]     # g = dz * act'(z), pre-activation gradient
         self.dx = Slab(torch.empty_like(x))
-        self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev))
-                      for w, b in conv_params]
+        self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev),
+                       None if b is None else torch.empty(b.shape, dtype=torch.float32, device=dev)) for w, b in conv_params]
 
         self._build_ops()
 
@@ -78,9 +94,11 @@ class CosmoFlowStack:
                     cur, w, b, zshape, p, mask, ACT_LEAKY, al, ws), fl, (cur.t.numel() + p.t.numel() + w.numel()) * es + mask.numel())
             else:
                 io = (cur.t.numel() + z.t.numel() + w.numel()) * es
-                self._op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z: conv3d_fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl, io)
-                self._op(f"pool{i + 1}_fwd", lambda z=z, p=p: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
-            cur = p
+                fwd = conv3d_s2_fwd if self.strides[i] == 2 else conv3d_fwd
+                self._op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z, fwd=fwd: fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl, io)
+                if p is not None:
+                    self._op(f"pool{i + 1}_fwd", lambda z=z, p=p: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
+            cur = self.out[i]
         h = self.flat
         for i, (w, b) in enumerate(self.fc):
             y = self.y[i]
@@ -92,7 +110,7 @@ class CosmoFlowStack:
         self._op("mse", lambda: mse_fwd_bwd(self.y[last], self.target, self.loss, self.dy[last]))
         for i in range(last, -1, -1):
             xin = self.flat if i == 0 else self.y[i - 1]
-            dxin = self.dp[-1].t.view(xin.shape) if i == 0 else self.dy[i - 1]
+            dxin = self.dout[-1].t.view(xin.shape) if i == 0 else self.dy[i - 1]
             w = self.fc[i][0]
             act = ACT_NONE if i == last else ACT_LEAKY
             self._op(f"fc{i + 1}_bwd", lambda xin=xin, w=w, i=i, dxin=dxin, act=act: dense_bwd(
@@ -101,21 +119,26 @@ class CosmoFlowStack:
         for i in range(nconv - 1, -1, -1):
             w = self.conv[i][0]
             z, g, dp = self.z[i], self.g[i], self.dp[i]
-            xin = self.x if i == 0 else self.p[i - 1]
-            dxin = self.dx if i == 0 else self.dp[i - 1]
+            xin = self.x if i == 0 else self.out[i - 1]
+            dxin = self.dx if i == 0 else self.dout[i - 1]
             fl = 2 * 27 * w.shape[1] * g.t.numel()
-            # pooling backward and activation backward in one pass; BF and BD then run unmasked on g
+            zb, actb = None, ACT_NONE
             if self.fused[i]:
+                # pooling backward and activation backward in one pass; BF and BD then run unmasked on g
                 mask = self.mask[i]
                 self._op(f"pool{i + 1}_bwd_mask", lambda dp=dp, mask=mask, g=g: pool3d_bwd_mask(dp, mask, g, ACT_LEAKY, al), 0,
                          (dp.t.numel() + g.t.numel()) * es + mask.numel())
-            else:
+            elif dp is not None:
                 self._op(f"pool{i + 1}_bwd_act", lambda dp=dp, z=z, g=g: pool3d_bwd_act(dp, None, z, g, POOL_AVG, ACT_LEAKY, al), 0,
                          (dp.t.numel() + z.t.numel() + g.t.numel()) * es)
-            self._op(f"conv{i + 1}_bwd_filter", lambda xin=xin, g=g, i=i: conv3d_bwd_filter(
-                xin, g, None, self.dconv[i][0], self.dconv[i][1], ACT_NONE, 0.0, ws), fl,
+            else:
+                zb, actb = z, ACT_LEAKY          # no pooling: g is the raw dz, BF and BD apply the activation derivative from z
+            bf = conv3d_s2_bwd_filter if self.strides[i] == 2 else conv3d_bwd_filter
+            bd = conv3d_s2_bwd_data if self.strides[i] == 2 else conv3d_bwd_data
+            self._op(f"conv{i + 1}_bwd_filter", lambda xin=xin, g=g, i=i, bf=bf, zb=zb, actb=actb: bf(
+                xin, g, zb, self.dconv[i][0], self.dconv[i][1], actb, al, ws), fl,
                 (xin.t.numel() + g.t.numel()) * es + w.numel() * 4)
-            self._op(f"conv{i + 1}_bwd_data", lambda g=g, w=w, dxin=dxin: conv3d_bwd_data(g, None, w, dxin, ACT_NONE, 0.0, ws),
+            self._op(f"conv{i + 1}_bwd_data", lambda g=g, w=w, dxin=dxin, bd=bd, zb=zb, actb=actb: bd(g, zb, w, dxin, actb, al, ws),
                      fl, (g.t.numel() + dxin.t.numel() + w.numel()) * es)
 
     def forward(self):
@@ -225,6 +248,101 @@ class UNetLevel:
         exchange("g1", G["g1"], 1)
         op("c1_bwd_filter", lambda: conv3d_bwd_filter(x, G["g1"], None, *dP["c1"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
         op("c1_bwd_data", lambda: conv3d_bwd_data(G["g1"], None, P["c1"][0], G["dx"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
+
+    def forward(self):
+        for o in self.ops[:self.n_fwd_ops]:
+            o["fn"]()
+
+    def step(self):
+        for o in self.ops:
+            o["fn"]()
+
+    def conv_flops(self) -> int:
+        return sum(o["flops"] for o in self.ops)
+
+
+class CosmoFlowShardChain:
+    """The spatially-partitioned front of the Table I network on ONE depth shard (Sec. II-B, III-A): stages of
+    3x3x3 convolution + leaky-ReLU + 2x2x2 average pooling whose inputs carry one halo plane per side.  Per stage,
+    forward: halo_unpack of the two faces received from the depth neighbours, convolution (+ pooling; fused for the
+    first stage), halo_pack of the pooled tensor's two faces for the neighbours; backward: pooling + activation
+    backward into g, halo_pack / halo_unpack of g's faces, BF and BD.  The faces a neighbour would send are given
+    as buffers (None at the global boundary: zero fill); the exchange itself is not part of this list.  After the
+    last stage the paper redistributes the small tensor to sample parallelism; that stage's output has no halo."""
+
+    def __init__(self, x: Slab, conv_params, dout: torch.Tensor, faces: dict, alpha: float = 0.01, fuse_pool: bool = True):
+        from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
+        self.ws = Workspace()
+        ws, al = self.ws, alpha
+        dt, dev = x.t.dtype, x.t.device
+        es = x.t.element_size()
+        n, L = x.t.shape[0], len(conv_params)
+        self.conv = conv_params
+        a, self.z, self.mask, self.g, self.da = [x], [], [], [], [None]
+        for i, (w, _) in enumerate(conv_params):
+            cur = a[i]
+            H, W, co = cur.t.shape[3], cur.t.shape[4], w.shape[0]
+            fused = bool(fuse_pool) and dt == torch.bfloat16 and w.shape[1] <= 4 and co <= 32 and cur.d % 2 == 0 and H % 2 == 0 and W % 16 == 0
+            self.z.append(None if fused else Slab(torch.empty((n, co, cur.d, H, W), dtype=dt, device=dev), 0, 0, cur.d_offset, cur.d_global))
+            self.mask.append(torch.empty((n * co * cur.d * H * W // 8,), dtype=torch.uint8, device=dev) if fused else None)
+            self.g.append(Slab(torch.zeros((n, co, cur.d + 2, H, W), dtype=dt, device=dev), 1, 1, cur.d_offset, cur.d_global))
+            halo = 1 if i < L - 1 else 0
+            a.append(Slab(torch.zeros((n, co, cur.d // 2 + 2 * halo, H // 2, W // 2), dtype=dt, device=dev), halo, halo,
+                          cur.d_offset // 2, cur.d_global // 2))
+            self.da.append(Slab(dout, 0, 0, cur.d_offset // 2, cur.d_global // 2) if i == L - 1 else
+                           Slab(torch.empty((n, co, cur.d // 2, H // 2, W // 2), dtype=dt, device=dev), 0, 0, cur.d_offset // 2, cur.d_global // 2))
+        self.a = a
+        self.da[0] = Slab(torch.empty((n, x.t.shape[1], x.d, x.t.shape[3], x.t.shape[4]), dtype=dt, device=dev), 0, 0, x.d_offset, x.d_global)
+        self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev),
+                       None if b is None else torch.empty(b.shape, dtype=torch.float32, device=dev)) for w, b in conv_params]
+        send = lambda t: [torch.empty(halo_bytes(t, 1) // es, dtype=dt, device=dev) for _ in range(2)]
+        self.sent = {}
+        self.ops = []
+
+        def op(name, fn, flops=0, nbytes=0):
+            self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": int(nbytes)})
+
+        def unpack(name, t):
+            lo, hi = faces[name]
+            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, 1), halo_unpack(hi, t, FACE_D_HI, 1)), 0, 4 * halo_bytes(t, 1))
+
+        def pack(name, t):
+            bufs = self.sent[name] = send(t)
+            op(f"halo_pack_{name}", lambda: (halo_pack(t, FACE_D_LO, 1, bufs[0]), halo_pack(t, FACE_D_HI, 1, bufs[1])), 0, 4 * halo_bytes(t, 1))
+
+        for i, (w, b) in enumerate(conv_params):
+            cur, nxt, z, mask, g = a[i], a[i + 1], self.z[i], self.mask[i], self.g[i]
+            vox = n * cur.d * cur.t.shape[3] * cur.t.shape[4]
+            fl = 2 * 27 * w.shape[1] * w.shape[0] * vox
+            unpack(f"a{i}", cur)
+            if z is None:
+                zshape = (n, w.shape[0], cur.d, cur.t.shape[3], cur.t.shape[4])
+                op(f"conv{i + 1}_fwd_pool", lambda cur=cur, w=w, b=b, zshape=zshape, nxt=nxt, mask=mask: conv3d_fwd_pool(
+                    cur, w, b, zshape, nxt, mask, ACT_LEAKY, al, ws), fl, (cur.t.numel() + vox * w.shape[0] // 8) * es + mask.numel())
+            else:
+                op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z: conv3d_fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl,
+                   (cur.t.numel() + z.t.numel()) * es)
+                op(f"pool{i + 1}_fwd", lambda z=z, nxt=nxt: pool3d_fwd(z, nxt, POOL_AVG), 0, z.t.numel() * es * 9 // 8)
+            if i < L - 1:
+                pack(f"a{i + 1}", nxt)
+        self.n_fwd_ops = len(self.ops)
+        for i in range(L - 1, -1, -1):
+            w = conv_params[i][0]
+            cur, z, mask, g, dp = a[i], self.z[i], self.mask[i], self.g[i], self.da[i + 1]
+            vox = n * cur.d * cur.t.shape[3] * cur.t.shape[4]
+            fl = 2 * 27 * w.shape[1] * w.shape[0] * vox
+            if z is None:
+                op(f"pool{i + 1}_bwd_mask", lambda dp=dp, mask=mask, g=g: pool3d_bwd_mask(dp, mask, g, ACT_LEAKY, al), 0,
+                   (dp.t.numel() + vox * w.shape[0]) * es + mask.numel())
+            else:
+                op(f"pool{i + 1}_bwd_act", lambda dp=dp, z=z, g=g: pool3d_bwd_act(dp, None, z, g, POOL_AVG, ACT_LEAKY, al), 0,
+                   (dp.t.numel() + 2 * z.t.numel()) * es)
+            pack(f"g{i + 1}", g)
+            unpack(f"g{i + 1}", g)
+            op(f"conv{i + 1}_bwd_filter", lambda cur=cur, g=g, i=i: conv3d_bwd_filter(cur, g, None, self.dconv[i][0], self.dconv[i][1],
+                                                                                       ACT_NONE, 0.0, ws), fl, (cur.t.numel() + vox * w.shape[0]) * es)
+            op(f"conv{i + 1}_bwd_data", lambda g=g, w=w, i=i: conv3d_bwd_data(g, None, w, self.da[i], ACT_NONE, 0.0, ws), fl,
+               (g.t.numel() + self.da[i].t.numel()) * es)
 
     def forward(self):
         for o in self.ops[:self.n_fwd_ops]:

@@ -23,10 +23,28 @@ def conv_params(seed, stream, cin, cout, taps=27, transposed=False):
     return w, bias
 
 
-def cosmoflow_params(seed=BASE_SEED, width=128, channels=COSMO_CHANNELS, fc=COSMO_FC):
-    """{'conv': [(w,b)...], 'fc': [(w,b)...]} for the CosmoFlow-shaped stack on a width^3 input."""
+TABLE1_CHANNELS = (4, 16, 32, 64, 128, 256, 256, 256)
+TABLE1_STRIDES = (1, 1, 1, 2, 1, 1, 1)
+
+
+def table1_layout(width=128):
+    """Channels, strides and pooling flags of the seven convolutions of Table I for a width^3 input
+    (128, 256 or 512): every convolution is followed by a pooling until the volume is 2^3."""
+    pools, w = [], width
+    for st in TABLE1_STRIDES:
+        w //= st
+        pools.append(w > 2)
+        if w > 2:
+            w //= 2
+    return TABLE1_CHANNELS, TABLE1_STRIDES, tuple(pools), TABLE1_CHANNELS[-1] * w ** 3
+
+
+def cosmoflow_params(seed=BASE_SEED, width=128, channels=COSMO_CHANNELS, fc=COSMO_FC, flat_w=None):
+    """{'conv': [(w,b)...], 'fc': [(w,b)...]} for the CosmoFlow-shaped stack on a width^3 input.
+    flat_w: length of the flattened last activation (default: every stage halves the width once)."""
     conv = [conv_params(seed, 100 + 2 * i, channels[i], channels[i + 1]) for i in range(len(channels) - 1)]
-    flat_w = channels[-1] * (width >> (len(channels) - 1)) ** 3
+    if flat_w is None:
+        flat_w = channels[-1] * (width >> (len(channels) - 1)) ** 3
     dims = (flat_w, *fc)
     fcs = []
     for i in range(len(fc)):
@@ -68,3 +86,27 @@ def unet_level_inputs(seed=BASE_SEED, d_global=256, d=64, d_offset=64, hw=256):
             hi = None if hi is None else np.maximum(hi, 0.0)
         faces[name] = (lo, hi)
     return x, params, dout, faces
+
+
+def shard_chain_inputs(seed=BASE_SEED, d_global=512, d=64, d_offset=64, hw=512, channels=(4, 16, 32, 64), n=1):
+    """Inputs of the spatially-partitioned front of the Table I network on one depth shard: the input slab with a
+    1-plane halo cut from the seeded volume, the stages' filters (no biases, Sec. IV), the gradient arriving at the
+    last pooled tensor, and stand-in faces for what the two depth neighbours would send: 'a0' (the input's own halo
+    planes), 'a1'.. (pooled activations), 'g1'.. (activation gradients); None at a global boundary."""
+    x = slab("cosmo", seed, 400, (n, channels[0], d_global, hw, hw), d_offset - 1, d_offset + d + 1)
+    conv = [(conv_params(seed, 410 + 2 * i, channels[i], channels[i + 1])[0], None) for i in range(len(channels) - 1)]
+    L = len(conv)
+    has_lo, has_hi = d_offset > 0, d_offset + d < d_global
+    faces = {"a0": (x[:, :, :1].copy() if has_lo else None, x[:, :, -1:].copy() if has_hi else None)}
+    for i in range(1, L + 1):
+        s = hw >> (i - 1)
+        for k, (name, c, width, scale) in enumerate((("a", channels[i], s // 2, 0.5), ("g", channels[i], s, 0.125))):
+            if name == "a" and i == L:
+                continue
+            shape = (n, c, 1, width, width)
+            lo = scale * flat("normal", seed, 420 + 8 * i + 4 * k, shape) if has_lo else None
+            hi = scale * flat("normal", seed, 421 + 8 * i + 4 * k, shape) if has_hi else None
+            faces[f"{name}{i}"] = (lo, hi)
+    dl, sl = d >> L, hw >> L
+    dout = slab("normal", seed, 490, (n, channels[-1], d_global >> L, sl, sl), d_offset >> L, (d_offset >> L) + dl)
+    return x, conv, dout, faces

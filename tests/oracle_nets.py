@@ -6,7 +6,7 @@ import numpy as np
 import oracle as orc
 
 
-def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, q=None):
+def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, q=None, strides=None, pools=None):
     """Forward + backward of the CosmoFlow-shaped stack.  `q` rounds every STORED activation and
     activation gradient to the storage type (bf16 in / fp32 accumulate / bf16 out is the arithmetic
     contract of each layer, so a stack stores rounded tensors between layers); all sums stay fp64.  `count`: number of entries the MSE mean runs
@@ -15,13 +15,19 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         q = lambda a: a
     qs = lambda s: orc.Slab(q(s.a), s.halo_lo, s.halo_hi, s.d_offset, s.d_global)
     xs = orc.Slab(x)
-    cur, zs, ps = xs, [], []
-    for w, b in conv_params:
-        z = qs(orc.conv3d_fwd(cur, w, b, act=orc.ACT_LEAKY, alpha=alpha))
-        p = qs(orc.pool3d_fwd(z, orc.POOL_AVG))
+    strides = strides or [1] * len(conv_params)
+    pools = pools or [True] * len(conv_params)
+    cur, zs, ps, outs = xs, [], [], []
+    for i, (w, b) in enumerate(conv_params):
+        if strides[i] == 2:
+            z = qs(orc.conv3d_s2_fwd(cur, w, b, orc.ACT_LEAKY, alpha))
+        else:
+            z = qs(orc.conv3d_fwd(cur, w, b, act=orc.ACT_LEAKY, alpha=alpha))
+        p = qs(orc.pool3d_fwd(z, orc.POOL_AVG)) if pools[i] else None
         zs.append(z)
         ps.append(p)
-        cur = p
+        cur = p if p is not None else z
+        outs.append(cur)
     n = x.shape[0]
     h = cur.a.reshape(n, -1)
     hs, ys = [h], []
@@ -40,16 +46,24 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         g, dw, db = orc.dense_bwd(hs[i], fc_params[i][0], ys[i], g, orc.ACT_NONE if i == last else orc.ACT_LEAKY, alpha)
         dfc[i] = (dw, db)
         g = q(g)
-    dp = orc.Slab(g.reshape(ps[-1].a.shape))
+    dp = orc.Slab(g.reshape(outs[-1].a.shape))
     dconv = [None] * len(conv_params)
     gs = [None] * len(conv_params)
     for i in range(len(conv_params) - 1, -1, -1):
-        # pooling backward and activation backward form one stored tensor g (rounded once)
-        g = qs(orc.act_bwd(orc.pool3d_bwd(dp, None, orc.POOL_AVG), None, zs[i], orc.ACT_LEAKY, alpha))
+        # pooling backward and activation backward form one stored tensor g (rounded once); without a pooling the
+        # stored tensor is dz and the activation derivative is applied inside the two backward convolutions
+        dz = orc.pool3d_bwd(dp, None, orc.POOL_AVG) if pools[i] else dp
+        g = orc.act_bwd(dz, None, zs[i], orc.ACT_LEAKY, alpha)
+        if pools[i]:
+            g = qs(g)
         gs[i] = g
-        xin = xs if i == 0 else ps[i - 1]
-        dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
-        dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
+        xin = xs if i == 0 else outs[i - 1]
+        if strides[i] == 2:
+            dconv[i] = orc.conv3d_s2_bwd_filter(xin, g, None)
+            dp = qs(orc.conv3d_s2_bwd_data(g, None, conv_params[i][0], xin))
+        else:
+            dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
+            dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
     return {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "dfc": dfc, "dconv": dconv, "g": gs, "dx": dp}
 
 
@@ -102,3 +116,37 @@ def unet_level_oracle(x, halo, d_offset, d_global, P, dout, faces, q=None):
     dP["c1"] = orc.conv3d_bwd_filter(xs, G["g1"], None)
     G["dx"] = qs(orc.conv3d_bwd_data(G["g1"], None, P["c1"][0]))
     return T, G, dP
+
+
+def shard_chain_oracle(x, d_offset, d_global, conv_params, dout, faces, alpha=0.01, q=None):
+    """The chain of paper_2007_12856_amd.nets.CosmoFlowShardChain with the oracle.  x: [n,c,d+2,H,W] float64."""
+    if q is None:
+        q = lambda a: a
+    qs = lambda s: orc.Slab(q(s.a), s.halo_lo, s.halo_hi, s.d_offset, s.d_global)
+
+    def with_halo(s, name):
+        n, c, _, h, w = s.a.shape
+        t = orc.Slab(np.zeros((n, c, s.d + 2, h, w)), 1, 1, s.d_offset, s.d_global)
+        t.interior[...] = s.interior
+        lo, hi = faces[name]
+        orc.halo_unpack(lo, t, orc.FACE_D_LO, 1)
+        orc.halo_unpack(hi, t, orc.FACE_D_HI, 1)
+        return t
+
+    L = len(conv_params)
+    a = [with_halo(orc.Slab(x, 1, 1, d_offset, d_global), "a0")]
+    zs = []
+    for i, (w, b) in enumerate(conv_params):
+        z = qs(orc.conv3d_fwd(a[i], w, b, act=orc.ACT_LEAKY, alpha=alpha))
+        p = qs(orc.pool3d_fwd(z, orc.POOL_AVG))
+        zs.append(z)
+        a.append(with_halo(p, f"a{i + 1}") if i < L - 1 else p)
+    dp = orc.Slab(dout, 0, 0, a[L].d_offset, a[L].d_global)
+    dconv, gs, da = [None] * L, [None] * L, [None] * L
+    for i in range(L - 1, -1, -1):
+        g = with_halo(qs(orc.act_bwd(orc.pool3d_bwd(dp, None, orc.POOL_AVG), None, zs[i], orc.ACT_LEAKY, alpha)), f"g{i + 1}")
+        gs[i] = g
+        dconv[i] = orc.conv3d_bwd_filter(a[i], g, None)
+        dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
+        da[i] = dp
+    return {"a": a, "z": zs, "g": gs, "dconv": dconv, "da": da}
