@@ -211,7 +211,7 @@ __global__ void __launch_bounds__(256) dense_fwd_kernel(const T* __restrict__ x,
   const bool vec = (a.k % V == 0) && ((uintptr_t)w % 16 == 0) && ((uintptr_t)x % 16 == 0);
   if (vec) {
     struct alignas(16) Pk { T v[V]; };
-    constexpr int UN = 4;   // weight loads in flight per lane
+    constexpr int UN = sizeof(T) == 2 ? 8 : 4;   // weight loads in flight per lane
     for (int k0 = lane * V; k0 < a.k; k0 += 64 * V * UN) {
       Pk wv[UN];
 #pragma unroll
@@ -262,6 +262,7 @@ __global__ void __launch_bounds__(256) dense_fwd_kernel(const T* __restrict__ x,
 // Forward for inputs that fit the LDS (m * k elements <= 128 KB, k a multiple of 16 / sizeof(T)): x is staged once
 // per (persistent) workgroup, every weight row is then streamed from HBM exactly once by one wavefront and
 // meets x in LDS, so the L2 sees the weights only.  Eight wavefronts per workgroup, rows handed out round-robin.
+typedef __bf16 dn_bf16x2 __attribute__((ext_vector_type(2)));
 template <typename T>
 __global__ void __launch_bounds__(512) dense_fwd_lds_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                             const float* __restrict__ bias, T* __restrict__ y, DenseArgs a) {
@@ -277,7 +278,7 @@ __global__ void __launch_bounds__(512) dense_fwd_lds_kernel(const T* __restrict_
 #pragma unroll
     for (int i = 0; i < DM; ++i) acc[i] = 0.f;
     const uint4* wr = reinterpret_cast<const uint4*>(w + (int64_t)j * a.k);
-    constexpr int UN = 4;   // weight loads in flight per lane
+    constexpr int UN = sizeof(T) == 2 ? 8 : 4;   // weight loads in flight per lane
     for (int u0 = lane; u0 < ku; u0 += 64 * UN) {
       uint4 wv[UN];
 #pragma unroll
@@ -291,9 +292,18 @@ __global__ void __launch_bounds__(512) dense_fwd_lds_kernel(const T* __restrict_
 #pragma unroll
           for (int i = 0; i < DM; ++i) {
             if (i < a.m) {
-              const Pk xp = __builtin_bit_cast(Pk, x_lds[i * ku + uu]);
+              if constexpr (sizeof(T) == 2) {
+                // bf16: one v_dot2 per pair of weights, no conversions
+                const uint4 xq = x_lds[i * ku + uu];
+                acc[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dn_bf16x2, wv[u].x), __builtin_bit_cast(dn_bf16x2, xq.x), acc[i], false);
+                acc[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dn_bf16x2, wv[u].y), __builtin_bit_cast(dn_bf16x2, xq.y), acc[i], false);
+                acc[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dn_bf16x2, wv[u].z), __builtin_bit_cast(dn_bf16x2, xq.z), acc[i], false);
+                acc[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dn_bf16x2, wv[u].w), __builtin_bit_cast(dn_bf16x2, xq.w), acc[i], false);
+              } else {
+                const Pk xp = __builtin_bit_cast(Pk, x_lds[i * ku + uu]);
 #pragma unroll
-              for (int e = 0; e < V; ++e) acc[i] = fmaf(ld(&wp.v[e]), ld(&xp.v[e]), acc[i]);
+                for (int e = 0; e < V; ++e) acc[i] = fmaf(ld(&wp.v[e]), ld(&xp.v[e]), acc[i]);
+              }
             }
           }
         }
