@@ -172,6 +172,8 @@ def main():
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
     ap.add_argument("--unfused", action="store_true", help="store the first stage's unpooled activation (separate conv, pool and "
                     "pool-backward calls) instead of the fused forward + sign mask")
+    ap.add_argument("--no-overlap", action="store_true", help="keep every call of the step on one stream (default: the backward-filter "
+                    "calls of stages 2.. run on a second stream beside the backward-data chain)")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
@@ -261,6 +263,11 @@ def main():
                           "algorithmic_bytes": op["bytes"], "algorithmic_flops": op["flops"]}))
         return
 
+    # the timed steps put the backward-filter calls of stages 2.. on a second stream (joined at the end of every step);
+    # the per-call pass above ran everything on one stream so that every call was timed alone
+    net.overlap = not args.no_overlap
+    net.step()
+    torch.cuda.synchronize()
     # timed region: exactly K steps; one HIP-event pair per step around the dominant call
     # (events are recorded on the stream the kernels are launched on)
     dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -304,6 +311,7 @@ def main():
         "voxels_per_s": voxels / (ms_per_step * 1e-3),
         "conv_gflop_per_step": flops / 1e9,
         "pct_of_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+        "streams": 1 if args.no_overlap else 2,
         "roofline": roof,
         "per_call": per_call,
     }

@@ -75,6 +75,19 @@ def test_cosmoflow_stack_miniature_with_fused_first_stage():
         assert rel_l2(from_dev(net.dconv[i][0]), ref["dconv"][i][0]) <= 2 * tol, f"dw{i}"
         assert rel_l2(from_dev(net.dconv[i][1]), ref["dconv"][i][1]) <= 2 * tol, f"db{i}"
     assert rel_l2(from_dev(net.dx.t), ref["dx"].a) <= 2 * tol
+    # the same backward with the late backward-filter calls on a second stream: identical bits, several times over
+    serial = [(dw.clone(), db.clone()) for dw, db in net.dconv]
+    dx_serial = net.dx.t.clone()
+    net.overlap = True
+    for _ in range(3):
+        for dw, db in net.dconv:
+            dw.fill_(7.0)
+            db.fill_(7.0)
+        net.backward_after_loss()
+        torch.cuda.synchronize()
+        for (dw, db), (dw0, db0) in zip(net.dconv, serial):
+            assert torch.equal(dw, dw0) and torch.equal(db, db0)
+        assert torch.equal(net.dx.t, dx_serial)
 
 
 @pytest.mark.parametrize("dtype,tol", [("f32", 1e-5), ("bf16", 2e-2)])
