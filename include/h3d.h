@@ -244,7 +244,9 @@ h3d_status h3d_split_c(void* handle, const h3d_tensor* in, h3d_tensor* a, h3d_te
  * m <= 8 rows per call (the per-GPU sample count after the spatial layers), else H3D_EUNSUPPORTED. */
 h3d_status h3d_dense_fwd(void* handle, const void* x, const void* w, const float* bias, void* y, int dtype, int m,
                          int n, int k, int act, float alpha, void* stream);
-/* dy [m][n], y saved output; dx [m][k] (dtype) or NULL, dw fp32 [n][k], db fp32 [n] or NULL; overwritten. */
+/* dy [m][n], y saved output; dx [m][k] (dtype) or NULL, dw fp32 [n][k] or NULL, db fp32 [n] or NULL (NULL when dw
+ * is NULL); overwritten.  The two halves are independent kernels: a caller may ask for dx alone and for dw / db
+ * alone in two calls (on two streams). */
 h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, const void* y, const void* dy, void* dx,
                          float* dw, float* db, int dtype, int m, int n, int k, int act, float alpha, void* stream);
 /* loss[0] (fp32, device) = mean over all `count` entries of (pred-target)^2; dpred = 2 (pred-target)/count

@@ -720,7 +720,9 @@ extern "C" h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, 
   if (!handle) return H3D_EINVAL;
   H3D_TRY(dense_check(handle, dtype, m, n, k, act));
   if (n == 0 || k == 0) return H3D_OK;
-  if (!x || !w || !dy || !dw || (act != H3D_ACT_NONE && !y)) return fail(handle, H3D_EINVAL, "dense_bwd: NULL pointer");
+  if (!x || !w || !dy || (act != H3D_ACT_NONE && !y)) return fail(handle, H3D_EINVAL, "dense_bwd: NULL pointer");
+  if (!dw && db) return fail(handle, H3D_EINVAL, "dense_bwd: db is computed together with dw");
+  if (!dw && !dx) return H3D_OK;
   DenseArgs a{m, n, k, act_slope(act, alpha), act};
   hipStream_t s = (hipStream_t)stream;
   dim3 gdx((unsigned)cdiv(k, 128)), gdw((unsigned)std::min<int64_t>(cdiv(k, 1024), 64), (unsigned)cdiv(n, DW_ROWS));
@@ -732,11 +734,11 @@ extern "C" h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, 
   if (dtype == H3D_F32) {
     if (dx && dx_vec) hipLaunchKernelGGL((dense_bwd_dx_vec_kernel<float>), dim3((unsigned)cdiv(k, 32)), dim3(1024), dx_lds, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);
     else if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<float>), gdx, dim3(1024), 0, s, (const float*)w, (const float*)y, (const float*)dy, (float*)dx, a);
-    hipLaunchKernelGGL((dense_bwd_dw_kernel<float>), gdw, dim3(256), 0, s, (const float*)x, (const float*)y, (const float*)dy, dw, db, a);
+    if (dw) hipLaunchKernelGGL((dense_bwd_dw_kernel<float>), gdw, dim3(256), 0, s, (const float*)x, (const float*)y, (const float*)dy, dw, db, a);
   } else {
     if (dx && dx_vec) hipLaunchKernelGGL((dense_bwd_dx_vec_kernel<bf16_t>), dim3((unsigned)cdiv(k, 64)), dim3(1024), dx_lds, s, (const bf16_t*)w, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dx, a);
     else if (dx) hipLaunchKernelGGL((dense_bwd_dx_kernel<bf16_t>), gdx, dim3(1024), 0, s, (const bf16_t*)w, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dx, a);
-    hipLaunchKernelGGL((dense_bwd_dw_kernel<bf16_t>), gdw, dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)y, (const bf16_t*)dy, dw, db, a);
+    if (dw) hipLaunchKernelGGL((dense_bwd_dw_kernel<bf16_t>), gdw, dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)y, (const bf16_t*)dy, dw, db, a);
   }
   return launch_status(handle, "dense_bwd");
 }

@@ -124,8 +124,10 @@ class CosmoFlowStack:
             dxin = self.dout[-1].t.view(xin.shape) if i == 0 else self.dy[i - 1]
             w = self.fc[i][0]
             act = ACT_NONE if i == last else ACT_LEAKY
-            self._op(f"fc{i + 1}_bwd", lambda xin=xin, w=w, i=i, dxin=dxin, act=act: dense_bwd(
-                xin, w, self.y[i], self.dy[i], dxin, self.dfc[i][0], self.dfc[i][1], act, al),
+            # two independent halves: dx on the current stream (the chain continues with it), dw / db beside it
+            self._op(f"fc{i + 1}_bwd", lambda xin=xin, w=w, i=i, dxin=dxin, act=act: (
+                dense_bwd(xin, w, self.y[i], self.dy[i], dxin, None, None, act, al),
+                self._on_side(lambda _ws: dense_bwd(xin, w, self.y[i], self.dy[i], None, self.dfc[i][0], self.dfc[i][1], act, al))),
                 4 * xin.shape[0] * w.numel(), w.numel() * es + w.numel() * 4)
         for i in range(nconv - 1, -1, -1):
             w = self.conv[i][0]

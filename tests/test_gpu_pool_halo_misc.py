@@ -222,6 +222,12 @@ def test_dense_and_mse(m, n, k, act, dtype):
     h3d.dense_bwd(to_dev(x, dtype), to_dev(w, dtype), to_dev(yq, dtype), to_dev(dy, dtype), dx, dw, db, act, 0.01)
     assert rel_l2(from_dev(dx), dxo) <= TOL[dtype]
     assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+    # the two halves asked for separately (a caller may put them on two streams): same bits
+    dx2, dw2, db2 = torch.full_like(dx, 3.0), torch.full_like(dw, 3.0), torch.full_like(db, 3.0)
+    args = (to_dev(x, dtype), to_dev(w, dtype), to_dev(yq, dtype), to_dev(dy, dtype))
+    h3d.dense_bwd(*args, dx2, None, None, act, 0.01)
+    h3d.dense_bwd(*args, None, dw2, db2, act, 0.01)
+    assert torch.equal(dx, dx2) and torch.equal(dw, dw2) and torch.equal(db, db2)
     # loss
     t = synth.round_f32(synth.flat("uniform", SEED, 14, (m, n))).astype(np.float64)
     Lo, go = orc.mse_fwd_bwd(yq, t)
