@@ -174,6 +174,8 @@ def main():
                     "pool-backward calls) instead of the fused forward + sign mask")
     ap.add_argument("--no-overlap", action="store_true", help="keep every call of the step on one stream (default: the backward-filter "
                     "calls of stages 2.. run on a second stream beside the backward-data chain)")
+    ap.add_argument("--calibrate", action="store_true", help="print what this device sustains under the simplest load: a register-only "
+                    "bf16 MFMA loop (both tile shapes), a streaming read of 1 GiB and of 64 MiB, and a plain copy")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
@@ -193,6 +195,42 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     h3d.lib()   # fail loudly if the HIP library is not built
+    if args.calibrate:
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+
+        def timed(fn, reps):
+            fn(0)
+            fn(1)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for r in range(reps):
+                fn(r)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        scratch = torch.ones(h3d.probe_mfma_scratch_bytes() // 4, dtype=torch.float32, device="cuda")
+        res = {"metric": "calibration", "device": torch.cuda.get_device_name(0)}
+        for shape, nm in ((0, "mfma_16x16x32_bf16_tflops"), (1, "mfma_32x32x16_bf16_tflops")):
+            fl = []
+            ms = timed(lambda r: fl.append(h3d.probe_mfma_bf16(shape, 4096, scratch)), 5)
+            res[nm] = round(fl[0] / ms / 1e9, 1)
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        big = [torch.ones(1 << 28, dtype=torch.float32, device="cuda") for _ in range(3)]      # 3 x 1 GiB, rotated
+        ms = timed(lambda r: h3d.probe_read(big[r % 3], sink), 9)
+        res["read_1GiB_gbs"] = round((1 << 30) / ms / 1e6, 1)
+        small = [b[i * (1 << 24):(i + 1) * (1 << 24)] for b in big for i in range(16)]             # 48 x 64 MiB, rotated
+        ms = timed(lambda r: h3d.probe_read(small[(7 * r) % 48], sink), 48)
+        res["read_64MiB_cold_gbs"] = round((1 << 26) / ms / 1e6, 1)
+        res["read_64MiB_cold_us"] = round(ms * 1e3, 2)
+        del big, small
+        t = h3d.Slab(torch.randn((1, 16, 64, 512, 512), device="cuda").to(torch.bfloat16))
+        buf = torch.empty_like(t.t)
+        ms = timed(lambda r: h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf), 10)
+        res["copy_gbs"] = round(2 * t.t.numel() * 2 / ms / 1e6, 1)
+        res["published_peaks"] = {"mfma_bf16_tflops": PEAK_MFMA_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}
+        print(json.dumps(res))
+        return
     if args.copy_ref:
         t = h3d.Slab(torch.randn((1, 16, 64, 512, 512), device="cuda").to(torch.bfloat16))
         buf = torch.empty_like(t.t)

@@ -278,6 +278,20 @@ h3d_status h3d_bn_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, c
                       const float* gamma, const float* sum_dy, const float* sum_dy_xhat, int64_t count, h3d_tensor* dx,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* ---- calibration probes (for the benchmark, not part of the method: Sec. V of the paper compares measured rates with
+ * the machine's peak; these give what the device at hand sustains under the simplest load, to read a kernel's
+ * fraction of the published peak against) ----
+ * h3d_probe_mfma_bf16: a register-only loop of `iters` x 4 (shape 0: 16x16x32) or `iters` x 2 (shape 1: 32x32x16)
+ * independent bf16 MFMAs per wavefront on 2048 x 4 wavefronts; *flops (HOST) receives the flop count of the launch,
+ * the caller times it.  scratch: DEVICE, h3d_probe_mfma_scratch_bytes() bytes, 16-byte aligned, contents arbitrary
+ * (finite values avoid slow paths), overwritten.
+ * h3d_probe_read: reads `bytes` (whole 16-byte units) of buf (DEVICE, 16-byte aligned) once, writes nothing
+ * (sink: DEVICE, 4 bytes, practically never written). */
+size_t h3d_probe_mfma_scratch_bytes(void);
+h3d_status h3d_probe_mfma_bf16(void* handle, int shape, int iters, void* scratch, size_t scratch_bytes, double* flops,
+                               void* stream);
+h3d_status h3d_probe_read(void* handle, const void* buf, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif
