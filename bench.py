@@ -91,6 +91,27 @@ def side_workload(args, seed):
                                   {k: (dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
         name = (f"conv1-pool1 .. conv3-pool3 of Table I's 512^3 network on one interior shard of an 8-way depth partition "
                 f"(N={args.batch} x 4x(64+2)x512x512 bf16), halo faces packed and unpacked per stage, fwd+bwd")
+    elif args.workload == "xent":
+        # segmentation loss on the output shard of the U-Net shape: 3 classes, 64 x 256 x 256 voxels of a 256^3 volume
+        class _Xent:
+            def __init__(self):
+                g = torch.Generator(device="cuda")
+                g.manual_seed(seed)
+                z = h3d.Slab((3.0 * torch.randn((1, 3, 64, 256, 256), generator=g, device="cuda")).to(bf), 0, 0, 64, 256)
+                lab = torch.randint(0, 3, (1, 64, 256, 256), generator=g, device="cuda", dtype=torch.uint8)
+                dz, loss, ws = h3d.Slab(torch.empty_like(z.t), 0, 0, 64, 256), torch.zeros(1, device="cuda"), h3d.Workspace()
+                nb = 2 * z.t.numel() * 2 + lab.numel()
+                self.keep = (z, lab, dz, loss)
+                self.ops = [{"name": "softmax_xent_fwd_bwd", "fn": lambda: h3d.softmax_xent_fwd_bwd(z, lab, 256 ** 3, loss, dz, ws),
+                             "flops": 0, "bytes": nb}]
+
+            def step(self):
+                self.ops[0]["fn"]()
+
+            def conv_flops(self):
+                return 0
+        net = _Xent()
+        name = "softmax cross-entropy, forward + gradient, 3 classes on a 64x256x256 shard of a 256^3 volume, bf16"
     elif args.workload == "late256":
         net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
         name = "late layer N=8, 256->256, 16^3 bf16"
@@ -177,7 +198,7 @@ def main():
     ap.add_argument("--calibrate", action="store_true", help="print what this device sustains under the simplest load: a register-only "
                     "bf16 MFMA loop (both tile shapes), a streaming read of 1 GiB and of 64 MiB, and a plain copy")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "shard512", "unet", "late256", "split256", "bn"],
+    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "xent", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
                          "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
     args = ap.parse_args()

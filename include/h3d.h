@@ -254,6 +254,19 @@ h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, const void*
 h3d_status h3d_mse_fwd_bwd(void* handle, const void* pred, const float* target, float* loss, void* dpred, int dtype,
                            int count, void* stream);
 
+/* ---- per-voxel softmax cross-entropy of a segmentation output (the 3D U-Net's loss; Sec. III-A: the cross-entropy loss
+ * is among the components that needed a version for large 3-D data, and the ground truth is partitioned like the
+ * activations) ----
+ * logits / dlogits: the same shard, c = classes (1..255), packed, either dtype; interiors only, halos untouched.
+ * labels: DEVICE uint8 [n][d][h][w] of the shard's interior; a value >= c marks a voxel that has no class: it adds
+ * nothing to the loss and its gradient is zero.  count: voxels x samples over ALL shards (the mean's denominator).
+ * loss[0] (DEVICE fp32) = -(1/count) * sum over this shard's voxels of log softmax(logits)[label]: the shard's part of
+ * the mean (the shards' parts add up; that sum is the caller's allreduce).  dlogits = (softmax - onehot) / count.
+ * One streaming pass; fixed-order summation (same bits every run).  Workspace: h3d_softmax_xent_workspace_bytes. */
+size_t h3d_softmax_xent_workspace_bytes(void* handle, const h3d_tensor* logits);
+h3d_status h3d_softmax_xent_fwd_bwd(void* handle, const h3d_tensor* logits, const uint8_t* labels, int64_t count, float* loss,
+                                    h3d_tensor* dlogits, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- batch normalisation, the parts local to a shard (Sec. II-B: partial statistics per partition are aggregated
  * with an allreduce; Sec. III-C: a batch-normalisation layer costs this computation plus the allreduce of the
  * per-channel sum and squared sum).  The allreduce itself is the caller's.  All per-channel arrays are fp32

@@ -57,6 +57,8 @@ _SIGNATURES = {
     "h3d_conv3d_s2_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_s2_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_s2_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_softmax_xent_workspace_bytes": (ctypes.c_size_t, [_P, _T]),
+    "h3d_softmax_xent_fwd_bwd": (ctypes.c_int, [_P, _T, _P, ctypes.c_int64, _P, _T, _P, ctypes.c_size_t, _P]),
     "h3d_probe_mfma_scratch_bytes": (ctypes.c_size_t, []),
     "h3d_probe_mfma_bf16": (ctypes.c_int, [_P, ctypes.c_int, ctypes.c_int, _P, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), _P]),
     "h3d_probe_read": (ctypes.c_int, [_P, _P, ctypes.c_size_t, _P, _P]),
@@ -473,6 +475,17 @@ def h3d_bn_bwd(dy: Slab, x: Slab, mean, invstd, gamma, sum_dy, sum_dy_xhat, coun
     return dx
 
 
+def h3d_softmax_xent_workspace_bytes(logits: Slab) -> int:
+    return int(lib().h3d_softmax_xent_workspace_bytes(handle(), ctypes.byref(logits.desc())))
+
+
+def h3d_softmax_xent_fwd_bwd(logits: Slab, labels, count: int, loss, dlogits: Slab, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_softmax_xent_workspace_bytes(logits))
+    _check(lib().h3d_softmax_xent_fwd_bwd(handle(), ctypes.byref(logits.desc()), _ptr(labels), int(count), _ptr(loss),
+                                          ctypes.byref(dlogits.desc()), p, n, _stream()))
+    return loss, dlogits
+
+
 def h3d_probe_mfma_scratch_bytes() -> int:
     return int(lib().h3d_probe_mfma_scratch_bytes())
 
@@ -503,4 +516,5 @@ conv3d_fwd_pool, act_mask, act_mask_bytes, pool3d_bwd_mask = h3d_conv3d_fwd_pool
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c
 dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd
+softmax_xent_fwd_bwd = h3d_softmax_xent_fwd_bwd
 probe_mfma_bf16, probe_read, probe_mfma_scratch_bytes = h3d_probe_mfma_bf16, h3d_probe_read, h3d_probe_mfma_scratch_bytes

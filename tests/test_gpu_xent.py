@@ -1,0 +1,88 @@
+"""GPU parity of the per-voxel softmax cross-entropy (the segmentation loss of the U-Net shape) against the CPU oracle:
+loss value and gradient, vector and scalar paths, both dtypes, depth shards with halos, voxels without a class."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import synth
+from helpers import TOL, from_dev, quantize, rel_l2, to_dev
+
+pytestmark = pytest.mark.gpu
+SEED = synth.BASE_SEED
+
+
+def labels_for(shape, c, stream):
+    u = synth.flat("uniform", SEED, stream, shape, 0.0, 1.0)
+    return np.minimum((u * c).astype(np.int64), c - 1)
+
+
+# (n, classes, d, h, w)
+CASES = [(1, 3, 8, 16, 64), (2, 3, 4, 6, 40), (1, 2, 3, 5, 7), (1, 5, 2, 4, 16), (2, 8, 2, 3, 24), (1, 11, 2, 3, 8), (1, 1, 2, 2, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CASES)
+def test_softmax_xent_matches_the_oracle(case, dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    n, c, d, h, w = case
+    z = quantize(3.0 * synth.flat("normal", SEED, 700, (n, c, d, h, w)), dtype)
+    lab = labels_for((n, d, h, w), c, 701)
+    lo, go = orc.softmax_xent_fwd_bwd(orc.Slab(z), lab)
+    zg = h3d.Slab(to_dev(z, dtype))
+    gg = h3d.Slab(torch.full_like(zg.t, 5.0))
+    loss = torch.full((1,), -1.0, device="cuda")
+    labd = torch.from_numpy(lab.astype(np.uint8)).cuda()
+    h3d.softmax_xent_fwd_bwd(zg, labd, lab.size, loss, gg)
+    assert abs(loss.item() - lo) <= 1e-5 * max(abs(lo), 1e-3)
+    assert rel_l2(from_dev(gg.t), go) <= TOL[dtype]
+    loss2, g2 = torch.empty_like(loss), h3d.Slab(torch.empty_like(gg.t))
+    h3d.softmax_xent_fwd_bwd(zg, labd, lab.size, loss2, g2)
+    assert torch.equal(loss, loss2) and torch.equal(gg.t, g2.t)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_softmax_xent_on_shards_with_halos_and_unlabelled_voxels(dtype):
+    import torch
+    import paper_2007_12856_amd as h3d
+    n, c, dg, h, w = 2, 3, 8, 4, 16
+    zfull = quantize(2.0 * synth.flat("normal", SEED, 702, (n, c, dg, h, w)), dtype)
+    lab = labels_for((n, dg, h, w), c, 703)
+    lab[0, 1, 2, 3:9] = 255
+    lab[1, 6, 0, :] = 200
+    count = lab.size
+    full_loss, full_g = orc.softmax_xent_fwd_bwd(orc.Slab(zfull), lab, count)
+    total = 0.0
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    for s in range(4):
+        a = np.full((n, c, 4, h, w), 1e4)                       # halo planes hold a value that would ruin a sum
+        a[:, :, 1:3] = zfull[:, :, 2 * s:2 * s + 2]
+        zg = h3d.Slab(to_dev(a, dtype), 1, 1, 2 * s, dg)
+        gg = h3d.Slab(torch.full((n, c, 2 + 2, h, w), 9.0, dtype=td, device="cuda"), 2, 0, 2 * s, dg)
+        loss = torch.zeros((1,), device="cuda")
+        labd = torch.from_numpy(np.ascontiguousarray(lab[:, 2 * s:2 * s + 2]).astype(np.uint8)).cuda()
+        h3d.softmax_xent_fwd_bwd(zg, labd, count, loss, gg)
+        total += loss.item()
+        got = from_dev(gg.t)
+        assert rel_l2(got[:, :, 2:], full_g[:, :, 2 * s:2 * s + 2]) <= TOL[dtype]
+        assert np.all(got[:, :, :2] == 9.0)
+    assert abs(total - full_loss) <= 1e-5 * abs(full_loss)
+    assert np.all(full_g[0, :, 1, 2, 3:9] == 0.0)
+
+
+def test_softmax_xent_errors():
+    import torch
+    import paper_2007_12856_amd as h3d
+    z = h3d.Slab(torch.zeros((1, 3, 2, 2, 8), device="cuda"))
+    lab = torch.zeros((1, 2, 2, 8), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros((1,), device="cuda")
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.softmax_xent_fwd_bwd(z, lab, 32, loss, h3d.Slab(torch.zeros((1, 4, 2, 2, 8), device="cuda")))
+    assert e.value.status == -1
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.softmax_xent_fwd_bwd(z, lab, 0, loss, h3d.Slab(torch.zeros_like(z.t)))
+    assert e.value.status == -1
+    empty = h3d.Slab(torch.zeros((1, 3, 0, 2, 8), device="cuda"))
+    h3d.softmax_xent_fwd_bwd(empty, None, 32, loss.fill_(3.0), h3d.Slab(torch.zeros((1, 3, 0, 2, 8), device="cuda")))
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0

@@ -72,3 +72,20 @@ def test_shards_add_up_and_halos_are_ignored():
         total += loss
         np.testing.assert_array_equal(g, full_g[:, :, 2 * s:2 * s + 2])
     assert abs(total - full_loss) < 1e-14
+
+
+def test_voxels_without_a_class():
+    z, lab = case(n=1, c=3, d=2, h=2, w=4)
+    count = lab.size
+    skip = np.zeros(lab.shape, dtype=bool)
+    skip[0, 0, 1, :2] = True
+    lab2 = np.where(skip, 255, lab)
+    loss, g = orc.softmax_xent_fwd_bwd(Slab(z), lab2, count)
+    # the same as masking the per-voxel terms of torch's unreduced loss by hand
+    zt = torch.tensor(z, requires_grad=True)
+    per = torch.nn.functional.cross_entropy(zt, torch.tensor(lab), reduction="none")
+    ref = (per * torch.tensor(~skip)).sum() / count
+    ref.backward()
+    assert abs(loss - ref.item()) < 1e-13
+    np.testing.assert_allclose(g, zt.grad.numpy(), rtol=0, atol=1e-15)
+    assert np.all(g[0, :, 0, 1, :2] == 0.0)
