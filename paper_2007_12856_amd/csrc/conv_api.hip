@@ -88,7 +88,7 @@ extern "C" h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const vo
   H3D_TRY(check_pair(handle, x, z, "conv3d_fwd"));
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
-  if (c4_roll_supported(x, z) && !getenv("H3D_NO_C4_ROLL")) return conv3d_fwd_c4_roll(handle, x, w, bias, z, nullptr, nullptr, slope, ws, ws_bytes, s);
+  if (c4_roll_supported(x, z)) return conv3d_fwd_c4_roll(handle, x, w, bias, z, nullptr, nullptr, slope, ws, ws_bytes, s);
   if (c4_fwd_supported(x, z)) return conv3d_fwd_c4(handle, x, w, bias, z, slope, ws, ws_bytes, s);
   if (mfma_fwd_supported(x, z)) return conv3d_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return conv3d_direct<float>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
@@ -110,7 +110,7 @@ extern "C" h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, con
   H3D_TRY(pool_shapes_check(handle, &zc, y, "conv3d_fwd_pool"));
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
-  if (c4_fwd_pool_supported(x, z, y) && c4_roll_supported(x, z) && !getenv("H3D_NO_C4_ROLL"))
+  if (c4_fwd_pool_supported(x, z, y) && c4_roll_supported(x, z))
     return conv3d_fwd_c4_roll(handle, x, w, bias, z, y, mask, slope, ws, ws_bytes, s);
   if (c4_fwd_pool_supported(x, z, y)) return conv3d_fwd_c4_pool(handle, x, w, bias, z, y, mask, slope, ws, ws_bytes, s);
   // other shapes: the three passes one after the other (the unpooled output must then be stored)

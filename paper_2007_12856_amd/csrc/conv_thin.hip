@@ -546,7 +546,6 @@ h3d_status launch_thin_roll(void* handle, const h3d_tensor* in, const float* bia
     int nb = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, Cfg::THREADS, Cfg::LDS_BYTES) != hipSuccess || nb < 1) nb = 1;
     wgs_per_cu = nb;
-    if (getenv("H3D_DEBUG")) fprintf(stderr, "thin_roll<%d,%d>: %d workgroups per CU\n", TD, CB, nb);
   }
   ThinRollArgs r;
   r.in = a.in; r.out = a.out; r.cin_k = a.cin_k; r.cout_k = a.cout_k; r.out_slope = out_slope;
@@ -562,7 +561,6 @@ h3d_status launch_thin_roll(void* handle, const h3d_tensor* in, const float* bia
     const int64_t cost = cdiv(base * s, slots) * (cdiv(out->h, s) + 5);
     if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = s; }
   }
-  if (getenv("H3D_SEGS") && atoi(getenv("H3D_SEGS")) > 0) best = atoi(getenv("H3D_SEGS"));
   r.seg_rows = (int)cdiv(out->h, best);
   r.segs = (int)cdiv(out->h, r.seg_rows);
   const int64_t nwg = base * r.segs;

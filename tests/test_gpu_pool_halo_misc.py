@@ -269,3 +269,19 @@ def test_pool_bwd_fused_with_activation_backward(mode, dtype):
         gg = dev_like(ref, dtype)
         h3d.pool3d_bwd_act(dyg, xg if mode == orc.POOL_MAX else None, zg, gg, mode, act, 0.01)
         assert rel_l2(from_dev(gg.t), ref.a) <= (1e-6 if dtype == "f32" else 4e-3)
+
+
+def test_calibration_probes_run_and_report_their_work():
+    import torch
+    import paper_2007_12856_amd as h3d
+    scratch = torch.ones(h3d.probe_mfma_scratch_bytes() // 4, device="cuda")
+    assert h3d.probe_mfma_bf16(0, 8, scratch) == 2048 * 4 * 8 * 4 * 2.0 * 16 * 16 * 32
+    assert h3d.probe_mfma_bf16(1, 8, scratch) == 2048 * 4 * 8 * 2 * 2.0 * 32 * 32 * 16
+    buf, sink = torch.ones(1 << 20, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert h3d.probe_read(buf, sink) == 4 << 20
+    torch.cuda.synchronize()
+    assert sink.item() == 0 and torch.isfinite(scratch).all()
+    with pytest.raises(h3d.H3DError):
+        h3d.probe_mfma_bf16(2, 8, scratch)
+    with pytest.raises(h3d.H3DError):
+        h3d.probe_mfma_bf16(0, 8, scratch[:16])
