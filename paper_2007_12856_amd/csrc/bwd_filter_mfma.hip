@@ -951,12 +951,13 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 4 : 2) bwd_filter_roll_smal
 }
 
 // Second stage: out[i] = sum over chunks of part[chunk][i] in a FIXED order.  A block takes 16
-// consecutive outputs; 16 thread groups each add every 16th chunk in increasing order, then the 16
-// group sums are added in group order.  (dw and the bias partials share the kernel: the bias
+// consecutive outputs; G thread groups (16, or 64 when there are many chunks) each add every G-th chunk in
+// increasing order, then the G group sums are added in group order.  (dw and the bias partials share the kernel: the bias
 // partials are stored behind the dw partials.)
-__global__ void __launch_bounds__(256) bfm_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
-                                                         float* __restrict__ db, int64_t nw, int cout, int nchunks) {
-  __shared__ float red[16][17];
+template <int G>
+__global__ void __launch_bounds__(16 * G) bfm_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                            float* __restrict__ db, int64_t nw, int cout, int nchunks) {
+  __shared__ float red[G][17];
   const int o = threadIdx.x & 15, cg = threadIdx.x >> 4;
   const int64_t i = (int64_t)blockIdx.x * 16 + o;
   const int64_t nout = nw + cout;
@@ -965,14 +966,22 @@ __global__ void __launch_bounds__(256) bfm_reduce_kernel(const float* __restrict
     const bool is_w = i < nw;
     const float* base = is_w ? part + i : part + (int64_t)nchunks * nw + (i - nw);
     const int64_t stride = is_w ? nw : cout;
-    for (int c = cg; c < nchunks; c += 16) s += base[(int64_t)c * stride];
+    int c = cg;
+    for (; c + 7 * G < nchunks; c += 8 * G) {      // eight loads in flight, added in increasing chunk order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)(c + u * G) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nchunks; c += G) s += base[(int64_t)c * stride];
   }
   red[cg][o] = s;
   __syncthreads();
   if (cg == 0 && i < nout) {
     float t = red[0][o];
 #pragma unroll
-    for (int k = 1; k < 16; ++k) t += red[k][o];
+    for (int k = 1; k < G; ++k) t += red[k][o];
     if (i < nw) dw[i] = t;
     else if (db) db[i - nw] = t;
   }
@@ -1254,8 +1263,11 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   else if (nw >= 32768 && nw % 4 == 0 && (uintptr_t)ws % 16 == 0 && (uintptr_t)dw % 16 == 0)     // (few weights: more, smaller workgroups)
     hipLaunchKernelGGL(bfm_reduce4_kernel, dim3((unsigned)(cdiv(nw / 4, 16) + cdiv(a.cout, 16))), dim3(256), 0, stream, (const float*)ws, dw,
                        db, nw, a.cout, a.npart);
+  else if (a.npart >= 128)
+    hipLaunchKernelGGL(bfm_reduce_kernel<64>, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(1024), 0, stream, (const float*)ws, dw, db, nw,
+                       a.cout, a.npart);
   else
-    hipLaunchKernelGGL(bfm_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
+    hipLaunchKernelGGL(bfm_reduce_kernel<16>, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw, db, nw,
                        a.cout, a.npart);
   return launch_status(handle, "conv3d_bwd_filter_mfma");
 }
