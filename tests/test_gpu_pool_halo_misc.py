@@ -200,7 +200,9 @@ def test_concat_split_bit_exact(dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("m,n,k,act", [(4, 64, 512, orc.ACT_LEAKY), (3, 7, 33, orc.ACT_NONE), (8, 300, 1000, orc.ACT_RELU),
                                        (4, 4, 256, orc.ACT_NONE), (1, 130, 2048, orc.ACT_LEAKY),
-                                       (4, 2048, 1024, orc.ACT_LEAKY), (4, 1032, 2080, orc.ACT_LEAKY), (8, 1024, 4096, orc.ACT_NONE)])
+                                       (4, 2048, 1024, orc.ACT_LEAKY), (4, 1032, 2080, orc.ACT_LEAKY), (8, 1024, 4096, orc.ACT_NONE),
+                                       (4, 300, 4096, orc.ACT_LEAKY), (3, 2048, 8192, orc.ACT_NONE), (2, 256, 12288, orc.ACT_RELU),
+                                       (4, 4100, 4096, orc.ACT_LEAKY)])
 def test_dense_and_mse(m, n, k, act, dtype):
     import torch
     import paper_2007_12856_amd as h3d
