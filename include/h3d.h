@@ -184,6 +184,10 @@ h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, const void* w,
                                void* ws, size_t ws_bytes, void* stream);
 /* mask of a stored output z (what the fused call writes by itself). */
 h3d_status h3d_act_mask(void* handle, const h3d_tensor* z, void* mask, void* stream);
+/* y = avgpool(x) and, in the same pass, the mask of x (what h3d_pool3d_fwd and h3d_act_mask write one after the other):
+ * for the layers whose activation IS stored, so that their backward pass need not read it again.  bf16, w a multiple
+ * of 16, 32-byte-aligned x; otherwise H3D_EUNSUPPORTED. */
+h3d_status h3d_pool3d_fwd_mask(void* handle, const h3d_tensor* x, h3d_tensor* y, void* mask, void* stream);
 /* g = avgpool_bwd(dy) * (bit ? 1 : slope): h3d_pool3d_bwd_act with the mask in place of z; same bits in g.
  * bf16, w a multiple of 16, act RELU or LEAKY. */
 h3d_status h3d_pool3d_bwd_mask(void* handle, const h3d_tensor* dy, const void* mask, h3d_tensor* g, int act, float alpha,

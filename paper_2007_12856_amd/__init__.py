@@ -66,6 +66,7 @@ _SIGNATURES = {
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd_act": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
+    "h3d_pool3d_fwd_mask": (ctypes.c_int, [_P, _T, _T, _P, _P]),
     "h3d_act_mask_bytes": (ctypes.c_size_t, [_T]),
     "h3d_conv3d_fwd_pool": (ctypes.c_int, [_P, _T, _P, _P, _T, _T, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_act_mask": (ctypes.c_int, [_P, _T, _P, _P]),
@@ -269,6 +270,11 @@ def h3d_conv3d_fwd_pool(x: Slab, w, bias, z, y: Slab, mask, act: int = ACT_NONE,
 def h3d_act_mask(z: Slab, mask):
     _check(lib().h3d_act_mask(handle(), ctypes.byref(z.desc()), _ptr(mask), _stream()))
     return mask
+
+
+def h3d_pool3d_fwd_mask(x: Slab, y: Slab, mask):
+    _check(lib().h3d_pool3d_fwd_mask(handle(), ctypes.byref(x.desc()), ctypes.byref(y.desc()), _ptr(mask), _stream()))
+    return y
 
 
 def h3d_pool3d_bwd_mask(dy: Slab, mask, g: Slab, act: int, alpha: float = 0.0):
@@ -513,6 +519,7 @@ pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
 box_bytes, box_pack, box_unpack = h3d_box_bytes, h3d_box_pack, h3d_box_unpack
 conv3d_fwd_pool, act_mask, act_mask_bytes, pool3d_bwd_mask = h3d_conv3d_fwd_pool, h3d_act_mask, h3d_act_mask_bytes, h3d_pool3d_bwd_mask
+pool3d_fwd_mask = h3d_pool3d_fwd_mask
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c
 dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd

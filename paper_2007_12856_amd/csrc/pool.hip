@@ -63,6 +63,43 @@ __global__ void __launch_bounds__(256) pool_fwd_kernel(const T* __restrict__ x, 
   *reinterpret_cast<Vec<T, VEC>*>(y + yoff) = o;
 }
 
+// Average pooling that also writes the sign mask of its input (bf16, 8 outputs = 16 inputs per thread and row): the
+// activation output is read here anyway, so the backward pass can take the 1-bit mask instead of reading it again.
+// Same pooled bits as pool_fwd_kernel<bf16_t, 8, AVG>, same mask bits as act_mask_kernel.
+__global__ void __launch_bounds__(256) pool_fwd_mask_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
+                                                            uint8_t* __restrict__ mask, PoolArgs a) {
+  constexpr int VEC = 8;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.total) return;
+  int64_t xoff, yoff;
+  decode<bf16_t, VEC>(a, t, xoff, yoff);
+  int64_t r0 = t;
+  const int wv = (int)(r0 % a.wv); r0 /= a.wv;
+  const int ho = (int)(r0 % a.y.h); r0 /= a.y.h;
+  const int q = (int)(r0 % a.y.d); r0 /= a.y.d;          // r0 = n * c + channel
+  Vec<bf16_t, 2 * VEC> r[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    r[k] = *reinterpret_cast<const Vec<bf16_t, 2 * VEC>*>(x + xoff + (k >> 1) * a.x.plane + (k & 1) * a.x.w);
+  Vec<bf16_t, VEC> o;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s += ld(&r[k].v[2 * i]) + ld(&r[k].v[2 * i + 1]);
+    st(&o.v[i], s * 0.125f);
+  }
+  *reinterpret_cast<Vec<bf16_t, VEC>*>(y + yoff) = o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    uint32_t bits = 0;
+#pragma unroll
+    for (int e = 0; e < 2 * VEC; ++e) bits |= ((int16_t)r[k].v[e] > 0 ? 1u : 0u) << e;     // a bf16 is > 0 iff its bits, as int16, are
+    const int64_t row = ((r0 * a.x.d + 2 * q + (k >> 1)) * a.x.h + 2 * ho + (k & 1)) * (a.x.w / 8) + 2 * wv;
+    *reinterpret_cast<uint16_t*>(mask + row) = (uint16_t)bits;
+  }
+}
+
 // ACT: also multiply by the activation derivative taken from the saved output z of the layer that
 // produced the pooled tensor (g = pool_bwd(dy) * (z > 0 ? 1 : slope)): one pass instead of a pooling
 // backward followed by an activation backward.
@@ -337,6 +374,27 @@ extern "C" h3d_status h3d_act_mask(void* handle, const h3d_tensor* z, void* mask
   else
     hipLaunchKernelGGL((act_mask_kernel<bf16_t>), dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)z->data, (uint8_t*)mask, g, total);
   return launch_status(handle, "act_mask");
+}
+
+extern "C" h3d_status h3d_pool3d_fwd_mask(void* handle, const h3d_tensor* x, h3d_tensor* y, void* mask, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  H3D_TRY(check_tensor_packed(handle, x, "x"));
+  H3D_TRY(check_tensor_packed(handle, y, "y"));
+  H3D_TRY(pool_check(handle, x, y, "pool3d_fwd_mask"));
+  if (x->dtype != H3D_BF16 || x->w % 16 || (uintptr_t)x->data % 32 || (uintptr_t)y->data % 16 || (uintptr_t)mask % 2)
+    return fail(handle, H3D_EUNSUPPORTED, "pool3d_fwd_mask: bf16, w a multiple of 16 and aligned tensors only");
+  PoolArgs a;
+  a.x = make_geo(x);
+  a.y = make_geo(y);
+  a.wv = y->w / 8;
+  a.total = (int64_t)y->n * y->c * y->d * y->h * a.wv;
+  if (a.total == 0) return H3D_OK;
+  if (!mask) return fail(handle, H3D_EINVAL, "pool3d_fwd_mask: NULL mask");
+  const int64_t grid = cdiv(a.total, 256);
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "pool3d_fwd_mask: too many blocks");
+  hipLaunchKernelGGL(pool_fwd_mask_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)x->data,
+                     (bf16_t*)y->data, (uint8_t*)mask, a);
+  return launch_status(handle, "pool3d_fwd_mask");
 }
 
 extern "C" h3d_status h3d_pool3d_bwd_mask(void* handle, const h3d_tensor* dy, const void* mask, h3d_tensor* g, int act, float alpha,

@@ -10,7 +10,7 @@ from __future__ import annotations
 import torch
 
 from . import (ACT_LEAKY, ACT_NONE, POOL_AVG, Slab, Workspace, conv3d_bwd_data, conv3d_bwd_filter, conv3d_fwd,
-               conv3d_fwd_pool, conv3d_s2_bwd_data, conv3d_s2_bwd_filter, conv3d_s2_fwd, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd)
+               conv3d_fwd_pool, conv3d_s2_bwd_data, conv3d_s2_bwd_filter, conv3d_s2_fwd, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd, pool3d_fwd_mask)
 
 
 class CosmoFlowStack:
@@ -55,7 +55,10 @@ class CosmoFlowStack:
             self.fused[i] = fused
             zshape = (n, w.shape[0], zd, zh, zw)
             z = None if fused else Slab(torch.empty(zshape, dtype=dt, device=dev))
-            self.mask.append(torch.empty((n * w.shape[0] * zd * zh * zw // 8,), dtype=torch.uint8, device=dev) if fused else None)
+            # stored activations that are pooled: the pooling forward also writes their sign mask (it reads them anyway), and
+            # the pooling backward takes the mask instead of reading the activation again
+            masked = (fused or (bool(fuse_pool) and dt == torch.bfloat16 and self.pools[i] and zd % 2 == 0 and zh % 2 == 0 and zw % 16 == 0))
+            self.mask.append(torch.empty((n * w.shape[0] * zd * zh * zw // 8,), dtype=torch.uint8, device=dev) if masked else None)
             # g: gradient at the convolution's output; after a pooling it is already multiplied by the activation
             # derivative (pooling backward and activation backward are one call), else it is the raw dz
             self.g.append(Slab(torch.empty(zshape, dtype=dt, device=dev)))
@@ -107,7 +110,11 @@ class CosmoFlowStack:
                 io = (cur.t.numel() + z.t.numel() + w.numel()) * es
                 fwd = conv3d_s2_fwd if self.strides[i] == 2 else conv3d_fwd
                 self._op(f"conv{i + 1}_fwd", lambda cur=cur, w=w, b=b, z=z, fwd=fwd: fwd(cur, w, b, z, ACT_LEAKY, al, ws), fl, io)
-                if p is not None:
+                if p is not None and self.mask[i] is not None:
+                    mask = self.mask[i]
+                    self._op(f"pool{i + 1}_fwd", lambda z=z, p=p, mask=mask: pool3d_fwd_mask(z, p, mask), 0,
+                             (z.t.numel() + p.t.numel()) * es + mask.numel())
+                elif p is not None:
                     self._op(f"pool{i + 1}_fwd", lambda z=z, p=p: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
             cur = self.out[i]
         h = self.flat
@@ -136,7 +143,7 @@ class CosmoFlowStack:
             dxin = self.dx if i == 0 else self.dout[i - 1]
             fl = 2 * 27 * w.shape[1] * g.t.numel()
             zb, actb = None, ACT_NONE
-            if self.fused[i]:
+            if dp is not None and self.mask[i] is not None:
                 # pooling backward and activation backward in one pass; BF and BD then run unmasked on g
                 mask = self.mask[i]
                 self._op(f"pool{i + 1}_bwd_mask", lambda dp=dp, mask=mask, g=g: pool3d_bwd_mask(dp, mask, g, ACT_LEAKY, al), 0,

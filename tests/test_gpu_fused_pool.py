@@ -108,3 +108,27 @@ def test_pool_bwd_from_mask_equals_pool_bwd_from_saved_output(shape, halo, act):
     dxo = orc.pool3d_bwd(dyo, zo, orc.POOL_AVG, dx_halo=halo)
     want = dxo.interior * np.where(zo.interior > 0, 1.0, alpha)
     assert rel_l2(from_dev(g2.interior), want) <= 4e-3
+
+
+@pytest.mark.parametrize("shape,halo", [((2, 3, 4, 6, 32), (0, 0)), ((1, 5, 2, 4, 80), (1, 1)), ((1, 16, 8, 32, 64), (1, 0))])
+def test_pool_fwd_with_mask_equals_the_two_separate_passes(shape, halo):
+    """The pooling forward that also writes the sign mask of its input: the pooled tensor of pool3d_fwd and the mask of
+    act_mask, bit for bit; halo planes of the input are not touched, halo planes of the output stay as they were."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = shape
+    za = synth.flat("normal", SEED, 15, (N, C, halo[0] + d + halo[1], H, W))
+    za[:, :, :, 1] = 0.0
+    _, zg = slab_pair(za, "bf16", halo, 4, 4 + d + 6)
+    mk = lambda: h3d.Slab(torch.full((N, C, d // 2 + 2, H // 2, W // 2), 9.0, dtype=torch.bfloat16, device="cuda"), 1, 1, 2, (4 + d + 6) // 2)
+    y1, y2 = mk(), mk()
+    m1 = torch.zeros((h3d.act_mask_bytes(zg, zg),), dtype=torch.uint8, device="cuda")
+    m2 = torch.full_like(m1, 0xAA)
+    h3d.pool3d_fwd(zg, y1, h3d.POOL_AVG)
+    h3d.act_mask(zg, m1)
+    h3d.pool3d_fwd_mask(zg, y2, m2)
+    assert torch.equal(y1.t, y2.t) and torch.equal(m1, m2)
+    with pytest.raises(h3d.H3DError) as e:                      # w not a multiple of 16
+        zz = h3d.Slab(torch.zeros((1, 1, 2, 2, 8), dtype=torch.bfloat16, device="cuda"))
+        h3d.pool3d_fwd_mask(zz, h3d.Slab(torch.zeros((1, 1, 1, 1, 4), dtype=torch.bfloat16, device="cuda")), m2)
+    assert e.value.status == -2
