@@ -122,6 +122,10 @@ def side_workload(args, seed):
                         dev(dout), {k: tuple(None if f is None else dev(f) for f in pr) for k, pr in faces.items()})
         name = "U-Net-shaped level on a 64x256x256 shard of a 256^3 volume (halo 2), bf16, fwd+bwd"
     stream = torch.cuda.current_stream()
+    if hasattr(net, "overlap") and not args.only:
+        # the stack's second stream (late backward-filter calls, dense weight gradients): their table rows then show the
+        # launch only, the "join" row the wait for them
+        net.overlap = not args.no_overlap
     for _ in range(args.warmup):
         net.step()
     torch.cuda.synchronize()
