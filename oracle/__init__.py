@@ -129,6 +129,41 @@ def conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, act=ACT_NONE, alpha=0.0
     return dw, db
 
 
+def convk_fwd(x: Slab, w, bias, act=ACT_NONE, alpha=0.0) -> Slab:
+    """Odd filter edge K (5 for the 5x5x5 filters of Sec. III-A), stride 1, zero padding K//2; shard interior only."""
+    w = _f64(w)
+    bias = _f64(bias)
+    k = w.shape[2]
+    assert w.shape[1:] == (x.a.shape[1], k, k, k)
+    z = x.like(w.shape[0])
+    _chk(_L().orc_convk_fwd(k, _p(x.a), x.geom(), _p(w), _p(bias), _p(z.a), z.geom(), int(act),
+                            ctypes.c_double(alpha)), "convk_fwd")
+    return z
+
+
+def convk_bwd_data(dz: Slab, z: Slab | None, w, act=ACT_NONE, alpha=0.0) -> Slab:
+    """dx = sum_{co,k} w[co,ci,k] * (dz*act'(z))~[q-k+K//2] on the shard interior."""
+    w = _f64(w)
+    k = w.shape[2]
+    assert w.shape[0] == dz.a.shape[1] and w.shape[2:] == (k, k, k)
+    dx = dz.like(w.shape[1])
+    _chk(_L().orc_convk_bwd_data(k, _p(dz.a), dz.geom(), _p(z.a) if z is not None else None,
+                                 z.geom() if z is not None else None, _p(w), _p(dx.a), dx.geom(), int(act),
+                                 ctypes.c_double(alpha)), "convk_bwd_data")
+    return dx
+
+
+def convk_bwd_filter(k: int, x: Slab, dz: Slab, z: Slab | None, act=ACT_NONE, alpha=0.0):
+    """The shard's partial dw [cout,cin,k,k,k] and db [cout]."""
+    cin, cout = x.a.shape[1], dz.a.shape[1]
+    dw = np.zeros((cout, cin, k, k, k), dtype=np.float64)
+    db = np.zeros((cout,), dtype=np.float64)
+    _chk(_L().orc_convk_bwd_filter(k, _p(x.a), x.geom(), _p(dz.a), dz.geom(), _p(z.a) if z is not None else None,
+                                   z.geom() if z is not None else None, _p(dw), _p(db), int(act),
+                                   ctypes.c_double(alpha)), "convk_bwd_filter")
+    return dw, db
+
+
 def _s2_out(x: Slab, channels: int, halo_lo: int = 0, halo_hi: int = 0, fill: float = np.nan) -> Slab:
     n, _, _, h, w = x.a.shape
     a = np.full((n, channels, halo_lo + x.d // 2 + halo_hi, (h + 1) // 2, (w + 1) // 2), fill, dtype=np.float64)

@@ -206,6 +206,140 @@ int orc_conv3d_bwd_filter(const double* x, const int64_t* xg, const double* dz, 
   return 0;
 }
 
+/* ------------------------------------------------- 5x5x5 convolution */
+/* Filters of 5x5x5 with stride 1 and two zero voxels of padding on every side (Sec. III-A names 3^3 and
+ * 5^3 as the two filter sizes whose halo faces have specialised packing kernels; the halo is then two
+ * planes wide).  Written for an odd filter edge K = 2R+1 so that K = 3 can be compared with the functions
+ * above; the shard interior only is produced (no halo recompute):
+ *   z[n,co,p]  = act(b[co] + sum_{ci,k} w[co,ci,k] * x~[n,ci,p+k-R])        p in [0,d)
+ *   dx[n,ci,q] = sum_{co,k} w[co,ci,k] * g~[n,co,q-k+R],  g = dz * act'(z)   q in [0,d)
+ *   dw[co,ci,k] = sum_{n,p in [0,d)} g[n,co,p] * x~[n,ci,p+k-R],  db[co] = sum g. */
+static int halo_ok_r(const int64_t* in, int64_t R) {
+  for (int64_t p = 0; p < in[G_D]; ++p)
+    for (int64_t k = -R; k <= R; ++k)
+      if (in_volume(in, p + k) && !stored(in, p + k)) return 0;
+  return 1;
+}
+
+int orc_convk_fwd(int K, const double* x, const int64_t* xg, const double* w, const double* bias, double* z,
+                  const int64_t* zg, int act, double alpha) {
+  if (K < 1 || K % 2 == 0 || !same_shard(xg, zg)) return -1;
+  const int64_t R = K / 2, N = xg[G_N], Ci = xg[G_C], Co = zg[G_C], D = xg[G_D], H = xg[G_H], W = xg[G_W];
+  if (!halo_ok_r(xg, R)) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(3) schedule(dynamic, 1)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t co = 0; co < Co; ++co)
+      for (int64_t p = 0; p < D; ++p)
+        for (int64_t h = 0; h < H; ++h)
+          for (int64_t v = 0; v < W; ++v) {
+            double acc = bias ? bias[co] : 0.0;
+            for (int64_t ci = 0; ci < Ci; ++ci)
+              for (int64_t kd = 0; kd < K; ++kd) {
+                if (!in_volume(xg, p + kd - R)) continue;
+                for (int64_t kh = 0; kh < K; ++kh) {
+                  const int64_t hh = h + kh - R;
+                  if (hh < 0 || hh >= H) continue;
+                  for (int64_t kw = 0; kw < K; ++kw) {
+                    const int64_t ww = v + kw - R;
+                    if (ww < 0 || ww >= W) continue;
+                    acc += w[(((co * Ci + ci) * K + kd) * K + kh) * K + kw] * x[at5(xg, n, ci, p + kd - R, hh, ww)];
+                  }
+                }
+              }
+            if (!(acc > 0.0)) acc *= slope;
+            z[at5(zg, n, co, p, h, v)] = acc;
+          }
+  return 0;
+}
+
+int orc_convk_bwd_data(int K, const double* dz, const int64_t* dzg, const double* z, const int64_t* zg,
+                       const double* w, double* dx, const int64_t* dxg, int act, double alpha) {
+  if (K < 1 || K % 2 == 0 || !same_shard(dzg, dxg)) return -1;
+  const int masked = (z != NULL && act != ACT_NONE);
+  if (masked && (!same_shard(zg, dzg) || zg[G_C] != dzg[G_C])) return -1;
+  const int64_t R = K / 2, N = dzg[G_N], Co = dzg[G_C], Ci = dxg[G_C], D = dzg[G_D], H = dzg[G_H], W = dzg[G_W];
+  if (!halo_ok_r(dzg, R)) return -4;
+  if (masked && !halo_ok_r(zg, R)) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(3) schedule(dynamic, 1)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t ci = 0; ci < Ci; ++ci)
+      for (int64_t q = 0; q < D; ++q)
+        for (int64_t h = 0; h < H; ++h)
+          for (int64_t v = 0; v < W; ++v) {
+            double acc = 0.0;
+            for (int64_t co = 0; co < Co; ++co)
+              for (int64_t kd = 0; kd < K; ++kd) {
+                const int64_t p = q - kd + R;
+                if (!in_volume(dzg, p)) continue;
+                for (int64_t kh = 0; kh < K; ++kh) {
+                  const int64_t hh = h - kh + R;
+                  if (hh < 0 || hh >= H) continue;
+                  for (int64_t kw = 0; kw < K; ++kw) {
+                    const int64_t ww = v - kw + R;
+                    if (ww < 0 || ww >= W) continue;
+                    double g = dz[at5(dzg, n, co, p, hh, ww)];
+                    if (masked && !(z[at5(zg, n, co, p, hh, ww)] > 0.0)) g *= slope;
+                    acc += w[(((co * Ci + ci) * K + kd) * K + kh) * K + kw] * g;
+                  }
+                }
+              }
+            dx[at5(dxg, n, ci, q, h, v)] = acc;
+          }
+  return 0;
+}
+
+int orc_convk_bwd_filter(int K, const double* x, const int64_t* xg, const double* dz, const int64_t* dzg,
+                         const double* z, const int64_t* zg, double* dw, double* db, int act, double alpha) {
+  if (K < 1 || K % 2 == 0 || !same_shard(xg, dzg)) return -1;
+  const int masked = (z != NULL && act != ACT_NONE);
+  if (masked && (!same_shard(zg, dzg) || zg[G_C] != dzg[G_C])) return -1;
+  const int64_t R = K / 2, K3 = (int64_t)K * K * K;
+  const int64_t N = xg[G_N], Ci = xg[G_C], Co = dzg[G_C], D = xg[G_D], H = xg[G_H], W = xg[G_W];
+  if (!halo_ok_r(xg, R)) return -4;
+  const double slope = act_slope(act, alpha);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int64_t co = 0; co < Co; ++co)
+    for (int64_t cik = 0; cik < Ci * K3; ++cik) {
+      const int64_t ci = cik / K3, k = cik % K3;
+      const int64_t kd = k / (K * K), kh = (k / K) % K, kw = k % K;
+      double acc = 0.0;
+      for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < D; ++p) {
+          if (!in_volume(xg, p + kd - R)) continue;
+          for (int64_t h = 0; h < H; ++h) {
+            const int64_t hh = h + kh - R;
+            if (hh < 0 || hh >= H) continue;
+            for (int64_t v = 0; v < W; ++v) {
+              const int64_t ww = v + kw - R;
+              if (ww < 0 || ww >= W) continue;
+              double g = dz[at5(dzg, n, co, p, h, v)];
+              if (masked && !(z[at5(zg, n, co, p, h, v)] > 0.0)) g *= slope;
+              acc += g * x[at5(xg, n, ci, p + kd - R, hh, ww)];
+            }
+          }
+        }
+      dw[co * Ci * K3 + cik] = acc;
+    }
+  if (db) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t co = 0; co < Co; ++co) {
+      double acc = 0.0;
+      for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < D; ++p)
+          for (int64_t h = 0; h < H; ++h)
+            for (int64_t v = 0; v < W; ++v) {
+              double g = dz[at5(dzg, n, co, p, h, v)];
+              if (masked && !(z[at5(zg, n, co, p, h, v)] > 0.0)) g *= slope;
+              acc += g;
+            }
+      db[co] = acc;
+    }
+  }
+  return 0;
+}
+
 /* ------------------------------------------------- stride-2 convolution */
 /* The fourth convolution of the CosmoFlow network has a stride of 2 (Table I); "same" padding
  * is read as one zero voxel on every side, as for the stride-1 layers, so that an even extent is
