@@ -142,6 +142,31 @@ h3d_status h3d_conv3d_s2_bwd_filter(void* handle, const h3d_tensor* x, const h3d
                                     float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
                                     void* stream);
 
+/* ---- 5x5x5 convolution, stride 1, zero padding 2 (Sec. III-A: 3^3 and 5^3 are the filter sizes the halo packing
+ * kernels are specialised for; with 5^3 the halo is two planes wide) ----
+ * Weights w: [cout][cin][5][5][5] packed, same dtype as the activations; bias, dw ([cout][cin][5][5][5] fp32), db,
+ * act / alpha as for the 3x3x3 calls.  Packed tensors only; both descriptors of a call are the same shard (n, d, h, w,
+ * d_offset, d_global, dtype) with at least one channel each.  The shard INTERIOR of the output argument is written;
+ * its halo planes are neither read nor written.  The tensor a call reads through the window (x in forward and
+ * backward-filter; dz, and z when act is not NONE, in backward-data) must store min(2, planes of the volume on that
+ * side) halo planes below and above, else H3D_EHALO; planes outside the global volume count as zero.
+ *   forward:          z[n,co,p]  = act(bias[co] + sum_{ci,k} w[co,ci,k] * x~[n,ci,p+k-2])
+ *   backward-data:    dx[n,ci,q] = sum_{co,k} w[co,ci,k] * g~[n,co,q-k+2],  g = dz * (z > 0 ? 1 : slope)
+ *   backward-filter:  dw[co,ci,k] = sum_n sum_{p in the interior} g[n,co,p] * x~[n,ci,p+k-2],  db[co] = sum g
+ *                     (overwritten; the shard's partial gradient; deterministic: fixed chunks of tiles, added in order)
+ * Workspace: h3d_conv3d_k5_workspace_bytes(handle, op, x, z) with x / z the input-side / output-side descriptors for
+ * every op (fp32 copy of the filter, or the per-chunk partial sums); 256-byte aligned; H3D_EWORKSPACE if too small.
+ * More than 65535 interior planes or n * ceil(channels/16) > 65535: H3D_EUNSUPPORTED.  fp32 accumulation on the
+ * vector ALU (no matrix-core form yet). */
+size_t h3d_conv3d_k5_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* z);
+h3d_status h3d_conv3d_k5_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z,
+                             int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+h3d_status h3d_conv3d_k5_bwd_data(void* handle, const h3d_tensor* dz, const h3d_tensor* z, const void* w,
+                                  h3d_tensor* dx, int act, float alpha, void* ws, size_t ws_bytes, void* stream);
+h3d_status h3d_conv3d_k5_bwd_filter(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z,
+                                    float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
+                                    void* stream);
+
 /* ---- activation backward as a separate pass (Sec. IV: leaky-ReLU after every conv; U-Net: ReLU) ----
  * g = (dz + dz2) * (z > 0 ? 1 : slope) on the shard INTERIOR; dz2 may be NULL (it merges the two
  * gradient branches of a skip connection).  z is the saved forward output.  Halo planes of g are

@@ -57,6 +57,10 @@ _SIGNATURES = {
     "h3d_conv3d_s2_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_s2_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_s2_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_conv3d_k5_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
+    "h3d_conv3d_k5_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_conv3d_k5_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_conv3d_k5_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_softmax_xent_workspace_bytes": (ctypes.c_size_t, [_P, _T]),
     "h3d_softmax_xent_fwd_bwd": (ctypes.c_int, [_P, _T, _P, ctypes.c_int64, _P, _T, _P, ctypes.c_size_t, _P]),
     "h3d_probe_mfma_scratch_bytes": (ctypes.c_size_t, []),
@@ -327,6 +331,34 @@ def h3d_conv3d_s2_bwd_filter(x: Slab, dy: Slab, y: Slab | None, dw, db, act: int
     return dw, db
 
 
+def h3d_conv3d_k5_workspace_bytes(op: int, x: Slab, z: Slab) -> int:
+    return int(lib().h3d_conv3d_k5_workspace_bytes(handle(), op, ctypes.byref(x.desc()), ctypes.byref(z.desc())))
+
+
+def h3d_conv3d_k5_fwd(x: Slab, w, bias, z: Slab, act: int = ACT_NONE, alpha: float = 0.0, ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_k5_workspace_bytes(OP_FWD, x, z))
+    _check(lib().h3d_conv3d_k5_fwd(handle(), ctypes.byref(x.desc()), _ptr(w), _ptr(bias), ctypes.byref(z.desc()), act,
+                                   alpha, p, n, _stream()))
+    return z
+
+
+def h3d_conv3d_k5_bwd_data(dz: Slab, z: Slab | None, w, dx: Slab, act: int = ACT_NONE, alpha: float = 0.0,
+                           ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_k5_workspace_bytes(OP_BWD_DATA, dx, dz))
+    _check(lib().h3d_conv3d_k5_bwd_data(handle(), ctypes.byref(dz.desc()), ctypes.byref(z.desc()) if z is not None else None,
+                                        _ptr(w), ctypes.byref(dx.desc()), act, alpha, p, n, _stream()))
+    return dx
+
+
+def h3d_conv3d_k5_bwd_filter(x: Slab, dz: Slab, z: Slab | None, dw, db, act: int = ACT_NONE, alpha: float = 0.0,
+                             ws: Workspace | None = None):
+    p, n = (ws or _ws).get(h3d_conv3d_k5_workspace_bytes(OP_BWD_FILTER, x, dz))
+    _check(lib().h3d_conv3d_k5_bwd_filter(handle(), ctypes.byref(x.desc()), ctypes.byref(dz.desc()),
+                                          ctypes.byref(z.desc()) if z is not None else None, _ptr(dw), _ptr(db), act, alpha,
+                                          p, n, _stream()))
+    return dw, db
+
+
 def h3d_act_bwd(dz: Slab, dz2: Slab | None, z: Slab, g: Slab, act: int, alpha: float = 0.0):
     _check(lib().h3d_act_bwd(handle(), ctypes.byref(dz.desc()), ctypes.byref(dz2.desc()) if dz2 is not None else None,
                              ctypes.byref(z.desc()), ctypes.byref(g.desc()), act, alpha, _stream()))
@@ -515,6 +547,7 @@ def h3d_probe_read(buf, sink) -> int:
 bn_stats, bn_finalize, bn_fwd, bn_bwd_stats, bn_bwd = h3d_bn_stats, h3d_bn_finalize, h3d_bn_fwd, h3d_bn_bwd_stats, h3d_bn_bwd
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
 conv3d_s2_fwd, conv3d_s2_bwd_data, conv3d_s2_bwd_filter = h3d_conv3d_s2_fwd, h3d_conv3d_s2_bwd_data, h3d_conv3d_s2_bwd_filter
+conv3d_k5_fwd, conv3d_k5_bwd_data, conv3d_k5_bwd_filter = h3d_conv3d_k5_fwd, h3d_conv3d_k5_bwd_data, h3d_conv3d_k5_bwd_filter
 pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act
 halo_bytes, halo_pack, halo_unpack = h3d_halo_bytes, h3d_halo_pack, h3d_halo_unpack
 box_bytes, box_pack, box_unpack = h3d_box_bytes, h3d_box_pack, h3d_box_unpack

@@ -1,0 +1,391 @@
+// 5x5x5 convolution, stride 1, two zero voxels of padding (Sec. III-A: the two filter sizes the halo packing is
+// specialised for are 3^3 and 5^3; the halo is two planes wide here).  All three passes on a depth shard.
+//
+// Direct form on the vector ALU with fp32 accumulation (fp32 or bf16 storage):
+//   forward / backward-data: a workgroup owns an 8 x 32 tile of one output plane and 16 output channels; per
+//     input channel the 5 x 12 x 36 input patch is staged in LDS (zero where the volume ends), every thread owns
+//     one voxel and 16 accumulators, and the 125 x 16 weights of the step come as fp32 from a packed copy whose
+//     addresses are the same for the whole workgroup (scalar loads, no LDS traffic).  Backward-data is the same
+//     kernel on g = dz * act'(z) (mask applied while staging) with the filter reversed and transposed.
+//   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
+//     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
+//     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).
+#include "common.h"
+
+namespace h3d {
+namespace {
+
+constexpr int K5_TAPS = 125;
+constexpr int K5_TH = 8, K5_TW = 32, K5_COB = 16;
+constexpr int K5_PH = K5_TH + 4, K5_PW = K5_TW + 4, K5_PWP = K5_PW + 1;
+constexpr int K5_PATCH = 5 * K5_PH * K5_PW;
+
+struct K5Args {
+  Geo in, out, zg;     // staged tensor (x or dz), written tensor (z or dx), mask tensor (saved output, backward only)
+  int pmin, pmax;      // local planes of `in` that are stored and inside the volume: [pmin, pmax)
+  int tiles_w, tiles_h, cobs;
+  float slope_in;      // factor on staged values where the saved output is not positive
+  float slope_out;     // activation of the written values
+};
+
+// wp[cob][cl][t][16] fp32, cl the channel the kernels loop over, 16 the channels a thread accumulates.
+// forward: wp[cob][ci][t][c] = w[16 cob + c][ci][t];  backward-data: wp[cib][co][t][c] = w[co][16 cib + c][124 - t].
+template <typename T>
+__global__ void __launch_bounds__(256) k5_pack_w_kernel(const T* __restrict__ w, float* __restrict__ wp, int cin, int cout,
+                                                        int transposed, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % K5_COB), t = (int)((i / K5_COB) % K5_TAPS);
+  const int loopc = transposed ? cout : cin, accc = transposed ? cin : cout;
+  const int cl = (int)((i / (K5_COB * K5_TAPS)) % loopc), cb = (int)(i / ((int64_t)K5_COB * K5_TAPS * loopc));
+  const int ca = cb * K5_COB + c;
+  float v = 0.f;
+  if (ca < accc) {
+    const int co = transposed ? cl : ca, ci = transposed ? ca : cl, tt = transposed ? K5_TAPS - 1 - t : t;
+    v = ld(w + ((int64_t)co * cin + ci) * K5_TAPS + tt);
+  }
+  wp[i] = v;
+}
+
+// one staged patch value: plane pp (local index), row hh, column ww of channel c of sample n; zero outside
+template <typename T, bool MASK>
+__device__ __forceinline__ float k5_fetch(const T* __restrict__ in, const T* __restrict__ zm, const K5Args& a, int n, int c, int pp,
+                                          int hh, int ww) {
+  if (pp < a.pmin || pp >= a.pmax || hh < 0 || hh >= a.in.h || ww < 0 || ww >= a.in.w) return 0.f;
+  const int64_t sp = (int64_t)hh * a.in.w + ww;
+  float v = ld(in + (int64_t)n * a.in.nstride + (int64_t)c * a.in.cstride + (int64_t)(pp + a.in.hlo) * a.in.plane + sp);
+  if (MASK) {
+    const float zv = ld(zm + (int64_t)n * a.zg.nstride + (int64_t)c * a.zg.cstride + (int64_t)(pp + a.zg.hlo) * a.zg.plane + sp);
+    if (!(zv > 0.f)) v *= a.slope_in;
+  }
+  return v;
+}
+
+template <typename T, bool MASK>
+__global__ void __launch_bounds__(256) k5_conv_kernel(const T* __restrict__ in, const T* __restrict__ zm, const float* __restrict__ wp,
+                                                      const float* __restrict__ bias, T* __restrict__ out, K5Args a) {
+  __shared__ float xs[5][K5_PH][K5_PWP];
+  const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
+  const int tw = blockIdx.x % a.tiles_w, th = blockIdx.x / a.tiles_w;
+  const int p = blockIdx.y;
+  const int n = blockIdx.z / a.cobs, cob = blockIdx.z % a.cobs;
+  const int h0 = th * K5_TH, w0 = tw * K5_TW;
+  float acc[K5_COB];
+#pragma unroll
+  for (int c = 0; c < K5_COB; ++c) acc[c] = 0.f;
+  const float* wb = wp + (int64_t)cob * a.in.c * (K5_TAPS * K5_COB);
+  for (int cl = 0; cl < a.in.c; ++cl) {
+    __syncthreads();
+    for (int idx = tid; idx < K5_PATCH; idx += 256) {
+      const int kd = idx / (K5_PH * K5_PW), r = (idx / K5_PW) % K5_PH, c = idx % K5_PW;
+      xs[kd][r][c] = k5_fetch<T, MASK>(in, zm, a, n, cl, p + kd - 2, h0 + r - 2, w0 + c - 2);
+    }
+    __syncthreads();
+    const float* wc = wb + (int64_t)cl * (K5_TAPS * K5_COB);
+    for (int kd = 0; kd < 5; ++kd)
+      for (int kh = 0; kh < 5; ++kh) {
+        const float* wr = wc + (kd * 5 + kh) * 5 * K5_COB;
+#pragma unroll
+        for (int kw = 0; kw < 5; ++kw) {
+          const float xv = xs[kd][ty + kh][tx + kw];
+#pragma unroll
+          for (int c = 0; c < K5_COB; ++c) acc[c] = fmaf(xv, wr[kw * K5_COB + c], acc[c]);
+        }
+      }
+  }
+  const int hh = h0 + ty, ww = w0 + tx;
+  if (hh >= a.out.h || ww >= a.out.w) return;
+  T* o = out + (int64_t)n * a.out.nstride + (int64_t)(p + a.out.hlo) * a.out.plane + (int64_t)hh * a.out.w + ww;
+#pragma unroll
+  for (int c = 0; c < K5_COB; ++c) {
+    const int co = cob * K5_COB + c;
+    if (co < a.out.c) {
+      float v = acc[c] + (bias ? bias[co] : 0.f);
+      if (!(v > 0.f)) v *= a.slope_out;
+      st(o + (int64_t)co * a.out.cstride, v);
+    }
+  }
+}
+
+// a.in = x, a.out = dz (the gradient), a.zg = saved output.  grid (chunks, cin, cobs).
+// part: [chunk][cout][cin][125], part_db: [chunk][cout]
+template <typename T, bool MASK>
+__global__ void __launch_bounds__(256) k5_bwf_kernel(const T* __restrict__ x, const T* __restrict__ dz, const T* __restrict__ zm,
+                                                     float* __restrict__ part, float* __restrict__ part_db, K5Args a,
+                                                     int tiles_total, int tiles_per_chunk) {
+  __shared__ float xs[5][K5_PH][K5_PWP];
+  __shared__ __attribute__((aligned(16))) float gs[K5_TH * K5_TW][K5_COB];
+  const int tid = threadIdx.x;
+  const int chunk = blockIdx.x, ci = blockIdx.y, cob = blockIdx.z;
+  const bool tap_thread = tid < 2 * K5_TAPS;
+  const int tap = tid % K5_TAPS, half = tid >= K5_TAPS ? 1 : 0;
+  const int kd = tap / 25, kh = (tap / 5) % 5, kw = tap % 5;
+  const bool db_thread = ci == 0 && tid < K5_COB;
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+  float dbacc = 0.f;
+  const int t_lo = chunk * tiles_per_chunk;
+  const int t_hi = min(t_lo + tiles_per_chunk, tiles_total);
+  const int tiles_pl = a.tiles_w * a.tiles_h;
+  for (int tile = t_lo; tile < t_hi; ++tile) {
+    const int tw = tile % a.tiles_w, th = (tile / a.tiles_w) % a.tiles_h;
+    const int p = (tile / tiles_pl) % a.in.d, n = tile / (tiles_pl * a.in.d);
+    const int h0 = th * K5_TH, w0 = tw * K5_TW;
+    __syncthreads();
+    for (int idx = tid; idx < K5_PATCH; idx += 256) {
+      const int pd = idx / (K5_PH * K5_PW), r = (idx / K5_PW) % K5_PH, c = idx % K5_PW;
+      xs[pd][r][c] = k5_fetch<T, false>(x, nullptr, a, n, ci, p + pd - 2, h0 + r - 2, w0 + c - 2);
+    }
+    for (int idx = tid; idx < K5_TH * K5_TW * K5_COB; idx += 256) {
+      const int c = idx / (K5_TH * K5_TW), v = idx % (K5_TH * K5_TW);
+      const int co = cob * K5_COB + c, hh = h0 + (v >> 5), ww = w0 + (v & 31);
+      float g = 0.f;
+      if (co < a.out.c && hh < a.out.h && ww < a.out.w) {
+        const int64_t sp = (int64_t)hh * a.out.w + ww;
+        g = ld(dz + (int64_t)n * a.out.nstride + (int64_t)co * a.out.cstride + (int64_t)(p + a.out.hlo) * a.out.plane + sp);
+        if (MASK) {
+          const float zv = ld(zm + (int64_t)n * a.zg.nstride + (int64_t)co * a.zg.cstride + (int64_t)(p + a.zg.hlo) * a.zg.plane + sp);
+          if (!(zv > 0.f)) g *= a.slope_in;
+        }
+      }
+      gs[v][c] = g;
+    }
+    __syncthreads();
+    if (tap_thread) {
+      const float* xb = &xs[kd][kh][kw];
+      for (int vy = 0; vy < K5_TH; ++vy) {
+#pragma unroll 8
+        for (int vx = 0; vx < K5_TW; ++vx) {
+          const float xv = xb[vy * K5_PWP + vx];
+          const float4 ga = *reinterpret_cast<const float4*>(&gs[vy * K5_TW + vx][half * 8]);
+          const float4 gb = *reinterpret_cast<const float4*>(&gs[vy * K5_TW + vx][half * 8 + 4]);
+          acc[0] = fmaf(xv, ga.x, acc[0]); acc[1] = fmaf(xv, ga.y, acc[1]);
+          acc[2] = fmaf(xv, ga.z, acc[2]); acc[3] = fmaf(xv, ga.w, acc[3]);
+          acc[4] = fmaf(xv, gb.x, acc[4]); acc[5] = fmaf(xv, gb.y, acc[5]);
+          acc[6] = fmaf(xv, gb.z, acc[6]); acc[7] = fmaf(xv, gb.w, acc[7]);
+        }
+      }
+    }
+    if (db_thread) {
+      float s = 0.f;
+      for (int v = 0; v < K5_TH * K5_TW; ++v) s += gs[v][tid];
+      dbacc += s;
+    }
+  }
+  if (tap_thread) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int co = cob * K5_COB + half * 8 + c;
+      if (co < a.out.c) part[(((int64_t)chunk * a.out.c + co) * a.in.c + ci) * K5_TAPS + tap] = acc[c];
+    }
+  }
+  if (db_thread) {
+    const int co = cob * K5_COB + tid;
+    if (co < a.out.c) part_db[(int64_t)chunk * a.out.c + co] = dbacc;
+  }
+}
+
+// out[i] = sum over chunks, in chunk order, of part[chunk][i]
+__global__ void __launch_bounds__(256) k5_reduce_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t count, int chunks) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+  for (int c = 0; c < chunks; ++c) s += part[(int64_t)c * count + i];
+  out[i] = s;
+}
+
+struct K5Plan {
+  int tiles_w, tiles_h, tiles_total, chunks, tiles_per_chunk;
+  size_t wp_bytes, part_bytes, partdb_bytes;
+};
+
+size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// cin / cout: channels of the input-side / output-side tensor of the layer
+K5Plan k5_plan(const h3d_tensor* t, int cin, int cout, int op) {
+  K5Plan p{};
+  p.tiles_w = (int)cdiv(t->w, K5_TW);
+  p.tiles_h = (int)cdiv(t->h, K5_TH);
+  const int64_t total = (int64_t)t->n * t->d * p.tiles_w * p.tiles_h;
+  p.tiles_total = (int)total;
+  const int acc_c = op == H3D_OP_BWD_DATA ? cin : cout, loop_c = op == H3D_OP_BWD_DATA ? cout : cin;
+  const int64_t cobs = cdiv(acc_c, K5_COB);
+  p.wp_bytes = up256((size_t)cobs * loop_c * K5_TAPS * K5_COB * sizeof(float));
+  int64_t chunks = cdiv(1024, (int64_t)cin * cdiv(cout, K5_COB));
+  if (chunks > 128) chunks = 128;
+  if (chunks > total) chunks = total;
+  if (chunks < 1) chunks = 1;
+  p.chunks = (int)chunks;
+  p.tiles_per_chunk = (int)cdiv(total, chunks);
+  p.part_bytes = up256((size_t)chunks * cout * cin * K5_TAPS * sizeof(float));
+  p.partdb_bytes = up256((size_t)chunks * cout * sizeof(float));
+  return p;
+}
+
+// the planes a 5-wide window around the interior reaches: inside the volume they must be stored
+bool k5_halo_ok(const h3d_tensor* t) {
+  if (t->d == 0) return true;
+  const int64_t below = t->d_offset, above = t->d_global - t->d_offset - t->d;
+  return (below < 2 ? below : 2) <= t->halo_lo && (above < 2 ? above : 2) <= t->halo_hi;
+}
+
+h3d_status k5_check_pair(void* handle, const h3d_tensor* a, const h3d_tensor* b, const char* what) {
+  H3D_TRY(check_tensor_packed(handle, a, what));
+  H3D_TRY(check_tensor_packed(handle, b, what));
+  if (!same_shard(a, b)) return fail(handle, H3D_EINVAL, "%s: the two tensors are not the same shard (n, d, h, w, offsets, dtype)", what);
+  if (a->c < 1 || b->c < 1) return fail(handle, H3D_EINVAL, "%s: at least one channel on each side", what);
+  if ((int64_t)a->n * cdiv(a->c > b->c ? a->c : b->c, K5_COB) > 65535 || a->d > 65535)
+    return fail(handle, H3D_EUNSUPPORTED, "%s: more than 65535 planes or sample x channel blocks", what);
+  if ((int64_t)a->n * a->d * cdiv(a->h, K5_TH) * cdiv(a->w, K5_TW) >= ((int64_t)1 << 31))
+    return fail(handle, H3D_EUNSUPPORTED, "%s: too many tiles", what);
+  return H3D_OK;
+}
+
+K5Args k5_args(const h3d_tensor* in, const h3d_tensor* out, const h3d_tensor* z, const K5Plan& p, int acc_c, float slope_in,
+               float slope_out) {
+  K5Args a{};
+  a.in = make_geo(in);
+  a.out = make_geo(out);
+  a.zg = z ? make_geo(z) : a.in;
+  const int64_t lo = -(int64_t)in->halo_lo > -in->d_offset ? -(int64_t)in->halo_lo : -in->d_offset;
+  const int64_t hi_s = (int64_t)in->d + in->halo_hi, hi_v = in->d_global - in->d_offset;
+  a.pmin = (int)lo;
+  a.pmax = (int)(hi_s < hi_v ? hi_s : hi_v);
+  if (z) {   // the mask tensor may store fewer planes than the gradient: both must cover what is read
+    const int64_t zlo = -(int64_t)z->halo_lo, zhi = (int64_t)z->d + z->halo_hi;
+    if (a.pmin < zlo) a.pmin = (int)zlo;
+    if (a.pmax > zhi) a.pmax = (int)zhi;
+  }
+  a.tiles_w = p.tiles_w;
+  a.tiles_h = p.tiles_h;
+  a.cobs = (int)cdiv(acc_c, K5_COB);
+  a.slope_in = slope_in;
+  a.slope_out = slope_out;
+  return a;
+}
+
+template <typename T>
+void k5_launch_pack(const void* w, float* wp, int cin, int cout, int transposed, hipStream_t s) {
+  const int loopc = transposed ? cout : cin, accc = transposed ? cin : cout;
+  const int64_t total = cdiv(accc, K5_COB) * (int64_t)loopc * K5_TAPS * K5_COB;
+  hipLaunchKernelGGL((k5_pack_w_kernel<T>), dim3((unsigned)cdiv(total, 256)), dim3(256), 0, s, (const T*)w, wp, cin, cout, transposed, total);
+}
+
+template <typename T>
+void k5_launch_conv(const h3d_tensor* in, const h3d_tensor* z, const float* wp, const float* bias, h3d_tensor* out, const K5Args& a,
+                    hipStream_t s) {
+  const dim3 grid((unsigned)(a.tiles_w * a.tiles_h), (unsigned)in->d, (unsigned)(in->n * a.cobs));
+  if (z)
+    hipLaunchKernelGGL((k5_conv_kernel<T, true>), grid, dim3(256), 0, s, (const T*)in->data, (const T*)z->data, wp, bias, (T*)out->data, a);
+  else
+    hipLaunchKernelGGL((k5_conv_kernel<T, false>), grid, dim3(256), 0, s, (const T*)in->data, (const T*)nullptr, wp, bias, (T*)out->data, a);
+}
+
+template <typename T>
+void k5_launch_bwf(const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* part, float* part_db, const K5Args& a,
+                   const K5Plan& p, hipStream_t s) {
+  const dim3 grid((unsigned)p.chunks, (unsigned)x->c, (unsigned)a.cobs);
+  if (z)
+    hipLaunchKernelGGL((k5_bwf_kernel<T, true>), grid, dim3(256), 0, s, (const T*)x->data, (const T*)dz->data, (const T*)z->data, part,
+                       part_db, a, p.tiles_total, p.tiles_per_chunk);
+  else
+    hipLaunchKernelGGL((k5_bwf_kernel<T, false>), grid, dim3(256), 0, s, (const T*)x->data, (const T*)dz->data, (const T*)nullptr, part,
+                       part_db, a, p.tiles_total, p.tiles_per_chunk);
+}
+
+bool bad_act(int act) { return act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY; }
+
+}  // namespace
+}  // namespace h3d
+
+using namespace h3d;
+
+extern "C" size_t h3d_conv3d_k5_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* z) {
+  if (!handle || !x || !z || x->c < 1 || z->c < 1 || x->n < 0 || x->d < 0 || x->h < 0 || x->w < 0) return 0;
+  const K5Plan p = k5_plan(x, x->c, z->c, op);
+  switch (op) {
+    case H3D_OP_FWD:
+    case H3D_OP_BWD_DATA:
+      return p.wp_bytes;
+    case H3D_OP_BWD_FILTER:
+      return p.part_bytes + p.partdb_bytes;
+    default:
+      return 0;
+  }
+}
+
+extern "C" h3d_status h3d_conv3d_k5_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z, int act,
+                                        float alpha, void* ws, size_t ws_bytes, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (!x || !z) return fail(handle, H3D_EINVAL, "conv3d_k5_fwd: NULL descriptor");
+  H3D_TRY(k5_check_pair(handle, x, z, "conv3d_k5_fwd"));
+  if (!w) return fail(handle, H3D_EINVAL, "conv3d_k5_fwd: NULL weights");
+  if (bad_act(act)) return fail(handle, H3D_EINVAL, "bad activation %d", act);
+  if (!k5_halo_ok(x)) return fail(handle, H3D_EHALO, "conv3d_k5_fwd: x must store two halo planes on every side that is inside the volume");
+  if (!ws || ws_bytes < h3d_conv3d_k5_workspace_bytes(handle, H3D_OP_FWD, x, z)) return fail(handle, H3D_EWORKSPACE, "conv3d_k5_fwd: workspace too small");
+  if ((uintptr_t)ws & 255) return fail(handle, H3D_EINVAL, "conv3d_k5_fwd: workspace must be 256-byte aligned");
+  const K5Plan p = k5_plan(x, x->c, z->c, H3D_OP_FWD);
+  if (p.tiles_total == 0) return H3D_OK;
+  hipStream_t s = (hipStream_t)stream;
+  float* wp = (float*)ws;
+  const K5Args a = k5_args(x, z, nullptr, p, z->c, 1.f, act_slope(act, alpha));
+  if (x->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, x->c, z->c, 0, s); k5_launch_conv<float>(x, nullptr, wp, bias, z, a, s); }
+  else { k5_launch_pack<bf16_t>(w, wp, x->c, z->c, 0, s); k5_launch_conv<bf16_t>(x, nullptr, wp, bias, z, a, s); }
+  return launch_status(handle, "conv3d_k5_fwd");
+}
+
+extern "C" h3d_status h3d_conv3d_k5_bwd_data(void* handle, const h3d_tensor* dz, const h3d_tensor* z, const void* w, h3d_tensor* dx,
+                                             int act, float alpha, void* ws, size_t ws_bytes, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (!dz || !dx) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_data: NULL descriptor");
+  H3D_TRY(k5_check_pair(handle, dx, dz, "conv3d_k5_bwd_data"));
+  if (!w) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_data: NULL weights");
+  if (bad_act(act)) return fail(handle, H3D_EINVAL, "bad activation %d", act);
+  if (act == H3D_ACT_NONE) z = nullptr;
+  if (!k5_halo_ok(dz)) return fail(handle, H3D_EHALO, "conv3d_k5_bwd_data: dz must store two halo planes on every side that is inside the volume");
+  if (z) {
+    H3D_TRY(check_tensor_packed(handle, z, "z"));
+    if (!same_shard(z, dz) || z->c != dz->c) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_data: z and dz shapes differ");
+    if (!k5_halo_ok(z)) return fail(handle, H3D_EHALO, "conv3d_k5_bwd_data: z must store two halo planes on every side that is inside the volume");
+  }
+  if (!ws || ws_bytes < h3d_conv3d_k5_workspace_bytes(handle, H3D_OP_BWD_DATA, dx, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_k5_bwd_data: workspace too small");
+  if ((uintptr_t)ws & 255) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_data: workspace must be 256-byte aligned");
+  const K5Plan p = k5_plan(dx, dx->c, dz->c, H3D_OP_BWD_DATA);
+  if (p.tiles_total == 0) return H3D_OK;
+  hipStream_t s = (hipStream_t)stream;
+  float* wp = (float*)ws;
+  const K5Args a = k5_args(dz, dx, z, p, dx->c, act_slope(act, alpha), 1.f);
+  if (dz->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, dx->c, dz->c, 1, s); k5_launch_conv<float>(dz, z, wp, nullptr, dx, a, s); }
+  else { k5_launch_pack<bf16_t>(w, wp, dx->c, dz->c, 1, s); k5_launch_conv<bf16_t>(dz, z, wp, nullptr, dx, a, s); }
+  return launch_status(handle, "conv3d_k5_bwd_data");
+}
+
+extern "C" h3d_status h3d_conv3d_k5_bwd_filter(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw,
+                                               float* db, int act, float alpha, void* ws, size_t ws_bytes, void* stream) {
+  if (!handle) return H3D_EINVAL;
+  if (!x || !dz) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_filter: NULL descriptor");
+  H3D_TRY(k5_check_pair(handle, x, dz, "conv3d_k5_bwd_filter"));
+  if (!dw) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_filter: NULL dw");
+  if (bad_act(act)) return fail(handle, H3D_EINVAL, "bad activation %d", act);
+  if (act == H3D_ACT_NONE) z = nullptr;
+  if (!k5_halo_ok(x)) return fail(handle, H3D_EHALO, "conv3d_k5_bwd_filter: x must store two halo planes on every side that is inside the volume");
+  if (z) {
+    H3D_TRY(check_tensor_packed(handle, z, "z"));
+    if (!same_shard(z, dz) || z->c != dz->c) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_filter: z and dz shapes differ");
+  }
+  if (!ws || ws_bytes < h3d_conv3d_k5_workspace_bytes(handle, H3D_OP_BWD_FILTER, x, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_k5_bwd_filter: workspace too small");
+  if ((uintptr_t)ws & 255) return fail(handle, H3D_EINVAL, "conv3d_k5_bwd_filter: workspace must be 256-byte aligned");
+  const K5Plan p = k5_plan(x, x->c, dz->c, H3D_OP_BWD_FILTER);
+  hipStream_t s = (hipStream_t)stream;
+  float* part = (float*)ws;
+  float* part_db = (float*)((char*)ws + p.part_bytes);
+  // the mask is read on the interior only: the planes of the saved output that exist do not limit x's window
+  K5Args a = k5_args(x, dz, nullptr, p, dz->c, act_slope(act, alpha), 1.f);
+  if (z) a.zg = make_geo(z);
+  if (x->dtype == H3D_F32) k5_launch_bwf<float>(x, dz, z, part, part_db, a, p, s); else k5_launch_bwf<bf16_t>(x, dz, z, part, part_db, a, p, s);
+  const int64_t nw = (int64_t)dz->c * x->c * K5_TAPS;
+  hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, s, (const float*)part, dw, nw, p.chunks);
+  if (db) hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(dz->c, 256)), dim3(256), 0, s, (const float*)part_db, db, (int64_t)dz->c, p.chunks);
+  return launch_status(handle, "conv3d_k5_bwd_filter");
+}
