@@ -112,6 +112,41 @@ def side_workload(args, seed):
                 return 0
         net = _Xent()
         name = "softmax cross-entropy, forward + gradient, 3 classes on a 64x256x256 shard of a 256^3 volume, bf16"
+    elif args.workload == "k5":
+        # 5x5x5 filters (two halo planes): conv 16 -> 16 on a 32-plane interior shard of a 128^3 volume, the three passes
+        class _K5:
+            def __init__(self):
+                g = torch.Generator(device="cuda")
+                g.manual_seed(seed)
+                rnd = lambda *sh: torch.randn(sh, generator=g, device="cuda")
+                ci = co = 16
+                geo = (2, 2, 32, 128)
+                x = h3d.Slab(rnd(1, ci, 36, 128, 128).to(bf), *geo)
+                z = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
+                dz = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
+                dx = h3d.Slab(torch.empty_like(x.t), *geo)
+                zo = h3d.Slab(torch.empty_like(z.t), *geo)
+                w = (rnd(co, ci, 5, 5, 5) * (2.0 / (125 * ci)) ** 0.5).to(bf)
+                b = torch.zeros(co, device="cuda")
+                dw, db = torch.empty((co, ci, 5, 5, 5), device="cuda"), torch.empty(co, device="cuda")
+                ws = h3d.Workspace()
+                fl = 2 * 125 * ci * co * 32 * 128 * 128
+                nb = 2 * 36 * 128 * 128 * 2 * 16
+                self.keep = (x, z, dz, dx, zo, w, b, dw, db)
+                self.ops = [
+                    {"name": "k5_fwd", "fn": lambda: h3d.conv3d_k5_fwd(x, w, b, zo, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb},
+                    {"name": "k5_bwd_data", "fn": lambda: h3d.conv3d_k5_bwd_data(dz, z, w, dx, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
+                    {"name": "k5_bwd_filter", "fn": lambda: h3d.conv3d_k5_bwd_filter(x, dz, z, dw, db, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
+                ]
+
+            def step(self):
+                for o in self.ops:
+                    o["fn"]()
+
+            def conv_flops(self):
+                return sum(o["flops"] for o in self.ops)
+        net = _K5()
+        name = "5x5x5 convolution 16->16, 32-plane interior shard (+2 halo planes per side) of a 128^3 volume, bf16 storage, fp32 vector-ALU arithmetic, three passes"
     elif args.workload == "late256":
         net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
         name = "late layer N=8, 256->256, 16^3 bf16"
@@ -202,7 +237,7 @@ def main():
     ap.add_argument("--calibrate", action="store_true", help="print what this device sustains under the simplest load: a register-only "
                     "bf16 MFMA loop (both tile shapes), a streaming read of 1 GiB and of 64 MiB, and a plain copy")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "xent", "shard512", "unet", "late256", "split256", "bn"],
+    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "xent", "k5", "shard512", "unet", "late256", "split256", "bn"],
                     help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
                          "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
     args = ap.parse_args()
