@@ -7,6 +7,12 @@
 //     one voxel and 16 accumulators, and the 125 x 16 weights of the step come as fp32 from a packed copy whose
 //     addresses are the same for the whole workgroup (scalar loads, no LDS traffic).  Backward-data is the same
 //     kernel on g = dz * act'(z) (mask applied while staging) with the filter reversed and transposed.
+//     With bf16 storage the same two passes run on the matrix cores instead (k5_mfma_kernel): v_mfma_f32_32x32x16_bf16
+//     with 32 output channels on the rows, 32 voxels of an output row on the columns and 16 input channels of one tap
+//     as K; a workgroup owns 16 rows x 32 columns of one output plane, a wavefront 4 of the rows (4 accumulators share
+//     every weight fragment); per (16-channel chunk, kd) the 20 x 36 input patch of that plane is transposed into LDS
+//     channel-innermost (32 bytes per voxel: one 16-byte read per lane is a B fragment at any of the 25 shifts), the
+//     weight fragments come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] straight from memory.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
 //     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
 //     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).
@@ -195,6 +201,116 @@ __global__ void __launch_bounds__(256) k5_reduce_kernel(const float* __restrict_
   out[i] = s;
 }
 
+// ---- matrix-core form of forward / backward-data (bf16 storage) ----
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int KM_TH = 16, KM_TW = 32, KM_PH = KM_TH + 4, KM_PW = KM_TW + 4;
+constexpr int KM_COB = 32, KM_CIB = 16;
+
+// wpk[cb][cic][t][c][e] bf16: accumulated channel 32 cb + c, looped channel 16 cic + e (zero past the real counts);
+// forward: w[co = acc][ci = loop][t];  backward-data: w[co = loop][ci = acc][124 - t].
+__global__ void __launch_bounds__(256) k5_pack_w_mfma_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wpk, int cin, int cout,
+                                                             int transposed, int cics, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int e = (int)(i % KM_CIB), c = (int)((i / KM_CIB) % KM_COB), t = (int)((i / (KM_CIB * KM_COB)) % K5_TAPS);
+  const int cic = (int)((i / ((int64_t)KM_CIB * KM_COB * K5_TAPS)) % cics), cb = (int)(i / ((int64_t)KM_CIB * KM_COB * K5_TAPS * cics));
+  const int ca = cb * KM_COB + c, cl = cic * KM_CIB + e;
+  const int loopc = transposed ? cout : cin, accc = transposed ? cin : cout;
+  bf16_t v = 0;
+  if (ca < accc && cl < loopc) {
+    const int co = transposed ? cl : ca, ci = transposed ? ca : cl, tt = transposed ? K5_TAPS - 1 - t : t;
+    v = w[((int64_t)co * cin + ci) * K5_TAPS + tt];
+  }
+  wpk[i] = v;
+}
+
+// grid (tiles_w * tiles_h, d, n * cobs) with 16 x 32 tiles and blocks of 32 accumulated channels
+template <bool MASK>
+__global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ zm,
+                                                      const bf16_t* __restrict__ wpk, const float* __restrict__ bias,
+                                                      bf16_t* __restrict__ out, K5Args a, int cics) {
+  __shared__ __attribute__((aligned(16))) bf16_t xs[KM_PH * KM_PW * KM_CIB];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lc = lane & 31, lh = lane >> 5;
+  const int tw = blockIdx.x % a.tiles_w, th = blockIdx.x / a.tiles_w;
+  const int p = blockIdx.y;
+  const int n = blockIdx.z / a.cobs, cob = blockIdx.z % a.cobs;
+  const int h0 = th * KM_TH, w0 = tw * KM_TW;
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int cic = 0; cic < cics; ++cic) {
+    for (int kd = 0; kd < 5; ++kd) {
+      const int pp = p + kd - 2;
+      if (pp < a.pmin || pp >= a.pmax) continue;   // a plane outside the volume adds nothing (same for the whole workgroup)
+      __syncthreads();
+      for (int pos = tid; pos < KM_PH * KM_PW; pos += 256) {
+        const int r = pos / KM_PW, c = pos % KM_PW;
+        const int hh = h0 + r - 2, ww = w0 + c - 2;
+        uint32_t pk[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pk[e] = 0u;
+        if (hh >= 0 && hh < a.in.h && ww >= 0 && ww < a.in.w) {
+          const int64_t sp = (int64_t)hh * a.in.w + ww;
+          const bf16_t* src = in + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane + sp;
+          const bf16_t* zsrc = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(pp + a.zg.hlo) * a.zg.plane + sp : nullptr;
+#pragma unroll
+          for (int e = 0; e < KM_CIB; ++e) {
+            const int ci = cic * KM_CIB + e;
+            uint32_t v = 0u;
+            if (ci < a.in.c) {
+              v = src[(int64_t)ci * a.in.cstride];
+              if (MASK) {
+                const float zv = bf16_to_f32(zsrc[(int64_t)ci * a.zg.cstride]);
+                if (!(zv > 0.f)) v = f32_to_bf16(bf16_to_f32((bf16_t)v) * a.slope_in);
+              }
+            }
+            pk[e >> 1] |= v << (16 * (e & 1));
+          }
+        }
+        uint4* dst = reinterpret_cast<uint4*>(xs + pos * KM_CIB);
+        dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+      }
+      __syncthreads();
+      const bf16_t* wt = wpk + (((int64_t)cob * cics + cic) * K5_TAPS + kd * 25) * (KM_COB * KM_CIB);
+#pragma unroll
+      for (int kh = 0; kh < 5; ++kh) {
+#pragma unroll
+        for (int kw = 0; kw < 5; ++kw) {
+          const bf16x8 A = *reinterpret_cast<const bf16x8*>(wt + ((kh * 5 + kw) * KM_COB + lc) * KM_CIB + lh * 8);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int row = wave * 4 + i;
+            const bf16x8 B = *reinterpret_cast<const bf16x8*>(xs + ((row + kh) * KM_PW + lc + kw) * KM_CIB + lh * 8);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[i], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  // accumulator element r of lane (lc, lh): column = voxel lc, row = channel 8 (r / 4) + 4 lh + r % 4
+  const int ww = w0 + lc;
+  if (ww >= a.out.w) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int hh = h0 + wave * 4 + i;
+    if (hh >= a.out.h) continue;
+    bf16_t* o = out + (int64_t)n * a.out.nstride + (int64_t)(p + a.out.hlo) * a.out.plane + (int64_t)hh * a.out.w + ww;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = cob * KM_COB + 8 * (r >> 2) + 4 * lh + (r & 3);
+      if (co < a.out.c) {
+        float v = acc[i][r] + (bias ? bias[co] : 0.f);
+        if (!(v > 0.f)) v *= a.slope_out;
+        o[(int64_t)co * a.out.cstride] = f32_to_bf16(v);
+      }
+    }
+  }
+}
+
 struct K5Plan {
   int tiles_w, tiles_h, tiles_total, chunks, tiles_per_chunk;
   size_t wp_bytes, part_bytes, partdb_bytes;
@@ -211,7 +327,9 @@ K5Plan k5_plan(const h3d_tensor* t, int cin, int cout, int op) {
   p.tiles_total = (int)total;
   const int acc_c = op == H3D_OP_BWD_DATA ? cin : cout, loop_c = op == H3D_OP_BWD_DATA ? cout : cin;
   const int64_t cobs = cdiv(acc_c, K5_COB);
-  p.wp_bytes = up256((size_t)cobs * loop_c * K5_TAPS * K5_COB * sizeof(float));
+  const size_t alu_bytes = (size_t)cobs * loop_c * K5_TAPS * K5_COB * sizeof(float);
+  const size_t mfma_bytes = (size_t)cdiv(acc_c, KM_COB) * cdiv(loop_c, KM_CIB) * K5_TAPS * KM_COB * KM_CIB * sizeof(bf16_t);
+  p.wp_bytes = up256(alu_bytes > mfma_bytes ? alu_bytes : mfma_bytes);   // either form of the packed filter fits
   int64_t chunks = cdiv(1024, (int64_t)cin * cdiv(cout, K5_COB));
   if (chunks > 128) chunks = 128;
   if (chunks > total) chunks = total;
@@ -294,6 +412,27 @@ void k5_launch_bwf(const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* 
                        part_db, a, p.tiles_total, p.tiles_per_chunk);
 }
 
+// bf16 forward / backward-data on the matrix cores: `in` is the staged tensor, `out` the written one
+void k5_launch_mfma(const h3d_tensor* in, const h3d_tensor* z, const void* w, int cin, int cout, int transposed, const float* bias,
+                    h3d_tensor* out, K5Args a, void* ws, hipStream_t s) {
+  const int loopc = transposed ? cout : cin, accc = transposed ? cin : cout;
+  const int cics = (int)cdiv(loopc, KM_CIB), cobs = (int)cdiv(accc, KM_COB);
+  const int64_t total = (int64_t)cobs * cics * K5_TAPS * KM_COB * KM_CIB;
+  bf16_t* wpk = (bf16_t*)ws;
+  hipLaunchKernelGGL(k5_pack_w_mfma_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)w, wpk, cin, cout, transposed,
+                     cics, total);
+  a.tiles_w = (int)cdiv(in->w, KM_TW);
+  a.tiles_h = (int)cdiv(in->h, KM_TH);
+  a.cobs = cobs;
+  const dim3 grid((unsigned)(a.tiles_w * a.tiles_h), (unsigned)in->d, (unsigned)(in->n * cobs));
+  if (z)
+    hipLaunchKernelGGL((k5_mfma_kernel<true>), grid, dim3(256), 0, s, (const bf16_t*)in->data, (const bf16_t*)z->data, (const bf16_t*)wpk, bias,
+                       (bf16_t*)out->data, a, cics);
+  else
+    hipLaunchKernelGGL((k5_mfma_kernel<false>), grid, dim3(256), 0, s, (const bf16_t*)in->data, (const bf16_t*)nullptr, (const bf16_t*)wpk, bias,
+                       (bf16_t*)out->data, a, cics);
+}
+
 bool bad_act(int act) { return act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY; }
 
 }  // namespace
@@ -331,7 +470,7 @@ extern "C" h3d_status h3d_conv3d_k5_fwd(void* handle, const h3d_tensor* x, const
   float* wp = (float*)ws;
   const K5Args a = k5_args(x, z, nullptr, p, z->c, 1.f, act_slope(act, alpha));
   if (x->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, x->c, z->c, 0, s); k5_launch_conv<float>(x, nullptr, wp, bias, z, a, s); }
-  else { k5_launch_pack<bf16_t>(w, wp, x->c, z->c, 0, s); k5_launch_conv<bf16_t>(x, nullptr, wp, bias, z, a, s); }
+  else k5_launch_mfma(x, nullptr, w, x->c, z->c, 0, bias, z, a, ws, s);
   return launch_status(handle, "conv3d_k5_fwd");
 }
 
@@ -357,7 +496,7 @@ extern "C" h3d_status h3d_conv3d_k5_bwd_data(void* handle, const h3d_tensor* dz,
   float* wp = (float*)ws;
   const K5Args a = k5_args(dz, dx, z, p, dx->c, act_slope(act, alpha), 1.f);
   if (dz->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, dx->c, dz->c, 1, s); k5_launch_conv<float>(dz, z, wp, nullptr, dx, a, s); }
-  else { k5_launch_pack<bf16_t>(w, wp, dx->c, dz->c, 1, s); k5_launch_conv<bf16_t>(dz, z, wp, nullptr, dx, a, s); }
+  else k5_launch_mfma(dz, z, w, dx->c, dz->c, 1, nullptr, dx, a, ws, s);
   return launch_status(handle, "conv3d_k5_bwd_data");
 }
 
