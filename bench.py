@@ -113,13 +113,13 @@ def side_workload(args, seed):
         net = _Xent()
         name = "softmax cross-entropy, forward + gradient, 3 classes on a 64x256x256 shard of a 256^3 volume, bf16"
     elif args.workload == "k5":
-        # 5x5x5 filters (two halo planes): conv 16 -> 16 on a 32-plane interior shard of a 128^3 volume, the three passes
+        # 5x5x5 filters (two halo planes): conv 32 -> 32 on a 32-plane interior shard of a 128^3 volume, the three passes
         class _K5:
             def __init__(self):
                 g = torch.Generator(device="cuda")
                 g.manual_seed(seed)
                 rnd = lambda *sh: torch.randn(sh, generator=g, device="cuda")
-                ci = co = 16
+                ci = co = 32
                 geo = (2, 2, 32, 128)
                 x = h3d.Slab(rnd(1, ci, 36, 128, 128).to(bf), *geo)
                 z = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
@@ -131,7 +131,7 @@ def side_workload(args, seed):
                 dw, db = torch.empty((co, ci, 5, 5, 5), device="cuda"), torch.empty(co, device="cuda")
                 ws = h3d.Workspace()
                 fl = 2 * 125 * ci * co * 32 * 128 * 128
-                nb = 2 * 36 * 128 * 128 * 2 * 16
+                nb = 2 * 36 * 128 * 128 * 2 * ci
                 self.keep = (x, z, dz, dx, zo, w, b, dw, db)
                 self.ops = [
                     {"name": "k5_fwd", "fn": lambda: h3d.conv3d_k5_fwd(x, w, b, zo, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb},
@@ -146,7 +146,7 @@ def side_workload(args, seed):
             def conv_flops(self):
                 return sum(o["flops"] for o in self.ops)
         net = _K5()
-        name = "5x5x5 convolution 16->16, 32-plane interior shard (+2 halo planes per side) of a 128^3 volume, bf16 storage, fp32 vector-ALU arithmetic, three passes"
+        name = "5x5x5 convolution 32->32, 32-plane interior shard (+2 halo planes per side) of a 128^3 volume, bf16, three passes"
     elif args.workload == "late256":
         net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
         name = "late layer N=8, 256->256, 16^3 bf16"

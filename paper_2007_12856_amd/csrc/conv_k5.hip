@@ -10,7 +10,7 @@
 //     With bf16 storage the same two passes run on the matrix cores instead (k5_mfma_kernel): v_mfma_f32_32x32x16_bf16
 //     with 32 output channels on the rows, 32 voxels of an output row on the columns and 16 input channels of one tap
 //     as K; a workgroup owns 16 rows x 32 columns of one output plane, a wavefront 4 of the rows (4 accumulators share
-//     every weight fragment); per (16-channel chunk, kd) the 20 x 36 input patch of that plane is transposed into LDS
+//     every weight fragment, and the 8 patch rows they read per kw feed 20 products); per (16-channel chunk, kd) the 20 x 36 input patch of that plane is transposed into LDS
 //     channel-innermost (32 bytes per voxel: one 16-byte read per lane is a B fragment at any of the 25 shifts), the
 //     weight fragments come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] straight from memory.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
@@ -241,53 +241,74 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  for (int cic = 0; cic < cics; ++cic) {
-    for (int kd = 0; kd < 5; ++kd) {
-      const int pp = p + kd - 2;
-      if (pp < a.pmin || pp >= a.pmax) continue;   // a plane outside the volume adds nothing (same for the whole workgroup)
-      __syncthreads();
-      for (int pos = tid; pos < KM_PH * KM_PW; pos += 256) {
-        const int r = pos / KM_PW, c = pos % KM_PW;
-        const int hh = h0 + r - 2, ww = w0 + c - 2;
+  // A stage is one (16-channel chunk, kd) pair.  The values of stage s + 1 are loaded into registers before the
+  // multiplications of stage s start and go to LDS after them, so the memory latency hides behind the matrix work.
+  constexpr int ROUNDS = (KM_PH * KM_PW + 255) / 256;
+  bf16_t raw[ROUNDS][KM_CIB];
+  bf16_t zraw[MASK ? ROUNDS : 1][KM_CIB];
+  const int stages = cics * 5;
+  auto load_stage = [&](int s) {
+    const int cic = s / 5, pp = p + s % 5 - 2;
+    const bool plane_ok = pp >= a.pmin && pp < a.pmax;
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+      const int pos = tid + 256 * q;
+      const int r = pos / KM_PW, c = pos % KM_PW;
+      const int hh = h0 + r - 2, ww = w0 + c - 2;
+      const bool ok = plane_ok && pos < KM_PH * KM_PW && hh >= 0 && hh < a.in.h && ww >= 0 && ww < a.in.w;
+      const int64_t sp = (int64_t)hh * a.in.w + ww;
+      const bf16_t* src = in + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane + sp;
+      const bf16_t* zsrc = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(pp + a.zg.hlo) * a.zg.plane + sp : nullptr;
+#pragma unroll
+      for (int e = 0; e < KM_CIB; ++e) {
+        const int ci = cic * KM_CIB + e;
+        const bool okc = ok && ci < a.in.c;
+        raw[q][e] = okc ? src[(int64_t)ci * a.in.cstride] : (bf16_t)0;
+        if (MASK) zraw[q][e] = okc ? zsrc[(int64_t)ci * a.zg.cstride] : (bf16_t)0x3f80;
+      }
+    }
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+      const int pos = tid + 256 * q;
+      if (pos < KM_PH * KM_PW) {
         uint32_t pk[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) pk[e] = 0u;
-        if (hh >= 0 && hh < a.in.h && ww >= 0 && ww < a.in.w) {
-          const int64_t sp = (int64_t)hh * a.in.w + ww;
-          const bf16_t* src = in + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane + sp;
-          const bf16_t* zsrc = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(pp + a.zg.hlo) * a.zg.plane + sp : nullptr;
 #pragma unroll
-          for (int e = 0; e < KM_CIB; ++e) {
-            const int ci = cic * KM_CIB + e;
-            uint32_t v = 0u;
-            if (ci < a.in.c) {
-              v = src[(int64_t)ci * a.in.cstride];
-              if (MASK) {
-                const float zv = bf16_to_f32(zsrc[(int64_t)ci * a.zg.cstride]);
-                if (!(zv > 0.f)) v = f32_to_bf16(bf16_to_f32((bf16_t)v) * a.slope_in);
-              }
-            }
-            pk[e >> 1] |= v << (16 * (e & 1));
+        for (int e = 0; e < KM_CIB; ++e) {
+          uint32_t v = raw[q][e];
+          if (MASK) {
+            if (!(bf16_to_f32(zraw[q][e]) > 0.f)) v = f32_to_bf16(bf16_to_f32((bf16_t)v) * a.slope_in);
           }
+          pk[e >> 1] |= v << (16 * (e & 1));
         }
         uint4* dst = reinterpret_cast<uint4*>(xs + pos * KM_CIB);
         dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
       }
-      __syncthreads();
-      const bf16_t* wt = wpk + (((int64_t)cob * cics + cic) * K5_TAPS + kd * 25) * (KM_COB * KM_CIB);
+    }
+  };
+  load_stage(0);
+  for (int s = 0; s < stages; ++s) {
+    __syncthreads();          // the multiplications of the stage before have read the patch
+    store_stage();
+    __syncthreads();
+    if (s + 1 < stages) load_stage(s + 1);
+    const bf16_t* wt = wpk + (((int64_t)cob * cics + s / 5) * K5_TAPS + (s % 5) * 25) * (KM_COB * KM_CIB);
+    // the 4 output rows of the wavefront and the 5 kh taps meet 8 patch rows: per kw, 8 fragment reads feed 20 products
+#pragma unroll 1
+    for (int kw = 0; kw < 5; ++kw) {
+      bf16x8 B[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        B[r] = *reinterpret_cast<const bf16x8*>(xs + ((wave * 4 + r) * KM_PW + lc + kw) * KM_CIB + lh * 8);
 #pragma unroll
       for (int kh = 0; kh < 5; ++kh) {
+        const bf16x8 A = *reinterpret_cast<const bf16x8*>(wt + ((kh * 5 + kw) * KM_COB + lc) * KM_CIB + lh * 8);
 #pragma unroll
-        for (int kw = 0; kw < 5; ++kw) {
-          const bf16x8 A = *reinterpret_cast<const bf16x8*>(wt + ((kh * 5 + kw) * KM_COB + lc) * KM_CIB + lh * 8);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int row = wave * 4 + i;
-            const bf16x8 B = *reinterpret_cast<const bf16x8*>(xs + ((row + kh) * KM_PW + lc + kw) * KM_CIB + lh * 8);
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[i], 0, 0, 0);
-          }
-        }
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[i + kh], acc[i], 0, 0, 0);
       }
     }
   }
