@@ -332,8 +332,158 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
   }
 }
 
+// ---- matrix-core form of backward-filter (bf16 storage, W a multiple of 8, 16-byte aligned tensors) ----
+// dw[co][ci][tap] is a contraction over voxels: rows = 32 output channels (A = g), columns = 32 input channels
+// (B = x shifted by the tap), K = 16 consecutive voxels of a row; both operands keep NCDHW (8 consecutive W voxels
+// are one 16-byte piece).  A workgroup of five wavefronts owns (chunk of 32 x 128 tiles, kd, 32 co, 32 ci); wavefront
+// kh holds the five kw accumulators of its (kd, kh).  It walks down the rows of a tile: per output row the g row and
+// one new x row go to LDS (x rows in a ring of five: output row t and tap kh read x row t + kh); for 16 voxels the x
+// window of 12 elements is read once (4 + 16 + 4 bytes) and the odd shifts are made from it with v_alignbit.
+constexpr int KB_TH = 32, KB_TW = 128, KB_C = 32;
+constexpr int KB_XW = 152, KB_GW = 136;          // row pitches (elements): 76 and 68 dwords, conflict-free 16-byte reads
+constexpr int KB_XG = KB_XW / 8, KB_GG = KB_TW / 8;
+constexpr int KB_THREADS = 320;
+
+template <bool MASK>
+__global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
+                                                                 const bf16_t* __restrict__ zm, float* __restrict__ part,
+                                                                 float* __restrict__ part_db, K5Args a, int units_total,
+                                                                 int units_per_chunk, int cibs) {
+  __shared__ __attribute__((aligned(16))) bf16_t xr[5 * KB_C * KB_XW];
+  __shared__ __attribute__((aligned(16))) bf16_t gr[KB_C * KB_GW];
+  const int tid = threadIdx.x, kh = tid >> 6, lane = tid & 63, lc = lane & 31, lh = lane >> 5;
+  const int chunk = blockIdx.x, kd = blockIdx.y;
+  const int cob = blockIdx.z / cibs, cib = blockIdx.z % cibs;
+  const bool db_wave = kd == 2 && cib == 0 && kh == 2;
+  f32x16 acc[5];
+#pragma unroll
+  for (int k = 0; k < 5; ++k)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[k][r] = 0.f;
+  float dbacc = 0.f;
+  const int tiles_pl = a.tiles_w * a.tiles_h;
+  const int u_lo = chunk * units_per_chunk;
+  const int u_hi = min(u_lo + units_per_chunk, units_total);
+  for (int unit = u_lo; unit < u_hi; ++unit) {
+    const int wt = unit % a.tiles_w, ht = (unit / a.tiles_w) % a.tiles_h;
+    const int p = (unit / tiles_pl) % a.in.d, n = unit / (tiles_pl * a.in.d);
+    const int pp = p + kd - 2;
+    if (pp < a.pmin || pp >= a.pmax) continue;   // x is zero on that plane (same decision for the whole workgroup)
+    const int h0 = ht * KB_TH, w0 = wt * KB_TW;
+    const int rows = min(KB_TH, a.in.h - h0);
+    const bf16_t* xb = x + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane;
+    const bf16_t* gb = dz + (int64_t)n * a.out.nstride + (int64_t)(p + a.out.hlo) * a.out.plane;
+    const bf16_t* zb = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(p + a.zg.hlo) * a.zg.plane : nullptr;
+    uint4 xq0, xq1, gq0, gq1, zq0 = make_uint4(0u, 0u, 0u, 0u), zq1 = zq0;
+    // x row h0 - 2 + j, columns w0 - 8 .. w0 + 143, as 19 pieces of 8 per channel; piece idx of the row
+    auto load_x1 = [&](int j, int idx) -> uint4 {
+      const int hh = h0 - 2 + j;
+      const int cl = idx / KB_XG, g = idx % KB_XG;
+      const int ci = cib * KB_C + cl, col = w0 - 8 + 8 * g;
+      const bool ok = idx < KB_C * KB_XG && hh >= 0 && hh < a.in.h && ci < a.in.c && col >= 0 && col < a.in.w;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (ok) v = *reinterpret_cast<const uint4*>(xb + (int64_t)ci * a.in.cstride + (int64_t)hh * a.in.w + col);
+      return v;
+    };
+    auto store_x1 = [&](int j, int idx, const uint4& v) {
+      if (idx < KB_C * KB_XG) *reinterpret_cast<uint4*>(xr + ((j % 5) * KB_C + idx / KB_XG) * KB_XW + 8 * (idx % KB_XG)) = v;
+    };
+    // g row h0 + t, columns w0 .. w0 + 127, 16 pieces per channel
+    auto load_g1 = [&](int t, int idx, uint4& gv, uint4& zv) {
+      const int hh = h0 + t;
+      const int cl = idx / KB_GG, g = idx % KB_GG;
+      const int co = cob * KB_C + cl, col = w0 + 8 * g;
+      const bool ok = idx < KB_C * KB_GG && hh < a.out.h && co < a.out.c && col < a.out.w;
+      const int64_t sp = (int64_t)hh * a.out.w + col;
+      gv = make_uint4(0u, 0u, 0u, 0u);
+      if (ok) gv = *reinterpret_cast<const uint4*>(gb + (int64_t)co * a.out.cstride + sp);
+      if (MASK) {
+        zv = make_uint4(0u, 0u, 0u, 0u);
+        if (ok) zv = *reinterpret_cast<const uint4*>(zb + (int64_t)co * a.zg.cstride + sp);
+      }
+    };
+    auto mask2 = [&](uint32_t gd, uint32_t zd) -> uint32_t {
+      uint32_t lo = gd & 0xffffu, hi = gd >> 16;
+      if (!(bf16_to_f32((bf16_t)(zd & 0xffffu)) > 0.f)) lo = f32_to_bf16(bf16_to_f32((bf16_t)lo) * a.slope_in);
+      if (!(bf16_to_f32((bf16_t)(zd >> 16)) > 0.f)) hi = f32_to_bf16(bf16_to_f32((bf16_t)hi) * a.slope_in);
+      return lo | (hi << 16);
+    };
+    auto store_g1 = [&](int idx, uint4 v, const uint4& zv) {
+      if (idx < KB_C * KB_GG) {
+        if (MASK) v = make_uint4(mask2(v.x, zv.x), mask2(v.y, zv.y), mask2(v.z, zv.z), mask2(v.w, zv.w));
+        *reinterpret_cast<uint4*>(gr + (idx / KB_GG) * KB_GW + 8 * (idx % KB_GG)) = v;
+      }
+    };
+    auto load_x = [&](int j) { xq0 = load_x1(j, tid); xq1 = load_x1(j, tid + KB_THREADS); };
+    auto store_x = [&](int j) { store_x1(j, tid, xq0); store_x1(j, tid + KB_THREADS, xq1); };
+    auto load_g = [&](int t) { load_g1(t, tid, gq0, zq0); load_g1(t, tid + KB_THREADS, gq1, zq1); };
+    auto store_g = [&]() { store_g1(tid, gq0, zq0); store_g1(tid + KB_THREADS, gq1, zq1); };
+    __syncthreads();                 // the tile before has been multiplied
+#pragma unroll 1
+    for (int j = 0; j < 4; ++j) {
+      load_x(j);
+      store_x(j);
+    }
+    load_x(4);
+    load_g(0);
+    for (int t = 0; t < rows; ++t) {
+      __syncthreads();               // row t - 1 has been multiplied: its oldest x row and the g row are free
+      store_x(t + 4);
+      store_g();
+      __syncthreads();
+      if (t + 1 < rows) {            // in flight during the multiplications
+        load_x(t + 5);
+        load_g(t + 1);
+      }
+      const bf16_t* xrow = xr + (((t + kh) % 5) * KB_C + lc) * KB_XW;
+      const bf16_t* grow = gr + lc * KB_GW;
+#pragma unroll
+      for (int ks = 0; ks < KB_TW / 16; ++ks) {
+        if (w0 + 16 * ks >= a.in.w) break;
+        const int e0 = 16 * ks + 8 * lh;
+        const bf16x8 A = *reinterpret_cast<const bf16x8*>(grow + e0);
+        const uint4 q = *reinterpret_cast<const uint4*>(xrow + 8 + e0);
+        const uint32_t dm = *reinterpret_cast<const uint32_t*>(xrow + 6 + e0);
+        const uint32_t dp = *reinterpret_cast<const uint32_t*>(xrow + 16 + e0);
+        // dwords dm, q.x .. q.w, dp hold elements -2 .. 9 around the piece; o* are the dwords that start at an odd element
+        const uint32_t o0 = __builtin_amdgcn_alignbit(q.x, dm, 16), o1 = __builtin_amdgcn_alignbit(q.y, q.x, 16);
+        const uint32_t o2 = __builtin_amdgcn_alignbit(q.z, q.y, 16), o3 = __builtin_amdgcn_alignbit(q.w, q.z, 16);
+        const uint32_t o4 = __builtin_amdgcn_alignbit(dp, q.w, 16);
+        const uint4 b0 = make_uint4(dm, q.x, q.y, q.z), b1 = make_uint4(o0, o1, o2, o3);
+        const uint4 b2 = q, b3 = make_uint4(o1, o2, o3, o4);
+        const uint4 b4 = make_uint4(q.y, q.z, q.w, dp);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b0), acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b1), acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b2), acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b3), acc[3], 0, 0, 0);
+        acc[4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b4), acc[4], 0, 0, 0);
+        if (db_wave) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dbacc += (float)A[e];
+        }
+      }
+    }
+  }
+  // accumulator element r of lane (lc, lh): column = input channel lc, row = output channel 8 (r / 4) + 4 lh + r % 4
+  const int ci = cib * KB_C + lc;
+#pragma unroll
+  for (int kw = 0; kw < 5; ++kw)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = cob * KB_C + 8 * (r >> 2) + 4 * lh + (r & 3);
+      if (co < a.out.c && ci < a.in.c)
+        part[(((int64_t)chunk * a.out.c + co) * a.in.c + ci) * K5_TAPS + kd * 25 + kh * 5 + kw] = acc[kw][r];
+    }
+  if (db_wave) {
+    const float v = dbacc + __shfl_xor(dbacc, 32, 64);
+    const int co = cob * KB_C + lc;
+    if (lh == 0 && co < a.out.c) part_db[(int64_t)chunk * a.out.c + co] = v;
+  }
+}
+
 struct K5Plan {
   int tiles_w, tiles_h, tiles_total, chunks, tiles_per_chunk;
+  int bf_tiles_w, bf_tiles_h, bf_units, bf_chunks, bf_units_per_chunk;   // matrix-core backward-filter
   size_t wp_bytes, part_bytes, partdb_bytes;
 };
 
@@ -357,8 +507,19 @@ K5Plan k5_plan(const h3d_tensor* t, int cin, int cout, int op) {
   if (chunks < 1) chunks = 1;
   p.chunks = (int)chunks;
   p.tiles_per_chunk = (int)cdiv(total, chunks);
-  p.part_bytes = up256((size_t)chunks * cout * cin * K5_TAPS * sizeof(float));
-  p.partdb_bytes = up256((size_t)chunks * cout * sizeof(float));
+  p.bf_tiles_w = (int)cdiv(t->w, KB_TW);
+  p.bf_tiles_h = (int)cdiv(t->h, KB_TH);
+  const int64_t units = (int64_t)t->n * t->d * p.bf_tiles_w * p.bf_tiles_h;
+  p.bf_units = (int)units;
+  int64_t bf_chunks = cdiv(2048, 5 * cdiv(cin, KB_C) * cdiv(cout, KB_C));
+  if (bf_chunks > 128) bf_chunks = 128;
+  if (bf_chunks > units) bf_chunks = units;
+  if (bf_chunks < 1) bf_chunks = 1;
+  p.bf_chunks = (int)bf_chunks;
+  p.bf_units_per_chunk = (int)cdiv(units, bf_chunks);
+  const int64_t most = chunks > bf_chunks ? chunks : bf_chunks;   // either form of the partial sums fits
+  p.part_bytes = up256((size_t)most * cout * cin * K5_TAPS * sizeof(float));
+  p.partdb_bytes = up256((size_t)most * cout * sizeof(float));
   return p;
 }
 
@@ -543,9 +704,27 @@ extern "C" h3d_status h3d_conv3d_k5_bwd_filter(void* handle, const h3d_tensor* x
   // the mask is read on the interior only: the planes of the saved output that exist do not limit x's window
   K5Args a = k5_args(x, dz, nullptr, p, dz->c, act_slope(act, alpha), 1.f);
   if (z) a.zg = make_geo(z);
-  if (x->dtype == H3D_F32) k5_launch_bwf<float>(x, dz, z, part, part_db, a, p, s); else k5_launch_bwf<bf16_t>(x, dz, z, part, part_db, a, p, s);
+  const bool aligned16 = (((uintptr_t)x->data | (uintptr_t)dz->data | (uintptr_t)(z ? z->data : nullptr)) & 15) == 0;
+  int chunks = p.chunks;
+  if (x->dtype == H3D_F32) {
+    k5_launch_bwf<float>(x, dz, z, part, part_db, a, p, s);
+  } else if (x->w % 8 == 0 && aligned16) {   // matrix cores: whole 16-byte pieces of 8 voxels
+    chunks = p.bf_chunks;
+    a.tiles_w = p.bf_tiles_w;
+    a.tiles_h = p.bf_tiles_h;
+    const int cibs = (int)cdiv(x->c, KB_C), cobs = (int)cdiv(dz->c, KB_C);
+    const dim3 grid((unsigned)chunks, 5u, (unsigned)(cobs * cibs));
+    if (z)
+      hipLaunchKernelGGL((k5_bwf_mfma_kernel<true>), grid, dim3(KB_THREADS), 0, s, (const bf16_t*)x->data, (const bf16_t*)dz->data,
+                         (const bf16_t*)z->data, part, part_db, a, p.bf_units, p.bf_units_per_chunk, cibs);
+    else
+      hipLaunchKernelGGL((k5_bwf_mfma_kernel<false>), grid, dim3(KB_THREADS), 0, s, (const bf16_t*)x->data, (const bf16_t*)dz->data,
+                         (const bf16_t*)nullptr, part, part_db, a, p.bf_units, p.bf_units_per_chunk, cibs);
+  } else {
+    k5_launch_bwf<bf16_t>(x, dz, z, part, part_db, a, p, s);
+  }
   const int64_t nw = (int64_t)dz->c * x->c * K5_TAPS;
-  hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, s, (const float*)part, dw, nw, p.chunks);
-  if (db) hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(dz->c, 256)), dim3(256), 0, s, (const float*)part_db, db, (int64_t)dz->c, p.chunks);
+  hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, s, (const float*)part, dw, nw, chunks);
+  if (db) hipLaunchKernelGGL(k5_reduce_kernel, dim3((unsigned)cdiv(dz->c, 256)), dim3(256), 0, s, (const float*)part_db, db, (int64_t)dz->c, chunks);
   return launch_status(handle, "conv3d_k5_bwd_filter");
 }

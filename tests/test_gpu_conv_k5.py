@@ -19,6 +19,7 @@ SHAPES = [
     (1, 16, 32, 6, 16, 64),      # two channel blocks, whole tiles
     (1, 17, 18, 3, 9, 33),       # one channel past a block on both sides
     (1, 4, 16, 5, 20, 70),
+    (1, 33, 34, 2, 35, 136),     # two tiles in H and in W for every kernel form, one channel past a 32-block
 ]
 
 
