@@ -156,8 +156,10 @@ h3d_status h3d_conv3d_s2_bwd_filter(void* handle, const h3d_tensor* x, const h3d
  *                     (overwritten; the shard's partial gradient; deterministic: fixed chunks of tiles, added in order)
  * Workspace: h3d_conv3d_k5_workspace_bytes(handle, op, x, z) with x / z the input-side / output-side descriptors for
  * every op (fp32 copy of the filter, or the per-chunk partial sums); 256-byte aligned; H3D_EWORKSPACE if too small.
- * More than 65535 interior planes or n * ceil(channels/16) > 65535: H3D_EUNSUPPORTED.  fp32 accumulation on the
- * vector ALU (no matrix-core form yet). */
+ * More than 65535 interior planes or n * ceil(channels/16) > 65535: H3D_EUNSUPPORTED.  fp32 accumulation; bf16
+ * tensors run on the matrix cores (backward-data and backward-filter then round g to bf16 once, as the 3x3x3 calls
+ * do; backward-filter needs w a multiple of 8 and 16-byte aligned data for that form), fp32 tensors and the
+ * remaining bf16 cases on the vector ALU. */
 size_t h3d_conv3d_k5_workspace_bytes(void* handle, int op, const h3d_tensor* x, const h3d_tensor* z);
 h3d_status h3d_conv3d_k5_fwd(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z,
                              int act, float alpha, void* ws, size_t ws_bytes, void* stream);

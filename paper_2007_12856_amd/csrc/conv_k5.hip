@@ -15,7 +15,9 @@
 //     weight fragments come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] straight from memory.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
 //     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
-//     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).
+//     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).  With bf16
+//     storage, W a multiple of 8 and 16-byte aligned tensors the partial sums come from k5_bwf_mfma_kernel instead
+//     (described above it).
 #include "common.h"
 
 namespace h3d {
