@@ -300,18 +300,27 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
     if (s + 1 < stages) load_stage(s + 1);
     const bf16_t* wt = wpk + (((int64_t)cob * cics + s / 5) * K5_TAPS + (s % 5) * 25) * (KM_COB * KM_CIB);
     // the 4 output rows of the wavefront and the 5 kh taps meet 8 patch rows: per kw, 8 fragment reads feed 20 products
-#pragma unroll 1
+    const bf16_t* wl = wt + lc * KM_CIB + lh * 8;
+    bf16x8 Ac[5], An[5];
+#pragma unroll
+    for (int kh = 0; kh < 5; ++kh) Ac[kh] = *reinterpret_cast<const bf16x8*>(wl + (kh * 5) * (KM_COB * KM_CIB));
+#pragma unroll
     for (int kw = 0; kw < 5; ++kw) {
+      if (kw < 4) {                    // the weight fragments of the next kw travel while this one is multiplied
+#pragma unroll
+        for (int kh = 0; kh < 5; ++kh) An[kh] = *reinterpret_cast<const bf16x8*>(wl + (kh * 5 + kw + 1) * (KM_COB * KM_CIB));
+      }
       bf16x8 B[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r)
         B[r] = *reinterpret_cast<const bf16x8*>(xs + ((wave * 4 + r) * KM_PW + lc + kw) * KM_CIB + lh * 8);
 #pragma unroll
       for (int kh = 0; kh < 5; ++kh) {
-        const bf16x8 A = *reinterpret_cast<const bf16x8*>(wt + ((kh * 5 + kw) * KM_COB + lc) * KM_CIB + lh * 8);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[i + kh], acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[kh], B[i + kh], acc[i], 0, 0, 0);
       }
+#pragma unroll
+      for (int kh = 0; kh < 5; ++kh) Ac[kh] = An[kh];
     }
   }
   // accumulator element r of lane (lc, lh): column = voxel lc, row = channel 8 (r / 4) + 4 lh + r % 4
@@ -440,8 +449,7 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
       const bf16_t* xrow = xr + (((t + kh) % 5) * KB_C + lc) * KB_XW;
       const bf16_t* grow = gr + lc * KB_GW;
 #pragma unroll
-      for (int ks = 0; ks < KB_TW / 16; ++ks) {
-        if (w0 + 16 * ks >= a.in.w) break;
+      for (int ks = 0; ks < KB_TW / 16; ++ks) {   // columns past W hold g = 0: no branch, the reads run ahead of the products
         const int e0 = 16 * ks + 8 * lh;
         const bf16x8 A = *reinterpret_cast<const bf16x8*>(grow + e0);
         const uint4 q = *reinterpret_cast<const uint4*>(xrow + 8 + e0);
@@ -459,10 +467,8 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
         acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b2), acc[2], 0, 0, 0);
         acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b3), acc[3], 0, 0, 0);
         acc[4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, b4), acc[4], 0, 0, 0);
-        if (db_wave) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) dbacc += (float)A[e];
-        }
+        for (int e = 0; e < 8; ++e) dbacc += (float)A[e];   // every wavefront sums g (free beside the products); one of them writes it
       }
     }
   }
