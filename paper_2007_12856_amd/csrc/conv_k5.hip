@@ -12,7 +12,8 @@
 //     as K; a workgroup owns 16 rows x 32 columns of one output plane, a wavefront 4 of the rows (4 accumulators share
 //     every weight fragment, and the 8 patch rows they read per kw feed 20 products); per (16-channel chunk, kd) the 20 x 36 input patch of that plane is transposed into LDS
 //     channel-innermost (32 bytes per voxel: one 16-byte read per lane is a B fragment at any of the 25 shifts), the
-//     weight fragments come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] straight from memory.
+//     weight fragments of the stage come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] and pass
+//     through LDS with the patch.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
 //     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
 //     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).  With bf16
@@ -233,6 +234,7 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
                                                       const bf16_t* __restrict__ wpk, const float* __restrict__ bias,
                                                       bf16_t* __restrict__ out, K5Args a, int cics) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[KM_PH * KM_PW * KM_CIB];
+  __shared__ __attribute__((aligned(16))) bf16_t wsm[25 * KM_COB * KM_CIB];   // the 25 weight fragments of the stage
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lc = lane & 31, lh = lane >> 5;
   const int tw = blockIdx.x % a.tiles_w, th = blockIdx.x / a.tiles_w;
   const int p = blockIdx.y;
@@ -249,9 +251,21 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
   bf16_t raw[ROUNDS][KM_CIB];
   bf16_t zraw[MASK ? ROUNDS : 1][KM_CIB];
   const int stages = cics * 5;
+  constexpr int WPIECES = 25 * KM_COB * KM_CIB / 8, WROUNDS = (WPIECES + 255) / 256;   // 16-byte pieces of a stage's weights
+  uint4 wq[WROUNDS];
   auto load_stage = [&](int s) {
     const int cic = s / 5, pp = p + s % 5 - 2;
     const bool plane_ok = pp >= a.pmin && pp < a.pmax;
+    // the weights travel with the patch and are read from LDS: no memory load stands between the products, so
+    // nothing waits for the patch of the next stage before its time
+    const bf16_t* wt = wpk + (((int64_t)cob * cics + cic) * K5_TAPS + (s % 5) * 25) * (KM_COB * KM_CIB);
+#pragma unroll
+    for (int q = 0; q < WROUNDS; ++q) {
+      const int idx = tid + 256 * q;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (idx < WPIECES) v = *reinterpret_cast<const uint4*>(wt + idx * 8);
+      wq[q] = v;
+    }
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
       const int pos = tid + 256 * q;
@@ -271,6 +285,11 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
     }
   };
   auto store_stage = [&]() {
+#pragma unroll
+    for (int q = 0; q < WROUNDS; ++q) {
+      const int idx = tid + 256 * q;
+      if (idx < WPIECES) *reinterpret_cast<uint4*>(wsm + idx * 8) = wq[q];
+    }
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
       const int pos = tid + 256 * q;
@@ -298,29 +317,20 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
     store_stage();
     __syncthreads();
     if (s + 1 < stages) load_stage(s + 1);
-    const bf16_t* wt = wpk + (((int64_t)cob * cics + s / 5) * K5_TAPS + (s % 5) * 25) * (KM_COB * KM_CIB);
     // the 4 output rows of the wavefront and the 5 kh taps meet 8 patch rows: per kw, 8 fragment reads feed 20 products
-    const bf16_t* wl = wt + lc * KM_CIB + lh * 8;
-    bf16x8 Ac[5], An[5];
-#pragma unroll
-    for (int kh = 0; kh < 5; ++kh) Ac[kh] = *reinterpret_cast<const bf16x8*>(wl + (kh * 5) * (KM_COB * KM_CIB));
-#pragma unroll
+    const bf16_t* wl = wsm + lc * KM_CIB + lh * 8;
+#pragma unroll 1
     for (int kw = 0; kw < 5; ++kw) {
-      if (kw < 4) {                    // the weight fragments of the next kw travel while this one is multiplied
-#pragma unroll
-        for (int kh = 0; kh < 5; ++kh) An[kh] = *reinterpret_cast<const bf16x8*>(wl + (kh * 5 + kw + 1) * (KM_COB * KM_CIB));
-      }
       bf16x8 B[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r)
         B[r] = *reinterpret_cast<const bf16x8*>(xs + ((wave * 4 + r) * KM_PW + lc + kw) * KM_CIB + lh * 8);
 #pragma unroll
       for (int kh = 0; kh < 5; ++kh) {
+        const bf16x8 A = *reinterpret_cast<const bf16x8*>(wl + (kh * 5 + kw) * (KM_COB * KM_CIB));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[kh], B[i + kh], acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[i + kh], acc[i], 0, 0, 0);
       }
-#pragma unroll
-      for (int kh = 0; kh < 5; ++kh) Ac[kh] = An[kh];
     }
   }
   // accumulator element r of lane (lc, lh): column = voxel lc, row = channel 8 (r / 4) + 4 lh + r % 4
