@@ -10,10 +10,10 @@
 //     With bf16 storage the same two passes run on the matrix cores instead (k5_mfma_kernel): v_mfma_f32_32x32x16_bf16
 //     with 32 output channels on the rows, 32 voxels of an output row on the columns and 16 input channels of one tap
 //     as K; a workgroup owns 16 rows x 32 columns of one output plane, a wavefront 4 of the rows (4 accumulators share
-//     every weight fragment, and the 8 patch rows they read per kw feed 20 products); per (16-channel chunk, kd) the 20 x 36 input patch of that plane is transposed into LDS
-//     channel-innermost (32 bytes per voxel: one 16-byte read per lane is a B fragment at any of the 25 shifts), the
-//     weight fragments of the stage come from a packed bf16 copy [co block][ci chunk][tap][32 co][16 ci] and pass
-//     through LDS with the patch.
+//     every weight fragment, and the 8 patch rows they read per kw feed 20 products); per (16-channel chunk, kd) the
+//     20 x 36 input patch of that plane is transposed into LDS channel-innermost (32 bytes per voxel: one 16-byte read
+//     per lane is a B fragment at any of the 25 shifts), the weight fragments of the stage come from a packed bf16
+//     copy [co block][ci chunk][tap][32 co][16 ci] and pass through LDS with the patch.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
 //     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
 //     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).  With bf16
