@@ -458,8 +458,10 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
       }
       const bf16_t* xrow = xr + (((t + kh) % 5) * KB_C + lc) * KB_XW;
       const bf16_t* grow = gr + lc * KB_GW;
+      const int nks = min(KB_TW / 16, (a.in.w - w0 + 15) / 16);   // steps that hold columns of the volume (the rest is g = 0)
 #pragma unroll
-      for (int ks = 0; ks < KB_TW / 16; ++ks) {   // columns past W hold g = 0: no branch, the reads run ahead of the products
+      for (int ks = 0; ks < KB_TW / 16; ++ks) {
+        if ((ks & 3) == 0 && ks >= nks) break;   // decided per group of four steps: inside a group the reads run ahead of the products
         const int e0 = 16 * ks + 8 * lh;
         const bf16x8 A = *reinterpret_cast<const bf16x8*>(grow + e0);
         const uint4 q = *reinterpret_cast<const uint4*>(xrow + 8 + e0);
@@ -529,8 +531,8 @@ K5Plan k5_plan(const h3d_tensor* t, int cin, int cout, int op) {
   p.bf_tiles_h = (int)cdiv(t->h, KB_TH);
   const int64_t units = (int64_t)t->n * t->d * p.bf_tiles_w * p.bf_tiles_h;
   p.bf_units = (int)units;
-  int64_t bf_chunks = cdiv(2048, 5 * cdiv(cin, KB_C) * cdiv(cout, KB_C));
-  if (bf_chunks > 128) bf_chunks = 128;
+  int64_t bf_chunks = cdiv(1024, 5 * cdiv(cin, KB_C) * cdiv(cout, KB_C));
+  if (bf_chunks > 64) bf_chunks = 64;
   if (bf_chunks > units) bf_chunks = units;
   if (bf_chunks < 1) bf_chunks = 1;
   p.bf_chunks = (int)bf_chunks;
