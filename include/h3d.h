@@ -155,7 +155,8 @@ h3d_status h3d_conv3d_s2_bwd_filter(void* handle, const h3d_tensor* x, const h3d
  *   backward-filter:  dw[co,ci,k] = sum_n sum_{p in the interior} g[n,co,p] * x~[n,ci,p+k-2],  db[co] = sum g
  *                     (overwritten; the shard's partial gradient; deterministic: fixed chunks of tiles, added in order)
  * Workspace: h3d_conv3d_k5_workspace_bytes(handle, op, x, z) with x / z the input-side / output-side descriptors for
- * every op (fp32 copy of the filter, or the per-chunk partial sums); 256-byte aligned; H3D_EWORKSPACE if too small.
+ * every op (packed copy of the filter, or the per-chunk partial sums; for bf16 backward passes also g = dz * act'(z),
+ * the size of dz); 256-byte aligned; H3D_EWORKSPACE if too small.
  * More than 65535 interior planes or n * ceil(channels/16) > 65535: H3D_EUNSUPPORTED.  fp32 accumulation; bf16
  * tensors run on the matrix cores (backward-data and backward-filter then round g to bf16 once, as the 3x3x3 calls
  * do; backward-filter needs w a multiple of 8 and 16-byte aligned data for that form), fp32 tensors and the

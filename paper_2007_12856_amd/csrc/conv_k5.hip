@@ -13,7 +13,8 @@
 //     every weight fragment, and the 8 patch rows they read per kw feed 20 products); per (16-channel chunk, kd) the
 //     20 x 36 input patch of that plane is transposed into LDS channel-innermost (32 bytes per voxel: one 16-byte read
 //     per lane is a B fragment at any of the 25 shifts), the weight fragments of the stage come from a packed bf16
-//     copy [co block][ci chunk][tap][32 co][16 ci] and pass through LDS with the patch.
+//     copy [co block][ci chunk][tap][32 co][16 ci] and pass through LDS with the patch.  The bf16 backward passes
+//     make g = dz * act'(z) once (k5_grad_kernel, into the workspace) instead of masking while staging.
 //   backward-filter: a workgroup owns (chunk of tiles, ci, 16 output channels); a thread owns one of the 125 taps
 //     and 8 of the 16 channels and walks the 256 voxels of a tile with x and g in LDS; per-chunk partial sums go
 //     to the workspace and a second kernel adds them in chunk order (two calls give identical bits).  With bf16
@@ -228,11 +229,11 @@ __global__ void __launch_bounds__(256) k5_pack_w_mfma_kernel(const bf16_t* __res
   wpk[i] = v;
 }
 
-// grid (tiles_w * tiles_h, d, n * cobs) with 16 x 32 tiles and blocks of 32 accumulated channels
-template <bool MASK>
-__global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ zm,
-                                                      const bf16_t* __restrict__ wpk, const float* __restrict__ bias,
-                                                      bf16_t* __restrict__ out, K5Args a, int cics) {
+// grid (tiles_w * tiles_h, d, n * cobs) with 16 x 32 tiles and blocks of 32 accumulated channels.  Backward-data passes
+// g = dz * act'(z), made once by k5_grad_kernel: staging the mask here cost two loads per value, five times per plane.
+__global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ wpk,
+                                                      const float* __restrict__ bias, bf16_t* __restrict__ out, K5Args a,
+                                                      int cics) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[KM_PH * KM_PW * KM_CIB];
   __shared__ __attribute__((aligned(16))) bf16_t wsm[25 * KM_COB * KM_CIB];   // the 25 weight fragments of the stage
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lc = lane & 31, lh = lane >> 5;
@@ -249,7 +250,6 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
   // multiplications of stage s start and go to LDS after them, so the memory latency hides behind the matrix work.
   constexpr int ROUNDS = (KM_PH * KM_PW + 255) / 256;
   bf16_t raw[ROUNDS][KM_CIB];
-  bf16_t zraw[MASK ? ROUNDS : 1][KM_CIB];
   const int stages = cics * 5;
   constexpr int WPIECES = 25 * KM_COB * KM_CIB / 8, WROUNDS = (WPIECES + 255) / 256;   // 16-byte pieces of a stage's weights
   uint4 wq[WROUNDS];
@@ -274,13 +274,11 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
       const bool ok = plane_ok && pos < KM_PH * KM_PW && hh >= 0 && hh < a.in.h && ww >= 0 && ww < a.in.w;
       const int64_t sp = (int64_t)hh * a.in.w + ww;
       const bf16_t* src = in + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane + sp;
-      const bf16_t* zsrc = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(pp + a.zg.hlo) * a.zg.plane + sp : nullptr;
 #pragma unroll
       for (int e = 0; e < KM_CIB; ++e) {
         const int ci = cic * KM_CIB + e;
         const bool okc = ok && ci < a.in.c;
         raw[q][e] = okc ? src[(int64_t)ci * a.in.cstride] : (bf16_t)0;
-        if (MASK) zraw[q][e] = okc ? zsrc[(int64_t)ci * a.zg.cstride] : (bf16_t)0x3f80;
       }
     }
   };
@@ -299,11 +297,7 @@ __global__ void __launch_bounds__(256) k5_mfma_kernel(const bf16_t* __restrict__
         for (int e = 0; e < 8; ++e) pk[e] = 0u;
 #pragma unroll
         for (int e = 0; e < KM_CIB; ++e) {
-          uint32_t v = raw[q][e];
-          if (MASK) {
-            if (!(bf16_to_f32(zraw[q][e]) > 0.f)) v = f32_to_bf16(bf16_to_f32((bf16_t)v) * a.slope_in);
-          }
-          pk[e >> 1] |= v << (16 * (e & 1));
+          pk[e >> 1] |= (uint32_t)raw[q][e] << (16 * (e & 1));
         }
         uint4* dst = reinterpret_cast<uint4*>(xs + pos * KM_CIB);
         dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
@@ -365,11 +359,10 @@ constexpr int KB_XW = 152, KB_GW = 136;          // row pitches (elements): 76 a
 constexpr int KB_XG = KB_XW / 8, KB_GG = KB_TW / 8;
 constexpr int KB_THREADS = 320;
 
-template <bool MASK>
-__global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
-                                                                 const bf16_t* __restrict__ zm, float* __restrict__ part,
-                                                                 float* __restrict__ part_db, K5Args a, int units_total,
-                                                                 int units_per_chunk, int cibs) {
+// `g` is dz, or dz * act'(z) made once by k5_grad_kernel (every (kd, ci block) workgroup reads it).
+__global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
+                                                                 float* __restrict__ part, float* __restrict__ part_db, K5Args a,
+                                                                 int units_total, int units_per_chunk, int cibs) {
   __shared__ __attribute__((aligned(16))) bf16_t xr[5 * KB_C * KB_XW];
   __shared__ __attribute__((aligned(16))) bf16_t gr[KB_C * KB_GW];
   const int tid = threadIdx.x, kh = tid >> 6, lane = tid & 63, lc = lane & 31, lh = lane >> 5;
@@ -393,9 +386,8 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
     const int h0 = ht * KB_TH, w0 = wt * KB_TW;
     const int rows = min(KB_TH, a.in.h - h0);
     const bf16_t* xb = x + (int64_t)n * a.in.nstride + (int64_t)(pp + a.in.hlo) * a.in.plane;
-    const bf16_t* gb = dz + (int64_t)n * a.out.nstride + (int64_t)(p + a.out.hlo) * a.out.plane;
-    const bf16_t* zb = MASK ? zm + (int64_t)n * a.zg.nstride + (int64_t)(p + a.zg.hlo) * a.zg.plane : nullptr;
-    uint4 xq0, xq1, gq0, gq1, zq0 = make_uint4(0u, 0u, 0u, 0u), zq1 = zq0;
+    const bf16_t* gb = g + (int64_t)n * a.out.nstride + (int64_t)(p + a.out.hlo) * a.out.plane;
+    uint4 xq0, xq1, gq0, gq1;
     // x row h0 - 2 + j, columns w0 - 8 .. w0 + 143, as 19 pieces of 8 per channel; piece idx of the row
     auto load_x1 = [&](int j, int idx) -> uint4 {
       const int hh = h0 - 2 + j;
@@ -410,35 +402,22 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
       if (idx < KB_C * KB_XG) *reinterpret_cast<uint4*>(xr + ((j % 5) * KB_C + idx / KB_XG) * KB_XW + 8 * (idx % KB_XG)) = v;
     };
     // g row h0 + t, columns w0 .. w0 + 127, 16 pieces per channel
-    auto load_g1 = [&](int t, int idx, uint4& gv, uint4& zv) {
+    auto load_g1 = [&](int t, int idx, uint4& gv) {
       const int hh = h0 + t;
-      const int cl = idx / KB_GG, g = idx % KB_GG;
-      const int co = cob * KB_C + cl, col = w0 + 8 * g;
+      const int cl = idx / KB_GG, gi = idx % KB_GG;
+      const int co = cob * KB_C + cl, col = w0 + 8 * gi;
       const bool ok = idx < KB_C * KB_GG && hh < a.out.h && co < a.out.c && col < a.out.w;
       const int64_t sp = (int64_t)hh * a.out.w + col;
       gv = make_uint4(0u, 0u, 0u, 0u);
       if (ok) gv = *reinterpret_cast<const uint4*>(gb + (int64_t)co * a.out.cstride + sp);
-      if (MASK) {
-        zv = make_uint4(0u, 0u, 0u, 0u);
-        if (ok) zv = *reinterpret_cast<const uint4*>(zb + (int64_t)co * a.zg.cstride + sp);
-      }
     };
-    auto mask2 = [&](uint32_t gd, uint32_t zd) -> uint32_t {
-      uint32_t lo = gd & 0xffffu, hi = gd >> 16;
-      if (!(bf16_to_f32((bf16_t)(zd & 0xffffu)) > 0.f)) lo = f32_to_bf16(bf16_to_f32((bf16_t)lo) * a.slope_in);
-      if (!(bf16_to_f32((bf16_t)(zd >> 16)) > 0.f)) hi = f32_to_bf16(bf16_to_f32((bf16_t)hi) * a.slope_in);
-      return lo | (hi << 16);
-    };
-    auto store_g1 = [&](int idx, uint4 v, const uint4& zv) {
-      if (idx < KB_C * KB_GG) {
-        if (MASK) v = make_uint4(mask2(v.x, zv.x), mask2(v.y, zv.y), mask2(v.z, zv.z), mask2(v.w, zv.w));
-        *reinterpret_cast<uint4*>(gr + (idx / KB_GG) * KB_GW + 8 * (idx % KB_GG)) = v;
-      }
+    auto store_g1 = [&](int idx, const uint4& v) {
+      if (idx < KB_C * KB_GG) *reinterpret_cast<uint4*>(gr + (idx / KB_GG) * KB_GW + 8 * (idx % KB_GG)) = v;
     };
     auto load_x = [&](int j) { xq0 = load_x1(j, tid); xq1 = load_x1(j, tid + KB_THREADS); };
     auto store_x = [&](int j) { store_x1(j, tid, xq0); store_x1(j, tid + KB_THREADS, xq1); };
-    auto load_g = [&](int t) { load_g1(t, tid, gq0, zq0); load_g1(t, tid + KB_THREADS, gq1, zq1); };
-    auto store_g = [&]() { store_g1(tid, gq0, zq0); store_g1(tid + KB_THREADS, gq1, zq1); };
+    auto load_g = [&](int t) { load_g1(t, tid, gq0); load_g1(t, tid + KB_THREADS, gq1); };
+    auto store_g = [&]() { store_g1(tid, gq0); store_g1(tid + KB_THREADS, gq1); };
     __syncthreads();                 // the tile before has been multiplied
 #pragma unroll 1
     for (int j = 0; j < 4; ++j) {
@@ -498,6 +477,44 @@ __global__ void __launch_bounds__(KB_THREADS) k5_bwf_mfma_kernel(const bf16_t* _
     const float v = dbacc + __shfl_xor(dbacc, 32, 64);
     const int co = cob * KB_C + lc;
     if (lh == 0 && co < a.out.c) part_db[(int64_t)chunk * a.out.c + co] = v;
+  }
+}
+
+// g = dz * (z > 0 ? 1 : slope) on every stored plane of dz (bf16), once, so that backward-data stages plain values:
+// its workgroups read every plane five times (once per kd) and once per block of output channels.  z may store other
+// halo planes than dz; a plane of dz without a stored partner in z is copied (backward-data never reads it).
+// One thread per piece of V elements of a plane (V = 8 when planes are whole 16-byte pieces, else 1).
+template <int V>
+__global__ void __launch_bounds__(256) k5_grad_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ zm,
+                                                      bf16_t* __restrict__ g, Geo dg, Geo zg, float slope, int64_t pieces) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= pieces) return;
+  const int64_t per_plane = dg.plane / V;
+  const int64_t off = (i % per_plane) * V, sp = (i / per_plane) % dg.ds, nc = i / (per_plane * dg.ds);
+  const int64_t di = (nc * dg.ds + sp) * dg.plane + off;
+  const int64_t zp = sp - dg.hlo + zg.hlo;
+  const bool masked = zp >= 0 && zp < zg.ds;
+  const int64_t zi = (nc * zg.ds + zp) * zg.plane + off;
+  if (V == 8) {
+    uint4 v = *reinterpret_cast<const uint4*>(dz + di);
+    if (masked) {
+      const uint4 zv = *reinterpret_cast<const uint4*>(zm + zi);
+      uint32_t gv[4] = {v.x, v.y, v.z, v.w};
+      const uint32_t zz[4] = {zv.x, zv.y, zv.z, zv.w};
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        uint32_t lo = gv[d] & 0xffffu, hi = gv[d] >> 16;
+        if (!(bf16_to_f32((bf16_t)(zz[d] & 0xffffu)) > 0.f)) lo = f32_to_bf16(bf16_to_f32((bf16_t)lo) * slope);
+        if (!(bf16_to_f32((bf16_t)(zz[d] >> 16)) > 0.f)) hi = f32_to_bf16(bf16_to_f32((bf16_t)hi) * slope);
+        gv[d] = lo | (hi << 16);
+      }
+      v = make_uint4(gv[0], gv[1], gv[2], gv[3]);
+    }
+    *reinterpret_cast<uint4*>(g + di) = v;
+  } else {
+    bf16_t v = dz[di];
+    if (masked && !(bf16_to_f32(zm[zi]) > 0.f)) v = f32_to_bf16(bf16_to_f32(v) * slope);
+    g[di] = v;
   }
 }
 
@@ -615,8 +632,8 @@ void k5_launch_bwf(const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* 
 }
 
 // bf16 forward / backward-data on the matrix cores: `in` is the staged tensor, `out` the written one
-void k5_launch_mfma(const h3d_tensor* in, const h3d_tensor* z, const void* w, int cin, int cout, int transposed, const float* bias,
-                    h3d_tensor* out, K5Args a, void* ws, hipStream_t s) {
+void k5_launch_mfma(const h3d_tensor* in, const void* w, int cin, int cout, int transposed, const float* bias, h3d_tensor* out,
+                    K5Args a, void* ws, hipStream_t s) {
   const int loopc = transposed ? cout : cin, accc = transposed ? cin : cout;
   const int cics = (int)cdiv(loopc, KM_CIB), cobs = (int)cdiv(accc, KM_COB);
   const int64_t total = (int64_t)cobs * cics * K5_TAPS * KM_COB * KM_CIB;
@@ -627,12 +644,21 @@ void k5_launch_mfma(const h3d_tensor* in, const h3d_tensor* z, const void* w, in
   a.tiles_h = (int)cdiv(in->h, KM_TH);
   a.cobs = cobs;
   const dim3 grid((unsigned)(a.tiles_w * a.tiles_h), (unsigned)in->d, (unsigned)(in->n * cobs));
-  if (z)
-    hipLaunchKernelGGL((k5_mfma_kernel<true>), grid, dim3(256), 0, s, (const bf16_t*)in->data, (const bf16_t*)z->data, (const bf16_t*)wpk, bias,
-                       (bf16_t*)out->data, a, cics);
+  hipLaunchKernelGGL(k5_mfma_kernel, grid, dim3(256), 0, s, (const bf16_t*)in->data, (const bf16_t*)wpk, bias, (bf16_t*)out->data, a, cics);
+}
+
+// g = dz * act'(z) into `g` (every stored plane of dz)
+void k5_launch_grad(const h3d_tensor* dz, const h3d_tensor* z, void* g, float slope, hipStream_t s) {
+  const Geo dg = make_geo(dz), zg = make_geo(z);
+  const bool vec = dg.plane % 8 == 0 && (((uintptr_t)dz->data | (uintptr_t)z->data) & 15) == 0;
+  const int64_t pieces = (int64_t)dz->n * dz->c * dg.ds * (dg.plane / (vec ? 8 : 1));
+  if (pieces == 0) return;
+  if (vec)
+    hipLaunchKernelGGL((k5_grad_kernel<8>), dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, (const bf16_t*)dz->data,
+                       (const bf16_t*)z->data, (bf16_t*)g, dg, zg, slope, pieces);
   else
-    hipLaunchKernelGGL((k5_mfma_kernel<false>), grid, dim3(256), 0, s, (const bf16_t*)in->data, (const bf16_t*)nullptr, (const bf16_t*)wpk, bias,
-                       (bf16_t*)out->data, a, cics);
+    hipLaunchKernelGGL((k5_grad_kernel<1>), dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, (const bf16_t*)dz->data,
+                       (const bf16_t*)z->data, (bf16_t*)g, dg, zg, slope, pieces);
 }
 
 bool bad_act(int act) { return act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY; }
@@ -647,10 +673,12 @@ extern "C" size_t h3d_conv3d_k5_workspace_bytes(void* handle, int op, const h3d_
   const K5Plan p = k5_plan(x, x->c, z->c, op);
   switch (op) {
     case H3D_OP_FWD:
-    case H3D_OP_BWD_DATA:
       return p.wp_bytes;
-    case H3D_OP_BWD_FILTER:
-      return p.part_bytes + p.partdb_bytes;
+    case H3D_OP_BWD_DATA:   // bf16: room for g = dz * act'(z) on every stored plane of dz (z is the output-side descriptor here)
+      return p.wp_bytes + (z->dtype == H3D_BF16 ? up256((size_t)z->n * z->c * (z->halo_lo + z->d + z->halo_hi) * z->h * z->w * sizeof(bf16_t)) : 0);
+    case H3D_OP_BWD_FILTER:   // bf16: room for g as in backward-data
+      return p.part_bytes + p.partdb_bytes +
+             (z->dtype == H3D_BF16 ? up256((size_t)z->n * z->c * (z->halo_lo + z->d + z->halo_hi) * z->h * z->w * sizeof(bf16_t)) : 0);
     default:
       return 0;
   }
@@ -672,7 +700,7 @@ extern "C" h3d_status h3d_conv3d_k5_fwd(void* handle, const h3d_tensor* x, const
   float* wp = (float*)ws;
   const K5Args a = k5_args(x, z, nullptr, p, z->c, 1.f, act_slope(act, alpha));
   if (x->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, x->c, z->c, 0, s); k5_launch_conv<float>(x, nullptr, wp, bias, z, a, s); }
-  else k5_launch_mfma(x, nullptr, w, x->c, z->c, 0, bias, z, a, ws, s);
+  else k5_launch_mfma(x, w, x->c, z->c, 0, bias, z, a, ws, s);
   return launch_status(handle, "conv3d_k5_fwd");
 }
 
@@ -698,7 +726,14 @@ extern "C" h3d_status h3d_conv3d_k5_bwd_data(void* handle, const h3d_tensor* dz,
   float* wp = (float*)ws;
   const K5Args a = k5_args(dz, dx, z, p, dx->c, act_slope(act, alpha), 1.f);
   if (dz->dtype == H3D_F32) { k5_launch_pack<float>(w, wp, dx->c, dz->c, 1, s); k5_launch_conv<float>(dz, z, wp, nullptr, dx, a, s); }
-  else k5_launch_mfma(dz, z, w, dx->c, dz->c, 1, nullptr, dx, a, ws, s);
+  else if (!z) k5_launch_mfma(dz, w, dx->c, dz->c, 1, nullptr, dx, a, ws, s);
+  else {
+    // the masked gradient once, then the kernel without a mask (`a` keeps the plane range that dz and z both store)
+    h3d_tensor gt = *dz;
+    gt.data = (char*)ws + p.wp_bytes;
+    k5_launch_grad(dz, z, gt.data, a.slope_in, s);
+    k5_launch_mfma(&gt, w, dx->c, dz->c, 1, nullptr, dx, a, ws, s);
+  }
   return launch_status(handle, "conv3d_k5_bwd_data");
 }
 
@@ -734,12 +769,14 @@ extern "C" h3d_status h3d_conv3d_k5_bwd_filter(void* handle, const h3d_tensor* x
     a.tiles_h = p.bf_tiles_h;
     const int cibs = (int)cdiv(x->c, KB_C), cobs = (int)cdiv(dz->c, KB_C);
     const dim3 grid((unsigned)chunks, 5u, (unsigned)(cobs * cibs));
-    if (z)
-      hipLaunchKernelGGL((k5_bwf_mfma_kernel<true>), grid, dim3(KB_THREADS), 0, s, (const bf16_t*)x->data, (const bf16_t*)dz->data,
-                         (const bf16_t*)z->data, part, part_db, a, p.bf_units, p.bf_units_per_chunk, cibs);
-    else
-      hipLaunchKernelGGL((k5_bwf_mfma_kernel<false>), grid, dim3(KB_THREADS), 0, s, (const bf16_t*)x->data, (const bf16_t*)dz->data,
-                         (const bf16_t*)nullptr, part, part_db, a, p.bf_units, p.bf_units_per_chunk, cibs);
+    const void* gsrc = dz->data;
+    if (z) {   // the masked gradient once (every (kd, ci block) workgroup reads it), then the kernel without a mask
+      void* gbuf = (char*)ws + p.part_bytes + p.partdb_bytes;
+      k5_launch_grad(dz, z, gbuf, a.slope_in, s);
+      gsrc = gbuf;
+    }
+    hipLaunchKernelGGL(k5_bwf_mfma_kernel, grid, dim3(KB_THREADS), 0, s, (const bf16_t*)x->data, (const bf16_t*)gsrc, part, part_db, a,
+                       p.bf_units, p.bf_units_per_chunk, cibs);
   } else {
     k5_launch_bwf<bf16_t>(x, dz, z, part, part_db, a, p, s);
   }
