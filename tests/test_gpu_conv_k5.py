@@ -149,6 +149,49 @@ def test_k5_larger_volume_sampled_against_the_oracle_definition():
     assert rel_l2(val, ref) <= TOL["bf16"]
 
 
+def test_k5_backward_at_the_bench_shape_sampled_against_the_definition():
+    """The launch configuration bench.py times (32 -> 32 channels, 128 x 128 planes, an interior shard with two halo
+    planes per side, leaky-ReLU mask), on 8 interior planes: sampled dx voxels and dw entries are computed one by one
+    from the definition in fp64 (g = dz * act'(z) taken from the unrounded product, as the oracle does)."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W, off, Dg, alpha = 1, 32, 8, 128, 128, 32, 128, 0.01
+    print("k5 sampled backward at the bench shape", flush=True)
+    w, _ = _weights(C, C, "bf16", 550)
+    full = (N, C, Dg, H, W)
+    xa = quantize(cut("uniform", SEED, 551, full, off, d, (2, 2)), "bf16")
+    dza = quantize(cut("uniform", SEED, 552, full, off, d, (2, 2)), "bf16")
+    za = quantize(cut("normal", SEED, 553, full, off, d, (2, 2)), "bf16")
+    _, xg = slab_pair(xa, "bf16", (2, 2), off, Dg)
+    _, dzg = slab_pair(dza, "bf16", (2, 2), off, Dg)
+    _, zg = slab_pair(za, "bf16", (2, 2), off, Dg)
+    g = dza * np.where(za > 0, 1.0, alpha)                       # [1, C, d+4, H, W], stored planes -2 .. d+1
+    gp = np.zeros((C, d + 4, H + 4, W + 4)); gp[:, :, 2:-2, 2:-2] = g[0]
+    xp = np.zeros((C, d + 4, H + 4, W + 4)); xp[:, :, 2:-2, 2:-2] = xa[0]
+    rng = np.random.default_rng(SEED + 554)
+    # backward-data: dx[ci,q,h,v] = sum_{co,k} w[co,ci,k] g~[co,q-k+2]  (window of g reversed against the filter)
+    dxg = h3d.conv3d_k5_bwd_data(dzg, zg, to_dev(w, "bf16"), h3d.Slab(torch.full((N, C, d, H, W), 7.0, device="cuda", dtype=torch.bfloat16),
+                                                                   0, 0, off, Dg), h3d.ACT_LEAKY, alpha)
+    got = from_dev(dxg.t)
+    pts = [(0, 0, 0, 0), (C - 1, d - 1, H - 1, W - 1), (3, 0, H - 1, 17), (17, d - 1, 0, 1)]
+    pts += [tuple(int(v) for v in (rng.integers(C), rng.integers(d), rng.integers(H), rng.integers(W))) for _ in range(150)]
+    ref = np.array([np.sum(w[:, ci, ::-1, ::-1, ::-1] * gp[:, q:q + 5, h:h + 5, v:v + 5]) for ci, q, h, v in pts])
+    val = np.array([got[0, ci, q, h, v] for ci, q, h, v in pts])
+    assert rel_l2(val, ref) <= TOL["bf16"]
+    # backward-filter: dw[co,ci,k] = sum over the interior of g[co,p] x~[ci,p+k-2]; db[co] = sum g
+    dw = torch.full((C, C, 5, 5, 5), 777.0, device="cuda")
+    db = torch.full((C,), 777.0, device="cuda")
+    h3d.conv3d_k5_bwd_filter(xg, dzg, zg, dw, db, h3d.ACT_LEAKY, alpha)
+    gi = g[0][:, 2:-2]                                            # interior planes
+    ent = [(0, 0, 0, 0, 0), (C - 1, C - 1, 4, 4, 4), (5, 9, 2, 2, 2), (31, 0, 0, 4, 1)]
+    ent += [tuple(int(v) for v in (rng.integers(C), rng.integers(C), rng.integers(5), rng.integers(5), rng.integers(5))) for _ in range(60)]
+    ref = np.array([np.sum(gi[co] * xp[ci, kd:kd + d, kh:kh + H, kw:kw + W]) for co, ci, kd, kh, kw in ent])
+    gw = from_dev(dw)
+    val = np.array([gw[e] for e in ent])
+    assert rel_l2(val, ref) <= _tol_w("bf16")
+    assert rel_l2(from_dev(db), gi.sum(axis=(1, 2, 3))) <= _tol_w("bf16")
+
+
 def test_k5_errors_do_not_launch():
     import ctypes
     import torch
