@@ -120,7 +120,7 @@ static inline size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
 struct S2Plan {
   h3d_tensor xs;   // x' (8 cin channels, halo 1/1)
   h3d_tensor gs;   // g  (cout channels, halo 1/1)
-  h3d_tensor yv;   // interior of y as a plane-run view (cout channels, no halo)
+  h3d_tensor yv;   // interior of y: y itself when it stores no halo planes, else a plane-run view (cout channels, no halo)
   h3d_tensor dxs;  // dx' (8 cin channels, no halo)
   size_t xs_bytes, gs_bytes, dxs_bytes, we_bytes, dwe_bytes;
 };
@@ -137,8 +137,10 @@ static S2Plan s2_plan(const h3d_tensor* x, const h3d_tensor* y) {
   p.dxs = t; p.dxs.c = 8 * x->c;
   p.yv = t; p.yv.c = y->c;
   const int64_t yplane = (int64_t)y->h * y->w, yds = y->halo_lo + y->d + y->halo_hi;
-  p.yv.c_stride = yplane * yds;
-  p.yv.n_stride = p.yv.c_stride * y->c;
+  if (y->halo_lo || y->halo_hi) {   // without halo planes y itself is the packed interior: the inner call may then take
+    p.yv.c_stride = yplane * yds;   // the channel-split kernel, which plane-run views never do (8 x cin input channels on a
+    p.yv.n_stride = p.yv.c_stride * y->c;   // small volume is exactly its case)
+  }
   p.yv.data = y->data ? (char*)y->data + (size_t)y->halo_lo * yplane * es : nullptr;
   const size_t vol = (size_t)y->h * y->w;
   p.xs_bytes = up256((size_t)x->n * 8 * x->c * (y->d + 2) * vol * es);
