@@ -39,32 +39,38 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
     loss, g = orc.mse_fwd_bwd(ys[-1], target)
     if count is not None:
         loss, g = loss * target.size / count, g * target.size / count
-    g = q(g)
-    dpred = g
-    dfc = [None] * len(fc_params)
-    for i in range(last, -1, -1):
-        g, dw, db = orc.dense_bwd(hs[i], fc_params[i][0], ys[i], g, orc.ACT_NONE if i == last else orc.ACT_LEAKY, alpha)
-        dfc[i] = (dw, db)
-        g = q(g)
-    dp = orc.Slab(g.reshape(outs[-1].a.shape))
-    dconv = [None] * len(conv_params)
-    gs = [None] * len(conv_params)
-    for i in range(len(conv_params) - 1, -1, -1):
-        # pooling backward and activation backward form one stored tensor g (rounded once); without a pooling the
-        # stored tensor is dz and the activation derivative is applied inside the two backward convolutions
-        dz = orc.pool3d_bwd(dp, None, orc.POOL_AVG) if pools[i] else dp
-        g = orc.act_bwd(dz, None, zs[i], orc.ACT_LEAKY, alpha)
-        if pools[i]:
-            g = qs(g)
-        gs[i] = g
-        xin = xs if i == 0 else outs[i - 1]
-        if strides[i] == 2:
-            dconv[i] = orc.conv3d_s2_bwd_filter(xin, g, None)
-            dp = qs(orc.conv3d_s2_bwd_data(g, None, conv_params[i][0], xin))
-        else:
-            dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
-            dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
-    return {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "dfc": dfc, "dconv": dconv, "g": gs, "dx": dp}
+    dpred = q(g)
+
+    def backward(g):
+        """BD / BF of every layer from the loss gradient g [n, outputs]; linear in g (the masks come from the forward)."""
+        dfc = [None] * len(fc_params)
+        for i in range(last, -1, -1):
+            g, dw, db = orc.dense_bwd(hs[i], fc_params[i][0], ys[i], g, orc.ACT_NONE if i == last else orc.ACT_LEAKY, alpha)
+            dfc[i] = (dw, db)
+            g = q(g)
+        dp = orc.Slab(g.reshape(outs[-1].a.shape))
+        dconv = [None] * len(conv_params)
+        gs = [None] * len(conv_params)
+        for i in range(len(conv_params) - 1, -1, -1):
+            # pooling backward and activation backward form one stored tensor g (rounded once); without a pooling the
+            # stored tensor is dz and the activation derivative is applied inside the two backward convolutions
+            dz = orc.pool3d_bwd(dp, None, orc.POOL_AVG) if pools[i] else dp
+            g = orc.act_bwd(dz, None, zs[i], orc.ACT_LEAKY, alpha)
+            if pools[i]:
+                g = qs(g)
+            gs[i] = g
+            xin = xs if i == 0 else outs[i - 1]
+            if strides[i] == 2:
+                dconv[i] = orc.conv3d_s2_bwd_filter(xin, g, None)
+                dp = qs(orc.conv3d_s2_bwd_data(g, None, conv_params[i][0], xin))
+            else:
+                dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
+                dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
+        return {"dfc": dfc, "dconv": dconv, "g": gs, "dx": dp}
+
+    out = {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "backward": backward}
+    out.update(backward(dpred))
+    return out
 
 
 def unet_level_oracle(x, halo, d_offset, d_global, P, dout, faces, q=None):

@@ -7,7 +7,7 @@ import pytest
 
 import oracle as orc
 import synth
-from helpers import TOL, cut, dev_like, from_dev, quantize, rel_l2, slab_pair, to_dev
+from helpers import TOL, cut, dev_like, from_dev, quantize, close, rel_l2, slab_pair, to_dev
 
 pytestmark = pytest.mark.gpu
 SEED = synth.BASE_SEED
@@ -47,18 +47,18 @@ def test_k5_three_passes_unsharded(shape, dtype):
     xo, xg = slab_pair(synth.flat("uniform", SEED, 501, (N, Ci, D, H, W)), dtype)
     zo = orc.convk_fwd(xo, w, bias, orc.ACT_LEAKY, alpha)
     zg = h3d.conv3d_k5_fwd(xg, wd, bd, dev_like(zo, dtype), h3d.ACT_LEAKY, alpha)
-    assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+    close(from_dev(zg.t), zo.a, TOL[dtype])
     zq_o, zq_g = slab_pair(zo.a, dtype)
     dzo, dzg = slab_pair(synth.flat("uniform", SEED, 502, zo.a.shape), dtype)
     dxo = orc.convk_bwd_data(dzo, zq_o, w, orc.ACT_LEAKY, alpha)
     dxg = h3d.conv3d_k5_bwd_data(dzg, zq_g, wd, dev_like(dxo, dtype), h3d.ACT_LEAKY, alpha)
-    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    close(from_dev(dxg.t), dxo.a, TOL[dtype])
     dwo, dbo = orc.convk_bwd_filter(5, xo, dzo, zq_o, orc.ACT_LEAKY, alpha)
     dw = torch.full((Co, Ci, 5, 5, 5), 777.0, device="cuda")
     db = torch.full((Co,), 777.0, device="cuda")
     h3d.conv3d_k5_bwd_filter(xg, dzg, zq_g, dw, db, h3d.ACT_LEAKY, alpha)
-    assert rel_l2(from_dev(dw), dwo) <= _tol_w(dtype)
-    assert rel_l2(from_dev(db), dbo) <= _tol_w(dtype)
+    close(from_dev(dw), dwo, _tol_w(dtype))
+    close(from_dev(db), dbo, _tol_w(dtype))
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
     h3d.conv3d_k5_bwd_filter(xg, dzg, zq_g, dw2, db2, h3d.ACT_LEAKY, alpha)
     assert torch.equal(dw, dw2) and torch.equal(db, db2)
@@ -76,16 +76,16 @@ def test_k5_no_bias_other_activations(dtype, act):
     xo, xg = slab_pair(synth.flat("normal", SEED, 503, (N, Ci, D, H, W)), dtype)
     zo = orc.convk_fwd(xo, w, None, act)
     zg = h3d.conv3d_k5_fwd(xg, wd, None, dev_like(zo, dtype), act, 0.0)
-    assert rel_l2(from_dev(zg.t), zo.a) <= TOL[dtype]
+    close(from_dev(zg.t), zo.a, TOL[dtype])
     zq_o, zq_g = slab_pair(zo.a, dtype)
     dzo, dzg = slab_pair(synth.flat("normal", SEED, 504, zo.a.shape), dtype)
     dxo = orc.convk_bwd_data(dzo, zq_o, w, act)
     dxg = h3d.conv3d_k5_bwd_data(dzg, zq_g, wd, dev_like(dxo, dtype), act, 0.0)
-    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    close(from_dev(dxg.t), dxo.a, TOL[dtype])
     dwo, _ = orc.convk_bwd_filter(5, xo, dzo, zq_o, act)
     dw = torch.full((Co, Ci, 5, 5, 5), 777.0, device="cuda")
     h3d.conv3d_k5_bwd_filter(xg, dzg, zq_g, dw, None, act, 0.0)
-    assert rel_l2(from_dev(dw), dwo) <= _tol_w(dtype)
+    close(from_dev(dw), dwo, _tol_w(dtype))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -108,7 +108,7 @@ def test_k5_on_depth_shards(shard, dtype):
     zg = h3d.Slab(torch.full((N, Co, d + 3, H, W), 12345.0, device="cuda", dtype=td), 1, 2, off, Dg)
     h3d.conv3d_k5_fwd(xg, wd, bd, zg, h3d.ACT_LEAKY, alpha)
     got = from_dev(zg.t)
-    assert rel_l2(got[:, :, 1:-2], zo.a) <= TOL[dtype]
+    close(got[:, :, 1:-2], zo.a, TOL[dtype])
     canary = got[0, 0, 0, 0, 0]
     assert canary == 12345.0 or dtype == "bf16"
     assert np.all(got[:, :, 0] == canary) and np.all(got[:, :, -2:] == canary)
@@ -118,13 +118,13 @@ def test_k5_on_depth_shards(shard, dtype):
     zso, zsg = slab_pair(cut("normal", SEED, 507, full_z, off, d, (2, 2)), dtype, (2, 2), off, Dg)
     dxo = orc.convk_bwd_data(dzo, zso, w, orc.ACT_LEAKY, alpha)
     dxg = h3d.conv3d_k5_bwd_data(dzg, zsg, wd, dev_like(dxo, dtype), h3d.ACT_LEAKY, alpha)
-    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    close(from_dev(dxg.t), dxo.a, TOL[dtype])
     dwo, dbo = orc.convk_bwd_filter(5, xo, dzo, zso, orc.ACT_LEAKY, alpha)
     dw = torch.full((Co, Ci, 5, 5, 5), 777.0, device="cuda")
     db = torch.full((Co,), 777.0, device="cuda")
     h3d.conv3d_k5_bwd_filter(xg, dzg, zsg, dw, db, h3d.ACT_LEAKY, alpha)
-    assert rel_l2(from_dev(dw), dwo) <= _tol_w(dtype)
-    assert rel_l2(from_dev(db), dbo) <= _tol_w(dtype)
+    close(from_dev(dw), dwo, _tol_w(dtype))
+    close(from_dev(db), dbo, _tol_w(dtype))
 
 
 def test_k5_larger_volume_sampled_against_the_oracle_definition():
@@ -146,7 +146,7 @@ def test_k5_larger_volume_sampled_against_the_oracle_definition():
     pts += [tuple(int(v) for v in (rng.integers(Co), rng.integers(D), rng.integers(D), rng.integers(D))) for _ in range(200)]
     ref = np.array([bias[co] + np.sum(w[co] * xp[:, p:p + 5, h:h + 5, v:v + 5]) for co, p, h, v in pts])
     val = np.array([got[0, co, p, h, v] for co, p, h, v in pts])
-    assert rel_l2(val, ref) <= TOL["bf16"]
+    close(val, ref, TOL["bf16"])
 
 
 def test_k5_backward_at_the_bench_shape_sampled_against_the_definition():
@@ -177,7 +177,7 @@ def test_k5_backward_at_the_bench_shape_sampled_against_the_definition():
     pts += [tuple(int(v) for v in (rng.integers(C), rng.integers(d), rng.integers(H), rng.integers(W))) for _ in range(150)]
     ref = np.array([np.sum(w[:, ci, ::-1, ::-1, ::-1] * gp[:, q:q + 5, h:h + 5, v:v + 5]) for ci, q, h, v in pts])
     val = np.array([got[0, ci, q, h, v] for ci, q, h, v in pts])
-    assert rel_l2(val, ref) <= TOL["bf16"]
+    close(val, ref, TOL["bf16"])
     # backward-filter: dw[co,ci,k] = sum over the interior of g[co,p] x~[ci,p+k-2]; db[co] = sum g
     dw = torch.full((C, C, 5, 5, 5), 777.0, device="cuda")
     db = torch.full((C,), 777.0, device="cuda")
@@ -188,8 +188,8 @@ def test_k5_backward_at_the_bench_shape_sampled_against_the_definition():
     ref = np.array([np.sum(gi[co] * xp[ci, kd:kd + d, kh:kh + H, kw:kw + W]) for co, ci, kd, kh, kw in ent])
     gw = from_dev(dw)
     val = np.array([gw[e] for e in ent])
-    assert rel_l2(val, ref) <= _tol_w("bf16")
-    assert rel_l2(from_dev(db), gi.sum(axis=(1, 2, 3))) <= _tol_w("bf16")
+    close(val, ref, _tol_w("bf16"))
+    close(from_dev(db), gi.sum(axis=(1, 2, 3)), _tol_w("bf16"))
 
 
 def test_k5_errors_do_not_launch():

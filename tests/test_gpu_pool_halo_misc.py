@@ -4,7 +4,7 @@ import pytest
 
 import oracle as orc
 import synth
-from helpers import TOL, dev_like, from_dev, quantize, rel_l2, slab_pair, to_dev
+from helpers import TOL, dev_like, from_dev, quantize, close, rel_l2, slab_pair, to_dev
 
 pytestmark = pytest.mark.gpu
 SEED = synth.BASE_SEED + 1
@@ -30,7 +30,7 @@ def test_pool_fwd_bwd(shape, halo, mode, dtype):
     if mode == orc.POOL_MAX:
         assert np.array_equal(got[:, :, 1:], yo.interior)
     else:
-        assert rel_l2(got[:, :, 1:], yo.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+        close(got[:, :, 1:], yo.interior, (1e-6 if dtype == "f32" else 4e-3))
     assert np.all(got[:, :, 0] == 12345.0 if dtype == "f32" else got[:, :, 0] == quantize(12345.0, "bf16"))
     dyo, dyg = slab_pair(synth.flat("normal", SEED, 2, yo.a.shape), dtype, (1, 0), yo.d_offset, yo.d_global)
     dxo = orc.pool3d_bwd(dyo, xo, mode, dx_halo=halo)
@@ -40,7 +40,7 @@ def test_pool_fwd_bwd(shape, halo, mode, dtype):
     if mode == orc.POOL_MAX:
         assert np.array_equal(got, dxo.interior)     # routing is exact, ties included
     else:
-        assert rel_l2(got, dxo.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+        close(got, dxo.interior, (1e-6 if dtype == "f32" else 4e-3))
     if halo[0]:
         assert np.all(from_dev(dxg.t)[:, :, :halo[0]] == 7.0)
 
@@ -169,16 +169,17 @@ def test_deconv2(cin, cout, shape, dtype):
     xo, xg = slab_pair(synth.flat("normal", SEED, 6, (N, cin, d, H, W)), dtype, (0, 0), 2, 2 + d + 2)
     yo = orc.deconv2_fwd(xo, w, bias)
     yg = h3d.deconv2_fwd(xg, to_dev(w, dtype), to_dev(bias, "f32"), dev_like(yo, dtype))
-    assert rel_l2(from_dev(yg.t), yo.a) <= TOL[dtype]
+    close(from_dev(yg.t), yo.a, TOL[dtype])
     dyo, dyg = slab_pair(synth.flat("normal", SEED, 7, yo.a.shape), dtype, (0, 0), yo.d_offset, yo.d_global)
     dxo = orc.deconv2_bwd_data(dyo, w)
     dxg = h3d.deconv2_bwd_data(dyg, to_dev(w, dtype), dev_like(dxo, dtype))
-    assert rel_l2(from_dev(dxg.t), dxo.a) <= TOL[dtype]
+    close(from_dev(dxg.t), dxo.a, TOL[dtype])
     dwo, dbo = orc.deconv2_bwd_filter(xo, dyo)
     dw = torch.empty((cin, cout, 2, 2, 2), device="cuda")
     db = torch.empty((cout,), device="cuda")
     h3d.deconv2_bwd_filter(xg, dyg, dw, db)
-    assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+    close(from_dev(dw), dwo, TOL[dtype])
+    close(from_dev(db), dbo, TOL[dtype])
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
     h3d.deconv2_bwd_filter(xg, dyg, dw2, db2)
     assert torch.equal(dw, dw2) and torch.equal(db, db2)
@@ -214,7 +215,7 @@ def test_dense_and_mse(m, n, k, act, dtype):
     yo = orc.dense_fwd(x, w, bias, act, 0.01)
     y = torch.empty((m, n), dtype=td, device="cuda")
     h3d.dense_fwd(to_dev(x, dtype), to_dev(w, dtype), to_dev(bias, "f32"), y, act, 0.01)
-    assert rel_l2(from_dev(y), yo) <= TOL[dtype]
+    close(from_dev(y), yo, TOL[dtype])
     yq = quantize(yo, dtype)
     dy = quantize(synth.flat("normal", SEED, 13, (m, n)), dtype)
     dxo, dwo, dbo = orc.dense_bwd(x, w, yq, dy, act, 0.01)
@@ -222,8 +223,9 @@ def test_dense_and_mse(m, n, k, act, dtype):
     dw = torch.empty((n, k), device="cuda")
     db = torch.empty((n,), device="cuda")
     h3d.dense_bwd(to_dev(x, dtype), to_dev(w, dtype), to_dev(yq, dtype), to_dev(dy, dtype), dx, dw, db, act, 0.01)
-    assert rel_l2(from_dev(dx), dxo) <= TOL[dtype]
-    assert rel_l2(from_dev(dw), dwo) <= TOL[dtype] and rel_l2(from_dev(db), dbo) <= TOL[dtype]
+    close(from_dev(dx), dxo, TOL[dtype])
+    close(from_dev(dw), dwo, TOL[dtype])
+    close(from_dev(db), dbo, TOL[dtype])
     # the two halves asked for separately (a caller may put them on two streams): same bits
     dx2, dw2, db2 = torch.full_like(dx, 3.0), torch.full_like(dw, 3.0), torch.full_like(db, 3.0)
     args = (to_dev(x, dtype), to_dev(w, dtype), to_dev(yq, dtype), to_dev(dy, dtype))
@@ -237,7 +239,7 @@ def test_dense_and_mse(m, n, k, act, dtype):
     dp = torch.empty((m, n), dtype=td, device="cuda")
     h3d.mse_fwd_bwd(to_dev(yq, dtype), to_dev(t, "f32"), loss, dp)
     assert abs(loss.item() - Lo) <= 1e-5 * abs(Lo)
-    assert rel_l2(from_dev(dp), go) <= TOL[dtype]
+    close(from_dev(dp), go, TOL[dtype])
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -253,7 +255,7 @@ def test_act_bwd(shape, dtype):
         gg = dev_like(go, dtype)
         h3d.act_bwd(dzg, d2g if two else None, zg, gg, act, 0.01)
         got = from_dev(gg.t)
-        assert rel_l2(got[:, :, 2:], go.interior) <= (1e-6 if dtype == "f32" else 4e-3)
+        close(got[:, :, 2:], go.interior, (1e-6 if dtype == "f32" else 4e-3))
         assert np.all(got[:, :, :2] == quantize(12345.0, dtype))      # halo planes untouched
 
 
@@ -270,7 +272,7 @@ def test_pool_bwd_fused_with_activation_backward(mode, dtype):
         ref = orc.act_bwd(orc.pool3d_bwd(dyo, xo, mode), None, zo, act, 0.01)
         gg = dev_like(ref, dtype)
         h3d.pool3d_bwd_act(dyg, xg if mode == orc.POOL_MAX else None, zg, gg, mode, act, 0.01)
-        assert rel_l2(from_dev(gg.t), ref.a) <= (1e-6 if dtype == "f32" else 4e-3)
+        close(from_dev(gg.t), ref.a, (1e-6 if dtype == "f32" else 4e-3))
 
 
 def test_calibration_probes_run_and_report_their_work():

@@ -5,7 +5,7 @@ import pytest
 
 import oracle as orc
 import synth
-from helpers import TOL, from_dev, quantize, rel_l2, to_dev
+from helpers import TOL, from_dev, quantize, close, rel_l2, to_dev
 
 pytestmark = pytest.mark.gpu
 SEED = synth.BASE_SEED
@@ -35,7 +35,7 @@ def test_softmax_xent_matches_the_oracle(case, dtype):
     labd = torch.from_numpy(lab.astype(np.uint8)).cuda()
     h3d.softmax_xent_fwd_bwd(zg, labd, lab.size, loss, gg)
     assert abs(loss.item() - lo) <= 1e-5 * max(abs(lo), 1e-3)
-    assert rel_l2(from_dev(gg.t), go) <= TOL[dtype]
+    close(from_dev(gg.t), go, TOL[dtype])
     loss2, g2 = torch.empty_like(loss), h3d.Slab(torch.empty_like(gg.t))
     h3d.softmax_xent_fwd_bwd(zg, labd, lab.size, loss2, g2)
     assert torch.equal(loss, loss2) and torch.equal(gg.t, g2.t)
@@ -64,7 +64,7 @@ def test_softmax_xent_on_shards_with_halos_and_unlabelled_voxels(dtype):
         h3d.softmax_xent_fwd_bwd(zg, labd, count, loss, gg)
         total += loss.item()
         got = from_dev(gg.t)
-        assert rel_l2(got[:, :, 2:], full_g[:, :, 2 * s:2 * s + 2]) <= TOL[dtype]
+        close(got[:, :, 2:], full_g[:, :, 2 * s:2 * s + 2], TOL[dtype])
         assert np.all(got[:, :, :2] == 9.0)
     assert abs(total - full_loss) <= 1e-5 * abs(full_loss)
     assert np.all(full_g[0, :, 1, 2, 3:9] == 0.0)

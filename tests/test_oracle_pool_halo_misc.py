@@ -239,3 +239,28 @@ def test_dense_and_mse_against_torch_and_finite_differences():
     # closed form: pred = target + 1 everywhere -> loss 1, gradient 2/size
     L1, g1 = orc.mse_fwd_bwd(t + 1.0, t)
     assert abs(L1 - 1.0) < 1e-15 and np.allclose(g1, 2.0 / t.size)
+
+
+def test_act_mask_bytes_of_a_hand_written_slab():
+    """Sign mask of a saved activation (the (leaky-)ReLU derivative only needs z > 0): bytes written out by hand for two
+    rows of 16 voxels inside a slab with one halo plane per side.  Bit k of byte j of a row is voxel 8 j + k, a zero and a
+    negative zero are NOT positive, halo planes are left out, rows follow [n][c][interior plane][h]."""
+    nz = -0.0
+    assert np.signbit(nz)
+    row0 = [1.0, -1.0, 0.0, nz, 2.0, 0.5, -3.0, 1e-30,      # bits 0,4,5,7      -> 0b10110001
+            -2.0, 3.0, nz, 0.0, -1e-30, -5.0, 7.0, -0.25]   # bits 1,6          -> 0b01000010
+    row1 = [-1.0, 1.0, 1.0, nz, 0.0, 0.0, 0.0, 3.0,         # bits 1,2,7        -> 0b10000110
+            4.0, 4.0, 4.0, 4.0, 4.0, 4.0, 4.0, -4.0]        # bits 0..6         -> 0b01111111
+    a = np.full((1, 1, 3, 2, 16), 9.0)                       # halo planes all positive: they must not show up
+    a[0, 0, 1, 0], a[0, 0, 1, 1] = row0, row1
+    m = orc.act_mask(Slab(a, 1, 1, 4, 12))
+    assert m.dtype == np.uint8 and m.shape == (1, 1, 1, 2, 2)
+    assert m.tolist() == [[[[[0b10110001, 0b01000010], [0b10000110, 0b01111111]]]]]
+    # the same bytes by the definition, voxel by voxel (brute force over a seeded slab, several channels and planes)
+    rng = np.random.default_rng(5)
+    z = rng.standard_normal((2, 3, 4, 3, 24))
+    z[rng.random(z.shape) < 0.2] = 0.0
+    z[rng.random(z.shape) < 0.1] = nz
+    got = orc.act_mask(Slab(z, 1, 0, 2, 8))
+    for n, c, d, h, w in itertools.product(range(2), range(3), range(3), range(3), range(24)):
+        assert (got[n, c, d, h, w // 8] >> (w % 8)) & 1 == (1 if z[n, c, d + 1, h, w] > 0 else 0)
