@@ -51,7 +51,9 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
         dp = orc.Slab(g.reshape(outs[-1].a.shape))
         dconv = [None] * len(conv_params)
         gs = [None] * len(conv_params)
+        dps = [None] * len(conv_params)
         for i in range(len(conv_params) - 1, -1, -1):
+            dps[i] = dp
             # pooling backward and activation backward form one stored tensor g (rounded once); without a pooling the
             # stored tensor is dz and the activation derivative is applied inside the two backward convolutions
             dz = orc.pool3d_bwd(dp, None, orc.POOL_AVG) if pools[i] else dp
@@ -66,9 +68,9 @@ def cosmoflow_oracle(x, target, conv_params, fc_params, alpha=0.01, count=None, 
             else:
                 dconv[i] = orc.conv3d_bwd_filter(xin, g, None)
                 dp = qs(orc.conv3d_bwd_data(g, None, conv_params[i][0]))
-        return {"dfc": dfc, "dconv": dconv, "g": gs, "dx": dp}
+        return {"dfc": dfc, "dconv": dconv, "g": gs, "dx": dp, "dp": dps}
 
-    out = {"z": zs, "p": ps, "y": ys, "loss": loss, "dpred": dpred, "backward": backward}
+    out = {"z": zs, "p": ps, "out": outs, "y": ys, "loss": loss, "dpred": dpred, "backward": backward}
     out.update(backward(dpred))
     return out
 

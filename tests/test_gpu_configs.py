@@ -136,10 +136,15 @@ def test_cfg1_single_layer_fp32():
 # ---------------------------------------------------------------- configuration 2
 def test_cfg2_cosmoflow_stack_full_size():
     """N=4 x 4x128^3 bf16, five conv+leaky+avg-pool stages, dense 16384-2048-256-4, MSE, fwd+bwd, built and run exactly
-    as bench.py times it: first stage fused (conv + pooling forward, sign mask, no stored activation), every pooling
-    backward from a sign mask, the backward-filter calls of the late stages and the dense weight gradients on a second
-    stream.  The oracle evaluates the whole batch (storage rounding between layers as on the GPU; FP, BD and BF of every
-    layer, Sec. III-C, on the shapes of Table I's first stages); every stored tensor of the step is compared."""
+    as bench.py times it: first stage fused (conv + pooling forward, sign mask, no stored activation), pooling backward
+    from a sign mask, the backward-filter calls of the late stages and the dense weight gradients on a second stream.
+    Two comparisons, both on the whole batch (FP, BD and BF of every layer, Sec. III-C, on the shapes of Table I's first stages):
+    A. the step against the oracle's evaluation of the same network on the same bf16 inputs and weights (fp64 sums, stored
+       tensors rounded to bf16 as on the GPU), every tensor on the bf16 bar: forward, loss and loss gradient in one
+       unbroken pass; the backward pass of the convolution stages from the oracle's gradient at the flatten;
+    B. every backward stage (dense head, then each convolution stage) once more from IDENTICAL inputs (the oracle's
+       tensors, rounded to bf16, uploaded into the stage's buffers), on the bars of the single calls: bf16 results one
+       rounding, fp32 filter gradients 2e-4."""
     import torch
     from test_gpu_stack import BWD_ELEM, FWD_ELEM, build, loss_bound
     from oracle_nets import cosmoflow_oracle
@@ -148,12 +153,22 @@ def test_cfg2_cosmoflow_stack_full_size():
     # (the last stage's 8-voxel rows are too short for the mask kernels: its pooling backward reads the stored activation)
     assert net.fused == [True, False, False, False, False] and [m is not None for m in net.mask] == [True, True, True, True, False]
     names = [o["name"] for o in net.ops]
-    assert names[:3] == ["conv1_fwd_pool", "conv2_fwd", "pool2_fwd"] and "pool1_bwd_mask" in names and "pool4_bwd_mask" in names and "pool5_bwd_act" in names
+    assert names[:3] == ["conv1_fwd_pool", "conv2_fwd", "pool2_fwd"]
+    assert "pool1_bwd_mask" in names and "pool4_bwd_mask" in names and "pool5_bwd_act" in names
     net.step()
     torch.cuda.synchronize()
     assert net.side is not None                         # the second stream was used
-    tol = TOL[BF]
-    ref = cosmoflow_oracle(xq, tq, convq, fcq, q=lambda v: quantize(v, BF))
+    tol, alpha = TOL[BF], 0.01
+    qz = lambda v: quantize(v, BF)
+    # The oracle rounds every STORED tensor to bf16 as the GPU does (sums in fp64).  Against the network evaluated without
+    # that rounding the forward tensors agree to 2-3e-3, but the backward pass cannot be compared: the slope of a leaky
+    # ReLU is taken from the sign of the stored activation, a relative difference of 2.5e-3 between the two forward
+    # passes puts about 0.2 % of the activations on different sides of zero, and a fraction f of voxels with the slope
+    # off by a factor of 100 is a relative L2 difference of sqrt(2 f) = 6e-2 in g (measured: 3.6e-2 after one stage,
+    # 7e-2 after five).  With the storage format part of each layer's contract on both sides the forward passes differ
+    # by 1e-5 .. 1e-3 and such flips are rare.
+    ref = cosmoflow_oracle(xq, tq, convq, fcq, q=qz)
+    # ---- A: the unbroken step
     close(from_dev(net.p[0].t), ref["p"][0].a, tol, "p1", **FWD_ELEM[BF])
     for i in range(1, 5):
         close(from_dev(net.z[i].t), ref["z"][i].a, tol, f"z{i + 1}", **FWD_ELEM[BF])
@@ -164,26 +179,89 @@ def test_cfg2_cosmoflow_stack_full_size():
     diff = np.unpackbits((got ^ want)[..., None], axis=-1, bitorder="little").reshape(ref["z"][0].a.shape).astype(bool)
     assert diff.mean() < 1e-3 and np.all(np.abs(ref["z"][0].a[diff]) <= 1e-2 * np.abs(ref["z"][0].a).max())
     del want, got, diff
-    close(from_dev(net.y[-1]), ref["y"][-1], tol, "pred")
-    assert abs(net.loss.item() - ref["loss"]) <= loss_bound(ref["y"][-1], tq, tol) * abs(ref["loss"])
-    # backward from the oracle's loss gradient on both sides (the unbroken chain is test_cosmoflow_stack_miniature_unbroken_chain)
-    net.dy[-1].copy_(to_dev(ref["dpred"], BF))
-    net.backward_after_loss()
+    pred = ref["y"][-1]
+    close(from_dev(net.y[-1]), pred, tol, "pred")
+    assert abs(net.loss.item() - ref["loss"]) <= loss_bound(pred, tq, tol) * abs(ref["loss"])
+    # the loss gradient turns a relative difference e of pred into e |pred| / |pred - t| of itself (the MSE call is
+    # compared on identical inputs in test_dense_and_mse); with targets in [-1, 1] and small predictions that factor is < 1
+    amp = np.linalg.norm(pred) / np.linalg.norm(pred - tq)
+    close(from_dev(net.dy[-1]), ref["dpred"], tol * max(1.0, amp), "loss gradient")
+    # The backward pass of the convolution stages, as the step runs it, from the oracle's gradient at the flatten.  (The
+    # dense head is cut off here and compared from identical inputs below: its layers have 256 and 2048 outputs per
+    # sample, and ONE activation within rounding of zero whose sign differs between the two forward passes changes the
+    # slope of that output from 0.01 to 1 - a few per cent of such a small layer's gradient norm, passed on unchanged to
+    # every tensor below.  In the convolution stages the same flips are a vanishing share of millions of voxels.)
+    net.dp[4].t.copy_(to_dev(qz(ref["dp"][4].a), BF))
+    ops = {o["name"]: o["fn"] for o in net.ops}
+    for o in net.ops[names.index("pool5_bwd_act"):]:
+        o["fn"]()
     torch.cuda.synchronize()
+    # element by element here only coarsely: stage 5's activations differ by 1.2e-3 between the two forward passes, 1e-4 of
+    # them lie on different sides of zero, which alone is sqrt(2e-4) = 1.4e-2 of g5's norm and is spread by every
+    # backward-data convolution below; part B holds every element of every stage to the single-call bounds
+    coarse = dict(elem=2.0 ** -3, outliers=2e-3)
     for i in range(5):
-        close(from_dev(net.g[i].t), ref["g"][i].a, tol, f"g{i + 1}", **BWD_ELEM[BF])
-        close(from_dev(net.dconv[i][0]), ref["dconv"][i][0], tol, f"dw{i + 1}", **BWD_ELEM[BF])
-        close(from_dev(net.dconv[i][1]), ref["dconv"][i][1], tol, f"db{i + 1}", **BWD_ELEM[BF])
-    for i in range(3):
-        close(from_dev(net.dfc[i][0]), ref["dfc"][i][0], tol, f"dfc{i + 1}", **BWD_ELEM[BF])
-        close(from_dev(net.dfc[i][1]), ref["dfc"][i][1], tol, f"dfc{i + 1} bias", **BWD_ELEM[BF])
-    close(from_dev(net.dx.t), ref["dx"].a, tol, "dx", **BWD_ELEM[BF])
-    # the two-stream schedule is deterministic: a second backward pass returns identical bits
-    keep = [t.clone() for pair in net.dconv + net.dfc for t in pair] + [net.dx.t.clone()]
-    net.backward_after_loss()
+        close(from_dev(net.g[i].t), ref["g"][i].a, tol, f"g{i + 1}", **coarse)
+        close(from_dev(net.dconv[i][0]), ref["dconv"][i][0], tol, f"dw{i + 1}", **coarse)
+        close(from_dev(net.dconv[i][1]), ref["dconv"][i][1], tol, f"db{i + 1}", **coarse)
+    close(from_dev(net.dx.t), ref["dx"].a, tol, "dx", **coarse)
+    # the two-stream schedule is deterministic: the whole backward pass twice, identical bits
+    net.backward()
     torch.cuda.synchronize()
-    for a, b in zip(keep, [t for pair in net.dconv + net.dfc for t in pair] + [net.dx.t]):
+    grads = lambda: [t for pair in net.dconv + net.dfc for t in pair] + [net.dx.t]
+    keep = [t.clone() for t in grads()]
+    for t in grads():
+        t.fill_(3.0)
+    net.backward()
+    torch.cuda.synchronize()
+    for a, b in zip(keep, grads()):
         assert torch.equal(a, b)
+    del keep
+    # ---- B: the dense head's backward from identical inputs (BD and BF of the fully-connected layers)
+    hq = [qz(ref["p"][4].a).reshape(4, -1)] + [qz(y) for y in ref["y"]]
+    net.p[4].t.copy_(to_dev(hq[0].reshape(ref["p"][4].a.shape), BF))
+    for i in range(3):
+        net.y[i].copy_(to_dev(hq[i + 1], BF))
+    g = qz(ref["dpred"])
+    for i in (2, 1, 0):
+        net.dy[i].copy_(to_dev(g, BF))
+        ops[f"fc{i + 1}_bwd"]()
+        ops["join"]()
+        torch.cuda.synchronize()
+        g, dw, db = orc.dense_bwd(hq[i], fcq[i][0], hq[i + 1], g, orc.ACT_NONE if i == 2 else orc.ACT_LEAKY, alpha)
+        close(from_dev(net.dfc[i][0]), dw, tol, f"fc{i + 1} dw")
+        close(from_dev(net.dfc[i][1]), db, tol, f"fc{i + 1} db")
+        close(from_dev(net.dp[4].t).reshape(4, -1) if i == 0 else from_dev(net.dy[i - 1]), g, tol, f"fc{i + 1} dx")
+        g = qz(g)
+    # ---- B: the convolution stages one by one from identical inputs, with the calls (and streams) of the step
+    for i in range(4, -1, -1):
+        w = convq[i][0]
+        zq = orc.Slab(qz(ref["z"][i].a))
+        dpq = orc.Slab(qz(ref["dp"][i].a))
+        xin = orc.Slab(xq) if i == 0 else orc.Slab(qz(ref["out"][i - 1].a))
+        net.dp[i].t.copy_(to_dev(dpq.a, BF))
+        if i > 0:
+            net.out[i - 1].t.copy_(to_dev(xin.a, BF))
+        if net.z[i] is not None:
+            net.z[i].t.copy_(to_dev(zq.a, BF))
+        if net.mask[i] is not None:
+            net.mask[i].copy_(torch.from_numpy(orc.act_mask(zq).ravel()).cuda())
+        for nm in (f"pool{i + 1}_bwd_mask", f"pool{i + 1}_bwd_act"):
+            if nm in ops:
+                ops[nm]()
+        ops[f"conv{i + 1}_bwd_filter"]()
+        ops[f"conv{i + 1}_bwd_data"]()
+        ops["join"]()
+        torch.cuda.synchronize()
+        g = orc.act_bwd(orc.pool3d_bwd(dpq, None, orc.POOL_AVG), None, zq, orc.ACT_LEAKY, alpha)
+        close(from_dev(net.g[i].t), g.a, 4e-3, f"stage {i + 1} g", elem=2.0 ** -8)       # one bf16 rounding of an exact product
+        gq = orc.Slab(qz(g.a))
+        dw, db = orc.conv3d_bwd_filter(xin, gq, None)
+        close(from_dev(net.dconv[i][0]), dw, 2e-4, f"stage {i + 1} dw")
+        close(from_dev(net.dconv[i][1]), db, 2e-4, f"stage {i + 1} db")
+        dxi = orc.conv3d_bwd_data(gq, None, w)
+        close(from_dev((net.dx if i == 0 else net.dout[i - 1]).t), dxi.a, tol, f"stage {i + 1} dx")
+        del g, gq, dw, db, dxi, zq, dpq, xin
 
 
 # ---------------------------------------------------------------- configuration 3
