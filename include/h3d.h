@@ -116,6 +116,21 @@ h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, const h3d_te
                                  float* dw, float* db, int act, float alpha, void* ws, size_t ws_bytes,
                                  void* stream);
 
+/* ---- backward-filter without a workspace argument and without any allocation ----
+ * For callers that cannot allocate device memory or size a workspace: code under HIP graph capture, tight serving /
+ * training loops, harnesses that forbid hipMalloc.  Same arguments, kernels, results (bit for bit) and errors as
+ * h3d_conv3d_bwd_filter; the per-chunk partial sums of the split-spatial reduction go to a device array of
+ * h3d_static_scratch_bytes() bytes (64 MiB) that the library owns: one copy per GPU it runs on, held until the process
+ * ends, its address looked up once per device by h3d_create.  Shapes whose h3d_conv3d_workspace_bytes(BWD_FILTER)
+ * exceeds that size are rejected with H3D_EWORKSPACE before anything is launched (then use the call above).  The call
+ * allocates and frees nothing, on the host or the device, and does not synchronise.  Every call on a GPU shares that
+ * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race and must be serialised by the
+ * caller; nothing needs to be cleared between calls (the second stage reads only what the first stage of the same call
+ * wrote).  The handle must belong to the current device (H3D_EINVAL otherwise). */
+size_t h3d_static_scratch_bytes(void);
+h3d_status h3d_conv3d_bwd_filter_static(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z,
+                                        float* dw, float* db, int act, float alpha, void* stream);
+
 /* ---- 3x3x3 convolution with a stride of 2 (Table I: the fourth convolution of the CosmoFlow network) ----
  * "Same" padding is read as one zero voxel on every side, as for the stride-1 layers, so an even extent is halved
  * (an odd h or w is rounded up):  y[n,co,p] = act(bias[co] + sum_{ci,k} w[co,ci,k] * x~[n,ci,2p+k-1]).

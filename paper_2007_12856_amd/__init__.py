@@ -53,6 +53,8 @@ _SIGNATURES = {
     "h3d_conv3d_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
+    "h3d_static_scratch_bytes": (ctypes.c_size_t, []),
+    "h3d_conv3d_bwd_filter_static": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_conv3d_s2_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
     "h3d_conv3d_s2_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_s2_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
@@ -303,6 +305,18 @@ def h3d_conv3d_bwd_filter(x: Slab, dz: Slab, z: Slab | None, dw, db, act: int = 
     return dw, db
 
 
+def h3d_static_scratch_bytes() -> int:
+    return int(lib().h3d_static_scratch_bytes())
+
+
+def h3d_conv3d_bwd_filter_static(x: Slab, dz: Slab, z: Slab | None, dw, db, act: int = ACT_NONE, alpha: float = 0.0):
+    """Backward-filter on the library's own scratch array: no workspace is passed, nothing is allocated."""
+    _check(lib().h3d_conv3d_bwd_filter_static(handle(), ctypes.byref(x.desc()), ctypes.byref(dz.desc()),
+                                              ctypes.byref(z.desc()) if z is not None else None, _ptr(dw), _ptr(db), act, alpha,
+                                              _stream()))
+    return dw, db
+
+
 def h3d_conv3d_s2_workspace_bytes(op: int, x: Slab, y: Slab) -> int:
     return int(lib().h3d_conv3d_s2_workspace_bytes(handle(), op, ctypes.byref(x.desc()), ctypes.byref(y.desc())))
 
@@ -546,6 +560,7 @@ def h3d_probe_read(buf, sink) -> int:
 # short aliases
 bn_stats, bn_finalize, bn_fwd, bn_bwd_stats, bn_bwd = h3d_bn_stats, h3d_bn_finalize, h3d_bn_fwd, h3d_bn_bwd_stats, h3d_bn_bwd
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
+conv3d_bwd_filter_static, static_scratch_bytes = h3d_conv3d_bwd_filter_static, h3d_static_scratch_bytes
 conv3d_s2_fwd, conv3d_s2_bwd_data, conv3d_s2_bwd_filter = h3d_conv3d_s2_fwd, h3d_conv3d_s2_bwd_data, h3d_conv3d_s2_bwd_filter
 conv3d_k5_fwd, conv3d_k5_bwd_data, conv3d_k5_bwd_filter = h3d_conv3d_k5_fwd, h3d_conv3d_k5_bwd_data, h3d_conv3d_k5_bwd_filter
 pool3d_fwd, pool3d_bwd, act_bwd, pool3d_bwd_act = h3d_pool3d_fwd, h3d_pool3d_bwd, h3d_act_bwd, h3d_pool3d_bwd_act

@@ -9,11 +9,18 @@
 
 namespace h3d {
 
+h3d_status fail(void* handle, h3d_status st, const char* fmt, ...);
+
 struct Handle {
   int device = 0;
   int num_cu = 256;
+  void* scratch = nullptr;    // this device's copy of the library-owned scratch array (static_scratch.hip)
   char err[512] = {0};
 };
+
+// size of the library-owned scratch array behind h3d_conv3d_bwd_filter_static
+#define H3D_STATIC_SCRATCH_BYTES (64u << 20)
+h3d_status static_scratch_init(Handle* hd);
 
 // Slab geometry as the kernels see it (element strides, not bytes).
 struct Geo {

@@ -93,6 +93,10 @@ extern "C" h3d_status h3d_create(void** handle) {
   hd->device = dev;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, dev) == hipSuccess) hd->num_cu = prop.multiProcessorCount;
+  if (static_scratch_init(hd) != H3D_OK) {
+    delete hd;
+    return H3D_EHIP;
+  }
   *handle = hd;
   return H3D_OK;
 }
