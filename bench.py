@@ -1,21 +1,31 @@
 #!/usr/bin/env python3
-"""Benchmark of the conv3d hot path on one MI355X.
+"""Benchmark of the conv3d hot path on one MI355X: all five benchmark configurations in one run.
 
-Workload (default): the CosmoFlow-shaped network step — N=4 samples of 4x128^3, five
-conv3d 3x3x3 + leaky-ReLU + 2x2x2 avg-pool stages (16..256 channels), dense 16384-2048-256-4,
-MSE; bf16 storage, fp32 accumulation; forward + backward (BD and BF of every layer).
-A step = one pass of that whole path over one synthetic batch already resident in HBM.
+A "step" is one pass of the whole hot path of a configuration over one synthetic batch already resident in HBM:
+  unet      (configuration 4, the headline: the largest single-GPU configuration, 8.2 TFlop per step) the U-Net-shaped
+            level on a 64x256x256 shard of a 256^3 volume, bf16, forward + backward;
+  cosmoflow (configuration 2) the CosmoFlow-shaped stack, N=4 x 4x128^3, bf16, forward + backward;
+  shard512  (configuration 3) conv 4->16 + leaky-ReLU + avg-pool + halo faces on one 8-way depth shard of a 4x512^3 sample;
+  late256   (configuration 5) the weight-gradient-bound late layer, N=8, 256->256 channels on 16^3;
+  single32  (configuration 1) one fp32 layer, 4->16 channels on 32^3 (the correctness-sized case).
+For each: W warm-up steps, then EXACTLY K timed steps between two device synchronisations (wall clock), then P >= 10
+passes with one HIP-event pair per library call (recorded on the launch stream) whose medians fill the per-call table.
 
-Prints ONE JSON line: conv3d fwd+bwd TFLOP/s of the step (conv flops by Table I's convention,
-2*27*Cin*Cout per output voxel and pass, divided by the whole step time), voxels/s, a per-call
-table, the roofline of the dominant call (timed with HIP events inside the timed region) and
-the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line.  Headline: conv3d fwd+bwd TFLOP/s of the U-Net-shaped level (conv flops by Table I's convention,
+2*27*Cin*Cout per output voxel and pass, over the whole step time), voxels/s, `configs` with the same figures, a
+per-call table and a per-kernel table for every configuration (fractions of the published peaks AND of the ceilings
+measured in this run by the calibration probes), `roofline` for the kernel with the largest total time in the headline
+step (HIP events around its calls inside the timed region), and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import hashlib
 import json
 import os
+import statistics
+import subprocess
 import sys
 import time
 
@@ -26,10 +36,13 @@ PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_FP32_VALU_TFLOPS = 157.3
 RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+ALL = ["unet", "cosmoflow", "shard512", "late256", "single32"]
+OTHERS = ["table1", "chain512", "k5", "split256", "bn"]
 
 
+# ----------------------------------------------------------------------------------------------- CPU baseline
 def cpu_baseline(seed):
-    """The oracle, as it stands, on a bounded sample: stage 2 of the stack (16->32 channels on 64^3),
+    """The oracle, as it stands, on a bounded sample: stage 2 of the CosmoFlow-shaped stack (16->32 channels on 64^3),
     the whole batch of four samples, all three passes (FP, BD, BF): about 10 s on the GPU machine's host cores."""
     import numpy as np
     import oracle as orc
@@ -46,175 +59,401 @@ def cpu_baseline(seed):
     dt = time.time() - t0
     flops = 3 * orc.conv_flops(16, 32, 4 * 64 ** 3)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "stage-2 conv (16->32 ch, 64^3, 4 samples) fwd+bwd_data+bwd_filter, fp64 direct loops",
+            "sample": "conv 16->32 ch on 64^3, 4 samples (stage 2 of the CosmoFlow-shaped stack), fwd+bwd_data+bwd_filter, fp64 direct loops",
             "seconds": round(dt, 2), "voxels_per_s": 4 * 64 ** 3 / dt}
 
 
-def side_workload(args, seed):
-    """Per-call tables for the other configurations (not the headline line)."""
+# ----------------------------------------------------------------------------------------------- calibration probes
+class Probes:
+    """ctypes view of libbench_probes.so (bench_probes.hip beside this file; built here when missing)."""
+
+    def __init__(self):
+        path = os.path.join(ROOT, "libbench_probes.so")
+        if not os.path.exists(path):
+            from paper_2007_12856_amd import build
+            build.build_probes()
+        L = ctypes.CDLL(path)
+        P = ctypes.c_void_p
+        L.bp_mfma_scratch_bytes.restype = ctypes.c_size_t
+        L.bp_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, P, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), P]
+        L.bp_read.argtypes = [P, ctypes.c_size_t, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, P]
+        L.bp_write.argtypes = [P, ctypes.c_size_t, ctypes.c_int, P]
+        L.bp_copy.argtypes = [P, P, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, P]
+        self.L = L
+
+    @staticmethod
+    def _stream():
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def mfma(self, shape, iters, scratch):
+        fl = ctypes.c_double(0.0)
+        rc = self.L.bp_mfma_bf16(shape, iters, ctypes.c_void_p(scratch.data_ptr()), scratch.numel() * scratch.element_size(),
+                                 ctypes.byref(fl), self._stream())
+        assert rc == 0, rc
+        return fl.value
+
+    def read(self, buf, sink, blocks, unroll=8, contig=0):
+        rc = self.L.bp_read(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), ctypes.c_void_p(sink.data_ptr()),
+                            blocks, unroll, contig, self._stream())
+        assert rc == 0, rc
+
+    def write(self, buf, blocks):
+        rc = self.L.bp_write(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), blocks, self._stream())
+        assert rc == 0, rc
+
+    def copy(self, src, dst, blocks, unroll=8):
+        rc = self.L.bp_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), src.numel() * src.element_size(),
+                            blocks, unroll, self._stream())
+        assert rc == 0, rc
+
+
+def _timed(fn, reps):
+    import torch
+    fn(0)
+    fn(1)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for r in range(reps):
+        fn(r)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def calibrate(full=False):
+    """What this device sustains under the simplest load: register-only bf16 MFMA loops (both tile shapes), a streaming
+    read, write and copy of buffers far larger than the 256 MB last-level cache (rotated).  `full` sweeps grid sizes,
+    loads in flight and access order of the read probe."""
+    import torch
+    pr = Probes()
+    res = {"device": torch.cuda.get_device_name(0)}
+    scratch = torch.ones(pr.L.bp_mfma_scratch_bytes() // 4 + 4, dtype=torch.float32, device="cuda")
+    for shape, nm in ((0, "mfma_16x16x32_bf16_tflops"), (1, "mfma_32x32x16_bf16_tflops")):
+        fl = []
+        ms = _timed(lambda r: fl.append(pr.mfma(shape, 4096, scratch)), 5)
+        res[nm] = round(fl[0] / ms / 1e9, 1)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    big = [torch.ones(1 << 28, dtype=torch.float32, device="cuda") for _ in range(3)]      # 3 x 1 GiB, rotated
+    nb = 1 << 30
+    if full:
+        sweep = {}
+        for blocks in (1024, 2048, 4096, 8192, 16384, 65536):
+            for un in (4, 8, 16):
+                for contig in (0, 1):
+                    ms = _timed(lambda r: pr.read(big[r % 3], sink, blocks, un, contig), 6)
+                    sweep[f"blocks{blocks}_inflight{un}_{'contig' if contig else 'stride'}"] = round(nb / ms / 1e6, 1)
+        res["read_sweep_gbs"] = sweep
+        res["read_1GiB_gbs"] = max(sweep.values())
+    else:
+        res["read_1GiB_gbs"] = round(max(nb / _timed(lambda r: pr.read(big[r % 3], sink, b, u, 0), 6) / 1e6 for b, u in ((2048, 8), (8192, 8))), 1)
+    res["write_1GiB_gbs"] = round(max(nb / _timed(lambda r: pr.write(big[r % 3], b), 6) / 1e6 for b in (2048, 8192)), 1)
+    res["copy_1GiB_gbs_read_plus_written"] = round(max(2 * nb / _timed(lambda r: pr.copy(big[r % 3], big[(r + 1) % 3], b, 8), 6) / 1e6
+                                                       for b in (2048, 8192)), 1)
+    res["published_peaks"] = {"mfma_bf16_tflops": PEAK_MFMA_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}
+    del big
+    torch.cuda.empty_cache()
+    return res
+
+
+# ----------------------------------------------------------------------------------------------- workloads
+def _randn(gen, shape, dtype, scale=1.0):
+    import torch
+    return (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(dtype)
+
+
+def _cosmo_field(gen, shape, dtype):
+    """log(1 + k), k ~ Poisson(exp(g)), g ~ N(0,1) clipped to +-3: the CosmoFlow stand-in of synth/, drawn on the GPU."""
+    import torch
+    g = torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).clamp_(-3.0, 3.0)
+    return torch.log1p(torch.poisson(torch.exp(g), generator=gen)).to(dtype)
+
+
+def _single_layer(seed, n, cin, cout, d, hw, d_offset, d_global, dtype, field="normal", pool=True, **kw):
+    """Harness inputs of one layer on a shard (seeded, drawn on the GPU): x with one halo plane per side, weights
+    U[+-sqrt(3/fan_in)], bias U[+-0.1], the gradient slab g ~ N(0,1) with one halo plane per side, pooled gradient."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    from paper_2007_12856_amd.nets import SingleLayer
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    xs = (n, cin, d + 2, hw, hw)
+    x = h3d.Slab(_cosmo_field(gen, xs, dtype) if field == "cosmo" else _randn(gen, xs, dtype), 1, 1, d_offset, d_global)
+    bound = (3.0 / (27 * cin)) ** 0.5
+    w = ((torch.rand((cout, cin, 3, 3, 3), generator=gen, device="cuda") * 2 - 1) * bound).to(dtype)
+    b = torch.rand((cout,), generator=gen, device="cuda") * 0.2 - 0.1
+    g = h3d.Slab(_randn(gen, (n, cout, d + 2, hw, hw), dtype), 1, 1, d_offset, d_global)
+    dp = h3d.Slab(_randn(gen, (n, cout, d // 2, hw // 2, hw // 2), dtype), 0, 0, d_offset // 2, d_global // 2) if pool else None
+    return SingleLayer(x, w, b, g, dp, pool=pool, **kw)
+
+
+def build_workload(name, args, seed):
+    """(net, description, network-input voxels per step, storage dtype)."""
     import numpy as np
     import torch
     import synth
     from synth import recipes
     import paper_2007_12856_amd as h3d
-    from paper_2007_12856_amd.nets import SingleLayer, UNetLevel
+    from paper_2007_12856_amd import nets
     bf = torch.bfloat16
-    if args.workload == "shard512":
-        net = SingleLayer(1, 4, 16, 64, 512, 64, 512, seed=seed, faces_hw=True)
-        name = "one 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky + avg-pool, D halo faces; H and W faces of g"
-    elif args.workload == "split256":
-        net = SingleLayer(1, 64, 64, 32, 256, 32, 256, pool=False, seed=seed, split=True)
-        name = "one 8-way depth shard of a 64-channel 256^3 sample: conv 64->64 whole, and as main planes + two 1-plane strips"
-    elif args.workload == "bn":
-        from paper_2007_12856_amd.nets import BatchNormLayer
-        net = BatchNormLayer(4, 16, 128, 128, seed=seed)
-        name = "local batch-normalisation passes on the first convolution's output: 4 x 16 x 128^3 bf16"
-    elif args.workload == "table1":
-        # the seven convolutions of Table I (fourth one with a stride of 2, no convolution biases, pooling until the
-        # volume is 2^3), dense head 2048-256-4, on whole samples of --width^3 (128 or 256)
-        from paper_2007_12856_amd.nets import CosmoFlowStack
-        dev = lambda a, dt=bf: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+    dev = lambda a, dt=bf: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
+    if name == "unet":
+        # shapes and distributions of synth.recipes.unet_level_inputs (interior shard, d_offset 64 of 256), drawn on the GPU
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        P = {k: recipes.conv_params(seed, 310 + 2 * i, ci, co, taps=8 if k == "up" else 27, transposed=(k == "up"))
+             for i, (k, (ci, co)) in enumerate(recipes.UNET_WIDTHS.items())}
+        x = _randn(gen, (1, 1, 68, 256, 256), bf)
+        dout = _randn(gen, (1, 64, 64, 256, 256), bf)
+        spec = {"p": (64, 2, 2, True), "cat": (128, 1, 1, True), "g6": (64, 1, 1, False), "g4": (128, 1, 2, False),
+                "g3": (64, 1, 2, False), "g2": (64, 1, 1, False), "g1": (32, 1, 1, False)}
+        faces = {}
+        for k, (c, width, level, nonneg) in spec.items():
+            pair = [_randn(gen, (1, c, width, 256 // level, 256 // level), bf) for _ in range(2)]
+            faces[k] = tuple(torch.relu(f) if nonneg else f for f in pair)
+        net = nets.UNetLevel(h3d.Slab(x, 2, 2, 64, 256), {k: (dev(w), dev(b, torch.float32)) for k, (w, b) in P.items()}, dout, faces)
+        return net, ("U-Net-shaped level on an interior 64x256x256 shard of a 1-channel 256^3 volume (2-voxel halo), bf16: conv 1-32-64, "
+                     "max-pool, conv 64-64-128, transposed conv 128-64, concat, conv 128-64, ReLU; fwd+bwd"), 64 * 256 * 256, "bf16"
+    if name == "cosmoflow":
+        td = bf if args.dtype == "bf16" else torch.float32
+        P = recipes.cosmoflow_params(seed, args.width)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        x = _cosmo_field(gen, (args.batch, 4, args.width, args.width, args.width), td)       # the recipe of synth.recipes.cosmoflow_batch, on the GPU
+        t = torch.rand((args.batch, 4), generator=gen, device="cuda") * 2 - 1
+        net = nets.CosmoFlowStack(x, t, [(dev(w, td), dev(b, torch.float32)) for w, b in P["conv"]],
+                                  [(dev(w, td), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused)
+        net.overlap = not args.no_overlap
+        return net, (f"CosmoFlow-shaped stack: N={args.batch} x 4x{args.width}^3, conv 16-32-64-128-256 + leaky-ReLU + avg-pool, "
+                     f"dense 2048-256-4, MSE; fwd+bwd; {2 if net.overlap else 1} streams"), args.batch * args.width ** 3, args.dtype
+    if name == "shard512":
+        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", faces_hw=True)
+        return net, ("one interior 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky-ReLU + avg-pool, "
+                     "fwd / bwd-data / bwd-filter, D halo faces packed and unpacked; H and W faces of g"), 64 * 512 * 512, "bf16"
+    if name == "late256":
+        net = _single_layer(seed, 8, 256, 256, 16, 16, 0, 16, bf, pool=False)
+        return net, "weight-gradient-bound late layer: N=8, 256->256 channels, 16^3, bf16, fwd / bwd-data / bwd-filter", 8 * 16 ** 3, "bf16"
+    if name == "single32":
+        net = _single_layer(seed, 1, 4, 16, 32, 32, 0, 32, torch.float32, pool=False)
+        return net, "single layer, fp32: N=1, 4->16 channels, 32^3, bias + leaky-ReLU, fwd / bwd-data / bwd-filter", 32 ** 3, "f32"
+    if name == "split256":
+        net = _single_layer(seed, 1, 64, 64, 32, 256, 32, 256, bf, pool=False, split=True)
+        return net, "one 8-way depth shard of a 64-channel 256^3 sample: conv 64->64 whole, and as main planes + two 1-plane strips", 32 * 256 * 256, "bf16"
+    if name == "bn":
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        net = nets.BatchNormLayer(h3d.Slab(_randn(gen, (4, 16, 128, 128, 128), bf)), h3d.Slab(_randn(gen, (4, 16, 128, 128, 128), bf)))
+        return net, "local batch-normalisation passes on the first convolution's output: 4 x 16 x 128^3 bf16", 4 * 128 ** 3, "bf16"
+    if name == "table1":
         channels, strides, pools, flat_w = recipes.table1_layout(args.width)
         P = recipes.cosmoflow_params(seed, args.width, channels, recipes.COSMO_FC, flat_w)
         x, t = recipes.cosmoflow_batch(seed, args.batch, args.width)
-        net = CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), None) for w, _ in P["conv"]],
-                             [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused,
-                             strides=strides, pools=pools)
-        name = (f"network of Table I for {args.width}^3 inputs, N={args.batch}: conv 16-32-64-128(stride 2)-256-256-256, no conv biases, "
-                f"leaky-ReLU, avg-pool, dense 2048-256-4, MSE; fwd+bwd; {net.conv_flops() / args.batch / 1e9:.2f} conv GFlop per sample")
-    elif args.workload == "chain512":
-        # the spatially-partitioned front of Table I's 512^3 network on one interior shard of an 8-way depth partition
-        from paper_2007_12856_amd.nets import CosmoFlowShardChain
-        dev = lambda a, dt=bf: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
-        x, conv, dout, faces = recipes.shard_chain_inputs(seed, 512, 64, 64, 512, n=args.batch)
-        net = CosmoFlowShardChain(h3d.Slab(dev(x), 1, 1, 64, 512), [(dev(w), None) for w, _ in conv], dev(dout),
-                                  {k: (dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
-        name = (f"conv1-pool1 .. conv3-pool3 of Table I's 512^3 network on one interior shard of an 8-way depth partition "
-                f"(N={args.batch} x 4x(64+2)x512x512 bf16), halo faces packed and unpacked per stage, fwd+bwd")
-    elif args.workload == "xent":
-        # segmentation loss on the output shard of the U-Net shape: 3 classes, 64 x 256 x 256 voxels of a 256^3 volume
-        class _Xent:
-            def __init__(self):
-                g = torch.Generator(device="cuda")
-                g.manual_seed(seed)
-                z = h3d.Slab((3.0 * torch.randn((1, 3, 64, 256, 256), generator=g, device="cuda")).to(bf), 0, 0, 64, 256)
-                lab = torch.randint(0, 3, (1, 64, 256, 256), generator=g, device="cuda", dtype=torch.uint8)
-                dz, loss, ws = h3d.Slab(torch.empty_like(z.t), 0, 0, 64, 256), torch.zeros(1, device="cuda"), h3d.Workspace()
-                nb = 2 * z.t.numel() * 2 + lab.numel()
-                self.keep = (z, lab, dz, loss)
-                self.ops = [{"name": "softmax_xent_fwd_bwd", "fn": lambda: h3d.softmax_xent_fwd_bwd(z, lab, 256 ** 3, loss, dz, ws),
-                             "flops": 0, "bytes": nb}]
-
-            def step(self):
-                self.ops[0]["fn"]()
-
-            def conv_flops(self):
-                return 0
-        net = _Xent()
-        name = "softmax cross-entropy, forward + gradient, 3 classes on a 64x256x256 shard of a 256^3 volume, bf16"
-    elif args.workload == "k5":
-        # 5x5x5 filters (two halo planes): conv 32 -> 32 on a 32-plane interior shard of a 128^3 volume, the three passes
-        class _K5:
-            def __init__(self):
-                g = torch.Generator(device="cuda")
-                g.manual_seed(seed)
-                rnd = lambda *sh: torch.randn(sh, generator=g, device="cuda")
-                ci = co = 32
-                geo = (2, 2, 32, 128)
-                x = h3d.Slab(rnd(1, ci, 36, 128, 128).to(bf), *geo)
-                z = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
-                dz = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
-                dx = h3d.Slab(torch.empty_like(x.t), *geo)
-                zo = h3d.Slab(torch.empty_like(z.t), *geo)
-                w = (rnd(co, ci, 5, 5, 5) * (2.0 / (125 * ci)) ** 0.5).to(bf)
-                b = torch.zeros(co, device="cuda")
-                dw, db = torch.empty((co, ci, 5, 5, 5), device="cuda"), torch.empty(co, device="cuda")
-                ws = h3d.Workspace()
-                fl = 2 * 125 * ci * co * 32 * 128 * 128
-                nb = 2 * 36 * 128 * 128 * 2 * ci
-                self.keep = (x, z, dz, dx, zo, w, b, dw, db)
-                self.ops = [
-                    {"name": "k5_fwd", "fn": lambda: h3d.conv3d_k5_fwd(x, w, b, zo, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb},
-                    {"name": "k5_bwd_data", "fn": lambda: h3d.conv3d_k5_bwd_data(dz, z, w, dx, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
-                    {"name": "k5_bwd_filter", "fn": lambda: h3d.conv3d_k5_bwd_filter(x, dz, z, dw, db, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
-                ]
-
-            def step(self):
-                for o in self.ops:
-                    o["fn"]()
-
-            def conv_flops(self):
-                return sum(o["flops"] for o in self.ops)
-        net = _K5()
-        name = "5x5x5 convolution 32->32, 32-plane interior shard (+2 halo planes per side) of a 128^3 volume, bf16, three passes"
-    elif args.workload == "late256":
-        net = SingleLayer(8, 256, 256, 16, 16, 0, 16, pool=False, seed=seed)
-        name = "late layer N=8, 256->256, 16^3 bf16"
-    else:
-        dev = lambda a, dt=bf: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
-        x, P, dout, faces = recipes.unet_level_inputs(seed, 256, 64, 64, 256)
-        net = UNetLevel(h3d.Slab(dev(x), 2, 2, 64, 256), {k: (dev(w), dev(b, torch.float32)) for k, (w, b) in P.items()},
-                        dev(dout), {k: tuple(None if f is None else dev(f) for f in pr) for k, pr in faces.items()})
-        name = "U-Net-shaped level on a 64x256x256 shard of a 256^3 volume (halo 2), bf16, fwd+bwd"
-    stream = torch.cuda.current_stream()
-    if hasattr(net, "overlap") and not args.only:
-        # the stack's second stream (late backward-filter calls, dense weight gradients): their table rows then show the
-        # launch only, the "join" row the wait for them
+        net = nets.CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), None) for w, _ in P["conv"]],
+                                  [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused,
+                                  strides=strides, pools=pools)
         net.overlap = not args.no_overlap
-    for _ in range(args.warmup):
+        return net, (f"network of Table I for {args.width}^3 inputs, N={args.batch}: conv 16-32-64-128(stride 2)-256-256-256, no conv biases, "
+                     f"leaky-ReLU, avg-pool, dense 2048-256-4, MSE; fwd+bwd; {net.conv_flops() / args.batch / 1e9:.2f} conv GFlop per sample"), \
+            args.batch * args.width ** 3, "bf16"
+    if name == "chain512":
+        x, conv, dout, faces = recipes.shard_chain_inputs(seed, 512, 64, 64, 512, n=args.batch)
+        net = nets.CosmoFlowShardChain(h3d.Slab(dev(x), 1, 1, 64, 512), [(dev(w), None) for w, _ in conv], dev(dout),
+                                       {k: (dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
+        return net, (f"conv1-pool1 .. conv3-pool3 of Table I's 512^3 network on one interior shard of an 8-way depth partition "
+                     f"(N={args.batch} x 4x(64+2)x512x512 bf16), halo faces packed and unpacked per stage, fwd+bwd"), args.batch * 64 * 512 * 512, "bf16"
+    if name == "k5":
+        return _k5_workload(seed), "5x5x5 convolution 32->32, 32-plane interior shard (+2 halo planes per side) of a 128^3 volume, bf16, three passes", \
+            32 * 128 * 128, "bf16"
+    raise SystemExit(f"bench.py: unknown workload {name}")
+
+
+def _k5_workload(seed):
+    import torch
+    import paper_2007_12856_amd as h3d
+    bf = torch.bfloat16
+
+    class _K5:
+        def __init__(self):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(seed)
+            rnd = lambda *sh: torch.randn(sh, generator=g, device="cuda")
+            ci = co = 32
+            geo = (2, 2, 32, 128)
+            x = h3d.Slab(rnd(1, ci, 36, 128, 128).to(bf), *geo)
+            z = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
+            dz = h3d.Slab(rnd(1, co, 36, 128, 128).to(bf), *geo)
+            dx = h3d.Slab(torch.empty_like(x.t), *geo)
+            zo = h3d.Slab(torch.empty_like(z.t), *geo)
+            w = (rnd(co, ci, 5, 5, 5) * (2.0 / (125 * ci)) ** 0.5).to(bf)
+            b = torch.zeros(co, device="cuda")
+            dw, db = torch.empty((co, ci, 5, 5, 5), device="cuda"), torch.empty(co, device="cuda")
+            ws = h3d.Workspace()
+            fl = 2 * 125 * ci * co * 32 * 128 * 128
+            nb = 2 * 36 * 128 * 128 * 2 * ci
+            self.keep = (x, z, dz, dx, zo, w, b, dw, db)
+            self.ops = [
+                {"name": "k5_fwd", "fn": lambda: h3d.conv3d_k5_fwd(x, w, b, zo, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb},
+                {"name": "k5_bwd_data", "fn": lambda: h3d.conv3d_k5_bwd_data(dz, z, w, dx, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
+                {"name": "k5_bwd_filter", "fn": lambda: h3d.conv3d_k5_bwd_filter(x, dz, z, dw, db, h3d.ACT_LEAKY, 0.01, ws), "flops": fl, "bytes": nb * 3 // 2},
+            ]
+
+        def step(self):
+            for o in self.ops:
+                o["fn"]()
+
+        def conv_flops(self):
+            return sum(o["flops"] for o in self.ops)
+    return _K5()
+
+
+# ----------------------------------------------------------------------------------------------- measurement
+def lib_source_hash():
+    """sha16 over the HIP sources of the library: a stored traffic figure only counts for the code it was measured on."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2007_12856_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` in `workload`, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE) scaled by
+    the plain-copy factors: the line 'TRAFFIC <workload> <kernel> <bytes per launch> <source hash>' of profiles/hbm_traffic.txt
+    (commands and raw counter values in that file).  None when there is no line for this kernel or when the library's sources
+    have changed since it was measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    cur = lib_source_hash()
+    for line in open(path):
+        f = line.split()
+        if len(f) == 5 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == kernel and f[4] == cur:
+            return int(f[3])
+    return None
+
+
+def fractions(flops, nbytes, ms, ceil):
+    """TFLOP/s, GB/s and their fractions of the published peaks and of the ceilings measured by the probes."""
+    out = {}
+    if flops:
+        tf = flops / ms / 1e9
+        out.update(tflops=round(tf, 2), mfma_frac=round(tf / PEAK_MFMA_BF16_TFLOPS, 4))
+        if ceil:
+            out["mfma_frac_of_measured"] = round(tf / ceil["mfma_32x32x16_bf16_tflops"], 4)
+    if nbytes:
+        gb = nbytes / ms / 1e6
+        out.update(gbs=round(gb, 1), hbm_frac=round(gb / PEAK_HBM_GBS, 4))
+        if ceil:
+            out["hbm_frac_of_measured"] = round(gb / ceil["copy_1GiB_gbs_read_plus_written"], 4)
+    if flops or nbytes:
+        out["bound"] = "mfma" if flops and flops / max(nbytes, 1) >= RIDGE else "hbm"
+    return out
+
+
+def run_workload(name, args, seed, ceil, steps, warmup, passes, events_for=None):
+    """Warm-up, K timed steps (wall clock between two synchronisations), `passes` per-call passes (HIP events on the launch
+    stream, medians).  Returns the result dict; `events_for(kernel_table)` (headline only) picks the kernel whose calls get an
+    event pair inside the timed region."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    t_build = time.perf_counter()
+    net, label, voxels, dtype = build_workload(name, args, seed)
+    t_build = time.perf_counter() - t_build
+    stream = torch.cuda.current_stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    overlap = getattr(net, "overlap", False)
+    for _ in range(max(warmup, 1)):
         net.step()
     torch.cuda.synchronize()
-    if args.only:
-        sel = [o for o in net.ops if o["name"] == args.only]
-        if not sel:
-            sys.exit(f"bench.py: --only must be one of {[o['name'] for o in net.ops]}")
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(args.steps):
-            sel[0]["fn"]()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
-        print(json.dumps({"metric": "single call", "kernel": args.only, "ms": ms, "steps": args.steps,
-                          "tflops": sel[0]["flops"] / ms / 1e9, "config": {"workload": name}}))
-        return
-    tot = {o["name"]: 0.0 for o in net.ops}
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    # which kernel does each call run (asked of the library after the call)
+    kernels = []
+    for o in net.ops:
+        o["fn"]()
+        kernels.append(h3d.h3d_last_kernel() if (o["flops"] or o["bytes"]) else "")
+    torch.cuda.synchronize()
+
+    def per_call_pass():
         evs = []
         for o in net.ops:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = ev(), ev()
             e0.record(stream)
             o["fn"]()
             e1.record(stream)
-            evs.append((o, e0, e1))
+            evs.append((e0, e1))
         torch.cuda.synchronize()
-        for o, e0, e1 in evs:
-            tot[o["name"]] += e0.elapsed_time(e1)
-    dt = time.perf_counter() - t0
+        return [a.elapsed_time(b) for a, b in evs]
+
+    # the per-call passes run on ONE stream so that every call is timed alone
+    if overlap:
+        net.overlap = False
+    per_call_pass()
+    samples = [per_call_pass() for _ in range(passes)]
+    med = [statistics.median(s[i] for s in samples) for i in range(len(net.ops))]
+    if overlap:
+        net.overlap = True
+        net.step()
+        torch.cuda.synchronize()
+    # kernel table: calls grouped by the kernel the library ran for them
+    groups = {}
+    for o, k, ms in zip(net.ops, kernels, med):
+        if not k:
+            continue
+        g = groups.setdefault(k, {"kernel": k, "calls": [], "ms": 0.0, "flops": 0, "bytes": 0})
+        g["calls"].append(o["name"])
+        g["ms"] += ms
+        g["flops"] += o["flops"]
+        g["bytes"] += o["bytes"]
+    ktable = sorted(groups.values(), key=lambda g: -g["ms"])
+    dom = events_for(ktable) if events_for else None
+    dom_idx = [i for i, k in enumerate(kernels) if dom and k == dom["kernel"]]
+    dom_ev = []
+    # ---- timed region: exactly K steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        if dom_idx:
+            for i, o in enumerate(net.ops):
+                if i in dom_idx:
+                    e0, e1 = ev(), ev()
+                    e0.record(stream)
+                    o["fn"]()
+                    e1.record(stream)
+                    dom_ev.append((i, e0, e1))
+                else:
+                    o["fn"]()
+        else:
+            net.step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    flops = net.conv_flops()
     per_call = []
-    for o in net.ops:
-        ms = tot[o["name"]] / args.steps
-        per_call.append({"name": o["name"], "ms": round(ms, 4), "tflops": round(o["flops"] / ms / 1e9, 1) if o["flops"] else None,
-                         "gbs": round(o["bytes"] / ms / 1e6, 1) if o["bytes"] else None})
-    ms_step = sum(tot.values()) / args.steps
-    print(json.dumps({"metric": "conv3d fwd+bwd TFLOP/s", "value": net.conv_flops() / ms_step / 1e9, "unit": "TFLOP/s", "n_gpus": 1,
-                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "dtype": "bf16", "data": "synthetic",
-                      "config": {"workload": name}, "per_call": per_call}))
-
-
-def measured_traffic(workload, call):
-    """HBM bytes per launch of `call`, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the
-    plain-copy factors; read from the 'TRAFFIC <call> <bytes>' lines of profiles/<workload>_step_hbm_traffic.txt.
-    None when no measurement of that call is on record."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_step_hbm_traffic.txt")
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        f = line.split()
-        if len(f) == 3 and f[0] == "TRAFFIC" and f[1] == call:
-            return int(f[2])
-    return None
+    for o, k, ms in zip(net.ops, kernels, med):
+        row = {"name": o["name"], "ms": round(ms, 4)}
+        if k:
+            row["kernel"] = k
+        row.update(fractions(o["flops"], o["bytes"], ms, ceil))
+        per_call.append(row)
+    for g in ktable:
+        g.update(fractions(g["flops"], g["bytes"], g["ms"], ceil))
+        g["ms"] = round(g["ms"], 4)
+        g["share_of_step"] = round(g["ms"] / sum(med), 4)
+    res = {"workload": label, "dtype": dtype, "ms_per_step": round(ms_per_step, 4), "ms_per_step_sum_of_calls": round(sum(med), 4),
+           "conv_gflop_per_step": round(flops / 1e9, 2), "tflops": round(flops / ms_per_step / 1e9, 2),
+           "mfma_frac": round(flops / ms_per_step / 1e9 / PEAK_MFMA_BF16_TFLOPS, 4), "voxels_per_s": round(voxels / (ms_per_step * 1e-3), 1),
+           "steps": steps, "passes": passes, "setup_s": round(t_build, 1), "per_kernel": ktable, "per_call": per_call}
+    if dom:
+        per_step = {}
+        for i, a, b in dom_ev:
+            per_step.setdefault(i, []).append(a.elapsed_time(b))
+        launches = len(dom_idx)
+        ms_total = sum(sum(v) / len(v) for v in per_step.values())          # mean over the K steps, summed over the kernel's calls
+        res["dominant"] = {"kernel": dom["kernel"], "calls": [net.ops[i]["name"] for i in dom_idx], "launches_per_step": launches,
+                           "ms_per_launch": ms_total / launches, "flops_per_launch": dom["flops"] / launches, "bytes_per_launch": dom["bytes"] / launches}
+    del net
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -222,197 +461,110 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--passes", type=int, default=11, help="per-call passes whose medians fill the tables (at least 10)")
     ap.add_argument("--batch", type=int, default=4)
     ap.add_argument("--width", type=int, default=128)
-    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"], help="storage type of the cosmoflow workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default=None, help="after warm-up, time only this call of the step (name as in per_call); "
-                    "used to profile one kernel under rocprofv3")
+    ap.add_argument("--no-calibration", action="store_true", help="skip the probes (fractions of the measured ceilings are then absent)")
+    ap.add_argument("--only", default=None, help="with --workload NAME: after warm-up, run only this call of the step (name as in per_call) "
+                    "--steps times; used to profile one kernel under rocprofv3")
     ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
-    ap.add_argument("--unfused", action="store_true", help="store the first stage's unpooled activation (separate conv, pool and "
-                    "pool-backward calls) instead of the fused forward + sign mask")
-    ap.add_argument("--no-overlap", action="store_true", help="keep every call of the step on one stream (default: the backward-filter "
-                    "calls of stages 2.. run on a second stream beside the backward-data chain)")
-    ap.add_argument("--calibrate", action="store_true", help="print what this device sustains under the simplest load: a register-only "
-                    "bf16 MFMA loop (both tile shapes), a streaming read of 1 GiB and of 64 MiB, and a plain copy")
+    ap.add_argument("--unfused", action="store_true", help="cosmoflow / table1 / chain512: store the first stage's unpooled activation "
+                    "(separate conv, pool and pool-backward calls) instead of the fused forward + sign mask")
+    ap.add_argument("--no-overlap", action="store_true", help="cosmoflow / table1: keep every call of the step on one stream (default: the "
+                    "backward-filter calls of the late stages run on a second stream beside the backward-data chain)")
+    ap.add_argument("--calibrate", action="store_true", help="print only what this device sustains under the simplest load (with a sweep of "
+                    "the read probe's grid size, loads in flight and access order)")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--workload", default="cosmoflow", choices=["cosmoflow", "table1", "chain512", "xent", "k5", "shard512", "unet", "late256", "split256", "bn"],
-                    help="cosmoflow (default, the metric's configuration); the others print per-call tables of the "
-                         "512^3 first-layer shard, the U-Net-shaped level and the 256->256 late layer")
+    ap.add_argument("--workload", default="all", choices=["all"] + ALL + OTHERS,
+                    help="all (default): the five benchmark configurations, headline on the U-Net-shaped level; one name: that workload alone")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the per-GPU share of the spatially-partitioned path); "
                  "--gpus must be 1")
 
-    import numpy as np
     import torch
     import synth
-    from synth import recipes
     import paper_2007_12856_amd as h3d
-    from paper_2007_12856_amd.nets import CosmoFlowStack
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     h3d.lib()   # fail loudly if the HIP library is not built
+    seed = synth.BASE_SEED if args.seed is None else args.seed
     if args.calibrate:
-        ev = lambda: torch.cuda.Event(enable_timing=True)
-
-        def timed(fn, reps):
-            fn(0)
-            fn(1)
-            torch.cuda.synchronize()
-            e0, e1 = ev(), ev()
-            e0.record()
-            for r in range(reps):
-                fn(r)
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
-        scratch = torch.ones(h3d.probe_mfma_scratch_bytes() // 4, dtype=torch.float32, device="cuda")
-        res = {"metric": "calibration", "device": torch.cuda.get_device_name(0)}
-        for shape, nm in ((0, "mfma_16x16x32_bf16_tflops"), (1, "mfma_32x32x16_bf16_tflops")):
-            fl = []
-            ms = timed(lambda r: fl.append(h3d.probe_mfma_bf16(shape, 4096, scratch)), 5)
-            res[nm] = round(fl[0] / ms / 1e9, 1)
-        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-        big = [torch.ones(1 << 28, dtype=torch.float32, device="cuda") for _ in range(3)]      # 3 x 1 GiB, rotated
-        ms = timed(lambda r: h3d.probe_read(big[r % 3], sink), 9)
-        res["read_1GiB_gbs"] = round((1 << 30) / ms / 1e6, 1)
-        small = [b[i * (1 << 24):(i + 1) * (1 << 24)] for b in big for i in range(16)]             # 48 x 64 MiB, rotated
-        ms = timed(lambda r: h3d.probe_read(small[(7 * r) % 48], sink), 48)
-        res["read_64MiB_cold_gbs"] = round((1 << 26) / ms / 1e6, 1)
-        res["read_64MiB_cold_us"] = round(ms * 1e3, 2)
-        del big, small
-        t = h3d.Slab(torch.randn((1, 16, 64, 512, 512), device="cuda").to(torch.bfloat16))
-        buf = torch.empty_like(t.t)
-        ms = timed(lambda r: h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf), 10)
-        res["copy_gbs"] = round(2 * t.t.numel() * 2 / ms / 1e6, 1)
-        res["published_peaks"] = {"mfma_bf16_tflops": PEAK_MFMA_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}
-        print(json.dumps(res))
+        print(json.dumps({"metric": "calibration", **calibrate(full=True)}))
         return
     if args.copy_ref:
         t = h3d.Slab(torch.randn((1, 16, 64, 512, 512), device="cuda").to(torch.bfloat16))
         buf = torch.empty_like(t.t)
-        for _ in range(args.warmup):
-            h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
+        ms = _timed(lambda r: h3d.halo_pack(t, h3d.FACE_D_LO, 64, buf), args.steps)
         nbytes = 2 * t.t.numel() * 2
         print(json.dumps({"metric": "copy GB/s", "value": nbytes / ms / 1e6, "unit": "GB/s", "ms": ms, "bytes": nbytes,
                           "kernel": "copy_runs_kernel (halo_pack of a whole interior)"}))
         return
-    seed = synth.BASE_SEED if args.seed is None else args.seed
-    td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
-    if args.workload != "cosmoflow":
-        return side_workload(args, seed)
-
-    def dev(a, dt=td):
-        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(dt)
-
-    P = recipes.cosmoflow_params(seed, args.width)
-    x, t = recipes.cosmoflow_batch(seed, args.batch, args.width)
-    net = CosmoFlowStack(dev(x), dev(t, torch.float32), [(dev(w), dev(b, torch.float32)) for w, b in P["conv"]],
-                         [(dev(w), dev(b, torch.float32)) for w, b in P["fc"]], fuse_pool=not args.unfused)
-    del P, x
-    stream = torch.cuda.current_stream()
-
-    # warm-up; the last warm-up step also times every call on its own to find the dominant one
-    for _ in range(max(args.warmup - 1, 0)):
-        net.step()
-    torch.cuda.synchronize()
-    # (two passes back to back, the second one counts: its first call follows a busy GPU like every other call)
-    for _ in range(2):
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in net.ops]
-        for op, (e0, e1) in zip(net.ops, evs):
-            e0.record(stream)
-            op["fn"]()
-            e1.record(stream)
-    torch.cuda.synchronize()
-    per_call = []
-    for op, (e0, e1) in zip(net.ops, evs):
-        ms = e0.elapsed_time(e1)
-        per_call.append({"name": op["name"], "ms": round(ms, 4),
-                         "tflops": round(op["flops"] / ms / 1e9, 2) if op["flops"] and op["name"].startswith("conv") else None,
-                         "gbs": round(op["bytes"] / ms / 1e6, 1) if op["bytes"] else None})
-    dom = max(range(len(net.ops)), key=lambda i: per_call[i]["ms"])
     if args.only:
-        names = [o["name"] for o in net.ops]
-        if args.only not in names:
-            sys.exit(f"bench.py: --only must be one of {names}")
-        dom = names.index(args.only)
-        op = net.ops[dom]
+        if args.workload == "all":
+            sys.exit("bench.py: --only needs --workload NAME")
+        net, label, _, _ = build_workload(args.workload, args, seed)
+        if hasattr(net, "overlap"):
+            net.overlap = False
+        sel = [o for o in net.ops if o["name"] == args.only]
+        if not sel:
+            sys.exit(f"bench.py: --only must be one of {[o['name'] for o in net.ops]}")
+        for _ in range(args.warmup):
+            net.step()
         torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(args.steps):
-            op["fn"]()
+            sel[0]["fn"]()
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
-        print(json.dumps({"metric": "single call", "kernel": op["name"], "ms": ms, "steps": args.steps,
-                          "tflops": op["flops"] / ms / 1e9, "gbs": op["bytes"] / ms / 1e6,
-                          "algorithmic_bytes": op["bytes"], "algorithmic_flops": op["flops"]}))
+        print(json.dumps({"metric": "single call", "call": args.only, "kernel": h3d.h3d_last_kernel(), "ms": ms, "steps": args.steps,
+                          "tflops": sel[0]["flops"] / ms / 1e9, "gbs": sel[0]["bytes"] / ms / 1e6, "algorithmic_bytes": sel[0]["bytes"],
+                          "algorithmic_flops": sel[0]["flops"], "config": {"workload": label}}))
         return
 
-    # the timed steps put the backward-filter calls of stages 2.. on a second stream (joined at the end of every step);
-    # the per-call pass above ran everything on one stream so that every call was timed alone
-    net.overlap = not args.no_overlap
-    net.step()
-    torch.cuda.synchronize()
-    # timed region: exactly K steps; one HIP-event pair per step around the dominant call
-    # (events are recorded on the stream the kernels are launched on)
-    dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        for i, op in enumerate(net.ops):
-            if i == dom:
-                dom_ev[k][0].record(stream)
-                op["fn"]()
-                dom_ev[k][1].record(stream)
-            else:
-                op["fn"]()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    dom_ms = sum(a.elapsed_time(b) for a, b in dom_ev) / args.steps
-
-    flops = net.conv_flops()
-    voxels = args.batch * args.width ** 3
-    op = net.ops[dom]
-    intensity = op["flops"] / max(op["bytes"], 1)
-    if op["flops"] and intensity >= RIDGE:
-        roof = {"bound": "mfma", "achieved": op["flops"] / dom_ms / 1e9, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s"}
-    else:
-        roof = {"bound": "hbm", "achieved": op["bytes"] / dom_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = op["name"]
-    roof["ms"] = round(dom_ms, 4)
-    roof["algorithmic_bytes"] = op["bytes"]
-    roof["algorithmic_flops"] = op["flops"]
-    roof["traffic"] = measured_traffic(args.workload, op["name"])
-
+    ceil = None if args.no_calibration else calibrate()
+    names = ALL if args.workload == "all" else [args.workload]
+    head = names[0]
+    passes = max(args.passes, 10)
+    results = {}
+    for nm in names:
+        results[nm] = run_workload(nm, args, seed, ceil, args.steps, args.warmup, passes,
+                                   events_for=(lambda kt: kt[0] if kt else None) if nm == head else None)
+    H = results[head]
     out = {
-        "metric": "conv3d fwd+bwd TFLOP/s", "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"CosmoFlow-shaped stack fwd+bwd: N={args.batch} x 4x{args.width}^3, conv 16-32-64-128-256 "
-                               f"+ leaky-ReLU + avg-pool, dense 2048-256-4, MSE",
-                   "global_batch": args.batch, "input": [4, args.width, args.width, args.width]},
-        "voxels_per_s": voxels / (ms_per_step * 1e-3),
-        "conv_gflop_per_step": flops / 1e9,
-        "pct_of_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
-        "streams": 1 if args.no_overlap else 2,
-        "roofline": roof,
-        "per_call": per_call,
+        "metric": "conv3d fwd+bwd TFLOP/s", "value": H["tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": H["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": H["dtype"], "data": "synthetic",
+        "config": {"workload": H["workload"], "name": head},
+        "voxels_per_s": H["voxels_per_s"], "conv_gflop_per_step": H["conv_gflop_per_step"],
+        "pct_of_bf16_mfma_peak": round(100.0 * H["mfma_frac"], 2),
     }
+    d = H.get("dominant")
+    if d:
+        ms = d["ms_per_launch"]
+        if d["flops_per_launch"] and d["flops_per_launch"] / max(d["bytes_per_launch"], 1) >= RIDGE:
+            roof = {"bound": "mfma", "achieved": d["flops_per_launch"] / ms / 1e9, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s"}
+            if ceil:
+                roof["frac_of_measured_ceiling"] = roof["achieved"] / ceil["mfma_32x32x16_bf16_tflops"]
+        else:
+            roof = {"bound": "hbm", "achieved": d["bytes_per_launch"] / ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+            if ceil:
+                roof["frac_of_measured_ceiling"] = roof["achieved"] / ceil["copy_1GiB_gbs_read_plus_written"]
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof.update(kernel=d["kernel"], calls=d["calls"], launches_per_step=d["launches_per_step"], ms=round(ms, 4),
+                    algorithmic_bytes=d["bytes_per_launch"], algorithmic_flops=d["flops_per_launch"],
+                    traffic=measured_traffic(head, d["kernel"]))
+        out["roofline"] = roof
+    if ceil:
+        out["measured_ceilings"] = ceil
+    out["configs"] = results
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(seed)
     print(json.dumps(out))

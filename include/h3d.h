@@ -82,6 +82,11 @@ typedef struct {
 h3d_status h3d_create(void** handle);
 h3d_status h3d_destroy(void* handle);
 const char* h3d_last_error(void* handle); /* handle-owned string, valid until the next call */
+/* For measurement tools: the name of the kernel that did the arithmetic of the last successful compute call on this
+ * handle (a call may also launch small helper kernels: weight packing, the ordered second stage of a reduction), as a
+ * profiler's kernel trace spells it, template arguments included where the library chooses among instances; "" before
+ * the first call.  Handle-owned string, valid until the next call. */
+const char* h3d_last_kernel(void* handle);
 
 /* ---- 3x3x3 convolution, stride 1, zero padding 1 (Table I caption; FP/BD/BF of Sec. III-C) ----
  *
@@ -214,13 +219,14 @@ h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tens
 /* ---- convolution forward fused with the 2x2x2 average pooling that follows it, and the matching backward step ----
  * (Sec. III-A: operations that are "normally considered cheap" - pooling, activations - dominate once the tensors
  * are large; here the unpooled activation never has to travel to memory and back.)
+ * AVERAGE pooling only (the CosmoFlow shapes; a max-pooled layer uses the separate calls).
  * y = avgpool(act(b + W * x)): the pooled tensor of the same shard (extents and offsets half of z's, halos allowed,
  * interior written).  z describes the unpooled output; z->data == NULL means it is not stored (only where a fused
  * kernel exists: bf16, Cin <= 4, Cout <= 32, z without halos, even d and h, w a multiple of 8; otherwise
  * H3D_EUNSUPPORTED) - with z->data set the call works for every shape h3d_conv3d_fwd and h3d_pool3d_fwd accept.
  * mask (DEVICE, h3d_act_mask_bytes(z) bytes, or NULL): one bit per unpooled voxel, set where the stored output is
  * > 0; bit k of byte j of a row is voxel 8 j + k, rows packed [n][c][interior plane][h][w/8].  It replaces z in
- * the backward pass (1/16 of its bytes). */
+ * the backward pass (1/16 of its bytes).  A mask with w not a multiple of 8 is H3D_EUNSUPPORTED, found before any launch. */
 size_t h3d_act_mask_bytes(const h3d_tensor* z);                       /* 0 if w is not a multiple of 8 */
 h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, const void* w, const float* bias, h3d_tensor* z,
                                h3d_tensor* y, void* mask, int act, float alpha,
@@ -301,19 +307,6 @@ h3d_status h3d_dense_bwd(void* handle, const void* x, const void* w, const void*
 h3d_status h3d_mse_fwd_bwd(void* handle, const void* pred, const float* target, float* loss, void* dpred, int dtype,
                            int count, void* stream);
 
-/* ---- per-voxel softmax cross-entropy of a segmentation output (the 3D U-Net's loss; Sec. III-A: the cross-entropy loss
- * is among the components that needed a version for large 3-D data, and the ground truth is partitioned like the
- * activations) ----
- * logits / dlogits: the same shard, c = classes (1..255), packed, either dtype; interiors only, halos untouched.
- * labels: DEVICE uint8 [n][d][h][w] of the shard's interior; a value >= c marks a voxel that has no class: it adds
- * nothing to the loss and its gradient is zero.  count: voxels x samples over ALL shards (the mean's denominator).
- * loss[0] (DEVICE fp32) = -(1/count) * sum over this shard's voxels of log softmax(logits)[label]: the shard's part of
- * the mean (the shards' parts add up; that sum is the caller's allreduce).  dlogits = (softmax - onehot) / count.
- * One streaming pass; fixed-order summation (same bits every run).  Workspace: h3d_softmax_xent_workspace_bytes. */
-size_t h3d_softmax_xent_workspace_bytes(void* handle, const h3d_tensor* logits);
-h3d_status h3d_softmax_xent_fwd_bwd(void* handle, const h3d_tensor* logits, const uint8_t* labels, int64_t count, float* loss,
-                                    h3d_tensor* dlogits, void* ws, size_t ws_bytes, void* stream);
-
 /* ---- batch normalisation, the parts local to a shard (Sec. II-B: partial statistics per partition are aggregated
  * with an allreduce; Sec. III-C: a batch-normalisation layer costs this computation plus the allreduce of the
  * per-channel sum and squared sum).  The allreduce itself is the caller's.  All per-channel arrays are fp32
@@ -337,20 +330,6 @@ h3d_status h3d_bn_bwd_stats(void* handle, const h3d_tensor* dy, const h3d_tensor
 h3d_status h3d_bn_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const float* mean, const float* invstd,
                       const float* gamma, const float* sum_dy, const float* sum_dy_xhat, int64_t count, h3d_tensor* dx,
                       void* ws, size_t ws_bytes, void* stream);
-
-/* ---- calibration probes (for the benchmark, not part of the method: Sec. V of the paper compares measured rates with
- * the machine's peak; these give what the device at hand sustains under the simplest load, to read a kernel's
- * fraction of the published peak against) ----
- * h3d_probe_mfma_bf16: a register-only loop of `iters` x 4 (shape 0: 16x16x32) or `iters` x 2 (shape 1: 32x32x16)
- * independent bf16 MFMAs per wavefront on 2048 x 4 wavefronts; *flops (HOST) receives the flop count of the launch,
- * the caller times it.  scratch: DEVICE, h3d_probe_mfma_scratch_bytes() bytes, 16-byte aligned, contents arbitrary
- * (finite values avoid slow paths), overwritten.
- * h3d_probe_read: reads `bytes` (whole 16-byte units) of buf (DEVICE, 16-byte aligned) once, writes nothing
- * (sink: DEVICE, 4 bytes, practically never written). */
-size_t h3d_probe_mfma_scratch_bytes(void);
-h3d_status h3d_probe_mfma_bf16(void* handle, int shape, int iters, void* scratch, size_t scratch_bytes, double* flops,
-                               void* stream);
-h3d_status h3d_probe_read(void* handle, const void* buf, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

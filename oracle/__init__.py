@@ -358,32 +358,6 @@ def mse_fwd_bwd(pred, target):
     return float(np.mean(diff * diff)), 2.0 * diff / diff.size
 
 
-def softmax_xent_fwd_bwd(logits: Slab, labels, count: int | None = None):
-    """Per-voxel softmax cross-entropy of a segmentation output on a slab (the 3D U-Net's loss; Sec. III-A names the
-    cross-entropy loss among the components that needed versions for large 3-D data, and the ground-truth labels are
-    partitioned like the activations).  logits: [n, classes, ...] slab, labels: integer [n, d, h, w] of the interior.
-    Returns (this shard's part of the mean loss, dlogits on the interior as an array [n, classes, d, h, w]); `count`
-    = voxels x samples over ALL shards (default: this slab's), so the parts of the shards add up to the mean.
-    A label >= classes marks a voxel without a class: no loss term, zero gradient, the denominator stays `count`."""
-    z = _f64(logits.interior)
-    lab = np.asarray(labels).astype(np.int64)
-    n, c, d, h, w = z.shape
-    assert lab.shape == (n, d, h, w) and lab.min(initial=0) >= 0
-    if count is None:
-        count = n * d * h * w
-    valid = lab < c                                            # a label >= classes marks a voxel without a class
-    labc = np.where(valid, lab, 0)
-    m = z.max(axis=1, keepdims=True)
-    e = np.exp(z - m)
-    se = e.sum(axis=1, keepdims=True)
-    logp = z - m - np.log(se)                                  # log softmax, computed with the maximum taken out
-    picked = np.take_along_axis(logp, labc[:, None], axis=1)[:, 0]
-    loss = -(picked * valid).sum() / count
-    onehot = np.zeros_like(z)
-    np.put_along_axis(onehot, labc[:, None], 1.0, axis=1)
-    return float(loss), (e / se - onehot) * valid[:, None] / count
-
-
 # ------------------------------------------------------------ batch normalisation, the local parts (Sec. II-B, III-C)
 # Distributed batch normalisation = per-shard partial sums, an allreduce over the shards (not part of this
 # code), then a per-channel affine map.  "Local" means: sums over the interior planes of THIS slab only.

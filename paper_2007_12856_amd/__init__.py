@@ -49,6 +49,7 @@ _SIGNATURES = {
     "h3d_create": (ctypes.c_int, [ctypes.POINTER(_P)]),
     "h3d_destroy": (ctypes.c_int, [_P]),
     "h3d_last_error": (ctypes.c_char_p, [_P]),
+    "h3d_last_kernel": (ctypes.c_char_p, [_P]),
     "h3d_conv3d_workspace_bytes": (ctypes.c_size_t, [_P, ctypes.c_int, _T, _T]),
     "h3d_conv3d_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
@@ -63,11 +64,6 @@ _SIGNATURES = {
     "h3d_conv3d_k5_fwd": (ctypes.c_int, [_P, _T, _P, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_k5_bwd_data": (ctypes.c_int, [_P, _T, _T, _P, _T, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
     "h3d_conv3d_k5_bwd_filter": (ctypes.c_int, [_P, _T, _T, _T, _P, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
-    "h3d_softmax_xent_workspace_bytes": (ctypes.c_size_t, [_P, _T]),
-    "h3d_softmax_xent_fwd_bwd": (ctypes.c_int, [_P, _T, _P, ctypes.c_int64, _P, _T, _P, ctypes.c_size_t, _P]),
-    "h3d_probe_mfma_scratch_bytes": (ctypes.c_size_t, []),
-    "h3d_probe_mfma_bf16": (ctypes.c_int, [_P, ctypes.c_int, ctypes.c_int, _P, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), _P]),
-    "h3d_probe_read": (ctypes.c_int, [_P, _P, ctypes.c_size_t, _P, _P]),
     "h3d_act_bwd": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
@@ -139,6 +135,11 @@ def h3d_destroy(h) -> None:
 
 def h3d_last_error(h=None) -> str:
     return (lib().h3d_last_error(h if h is not None else handle()) or b"").decode()
+
+
+def h3d_last_kernel(h=None) -> str:
+    """Name of the kernel that did the arithmetic of the last compute call (for the benchmark's per-kernel table)."""
+    return (lib().h3d_last_kernel(h if h is not None else handle()) or b"").decode()
 
 
 def handle():
@@ -527,36 +528,6 @@ def h3d_bn_bwd(dy: Slab, x: Slab, mean, invstd, gamma, sum_dy, sum_dy_xhat, coun
     return dx
 
 
-def h3d_softmax_xent_workspace_bytes(logits: Slab) -> int:
-    return int(lib().h3d_softmax_xent_workspace_bytes(handle(), ctypes.byref(logits.desc())))
-
-
-def h3d_softmax_xent_fwd_bwd(logits: Slab, labels, count: int, loss, dlogits: Slab, ws: Workspace | None = None):
-    p, n = (ws or _ws).get(h3d_softmax_xent_workspace_bytes(logits))
-    _check(lib().h3d_softmax_xent_fwd_bwd(handle(), ctypes.byref(logits.desc()), _ptr(labels), int(count), _ptr(loss),
-                                          ctypes.byref(dlogits.desc()), p, n, _stream()))
-    return loss, dlogits
-
-
-def h3d_probe_mfma_scratch_bytes() -> int:
-    return int(lib().h3d_probe_mfma_scratch_bytes())
-
-
-def h3d_probe_mfma_bf16(shape: int, iters: int, scratch) -> float:
-    """Enqueue the MFMA probe; returns the flop count of the launch (the caller times it)."""
-    flops = ctypes.c_double(0.0)
-    _check(lib().h3d_probe_mfma_bf16(handle(), shape, iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
-                                     ctypes.byref(flops), _stream()))
-    return flops.value
-
-
-def h3d_probe_read(buf, sink) -> int:
-    """Enqueue one streaming read of the whole tensor `buf`; returns the bytes read."""
-    nbytes = buf.numel() * buf.element_size()
-    _check(lib().h3d_probe_read(handle(), _ptr(buf), nbytes, _ptr(sink), _stream()))
-    return nbytes // 16 * 16
-
-
 # short aliases
 bn_stats, bn_finalize, bn_fwd, bn_bwd_stats, bn_bwd = h3d_bn_stats, h3d_bn_finalize, h3d_bn_fwd, h3d_bn_bwd_stats, h3d_bn_bwd
 conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filter = h3d_conv3d_fwd, h3d_conv3d_bwd_data, h3d_conv3d_bwd_filter
@@ -571,5 +542,3 @@ pool3d_fwd_mask = h3d_pool3d_fwd_mask
 deconv2_fwd, deconv2_bwd_data, deconv2_bwd_filter = h3d_deconv2_fwd, h3d_deconv2_bwd_data, h3d_deconv2_bwd_filter
 concat_c, split_c = h3d_concat_c, h3d_split_c
 dense_fwd, dense_bwd, mse_fwd_bwd = h3d_dense_fwd, h3d_dense_bwd, h3d_mse_fwd_bwd
-softmax_xent_fwd_bwd = h3d_softmax_xent_fwd_bwd
-probe_mfma_bf16, probe_read, probe_mfma_scratch_bytes = h3d_probe_mfma_bf16, h3d_probe_read, h3d_probe_mfma_scratch_bytes

@@ -50,5 +50,21 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_probes(verbose: bool = False) -> str:
+    """The benchmark's calibration probes (bench_probes.hip at the repository root): a library of their own, not part of
+    libh3d.so."""
+    root = os.path.dirname(HERE)
+    src, out = os.path.join(root, "bench_probes.hip"), os.path.join(root, "libbench_probes.so")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", src, "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on bench_probes.hip:\n" + r.stderr)
+    if verbose:
+        print("built", out)
+    return out
+
+
 if __name__ == "__main__":
     build(verbose=True)
+    build_probes(verbose=True)

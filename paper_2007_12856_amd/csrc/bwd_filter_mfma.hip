@@ -1145,6 +1145,7 @@ static h3d_status bf_roll_launch(void* handle, const bf16_t* x, const bf16_t* dz
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(192 * NRG * CIB), lds_bytes, stream, x, dz, part, a);
+  note_kernel(handle, "bwd_filter_roll_kernel<%d,%d,%d,%d>", RBW, NRG, CIB, TH);
   return H3D_OK;
 }
 
@@ -1162,6 +1163,7 @@ static h3d_status bf_roll_small_launch(void* handle, const bf16_t* x, const bf16
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds_bytes, stream, x, dz, part, a);
+  note_kernel(handle, "bwd_filter_roll_small_kernel<%d,%d,%d,%d>", RBW, NW, RB, NSEG);
   return H3D_OK;
 }
 
@@ -1179,6 +1181,7 @@ static h3d_status bf_launch(void* handle, const bf16_t* x, const bf16_t* dz, con
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(SMALLCI ? 256 : 192 * NRG), lds_bytes, stream, x, dz, z, part, a);
+  note_kernel(handle, "bwd_filter_mfma_kernel<%d,%d,%d,%d,%d,%d,%d>", RBW, NRG, TW, TH, (int)MASKED, (int)SMALLCI, (int)DMA);
   return H3D_OK;
 }
 

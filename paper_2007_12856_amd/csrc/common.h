@@ -16,6 +16,8 @@ struct Handle {
   int num_cu = 256;
   void* scratch = nullptr;    // this device's copy of the library-owned scratch array (static_scratch.hip)
   char err[512] = {0};
+  char kernel[160] = {0};     // principal kernel of the last compute call (h3d_last_kernel)
+  bool kernel_noted = false;
 };
 
 // size of the library-owned scratch array behind h3d_conv3d_bwd_filter_static
@@ -58,7 +60,9 @@ h3d_status check_tensor_packed(void* handle, const h3d_tensor* t, const char* na
 // every needed in-volume input plane for output planes [lo,hi) (local indices) must be stored
 bool halo_covers(const h3d_tensor* in, int64_t lo, int64_t hi);
 bool same_shard(const h3d_tensor* a, const h3d_tensor* b);
-h3d_status launch_status(void* handle, const char* what);
+h3d_status launch_status(void* handle, const char* what);   // also records `what` as the call's kernel unless one was noted
+// name of the kernel that does the arithmetic of the call under way (shown by h3d_last_kernel)
+void note_kernel(void* handle, const char* fmt, ...);
 
 inline float act_slope(int act, float alpha) { return act == H3D_ACT_LEAKY ? alpha : (act == H3D_ACT_RELU ? 0.f : 1.f); }
 

@@ -108,6 +108,9 @@ extern "C" h3d_status h3d_conv3d_fwd_pool(void* handle, const h3d_tensor* x, con
   if (!w && x->c * z->c > 0) return fail(handle, H3D_EINVAL, "conv3d_fwd_pool: NULL weights");
   H3D_TRY(check_pair(handle, x, &zc, "conv3d_fwd_pool"));
   H3D_TRY(pool_shapes_check(handle, &zc, y, "conv3d_fwd_pool"));
+  // what the mask pass of the three-pass route would refuse is refused here, before anything is enqueued
+  if (mask && z->w % 8) return fail(handle, H3D_EUNSUPPORTED, "conv3d_fwd_pool: a mask needs w to be a multiple of 8");
+  if (!is_packed(z)) return fail(handle, H3D_EUNSUPPORTED, "conv3d_fwd_pool: z must be a packed tensor (the pooling pass takes no plane-run views)");
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
   if (c4_fwd_pool_supported(x, z, y) && c4_roll_supported(x, z))

@@ -394,6 +394,253 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Wide-blocked form of the same implicit GEMM for the large layers (more than 16 columns, at least 3 stored output
+// planes, no fused mask): FOUR wavefronts per workgroup, one per SIMD, each owning CB blocks of 32 output channels x
+// 8 MFMA column blocks (8 rows x 32 columns of one plane = 256 voxels): CB * 8 accumulator tiles = up to 256
+// registers, which the compiler keeps in the accumulation registers.  Per (kd,kw) step a wavefront then needs 3 * CB
+// weight fragments and 10 row fragments for 24 * CB products: one weight fragment feeds 8 products and one row
+// fragment up to 3 * CB, against 4 and 2-3 in the kernel above, so the weight stream from L2 and the LDS reads per
+// product are both halved, and a chunk of 16 input channels is 216 * CB products per wavefront between two barriers.
+// With one wavefront per SIMD nothing hides a stall, so everything is requested ahead: weight fragments two steps
+// ahead (three register sets; they do not depend on the tile, so the stream runs on across chunk and tile borders),
+// row fragments one step ahead, and the input of the next stage in two halves (one group of 8 channels each, 40
+// registers) that are requested at steps 0 and 4 and written to the other LDS buffer at steps 4 and 9.
+// The sums are taken in the order of the kernel above (chunk, kd, kw, kh), so the two give identical bits.
+template <int CB>
+__global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
+                                                               const float* __restrict__ bias, bf16_t* __restrict__ out, MfmaArgs a) {
+  constexpr int VB = 8, TD = 4, TH = 8, TW = 32;
+  constexpr int TD2 = TD + 2, TH2 = TH + 2;
+  constexpr int P = 36, PAIRS = 18;            // LDS row: w in [w0-2, w0+34), 16-byte units of 8 channels
+  constexpr int CIG_UNITS = TD2 * TH2 * P;
+  constexpr int BUF_UNITS = 2 * CIG_UNITS;
+  constexpr int NITEMS = TD2 * TH2 * PAIRS;   // (plane, row, pair of columns) items of one channel group
+  constexpr int ROUNDS = (NITEMS + 255) / 256;
+  constexpr int NFRAG = VB + 2;
+  extern __shared__ uint4 lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wd = tid >> 6;
+  const int co_blk0 = blockIdx.y * CB;
+  const int W = a.in.w, H = a.in.h;
+
+  int lds_unit[ROUNDS], item_meta[ROUNDS];     // meta: pair | hy << 8 | dz << 16 | valid << 24
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int item = tid + r * 256;
+    const int pair = item % PAIRS;
+    int x = item / PAIRS;
+    const int hy = x % TH2; x /= TH2;
+    const int dz = x % TD2;
+    const int valid = item < NITEMS ? 1 : 0;
+    lds_unit[r] = (dz * TH2 + hy) * P + 2 * pair;
+    item_meta[r] = pair | (hy << 8) | (dz << 16) | (valid << 24);
+  }
+
+  int voff[ROUNDS];
+  int n_plan = 0;
+  const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wp, (uint32_t)a.ncoblk * a.nchunks * 27 * 1024);
+  auto plan_tile = [&](int tile) {
+    int t = tile;
+    const int tw = t % a.tiles_w; t /= a.tiles_w;
+    const int th = t % a.tiles_h; t /= a.tiles_h;
+    const int td = t % a.tiles_d;
+    const int n = t / a.tiles_d;
+    const int w0 = tw * TW, h0 = th * TH, ps0 = td * TD;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int m = item_meta[r];
+      const int pair = m & 0xff, hy = (m >> 8) & 0xff, dz = (m >> 16) & 0xff;
+      const int p_in = ps0 - a.out.hlo + dz - 1;
+      const int64_t gq = a.in.doff + p_in;
+      const int sp = p_in + a.in.hlo;
+      const int h = h0 + hy - 1, w = w0 - 2 + 2 * pair;
+      const bool ok = (m >> 24) && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && h >= 0 && h < H && w >= 0 && w + 1 < W;
+      voff[r] = ok ? 2 * (sp * (int)a.in.plane + h * W + w) : BUF_OOB;
+    }
+    n_plan = n;
+  };
+
+  uint32_t v[ROUNDS][8];
+  // part `q` of 3 of one group of 8 input channels of chunk c for the planned tile (`live` false: nothing to fetch, all
+  // loads out of range).  A group is requested over three steps so that no request queue ever holds a long batch in
+  // front of the weight fragments (vector loads return in order).
+  auto load_part = [&](int c, int cig, int q, bool live) {
+    const __amdgpu_buffer_rsrc_t rs_in = make_rsrc(in + n_plan * a.in.nstride, (uint32_t)a.in.nstride * 2);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (e / 3 != q) continue;                      // channels 0-2, 3-5, 6-7
+      const int ch = c * CI_CHUNK + cig * 8 + e;
+      const bool chan_ok = live && ch < a.cin_k;     // wave-uniform
+      const int soff = __builtin_amdgcn_readfirstlane(chan_ok ? 2 * ch * (int)a.in.cstride : 0);
+#pragma unroll
+      for (int r = 0; r < ROUNDS; ++r) v[r][e] = __builtin_amdgcn_raw_buffer_load_b32(rs_in, chan_ok ? voff[r] : BUF_OOB, soff, 0);
+    }
+  };
+  auto load_half = [&](int c, int cig, bool live) {
+    load_part(c, cig, 0, live);
+    load_part(c, cig, 1, live);
+    load_part(c, cig, 2, live);
+  };
+  auto store_half = [&](int buf, int cig) {
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      if (!(item_meta[r] >> 24)) continue;
+      uint4 u0, u1;
+      u0.x = __builtin_amdgcn_perm(v[r][1], v[r][0], 0x05040100); u1.x = __builtin_amdgcn_perm(v[r][1], v[r][0], 0x07060302);
+      u0.y = __builtin_amdgcn_perm(v[r][3], v[r][2], 0x05040100); u1.y = __builtin_amdgcn_perm(v[r][3], v[r][2], 0x07060302);
+      u0.z = __builtin_amdgcn_perm(v[r][5], v[r][4], 0x05040100); u1.z = __builtin_amdgcn_perm(v[r][5], v[r][4], 0x07060302);
+      u0.w = __builtin_amdgcn_perm(v[r][7], v[r][6], 0x05040100); u1.w = __builtin_amdgcn_perm(v[r][7], v[r][6], 0x07060302);
+      uint4* dst = lds + buf * BUF_UNITS + cig * CIG_UNITS + lds_unit[r];
+      dst[0] = u0;
+      dst[1] = u1;
+    }
+  };
+
+  const int j = lane & 31;
+  f32x16 acc[CB][VB];
+  auto init_acc = [&]() {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int co = (co_blk0 + cb) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        const float bv = (bias && co < a.cout_k) ? bias[co] : 0.f;
+#pragma unroll
+        for (int b = 0; b < VB; ++b) acc[cb][b][r] = bv;
+      }
+  };
+  init_acc();
+
+  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2) * P + j + 1;
+  const int a_voff = lane * 16;
+  // weight fragments of one (kd,kw) step: [kh][channel block]; a channel block beyond Cout re-reads the last valid one
+  auto load_a = [&](int c, int step, uint4 (&dst)[3][CB]) {
+    const int kd = step / 3, kw = step % 3;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      const int blk = min(co_blk0 + cb, a.ncoblk - 1);
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh) {
+        const int soff = __builtin_amdgcn_readfirstlane(((blk * a.nchunks + c) * 27 + kd * 9 + kh * 3 + kw) * 1024);
+        const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, soff, 0);
+        dst[kh][cb] = uint4{t.x, t.y, t.z, t.w};
+      }
+    }
+  };
+
+  uint4 afr[2][3][CB];        // weight fragments of the current and of the next step
+  const int G = gridDim.x;
+  int tile = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+  if (tile >= a.ntiles) return;
+  const int nch = a.nchunks;
+
+  // One chunk: 9 steps of 24 * CB products.  c_next: the chunk whose weight stream follows this one's.  The step order
+  // is: request the next step's weight fragments, then this step's share of the next stage's input, then multiply; a
+  // row fragment register is refilled for the next step as soon as its last product has been issued.
+  auto compute_chunk = [&](int c, int c_next, int buf, bool more, int next_tile, bool last_chunk) {
+    const uint4* base = lds + buf * BUF_UNITS + lane_unit;
+    uint4 bfr[NFRAG];
+#pragma unroll
+    for (int s = 0; s < NFRAG; ++s) bfr[s] = base[s * P];
+    const int cn = last_chunk ? 0 : c + 1;
+#pragma unroll
+    for (int step = 0; step < 9; ++step) {
+      if (step + 1 < 9) load_a(c, step + 1, afr[(step + 1) & 1]);
+      else load_a(c_next, 0, afr[(step + 1) & 1]);
+      if (step == 0 && last_chunk && more) plan_tile(next_tile);
+      if (step < 3) load_part(cn, 0, step, more);
+      if (step == 4 && more) store_half(buf ^ 1, 0);
+      if (step >= 4 && step < 7) load_part(cn, 1, step - 4, more);
+      __builtin_amdgcn_sched_barrier(0);
+      const int kd1 = (step + 1) / 3, kw1 = (step + 1) % 3;
+#pragma unroll
+      for (int s = 0; s < NFRAG; ++s) {
+        const bf16x8 B = __builtin_bit_cast(bf16x8, bfr[s]);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+          const int b = s - kh;
+          if (b >= 0 && b < VB) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+              acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afr[step & 1][kh][cb]), B, acc[cb][b], 0, 0, 0);
+          }
+        }
+        if (step + 1 < 9) bfr[s] = base[(kd1 * TH2 + s) * P + kw1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (more) store_half(buf ^ 1, 1);
+    // nine steps: the fragments requested at step 8 sit in set 1, the next chunk starts with set 0
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) afr[0][kh][cb] = afr[1][kh][cb];
+  };
+
+  auto epilogue = [&](int tile_) {
+    int t = tile_;
+    const int tw = t % a.tiles_w; t /= a.tiles_w;
+    const int th = t % a.tiles_h; t /= a.tiles_h;
+    const int td = t % a.tiles_d;
+    const int n = t / a.tiles_d;
+    const int w0 = tw * TW, h0 = th * TH, ps = td * TD + wd;
+    if (ps >= a.out.ds) return;
+    const int64_t gp = a.out.doff + ps - a.out.hlo;
+    const bool inside = gp >= 0 && gp < a.out.dglob;
+    const int row_ch = 4 * (lane >> 5);
+    const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
+    // lane pairs swap one value so that every lane stores one dword (two voxels of one channel), as in the kernel above
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      if (co_blk0 + cb >= a.ncoblk) continue;
+#pragma unroll
+      for (int b = 0; b < VB; ++b) {
+        const int h = h0 + b, w = w0 + j - (odd ? 1 : 0);
+        const int vo = (h < H && w < W) ? 2 * ((row_ch + (odd ? 1 : 0)) * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const int co_u = (co_blk0 + cb) * 32 + 8 * (r / 4) + (r % 4);
+          const bool ch_ok = co_u + row_ch + (odd ? 1 : 0) < a.cout_k;
+          float v0 = acc[cb][b][r], v1 = acc[cb][b][r + 1];
+          if (!(v0 > 0.f)) v0 *= a.out_slope;
+          if (!(v1 > 0.f)) v1 *= a.out_slope;
+          const float give = odd ? v0 : v1;
+          const float got = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(give), 0xB1, 0xF, 0xF, true));
+          const uint32_t pk = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
+          __builtin_amdgcn_raw_buffer_store_b32(inside ? pk : 0u, rs_out, ch_ok ? vo : BUF_OOB,
+                                                __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
+        }
+      }
+    }
+  };
+
+  // prologue: first stage into buffer 0, first two steps of the weight stream
+  plan_tile(tile);
+  load_half(0, 0, true);
+  store_half(0, 0);
+  load_half(0, 1, true);
+  store_half(0, 1);
+  load_a(0, 0, afr[0]);
+  __syncthreads();
+  int buf = 0;
+  while (true) {
+    const int next_tile = tile + G;
+    for (int c = 0; c < nch; ++c) {
+      const bool last_chunk = c + 1 == nch;
+      const bool more = !last_chunk || next_tile < a.ntiles;
+      compute_chunk(c, last_chunk ? 0 : c + 1, buf, more, next_tile, last_chunk);
+      __syncthreads();
+      buf ^= 1;
+    }
+    epilogue(tile);
+    init_acc();
+    tile = next_tile;
+    if (tile >= a.ntiles) break;
+  }
+}
+
 // out = act(bias + sum over splits of part[split]) in split order; planes outside the global volume are zero.
 // part holds raw accumulator tiles (see the SPLIT epilogue): an output element (n, co, ps, h, w) is register
 // b*16 + r of lane `lane` of the wavefront (channel block co/32, plane ps % ND) of tile (n, ps/ND, h/TH, w/TW).
@@ -504,7 +751,38 @@ static h3d_status launch_variant(void* handle, const bf16_t* in, const bf16_t* m
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy, (unsigned)a.csplit), dim3(WG_THREADS), lds_bytes, stream, in, mask, wp,
                      a.csplit > 1 ? nullptr : bias, out, a);
+  note_kernel(handle, "conv3d_mfma_kernel<%d,%d,%d,%d,%d,%d,%d>", NCB, ND, TWC, (int)MASKED, (int)VEC, (int)SPLIT, (int)FLAT);
+  if (a.csplit > 1) return hipGetLastError() == hipSuccess ? H3D_OK : fail(handle, H3D_EHIP, "conv3d_mfma: launch failed");
   return launch_status(handle, "conv3d_mfma");
+}
+
+static bool wide_shape(const MfmaArgs& a) {
+  return a.out.w > 16 && a.out.ds >= 3 && a.out.h >= 4 && a.csplit == 1;
+}
+
+template <int CB>
+static h3d_status launch_wide(void* handle, const bf16_t* in, const uint4* wp, const float* bias, bf16_t* out, MfmaArgs a, int n,
+                              hipStream_t stream) {
+  constexpr size_t lds_bytes = (size_t)2 * 2 * 6 * 10 * 36 * 16;
+  a.tiles_w = (int)cdiv(a.out.w, 32);
+  a.tiles_h = (int)cdiv(a.out.h, 8);
+  a.tiles_d = (int)cdiv(a.out.ds, 4);
+  const int64_t ntiles = (int64_t)n * a.tiles_d * a.tiles_h * a.tiles_w;
+  const int64_t gy = cdiv(a.ncoblk, CB);
+  if (ntiles >= ((int64_t)1 << 31) || gy > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many workgroups");
+  a.ntiles = (int)ntiles;
+  const int num_cu = static_cast<Handle*>(handle)->num_cu;
+  const int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / gy));
+  auto kern = conv3d_mfma_wide_kernel<CB>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(256), lds_bytes, stream, in, wp, bias, out, a);
+  note_kernel(handle, "conv3d_mfma_wide_kernel<%d>", CB);
+  return launch_status(handle, "conv3d_mfma_wide");
 }
 
 template <bool MASKED, bool VEC>
@@ -560,6 +838,7 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   a.chunks_per_split = (int)cdiv(a.nchunks, a.csplit);
   a.part = a.csplit > 1 ? reinterpret_cast<float*>(static_cast<char*>(ws) + mfma_wp_bytes(in, out)) : nullptr;
   h3d_status st;
+  if (!mask && vec && a.cout_k > 32 && wide_shape(a)) return launch_wide<2>(handle, ip, wq, bias, op, a, out->n, stream);
   if (mask) st = vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
                      : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
   else st = vec ? pick_variant<false, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)

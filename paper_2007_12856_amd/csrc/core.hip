@@ -70,9 +70,24 @@ bool halo_covers(const h3d_tensor* in, int64_t lo, int64_t hi) {
   return true;
 }
 
+void note_kernel(void* handle, const char* fmt, ...) {
+  if (!handle) return;
+  Handle* hd = static_cast<Handle*>(handle);
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(hd->kernel, sizeof(hd->kernel), fmt, ap);
+  va_end(ap);
+  hd->kernel_noted = true;
+}
+
 h3d_status launch_status(void* handle, const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(handle, H3D_EHIP, "%s: %s", what, hipGetErrorString(e));
+  Handle* hd = static_cast<Handle*>(handle);
+  if (hd) {
+    if (!hd->kernel_noted) snprintf(hd->kernel, sizeof(hd->kernel), "%s", what);
+    hd->kernel_noted = false;          // the next call starts afresh
+  }
   return H3D_OK;
 }
 
@@ -105,6 +120,11 @@ extern "C" h3d_status h3d_destroy(void* handle) {
   if (!handle) return H3D_EINVAL;
   delete static_cast<Handle*>(handle);
   return H3D_OK;
+}
+
+extern "C" const char* h3d_last_kernel(void* handle) {
+  if (!handle) return "";
+  return static_cast<Handle*>(handle)->kernel;
 }
 
 extern "C" const char* h3d_last_error(void* handle) {

@@ -253,8 +253,11 @@ class UNetLevel:
         self.dP = {k: grads(k) for k in params}
         self.ops = []
 
-        def op(name, fn, flops=0):
-            self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": 0})
+        es = x.t.element_size()
+
+        def op(name, fn, flops=0, io=()):
+            # algorithmic bytes of a call: every tensor it reads or writes once (stored planes, weights included)
+            self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": int(sum(t.numel() * t.element_size() for t in io))})
 
         def cflops(name, out):   # 2*27*Cin*Cout per produced output voxel
             w = params[name][0]
@@ -262,46 +265,59 @@ class UNetLevel:
 
         def exchange(name, t, width):
             lo, hi = faces[name]
-            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, width), halo_unpack(hi, t, FACE_D_HI, width)))
+            io = [f for f in (lo, hi) if f is not None] * 2
+            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, width), halo_unpack(hi, t, FACE_D_HI, width)), 0, io)
 
         P = params
-        op("c1_fwd", lambda: conv3d_fwd(x, *P["c1"], T["a1"], R, 0.0, ws), cflops("c1", T["a1"]))
-        op("c2_fwd", lambda: conv3d_fwd(T["a1"], *P["c2"], T["a2"], R, 0.0, ws), cflops("c2", T["a2"]))
-        op("pool_fwd", lambda: pool3d_fwd(T["a2"], T["p"], POOL_MAX))
+        W = {k: v[0] for k, v in params.items()}
+        dflops = 2 * 128 * 64 * T["up"].t.numel() // 64
+        op("c1_fwd", lambda: conv3d_fwd(x, *P["c1"], T["a1"], R, 0.0, ws), cflops("c1", T["a1"]), (x.t, T["a1"].t, W["c1"]))
+        op("c2_fwd", lambda: conv3d_fwd(T["a1"], *P["c2"], T["a2"], R, 0.0, ws), cflops("c2", T["a2"]), (T["a1"].t, T["a2"].t, W["c2"]))
+        op("pool_fwd", lambda: pool3d_fwd(T["a2"], T["p"], POOL_MAX), 0, (T["a2"].t, T["p"].interior))
         exchange("p", T["p"], 2)
-        op("c3_fwd", lambda: conv3d_fwd(T["p"], *P["c3"], T["b1"], R, 0.0, ws), cflops("c3", T["b1"]))
-        op("c4_fwd", lambda: conv3d_fwd(T["b1"], *P["c4"], T["b2"], R, 0.0, ws), cflops("c4", T["b2"]))
-        op("up_fwd", lambda: deconv2_fwd(T["b2"], *P["up"], T["up"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
-        op("concat", lambda: concat_c(T["a2"], T["up"], T["cat"]))
+        op("c3_fwd", lambda: conv3d_fwd(T["p"], *P["c3"], T["b1"], R, 0.0, ws), cflops("c3", T["b1"]), (T["p"].t, T["b1"].t, W["c3"]))
+        op("c4_fwd", lambda: conv3d_fwd(T["b1"], *P["c4"], T["b2"], R, 0.0, ws), cflops("c4", T["b2"]), (T["b1"].t, T["b2"].t, W["c4"]))
+        op("up_fwd", lambda: deconv2_fwd(T["b2"], *P["up"], T["up"], ws), dflops, (T["b2"].t, T["up"].t, W["up"]))
+        op("concat", lambda: concat_c(T["a2"], T["up"], T["cat"]), 0, (T["a2"].t, T["up"].t, T["cat"].interior))
         exchange("cat", T["cat"], 1)
-        op("c6_fwd", lambda: conv3d_fwd(T["cat"], *P["c6"], T["out"], R, 0.0, ws), cflops("c6", T["out"]))
+        op("c6_fwd", lambda: conv3d_fwd(T["cat"], *P["c6"], T["out"], R, 0.0, ws), cflops("c6", T["out"]), (T["cat"].t, T["out"].t, W["c6"]))
         self.n_fwd_ops = len(self.ops)
         # ---- backward
         dP = self.dP
-        op("act_bwd_out", lambda: act_bwd(G["dout"], None, T["out"], G["g6"], R))
+        op("act_bwd_out", lambda: act_bwd(G["dout"], None, T["out"], G["g6"], R), 0, (G["dout"].t, T["out"].t, G["g6"].interior))
         exchange("g6", G["g6"], 1)
-        op("c6_bwd_filter", lambda: conv3d_bwd_filter(T["cat"], G["g6"], None, *dP["c6"], NONE, 0.0, ws), cflops("c6", T["out"]))
-        op("c6_bwd_data", lambda: conv3d_bwd_data(G["g6"], None, P["c6"][0], G["dcat"], NONE, 0.0, ws), cflops("c6", T["out"]))
-        op("split", lambda: split_c(G["dcat"], G["d_skip"], G["d_up"]))
-        op("up_bwd_filter", lambda: deconv2_bwd_filter(T["b2"], G["d_up"], *dP["up"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
-        op("up_bwd_data", lambda: deconv2_bwd_data(G["d_up"], P["up"][0], G["d_b2"], ws), 2 * 128 * 64 * T["up"].t.numel() // 64)
-        op("act_bwd_b2", lambda: act_bwd(G["d_b2"], None, T["b2"], G["g4"], R))
+        op("c6_bwd_filter", lambda: conv3d_bwd_filter(T["cat"], G["g6"], None, *dP["c6"], NONE, 0.0, ws), cflops("c6", T["out"]),
+           (T["cat"].t, G["g6"].interior, dP["c6"][0]))
+        op("c6_bwd_data", lambda: conv3d_bwd_data(G["g6"], None, P["c6"][0], G["dcat"], NONE, 0.0, ws), cflops("c6", T["out"]),
+           (G["g6"].t, G["dcat"].t, W["c6"]))
+        op("split", lambda: split_c(G["dcat"], G["d_skip"], G["d_up"]), 0, (G["dcat"].t, G["d_skip"].t, G["d_up"].t))
+        op("up_bwd_filter", lambda: deconv2_bwd_filter(T["b2"], G["d_up"], *dP["up"], ws), dflops, (T["b2"].t, G["d_up"].t, dP["up"][0]))
+        op("up_bwd_data", lambda: deconv2_bwd_data(G["d_up"], P["up"][0], G["d_b2"], ws), dflops, (G["d_up"].t, G["d_b2"].t, W["up"]))
+        op("act_bwd_b2", lambda: act_bwd(G["d_b2"], None, T["b2"], G["g4"], R), 0, (G["d_b2"].t, T["b2"].t, G["g4"].interior))
         exchange("g4", G["g4"], 1)
-        op("c4_bwd_filter", lambda: conv3d_bwd_filter(T["b1"], G["g4"], None, *dP["c4"], NONE, 0.0, ws), cflops("c4", T["b2"]))
-        op("c4_bwd_data", lambda: conv3d_bwd_data(G["g4"], None, P["c4"][0], G["d_b1"], NONE, 0.0, ws), cflops("c4", T["b2"]))
-        op("act_bwd_b1", lambda: act_bwd(G["d_b1"], None, T["b1"], G["g3"], R))
+        op("c4_bwd_filter", lambda: conv3d_bwd_filter(T["b1"], G["g4"], None, *dP["c4"], NONE, 0.0, ws), cflops("c4", T["b2"]),
+           (T["b1"].t, G["g4"].interior, dP["c4"][0]))
+        op("c4_bwd_data", lambda: conv3d_bwd_data(G["g4"], None, P["c4"][0], G["d_b1"], NONE, 0.0, ws), cflops("c4", T["b2"]),
+           (G["g4"].t, G["d_b1"].t, W["c4"]))
+        op("act_bwd_b1", lambda: act_bwd(G["d_b1"], None, T["b1"], G["g3"], R), 0, (G["d_b1"].t, T["b1"].interior, G["g3"].interior))
         exchange("g3", G["g3"], 1)
-        op("c3_bwd_filter", lambda: conv3d_bwd_filter(T["p"], G["g3"], None, *dP["c3"], NONE, 0.0, ws), cflops("c3", G["d_b1"]))
-        op("c3_bwd_data", lambda: conv3d_bwd_data(G["g3"], None, P["c3"][0], G["d_p"], NONE, 0.0, ws), cflops("c3", G["d_b1"]))
-        op("pool_bwd", lambda: pool3d_bwd(G["d_p"], T["a2"], G["d_a2"], POOL_MAX))
-        op("act_bwd_a2", lambda: act_bwd(G["d_a2"], G["d_skip"], T["a2"], G["g2"], R))
+        op("c3_bwd_filter", lambda: conv3d_bwd_filter(T["p"], G["g3"], None, *dP["c3"], NONE, 0.0, ws), cflops("c3", G["d_b1"]),
+           (T["p"].t, G["g3"].interior, dP["c3"][0]))
+        op("c3_bwd_data", lambda: conv3d_bwd_data(G["g3"], None, P["c3"][0], G["d_p"], NONE, 0.0, ws), cflops("c3", G["d_b1"]),
+           (G["g3"].t, G["d_p"].t, W["c3"]))
+        op("pool_bwd", lambda: pool3d_bwd(G["d_p"], T["a2"], G["d_a2"], POOL_MAX), 0, (G["d_p"].t, T["a2"].t, G["d_a2"].t))
+        op("act_bwd_a2", lambda: act_bwd(G["d_a2"], G["d_skip"], T["a2"], G["g2"], R), 0, (G["d_a2"].t, G["d_skip"].t, T["a2"].t, G["g2"].interior))
         exchange("g2", G["g2"], 1)
-        op("c2_bwd_filter", lambda: conv3d_bwd_filter(T["a1"], G["g2"], None, *dP["c2"], NONE, 0.0, ws), cflops("c2", T["a2"]))
-        op("c2_bwd_data", lambda: conv3d_bwd_data(G["g2"], None, P["c2"][0], G["d_a1"], NONE, 0.0, ws), cflops("c2", T["a2"]))
-        op("act_bwd_a1", lambda: act_bwd(G["d_a1"], None, T["a1"], G["g1"], R))
+        op("c2_bwd_filter", lambda: conv3d_bwd_filter(T["a1"], G["g2"], None, *dP["c2"], NONE, 0.0, ws), cflops("c2", T["a2"]),
+           (T["a1"].t, G["g2"].interior, dP["c2"][0]))
+        op("c2_bwd_data", lambda: conv3d_bwd_data(G["g2"], None, P["c2"][0], G["d_a1"], NONE, 0.0, ws), cflops("c2", T["a2"]),
+           (G["g2"].t, G["d_a1"].t, W["c2"]))
+        op("act_bwd_a1", lambda: act_bwd(G["d_a1"], None, T["a1"], G["g1"], R), 0, (G["d_a1"].t, T["a1"].interior, G["g1"].interior))
         exchange("g1", G["g1"], 1)
-        op("c1_bwd_filter", lambda: conv3d_bwd_filter(x, G["g1"], None, *dP["c1"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
-        op("c1_bwd_data", lambda: conv3d_bwd_data(G["g1"], None, P["c1"][0], G["dx"], NONE, 0.0, ws), cflops("c1", G["d_a1"]))
+        op("c1_bwd_filter", lambda: conv3d_bwd_filter(x, G["g1"], None, *dP["c1"], NONE, 0.0, ws), cflops("c1", G["d_a1"]),
+           (x.t, G["g1"].interior, dP["c1"][0]))
+        op("c1_bwd_data", lambda: conv3d_bwd_data(G["g1"], None, P["c1"][0], G["dx"], NONE, 0.0, ws), cflops("c1", G["d_a1"]),
+           (G["g1"].t, G["dx"].t, W["c1"]))
 
     def forward(self):
         for o in self.ops[:self.n_fwd_ops]:
@@ -413,23 +429,19 @@ class CosmoFlowShardChain:
 class SingleLayer:
     """One conv3d layer on a depth shard with its pooling and halo traffic, as a list of calls:
     halo_unpack of both D faces, conv fwd (+bias+act), pool fwd, halo_pack of the input faces;
-    pool bwd fused with the activation backward, BF and BD on g (g carries a 1-plane halo)."""
+    pool bwd fused with the activation backward, BF and BD on g (g carries a 1-plane halo).
+    The caller brings the tensors that hold values (x with its halo planes, w, b, the gradient slab g with a halo
+    plane per side, the pooled gradient dp when pooling is on); buffers that are only written are made here."""
 
-    def __init__(self, n, cin, cout, d, hw, d_offset, d_global, pool=True, act=ACT_LEAKY, alpha=0.01, dtype=torch.bfloat16, seed=0,
-                 split=False, faces_hw=False):
+    def __init__(self, x: Slab, w, b, g: Slab, dp: Slab | None = None, pool=True, act=ACT_LEAKY, alpha=0.01, split=False, faces_hw=False):
         from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
-        dev = "cuda"
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(seed)
-        rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dtype)
+        dev, dtype = x.t.device, x.t.dtype
+        n, cin, _, hw, _ = x.t.shape
+        cout, d, d_offset, d_global = w.shape[0], x.d, x.d_offset, x.d_global
         self.ws = Workspace()
-        ws, es = self.ws, 2 if dtype == torch.bfloat16 else 4
-        x = self.x = Slab(rnd(n, cin, d + 2, hw, hw), 1, 1, d_offset, d_global)
-        bound = (3.0 / (27 * cin)) ** 0.5
-        w = self.w = ((torch.rand((cout, cin, 3, 3, 3), generator=gen, device=dev) * 2 - 1) * bound).to(dtype)
-        b = self.b = (torch.rand((cout,), generator=gen, device=dev) * 0.2 - 0.1)
+        ws, es = self.ws, x.t.element_size()
+        self.x, self.w, self.b, self.g = x, w, b, g
         z = self.z = Slab(torch.empty((n, cout, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
-        g = self.g = Slab(rnd(n, cout, d + 2, hw, hw), 1, 1, d_offset, d_global)
         dx = self.dx = Slab(torch.empty((n, cin, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
         self.dw = torch.empty((cout, cin, 3, 3, 3), device=dev)
         self.db = torch.empty((cout,), device=dev)
@@ -455,7 +467,7 @@ class SingleLayer:
                fl * 2 // d, (pl * 2 * (3 * cin + cout) + 2 * w.numel()) * es)
         if pool:
             p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
-            dp = self.dp = Slab(rnd(n, cout, d // 2, hw // 2, hw // 2), 0, 0, d_offset // 2, d_global // 2)
+            self.dp = dp
             op("pool_fwd", lambda: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
             op("pool_bwd_act", lambda: pool3d_bwd_act(dp, None, z, g, POOL_AVG, act, alpha), 0, (dp.t.numel() + 2 * z.t.numel()) * es)
         op("halo_pack_g", lambda: (halo_pack(g, FACE_D_LO, 1, gfaces[0]), halo_pack(g, FACE_D_HI, 1, gfaces[1])), 0, 4 * gfaces[0].numel() * es)
@@ -490,17 +502,15 @@ class SingleLayer:
 
 class BatchNormLayer:
     """The local passes of one distributed batch-normalisation layer on a slab, as a list of calls (the allreduce of
-    the per-channel sums between them is the caller's and is not part of this list)."""
+    the per-channel sums between them is the caller's and is not part of this list).  x, dy: the caller's tensors."""
 
-    def __init__(self, n, c, d, hw, dtype=torch.bfloat16, seed=0):
+    def __init__(self, x: Slab, dy: Slab):
         from . import bn_bwd, bn_bwd_stats, bn_finalize, bn_fwd, bn_stats
-        dev = "cuda"
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(seed)
-        rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dtype)
+        dev = x.t.device
+        n, c, _, hw, _ = x.t.shape
+        d = x.d
         self.ws = Workspace()
-        ws, es = self.ws, 2 if dtype == torch.bfloat16 else 4
-        x, dy = Slab(rnd(n, c, d, hw, hw)), Slab(rnd(n, c, d, hw, hw))
+        ws, es = self.ws, x.t.element_size()
         y, dx = Slab(torch.empty_like(x.t)), Slab(torch.empty_like(x.t))
         vec = lambda: torch.empty(c, device=dev)
         s, sq, mean, invstd, sdy, sdx = vec(), vec(), vec(), vec(), vec(), vec()
