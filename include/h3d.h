@@ -66,10 +66,13 @@ typedef struct {
   int64_t d_offset;         /* global depth index of interior plane 0                      */
   int64_t d_global;         /* depth of the unsharded sample                               */
   /* Elements between consecutive channels / samples.  0 = packed: (halo_lo+d+halo_hi)*h*w and c times that.
-   * Non-zero strides describe a RUN OF PLANES inside a taller stored slab, i.e. the main / halo sub-domains
-   * of Sec. III-C (D_main = planes that need no halo, D_halo = the strips that do): `data` points at the
-   * run's first stored plane, d / halo_* / d_offset describe the run, the strides are the parent's.  Only
-   * the three convolution passes accept such a view; every other entry point returns H3D_EUNSUPPORTED.
+   * Non-zero strides describe a VIEW of a larger stored tensor: a RUN OF PLANES inside a taller slab, i.e. the main /
+   * halo sub-domains of Sec. III-C (D_main = planes that need no halo, D_halo = the strips that do), and / or a RANGE
+   * OF CHANNELS of a tensor with more channels (the two halves of a U-Net concatenation, Sec. III-A: a layer then
+   * writes its output straight into its half and no copy is made).  `data` points at the view's first stored plane
+   * of its first channel, n / c / d / halo_* / d_offset describe the view, the strides are the parent's.  Views are
+   * accepted by the three convolution passes, h3d_act_bwd, h3d_pool3d_fwd / _bwd / _bwd_act and the h3d_deconv2_*
+   * calls; every other entry point returns H3D_EUNSUPPORTED.
    * Forward / backward-data on views that tile a slab give the whole-slab call's result bit for bit, except
    * where the whole-slab call is small enough to take the channel-split kernel (bf16, W <= 16, fewer than 64
    * workgroups): views are never split, so the fp32 summation order of the two differs there. */
@@ -209,12 +212,14 @@ h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* 
                           void* stream);
 
 /* Pooling backward fused with the activation backward of the layer below it:
- * g = pool3d_bwd(dy) * (z > 0 ? 1 : slope), z the saved output of the conv+activation that fed the
- * pooling (same shape as g; its halos may differ).  One streaming pass; the backward convolutions are
- * then called on g with act NONE.  With bf16 storage g is rounded once (the unfused sequence rounds
- * the pooled gradient first). */
+ * g = (pool3d_bwd(dy) + dz2) * (z > 0 ? 1 : slope), z the saved output of the conv+activation that fed the
+ * pooling (same shape as g; its halos may differ); dz2 (same shape as g, or NULL) is a second gradient arriving at
+ * that output - the skip branch of a U-Net level (Sec. III-A), which leaves the encoder beside the pooling.  One
+ * streaming pass instead of pooling backward, add and activation backward; the backward convolutions are then called
+ * on g with act NONE.  The un-pooled gradient is rounded to the storage type as h3d_pool3d_bwd stores it, then the
+ * sum is masked and rounded once: the bits of the separate calls. */
 h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z,
-                              h3d_tensor* g, int mode, int act, float alpha, void* stream);
+                              const h3d_tensor* dz2, h3d_tensor* g, int mode, int act, float alpha, void* stream);
 
 /* ---- convolution forward fused with the 2x2x2 average pooling that follows it, and the matching backward step ----
  * (Sec. III-A: operations that are "normally considered cheap" - pooling, activations - dominate once the tensors

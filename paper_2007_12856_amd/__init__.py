@@ -67,7 +67,7 @@ _SIGNATURES = {
     "h3d_act_bwd": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_pool3d_fwd": (ctypes.c_int, [_P, _T, _T, ctypes.c_int, _P]),
     "h3d_pool3d_bwd": (ctypes.c_int, [_P, _T, _T, _T, ctypes.c_int, _P]),
-    "h3d_pool3d_bwd_act": (ctypes.c_int, [_P, _T, _T, _T, _T, ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
+    "h3d_pool3d_bwd_act": (ctypes.c_int, [_P, _T, _T, _T, _T, _T, ctypes.c_int, ctypes.c_int, ctypes.c_float, _P]),
     "h3d_pool3d_fwd_mask": (ctypes.c_int, [_P, _T, _T, _P, _P]),
     "h3d_act_mask_bytes": (ctypes.c_size_t, [_T]),
     "h3d_conv3d_fwd_pool": (ctypes.c_int, [_P, _T, _P, _P, _T, _T, _P, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t, _P]),
@@ -210,6 +210,15 @@ class Slab:
         a, b = self.halo_lo + p0 - halo_lo, self.halo_lo + p1 + halo_hi
         assert 0 <= a <= b <= self.t.shape[2]
         return Slab(self.t[:, :, a:b], halo_lo, halo_hi, self.d_offset + p0, self.d_global)
+
+    def channels(self, c0: int, c1: int, halo_lo: int | None = None, halo_hi: int | None = None) -> "Slab":
+        """Channels [c0, c1) of this slab as a view (no copy, same memory), optionally with narrower halos: the planes
+        dropped from the halo are simply not part of the view."""
+        hl = self.halo_lo if halo_lo is None else halo_lo
+        hh = self.halo_hi if halo_hi is None else halo_hi
+        assert 0 <= c0 <= c1 <= self.t.shape[1] and hl <= self.halo_lo and hh <= self.halo_hi
+        a, b = self.halo_lo - hl, self.t.shape[2] - (self.halo_hi - hh)
+        return Slab(self.t[:, c0:c1, a:b], hl, hh, self.d_offset, self.d_global)
 
     def like(self, channels: int, halo_lo: int = 0, halo_hi: int = 0, d: int | None = None, h: int | None = None,
              w: int | None = None, d_offset: int | None = None, d_global: int | None = None) -> "Slab":
@@ -391,9 +400,10 @@ def h3d_pool3d_bwd(dy: Slab, x: Slab | None, dx: Slab, mode: int):
     return dx
 
 
-def h3d_pool3d_bwd_act(dy: Slab, x: Slab | None, z: Slab, g: Slab, mode: int, act: int, alpha: float = 0.0):
+def h3d_pool3d_bwd_act(dy: Slab, x: Slab | None, z: Slab, g: Slab, mode: int, act: int, alpha: float = 0.0, dz2: Slab | None = None):
     _check(lib().h3d_pool3d_bwd_act(handle(), ctypes.byref(dy.desc()), ctypes.byref(x.desc()) if x is not None else None,
-                                    ctypes.byref(z.desc()), ctypes.byref(g.desc()), mode, act, alpha, _stream()))
+                                    ctypes.byref(z.desc()), ctypes.byref(dz2.desc()) if dz2 is not None else None,
+                                    ctypes.byref(g.desc()), mode, act, alpha, _stream()))
     return g
 
 

@@ -76,10 +76,10 @@ using namespace h3d;
 extern "C" h3d_status h3d_act_bwd(void* handle, const h3d_tensor* dz, const h3d_tensor* dz2, const h3d_tensor* z, h3d_tensor* g,
                                   int act, float alpha, void* stream) {
   if (!handle) return H3D_EINVAL;
-  H3D_TRY(check_tensor_packed(handle, dz, "dz"));
-  H3D_TRY(check_tensor_packed(handle, z, "z"));
-  H3D_TRY(check_tensor_packed(handle, g, "g"));
-  if (dz2) H3D_TRY(check_tensor_packed(handle, dz2, "dz2"));
+  H3D_TRY(check_tensor(handle, dz, "dz"));
+  H3D_TRY(check_tensor(handle, z, "z"));
+  H3D_TRY(check_tensor(handle, g, "g"));
+  if (dz2) H3D_TRY(check_tensor(handle, dz2, "dz2"));
   if (act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY) return fail(handle, H3D_EINVAL, "act_bwd: bad activation");
   if (!same_shard(dz, g) || !same_shard(z, g) || dz->c != g->c || z->c != g->c || (dz2 && (!same_shard(dz2, g) || dz2->c != g->c)))
     return fail(handle, H3D_EINVAL, "act_bwd: all tensors must agree in n,c,d,h,w,d_offset,d_global,dtype");

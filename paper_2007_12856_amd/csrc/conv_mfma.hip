@@ -838,7 +838,10 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   a.chunks_per_split = (int)cdiv(a.nchunks, a.csplit);
   a.part = a.csplit > 1 ? reinterpret_cast<float*>(static_cast<char*>(ws) + mfma_wp_bytes(in, out)) : nullptr;
   h3d_status st;
-  if (!mask && vec && a.cout_k > 32 && wide_shape(a)) return launch_wide<2>(handle, ip, wq, bias, op, a, out->n, stream);
+  if (!mask && vec && wide_shape(a)) {
+    if (a.cout_k > 32) return launch_wide<2>(handle, ip, wq, bias, op, a, out->n, stream);
+    if (a.cin_k > 16) return launch_wide<1>(handle, ip, wq, bias, op, a, out->n, stream);
+  }
   if (mask) st = vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
                      : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
   else st = vec ? pick_variant<false, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)

@@ -180,8 +180,8 @@ static void df_plan(int64_t voxels, int cin, int cout, int64_t* chunk, int* nchu
 }
 
 static h3d_status deconv_check(void* handle, const h3d_tensor* x, const h3d_tensor* y, const char* what) {
-  H3D_TRY(check_tensor_packed(handle, x, "x"));
-  H3D_TRY(check_tensor_packed(handle, y, "y"));
+  H3D_TRY(check_tensor(handle, x, "x"));
+  H3D_TRY(check_tensor(handle, y, "y"));
   if (x->dtype != y->dtype || x->n != y->n || y->d != 2 * x->d || y->h != 2 * x->h || y->w != 2 * x->w ||
       y->d_offset != 2 * x->d_offset || y->d_global != 2 * x->d_global)
     return fail(handle, H3D_EINVAL, "%s: fine tensor must be exactly twice the coarse one (extents and offsets)", what);

@@ -103,16 +103,21 @@ __global__ void __launch_bounds__(256) pool_fwd_mask_kernel(const bf16_t* __rest
 // ACT: also multiply by the activation derivative taken from the saved output z of the layer that
 // produced the pooled tensor (g = pool_bwd(dy) * (z > 0 ? 1 : slope)): one pass instead of a pooling
 // backward followed by an activation backward.
-template <typename T, int VEC, int MODE, bool ACT>
+// ADD: a second gradient of the big tensor's shape (the skip branch of a U-Net level) is added to the un-pooled one
+// before the activation derivative: g = (pool_bwd(dy) + dz2) * (z > 0 ? 1 : slope), rounded once.
+template <typename T, int VEC, int MODE, bool ACT, bool ADD>
 __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                        T* __restrict__ dx, PoolArgs a, Geo xin, const T* __restrict__ z,
-                                                       Geo zg, float slope) {
+                                                       Geo zg, float slope, const T* __restrict__ dz2, Geo d2g) {
   int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= a.total) return;
   int64_t dxoff, yoff;
   decode<T, VEC>(a, t, dxoff, yoff);
   Vec<T, VEC> g = *reinterpret_cast<const Vec<T, VEC>*>(dy + yoff);
   Vec<T, 2 * VEC> o[4];
+  Vec<T, 2 * VEC> r[4];          // rows of the pooling's forward input (max pooling)
+  // a ReLU'd tensor that was max-pooled is both the pooling's input and the saved activation: read it once
+  const bool z_is_x = MODE == H3D_POOL_MAX && ACT && z == x && zg.cstride == xin.cstride && zg.nstride == xin.nstride && zg.hlo == xin.hlo;
   if (MODE == H3D_POOL_AVG) {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
@@ -127,7 +132,6 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy,
     b.x = xin;
     int64_t xoff, dummy;
     decode<T, VEC>(b, t, xoff, dummy);
-    Vec<T, 2 * VEC> r[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       r[k] = *reinterpret_cast<const Vec<T, 2 * VEC>*>(x + xoff + (k >> 1) * xin.plane + (k & 1) * xin.w);
@@ -150,17 +154,31 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const T* __restrict__ dy,
         for (int j = 0; j < 2; ++j) o[k].v[2 * i + j] = (best == k * 2 + j) ? g.v[i] : zero;
     }
   }
-  if (ACT) {
+  if (ACT || ADD) {
     PoolArgs b = a;
     b.x = zg;
-    int64_t zoff, dummy;
-    decode<T, VEC>(b, t, zoff, dummy);
+    int64_t zoff = 0, d2off = 0, dummy;
+    if (ACT) decode<T, VEC>(b, t, zoff, dummy);
+    b.x = d2g;
+    if (ADD) decode<T, VEC>(b, t, d2off, dummy);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      Vec<T, 2 * VEC> m = *reinterpret_cast<const Vec<T, 2 * VEC>*>(z + zoff + (k >> 1) * zg.plane + (k & 1) * zg.w);
+      Vec<T, 2 * VEC> m, e;
+      if (ACT) {
+        if (z_is_x) m = r[k];
+        else m = *reinterpret_cast<const Vec<T, 2 * VEC>*>(z + zoff + (k >> 1) * zg.plane + (k & 1) * zg.w);
+      }
+      if (ADD) e = *reinterpret_cast<const Vec<T, 2 * VEC>*>(dz2 + d2off + (k >> 1) * d2g.plane + (k & 1) * d2g.w);
 #pragma unroll
-      for (int i = 0; i < 2 * VEC; ++i)
-        if (!(ld(&m.v[i]) > 0.f)) st(&o[k].v[i], ld(&o[k].v[i]) * slope);
+      for (int i = 0; i < 2 * VEC; ++i) {
+        if (ADD) {
+          float v = ld(&o[k].v[i]) + ld(&e.v[i]);
+          if (ACT && !(ld(&m.v[i]) > 0.f)) v *= slope;
+          st(&o[k].v[i], v);
+        } else if (!(ld(&m.v[i]) > 0.f)) {
+          st(&o[k].v[i], ld(&o[k].v[i]) * slope);
+        }
+      }
     }
   }
 #pragma unroll
@@ -235,14 +253,16 @@ h3d_status pool_shapes_check(void* handle, const h3d_tensor* big, const h3d_tens
 }
 
 template <typename T>
-static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_tensor* extra, const h3d_tensor* extra2 = nullptr) {
+static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_tensor* extra, const h3d_tensor* extra2 = nullptr,
+                    const h3d_tensor* extra3 = nullptr) {
   // widest VEC (outputs per thread) such that every row start is aligned for the vector accesses
   const int cand = 16 / (2 * (int)sizeof(T)) * 2;  // bf16: 8, fp32: 4  (two 16-byte loads per input row)
   for (int v = cand; v > 1; v >>= 1) {
     bool ok = small->w % v == 0 && ((uintptr_t)small->data % (v * sizeof(T))) == 0 &&
               ((uintptr_t)big->data % (2 * v * sizeof(T))) == 0 &&
               (!extra || ((uintptr_t)extra->data % (2 * v * sizeof(T))) == 0) &&
-              (!extra2 || ((uintptr_t)extra2->data % (2 * v * sizeof(T))) == 0);
+              (!extra2 || ((uintptr_t)extra2->data % (2 * v * sizeof(T))) == 0) &&
+              (!extra3 || ((uintptr_t)extra3->data % (2 * v * sizeof(T))) == 0);
     if (ok) return v;
   }
   return 0;  // scalar: VEC = 1 needs pairs aligned to 2 elements
@@ -250,14 +270,15 @@ static int pick_vec(const h3d_tensor* big, const h3d_tensor* small, const h3d_te
 
 template <typename T, int MODE>
 static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, const h3d_tensor* small,
-                              const h3d_tensor* xin, hipStream_t stream, const h3d_tensor* zt = nullptr, float slope = 1.f) {
+                              const h3d_tensor* xin, hipStream_t stream, const h3d_tensor* zt = nullptr, float slope = 1.f,
+                              const h3d_tensor* d2t = nullptr) {
   PoolArgs a;
   a.x = make_geo(big);
   a.y = make_geo(small);
-  int vec = pick_vec<T>(big, small, xin, zt);
+  int vec = pick_vec<T>(big, small, xin, zt, d2t);
   if (vec == 0) {
     bool ok = ((uintptr_t)big->data % (2 * sizeof(T))) == 0 && (!xin || ((uintptr_t)xin->data % (2 * sizeof(T))) == 0) &&
-              (!zt || ((uintptr_t)zt->data % (2 * sizeof(T))) == 0);
+              (!zt || ((uintptr_t)zt->data % (2 * sizeof(T))) == 0) && (!d2t || ((uintptr_t)d2t->data % (2 * sizeof(T))) == 0);
     if (!ok) return fail(handle, H3D_EUNSUPPORTED, "pool3d: data pointers must be aligned to two elements");
     vec = 1;
   }
@@ -268,7 +289,9 @@ static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, con
   if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "pool3d: too many blocks");
   Geo gx = xin ? make_geo(xin) : a.x;
   Geo gz = zt ? make_geo(zt) : a.x;
+  Geo gd2 = d2t ? make_geo(d2t) : a.x;
   const T* zp = zt ? (const T*)zt->data : nullptr;
+  const T* d2p = d2t ? (const T*)d2t->data : nullptr;
   const T* bigp = (const T*)big->data;
   const T* smallp = (const T*)small->data;
 #define H3D_POOL_CASE(V)                                                                                           \
@@ -276,12 +299,18 @@ static h3d_status pool_launch(void* handle, bool fwd, const h3d_tensor* big, con
     if (fwd)                                                                                                       \
       hipLaunchKernelGGL((pool_fwd_kernel<T, V, MODE>), dim3((unsigned)grid), dim3(256), 0, stream, bigp,          \
                          (T*)small->data, a);                                                                      \
+    else if (zt && d2t)                                                                                            \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, true, true>), dim3((unsigned)grid), dim3(256), 0, stream,    \
+                         smallp, xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope, d2p, gd2); \
     else if (zt)                                                                                                   \
-      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, true>), dim3((unsigned)grid), dim3(256), 0, stream, smallp,  \
-                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope);                \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, true, false>), dim3((unsigned)grid), dim3(256), 0, stream,   \
+                         smallp, xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope, d2p, gd2); \
+    else if (d2t)                                                                                                  \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, false, true>), dim3((unsigned)grid), dim3(256), 0, stream,   \
+                         smallp, xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope, d2p, gd2); \
     else                                                                                                           \
-      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, false>), dim3((unsigned)grid), dim3(256), 0, stream, smallp, \
-                         xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope);                \
+      hipLaunchKernelGGL((pool_bwd_kernel<T, V, MODE, false, false>), dim3((unsigned)grid), dim3(256), 0, stream,  \
+                         smallp, xin ? (const T*)xin->data : nullptr, (T*)big->data, a, gx, zp, gz, slope, d2p, gd2); \
     break;
   switch (vec) {
     H3D_POOL_CASE(8)
@@ -299,8 +328,8 @@ using namespace h3d;
 
 extern "C" h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tensor* y, int mode, void* stream) {
   if (!handle) return H3D_EINVAL;
-  H3D_TRY(check_tensor_packed(handle, x, "x"));
-  H3D_TRY(check_tensor_packed(handle, y, "y"));
+  H3D_TRY(check_tensor(handle, x, "x"));
+  H3D_TRY(check_tensor(handle, y, "y"));
   if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_fwd: bad mode %d", mode);
   H3D_TRY(pool_check(handle, x, y, "pool3d_fwd"));
   hipStream_t s = (hipStream_t)stream;
@@ -311,47 +340,51 @@ extern "C" h3d_status h3d_pool3d_fwd(void* handle, const h3d_tensor* x, h3d_tens
                               : pool_launch<bf16_t, H3D_POOL_MAX>(handle, true, x, y, nullptr, s);
 }
 
-static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, h3d_tensor* dx,
-                                int mode, float slope, void* stream);
+static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, const h3d_tensor* dz2,
+                                h3d_tensor* dx, int mode, float slope, void* stream);
 
 extern "C" h3d_status h3d_pool3d_bwd(void* handle, const h3d_tensor* dy, const h3d_tensor* x, h3d_tensor* dx, int mode,
                                      void* stream) {
-  return pool_bwd_impl(handle, dy, x, nullptr, dx, mode, 1.f, stream);
+  return pool_bwd_impl(handle, dy, x, nullptr, nullptr, dx, mode, 1.f, stream);
 }
 
 extern "C" h3d_status h3d_pool3d_bwd_act(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z,
-                                         h3d_tensor* g, int mode, int act, float alpha, void* stream) {
+                                         const h3d_tensor* dz2, h3d_tensor* g, int mode, int act, float alpha, void* stream) {
   if (!handle) return H3D_EINVAL;
   if (act != H3D_ACT_NONE && act != H3D_ACT_RELU && act != H3D_ACT_LEAKY) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: bad activation");
   if (act == H3D_ACT_NONE) z = nullptr;
   else if (!z) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: the saved output z is required");
-  return pool_bwd_impl(handle, dy, x, z, g, mode, act_slope(act, alpha), stream);
+  return pool_bwd_impl(handle, dy, x, z, dz2, g, mode, act_slope(act, alpha), stream);
 }
 
-static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, h3d_tensor* dx,
-                                int mode, float slope, void* stream) {
+static h3d_status pool_bwd_impl(void* handle, const h3d_tensor* dy, const h3d_tensor* x, const h3d_tensor* z, const h3d_tensor* dz2,
+                                h3d_tensor* dx, int mode, float slope, void* stream) {
   if (!handle) return H3D_EINVAL;
   if (z) {
-    H3D_TRY(check_tensor_packed(handle, z, "z"));
+    H3D_TRY(check_tensor(handle, z, "z"));
     if (!dx || !same_shard(z, dx) || z->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: z and g shapes differ");
   }
-  H3D_TRY(check_tensor_packed(handle, dy, "dy"));
-  H3D_TRY(check_tensor_packed(handle, dx, "dx"));
+  if (dz2) {
+    H3D_TRY(check_tensor(handle, dz2, "dz2"));
+    if (!dx || !same_shard(dz2, dx) || dz2->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd_act: dz2 and g shapes differ");
+  }
+  H3D_TRY(check_tensor(handle, dy, "dy"));
+  H3D_TRY(check_tensor(handle, dx, "dx"));
   if (mode != H3D_POOL_AVG && mode != H3D_POOL_MAX) return fail(handle, H3D_EINVAL, "pool3d_bwd: bad mode %d", mode);
   H3D_TRY(pool_check(handle, dx, dy, "pool3d_bwd"));
   if (mode == H3D_POOL_MAX) {
     if (!x) return fail(handle, H3D_EINVAL, "pool3d_bwd: max pooling needs the forward input x");
-    H3D_TRY(check_tensor_packed(handle, x, "x"));
+    H3D_TRY(check_tensor(handle, x, "x"));
     if (!same_shard(x, dx) || x->c != dx->c) return fail(handle, H3D_EINVAL, "pool3d_bwd: x and dx shapes differ");
   } else {
     x = nullptr;
   }
   hipStream_t s = (hipStream_t)stream;
   if (dx->dtype == H3D_F32)
-    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope)
-                                : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
-  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope)
-                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope);
+    return mode == H3D_POOL_AVG ? pool_launch<float, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope, dz2)
+                                : pool_launch<float, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope, dz2);
+  return mode == H3D_POOL_AVG ? pool_launch<bf16_t, H3D_POOL_AVG>(handle, false, dx, dy, x, s, z, slope, dz2)
+                              : pool_launch<bf16_t, H3D_POOL_MAX>(handle, false, dx, dy, x, s, z, slope, dz2);
 }
 
 extern "C" size_t h3d_act_mask_bytes(const h3d_tensor* z) {

@@ -244,12 +244,17 @@ class UNetLevel:
             w, b = params[name]
             return torch.empty(w.shape, dtype=torch.float32, device=dev), torch.empty(b.shape, dtype=torch.float32, device=dev)
 
-        T = self.T = {"a1": slab(32, 1), "a2": slab(64, 0), "p": slab(64, 2, 2), "b1": slab(64, 1, 2), "b2": slab(128, 0, 2),
-                      "up": slab(64, 0), "cat": slab(128, 1), "out": slab(64, 0)}
-        G = self.G = {"dout": Slab(dout, 0, 0, off, dg), "g6": slab(64, 1), "dcat": slab(128, 0), "d_skip": slab(64, 0),
-                      "d_up": slab(64, 0), "d_b2": slab(128, 0, 2), "g4": slab(128, 1, 2), "d_b1": slab(64, 0, 2),
-                      "g3": slab(64, 1, 2), "d_p": slab(64, 0, 2), "d_a2": slab(64, 0), "g2": slab(64, 1), "d_a1": slab(32, 0),
+        # The concatenation is not a copy: the skip tensor a2 and the up-sampled tensor ARE the two channel halves of
+        # `cat` (views of its interior planes), written in place by the convolution and the transposed convolution that
+        # produce them; in the backward pass the two halves of dcat are read in place the same way.
+        T = self.T = {"a1": slab(32, 1), "p": slab(64, 2, 2), "b1": slab(64, 1, 2), "b2": slab(128, 0, 2),
+                      "cat": slab(128, 1), "out": slab(64, 0)}
+        T["a2"], T["up"] = T["cat"].channels(0, 64, 0, 0), T["cat"].channels(64, 128, 0, 0)
+        G = self.G = {"dout": Slab(dout, 0, 0, off, dg), "g6": slab(64, 1), "dcat": slab(128, 0),
+                      "d_b2": slab(128, 0, 2), "g4": slab(128, 1, 2), "d_b1": slab(64, 0, 2),
+                      "g3": slab(64, 1, 2), "d_p": slab(64, 0, 2), "g2": slab(64, 1), "d_a1": slab(32, 0),
                       "g1": slab(32, 1), "dx": slab(1, 0)}
+        G["d_skip"], G["d_up"] = G["dcat"].channels(0, 64), G["dcat"].channels(64, 128)
         self.dP = {k: grads(k) for k in params}
         self.ops = []
 
@@ -278,7 +283,6 @@ class UNetLevel:
         op("c3_fwd", lambda: conv3d_fwd(T["p"], *P["c3"], T["b1"], R, 0.0, ws), cflops("c3", T["b1"]), (T["p"].t, T["b1"].t, W["c3"]))
         op("c4_fwd", lambda: conv3d_fwd(T["b1"], *P["c4"], T["b2"], R, 0.0, ws), cflops("c4", T["b2"]), (T["b1"].t, T["b2"].t, W["c4"]))
         op("up_fwd", lambda: deconv2_fwd(T["b2"], *P["up"], T["up"], ws), dflops, (T["b2"].t, T["up"].t, W["up"]))
-        op("concat", lambda: concat_c(T["a2"], T["up"], T["cat"]), 0, (T["a2"].t, T["up"].t, T["cat"].interior))
         exchange("cat", T["cat"], 1)
         op("c6_fwd", lambda: conv3d_fwd(T["cat"], *P["c6"], T["out"], R, 0.0, ws), cflops("c6", T["out"]), (T["cat"].t, T["out"].t, W["c6"]))
         self.n_fwd_ops = len(self.ops)
@@ -290,7 +294,6 @@ class UNetLevel:
            (T["cat"].t, G["g6"].interior, dP["c6"][0]))
         op("c6_bwd_data", lambda: conv3d_bwd_data(G["g6"], None, P["c6"][0], G["dcat"], NONE, 0.0, ws), cflops("c6", T["out"]),
            (G["g6"].t, G["dcat"].t, W["c6"]))
-        op("split", lambda: split_c(G["dcat"], G["d_skip"], G["d_up"]), 0, (G["dcat"].t, G["d_skip"].t, G["d_up"].t))
         op("up_bwd_filter", lambda: deconv2_bwd_filter(T["b2"], G["d_up"], *dP["up"], ws), dflops, (T["b2"].t, G["d_up"].t, dP["up"][0]))
         op("up_bwd_data", lambda: deconv2_bwd_data(G["d_up"], P["up"][0], G["d_b2"], ws), dflops, (G["d_up"].t, G["d_b2"].t, W["up"]))
         op("act_bwd_b2", lambda: act_bwd(G["d_b2"], None, T["b2"], G["g4"], R), 0, (G["d_b2"].t, T["b2"].t, G["g4"].interior))
@@ -305,8 +308,9 @@ class UNetLevel:
            (T["p"].t, G["g3"].interior, dP["c3"][0]))
         op("c3_bwd_data", lambda: conv3d_bwd_data(G["g3"], None, P["c3"][0], G["d_p"], NONE, 0.0, ws), cflops("c3", G["d_b1"]),
            (G["g3"].t, G["d_p"].t, W["c3"]))
-        op("pool_bwd", lambda: pool3d_bwd(G["d_p"], T["a2"], G["d_a2"], POOL_MAX), 0, (G["d_p"].t, T["a2"].t, G["d_a2"].t))
-        op("act_bwd_a2", lambda: act_bwd(G["d_a2"], G["d_skip"], T["a2"], G["g2"], R), 0, (G["d_a2"].t, G["d_skip"].t, T["a2"].t, G["g2"].interior))
+        # max-pooling backward, the skip branch's gradient and the activation derivative of a2 in one pass
+        op("pool_bwd_act_a2", lambda: pool3d_bwd_act(G["d_p"], T["a2"], T["a2"], G["g2"], POOL_MAX, R, 0.0, G["d_skip"]), 0,
+           (G["d_p"].t, T["a2"].t, G["d_skip"].t, G["g2"].interior))
         exchange("g2", G["g2"], 1)
         op("c2_bwd_filter", lambda: conv3d_bwd_filter(T["a1"], G["g2"], None, *dP["c2"], NONE, 0.0, ws), cflops("c2", T["a2"]),
            (T["a1"].t, G["g2"].interior, dP["c2"][0]))

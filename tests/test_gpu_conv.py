@@ -273,8 +273,15 @@ def test_plane_run_views_are_rejected_elsewhere():
     import paper_2007_12856_amd as h3d
     _, xg = slab_pair(synth.flat("normal", SEED, 54, (1, 2, 6, 4, 8)), "bf16")
     _, yg = slab_pair(np.zeros((1, 2, 3, 2, 4)), "bf16")
-    with pytest.raises(h3d.H3DError):
-        h3d.pool3d_fwd(xg.planes(0, 4), yg.planes(0, 2), h3d.POOL_AVG)
+    import torch
+    buf = torch.empty(2 * 2 * 4 * 8, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.halo_pack(xg.planes(0, 4), h3d.FACE_D_LO, 1, buf)
+    assert e.value.status == -2
+    with pytest.raises(h3d.H3DError) as e:
+        x4 = h3d.Slab(torch.zeros((2, 4, 6, 4, 8), dtype=torch.bfloat16, device="cuda"))      # (one sample: its first channels are packed memory)
+        h3d.concat_c(x4.channels(0, 2), x4.channels(2, 4), h3d.Slab(torch.empty_like(x4.t)))
+    assert e.value.status == -2
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -275,17 +275,96 @@ def test_pool_bwd_fused_with_activation_backward(mode, dtype):
         close(from_dev(gg.t), ref.a, (1e-6 if dtype == "f32" else 4e-3))
 
 
-def test_calibration_probes_run_and_report_their_work():
+# ---------------------------------------------------------------- views: channel ranges / plane runs of a larger tensor
+def _parent(shape, halo, seed_stream, fill=None):
+    """a packed device slab of noise (or a constant) whose channel ranges / plane runs serve as views"""
     import torch
     import paper_2007_12856_amd as h3d
-    scratch = torch.ones(h3d.probe_mfma_scratch_bytes() // 4, device="cuda")
-    assert h3d.probe_mfma_bf16(0, 8, scratch) == 2048 * 4 * 8 * 4 * 2.0 * 16 * 16 * 32
-    assert h3d.probe_mfma_bf16(1, 8, scratch) == 2048 * 4 * 8 * 2 * 2.0 * 32 * 32 * 16
-    buf, sink = torch.ones(1 << 20, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda")
-    assert h3d.probe_read(buf, sink) == 4 << 20
-    torch.cuda.synchronize()
-    assert sink.item() == 0 and torch.isfinite(scratch).all()
-    with pytest.raises(h3d.H3DError):
-        h3d.probe_mfma_bf16(2, 8, scratch)
-    with pytest.raises(h3d.H3DError):
-        h3d.probe_mfma_bf16(0, 8, scratch[:16])
+    a = synth.flat("normal", SEED, seed_stream, shape) if fill is None else np.full(shape, fill)
+    return a, h3d.Slab(to_dev(quantize(a, "bf16"), "bf16"), halo, halo, 4, 4 + shape[2] - 2 * halo + 6)
+
+
+@pytest.mark.parametrize("mode", ["avg", "max"])
+def test_pool_act_and_skip_add_on_channel_views(mode):
+    """The U-Net level's zero-copy concatenation: pooling forward reads one half of a 2C-channel slab in place, the fused
+    pooling backward reads the saved activation and the skip gradient as halves of two other slabs and adds the skip
+    gradient before the activation derivative; results equal the oracle's composition and, bit for bit, the same calls
+    on packed copies; nothing outside the addressed halves is touched."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = 2, 3, 4, 6, 32
+    code = h3d.POOL_AVG if mode == "avg" else h3d.POOL_MAX
+    ocode = orc.POOL_AVG if mode == "avg" else orc.POOL_MAX
+    za, zp = _parent((N, 2 * C, d + 2, H, W), 1, 61)             # the "cat" slab (1-plane halo): the skip half is channels [0, C)
+    za[:, :, :, 0] = 0.0                                          # ties after ReLU
+    zp.t.copy_(to_dev(quantize(za, "bf16"), "bf16"))
+    da, dp_ = _parent((N, 2 * C, d, H, W), 0, 62)                 # the "dcat" slab: the skip gradient is channels [0, C)
+    zv, skipv = zp.channels(0, C, 0, 0), dp_.channels(0, C)
+    zq = quantize(za, "bf16")[:, :C, 1:-1]
+    skipq = quantize(da, "bf16")[:, :C]
+    zo = orc.Slab(zq, 0, 0, 4, zp.d_global)
+    # forward on the view
+    yo = orc.pool3d_fwd(zo, ocode)
+    yg = dev_like(yo, "bf16")
+    h3d.pool3d_fwd(zv, yg, code)
+    yc = dev_like(yo, "bf16")
+    h3d.pool3d_fwd(h3d.Slab(zv.t.contiguous(), 0, 0, 4, zp.d_global), yc, code)
+    assert torch.equal(yg.t, yc.t)
+    close(from_dev(yg.t), yo.a, 4e-3, "pooled view")
+    # backward: g = (pool_bwd(dy) + skip) * relu'(z), written into a slab with a halo
+    dyo, dyg = slab_pair(synth.flat("normal", SEED, 63, (N, C, d // 2, H // 2, W // 2)), "bf16", (0, 0), 2, zp.d_global // 2)
+    g = h3d.Slab(torch.full((N, C, d + 2, H, W), 7.0, dtype=torch.bfloat16, device="cuda"), 1, 1, 4, zp.d_global)
+    h3d.pool3d_bwd_act(dyg, zv, zv, g, code, h3d.ACT_RELU, 0.0, dz2=skipv)
+    un = quantize(orc.pool3d_bwd(dyo, zo, ocode).a, "bf16")       # the un-pooled gradient as pool3d_bwd stores it
+    want = (un + skipq) * (zq > 0)
+    close(from_dev(g.interior), want, 4e-3, "fused pooling backward", elem=2.0 ** -8)
+    assert bool((g.t[:, :, [0, -1]] == 7.0).all())
+    # the separate calls on packed copies: same bits
+    zc = h3d.Slab(zv.t.contiguous(), 0, 0, 4, zp.d_global)
+    d1 = h3d.Slab(torch.empty((N, C, d, H, W), dtype=torch.bfloat16, device="cuda"), 0, 0, 4, zp.d_global)
+    h3d.pool3d_bwd(dyg, zc, d1, code)
+    g2 = h3d.Slab(torch.empty((N, C, d, H, W), dtype=torch.bfloat16, device="cuda"), 0, 0, 4, zp.d_global)
+    h3d.act_bwd(d1, h3d.Slab(skipv.t.contiguous(), 0, 0, 4, zp.d_global), zc, g2, h3d.ACT_RELU)
+    assert torch.equal(g.interior, g2.t)
+    # act_bwd itself on views (z and the second gradient in place)
+    g3 = h3d.Slab(torch.empty((N, C, d, H, W), dtype=torch.bfloat16, device="cuda"), 0, 0, 4, zp.d_global)
+    h3d.act_bwd(d1, skipv, zv, g3, h3d.ACT_RELU)
+    assert torch.equal(g3.t, g2.t)
+    # the parents are unchanged
+    assert torch.equal(zp.t, to_dev(quantize(za, "bf16"), "bf16")) and torch.equal(dp_.t, to_dev(quantize(da, "bf16"), "bf16"))
+
+
+def test_deconv_writes_and_reads_channel_views():
+    """Transposed convolution straight into the upper half of a 2C-channel slab with a halo, and its two backward passes
+    reading the upper half of the gradient slab in place: same bits as on packed tensors, the other half and the halo
+    planes untouched."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, dc, Hc, Wc = 1, 32, 16, 3, 6, 16
+    b = np.sqrt(3.0 / (8 * Ci))
+    w = quantize(synth.flat("uniform", SEED, 71, (Ci, Co, 2, 2, 2), -b, b), "bf16")
+    bias = synth.round_f32(synth.flat("uniform", SEED, 72, (Co,), -0.1, 0.1)).astype(np.float64)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 73, (N, Ci, dc, Hc, Wc)), "bf16", (0, 0), 2, 8)
+    wd, bd = to_dev(w, "bf16"), to_dev(bias, "f32")
+    cat = h3d.Slab(torch.full((N, 2 * Co, 2 * dc + 2, 2 * Hc, 2 * Wc), 5.0, dtype=torch.bfloat16, device="cuda"), 1, 1, 4, 16)
+    up = cat.channels(Co, 2 * Co, 0, 0)
+    h3d.deconv2_fwd(xg, wd, bd, up)
+    yc = h3d.Slab(torch.empty((N, Co, 2 * dc, 2 * Hc, 2 * Wc), dtype=torch.bfloat16, device="cuda"), 0, 0, 4, 16)
+    h3d.deconv2_fwd(xg, wd, bd, yc)
+    assert torch.equal(up.t, yc.t)
+    assert bool((cat.t[:, :Co] == 5.0).all()) and bool((cat.t[:, :, [0, -1]] == 5.0).all())
+    close(from_dev(up.t), orc.deconv2_fwd(xo, w, bias).a, TOL["bf16"], "deconv into a view")
+    dcat = h3d.Slab(to_dev(quantize(synth.flat("normal", SEED, 74, (N, 2 * Co, 2 * dc, 2 * Hc, 2 * Wc)), "bf16"), "bf16"), 0, 0, 4, 16)
+    dup = dcat.channels(Co, 2 * Co)
+    dupc = h3d.Slab(dup.t.contiguous(), 0, 0, 4, 16)
+    dx1, dx2 = dev_like(xo, "bf16"), dev_like(xo, "bf16")
+    h3d.deconv2_bwd_data(dup, wd, dx1)
+    h3d.deconv2_bwd_data(dupc, wd, dx2)
+    assert torch.equal(dx1.t, dx2.t)
+    dw1, db1 = torch.empty((Ci, Co, 2, 2, 2), device="cuda"), torch.empty((Co,), device="cuda")
+    dw2, db2 = torch.empty_like(dw1), torch.empty_like(db1)
+    h3d.deconv2_bwd_filter(xg, dup, dw1, db1)
+    h3d.deconv2_bwd_filter(xg, dupc, dw2, db2)
+    assert torch.equal(dw1, dw2) and torch.equal(db1, db2)
+    dwo, dbo = orc.deconv2_bwd_filter(xo, orc.Slab(from_dev(dupc.t), 0, 0, 4, 16))
+    close(from_dev(dw1), dwo, 2e-4, "deconv dw from a view")

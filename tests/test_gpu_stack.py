@@ -211,7 +211,9 @@ def test_unet_level_miniature(dg, d, d_offset, hw):
     for k in ("a1", "a2", "p", "b1", "b2", "up", "cat", "out"):
         close(from_dev(net.T[k].t), T[k].a, tol, k, **FWD_ELEM[dtype])
     assert np.array_equal(from_dev(net.T["cat"].t)[:, :, [0, -1]], T["cat"].a[:, :, [0, -1]])     # exchanged halo: bit-exact
-    for k in ("g6", "dcat", "d_b2", "g4", "d_b1", "g3", "d_p", "d_a2", "g2", "d_a1", "g1", "dx"):
+    assert "concat" not in [o["name"] for o in net.ops] and "split" not in [o["name"] for o in net.ops]     # views, no copies
+    assert net.T["a2"].t.data_ptr() == net.T["cat"].interior.data_ptr()
+    for k in ("g6", "dcat", "d_b2", "g4", "d_b1", "g3", "d_p", "g2", "d_a1", "g1", "dx"):
         close(from_dev(net.G[k].t), G[k].a, tol, k, **BWD_ELEM[dtype])
     for k in dP:
         close(from_dev(net.dP[k][0]), dP[k][0], tol, f"dw {k}", **BWD_ELEM[dtype])
