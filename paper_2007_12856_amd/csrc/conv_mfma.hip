@@ -21,6 +21,7 @@
 //   * the ci loop runs in chunks of 16 channels with two LDS buffers: the global loads of chunk
 //     c+1 are in flight while chunk c is multiplied.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 
@@ -498,17 +499,41 @@ __global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __r
   };
 
   const int j = lane & 31;
+  // The accumulators of a tile start from the bias (the sums are then taken in the order of the kernel above: same
+  // bits).  Writing 256 accumulation registers one by one from the vector ALU costs a wavefront about 5000 cycles
+  // per tile (measured); instead the bias enters as a product: a weight-shaped fragment that holds, for each channel
+  // of the block, the three bfloat16 pieces of its fp32 bias (upper, middle and lower 8 mantissa bits, cut by
+  // truncation: their sum is the bias exactly) in the first three of the 16 contraction slots and zeros in the others,
+  // multiplied by a fragment of ones: sixteen extra MFMAs per tile, D = hi + mid + lo + 0 ... = bias in every column.
+  uint4* biasf_l = lds + 2 * BUF_UNITS;       // [CB][64 lanes] fragments behind the two stage buffers
+  if (tid < CB * 64) {
+    const int cb = tid >> 6, l = tid & 63;
+    uint4 f = {0u, 0u, 0u, 0u};
+    const int co = (co_blk0 + cb) * 32 + l;
+    if (l < 32 && bias && co < a.cout_k) {
+      const float bv = bias[co];
+      const uint32_t hi = __float_as_uint(bv) & 0xffff0000u;
+      const float r1 = bv - __uint_as_float(hi);
+      const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+      const float r2 = r1 - __uint_as_float(mid);
+      const uint32_t lo = __float_as_uint(r2) & 0xffff0000u;
+      f.x = (hi >> 16) | mid;
+      f.y = lo >> 16;
+    }
+    biasf_l[tid] = f;
+  }
+  __syncthreads();
   f32x16 acc[CB][VB];
   auto init_acc = [&]() {
+    const uint4 ones_u = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_u);
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+    for (int cb = 0; cb < CB; ++cb) {
+      const bf16x8 bf = __builtin_bit_cast(bf16x8, biasf_l[cb * 64 + lane]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int co = (co_blk0 + cb) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-        const float bv = (bias && co < a.cout_k) ? bias[co] : 0.f;
-#pragma unroll
-        for (int b = 0; b < VB; ++b) acc[cb][b][r] = bv;
-      }
+      for (int b = 0; b < VB; ++b) acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, ones, zero, 0, 0, 0);
+    }
   };
   init_acc();
 
@@ -552,7 +577,6 @@ __global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __r
       if (step < 3) load_part(cn, 0, step, more);
       if (step == 4 && more) store_half(buf ^ 1, 0);
       if (step >= 4 && step < 7) load_part(cn, 1, step - 4, more);
-      __builtin_amdgcn_sched_barrier(0);
       const int kd1 = (step + 1) / 3, kw1 = (step + 1) % 3;
 #pragma unroll
       for (int s = 0; s < NFRAG; ++s) {
@@ -568,6 +592,14 @@ __global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __r
         }
         if (step + 1 < 9) bfr[s] = base[(kd1 * TH2 + s) * P + kw1];
       }
+      // one wavefront per SIMD: the requests, address arithmetic and LDS traffic of the step must be issued in the
+      // shadow of its products (a product occupies the matrix pipe for 32 cycles, the wavefront can issue about seven
+      // other instructions meanwhile), not in a block in front of them
+#pragma unroll
+      for (int i = 0; i < 24 * CB; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x326, 3, 0);      // up to three of: VALU, SALU, vector-memory read, LDS read / write
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) store_half(buf ^ 1, 1);
@@ -578,6 +610,9 @@ __global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __r
       for (int cb = 0; cb < CB; ++cb) afr[0][kh][cb] = afr[1][kh][cb];
   };
 
+  // Epilogue of a tile (CB * 128 values per lane): everything that does not depend on the value is taken out of the
+  // per-value path.  Activation as med3(v, slope * v, +inf) (the same bits as "v > 0 ? v : slope * v" for
+  // 0 <= slope <= 1), skipped when there is none.
   auto epilogue = [&](int tile_) {
     int t = tile_;
     const int tw = t % a.tiles_w; t /= a.tiles_w;
@@ -590,28 +625,62 @@ __global__ void __launch_bounds__(256) conv3d_mfma_wide_kernel(const bf16_t* __r
     const bool inside = gp >= 0 && gp < a.out.dglob;
     const int row_ch = 4 * (lane >> 5);
     const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out + n * a.out.nstride, (uint32_t)a.out.nstride * 2);
-    // lane pairs swap one value so that every lane stores one dword (two voxels of one channel), as in the kernel above
+    // A lane holds one voxel of 16 channels; a store wants two neighbouring voxels of one channel.  Each lane packs
+    // its channel pair (r, r+1) to bf16, fetches its neighbour's packed pair (lanes 2k and 2k+1 hold voxels 2k and
+    // 2k+1) and picks, with a per-lane byte selector, channel r of both voxels (even lane) or channel r+1 of both
+    // (odd lane): one conversion, one lane exchange and one byte permute per stored dword, no selects.
     const bool odd = lane & 1;
+    const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+    const int cs2 = 2 * (int)a.out.cstride;
+    const int vbase = (row_ch + (odd ? 1 : 0)) * cs2 + 2 * (ps * (int)a.out.plane + h0 * W + w0 + j - (odd ? 1 : 0));
+    const bool w_ok = w0 + j - (odd ? 1 : 0) < W;
+    const bool act = a.out_slope != 1.f;        // wave-uniform
+    const float slope = a.out_slope;
+    const float inf = __builtin_inff();
+    int vo[VB];
+#pragma unroll
+    for (int b = 0; b < VB; ++b) vo[b] = (w_ok && h0 + b < H) ? vbase + 2 * b * W : BUF_OOB;
+    // ACT / WHOLE are wave-uniform facts: one branch per channel block, not one select per value
+    auto block = [&](int cb, auto act_c, auto whole_c) {
+      constexpr bool ACT = decltype(act_c)::value, WHOLE = decltype(whole_c)::value;
+      const int cblk = co_blk0 + cb;
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const int co_u = cblk * 32 + 8 * (r / 4) + (r % 4);
+        const int soff = __builtin_amdgcn_readfirstlane(co_u * cs2);
+        const bool ch_ok = WHOLE || co_u + row_ch + (odd ? 1 : 0) < a.cout_k;
+#pragma unroll
+        for (int b = 0; b < VB; ++b) {
+          float v0 = acc[cb][b][r], v1 = acc[cb][b][r + 1];
+          if (ACT) {      // max(v, slope v): v where v > 0, slope v elsewhere (0 <= slope <= 1)
+            const float s0 = v0 * slope, s1 = v1 * slope;
+            asm("v_max_f32 %0, %1, %2" : "=v"(v0) : "v"(v0), "v"(s0));
+            asm("v_max_f32 %0, %1, %2" : "=v"(v1) : "v"(v1), "v"(s1));
+          }
+          const uint32_t own = pack_bf16x2(v0, v1);
+          const uint32_t nb = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0xB1, 0xF, 0xF, true);
+          uint32_t pk = __builtin_amdgcn_perm(nb, own, sel);
+          int o = vo[b];
+          if (!WHOLE) {
+            pk = inside ? pk : 0u;
+            o = ch_ok ? o : BUF_OOB;
+          }
+          __builtin_amdgcn_raw_buffer_store_b32(pk, rs_out, o, soff, 0);
+        }
+      }
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
-      if (co_blk0 + cb >= a.ncoblk) continue;
-#pragma unroll
-      for (int b = 0; b < VB; ++b) {
-        const int h = h0 + b, w = w0 + j - (odd ? 1 : 0);
-        const int vo = (h < H && w < W) ? 2 * ((row_ch + (odd ? 1 : 0)) * (int)a.out.cstride + ps * (int)a.out.plane + h * W + w) : BUF_OOB;
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const int co_u = (co_blk0 + cb) * 32 + 8 * (r / 4) + (r % 4);
-          const bool ch_ok = co_u + row_ch + (odd ? 1 : 0) < a.cout_k;
-          float v0 = acc[cb][b][r], v1 = acc[cb][b][r + 1];
-          if (!(v0 > 0.f)) v0 *= a.out_slope;
-          if (!(v1 > 0.f)) v1 *= a.out_slope;
-          const float give = odd ? v0 : v1;
-          const float got = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(give), 0xB1, 0xF, 0xF, true));
-          const uint32_t pk = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
-          __builtin_amdgcn_raw_buffer_store_b32(inside ? pk : 0u, rs_out, ch_ok ? vo : BUF_OOB,
-                                                __builtin_amdgcn_readfirstlane(2 * co_u * (int)a.out.cstride), 0);
-        }
+      const int cblk = co_blk0 + cb;
+      if (cblk >= a.ncoblk) continue;
+      const bool whole = cblk * 32 + 32 <= a.cout_k && inside;     // the common case
+      if (whole) {
+        if (act) block(cb, T_{}, T_{});
+        else block(cb, F_{}, T_{});
+      } else {
+        block(cb, T_{}, F_{});       // (slope 1 leaves the values as they are)
       }
     }
   };
@@ -763,7 +832,7 @@ static bool wide_shape(const MfmaArgs& a) {
 template <int CB>
 static h3d_status launch_wide(void* handle, const bf16_t* in, const uint4* wp, const float* bias, bf16_t* out, MfmaArgs a, int n,
                               hipStream_t stream) {
-  constexpr size_t lds_bytes = (size_t)2 * 2 * 6 * 10 * 36 * 16;
+  constexpr size_t lds_bytes = (size_t)2 * 2 * 6 * 10 * 36 * 16 + CB * 64 * 16;     // two stage buffers + the bias fragments
   a.tiles_w = (int)cdiv(a.out.w, 32);
   a.tiles_h = (int)cdiv(a.out.h, 8);
   a.tiles_d = (int)cdiv(a.out.ds, 4);
