@@ -128,7 +128,7 @@ h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, const h3d_te
  * For callers that cannot allocate device memory or size a workspace: code under HIP graph capture, tight serving /
  * training loops, harnesses that forbid hipMalloc.  Same arguments, kernels, results (bit for bit) and errors as
  * h3d_conv3d_bwd_filter; the per-chunk partial sums of the split-spatial reduction go to a device array of
- * h3d_static_scratch_bytes() bytes (64 MiB) that the library owns: one copy per GPU it runs on, held until the process
+ * h3d_static_scratch_bytes() bytes (96 MiB) that the library owns: one copy per GPU it runs on, held until the process
  * ends, its address looked up once per device by h3d_create.  Shapes whose h3d_conv3d_workspace_bytes(BWD_FILTER)
  * exceeds that size are rejected with H3D_EWORKSPACE before anything is launched (then use the call above).  The call
  * allocates and frees nothing, on the host or the device, and does not synchronise.  Every call on a GPU shares that

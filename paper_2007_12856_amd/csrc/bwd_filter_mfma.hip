@@ -1116,6 +1116,11 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
   return p;
 }
 
+// the kernel on the 32x32x16 tile (bwd_filter_row32.hip)
+bool row32_bf_shape(const h3d_tensor* x, const h3d_tensor* dz);
+int row32_bf_nchunks(const h3d_tensor* x, const h3d_tensor* dz);
+h3d_status row32_bf_partials(void* handle, const h3d_tensor* x, const h3d_tensor* dz, float* part, int* npart, hipStream_t stream);
+
 bool mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
   if (x->dtype != H3D_BF16 || x->c < 1 || dz->c < 1) return false;
   return sample_span(x) < ((int64_t)1 << 40) && (int64_t)(x->halo_lo + x->d + x->halo_hi) * x->h * x->w < ((int64_t)1 << 30);
@@ -1128,6 +1133,7 @@ size_t mfma_bf_ws_bytes(const h3d_tensor* x, const h3d_tensor* dz) {
     const BfPlan pr = bf_plan_mfma(x, dz->c, true);
     nchunks = std::max(nchunks, pr.nchunks * pr.wpair);
   }
+  if (row32_bf_shape(x, dz)) nchunks = std::max(nchunks, row32_bf_nchunks(x, dz));
   return (size_t)nchunks * ((size_t)dz->c * x->c * 27 + dz->c) * sizeof(float);
 }
 
@@ -1216,7 +1222,9 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
                            float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
   const bool vec_ok = (x->w % 8 == 0) && ((uintptr_t)x->data % 16 == 0) && ((uintptr_t)dz->data % 16 == 0) && (!z || (uintptr_t)z->data % 16 == 0);
   const bool dma_ok = sample_span(x) * 2 < ((int64_t)1 << 31) && sample_span(dz) * 2 < ((int64_t)1 << 31);
-  const bool roll = !z && vec_ok && dma_ok && bf_roll_shape(x);
+  const bool row32 = !z && vec_ok && dma_ok && row32_bf_shape(x, dz) && sample_span(x) % 8 == 0 && sample_span(dz) % 8 == 0 &&
+                     x->c_stride % 8 == 0 && dz->c_stride % 8 == 0;
+  const bool roll = !row32 && !z && vec_ok && dma_ok && bf_roll_shape(x);
   BfPlan p = bf_plan_mfma(x, dz->c, roll);
   if (!ws || ws_bytes < mfma_bf_ws_bytes(x, dz)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace must be 16-byte aligned");
@@ -1239,7 +1247,9 @@ h3d_status bwd_filter_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* 
   const bf16_t* gp = (const bf16_t*)dz->data;
   const bf16_t* zp = z ? (const bf16_t*)z->data : nullptr;
   h3d_status st;
-  if (roll && x->c <= 4) {
+  if (row32) {
+    st = row32_bf_partials(handle, x, dz, (float*)ws, &a.npart, stream);
+  } else if (roll && x->c <= 4) {
     if (p.rbw == 2) st = bf_roll_small_launch<2, 8, 2, 1>(handle, xp, gp, (float*)ws, a, grid, stream);
     else if (p.tw == 64) st = bf_roll_small_launch<1, 4, 2, 2>(handle, xp, gp, (float*)ws, a, grid, stream);
     else st = bf_roll_small_launch<1, 8, 4, 1>(handle, xp, gp, (float*)ws, a, grid, stream);

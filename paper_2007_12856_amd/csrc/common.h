@@ -21,7 +21,7 @@ struct Handle {
 };
 
 // size of the library-owned scratch array behind h3d_conv3d_bwd_filter_static
-#define H3D_STATIC_SCRATCH_BYTES (64u << 20)
+#define H3D_STATIC_SCRATCH_BYTES (96u << 20)
 h3d_status static_scratch_init(Handle* hd);
 
 // Slab geometry as the kernels see it (element strides, not bytes).
@@ -87,6 +87,33 @@ __device__ __forceinline__ float ld(const float* p) { return *p; }
 __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void st(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ---- global -> LDS copies without registers (buffer_load ... lds) ---------------------------------------------------
+// The instruction is issued from inline assembly on purpose: the compiler's wait-count pass treats a copy into LDS as
+// aliasing every later LDS read and puts "s_waitcnt vmcnt(0)" in front of the first one, which serialises a prefetch
+// with the arithmetic it was meant to hide behind.  Issued this way the copies are invisible to that pass; the kernel
+// itself waits (s_waitcnt vmcnt) and synchronises (barrier) before anyone reads the destination.  Hidden operations can
+// only make the compiler's own vmcnt waits longer, never shorter: the counter is decremented in issue order.
+typedef int h3d_i32x4 __attribute__((ext_vector_type(4)));
+// raw buffer resource: byte range [base, base + bytes), accesses beyond it return zeros
+__device__ __forceinline__ h3d_i32x4 lds_dma_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  h3d_i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+// LDS byte address of a pointer into shared memory (wave-uniform)
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p);
+}
+// 64 lanes x 16 bytes from per-lane byte offsets `voff` of the buffer into 1 KB of LDS at `lds_byte_addr` (lane l at + 16 l)
+__device__ __forceinline__ void lds_dma16(h3d_i32x4 rs, uint32_t lds_byte_addr, int voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_byte_addr), "v"(voff), "s"(rs) : "memory", "m0");
+}
 
 template <typename T> struct dtype_of;
 template <> struct dtype_of<float> { static constexpr int value = H3D_F32; };

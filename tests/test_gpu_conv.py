@@ -97,14 +97,30 @@ BF_SHAPES = [
     (1, 24, 24, 5, 7, 33, 1),
     (1, 4, 16, 2, 20, 72, 1),
     (1, 2, 10, 3, 17, 128, 0),
+    # more than 32 channels on both sides: the kernel on the 32x32x16 tile (64-, 32- and 16-voxel row segments, ragged
+    # bands and channel blocks, a ragged last K-step, chunks of several strips that cross planes and samples)
+    (2, 40, 48, 3, 20, 16, 1),
+    (1, 72, 40, 2, 9, 32, 0),
+    (1, 64, 64, 4, 34, 64, 1),
+    (2, 40, 40, 5, 18, 24, 1),
+    (1, 36, 130, 2, 6, 136, 0),
+    (4, 130, 130, 5, 10, 16, 1),
 ]
 
 
+@pytest.mark.parametrize("walk", ["default", "x-aligned"])
 @pytest.mark.parametrize("shape", BF_SHAPES)
-def test_conv3d_bwd_filter_unmasked_bf16(shape):
+def test_conv3d_bwd_filter_unmasked_bf16(shape, walk, monkeypatch):
     import torch
     import paper_2007_12856_amd as h3d
     N, Ci, Co, D, H, W, halo = shape
+    if walk == "x-aligned":
+        # the kernel on the 32x32x16 tile has a second order of walking the planes, chosen by tensor size: force it
+        if not (Ci > 32 and Co > 32):
+            pytest.skip("only the many-channel kernel has two walks")
+        monkeypatch.setenv("H3D_BF_XALIGN", "1")
+    else:
+        monkeypatch.setenv("H3D_BF_XALIGN", "0")
     dtype = "bf16"
     # with halo: the middle slab of a volume two planes taller (the halo planes hold real neighbours);
     # without: the whole volume, zero beyond both ends
