@@ -29,17 +29,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BF_OOB = (int)0x80000000;   // byte offset beyond every buffer: such a lane transfers zeros
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t bf_rsrc(const void* base, uint32_t bytes) {
+__device__ __forceinline__ h3d_i32x4 bf_rsrc(const void* base, uint32_t bytes) { return lds_dma_rsrc(base, bytes); }
+// the same range as a resource of the compiler's own buffer loads (global -> registers)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t bf_rsrc_reg(const void* base, uint32_t bytes) {
   const uint64_t p = reinterpret_cast<uint64_t>(base);
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
   return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
                                            (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
 }
 
-// 64 lanes x 16 bytes from per-lane buffer offsets straight into 1 KB of LDS at `lds_dst` (wave-uniform)
-__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rs, uint4* lds_dst, int voff) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds_dst, 16, voff, 0, 0, 0);
-}
+// 64 lanes x 16 bytes from per-lane buffer offsets straight into 1 KB of LDS at `lds_dst` (wave-uniform); issued so that
+// the compiler does not wait for it before later LDS reads (common.h): every kernel here waits and synchronises itself
+__device__ __forceinline__ void dma16(h3d_i32x4 rs, uint4* lds_dst, int voff) { lds_dma16(rs, lds_addr_of(lds_dst), voff); }
 
 constexpr int cmod_ge(int lo, int target_mod16) {  // smallest v >= lo with v % 16 == target_mod16
   int v = lo;
@@ -243,8 +244,8 @@ __global__ void __launch_bounds__(SMALLCI ? 256 : 192 * NRG, DMA ? 3 : 1) bwd_fi
 
     if (DMA) {
       __syncthreads();   // everyone is done reading the previous tile
-      const __amdgpu_buffer_rsrc_t rs_x = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
-      const __amdgpu_buffer_rsrc_t rs_g = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+      const h3d_i32x4 rs_x = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+      const h3d_i32x4 rs_g = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
       const int tx = 2 * (p * (int)a.x.plane + h0 * W + w0), tg = 2 * (p * (int)a.g.plane + h0 * W + w0);
 #pragma unroll
       for (int i = 0; i < CXW; ++i) {
@@ -489,7 +490,7 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
 
   // plane q (relative to the slab's first owned plane) of sample n, rows h0-1.., columns w0-8.. -> slot q mod 4
   auto load_plane = [&](int n, int q, int h0, int w0) {
-    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const h3d_i32x4 rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
     const int64_t gq = a.x.doff + q;
     const bool plane_ok = gq >= 0 && gq < a.x.dglob;
     const int t0 = (q + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
@@ -508,7 +509,7 @@ __global__ void __launch_bounds__(192 * NRG * CIB, 3) bwd_filter_roll_kernel(con
     }
   };
   auto load_g = [&](int n, int q, int h0, int w0, int buf) {
-    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+    const h3d_i32x4 rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
     const int t0 = (q + a.g.hlo) * (int)a.g.plane + h0 * W + w0;
     uint4* dst = gl + buf * GPAD;
 #pragma unroll
@@ -741,7 +742,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 4 : 2) bwd_filter_roll_smal
     dx_meta[i] = ok ? (row | (u << 8) | (ci << 16)) : -1;
   }
   auto load_plane = [&](int n, int q, int h0, int w0) {
-    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const h3d_i32x4 rs = bf_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
     const int64_t gq = a.x.doff + q;
     const bool plane_ok = gq >= 0 && gq < a.x.dglob;
     const int t0 = (q + a.x.hlo) * (int)a.x.plane + (h0 - 1) * W + w0 - 8;
@@ -762,7 +763,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 4 : 2) bwd_filter_roll_smal
   // co0 + 16 rb + lc, voxels 8 lg .. 8 lg + 7 of the 32-column segment), one tile ahead, without touching LDS.
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   auto load_g = [&](u32x4 (&G)[RB][NSEG][RBW], int n, int q, int h0, int w0) {
-    const __amdgpu_buffer_rsrc_t rs = bf_rsrc(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
+    const __amdgpu_buffer_rsrc_t rs = bf_rsrc_reg(dz + n * a.g.nstride, (uint32_t)a.g.nstride * 2);
     const int t0 = (q + a.g.hlo) * (int)a.g.plane + (h0 + row0) * W + w0 + 8 * lg;
 #pragma unroll
     for (int r = 0; r < RB; ++r)

@@ -47,9 +47,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t db_rsrc(const void* base, uint
                                            (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
 }
 
-__device__ __forceinline__ void db_dma16(__amdgpu_buffer_rsrc_t rs, uint4* lds_dst, int voff) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds_dst, 16, voff, 0, 0, 0);
-}
+// global -> LDS copy issued so that the compiler does not wait for it before later LDS reads (common.h)
+__device__ __forceinline__ void db_dma16(h3d_i32x4 rs, uint4* lds_dst, int voff) { lds_dma16(rs, lds_addr_of(lds_dst), voff); }
 
 template <int MRB>
 __global__ void __launch_bounds__(64 * DB_NW, 4) deconv_bf_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
@@ -80,7 +79,7 @@ __global__ void __launch_bounds__(64 * DB_NW, 4) deconv_bf_mfma_kernel(const bf1
     dx_meta[i] = ok ? ((r1 >> 2) | ((r1 & 3) << 8) | ((ci0 + cil) << 16)) : -1;
   }
   auto load_x = [&](int n, int d, int h0, int w0, int buf) {
-    const __amdgpu_buffer_rsrc_t rs = db_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
+    const h3d_i32x4 rs = lds_dma_rsrc(x + n * a.x.nstride, (uint32_t)a.x.nstride * 2);
     const int t0 = (d + a.x.hlo) * (int)a.x.plane + h0 * Wc + w0;
 #pragma unroll
     for (int i = 0; i < CXW; ++i) {
