@@ -908,7 +908,13 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   a.part = a.csplit > 1 ? reinterpret_cast<float*>(static_cast<char*>(ws) + mfma_wp_bytes(in, out)) : nullptr;
   h3d_status st;
   if (!mask && vec && wide_shape(a)) {
-    if (a.cout_k > 32) return launch_wide<2>(handle, ip, wq, bias, op, a, out->n, stream);
+    if (a.cout_k > 32) {
+      // few tiles (a small volume): one channel block per workgroup doubles the workgroups, same sums in the same order
+      const int64_t ntiles = (int64_t)out->n * cdiv(a.out.ds, 4) * cdiv(a.out.h, 8) * cdiv(a.out.w, 32);
+      const int num_cu = static_cast<Handle*>(handle)->num_cu;
+      if (ntiles * cdiv(a.ncoblk, 2) * 4 < (int64_t)num_cu * 3) return launch_wide<1>(handle, ip, wq, bias, op, a, out->n, stream);
+      return launch_wide<2>(handle, ip, wq, bias, op, a, out->n, stream);
+    }
     if (a.cin_k > 16) return launch_wide<1>(handle, ip, wq, bias, op, a, out->n, stream);
   }
   if (mask) st = vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
