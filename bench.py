@@ -530,6 +530,17 @@ def main():
         return
 
     ceil = None if args.no_calibration else calibrate()
+    halo_rate = None
+    if args.workload == "all":
+        # one batched halo call of a size where the copy is not launch-bound (Sec. III-A packing kernels): the two lower
+        # halo planes of 8 samples x 32 channels x 512 x 512, 134 MB read + 134 MB written
+        t = h3d.Slab(torch.randn((8, 32, 6, 512, 512), device="cuda").to(torch.bfloat16), 2, 2, 8, 64)
+        buf = torch.empty((8 * 32 * 2 * 512 * 512,), dtype=torch.bfloat16, device="cuda")
+        ms = _timed(lambda r: h3d.halo_pack(t, h3d.FACE_D_LO, 2, buf), 20)
+        nbytes = 2 * buf.numel() * 2
+        halo_rate = {"call": "halo_pack, 2 planes of 8 x 32 x 512 x 512 bf16", "bytes_read_plus_written": nbytes, "ms": round(ms, 4),
+                     "gbs": round(nbytes / ms / 1e6, 1), "hbm_frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
+        del t, buf
     names = ALL if args.workload == "all" else [args.workload]
     head = names[0]
     passes = max(args.passes, 10)
@@ -564,6 +575,8 @@ def main():
         out["roofline"] = roof
     if ceil:
         out["measured_ceilings"] = ceil
+    if halo_rate:
+        out["halo_batched"] = halo_rate
     out["configs"] = results
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(seed)
