@@ -422,12 +422,15 @@ __global__ void __launch_bounds__(WG_THREADS) conv3d_mfma_kernel(const bf16_t* _
 // registers in all, the staged input serves the same 64 channels as with CB = 2, and while one wavefront of a SIMD waits
 // (request, LDS, barrier, epilogue stores) the other multiplies.  Measured against the four-wavefront CB = 2 form on one
 // box, seven layers of the U-Net level: 4 to 9 % faster on every one (128->64: 1.48 -> 1.43 ms, 32->64: 0.505 -> 0.46).
-// Instantiated: <1, 1> (at most 32 output channels, or small volumes) and <1, 2>.
-template <int CB, int WCB>
-__global__ void __launch_bounds__(256 * WCB) conv3d_mfma_wide_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
+// Instantiated: <1, 1> and <1, 1, 2> (at most 32 output channels, or small volumes) and <1, 2>.
+// RSP = 2 (for layers with a single block of output channels): eight wavefronts as well, the two of a plane taking
+// four rows of the tile each (64 accumulators, 6 row fragments per step).
+template <int CB, int WCB, int RSP = 1>
+__global__ void __launch_bounds__(256 * WCB * RSP) conv3d_mfma_wide_kernel(const bf16_t* __restrict__ in, const uint4* __restrict__ wp,
                                                                      const float* __restrict__ bias, bf16_t* __restrict__ out, MfmaArgs a) {
-  constexpr int NT = 256 * WCB;
-  constexpr int VB = 8, TD = 4, TH = 8, TW = 32;
+  static_assert(WCB * RSP <= 2, "at most eight wavefronts");
+  constexpr int NT = 256 * WCB * RSP;
+  constexpr int TD = 4, TH = 8, TW = 32, VB = TH / RSP;      // VB: row blocks (of 32 voxels) per wavefront
   constexpr int TD2 = TD + 2, TH2 = TH + 2;
   constexpr int P = 36, PAIRS = 18;            // LDS row: w in [w0-2, w0+34), 16-byte units of 8 channels
   constexpr int CIG_UNITS = TD2 * TH2 * P;
@@ -437,7 +440,8 @@ __global__ void __launch_bounds__(256 * WCB) conv3d_mfma_wide_kernel(const bf16_
   constexpr int NFRAG = VB + 2;
   extern __shared__ uint4 lds[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wd = (tid >> 6) & 3, wcb = tid >> 8;     // plane of the tile, channel-block group
+  const int tid = threadIdx.x, lane = tid & 63, wd = (tid >> 6) & 3;      // plane of the tile
+  const int wcb = WCB == 2 ? tid >> 8 : 0, rh = RSP == 2 ? tid >> 8 : 0;   // channel-block group, row half
   const int co_blk0 = (blockIdx.y * WCB + wcb) * CB;
   const int W = a.in.w, H = a.in.h;
 
@@ -553,7 +557,7 @@ __global__ void __launch_bounds__(256 * WCB) conv3d_mfma_wide_kernel(const bf16_
   };
   init_acc();
 
-  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2) * P + j + 1;
+  const int lane_unit = (lane >> 5) * CIG_UNITS + (wd * TH2 + rh * VB) * P + j + 1;
   const int a_voff = lane * 16;
   // weight fragments of one (kd,kw) step: [kh][channel block]; a channel block beyond Cout re-reads the last valid one
   auto load_a = [&](int c, int step, uint4 (&dst)[3][CB]) {
@@ -612,7 +616,7 @@ __global__ void __launch_bounds__(256 * WCB) conv3d_mfma_wide_kernel(const bf16_
       // shadow of its products (a product occupies the matrix pipe for 32 cycles, the wavefront can issue about seven
       // other instructions meanwhile), not in a block in front of them
 #pragma unroll
-      for (int i = 0; i < 24 * CB; ++i) {
+      for (int i = 0; i < 3 * VB * CB; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
         __builtin_amdgcn_sched_group_barrier(0x326, 3, 0);      // up to three of: VALU, SALU, vector-memory read, LDS read / write
       }
@@ -635,7 +639,7 @@ __global__ void __launch_bounds__(256 * WCB) conv3d_mfma_wide_kernel(const bf16_
     const int th = t % a.tiles_h; t /= a.tiles_h;
     const int td = t % a.tiles_d;
     const int n = t / a.tiles_d;
-    const int w0 = tw * TW, h0 = th * TH, ps = td * TD + wd;
+    const int w0 = tw * TW, h0 = th * TH + rh * VB, ps = td * TD + wd;      // this wavefront's first row
     if (ps >= a.out.ds) return;
     const int64_t gp = a.out.doff + ps - a.out.hlo;
     const bool inside = gp >= 0 && gp < a.out.dglob;
@@ -842,7 +846,7 @@ static bool wide_shape(const MfmaArgs& a) {
   return a.out.w > 16 && a.out.ds >= 3 && a.out.h >= 4 && a.csplit == 1;
 }
 
-template <int CB, int WCB = 1>
+template <int CB, int WCB = 1, int RSP = 1>
 static h3d_status launch_wide(void* handle, const bf16_t* in, const uint4* wp, const float* bias, bf16_t* out, MfmaArgs a, int n,
                               hipStream_t stream) {
   constexpr size_t lds_bytes = (size_t)2 * 2 * 6 * 10 * 36 * 16 + WCB * CB * 64 * 16;     // two stage buffers + the bias fragments
@@ -855,16 +859,17 @@ static h3d_status launch_wide(void* handle, const bf16_t* in, const uint4* wp, c
   a.ntiles = (int)ntiles;
   const int num_cu = static_cast<Handle*>(handle)->num_cu;
   const int64_t gx = std::min<int64_t>(ntiles, std::max<int64_t>(1, num_cu / gy));
-  auto kern = conv3d_mfma_wide_kernel<CB, WCB>;
+  auto kern = conv3d_mfma_wide_kernel<CB, WCB, RSP>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return fail(handle, H3D_EHIP, "conv3d: cannot raise the dynamic LDS limit to %zu bytes", lds_bytes);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(256 * WCB), lds_bytes, stream, in, wp, bias, out, a);
-  if (WCB == 1) note_kernel(handle, "conv3d_mfma_wide_kernel<%d>", CB);
-  else note_kernel(handle, "conv3d_mfma_wide_kernel<%d,%d>", CB, WCB);
+  hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(256 * WCB * RSP), lds_bytes, stream, in, wp, bias, out, a);
+  if (WCB * RSP == 1) note_kernel(handle, "conv3d_mfma_wide_kernel<%d>", CB);
+  else if (RSP == 1) note_kernel(handle, "conv3d_mfma_wide_kernel<%d,%d>", CB, WCB);
+  else note_kernel(handle, "conv3d_mfma_wide_kernel<%d,%d,%d>", CB, WCB, RSP);
   return launch_status(handle, "conv3d_mfma_wide");
 }
 
@@ -929,7 +934,15 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
       if (ntiles * cdiv(a.ncoblk, 2) * 4 < (int64_t)num_cu * 3) return launch_wide<1, 1>(handle, ip, wq, bias, op, a, out->n, stream);
       return launch_wide<1, 2>(handle, ip, wq, bias, op, a, out->n, stream);
     }
-    if (a.cin_k > 16) return launch_wide<1, 1>(handle, ip, wq, bias, op, a, out->n, stream);
+    if (a.cin_k > 16) {
+      // one block of output channels: with short channel loops (at most 32 input channels) or few tiles the eight-wavefront
+      // form that splits the rows of a plane measured faster (32->16 on 4 x 64^3 0.068 -> 0.062 ms, 32->1 on the U-Net
+      // shard 0.239 -> 0.222), with four chunks and many tiles slower (64->32 on the U-Net shard 0.480 -> 0.490)
+      const int64_t ntiles = (int64_t)out->n * cdiv(a.out.ds, 4) * cdiv(a.out.h, 8) * cdiv(a.out.w, 32);
+      if (a.nchunks <= 2 || ntiles < 2 * static_cast<Handle*>(handle)->num_cu)
+        return launch_wide<1, 1, 2>(handle, ip, wq, bias, op, a, out->n, stream);
+      return launch_wide<1, 1>(handle, ip, wq, bias, op, a, out->n, stream);
+    }
   }
   if (mask) st = vec ? pick_variant<true, true>(handle, ip, mp, wq, bias, op, a, out->n, stream)
                      : pick_variant<true, false>(handle, ip, mp, wq, bias, op, a, out->n, stream);
