@@ -106,6 +106,19 @@ def sampled_conv_case(cin, cout, n, d, hw, halo_in, halo_out, d_offset, d_global
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
     h3d.conv3d_bwd_filter(x, dz0, z0, dw2, db2, act, alpha)
     assert torch.equal(dw, dw2) and torch.equal(db, db2)      # deterministic split-spatial reduction
+    # the same call without a fused mask (the activation's derivative already applied upstream, as the benchmark's
+    # steps do it): at full shape this is the route to the unmasked kernels and their many-strip chunks
+    dwu_ref, dbu_ref = 0.0, 0.0
+    for p in ip:
+        xa = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2)
+        a, bq = orc.conv3d_bwd_filter(orc.Slab(xa[:, cis], 1, 1, d_offset + p, d_global),
+                                      orc.Slab(dzp[p][:, cos, 1:2], 0, 0, d_offset + p, d_global), None, act=orc.ACT_NONE)
+        dwu_ref, dbu_ref = dwu_ref + a, dbu_ref + bq
+    h3d.conv3d_bwd_filter(x, dz0, None, dw, db, h3d.ACT_NONE, 0.0)
+    close(from_dev(dw)[cos][:, cis], dwu_ref, 2e-4, "unmasked bwd_filter dw")
+    close(from_dev(db)[cos], dbu_ref, 2e-4, "unmasked bwd_filter db")
+    h3d.conv3d_bwd_filter(x, dz0, None, dw2, db2, h3d.ACT_NONE, 0.0)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
     return z
 
 
