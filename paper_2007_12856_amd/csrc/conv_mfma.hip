@@ -804,8 +804,53 @@ static size_t mfma_wp_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   return ((size_t)ncoblk * nchunks * 27 * 512 * sizeof(bf16_t) + 255) & ~(size_t)255;
 }
 
+bool conv3d_thin_supported(const h3d_tensor* in, const h3d_tensor* out);
+h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, bool transpose,
+                       float out_slope, void* ws, hipStream_t stream);
+
+// Backward-data onto at most 4 channels from 17 to 32 (the first layer of the U-Net-shaped level: 32 -> 1): the
+// row-streaming thin kernel holds 16 input channels in its LDS ring, so the sum over the channels is taken in two
+// passes, channels 0-15 into dx and the rest into a buffer of dx's size in the workspace, and the two are added:
+// dx = bf16(bf16(sum over the first 16) + bf16(sum over the others)), one rounding more than a single pass.
+// `in` is split into two channel-range views; both must be shapes of the row-streaming variant.
+constexpr size_t THIN2_WP_BYTES = 16384;
+static bool thin_two_pass_shape(const h3d_tensor* in, const h3d_tensor* out, h3d_tensor* ia, h3d_tensor* ib) {
+  if (in->dtype != H3D_BF16 || in->c <= 16 || in->c > 32 || out->c < 1 || out->c > 4 || !is_packed(out)) return false;
+  if (in->w % 8 || out->h < 8 || (uintptr_t)in->data % 16 || (out->data && (uintptr_t)out->data % 16)) return false;
+  const Geo g = make_geo(in);
+  if (g.cstride % 8) return false;
+  h3d_tensor a = *in, b = *in;
+  a.c = 16; a.c_stride = g.cstride; a.n_stride = g.nstride;
+  b.c = in->c - 16; b.c_stride = g.cstride; b.n_stride = g.nstride;
+  b.data = in->data ? (void*)((bf16_t*)in->data + 16 * g.cstride) : nullptr;
+  if (!conv3d_thin_supported(&a, out) || !conv3d_thin_supported(&b, out)) return false;
+  if (ia) *ia = a;
+  if (ib) *ib = b;
+  return true;
+}
+static size_t thin_two_pass_ws_bytes(const h3d_tensor* out) {
+  return THIN2_WP_BYTES + (size_t)out->n * out->c * (out->halo_lo + out->d + out->halo_hi) * out->h * out->w * sizeof(bf16_t);
+}
+// dst[i] = bf16(dst[i] + src[i]), 8 elements per thread (n8 groups), then the tail one by one
+__global__ void __launch_bounds__(256) add_bf16_kernel(bf16_t* __restrict__ dst, const bf16_t* __restrict__ src, int64_t n) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i + 8 <= n) {
+    uint4 a = *reinterpret_cast<const uint4*>(dst + i);
+    const uint4 b = *reinterpret_cast<const uint4*>(src + i);
+    auto add2 = [](uint32_t x, uint32_t y) {
+      return pack_bf16x2(__uint_as_float(x << 16) + __uint_as_float(y << 16),
+                         __uint_as_float(x & 0xffff0000u) + __uint_as_float(y & 0xffff0000u));
+    };
+    a.x = add2(a.x, b.x); a.y = add2(a.y, b.y); a.z = add2(a.z, b.z); a.w = add2(a.w, b.w);
+    *reinterpret_cast<uint4*>(dst + i) = a;
+  } else {
+    for (int64_t j = i; j < n; ++j) dst[j] = f32_to_bf16(bf16_to_f32(dst[j]) + bf16_to_f32(src[j]));
+  }
+}
+
 size_t mfma_fwd_ws_bytes(const h3d_tensor* in, const h3d_tensor* out) {
   size_t b = mfma_wp_bytes(in, out);
+  if (thin_two_pass_shape(in, out, nullptr, nullptr)) b = std::max(b, thin_two_pass_ws_bytes(out));
   const int s = mfma_splits(in, out);
   if (s > 1) b += (size_t)s * split_part_floats(out) * sizeof(float);
   return b;
@@ -893,10 +938,6 @@ static h3d_status pick_variant(void* handle, const bf16_t* in, const bf16_t* mas
                 : launch_variant<1, 8, 16, MASKED, VEC>(handle, in, mask, wp, bias, out, a, n, s);
 }
 
-bool conv3d_thin_supported(const h3d_tensor* in, const h3d_tensor* out);
-h3d_status conv3d_thin(void* handle, const h3d_tensor* in, const void* w, const float* bias, h3d_tensor* out, bool transpose,
-                       float out_slope, void* ws, hipStream_t stream);
-
 h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
                        h3d_tensor* out, bool transpose, float out_slope, float mask_slope, void* ws, size_t ws_bytes,
                        hipStream_t stream) {
@@ -912,6 +953,20 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
   if ((uintptr_t)ws % 16) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace must be 16-byte aligned");
   // a handful of output channels from at most 16 input channels: the tap-row-folding kernel
   if (!mask && conv3d_thin_supported(in, out)) return conv3d_thin(handle, in, w, bias, out, transpose, out_slope, ws, stream);
+  // .. from 17 to 32 channels, backward-data without bias and activation: two passes of it
+  h3d_tensor ia, ib;
+  if (!mask && transpose && !bias && out_slope == 1.f && thin_two_pass_shape(in, out, &ia, &ib)) {
+    h3d_tensor tmp = *out;
+    tmp.data = static_cast<char*>(ws) + THIN2_WP_BYTES;
+    H3D_TRY(conv3d_thin(handle, &ia, w, nullptr, out, true, 1.f, ws, stream));
+    // transposed packing reads w[c][m][tap] with c the channel of `in`: the second half starts 16 rows further on
+    H3D_TRY(conv3d_thin(handle, &ib, (const bf16_t*)w + (size_t)16 * out->c * 27, nullptr, &tmp, true, 1.f, ws, stream));
+    const int64_t n = (int64_t)out->n * a.out.nstride;
+    hipLaunchKernelGGL(add_bf16_kernel, dim3((unsigned)cdiv(cdiv(n, 8), 256)), dim3(256), 0, stream, (bf16_t*)out->data,
+                       (const bf16_t*)tmp.data, n);
+    note_kernel(handle, "conv3d_thin_roll (two passes)");
+    return launch_status(handle, "conv3d_thin_two_pass");
+  }
   const bool vec = (in->w % 2 == 0) && ((uintptr_t)in->data % 4 == 0) && ((uintptr_t)out->data % 4 == 0) &&
                    (!mask || (uintptr_t)mask->data % 4 == 0);
   const int cin = transpose ? a.cout_k : a.cin_k, cout = transpose ? a.cin_k : a.cout_k;

@@ -154,6 +154,10 @@ THIN_SHAPES = [
     (1, 2, 9, 9, 8, 64, 0),
     (1, 3, 16, 4, 20, 72, 1),
     (1, 4, 12, 2, 70, 32, 1),
+    # backward-data onto at most 4 channels from 17 to 32: two passes of the row-streaming kernel over channel halves
+    (1, 1, 32, 5, 12, 72, 1),
+    (2, 4, 24, 3, 9, 40, 0),
+    (1, 2, 17, 4, 16, 136, 1),
 ]
 
 
