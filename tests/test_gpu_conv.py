@@ -141,6 +141,36 @@ def test_conv3d_bwd_filter_unmasked_bf16(shape, kernel, monkeypatch):
         assert h3d.h3d_last_kernel().startswith("bwd_filter_row32_kernel"), h3d.h3d_last_kernel()
 
 
+def _row32_random_shapes(k=8):
+    rng = np.random.default_rng(SEED + 77)
+    out = []
+    for _ in range(k):
+        out.append((int(rng.integers(1, 4)), int(rng.integers(33, 81)), int(rng.integers(33, 81)), int(rng.integers(1, 6)),
+                    int(rng.integers(1, 21)), int(rng.choice([16, 24, 32, 40, 48, 64, 72, 96])), int(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("shape", _row32_random_shapes())
+def test_conv3d_bwd_filter_many_channels_random_shapes(shape, monkeypatch):
+    """Seeded random shapes for the kernel on the 32x32x16 tile (test hook H3D_BF_ROW32, see above): ragged channel
+    blocks, bands, K-steps and chunks in combinations nobody picked by hand."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    monkeypatch.setenv("H3D_BF_ROW32", "1")
+    N, Ci, Co, D, H, W, halo = shape
+    dtype = "bf16"
+    Dg, off = (D + 2, 1) if halo else (D, 0)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 32, (N, Ci, D + 2 * halo, H, W)), dtype, (halo, halo), off, Dg)
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 33, (N, Co, D, H, W)), dtype, (0, 0), off, Dg)
+    dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, None, act=orc.ACT_NONE)
+    dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
+    db = torch.full((Co,), 777.0, device="cuda")
+    h3d.conv3d_bwd_filter(xg, dzg, None, dw, db, h3d.ACT_NONE, 0.0)
+    assert h3d.h3d_last_kernel().startswith("bwd_filter_row32_kernel"), h3d.h3d_last_kernel()
+    close(from_dev(dw), dwo, 2e-4, f"dw {shape}")
+    close(from_dev(db), dbo, 2e-4, f"db {shape}")
+
+
 # (N, Cin, Cout, D, H, W, halo): layers with a handful of channels on one side and at most 16 on the other, wide
 # enough for the tap-row-folding kernel: backward-data onto <= 8 channels (no fused mask), forward onto <= 8
 THIN_SHAPES = [
