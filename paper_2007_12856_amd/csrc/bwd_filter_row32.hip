@@ -123,7 +123,6 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_row32_kernel(const bf16_t* 
   };
   h3d_i32x4 rs_g = {0, 0, 0, 0}, rs_x = {0, 0, 0, 0};
   const uint32_t xl_addr = lds_addr_of(xl), gl_addr = lds_addr_of(gl);
-  // planes p whose x plane p + kd - 1 lies inside the volume
   // planes p whose x plane p + kd - 1 lies inside the volume: the others are neither loaded nor multiplied
   const int p_lo = (int)max((int64_t)0, 1 - kd - a.x.doff), p_hi = (int)min((int64_t)D, a.x.dglob - a.x.doff - kd + 1);
   auto planes_ok = [&](int p) { return p >= p_lo && p < p_hi; };

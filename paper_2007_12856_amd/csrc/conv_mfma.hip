@@ -989,7 +989,7 @@ h3d_status conv3d_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mas
       if (ntiles * cdiv(a.ncoblk, 2) * 4 < (int64_t)num_cu * 3) return launch_wide<1, 1>(handle, ip, wq, bias, op, a, out->n, stream);
       return launch_wide<1, 2>(handle, ip, wq, bias, op, a, out->n, stream);
     }
-    if (a.cin_k > 16) {
+    if (a.cin_k > 8) {      // (16 input channels = one chunk per tile: 16->32 on 4 x 64^3 0.056 ms with the kernel above, 0.043 here)
       // one block of output channels: with short channel loops (at most 32 input channels) or few tiles the eight-wavefront
       // form that splits the rows of a plane measured faster (32->16 on 4 x 64^3 0.068 -> 0.062 ms, 32->1 on the U-Net
       // shard 0.239 -> 0.222), with four chunks and many tiles slower (64->32 on the U-Net shard 0.480 -> 0.490)
