@@ -35,9 +35,10 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_FP32_VALU_TFLOPS = 157.3
+PEAK_MFMA_F32_TFLOPS = 157.3          # fp32 tensors: v_mfma_f32_16x16x4_f32
 RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
 ALL = ["unet", "cosmoflow", "shard512", "late256", "single32"]
-OTHERS = ["table1", "chain512", "k5", "split256", "bn"]
+OTHERS = ["table1", "chain512", "k5", "split256", "bn", "layer_f32"]
 
 
 # ----------------------------------------------------------------------------------------------- CPU baseline
@@ -237,6 +238,9 @@ def build_workload(name, args, seed):
     if name == "single32":
         net = _single_layer(seed, 1, 4, 16, 32, 32, 0, 32, torch.float32, pool=False)
         return net, "single layer, fp32: N=1, 4->16 channels, 32^3, bias + leaky-ReLU, fwd / bwd-data / bwd-filter", 32 ** 3, "f32"
+    if name == "layer_f32":
+        net = _single_layer(seed, 1, 32, 64, 32, 128, 0, 32, torch.float32, pool=False)
+        return net, "one layer in the paper's precision: fp32 storage and arithmetic, 32->64 channels on 32x128x128, fwd / bwd-data / bwd-filter", 32 * 128 * 128, "f32"
     if name == "split256":
         net = _single_layer(seed, 1, 64, 64, 32, 256, 32, 256, bf, pool=False, split=True)
         return net, "one 8-way depth shard of a 64-channel 256^3 sample: conv 64->64 whole, and as main planes + two 1-plane strips", 32 * 256 * 256, "bf16"
@@ -334,13 +338,15 @@ def measured_traffic(workload, kernel):
     return None
 
 
-def fractions(flops, nbytes, ms, ceil):
-    """TFLOP/s, GB/s and their fractions of the published peaks and of the ceilings measured by the probes."""
+def fractions(flops, nbytes, ms, ceil, dtype="bf16"):
+    """TFLOP/s, GB/s and their fractions of the published peaks and of the ceilings measured by the probes.  The matrix-core
+    peak is that of the tensors' own type (bf16: 2500 TFLOP/s, fp32: 157.3); the measured ceiling exists for bf16 only."""
     out = {}
+    peak = PEAK_MFMA_F32_TFLOPS if dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
     if flops:
         tf = flops / ms / 1e9
-        out.update(tflops=round(tf, 2), mfma_frac=round(tf / PEAK_MFMA_BF16_TFLOPS, 4))
-        if ceil:
+        out.update(tflops=round(tf, 2), mfma_frac=round(tf / peak, 4))
+        if ceil and dtype != "f32":
             out["mfma_frac_of_measured"] = round(tf / ceil["mfma_32x32x16_bf16_tflops"], 4)
     if nbytes:
         gb = nbytes / ms / 1e6
@@ -348,7 +354,7 @@ def fractions(flops, nbytes, ms, ceil):
         if ceil:
             out["hbm_frac_of_measured"] = round(gb / ceil["copy_1GiB_gbs_read_plus_written"], 4)
     if flops or nbytes:
-        out["bound"] = "mfma" if flops and flops / max(nbytes, 1) >= RIDGE else "hbm"
+        out["bound"] = "mfma" if flops and flops / max(nbytes, 1) >= peak * 1e12 / (PEAK_HBM_GBS * 1e9) else "hbm"
     return out
 
 
@@ -433,15 +439,15 @@ def run_workload(name, args, seed, ceil, steps, warmup, passes, events_for=None)
         row = {"name": o["name"], "ms": round(ms, 4)}
         if k:
             row["kernel"] = k
-        row.update(fractions(o["flops"], o["bytes"], ms, ceil))
+        row.update(fractions(o["flops"], o["bytes"], ms, ceil, dtype))
         per_call.append(row)
     for g in ktable:
-        g.update(fractions(g["flops"], g["bytes"], g["ms"], ceil))
+        g.update(fractions(g["flops"], g["bytes"], g["ms"], ceil, dtype))
         g["ms"] = round(g["ms"], 4)
         g["share_of_step"] = round(g["ms"] / sum(med), 4)
     res = {"workload": label, "dtype": dtype, "ms_per_step": round(ms_per_step, 4), "ms_per_step_sum_of_calls": round(sum(med), 4),
            "conv_gflop_per_step": round(flops / 1e9, 2), "tflops": round(flops / ms_per_step / 1e9, 2),
-           "mfma_frac": round(flops / ms_per_step / 1e9 / PEAK_MFMA_BF16_TFLOPS, 4), "voxels_per_s": round(voxels / (ms_per_step * 1e-3), 1),
+           "mfma_frac": round(flops / ms_per_step / 1e9 / (PEAK_MFMA_F32_TFLOPS if dtype == "f32" else PEAK_MFMA_BF16_TFLOPS), 4), "voxels_per_s": round(voxels / (ms_per_step * 1e-3), 1),
            "steps": steps, "passes": passes, "setup_s": round(t_build, 1), "per_kernel": ktable, "per_call": per_call}
     if dom:
         per_step = {}
@@ -555,14 +561,16 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": H["dtype"], "data": "synthetic",
         "config": {"workload": H["workload"], "name": head},
         "voxels_per_s": H["voxels_per_s"], "conv_gflop_per_step": H["conv_gflop_per_step"],
-        "pct_of_bf16_mfma_peak": round(100.0 * H["mfma_frac"], 2),
+        ("pct_of_fp32_mfma_peak" if H["dtype"] == "f32" else "pct_of_bf16_mfma_peak"): round(100.0 * H["mfma_frac"], 2),
     }
+    f32 = H["dtype"] == "f32"
+    mfma_peak = PEAK_MFMA_F32_TFLOPS if f32 else PEAK_MFMA_BF16_TFLOPS
     d = H.get("dominant")
     if d:
         ms = d["ms_per_launch"]
-        if d["flops_per_launch"] and d["flops_per_launch"] / max(d["bytes_per_launch"], 1) >= RIDGE:
-            roof = {"bound": "mfma", "achieved": d["flops_per_launch"] / ms / 1e9, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s"}
-            if ceil:
+        if d["flops_per_launch"] and d["flops_per_launch"] / max(d["bytes_per_launch"], 1) >= mfma_peak * 1e12 / (PEAK_HBM_GBS * 1e9):
+            roof = {"bound": "mfma", "achieved": d["flops_per_launch"] / ms / 1e9, "peak": mfma_peak, "unit": "TFLOP/s"}
+            if ceil and not f32:
                 roof["frac_of_measured_ceiling"] = roof["achieved"] / ceil["mfma_32x32x16_bf16_tflops"]
         else:
             roof = {"bound": "hbm", "achieved": d["bytes_per_launch"] / ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s"}

@@ -15,6 +15,16 @@ h3d_status conv3d_direct(void* handle, const h3d_tensor* in, const h3d_tensor* m
 template <typename T>
 h3d_status bwd_filter_direct(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw,
                              float* db, float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream);
+// conv_f32_mfma.hip
+bool f32_mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out);
+size_t f32_mfma_fwd_ws_bytes(int cin_k, int cout_k);
+h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
+                           h3d_tensor* out, bool transpose, float out_slope, float mask_slope, void* ws, size_t ws_bytes,
+                           hipStream_t stream);
+bool f32_mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz);
+size_t f32_mfma_bf_ws_bytes(const h3d_tensor* x, int cout);
+h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw,
+                               float* db, float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream);
 // conv_small_cin.hip
 bool c4_fwd_supported(const h3d_tensor* in, const h3d_tensor* out);
 bool c4_fwd_pool_supported(const h3d_tensor* in, const h3d_tensor* z, const h3d_tensor* y);
@@ -67,10 +77,13 @@ extern "C" size_t h3d_conv3d_workspace_bytes(void* handle, int op, const h3d_ten
     case H3D_OP_BWD_DATA:  // x: dz (input of the correlation), z: dx
       b = std::max(b, direct_fwd_ws_bytes(x->c, z->c));
       if (mfma_fwd_supported(x, z)) b = std::max(b, mfma_fwd_ws_bytes(x, z));
+      if (f32_mfma_fwd_supported(x, z)) b = std::max(b, f32_mfma_fwd_ws_bytes(x->c, z->c));
       break;
     case H3D_OP_BWD_FILTER:  // x: activations, z: dz
-      b = direct_bf_ws_bytes(x, z->c);
-      if (mfma_bf_supported(x, z)) b = std::max(b, mfma_bf_ws_bytes(x, z));
+      // the size of the one kernel family h3d_conv3d_bwd_filter gives these shapes to (same order of tests as there)
+      if (mfma_bf_supported(x, z)) b = mfma_bf_ws_bytes(x, z);
+      else if (f32_mfma_bf_supported(x, z)) b = f32_mfma_bf_ws_bytes(x, z->c);
+      else b = direct_bf_ws_bytes(x, z->c);
       break;
     default:
       return 0;
@@ -91,6 +104,7 @@ extern "C" h3d_status h3d_conv3d_fwd(void* handle, const h3d_tensor* x, const vo
   if (c4_roll_supported(x, z)) return conv3d_fwd_c4_roll(handle, x, w, bias, z, nullptr, nullptr, slope, ws, ws_bytes, s);
   if (c4_fwd_supported(x, z)) return conv3d_fwd_c4(handle, x, w, bias, z, slope, ws, ws_bytes, s);
   if (mfma_fwd_supported(x, z)) return conv3d_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
+  if (f32_mfma_fwd_supported(x, z)) return conv3d_f32_mfma(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return conv3d_direct<float>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
   return conv3d_direct<bf16_t>(handle, x, nullptr, w, bias, z, false, slope, 1.f, ws, ws_bytes, s);
 }
@@ -142,6 +156,7 @@ extern "C" h3d_status h3d_conv3d_bwd_data(void* handle, const h3d_tensor* dz, co
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
   if (mfma_fwd_supported(dz, dx)) return conv3d_mfma(handle, dz, z, w, nullptr, dx, true, 1.f, slope, ws, ws_bytes, s);
+  if (f32_mfma_fwd_supported(dz, dx)) return conv3d_f32_mfma(handle, dz, z, w, nullptr, dx, true, 1.f, slope, ws, ws_bytes, s);
   if (dz->dtype == H3D_F32) return conv3d_direct<float>(handle, dz, z, w, nullptr, dx, true, 1.f, slope, ws, ws_bytes, s);
   return conv3d_direct<bf16_t>(handle, dz, z, w, nullptr, dx, true, 1.f, slope, ws, ws_bytes, s);
 }
@@ -164,6 +179,7 @@ extern "C" h3d_status h3d_conv3d_bwd_filter(void* handle, const h3d_tensor* x, c
   const float slope = act_slope(act, alpha);
   hipStream_t s = (hipStream_t)stream;
   if (mfma_bf_supported(x, dz)) return bwd_filter_mfma(handle, x, dz, z, dw, db, slope, ws, ws_bytes, s);
+  if (f32_mfma_bf_supported(x, dz)) return bwd_filter_f32_mfma(handle, x, dz, z, dw, db, slope, ws, ws_bytes, s);
   if (x->dtype == H3D_F32) return bwd_filter_direct<float>(handle, x, dz, z, dw, db, slope, ws, ws_bytes, s);
   return bwd_filter_direct<bf16_t>(handle, x, dz, z, dw, db, slope, ws, ws_bytes, s);
 }

@@ -1,0 +1,503 @@
+// 3x3x3 convolution passes (Sec. III-C: FP, BD, BF) on fp32 tensors, on the matrix cores: v_mfma_f32_16x16x4_f32,
+// fp32 products and fp32 accumulation (the paper's own precision).  The vector-ALU kernels of conv_direct.hip stay as
+// the fallback for tensors these kernels' 32-bit offsets cannot address.
+//
+//  * forward / backward-data (one kernel; BD = the same correlation of g = dz * act'(z) with the filter transposed and
+//    reversed by the pack kernel): implicit GEMM with M = 16 voxels of a row, N = 16 output channels, K = 4 input
+//    channels of one tap.  A workgroup of four wavefronts owns 4 planes x 8 rows x 32 columns x (16 CB) output
+//    channels, a wavefront one plane: 16 CB accumulator tiles.  Per group of 4 input channels the tile with its halo
+//    (6 x 10 x 34 voxels) and the 27 x 4 x 16 CB weights are staged in LDS; per (kd, kw) the 10 input rows are read
+//    once (20 fragments) and feed 3 kh x 16 CB products.  The result leaves as 16-byte stores (4 voxels of one channel
+//    per lane).  Two workgroups per CU: one stages while the other multiplies.
+//  * backward-filter: M = 16 input channels, N = 16 output channels, K = 4 voxels of a row.  A workgroup owns a
+//    16 x 16 block of the filter and a fixed chunk of 4-row x 32-column tiles of the voxel range; each wavefront takes
+//    one row of the tile and keeps 27 accumulator tiles (one per tap) plus one for the bias gradient (the product of g
+//    with a column of ones).  The four wavefronts' sums are added in wavefront order, the chunks' partial sums in
+//    chunk order by a second kernel: the same bits on every run.
+#include <algorithm>
+
+#include "common.h"
+
+namespace h3d {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// -------------------------------------------------------------------------------------- forward / backward-data
+constexpr int FT_P = 4, FT_R = 8, FT_W = 32;                    // output tile: planes, rows, columns
+constexpr int FX_P = FT_P + 2, FX_R = FT_R + 2, FX_C = FT_W + 2; // staged input planes, rows, columns
+constexpr int FX_RP = 36;                                        // row pitch in LDS (floats)
+constexpr int FX_PS = FX_R * FX_RP;                              // plane pitch
+constexpr int FX_CS = FX_P * FX_PS;                              // channel pitch: 2160 = 48 mod 64, so the four channels
+                                                                 // of a fragment read land in four different bank groups
+constexpr int FX_SP = FX_P * FX_R * FX_C;                        // staged voxels per channel (2040)
+constexpr int FX_PT = (FX_SP + 255) / 256;                       // per thread and channel (8)
+
+// w: [cout][cin][27] fp32 -> wk: [co group][ci group][27][4][NC]  (NC = 16 CB output channels, zeros where padded)
+// fwd:      kernel-view (co_k, ci_k, t) = w[co_k][ci_k][t]
+// bwd-data: kernel-view (co_k, ci_k, t) = w[ci_k][co_k][26 - t]      (cin_k = cout, cout_k = cin)
+__global__ void pack_w_f32_mfma_kernel(const float* __restrict__ w, float* __restrict__ wk, int cin, int cout, int transpose,
+                                       int ncig, int nc, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int cin_k = transpose ? cout : cin, cout_k = transpose ? cin : cout;
+  const int j = (int)(i % nc);
+  const int c = (int)((i / nc) % 4);
+  const int t = (int)((i / (4 * nc)) % 27);
+  const int cig = (int)((i / (108 * (int64_t)nc)) % ncig);
+  const int cog = (int)(i / (108 * (int64_t)nc * ncig));
+  const int ok = cog * nc + j, ik = cig * 4 + c;
+  float v = 0.f;
+  if (ok < cout_k && ik < cin_k) v = transpose ? w[((int64_t)ik * cin + ok) * 27 + (26 - t)] : w[((int64_t)ok * cin + ik) * 27 + t];
+  wk[i] = v;
+}
+
+struct F32Args {
+  Geo in, mask, out;
+  int cin, cout, ncig;
+  int npg, nhg, nwg;      // plane groups (over the stored planes of out), row groups, column groups
+  float out_slope, mask_slope;
+  int vec;                // 16-byte stores allowed
+};
+
+template <int CB, bool MASKED>
+__global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __restrict__ in, const float* __restrict__ mask,
+                                                                 const float* __restrict__ wk, const float* __restrict__ bias,
+                                                                 float* __restrict__ out, F32Args a) {
+  constexpr int NC = 16 * CB;
+  constexpr int WSZ = 27 * 4 * NC;                 // weights of one channel group (floats)
+  __shared__ float lds_x[4 * FX_CS];
+  __shared__ __attribute__((aligned(16))) float lds_w[WSZ];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int W = a.out.w, H = a.out.h;
+  int t = blockIdx.x;
+  const int wg = t % a.nwg; t /= a.nwg;
+  const int hg = t % a.nhg; t /= a.nhg;
+  const int pg = t % a.npg;
+  const int n = t / a.npg;
+  const int cog = blockIdx.y;
+  const int ps0 = pg * FT_P, h0 = hg * FT_R, w0 = wg * FT_W;
+
+  // what this thread stages of every channel: offsets in the tensor (-1: outside the volume, reads as zero) and in LDS
+  int xoff[FX_PT], moff[FX_PT], loff[FX_PT];
+#pragma unroll
+  for (int i = 0; i < FX_PT; ++i) {
+    const int s = tid + 256 * i;
+    const int col = s % FX_C, row = (s / FX_C) % FX_R, pl = s / (FX_C * FX_R);
+    loff[i] = s < FX_SP ? pl * FX_PS + row * FX_RP + col : -1;
+    const int q = ps0 - a.out.hlo - 1 + pl;                 // local plane index of the input
+    const int64_t gq = a.in.doff + q;
+    const int sp = q + a.in.hlo, hh = h0 - 1 + row, ww = w0 - 1 + col;
+    const bool ok = s < FX_SP && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && hh >= 0 && hh < H && ww >= 0 && ww < W;
+    xoff[i] = ok ? (int)(sp * a.in.plane + (int64_t)hh * W + ww) : -1;
+    if (MASKED) {
+      const int sm = q + a.mask.hlo;
+      const bool mok = ok && sm >= 0 && sm < a.mask.ds;
+      moff[i] = mok ? (int)(sm * a.mask.plane + (int64_t)hh * W + ww) : -1;
+      if (!mok) xoff[i] = -1;
+    }
+  }
+
+  const int ps = ps0 + wave;                               // stored plane of out this wavefront computes
+  const bool live = ps < a.out.ds;
+  const int64_t gp = a.out.doff + ps - a.out.hlo;
+  const bool inside = gp >= 0 && gp < a.out.dglob;
+
+  f32x4 acc[CB][FT_R][2];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    const int co = cog * NC + cb * 16 + (lane & 15);
+    const float b = (bias && co < a.cout) ? bias[co] : 0.f;
+#pragma unroll
+    for (int r = 0; r < FT_R; ++r)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) acc[cb][r][hf] = f32x4{b, b, b, b};
+  }
+
+  const float* xw = lds_x + (lane >> 4) * FX_CS + wave * FX_PS + (lane & 15);
+  const float* ww_ = lds_w + (lane >> 4) * NC + (lane & 15);
+  const float* in_n = in + (int64_t)n * a.in.nstride;
+  const float* mk_n = MASKED ? mask + (int64_t)n * a.mask.nstride : nullptr;
+
+  for (int cig = 0; cig < a.ncig; ++cig) {
+    // ---- stage 4 input channels (tile + halo) and their weights
+    float v[4][FX_PT];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int ci = cig * 4 + c;
+      const bool cok = ci < a.cin;
+      const float* xc = in_n + (int64_t)ci * a.in.cstride;
+      const float* mc = MASKED ? mk_n + (int64_t)ci * a.mask.cstride : nullptr;
+#pragma unroll
+      for (int i = 0; i < FX_PT; ++i) {
+        float x = 0.f;
+        if (cok && xoff[i] >= 0) {
+          x = xc[xoff[i]];
+          if (MASKED) {
+            const float m = mc[moff[i]];
+            if (!(m > 0.f)) x *= a.mask_slope;
+          }
+        }
+        v[c][i] = x;
+      }
+    }
+    const f32x4* wsrc = reinterpret_cast<const f32x4*>(wk + ((int64_t)cog * a.ncig + cig) * WSZ);
+    f32x4 wv[(WSZ / 4 + 255) / 256];
+#pragma unroll
+    for (int i = 0; i < (WSZ / 4 + 255) / 256; ++i) {
+      const int j = tid + 256 * i;
+      wv[i] = j < WSZ / 4 ? wsrc[j] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    __syncthreads();                                       // everyone is done with the previous group's tile
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int i = 0; i < FX_PT; ++i)
+        if (loff[i] >= 0) lds_x[c * FX_CS + loff[i]] = v[c][i];
+#pragma unroll
+    for (int i = 0; i < (WSZ / 4 + 255) / 256; ++i) {
+      const int j = tid + 256 * i;
+      if (j < WSZ / 4) reinterpret_cast<f32x4*>(lds_w)[j] = wv[i];
+    }
+    __syncthreads();
+
+    // ---- products: per (kd, kw) the ten rows are read once and meet the three kh weight fragments
+    if (live) {
+#pragma unroll
+      for (int kd = 0; kd < 3; ++kd) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          float bx[FX_R][2];
+#pragma unroll
+          for (int r = 0; r < FX_R; ++r)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) bx[r][hf] = xw[kd * FX_PS + r * FX_RP + hf * 16 + kw];
+#pragma unroll
+          for (int kh = 0; kh < 3; ++kh) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+              const float aw = ww_[((kd * 3 + kh) * 3 + kw) * 4 * NC + cb * 16];
+#pragma unroll
+              for (int r = 0; r < FT_R; ++r)
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+                  acc[cb][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r + kh][hf], aw, acc[cb][r][hf], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // ---- epilogue: activation, zero outside the volume, 16-byte stores of 4 voxels of one channel
+  if (!live) return;
+  float* on = out + (int64_t)n * a.out.nstride + (int64_t)ps * a.out.plane;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    const int co = cog * NC + cb * 16 + (lane & 15);
+    if (co >= a.cout) continue;
+    float* oc = on + (int64_t)co * a.out.cstride;
+#pragma unroll
+    for (int r = 0; r < FT_R; ++r) {
+      const int h = h0 + r;
+      if (h >= H) continue;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int wc = w0 + hf * 16 + 4 * (lane >> 4);
+        if (wc >= W) continue;
+        f32x4 o = acc[cb][r][hf];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float x = o[j];
+          if (!(x > 0.f)) x *= a.out_slope;
+          o[j] = inside ? x : 0.f;
+        }
+        float* p = oc + (int64_t)h * W + wc;
+        if (a.vec && wc + 3 < W) {
+          *reinterpret_cast<f32x4*>(p) = o;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (wc + j < W) p[j] = o[j];
+        }
+      }
+    }
+  }
+}
+
+static int f32_cb(int cout_k) { return cout_k <= 16 ? 1 : 2; }
+
+static bool fits_i32(const h3d_tensor* t) {
+  return (int64_t)(t->halo_lo + t->d + t->halo_hi) * t->h * t->w < ((int64_t)1 << 31);
+}
+
+bool f32_mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
+  return in->dtype == H3D_F32 && out->dtype == H3D_F32 && in->c > 0 && out->c > 0 && fits_i32(in) && fits_i32(out);
+}
+
+size_t f32_mfma_fwd_ws_bytes(int cin_k, int cout_k) {
+  const int nc = 16 * f32_cb(cout_k);
+  return (size_t)cdiv(cout_k, nc) * cdiv(cin_k, 4) * 108 * nc * sizeof(float);
+}
+
+h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor* mask, const void* w, const float* bias,
+                           h3d_tensor* out, bool transpose, float out_slope, float mask_slope, void* ws, size_t ws_bytes,
+                           hipStream_t stream) {
+  const int cin_k = in->c, cout_k = out->c;
+  const int cin = transpose ? cout_k : cin_k, cout = transpose ? cin_k : cout_k;
+  const int cb = f32_cb(cout_k), nc = 16 * cb;
+  if (!ws || ws_bytes < f32_mfma_fwd_ws_bytes(cin_k, cout_k)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
+  if (mask && !fits_i32(mask)) return fail(handle, H3D_EUNSUPPORTED, "conv3d: z too large for this kernel");
+  F32Args a;
+  a.in = make_geo(in);
+  a.mask = mask ? make_geo(mask) : a.in;
+  a.out = make_geo(out);
+  a.cin = cin_k; a.cout = cout_k; a.ncig = (int)cdiv(cin_k, 4);
+  a.npg = (int)cdiv(a.out.ds, FT_P); a.nhg = (int)cdiv(out->h, FT_R); a.nwg = (int)cdiv(out->w, FT_W);
+  a.out_slope = out_slope; a.mask_slope = mask_slope;
+  a.vec = (out->w % 4 == 0) && (a.out.cstride % 4 == 0) && (a.out.nstride % 4 == 0) && ((uintptr_t)out->data % 16 == 0);
+  const int64_t tiles = (int64_t)out->n * a.npg * a.nhg * a.nwg;
+  const int ncog = (int)cdiv(cout_k, nc);
+  if (tiles == 0) return H3D_OK;
+  if (tiles >= ((int64_t)1 << 31) || ncog > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many blocks");
+  const int64_t nw = (int64_t)ncog * a.ncig * 108 * nc;
+  hipLaunchKernelGGL(pack_w_f32_mfma_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
+                     cin, cout, transpose ? 1 : 0, a.ncig, nc, nw);
+  const dim3 g((unsigned)tiles, (unsigned)ncog);
+#define H3D_F32_LAUNCH(CBV, MK)                                                                                         \
+  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, MK>), g, dim3(256), 0, stream, (const float*)in->data,                \
+                     (const float*)(mask ? mask->data : nullptr), (const float*)ws, bias, (float*)out->data, a)
+  if (cb == 1) {
+    if (mask) H3D_F32_LAUNCH(1, true); else H3D_F32_LAUNCH(1, false);
+  } else {
+    if (mask) H3D_F32_LAUNCH(2, true); else H3D_F32_LAUNCH(2, false);
+  }
+#undef H3D_F32_LAUNCH
+  note_kernel(handle, "conv3d_f32_mfma_kernel<%d>", cb);
+  return launch_status(handle, "conv3d_f32_mfma");
+}
+
+// ------------------------------------------------------------------------------------------------ backward-filter
+constexpr int BT_R = 4, BT_W = 32;                 // tile of output voxels: rows, columns (one plane)
+constexpr int BX_R = BT_R + 2, BX_C = BT_W + 2;    // staged rows and columns of x (three planes)
+constexpr int BX_SP = 3 * BX_R * BX_C;             // 612 staged voxels per channel
+constexpr int BX_CS = 644;                         // channel pitch of x in LDS: 4 mod 64 (a fragment read takes lane
+                                                   // (c, k) to bank 4 c + k)
+constexpr int BG_CS = BT_R * BT_W + 4;             // channel pitch of g: 132 = 4 mod 64
+
+struct F32BfArgs {
+  Geo x, dz, z;
+  int cin, cout;
+  int nhg, nwg;
+  int64_t tiles;            // n * d * nhg * nwg
+  int tiles_per_chunk;
+  float mask_slope;
+};
+
+// partial sums: [chunk][cout][cin][28] (slot 27 = bias gradient, written for ci == 0 only)
+template <bool MASKED>
+__global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dz,
+                                                                     const float* __restrict__ z, float* __restrict__ part,
+                                                                     F32BfArgs a) {
+  __shared__ float lds_x[16 * BX_CS];
+  __shared__ float lds_g[16 * BG_CS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, cog = blockIdx.y, cig = blockIdx.z;
+  const int W = a.x.w, H = a.x.h, D = a.x.d;
+  f32x4 acc[28];
+#pragma unroll
+  for (int t = 0; t < 28; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const float* xr = lds_x + (lane & 15) * BX_CS + wave * BX_C + (lane >> 4);
+  const float* gr = lds_g + (lane & 15) * BG_CS + wave * BT_W + (lane >> 4);
+
+  // what this thread stages of a tile: three voxels of the x window in each of the 16 input channels, and one voxel of
+  // the g tile in 8 of the 16 output channels.  The loads of the next tile are issued before the products of the present
+  // one and land in registers meanwhile.
+  constexpr int BX_PT = (BX_SP + 255) / 256;              // 3
+  float xv[BX_PT][16], gv[8], zv[8];
+  const int gs = tid & 127, gc0 = (tid >> 7) * 8;         // g: voxel of the tile, first of this thread's channels
+  const int nci = min(16, a.cin - cig * 16), nco = min(16, a.cout - cog * 16);
+  auto load_tile = [&](int64_t tile) {
+    int64_t r = tile;
+    const int wg = (int)(r % a.nwg); r /= a.nwg;
+    const int hg = (int)(r % a.nhg); r /= a.nhg;
+    const int p = (int)(r % D);
+    const int n = (int)(r / D);
+    const int h0 = hg * BT_R, w0 = wg * BT_W;
+    const float* xb = x + (int64_t)n * a.x.nstride + (int64_t)(cig * 16) * a.x.cstride;
+#pragma unroll
+    for (int i = 0; i < BX_PT; ++i) {
+      const int s = tid + 256 * i;
+      const int col = s % BX_C, row = (s / BX_C) % BX_R, pl = s / (BX_C * BX_R);
+      const int q = p + pl - 1;
+      const int64_t gq = a.x.doff + q;
+      const int sp = q + a.x.hlo, hh = h0 - 1 + row, ww = w0 - 1 + col;
+      const bool ok = s < BX_SP && gq >= 0 && gq < a.x.dglob && sp >= 0 && sp < a.x.ds && hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const float* xp = xb + ((int64_t)sp * a.x.plane + (int64_t)hh * W + ww);
+#pragma unroll
+      for (int c = 0; c < 16; ++c) xv[i][c] = (ok && c < nci) ? xp[(int64_t)c * a.x.cstride] : 0.f;
+    }
+    const int hh = h0 + gs / BT_W, ww = w0 + gs % BT_W;
+    const bool gok = hh < H && ww < W;
+    const float* gp = dz + (int64_t)n * a.dz.nstride + (int64_t)(cog * 16 + gc0) * a.dz.cstride + (int64_t)(p + a.dz.hlo) * a.dz.plane + (int64_t)hh * W + ww;
+    const float* zp = MASKED ? z + (int64_t)n * a.z.nstride + (int64_t)(cog * 16 + gc0) * a.z.cstride + (int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)hh * W + ww : nullptr;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = gok && gc0 + j < nco;
+      gv[j] = ok ? gp[(int64_t)j * a.dz.cstride] : 0.f;
+      if (MASKED) zv[j] = ok ? zp[(int64_t)j * a.z.cstride] : 1.f;
+    }
+  };
+
+  const int64_t t0 = (int64_t)chunk * a.tiles_per_chunk;
+  const int64_t t1 = min(t0 + a.tiles_per_chunk, a.tiles);
+  if (t0 < t1) load_tile(t0);
+  for (int64_t tile = t0; tile < t1; ++tile) {
+    __syncthreads();                                      // the previous tile's fragments have been read
+#pragma unroll
+    for (int i = 0; i < BX_PT; ++i) {
+      const int s = tid + 256 * i;
+      if (s < BX_SP) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) lds_x[c * BX_CS + s] = xv[i][c];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float v = gv[j];
+      if (MASKED && !(zv[j] > 0.f)) v *= a.mask_slope;    // g = dz * act'(z)
+      lds_g[(gc0 + j) * BG_CS + gs] = v;
+    }
+    __syncthreads();
+    if (tile + 1 < t1) load_tile(tile + 1);
+    // ---- this wavefront's row: 8 steps of 4 voxels, 27 taps + the bias gradient
+#pragma unroll 2
+    for (int ks = 0; ks < BT_W / 4; ++ks) {
+      const float g = gr[4 * ks];
+#pragma unroll
+      for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+          for (int kw = 0; kw < 3; ++kw) {
+            const float xf = xr[kd * (BX_R * BX_C) + kh * BX_C + 4 * ks + kw];
+            acc[(kd * 3 + kh) * 3 + kw] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf, g, acc[(kd * 3 + kh) * 3 + kw], 0, 0, 0);
+          }
+      acc[27] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[27], 0, 0, 0);
+    }
+  }
+
+  // ---- the four wavefronts' sums, added in wavefront order through LDS (the x tile's space: 28 x 1024 B x 4 <= 41 KB)
+  float* red = lds_x;
+  for (int wv = 0; wv < 4; ++wv) {
+    __syncthreads();
+    if (wave == wv) {
+#pragma unroll
+      for (int t = 0; t < 28; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int idx = (t * 4 + j) * 64 + lane;
+          if (wv == 0) red[idx] = acc[t][j];
+          else if (wv < 3) red[idx] += acc[t][j];
+          else acc[t][j] += red[idx];
+        }
+    }
+  }
+  if (wave != 3) return;
+  // lane holds ci = 4 (lane / 16) + j, co = lane % 16 of every tap
+  const int co = cog * 16 + (lane & 15);
+  if (co >= a.cout) return;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int ci = cig * 16 + 4 * (lane >> 4) + j;
+    if (ci >= a.cin) continue;
+    float* pp = part + (((int64_t)chunk * a.cout + co) * a.cin + ci) * 28;
+#pragma unroll
+    for (int t = 0; t < 27; ++t) pp[t] = acc[t][j];
+    if (ci == 0) pp[27] = acc[27][j];
+  }
+}
+
+// dw / db = the chunks' partial sums added in a fixed order: a block takes 16 consecutive elements of a chunk row; each
+// of its 16 thread groups adds every 16th chunk in increasing order (eight loads in flight), then the 16 group sums are
+// added in group order.
+__global__ void __launch_bounds__(256) bwd_filter_f32_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                                    float* __restrict__ db, int cin, int cout, int nchunks) {
+  constexpr int G = 16;
+  __shared__ float red[G][17];
+  const int o = threadIdx.x & 15, cg = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + o;
+  const int64_t total = (int64_t)cout * cin * 28;
+  const int t = (int)(i % 28);
+  const int ci = (int)((i / 28) % cin);
+  const int co = (int)(i / (28 * (int64_t)cin));
+  const bool want = i < total && (t < 27 || (ci == 0 && db));
+  float s = 0.f;
+  if (want) {
+    const float* base = part + i;
+    int c = cg;
+    for (; c + 7 * G < nchunks; c += 8 * G) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)(c + u * G) * total];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nchunks; c += G) s += base[(int64_t)c * total];
+  }
+  red[cg][o] = s;
+  __syncthreads();
+  if (cg == 0 && want) {
+    float r = red[0][o];
+#pragma unroll
+    for (int k = 1; k < G; ++k) r += red[k][o];
+    if (t < 27) dw[((int64_t)co * cin + ci) * 27 + t] = r;
+    else db[co] = r;
+  }
+}
+
+static void f32_bf_plan(const h3d_tensor* x, int cout, int64_t* tiles, int* tpc, int* nchunks) {
+  *tiles = (int64_t)x->n * x->d * cdiv(x->h, BT_R) * cdiv(x->w, BT_W);
+  const int64_t blocks = cdiv(cout, 16) * cdiv(x->c, 16);
+  const int64_t per_chunk = (int64_t)cout * x->c * 28 * 4;
+  int64_t want = std::max<int64_t>(1, cdiv(1024, std::max<int64_t>(blocks, 1)));
+  want = std::min<int64_t>(want, std::max<int64_t>(1, ((int64_t)64 << 20) / std::max<int64_t>(per_chunk, 1)));
+  want = std::min<int64_t>(want, std::max<int64_t>(*tiles, 1));
+  *tpc = (int)std::max<int64_t>(1, cdiv(*tiles, want));
+  *nchunks = (int)std::max<int64_t>(1, cdiv(*tiles, *tpc));
+}
+
+bool f32_mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
+  return x->dtype == H3D_F32 && dz->dtype == H3D_F32 && x->c > 0 && dz->c > 0 && cdiv(x->c, 16) <= 65535 && cdiv(dz->c, 16) <= 65535;
+}
+
+size_t f32_mfma_bf_ws_bytes(const h3d_tensor* x, int cout) {
+  int64_t tiles;
+  int tpc, nchunks;
+  f32_bf_plan(x, cout, &tiles, &tpc, &nchunks);
+  return (size_t)nchunks * cout * x->c * 28 * sizeof(float);
+}
+
+h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* dz, const h3d_tensor* z, float* dw,
+                               float* db, float mask_slope, void* ws, size_t ws_bytes, hipStream_t stream) {
+  F32BfArgs a;
+  a.x = make_geo(x); a.dz = make_geo(dz); a.z = z ? make_geo(z) : a.dz;
+  a.cin = x->c; a.cout = dz->c; a.mask_slope = mask_slope;
+  a.nhg = (int)cdiv(x->h, BT_R); a.nwg = (int)cdiv(x->w, BT_W);
+  int nchunks;
+  f32_bf_plan(x, a.cout, &a.tiles, &a.tiles_per_chunk, &nchunks);
+  if (!ws || ws_bytes < f32_mfma_bf_ws_bytes(x, a.cout)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
+  const dim3 g((unsigned)nchunks, (unsigned)cdiv(a.cout, 16), (unsigned)cdiv(a.cin, 16));
+  if (z)
+    hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
+                       (const float*)z->data, (float*)ws, a);
+  else
+    hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<false>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
+                       (const float*)nullptr, (float*)ws, a);
+  const int64_t total = (int64_t)a.cout * a.cin * 28;
+  hipLaunchKernelGGL(bwd_filter_f32_reduce_kernel, dim3((unsigned)cdiv(total, 16)), dim3(256), 0, stream, (const float*)ws, dw, db,
+                     a.cin, a.cout, nchunks);
+  note_kernel(handle, "bwd_filter_f32_mfma_kernel");
+  return launch_status(handle, "conv3d_bwd_filter_f32_mfma");
+}
+
+}  // namespace h3d

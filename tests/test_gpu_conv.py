@@ -322,6 +322,68 @@ def test_main_halo_split_is_bit_exact(dtype, cin, cout, W, exact):
     close(from_dev(db), dbo, tol_w)
 
 
+# (N, Cin, Cout, D, H, W, halo, d_offset, d_global): fp32 tensors on the matrix cores.  Both instances of the forward kernel
+# (one and two blocks of 16 output channels per workgroup), channel counts that fill neither the groups of 4 input
+# channels nor the blocks of 16 output channels, two workgroups of output channels, W beyond one 32-column tile with a
+# ragged tail, W not a multiple of 4 (no 16-byte stores), H beyond one 8-row tile, more planes than one workgroup's four,
+# boundary and interior shards, and backward-filter chunks of several tiles
+F32_SHAPES = [
+    (1, 6, 16, 5, 11, 44, 0, 0, 5),
+    (2, 5, 20, 3, 9, 37, 1, 0, 3),
+    (1, 40, 48, 6, 20, 40, 1, 6, 18),
+    (2, 40, 48, 6, 20, 40, 1, 12, 18),
+    (1, 18, 70, 2, 8, 66, 0, 0, 2),
+    (1, 33, 7, 9, 4, 16, 1, 0, 12),
+]
+
+
+@pytest.mark.parametrize("shape", F32_SHAPES)
+def test_conv3d_fp32_matrix_core_kernels(shape):
+    """Sec. III-C FP / BD / BF in the paper's own precision (fp32 storage and arithmetic) against the fp64 oracle at the
+    1e-5 bar, with the kernel that ran checked by name."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, D, H, W, halo, off, Dg = shape
+    alpha = 0.01
+    w, bias = _weights(Ci, Co, "f32", 60)
+    wd, bd = to_dev(w, "f32"), to_dev(bias, "f32")
+    hl = (halo, halo)
+    xs = synth.flat("normal", SEED, 61, (N, Ci, D + 2 * halo, H, W))
+    dzs = synth.flat("normal", SEED, 62, (N, Co, D + 2 * halo, H, W))
+    for pl in range(D + 2 * halo):                    # canaries in halo planes outside the volume: never read
+        g = off - halo + pl
+        if g < 0 or g >= Dg:
+            xs[:, :, pl] = 999.0
+            dzs[:, :, pl] = 999.0
+    xo, xg = slab_pair(xs, "f32", hl, off, Dg)
+    zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=alpha)
+    zg = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, "f32"), h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel() == "conv3d_f32_mfma_kernel<%d>" % (1 if Co <= 16 else 2), h3d.h3d_last_kernel()
+    close(from_dev(zg.t), zo.a, 1e-5)
+    # backward passes: z and dz with the same halo (what the neighbours would have sent)
+    zfull = synth.flat("normal", SEED, 63, (N, Co, D + 2 * halo, H, W))
+    zso, zsg = slab_pair(zfull, "f32", hl, off, Dg)
+    dzo, dzg = slab_pair(dzs, "f32", hl, off, Dg)
+    dxo = orc.conv3d_bwd_data(dzo, zso, w, act=orc.ACT_LEAKY, alpha=alpha)
+    dxg = h3d.conv3d_bwd_data(dzg, zsg, wd, dev_like(dxo, "f32"), h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel() == "conv3d_f32_mfma_kernel<%d>" % (1 if Ci <= 16 else 2), h3d.h3d_last_kernel()
+    close(from_dev(dxg.t), dxo.a, 1e-5)
+    dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, zso, act=orc.ACT_LEAKY, alpha=alpha)
+    dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
+    db = torch.full((Co,), 777.0, device="cuda")
+    h3d.conv3d_bwd_filter(xg, dzg, zsg, dw, db, h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel() == "bwd_filter_f32_mfma_kernel", h3d.h3d_last_kernel()
+    close(from_dev(dw), dwo, 1e-5)
+    close(from_dev(db), dbo, 1e-5)
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    h3d.conv3d_bwd_filter(xg, dzg, zsg, dw2, db2, h3d.ACT_LEAKY, alpha)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+    # no activation, no saved output, no bias gradient wanted
+    dwo_n, _ = orc.conv3d_bwd_filter(xo, dzo, None, act=orc.ACT_NONE)
+    h3d.conv3d_bwd_filter(xg, dzg, None, dw2, None, h3d.ACT_NONE, 0.0)
+    close(from_dev(dw2), dwo_n, 1e-5)
+
+
 def test_plane_run_views_are_rejected_elsewhere():
     import paper_2007_12856_amd as h3d
     _, xg = slab_pair(synth.flat("normal", SEED, 54, (1, 2, 6, 4, 8)), "bf16")
