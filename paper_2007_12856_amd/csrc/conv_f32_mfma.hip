@@ -23,14 +23,12 @@ namespace h3d {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // -------------------------------------------------------------------------------------- forward / backward-data
-constexpr int FT_P = 4, FT_R = 8, FT_W = 32;                    // output tile: planes, rows, columns
-constexpr int FX_P = FT_P + 2, FX_R = FT_R + 2, FX_C = FT_W + 2; // staged input planes, rows, columns
-constexpr int FX_RP = 36;                                        // row pitch in LDS (floats)
-constexpr int FX_PS = FX_R * FX_RP;                              // plane pitch
-constexpr int FX_CS = FX_P * FX_PS;                              // channel pitch: 2160 = 48 mod 64, so the four channels
-                                                                 // of a fragment read land in four different bank groups
-constexpr int FX_SP = FX_P * FX_R * FX_C;                        // staged voxels per channel (2040)
-constexpr int FX_PT = (FX_SP + 255) / 256;                       // per thread and channel (8)
+constexpr int FT_P = 4, FT_W = 32;                 // output tile: planes and columns; rows = the template parameter TR (8,
+                                                   // or 2 when the volume has too few 8-row tiles to fill the chip)
+constexpr int FX_P = FT_P + 2, FX_C = FT_W + 2;    // staged input planes and columns
+constexpr int FX_RP = 36;                          // row pitch in LDS (floats)
+// channel pitch in LDS: 16 mod 64, so the four channels of a fragment read land in four different bank groups
+constexpr int fx_cs(int tr) { return (FX_P * (tr + 2) * FX_RP + 63) / 64 * 64 + 16; }
 
 // w: [cout][cin][27] fp32 -> wk: [co group][ci group][27][4][NC]  (NC = 16 CB output channels, zeros where padded)
 // fwd:      kernel-view (co_k, ci_k, t) = w[co_k][ci_k][t]
@@ -59,12 +57,17 @@ struct F32Args {
   int vec;                // 16-byte stores allowed
 };
 
-template <int CB, bool MASKED>
+template <int CB, int TR, bool MASKED>
 __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __restrict__ in, const float* __restrict__ mask,
                                                                  const float* __restrict__ wk, const float* __restrict__ bias,
                                                                  float* __restrict__ out, F32Args a) {
   constexpr int NC = 16 * CB;
   constexpr int WSZ = 27 * 4 * NC;                 // weights of one channel group (floats)
+  constexpr int FT_R = TR, FX_R = TR + 2;          // output rows, staged input rows
+  constexpr int FX_PS = FX_R * FX_RP;              // plane pitch
+  constexpr int FX_CS = fx_cs(TR);                 // channel pitch
+  constexpr int FX_SP = FX_P * FX_R * FX_C;        // staged voxels per channel (2040 for 8 rows)
+  constexpr int FX_PT = (FX_SP + 255) / 256;       // per thread and channel (8)
   __shared__ float lds_x[4 * FX_CS];
   __shared__ __attribute__((aligned(16))) float lds_w[WSZ];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -252,27 +255,36 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
   a.mask = mask ? make_geo(mask) : a.in;
   a.out = make_geo(out);
   a.cin = cin_k; a.cout = cout_k; a.ncig = (int)cdiv(cin_k, 4);
-  a.npg = (int)cdiv(a.out.ds, FT_P); a.nhg = (int)cdiv(out->h, FT_R); a.nwg = (int)cdiv(out->w, FT_W);
+  a.npg = (int)cdiv(a.out.ds, FT_P); a.nwg = (int)cdiv(out->w, FT_W);
+  const int ncog = (int)cdiv(cout_k, nc);
+  // 8-row tiles unless they would leave most of the chip idle: then 2-row tiles, four times as many workgroups
+  const int num_cu = static_cast<Handle*>(handle)->num_cu;
+  const int tr = ((int64_t)out->n * a.npg * cdiv(out->h, 8) * a.nwg * ncog < 2 * (int64_t)num_cu && out->h > 2) ? 2 : 8;
+  a.nhg = (int)cdiv(out->h, tr);
   a.out_slope = out_slope; a.mask_slope = mask_slope;
   a.vec = (out->w % 4 == 0) && (a.out.cstride % 4 == 0) && (a.out.nstride % 4 == 0) && ((uintptr_t)out->data % 16 == 0);
   const int64_t tiles = (int64_t)out->n * a.npg * a.nhg * a.nwg;
-  const int ncog = (int)cdiv(cout_k, nc);
   if (tiles == 0) return H3D_OK;
   if (tiles >= ((int64_t)1 << 31) || ncog > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many blocks");
   const int64_t nw = (int64_t)ncog * a.ncig * 108 * nc;
   hipLaunchKernelGGL(pack_w_f32_mfma_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
                      cin, cout, transpose ? 1 : 0, a.ncig, nc, nw);
   const dim3 g((unsigned)tiles, (unsigned)ncog);
-#define H3D_F32_LAUNCH(CBV, MK)                                                                                         \
-  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, MK>), g, dim3(256), 0, stream, (const float*)in->data,                \
+#define H3D_F32_LAUNCH(CBV, TRV, MK)                                                                                    \
+  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, TRV, MK>), g, dim3(256), 0, stream, (const float*)in->data,           \
                      (const float*)(mask ? mask->data : nullptr), (const float*)ws, bias, (float*)out->data, a)
+#define H3D_F32_LAUNCH_M(CBV, TRV)                                                                                      \
+  do {                                                                                                                  \
+    if (mask) H3D_F32_LAUNCH(CBV, TRV, true); else H3D_F32_LAUNCH(CBV, TRV, false);                                     \
+  } while (0)
   if (cb == 1) {
-    if (mask) H3D_F32_LAUNCH(1, true); else H3D_F32_LAUNCH(1, false);
+    if (tr == 8) H3D_F32_LAUNCH_M(1, 8); else H3D_F32_LAUNCH_M(1, 2);
   } else {
-    if (mask) H3D_F32_LAUNCH(2, true); else H3D_F32_LAUNCH(2, false);
+    if (tr == 8) H3D_F32_LAUNCH_M(2, 8); else H3D_F32_LAUNCH_M(2, 2);
   }
+#undef H3D_F32_LAUNCH_M
 #undef H3D_F32_LAUNCH
-  note_kernel(handle, "conv3d_f32_mfma_kernel<%d>", cb);
+  note_kernel(handle, "conv3d_f32_mfma_kernel<%d,%d>", cb, tr);
   return launch_status(handle, "conv3d_f32_mfma");
 }
 
