@@ -22,6 +22,23 @@ namespace h3d {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+namespace {
+// Loads go through raw buffer resources: an element outside the volume (or of a channel the tensor does not have) gets
+// the byte offset F32_OOB, which lies beyond the resource's range and reads as zero without a branch.  The channel is
+// added as a scalar offset (the range check looks at the vector offset alone).
+constexpr int F32_OOB = (int)0x80000000;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t f32_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p), hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                           (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+// soff = 4 * channel * channel stride: below 2^31 because a whole sample is (fits_buf on the host)
+__device__ __forceinline__ float f32_load(__amdgpu_buffer_rsrc_t rs, int voff, uint32_t soff) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, (int)__builtin_amdgcn_readfirstlane(soff), 0));
+}
+}  // namespace
+
 // -------------------------------------------------------------------------------------- forward / backward-data
 constexpr int FT_P = 4, FT_W = 32;                 // output tile: planes and columns; rows = the template parameter TR (8,
                                                    // or 2 when the volume has too few 8-row tiles to fill the chip)
@@ -80,7 +97,8 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
   const int cog = blockIdx.y;
   const int ps0 = pg * FT_P, h0 = hg * FT_R, w0 = wg * FT_W;
 
-  // what this thread stages of every channel: offsets in the tensor (-1: outside the volume, reads as zero) and in LDS
+  // what this thread stages of every channel: byte offsets in the channel (F32_OOB: outside the volume, reads as zero)
+  // and offsets in LDS
   int xoff[FX_PT], moff[FX_PT], loff[FX_PT];
 #pragma unroll
   for (int i = 0; i < FX_PT; ++i) {
@@ -91,12 +109,12 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
     const int64_t gq = a.in.doff + q;
     const int sp = q + a.in.hlo, hh = h0 - 1 + row, ww = w0 - 1 + col;
     const bool ok = s < FX_SP && gq >= 0 && gq < a.in.dglob && sp >= 0 && sp < a.in.ds && hh >= 0 && hh < H && ww >= 0 && ww < W;
-    xoff[i] = ok ? (int)(sp * a.in.plane + (int64_t)hh * W + ww) : -1;
+    xoff[i] = ok ? 4 * (int)(sp * a.in.plane + (int64_t)hh * W + ww) : F32_OOB;
     if (MASKED) {
       const int sm = q + a.mask.hlo;
       const bool mok = ok && sm >= 0 && sm < a.mask.ds;
-      moff[i] = mok ? (int)(sm * a.mask.plane + (int64_t)hh * W + ww) : -1;
-      if (!mok) xoff[i] = -1;
+      moff[i] = mok ? 4 * (int)(sm * a.mask.plane + (int64_t)hh * W + ww) : F32_OOB;
+      if (!mok) xoff[i] = F32_OOB;
     }
   }
 
@@ -118,8 +136,8 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 
   const float* xw = lds_x + (lane >> 4) * FX_CS + wave * FX_PS + (lane & 15);
   const float* ww_ = lds_w + (lane >> 4) * NC + (lane & 15);
-  const float* in_n = in + (int64_t)n * a.in.nstride;
-  const float* mk_n = MASKED ? mask + (int64_t)n * a.mask.nstride : nullptr;
+  const __amdgpu_buffer_rsrc_t rs_in = f32_rsrc(in + (int64_t)n * a.in.nstride, (uint32_t)(a.in.nstride * 4));
+  const __amdgpu_buffer_rsrc_t rs_mk = f32_rsrc(MASKED ? mask + (int64_t)n * a.mask.nstride : in, (uint32_t)(a.mask.nstride * 4));
 
   for (int cig = 0; cig < a.ncig; ++cig) {
     // ---- stage 4 input channels (tile + halo) and their weights
@@ -127,18 +145,14 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const int ci = cig * 4 + c;
-      const bool cok = ci < a.cin;
-      const float* xc = in_n + (int64_t)ci * a.in.cstride;
-      const float* mc = MASKED ? mk_n + (int64_t)ci * a.mask.cstride : nullptr;
+      const bool cok = ci < a.cin;                  // uniform
+      const uint32_t xs = 4u * ci * (uint32_t)a.in.cstride, ms = MASKED ? 4u * ci * (uint32_t)a.mask.cstride : 0u;
 #pragma unroll
       for (int i = 0; i < FX_PT; ++i) {
-        float x = 0.f;
-        if (cok && xoff[i] >= 0) {
-          x = xc[xoff[i]];
-          if (MASKED) {
-            const float m = mc[moff[i]];
-            if (!(m > 0.f)) x *= a.mask_slope;
-          }
+        float x = f32_load(rs_in, cok ? xoff[i] : F32_OOB, xs);
+        if (MASKED) {
+          const float m = f32_load(rs_mk, cok ? moff[i] : F32_OOB, ms);
+          x = m > 0.f ? x : x * a.mask_slope;
         }
         v[c][i] = x;
       }
@@ -229,12 +243,12 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 
 static int f32_cb(int cout_k) { return cout_k <= 16 ? 1 : 2; }
 
-static bool fits_i32(const h3d_tensor* t) {
-  return (int64_t)(t->halo_lo + t->d + t->halo_hi) * t->h * t->w < ((int64_t)1 << 31);
-}
+// a whole sample (all channels, with the tensor's real strides) within 2^31 bytes: what a buffer resource and the
+// 32-bit byte offsets of the kernels can address
+static bool fits_buf(const h3d_tensor* t) { return sample_span(t) < ((int64_t)1 << 29); }
 
 bool f32_mfma_fwd_supported(const h3d_tensor* in, const h3d_tensor* out) {
-  return in->dtype == H3D_F32 && out->dtype == H3D_F32 && in->c > 0 && out->c > 0 && fits_i32(in) && fits_i32(out);
+  return in->dtype == H3D_F32 && out->dtype == H3D_F32 && in->c > 0 && out->c > 0 && fits_buf(in) && fits_buf(out);
 }
 
 size_t f32_mfma_fwd_ws_bytes(int cin_k, int cout_k) {
@@ -249,7 +263,7 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
   const int cin = transpose ? cout_k : cin_k, cout = transpose ? cin_k : cout_k;
   const int cb = f32_cb(cout_k), nc = 16 * cb;
   if (!ws || ws_bytes < f32_mfma_fwd_ws_bytes(cin_k, cout_k)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
-  if (mask && !fits_i32(mask)) return fail(handle, H3D_EUNSUPPORTED, "conv3d: z too large for this kernel");
+  if (mask && !fits_buf(mask)) return fail(handle, H3D_EUNSUPPORTED, "conv3d: z too large for this kernel");
   F32Args a;
   a.in = make_geo(in);
   a.mask = mask ? make_geo(mask) : a.in;
@@ -335,7 +349,9 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
     const int p = (int)(r % D);
     const int n = (int)(r / D);
     const int h0 = hg * BT_R, w0 = wg * BT_W;
-    const float* xb = x + (int64_t)n * a.x.nstride + (int64_t)(cig * 16) * a.x.cstride;
+    const __amdgpu_buffer_rsrc_t rs_x = f32_rsrc(x + (int64_t)n * a.x.nstride, (uint32_t)(a.x.nstride * 4));
+    const __amdgpu_buffer_rsrc_t rs_g = f32_rsrc(dz + (int64_t)n * a.dz.nstride, (uint32_t)(a.dz.nstride * 4));
+    const __amdgpu_buffer_rsrc_t rs_z = f32_rsrc(MASKED ? z + (int64_t)n * a.z.nstride : dz, (uint32_t)(a.z.nstride * 4));
 #pragma unroll
     for (int i = 0; i < BX_PT; ++i) {
       const int s = tid + 256 * i;
@@ -344,19 +360,19 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
       const int64_t gq = a.x.doff + q;
       const int sp = q + a.x.hlo, hh = h0 - 1 + row, ww = w0 - 1 + col;
       const bool ok = s < BX_SP && gq >= 0 && gq < a.x.dglob && sp >= 0 && sp < a.x.ds && hh >= 0 && hh < H && ww >= 0 && ww < W;
-      const float* xp = xb + ((int64_t)sp * a.x.plane + (int64_t)hh * W + ww);
+      const int vo = ok ? 4 * (int)((int64_t)sp * a.x.plane + (int64_t)hh * W + ww) : F32_OOB;
 #pragma unroll
-      for (int c = 0; c < 16; ++c) xv[i][c] = (ok && c < nci) ? xp[(int64_t)c * a.x.cstride] : 0.f;
+      for (int c = 0; c < 16; ++c) xv[i][c] = f32_load(rs_x, c < nci ? vo : F32_OOB, 4u * (cig * 16 + c) * (uint32_t)a.x.cstride);
     }
     const int hh = h0 + gs / BT_W, ww = w0 + gs % BT_W;
     const bool gok = hh < H && ww < W;
-    const float* gp = dz + (int64_t)n * a.dz.nstride + (int64_t)(cog * 16 + gc0) * a.dz.cstride + (int64_t)(p + a.dz.hlo) * a.dz.plane + (int64_t)hh * W + ww;
-    const float* zp = MASKED ? z + (int64_t)n * a.z.nstride + (int64_t)(cog * 16 + gc0) * a.z.cstride + (int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)hh * W + ww : nullptr;
+    const int go = gok ? 4 * (int)((int64_t)(p + a.dz.hlo) * a.dz.plane + (int64_t)hh * W + ww) : F32_OOB;
+    const int zo = (MASKED && gok) ? 4 * (int)((int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)hh * W + ww) : F32_OOB;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const bool ok = gok && gc0 + j < nco;
-      gv[j] = ok ? gp[(int64_t)j * a.dz.cstride] : 0.f;
-      if (MASKED) zv[j] = ok ? zp[(int64_t)j * a.z.cstride] : 1.f;
+      const bool ok = gc0 + j < nco;                      // (gc0 differs between the two halves of the workgroup)
+      gv[j] = f32_load(rs_g, ok ? go : F32_OOB, 4u * (cog * 16 + gc0 + j) * (uint32_t)a.dz.cstride);
+      if (MASKED) zv[j] = f32_load(rs_z, ok ? zo : F32_OOB, 4u * (cog * 16 + gc0 + j) * (uint32_t)a.z.cstride);   // 0 where g is 0
     }
   };
 
@@ -479,7 +495,7 @@ static void f32_bf_plan(const h3d_tensor* x, int cout, int64_t* tiles, int* tpc,
 }
 
 bool f32_mfma_bf_supported(const h3d_tensor* x, const h3d_tensor* dz) {
-  return x->dtype == H3D_F32 && dz->dtype == H3D_F32 && x->c > 0 && dz->c > 0 && cdiv(x->c, 16) <= 65535 && cdiv(dz->c, 16) <= 65535;
+  return x->dtype == H3D_F32 && dz->dtype == H3D_F32 && x->c > 0 && dz->c > 0 && cdiv(x->c, 16) <= 65535 && cdiv(dz->c, 16) <= 65535 && fits_buf(x) && fits_buf(dz);
 }
 
 size_t f32_mfma_bf_ws_bytes(const h3d_tensor* x, int cout) {
@@ -498,6 +514,7 @@ h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tens
   int nchunks;
   f32_bf_plan(x, a.cout, &a.tiles, &a.tiles_per_chunk, &nchunks);
   if (!ws || ws_bytes < f32_mfma_bf_ws_bytes(x, a.cout)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
+  if (z && !fits_buf(z)) return fail(handle, H3D_EUNSUPPORTED, "conv3d_bwd_filter: z too large for this kernel");
   const dim3 g((unsigned)nchunks, (unsigned)cdiv(a.cout, 16), (unsigned)cdiv(a.cin, 16));
   if (z)
     hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
