@@ -401,16 +401,19 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
 #pragma unroll 2
     for (int ks = 0; ks < BT_W / 4; ++ks) {
       const float g = gr[4 * ks];
+      float xf[27];
 #pragma unroll
-      for (int kd = 0; kd < 3; ++kd)
+      for (int t = 0; t < 27; ++t) xf[t] = xr[(t / 9) * (BX_R * BX_C) + ((t / 3) % 3) * BX_C + 4 * ks + t % 3];
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-          for (int kw = 0; kw < 3; ++kw) {
-            const float xf = xr[kd * (BX_R * BX_C) + kh * BX_C + 4 * ks + kw];
-            acc[(kd * 3 + kh) * 3 + kw] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf, g, acc[(kd * 3 + kh) * 3 + kw], 0, 0, 0);
-          }
+      for (int t = 0; t < 27; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
       acc[27] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[27], 0, 0, 0);
+      // LDS reads several products ahead of their use: six reads first, then one read per two products
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+      for (int t = 0; t < 14; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
     }
   }
 
