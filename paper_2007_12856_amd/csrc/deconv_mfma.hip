@@ -61,8 +61,14 @@ __global__ void __launch_bounds__(64 * DB_NW, 4) deconv_bf_mfma_kernel(const bf1
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lg = lane >> 4, lc = lane & 15;
-  const int chunk = blockIdx.x;
-  const int co0 = (blockIdx.y % a.gco) * 16, ci0 = (blockIdx.y / a.gco) * CI_WG;
+  // Workgroups go to the 8 XCDs round-robin by their linear index.  The gco * gci workgroups of one chunk read the same
+  // x tiles (and, for gci > 1, the same dy rows): consecutive workgroups OF ONE XCD take the channel groups of one chunk,
+  // so that they run side by side and all but the first find the tile in that XCD's L2.
+  const int groups = a.gco * a.gci;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int grp = slot % groups, chunk = (slot / groups) * 8 + xcd;
+  if (chunk >= a.nchunks) return;                         // the grid is padded to a multiple of 8 chunks
+  const int co0 = (grp % a.gco) * 16, ci0 = (grp / a.gco) * CI_WG;
   const int ab = wave & 3, cob = wave >> 2;                // this wavefront: (a,b) and which 8 of the 16 output channels
   const int ta = ab >> 1, tb = ab & 1;
   const int co = co0 + cob * 8 + (lc >> 1), par = lc & 1;  // this lane's column: output channel and parity c
@@ -176,21 +182,43 @@ __global__ void __launch_bounds__(64 * DB_NW, 4) deconv_bf_mfma_kernel(const bf1
   }
 }
 
-// dw[i] = sum over chunks of part[chunk][i] (chunk order); db[co] = sum over chunks, then over the 8 taps
+// dw[i] = sum over chunks of part[chunk][i]; db[co] = sum over chunks and the 8 taps of the bias partials behind them.
+// Fixed order: a block takes 16 consecutive outputs; each of its 16 thread groups adds every 16th chunk in increasing
+// order (eight loads in flight), then the 16 group sums are added in group order.
 __global__ void __launch_bounds__(256) deconv_bf_mfma_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
                                                                     float* __restrict__ db, int64_t nw, int cout, int nchunks) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  constexpr int G = 16;
+  __shared__ float red[G][17];
+  const int o = threadIdx.x & 15, cg = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + o;
+  float s = 0.f;
   if (i < nw) {
-    float s = 0.f;
-    for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * nw + i];
-    dw[i] = s;
+    const float* base = part + i;
+    int c = cg;
+    for (; c + 7 * G < nchunks; c += 8 * G) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)(c + u * G) * nw];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nchunks; c += G) s += base[(int64_t)c * nw];
   } else if (db && i < nw + cout) {
-    const int co = (int)(i - nw);
-    const float* pb = part + (int64_t)nchunks * nw;
-    float s = 0.f;
-    for (int c = 0; c < nchunks; ++c)
-      for (int k = 0; k < 8; ++k) s += pb[((int64_t)c * cout + co) * 8 + k];
-    db[co] = s;
+    const float* pb = part + (int64_t)nchunks * nw + (i - nw) * 8;
+    for (int c = cg; c < nchunks; c += G) {
+      const float4 u0 = *reinterpret_cast<const float4*>(pb + (int64_t)c * cout * 8);
+      const float4 u1 = *reinterpret_cast<const float4*>(pb + (int64_t)c * cout * 8 + 4);
+      s += u0.x; s += u0.y; s += u0.z; s += u0.w; s += u1.x; s += u1.y; s += u1.z; s += u1.w;
+    }
+  }
+  red[cg][o] = s;
+  __syncthreads();
+  if (cg == 0) {
+    float r = red[0][o];
+#pragma unroll
+    for (int k = 1; k < G; ++k) r += red[k][o];
+    if (i < nw) dw[i] = r;
+    else if (db && i < nw + cout) db[i - nw] = r;
   }
 }
 
@@ -226,8 +254,9 @@ h3d_status dbf_launch(void* handle, const bf16_t* x, const bf16_t* dy, float* pa
       return fail(handle, H3D_EHIP, "deconv2_bwd_filter: cannot set the dynamic LDS size to %zu bytes", lds_bytes);
     attr_set = true;
   }
-  hipLaunchKernelGGL((deconv_bf_mfma_kernel<MRB>), dim3((unsigned)a.nchunks, (unsigned)(a.gco * a.gci)), dim3(64 * DB_NW), lds_bytes,
-                     stream, x, dy, part, a);
+  const int64_t grid = cdiv(a.nchunks, 8) * 8 * (int64_t)(a.gco * a.gci);
+  if (grid >= ((int64_t)1 << 31)) return fail(handle, H3D_EINVAL, "deconv2_bwd_filter: too many workgroups");
+  hipLaunchKernelGGL((deconv_bf_mfma_kernel<MRB>), dim3((unsigned)grid), dim3(64 * DB_NW), lds_bytes, stream, x, dy, part, a);
   return H3D_OK;
 }
 
@@ -276,7 +305,7 @@ h3d_status deconv_bf_mfma(void* handle, const h3d_tensor* x, const h3d_tensor* d
   else if (p.mrb == 4) st = dbf_launch<4>(handle, xp, yp, (float*)ws, a, stream);
   else st = dbf_launch<2>(handle, xp, yp, (float*)ws, a, stream);
   if (st != H3D_OK) return st;
-  hipLaunchKernelGGL(deconv_bf_mfma_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 256)), dim3(256), 0, stream, (const float*)ws, dw,
+  hipLaunchKernelGGL(deconv_bf_mfma_reduce_kernel, dim3((unsigned)cdiv(nw + a.cout, 16)), dim3(256), 0, stream, (const float*)ws, dw,
                      db, nw, a.cout, a.nchunks);
   return launch_status(handle, "deconv2_bwd_filter_mfma");
 }
