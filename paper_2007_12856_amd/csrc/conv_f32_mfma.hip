@@ -37,6 +37,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t f32_rsrc(const void* base, uin
 __device__ __forceinline__ float f32_load(__amdgpu_buffer_rsrc_t rs, int voff, uint32_t soff) {
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, (int)__builtin_amdgcn_readfirstlane(soff), 0));
 }
+// lane i of every row of 16 lanes receives the value of lane i + N of that row (zero beyond the row's end)
+template <int N>
+__device__ __forceinline__ float row_shl(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + N, 0xf, 0xf, true));
+}
 }  // namespace
 
 // -------------------------------------------------------------------------------------- forward / backward-data
@@ -66,6 +71,24 @@ __global__ void pack_w_f32_mfma_kernel(const float* __restrict__ w, float* __res
   wk[i] = v;
 }
 
+// Thin output side (at most 4 output channels: the BD of a first layer): the 16 columns of a product hold (kh, co) =
+// column 4 kh + co, so one product covers the three kh taps.  wk: [ci group][kd * 3 + kw][4][16], zeros where padded.
+__global__ void pack_w_f32_thin_kernel(const float* __restrict__ w, float* __restrict__ wk, int cin, int cout, int transpose,
+                                       int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int cin_k = transpose ? cout : cin, cout_k = transpose ? cin : cout;
+  const int j = (int)(i % 16);
+  const int c = (int)((i / 16) % 4);
+  const int dk = (int)((i / 64) % 9);
+  const int cig = (int)(i / 576);
+  const int kh = j / 4, ok = j % 4, ik = cig * 4 + c;
+  const int t = (dk / 3) * 9 + kh * 3 + dk % 3;
+  float v = 0.f;
+  if (kh < 3 && ok < cout_k && ik < cin_k) v = transpose ? w[((int64_t)ik * cin + ok) * 27 + (26 - t)] : w[((int64_t)ok * cin + ik) * 27 + t];
+  wk[i] = v;
+}
+
 struct F32Args {
   Geo in, mask, out;
   int cin, cout, ncig;
@@ -74,12 +97,13 @@ struct F32Args {
   int vec;                // 16-byte stores allowed
 };
 
-template <int CB, int TR, bool MASKED>
+template <int CB, int TR, bool MASKED, bool THIN = false>
 __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __restrict__ in, const float* __restrict__ mask,
                                                                  const float* __restrict__ wk, const float* __restrict__ bias,
                                                                  float* __restrict__ out, F32Args a) {
+  static_assert(!THIN || CB == 1, "the thin form has one block of columns");
   constexpr int NC = 16 * CB;
-  constexpr int WSZ = 27 * 4 * NC;                 // weights of one channel group (floats)
+  constexpr int WSZ = (THIN ? 9 : 27) * 4 * NC;    // weights of one channel group (floats)
   constexpr int FT_R = TR, FX_R = TR + 2;          // output rows, staged input rows
   constexpr int FX_PS = FX_R * FX_RP;              // plane pitch
   constexpr int FX_CS = fx_cs(TR);                 // channel pitch
@@ -123,13 +147,16 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
   const int64_t gp = a.out.doff + ps - a.out.hlo;
   const bool inside = gp >= 0 && gp < a.out.dglob;
 
-  f32x4 acc[CB][FT_R][2];
+  // accumulators: one per output row, starting from the bias — or, in the thin form, one per INPUT row (its three kh
+  // contributions sit in columns 4 kh + co and meet the output rows they belong to in the epilogue)
+  constexpr int NAR = THIN ? FX_R : FT_R;
+  f32x4 acc[CB][NAR][2];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const int co = cog * NC + cb * 16 + (lane & 15);
-    const float b = (bias && co < a.cout) ? bias[co] : 0.f;
+    const float b = (!THIN && bias && co < a.cout) ? bias[co] : 0.f;
 #pragma unroll
-    for (int r = 0; r < FT_R; ++r)
+    for (int r = 0; r < NAR; ++r)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) acc[cb][r][hf] = f32x4{b, b, b, b};
   }
@@ -157,7 +184,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
         v[c][i] = x;
       }
     }
-    const f32x4* wsrc = reinterpret_cast<const f32x4*>(wk + ((int64_t)cog * a.ncig + cig) * WSZ);
+    const f32x4* wsrc = reinterpret_cast<const f32x4*>(wk + ((int64_t)cog * a.ncig + cig) * WSZ);   // (thin: one column group)
     f32x4 wv[(WSZ / 4 + 255) / 256];
 #pragma unroll
     for (int i = 0; i < (WSZ / 4 + 255) / 256; ++i) {
@@ -188,16 +215,25 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
           for (int r = 0; r < FX_R; ++r)
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) bx[r][hf] = xw[kd * FX_PS + r * FX_RP + hf * 16 + kw];
+          if (THIN) {
+            const float aw = ww_[(kd * 3 + kw) * 4 * NC];
 #pragma unroll
-          for (int kh = 0; kh < 3; ++kh) {
+            for (int r = 0; r < FX_R; ++r)
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-              const float aw = ww_[((kd * 3 + kh) * 3 + kw) * 4 * NC + cb * 16];
+              for (int hf = 0; hf < 2; ++hf)
+                acc[0][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r][hf], aw, acc[0][r][hf], 0, 0, 0);
+          } else {
 #pragma unroll
-              for (int r = 0; r < FT_R; ++r)
+            for (int kh = 0; kh < 3; ++kh) {
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-                  acc[cb][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r + kh][hf], aw, acc[cb][r][hf], 0, 0, 0);
+              for (int cb = 0; cb < CB; ++cb) {
+                const float aw = ww_[((kd * 3 + kh) * 3 + kw) * 4 * NC + cb * 16];
+#pragma unroll
+                for (int r = 0; r < FT_R; ++r)
+#pragma unroll
+                  for (int hf = 0; hf < 2; ++hf)
+                    acc[cb][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r + kh][hf], aw, acc[cb][r][hf], 0, 0, 0);
+              }
             }
           }
         }
@@ -211,7 +247,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const int co = cog * NC + cb * 16 + (lane & 15);
-    if (co >= a.cout) continue;
+    const bool co_ok = co < a.cout;       // (tested at the store: the lane exchange of the thin form needs whole rows of lanes)
     float* oc = on + (int64_t)co * a.out.cstride;
 #pragma unroll
     for (int r = 0; r < FT_R; ++r) {
@@ -221,7 +257,16 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
       for (int hf = 0; hf < 2; ++hf) {
         const int wc = w0 + hf * 16 + 4 * (lane >> 4);
         if (wc >= W) continue;
-        f32x4 o = acc[cb][r][hf];
+        f32x4 o;
+        if (THIN) {
+          // output row r = input rows r, r + 1, r + 2 under kh = 0, 1, 2: columns co, 4 + co, 8 + co
+          const float b = (bias && co < a.cout) ? bias[co] : 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            o[j] = ((acc[0][r][hf][j] + row_shl<4>(acc[0][r + 1][hf][j])) + row_shl<8>(acc[0][r + 2][hf][j])) + b;
+        } else {
+          o = acc[cb][r][hf];
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float x = o[j];
@@ -229,6 +274,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
           o[j] = inside ? x : 0.f;
         }
         float* p = oc + (int64_t)h * W + wc;
+        if (!co_ok) continue;
         if (a.vec && wc + 3 < W) {
           *reinterpret_cast<f32x4*>(p) = o;
         } else {
@@ -261,6 +307,7 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
                            hipStream_t stream) {
   const int cin_k = in->c, cout_k = out->c;
   const int cin = transpose ? cout_k : cin_k, cout = transpose ? cin_k : cout_k;
+  const bool thin = cout_k <= 4;
   const int cb = f32_cb(cout_k), nc = 16 * cb;
   if (!ws || ws_bytes < f32_mfma_fwd_ws_bytes(cin_k, cout_k)) return fail(handle, H3D_EWORKSPACE, "conv3d: workspace too small");
   if (mask && !fits_buf(mask)) return fail(handle, H3D_EUNSUPPORTED, "conv3d: z too large for this kernel");
@@ -280,25 +327,36 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
   const int64_t tiles = (int64_t)out->n * a.npg * a.nhg * a.nwg;
   if (tiles == 0) return H3D_OK;
   if (tiles >= ((int64_t)1 << 31) || ncog > 65535) return fail(handle, H3D_EINVAL, "conv3d: too many blocks");
-  const int64_t nw = (int64_t)ncog * a.ncig * 108 * nc;
-  hipLaunchKernelGGL(pack_w_f32_mfma_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
-                     cin, cout, transpose ? 1 : 0, a.ncig, nc, nw);
+  const int64_t nw = thin ? (int64_t)a.ncig * 576 : (int64_t)ncog * a.ncig * 108 * nc;
+  if (thin)
+    hipLaunchKernelGGL(pack_w_f32_thin_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
+                       cin, cout, transpose ? 1 : 0, nw);
+  else
+    hipLaunchKernelGGL(pack_w_f32_mfma_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
+                       cin, cout, transpose ? 1 : 0, a.ncig, nc, nw);
   const dim3 g((unsigned)tiles, (unsigned)ncog);
-#define H3D_F32_LAUNCH(CBV, TRV, MK)                                                                                    \
-  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, TRV, MK>), g, dim3(256), 0, stream, (const float*)in->data,           \
+#define H3D_F32_LAUNCH(CBV, TRV, MK, ...)                                                                               \
+  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, TRV, MK, ##__VA_ARGS__>), g, dim3(256), 0, stream, (const float*)in->data, \
                      (const float*)(mask ? mask->data : nullptr), (const float*)ws, bias, (float*)out->data, a)
 #define H3D_F32_LAUNCH_M(CBV, TRV)                                                                                      \
   do {                                                                                                                  \
     if (mask) H3D_F32_LAUNCH(CBV, TRV, true); else H3D_F32_LAUNCH(CBV, TRV, false);                                     \
   } while (0)
-  if (cb == 1) {
+  if (thin) {
+    if (tr == 8) {
+      if (mask) H3D_F32_LAUNCH(1, 8, true, true); else H3D_F32_LAUNCH(1, 8, false, true);
+    } else {
+      if (mask) H3D_F32_LAUNCH(1, 2, true, true); else H3D_F32_LAUNCH(1, 2, false, true);
+    }
+  } else if (cb == 1) {
     if (tr == 8) H3D_F32_LAUNCH_M(1, 8); else H3D_F32_LAUNCH_M(1, 2);
   } else {
     if (tr == 8) H3D_F32_LAUNCH_M(2, 8); else H3D_F32_LAUNCH_M(2, 2);
   }
 #undef H3D_F32_LAUNCH_M
 #undef H3D_F32_LAUNCH
-  note_kernel(handle, "conv3d_f32_mfma_kernel<%d,%d>", cb, tr);
+  if (thin) note_kernel(handle, "conv3d_f32_mfma_kernel<thin,%d>", tr);
+  else note_kernel(handle, "conv3d_f32_mfma_kernel<%d,%d>", cb, tr);
   return launch_status(handle, "conv3d_f32_mfma");
 }
 
@@ -448,6 +506,127 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
   }
 }
 
+// Thin input side (at most 4 input channels: the BF of a first layer).  The 16 rows of a product hold (kw, ci) = row
+// 4 kw + ci (kw = 3 is padding), so one product covers the three kw taps of a (kd, kh): 9 products + the bias gradient
+// per K-step instead of 28, and only 4 channels of x are staged.  Little per workgroup (≤ 128 registers, 19 KB of LDS):
+// four workgroups per CU.  Same partial-sum layout and reduction as the general form.
+template <bool MASKED>
+__global__ void __launch_bounds__(256, 4) bwd_filter_f32_thin_kernel(const float* __restrict__ x, const float* __restrict__ dz,
+                                                                     const float* __restrict__ z, float* __restrict__ part,
+                                                                     F32BfArgs a) {
+  __shared__ float lds_x[4 * BX_CS];                      // (the padding rows read at most 3 floats past a tap: inside the array)
+  __shared__ float lds_g[16 * BG_CS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, cog = blockIdx.y;
+  const int W = a.x.w, H = a.x.h, D = a.x.d;
+  f32x4 acc[10];
+#pragma unroll
+  for (int t = 0; t < 10; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // A operand: lane l supplies row l % 16 = (kw, ci) at voxel l / 16 of the K-step
+  const float* xr = lds_x + (lane & 3) * BX_CS + wave * BX_C + (lane >> 4) + ((lane & 15) >> 2);
+  const float* gr = lds_g + (lane & 15) * BG_CS + wave * BT_W + (lane >> 4);
+
+  constexpr int BX_PT = (BX_SP + 255) / 256;              // 3
+  float xv[BX_PT][4], gv[8], zv[8];
+  const int gs = tid & 127, gc0 = (tid >> 7) * 8;
+  const int nco = min(16, a.cout - cog * 16);
+  auto load_tile = [&](int64_t tile) {
+    int64_t r = tile;
+    const int wg = (int)(r % a.nwg); r /= a.nwg;
+    const int hg = (int)(r % a.nhg); r /= a.nhg;
+    const int p = (int)(r % D);
+    const int n = (int)(r / D);
+    const int h0 = hg * BT_R, w0 = wg * BT_W;
+    const __amdgpu_buffer_rsrc_t rs_x = f32_rsrc(x + (int64_t)n * a.x.nstride, (uint32_t)(a.x.nstride * 4));
+    const __amdgpu_buffer_rsrc_t rs_g = f32_rsrc(dz + (int64_t)n * a.dz.nstride, (uint32_t)(a.dz.nstride * 4));
+    const __amdgpu_buffer_rsrc_t rs_z = f32_rsrc(MASKED ? z + (int64_t)n * a.z.nstride : dz, (uint32_t)(a.z.nstride * 4));
+#pragma unroll
+    for (int i = 0; i < BX_PT; ++i) {
+      const int s = tid + 256 * i;
+      const int col = s % BX_C, row = (s / BX_C) % BX_R, pl = s / (BX_C * BX_R);
+      const int q = p + pl - 1;
+      const int64_t gq = a.x.doff + q;
+      const int sp = q + a.x.hlo, hh = h0 - 1 + row, ww = w0 - 1 + col;
+      const bool ok = s < BX_SP && gq >= 0 && gq < a.x.dglob && sp >= 0 && sp < a.x.ds && hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const int vo = ok ? 4 * (int)((int64_t)sp * a.x.plane + (int64_t)hh * W + ww) : F32_OOB;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) xv[i][c] = f32_load(rs_x, c < a.cin ? vo : F32_OOB, 4u * c * (uint32_t)a.x.cstride);
+    }
+    const int hh = h0 + gs / BT_W, ww = w0 + gs % BT_W;
+    const bool gok = hh < H && ww < W;
+    const int go = gok ? 4 * (int)((int64_t)(p + a.dz.hlo) * a.dz.plane + (int64_t)hh * W + ww) : F32_OOB;
+    const int zo = (MASKED && gok) ? 4 * (int)((int64_t)(p + a.z.hlo) * a.z.plane + (int64_t)hh * W + ww) : F32_OOB;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = gc0 + j < nco;
+      gv[j] = f32_load(rs_g, ok ? go : F32_OOB, 4u * (cog * 16 + gc0 + j) * (uint32_t)a.dz.cstride);
+      if (MASKED) zv[j] = f32_load(rs_z, ok ? zo : F32_OOB, 4u * (cog * 16 + gc0 + j) * (uint32_t)a.z.cstride);
+    }
+  };
+
+  const int64_t t0 = (int64_t)chunk * a.tiles_per_chunk;
+  const int64_t t1 = min(t0 + a.tiles_per_chunk, a.tiles);
+  if (t0 < t1) load_tile(t0);
+  for (int64_t tile = t0; tile < t1; ++tile) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < BX_PT; ++i) {
+      const int s = tid + 256 * i;
+      if (s < BX_SP) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) lds_x[c * BX_CS + s] = xv[i][c];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float v = gv[j];
+      if (MASKED && !(zv[j] > 0.f)) v *= a.mask_slope;
+      lds_g[(gc0 + j) * BG_CS + gs] = v;
+    }
+    __syncthreads();
+    if (tile + 1 < t1) load_tile(tile + 1);
+#pragma unroll 2
+    for (int ks = 0; ks < BT_W / 4; ++ks) {
+      const float g = gr[4 * ks];
+      float xf[9];
+#pragma unroll
+      for (int t = 0; t < 9; ++t) xf[t] = xr[(t / 3) * (BX_R * BX_C) + (t % 3) * BX_C + 4 * ks];
+#pragma unroll
+      for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
+      acc[9] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[9], 0, 0, 0);
+    }
+  }
+
+  // ---- the four wavefronts' sums in wavefront order (10 x 1 KB through the x tile's space)
+  float* red = lds_x;
+  for (int wv = 0; wv < 4; ++wv) {
+    __syncthreads();
+    if (wave == wv) {
+#pragma unroll
+      for (int t = 0; t < 10; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int idx = (t * 4 + j) * 64 + lane;
+          if (wv == 0) red[idx] = acc[t][j];
+          else if (wv < 3) red[idx] += acc[t][j];
+          else acc[t][j] += red[idx];
+        }
+    }
+  }
+  if (wave != 3) return;
+  // lane holds kw = lane / 16 (3: padding), ci = j, co = lane % 16 of every (kd, kh)
+  const int co = cog * 16 + (lane & 15), kw = lane >> 4;
+  if (co >= a.cout || kw >= 3) return;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j >= a.cin) continue;
+    float* pp = part + (((int64_t)chunk * a.cout + co) * a.cin + j) * 28;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) pp[t * 3 + kw] = acc[t][j];
+    if (j == 0 && kw == 0) pp[27] = acc[9][0];
+  }
+}
+
 // dw / db = the chunks' partial sums added in a fixed order: a block takes 16 consecutive elements of a chunk row; each
 // of its 16 thread groups adds every 16th chunk in increasing order (eight loads in flight), then the 16 group sums are
 // added in group order.
@@ -519,7 +698,14 @@ h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tens
   if (!ws || ws_bytes < f32_mfma_bf_ws_bytes(x, a.cout)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
   if (z && !fits_buf(z)) return fail(handle, H3D_EUNSUPPORTED, "conv3d_bwd_filter: z too large for this kernel");
   const dim3 g((unsigned)nchunks, (unsigned)cdiv(a.cout, 16), (unsigned)cdiv(a.cin, 16));
-  if (z)
+  const bool thin = a.cin <= 4;
+  if (thin && z)
+    hipLaunchKernelGGL((bwd_filter_f32_thin_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
+                       (const float*)z->data, (float*)ws, a);
+  else if (thin)
+    hipLaunchKernelGGL((bwd_filter_f32_thin_kernel<false>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
+                       (const float*)nullptr, (float*)ws, a);
+  else if (z)
     hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
                        (const float*)z->data, (float*)ws, a);
   else
@@ -528,7 +714,7 @@ h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tens
   const int64_t total = (int64_t)a.cout * a.cin * 28;
   hipLaunchKernelGGL(bwd_filter_f32_reduce_kernel, dim3((unsigned)cdiv(total, 16)), dim3(256), 0, stream, (const float*)ws, dw, db,
                      a.cin, a.cout, nchunks);
-  note_kernel(handle, "bwd_filter_f32_mfma_kernel");
+  note_kernel(handle, thin ? "bwd_filter_f32_mfma_kernel<thin>" : "bwd_filter_f32_mfma_kernel");
   return launch_status(handle, "conv3d_bwd_filter_f32_mfma");
 }
 

@@ -336,6 +336,12 @@ F32_SHAPES = [
     (1, 33, 7, 9, 4, 16, 1, 0, 12),
     (2, 8, 40, 16, 100, 132, 0, 0, 16),     # enough 8-row tiles to fill the chip: the 8-row instances
     (2, 36, 12, 16, 100, 132, 0, 0, 16),
+    # at most 4 channels on the output side of the correlation (thin form: the three kh taps share a product) or on the
+    # input side of backward-filter (the three kw taps share a product)
+    (1, 4, 16, 6, 20, 40, 1, 0, 6),
+    (2, 20, 3, 5, 9, 37, 0, 0, 5),
+    (2, 1, 2, 3, 10, 72, 1, 3, 9),
+    (2, 16, 4, 16, 100, 132, 0, 0, 16),
 ]
 
 
@@ -363,7 +369,8 @@ def test_conv3d_fp32_matrix_core_kernels(shape):
     xo, xg = slab_pair(xs, "f32", hl, off, Dg)
     zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=alpha)
     zg = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, "f32"), h3d.ACT_LEAKY, alpha)
-    assert h3d.h3d_last_kernel().startswith("conv3d_f32_mfma_kernel<%d," % (1 if Co <= 16 else 2)), h3d.h3d_last_kernel()
+    form = lambda c: "thin" if c <= 4 else ("1" if c <= 16 else "2")
+    assert h3d.h3d_last_kernel().startswith("conv3d_f32_mfma_kernel<%s," % form(Co)), h3d.h3d_last_kernel()
     kernels_seen.add(h3d.h3d_last_kernel())
     close(from_dev(zg.t), zo.a, 1e-5)
     # backward passes: z and dz with the same halo (what the neighbours would have sent)
@@ -372,14 +379,14 @@ def test_conv3d_fp32_matrix_core_kernels(shape):
     dzo, dzg = slab_pair(dzs, "f32", hl, off, Dg)
     dxo = orc.conv3d_bwd_data(dzo, zso, w, act=orc.ACT_LEAKY, alpha=alpha)
     dxg = h3d.conv3d_bwd_data(dzg, zsg, wd, dev_like(dxo, "f32"), h3d.ACT_LEAKY, alpha)
-    assert h3d.h3d_last_kernel().startswith("conv3d_f32_mfma_kernel<%d," % (1 if Ci <= 16 else 2)), h3d.h3d_last_kernel()
+    assert h3d.h3d_last_kernel().startswith("conv3d_f32_mfma_kernel<%s," % form(Ci)), h3d.h3d_last_kernel()
     kernels_seen.add(h3d.h3d_last_kernel())
     close(from_dev(dxg.t), dxo.a, 1e-5)
     dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, zso, act=orc.ACT_LEAKY, alpha=alpha)
     dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
     db = torch.full((Co,), 777.0, device="cuda")
     h3d.conv3d_bwd_filter(xg, dzg, zsg, dw, db, h3d.ACT_LEAKY, alpha)
-    assert h3d.h3d_last_kernel() == "bwd_filter_f32_mfma_kernel", h3d.h3d_last_kernel()
+    assert h3d.h3d_last_kernel() == ("bwd_filter_f32_mfma_kernel<thin>" if Ci <= 4 else "bwd_filter_f32_mfma_kernel"), h3d.h3d_last_kernel()
     close(from_dev(dw), dwo, 1e-5)
     close(from_dev(db), dbo, 1e-5)
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
@@ -392,11 +399,11 @@ def test_conv3d_fp32_matrix_core_kernels(shape):
 
 
 def test_conv3d_fp32_every_instance_was_run():
-    """The shapes above reach all four instances of the fp32 forward / backward-data kernel (collected from the library's
+    """The shapes above reach all six instances of the fp32 forward / backward-data kernel (collected from the library's
     own report of the kernel it ran); skipped when that test was not run in this process."""
     if not kernels_seen:
         pytest.skip("test_conv3d_fp32_matrix_core_kernels did not run in this process")
-    assert kernels_seen == {"conv3d_f32_mfma_kernel<%d,%d>" % (cb, tr) for cb in (1, 2) for tr in (2, 8)}, kernels_seen
+    assert kernels_seen == {"conv3d_f32_mfma_kernel<%s,%d>" % (cb, tr) for cb in ("1", "2", "thin") for tr in (2, 8)}, kernels_seen
 
 
 def test_plane_run_views_are_rejected_elsewhere():
