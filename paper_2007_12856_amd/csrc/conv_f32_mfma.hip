@@ -45,9 +45,10 @@ __device__ __forceinline__ float row_shl(float v) {
 }  // namespace
 
 // -------------------------------------------------------------------------------------- forward / backward-data
-constexpr int FT_P = 4, FT_W = 32;                 // output tile: planes and columns; rows = the template parameter TR (8,
-                                                   // or 2 when the volume has too few 8-row tiles to fill the chip)
-constexpr int FX_P = FT_P + 2, FX_C = FT_W + 2;    // staged input planes and columns
+constexpr int FT_P = 4;                            // output tile: planes; rows = the template parameter TR (8, or 2 when the
+                                                   // volume has too few 8-row tiles to fill the chip); columns = 16 HV (two
+                                                   // 16-voxel halves, or one for volumes at most 16 voxels wide)
+constexpr int FX_P = FT_P + 2;                     // staged input planes
 constexpr int FX_RP = 36;                          // row pitch in LDS (floats)
 // channel pitch in LDS: 16 mod 64, so the four channels of a fragment read land in four different bank groups
 constexpr int fx_cs(int tr) { return (FX_P * (tr + 2) * FX_RP + 63) / 64 * 64 + 16; }
@@ -97,7 +98,7 @@ struct F32Args {
   int vec;                // 16-byte stores allowed
 };
 
-template <int CB, int TR, bool MASKED, bool THIN = false>
+template <int CB, int TR, int HV, bool MASKED, bool THIN = false>
 __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __restrict__ in, const float* __restrict__ mask,
                                                                  const float* __restrict__ wk, const float* __restrict__ bias,
                                                                  float* __restrict__ out, F32Args a) {
@@ -105,6 +106,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
   constexpr int NC = 16 * CB;
   constexpr int WSZ = (THIN ? 9 : 27) * 4 * NC;    // weights of one channel group (floats)
   constexpr int FT_R = TR, FX_R = TR + 2;          // output rows, staged input rows
+  constexpr int FT_W = 16 * HV, FX_C = FT_W + 2;   // output columns, staged input columns
   constexpr int FX_PS = FX_R * FX_RP;              // plane pitch
   constexpr int FX_CS = fx_cs(TR);                 // channel pitch
   constexpr int FX_SP = FX_P * FX_R * FX_C;        // staged voxels per channel (2040 for 8 rows)
@@ -150,7 +152,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
   // accumulators: one per output row, starting from the bias — or, in the thin form, one per INPUT row (its three kh
   // contributions sit in columns 4 kh + co and meet the output rows they belong to in the epilogue)
   constexpr int NAR = THIN ? FX_R : FT_R;
-  f32x4 acc[CB][NAR][2];
+  f32x4 acc[CB][NAR][HV];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const int co = cog * NC + cb * 16 + (lane & 15);
@@ -158,7 +160,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 #pragma unroll
     for (int r = 0; r < NAR; ++r)
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) acc[cb][r][hf] = f32x4{b, b, b, b};
+      for (int hf = 0; hf < HV; ++hf) acc[cb][r][hf] = f32x4{b, b, b, b};
   }
 
   const float* xw = lds_x + (lane >> 4) * FX_CS + wave * FX_PS + (lane & 15);
@@ -210,17 +212,17 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
       for (int kd = 0; kd < 3; ++kd) {
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
-          float bx[FX_R][2];
+          float bx[FX_R][HV];
 #pragma unroll
           for (int r = 0; r < FX_R; ++r)
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) bx[r][hf] = xw[kd * FX_PS + r * FX_RP + hf * 16 + kw];
+            for (int hf = 0; hf < HV; ++hf) bx[r][hf] = xw[kd * FX_PS + r * FX_RP + hf * 16 + kw];
           if (THIN) {
             const float aw = ww_[(kd * 3 + kw) * 4 * NC];
 #pragma unroll
             for (int r = 0; r < FX_R; ++r)
 #pragma unroll
-              for (int hf = 0; hf < 2; ++hf)
+              for (int hf = 0; hf < HV; ++hf)
                 acc[0][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r][hf], aw, acc[0][r][hf], 0, 0, 0);
           } else {
 #pragma unroll
@@ -231,7 +233,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
 #pragma unroll
                 for (int r = 0; r < FT_R; ++r)
 #pragma unroll
-                  for (int hf = 0; hf < 2; ++hf)
+                  for (int hf = 0; hf < HV; ++hf)
                     acc[cb][r][hf] = __builtin_amdgcn_mfma_f32_16x16x4f32(bx[r + kh][hf], aw, acc[cb][r][hf], 0, 0, 0);
               }
             }
@@ -254,7 +256,7 @@ __global__ void __launch_bounds__(256, 2) conv3d_f32_mfma_kernel(const float* __
       const int h = h0 + r;
       if (h >= H) continue;
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
+      for (int hf = 0; hf < HV; ++hf) {
         const int wc = w0 + hf * 16 + 4 * (lane >> 4);
         if (wc >= W) continue;
         f32x4 o;
@@ -316,7 +318,8 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
   a.mask = mask ? make_geo(mask) : a.in;
   a.out = make_geo(out);
   a.cin = cin_k; a.cout = cout_k; a.ncig = (int)cdiv(cin_k, 4);
-  a.npg = (int)cdiv(a.out.ds, FT_P); a.nwg = (int)cdiv(out->w, FT_W);
+  const int hv = out->w <= 16 ? 1 : 2;
+  a.npg = (int)cdiv(a.out.ds, FT_P); a.nwg = (int)cdiv(out->w, 16 * hv);
   const int ncog = (int)cdiv(cout_k, nc);
   // 8-row tiles unless they would leave most of the chip idle: then 2-row tiles, four times as many workgroups
   const int num_cu = static_cast<Handle*>(handle)->num_cu;
@@ -335,38 +338,43 @@ h3d_status conv3d_f32_mfma(void* handle, const h3d_tensor* in, const h3d_tensor*
     hipLaunchKernelGGL(pack_w_f32_mfma_kernel, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, stream, (const float*)w, (float*)ws,
                        cin, cout, transpose ? 1 : 0, a.ncig, nc, nw);
   const dim3 g((unsigned)tiles, (unsigned)ncog);
-#define H3D_F32_LAUNCH(CBV, TRV, MK, ...)                                                                               \
-  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, TRV, MK, ##__VA_ARGS__>), g, dim3(256), 0, stream, (const float*)in->data, \
+#define H3D_F32_LAUNCH(CBV, TRV, HVV, MK, TH)                                                                           \
+  hipLaunchKernelGGL((conv3d_f32_mfma_kernel<CBV, TRV, HVV, MK, TH>), g, dim3(256), 0, stream, (const float*)in->data,  \
                      (const float*)(mask ? mask->data : nullptr), (const float*)ws, bias, (float*)out->data, a)
-#define H3D_F32_LAUNCH_M(CBV, TRV)                                                                                      \
+#define H3D_F32_LAUNCH_M(CBV, TRV, HVV, TH)                                                                             \
   do {                                                                                                                  \
-    if (mask) H3D_F32_LAUNCH(CBV, TRV, true); else H3D_F32_LAUNCH(CBV, TRV, false);                                     \
+    if (mask) H3D_F32_LAUNCH(CBV, TRV, HVV, true, TH); else H3D_F32_LAUNCH(CBV, TRV, HVV, false, TH);                   \
   } while (0)
-  if (thin) {
-    if (tr == 8) {
-      if (mask) H3D_F32_LAUNCH(1, 8, true, true); else H3D_F32_LAUNCH(1, 8, false, true);
-    } else {
-      if (mask) H3D_F32_LAUNCH(1, 2, true, true); else H3D_F32_LAUNCH(1, 2, false, true);
-    }
-  } else if (cb == 1) {
-    if (tr == 8) H3D_F32_LAUNCH_M(1, 8); else H3D_F32_LAUNCH_M(1, 2);
-  } else {
-    if (tr == 8) H3D_F32_LAUNCH_M(2, 8); else H3D_F32_LAUNCH_M(2, 2);
-  }
+#define H3D_F32_LAUNCH_T(CBV, TH)                                                                                       \
+  do {                                                                                                                  \
+    if (tr == 8 && hv == 2) H3D_F32_LAUNCH_M(CBV, 8, 2, TH);                                                            \
+    else if (tr == 8) H3D_F32_LAUNCH_M(CBV, 8, 1, TH);                                                                  \
+    else if (hv == 2) H3D_F32_LAUNCH_M(CBV, 2, 2, TH);                                                                  \
+    else H3D_F32_LAUNCH_M(CBV, 2, 1, TH);                                                                               \
+  } while (0)
+  if (thin) H3D_F32_LAUNCH_T(1, true);
+  else if (cb == 1) H3D_F32_LAUNCH_T(1, false);
+  else H3D_F32_LAUNCH_T(2, false);
+#undef H3D_F32_LAUNCH_T
 #undef H3D_F32_LAUNCH_M
 #undef H3D_F32_LAUNCH
-  if (thin) note_kernel(handle, "conv3d_f32_mfma_kernel<thin,%d>", tr);
-  else note_kernel(handle, "conv3d_f32_mfma_kernel<%d,%d>", cb, tr);
+  if (thin) note_kernel(handle, "conv3d_f32_mfma_kernel<thin,%d,%d>", tr, hv);
+  else note_kernel(handle, "conv3d_f32_mfma_kernel<%d,%d,%d>", cb, tr, hv);
   return launch_status(handle, "conv3d_f32_mfma");
 }
 
 // ------------------------------------------------------------------------------------------------ backward-filter
-constexpr int BT_R = 4, BT_W = 32;                 // tile of output voxels: rows, columns (one plane)
-constexpr int BX_R = BT_R + 2, BX_C = BT_W + 2;    // staged rows and columns of x (three planes)
-constexpr int BX_SP = 3 * BX_R * BX_C;             // 612 staged voxels per channel
-constexpr int BX_CS = 644;                         // channel pitch of x in LDS: 4 mod 64 (a fragment read takes lane
-                                                   // (c, k) to bank 4 c + k)
-constexpr int BG_CS = BT_R * BT_W + 4;             // channel pitch of g: 132 = 4 mod 64
+// tile of output voxels (one plane, 128 voxels): 4 rows x 32 columns, one row per wavefront — or, for volumes at most 16
+// voxels wide (NARROW), 8 rows x 16 columns, two rows per wavefront
+struct BfTile {
+  int rows, cols, xr, xc, sp, rw, kc;   // tile rows / columns, staged rows / columns of x, staged voxels per channel,
+};                                      // rows per wavefront, K-steps per row
+constexpr BfTile bf_tile(bool narrow) {
+  return narrow ? BfTile{8, 16, 10, 18, 3 * 10 * 18, 2, 4} : BfTile{4, 32, 6, 34, 3 * 6 * 34, 1, 8};
+}
+constexpr int BX_CS = 644;                         // channel pitch of x in LDS (>= 612 staged voxels): 4 mod 64 (a fragment
+                                                   // read takes lane (c, k) to bank 4 c + k)
+constexpr int BG_CS = 128 + 4;                     // channel pitch of g: 132 = 4 mod 64
 
 struct F32BfArgs {
   Geo x, dz, z;
@@ -378,7 +386,7 @@ struct F32BfArgs {
 };
 
 // partial sums: [chunk][cout][cin][28] (slot 27 = bias gradient, written for ci == 0 only)
-template <bool MASKED>
+template <bool MASKED, bool NARROW>
 __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dz,
                                                                      const float* __restrict__ z, float* __restrict__ part,
                                                                      F32BfArgs a) {
@@ -390,8 +398,10 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
   f32x4 acc[28];
 #pragma unroll
   for (int t = 0; t < 28; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const float* xr = lds_x + (lane & 15) * BX_CS + wave * BX_C + (lane >> 4);
-  const float* gr = lds_g + (lane & 15) * BG_CS + wave * BT_W + (lane >> 4);
+  constexpr BfTile T = bf_tile(NARROW);
+  constexpr int BT_R = T.rows, BT_W = T.cols, BX_R = T.xr, BX_C = T.xc, BX_SP = T.sp;
+  const float* xr = lds_x + (lane & 15) * BX_CS + wave * T.rw * BX_C + (lane >> 4);
+  const float* gr = lds_g + (lane & 15) * BG_CS + wave * T.rw * BT_W + (lane >> 4);
 
   // what this thread stages of a tile: three voxels of the x window in each of the 16 input channels, and one voxel of
   // the g tile in 8 of the 16 output channels.  The loads of the next tile are issued before the products of the present
@@ -455,22 +465,25 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
     }
     __syncthreads();
     if (tile + 1 < t1) load_tile(tile + 1);
-    // ---- this wavefront's row: 8 steps of 4 voxels, 27 taps + the bias gradient
+    // ---- this wavefront's row(s): 8 steps of 4 voxels, 27 taps + the bias gradient
+#pragma unroll
+    for (int rr = 0; rr < T.rw; ++rr) {
 #pragma unroll 2
-    for (int ks = 0; ks < BT_W / 4; ++ks) {
-      const float g = gr[4 * ks];
-      float xf[27];
+      for (int kc = 0; kc < T.kc; ++kc) {
+        const float g = gr[rr * BT_W + 4 * kc];
+        float xf[27];
 #pragma unroll
-      for (int t = 0; t < 27; ++t) xf[t] = xr[(t / 9) * (BX_R * BX_C) + ((t / 3) % 3) * BX_C + 4 * ks + t % 3];
+        for (int t = 0; t < 27; ++t) xf[t] = xr[(t / 9) * (BX_R * BX_C) + ((t / 3) % 3 + rr) * BX_C + 4 * kc + t % 3];
 #pragma unroll
-      for (int t = 0; t < 27; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
-      acc[27] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[27], 0, 0, 0);
-      // LDS reads several products ahead of their use: six reads first, then one read per two products
-      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        for (int t = 0; t < 27; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
+        acc[27] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[27], 0, 0, 0);
+        // LDS reads several products ahead of their use: six reads first, then one read per two products
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
-      for (int t = 0; t < 14; ++t) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int t = 0; t < 14; ++t) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
       }
     }
   }
@@ -510,7 +523,7 @@ __global__ void __launch_bounds__(256, 2) bwd_filter_f32_mfma_kernel(const float
 // 4 kw + ci (kw = 3 is padding), so one product covers the three kw taps of a (kd, kh): 9 products + the bias gradient
 // per K-step instead of 28, and only 4 channels of x are staged.  Little per workgroup (≤ 128 registers, 19 KB of LDS):
 // four workgroups per CU.  Same partial-sum layout and reduction as the general form.
-template <bool MASKED>
+template <bool MASKED, bool NARROW>
 __global__ void __launch_bounds__(256, 4) bwd_filter_f32_thin_kernel(const float* __restrict__ x, const float* __restrict__ dz,
                                                                      const float* __restrict__ z, float* __restrict__ part,
                                                                      F32BfArgs a) {
@@ -523,8 +536,10 @@ __global__ void __launch_bounds__(256, 4) bwd_filter_f32_thin_kernel(const float
 #pragma unroll
   for (int t = 0; t < 10; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   // A operand: lane l supplies row l % 16 = (kw, ci) at voxel l / 16 of the K-step
-  const float* xr = lds_x + (lane & 3) * BX_CS + wave * BX_C + (lane >> 4) + ((lane & 15) >> 2);
-  const float* gr = lds_g + (lane & 15) * BG_CS + wave * BT_W + (lane >> 4);
+  constexpr BfTile T = bf_tile(NARROW);
+  constexpr int BT_R = T.rows, BT_W = T.cols, BX_R = T.xr, BX_C = T.xc, BX_SP = T.sp;
+  const float* xr = lds_x + (lane & 3) * BX_CS + wave * T.rw * BX_C + (lane >> 4) + ((lane & 15) >> 2);
+  const float* gr = lds_g + (lane & 15) * BG_CS + wave * T.rw * BT_W + (lane >> 4);
 
   constexpr int BX_PT = (BX_SP + 255) / 256;              // 3
   float xv[BX_PT][4], gv[8], zv[8];
@@ -585,15 +600,18 @@ __global__ void __launch_bounds__(256, 4) bwd_filter_f32_thin_kernel(const float
     }
     __syncthreads();
     if (tile + 1 < t1) load_tile(tile + 1);
+#pragma unroll
+    for (int rr = 0; rr < T.rw; ++rr) {
 #pragma unroll 2
-    for (int ks = 0; ks < BT_W / 4; ++ks) {
-      const float g = gr[4 * ks];
-      float xf[9];
+      for (int kc = 0; kc < T.kc; ++kc) {
+        const float g = gr[rr * BT_W + 4 * kc];
+        float xf[9];
 #pragma unroll
-      for (int t = 0; t < 9; ++t) xf[t] = xr[(t / 3) * (BX_R * BX_C) + (t % 3) * BX_C + 4 * ks];
+        for (int t = 0; t < 9; ++t) xf[t] = xr[(t / 3) * (BX_R * BX_C) + (t % 3 + rr) * BX_C + 4 * kc];
 #pragma unroll
-      for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
-      acc[9] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[9], 0, 0, 0);
+        for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[t], g, acc[t], 0, 0, 0);
+        acc[9] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.f, g, acc[9], 0, 0, 0);
+      }
     }
   }
 
@@ -666,7 +684,8 @@ __global__ void __launch_bounds__(256) bwd_filter_f32_reduce_kernel(const float*
 }
 
 static void f32_bf_plan(const h3d_tensor* x, int cout, int64_t* tiles, int* tpc, int* nchunks) {
-  *tiles = (int64_t)x->n * x->d * cdiv(x->h, BT_R) * cdiv(x->w, BT_W);
+  const BfTile T = bf_tile(x->w <= 16);
+  *tiles = (int64_t)x->n * x->d * cdiv(x->h, T.rows) * cdiv(x->w, T.cols);
   const int64_t blocks = cdiv(cout, 16) * cdiv(x->c, 16);
   const int64_t per_chunk = (int64_t)cout * x->c * 28 * 4;
   int64_t want = std::max<int64_t>(1, cdiv(1024, std::max<int64_t>(blocks, 1)));
@@ -692,25 +711,29 @@ h3d_status bwd_filter_f32_mfma(void* handle, const h3d_tensor* x, const h3d_tens
   F32BfArgs a;
   a.x = make_geo(x); a.dz = make_geo(dz); a.z = z ? make_geo(z) : a.dz;
   a.cin = x->c; a.cout = dz->c; a.mask_slope = mask_slope;
-  a.nhg = (int)cdiv(x->h, BT_R); a.nwg = (int)cdiv(x->w, BT_W);
+  const bool narrow = x->w <= 16;
+  const BfTile T = bf_tile(narrow);
+  a.nhg = (int)cdiv(x->h, T.rows); a.nwg = (int)cdiv(x->w, T.cols);
   int nchunks;
   f32_bf_plan(x, a.cout, &a.tiles, &a.tiles_per_chunk, &nchunks);
   if (!ws || ws_bytes < f32_mfma_bf_ws_bytes(x, a.cout)) return fail(handle, H3D_EWORKSPACE, "conv3d_bwd_filter: workspace too small");
   if (z && !fits_buf(z)) return fail(handle, H3D_EUNSUPPORTED, "conv3d_bwd_filter: z too large for this kernel");
   const dim3 g((unsigned)nchunks, (unsigned)cdiv(a.cout, 16), (unsigned)cdiv(a.cin, 16));
   const bool thin = a.cin <= 4;
-  if (thin && z)
-    hipLaunchKernelGGL((bwd_filter_f32_thin_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
-                       (const float*)z->data, (float*)ws, a);
-  else if (thin)
-    hipLaunchKernelGGL((bwd_filter_f32_thin_kernel<false>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
-                       (const float*)nullptr, (float*)ws, a);
-  else if (z)
-    hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<true>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
-                       (const float*)z->data, (float*)ws, a);
-  else
-    hipLaunchKernelGGL((bwd_filter_f32_mfma_kernel<false>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,
-                       (const float*)nullptr, (float*)ws, a);
+#define H3D_F32_BF(KERN, MK, NW)                                                                                        \
+  hipLaunchKernelGGL((KERN<MK, NW>), g, dim3(256), 0, stream, (const float*)x->data, (const float*)dz->data,            \
+                     (const float*)(z ? z->data : nullptr), (float*)ws, a)
+#define H3D_F32_BF_K(KERN)                                                                                              \
+  do {                                                                                                                  \
+    if (z && narrow) H3D_F32_BF(KERN, true, true);                                                                      \
+    else if (z) H3D_F32_BF(KERN, true, false);                                                                          \
+    else if (narrow) H3D_F32_BF(KERN, false, true);                                                                     \
+    else H3D_F32_BF(KERN, false, false);                                                                                \
+  } while (0)
+  if (thin) H3D_F32_BF_K(bwd_filter_f32_thin_kernel);
+  else H3D_F32_BF_K(bwd_filter_f32_mfma_kernel);
+#undef H3D_F32_BF_K
+#undef H3D_F32_BF
   const int64_t total = (int64_t)a.cout * a.cin * 28;
   hipLaunchKernelGGL(bwd_filter_f32_reduce_kernel, dim3((unsigned)cdiv(total, 16)), dim3(256), 0, stream, (const float*)ws, dw, db,
                      a.cin, a.cout, nchunks);

@@ -342,6 +342,10 @@ F32_SHAPES = [
     (2, 20, 3, 5, 9, 37, 0, 0, 5),
     (2, 1, 2, 3, 10, 72, 1, 3, 9),
     (2, 16, 4, 16, 100, 132, 0, 0, 16),
+    # volumes at most 16 voxels wide: 16-column tiles (forward / BD) and 8-row x 16-column tiles (BF)
+    (2, 20, 24, 4, 12, 8, 1, 0, 4),
+    (1, 3, 6, 5, 9, 12, 0, 0, 5),
+    (4, 5, 6, 16, 256, 16, 0, 0, 16),
 ]
 
 
@@ -399,11 +403,14 @@ def test_conv3d_fp32_matrix_core_kernels(shape):
 
 
 def test_conv3d_fp32_every_instance_was_run():
-    """The shapes above reach all six instances of the fp32 forward / backward-data kernel (collected from the library's
+    """The shapes above reach the instances of the fp32 forward / backward-data kernel (channel-block form x tile rows x
+    tile halves) (collected from the library's
     own report of the kernel it ran); skipped when that test was not run in this process."""
     if not kernels_seen:
         pytest.skip("test_conv3d_fp32_matrix_core_kernels did not run in this process")
-    assert kernels_seen == {"conv3d_f32_mfma_kernel<%s,%d>" % (cb, tr) for cb in ("1", "2", "thin") for tr in (2, 8)}, kernels_seen
+    want = {"conv3d_f32_mfma_kernel<%s,%d,2>" % (cb, tr) for cb in ("1", "2", "thin") for tr in (2, 8)}
+    want |= {"conv3d_f32_mfma_kernel<%s,1>" % k for k in ("1,8", "1,2", "2,2", "thin,2")}
+    assert want <= kernels_seen, (want - kernels_seen, kernels_seen)
 
 
 def test_plane_run_views_are_rejected_elsewhere():
