@@ -229,9 +229,10 @@ def build_workload(name, args, seed):
         return net, (f"CosmoFlow-shaped stack: N={args.batch} x 4x{args.width}^3, conv 16-32-64-128-256 + leaky-ReLU + avg-pool, "
                      f"dense 2048-256-4, MSE; fwd+bwd; {2 if net.overlap else 1} streams"), args.batch * args.width ** 3, args.dtype
     if name == "shard512":
-        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", faces_hw=True)
-        return net, ("one interior 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky-ReLU + avg-pool, "
-                     "fwd / bwd-data / bwd-filter, D halo faces packed and unpacked; H and W faces of g"), 64 * 512 * 512, "bf16"
+        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", faces_hw=True, fuse_pool=not args.unfused)
+        return net, ("one interior 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky-ReLU + avg-pool "
+                     + ("(three separate passes)" if args.unfused else "(one fused call, sign mask for the backward pass)") +
+                     ", bwd-data / bwd-filter, D halo faces packed and unpacked; H and W faces of g"), 64 * 512 * 512, "bf16"
     if name == "late256":
         net = _single_layer(seed, 8, 256, 256, 16, 16, 0, 16, bf, pool=False)
         return net, "weight-gradient-bound late layer: N=8, 256->256 channels, 16^3, bf16, fwd / bwd-data / bwd-filter", 8 * 16 ** 3, "bf16"
@@ -477,7 +478,7 @@ def main():
                     "--steps times; used to profile one kernel under rocprofv3")
     ap.add_argument("--copy-ref", action="store_true", help="run a plain copy of known size (halo_pack of a whole "
                     "16x64x512x512 bf16 interior: 536.9 MB read + 536.9 MB written) to calibrate HBM byte counters")
-    ap.add_argument("--unfused", action="store_true", help="cosmoflow / table1 / chain512: store the first stage's unpooled activation "
+    ap.add_argument("--unfused", action="store_true", help="cosmoflow / table1 / chain512 / shard512: store the first stage's unpooled activation "
                     "(separate conv, pool and pool-backward calls) instead of the fused forward + sign mask")
     ap.add_argument("--no-overlap", action="store_true", help="cosmoflow / table1: keep every call of the step on one stream (default: the "
                     "backward-filter calls of the late stages run on a second stream beside the backward-data chain)")

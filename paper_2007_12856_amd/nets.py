@@ -437,7 +437,8 @@ class SingleLayer:
     The caller brings the tensors that hold values (x with its halo planes, w, b, the gradient slab g with a halo
     plane per side, the pooled gradient dp when pooling is on); buffers that are only written are made here."""
 
-    def __init__(self, x: Slab, w, b, g: Slab, dp: Slab | None = None, pool=True, act=ACT_LEAKY, alpha=0.01, split=False, faces_hw=False):
+    def __init__(self, x: Slab, w, b, g: Slab, dp: Slab | None = None, pool=True, act=ACT_LEAKY, alpha=0.01, split=False, faces_hw=False,
+                 fuse_pool=False):
         from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
         dev, dtype = x.t.device, x.t.dtype
         n, cin, _, hw, _ = x.t.shape
@@ -445,7 +446,11 @@ class SingleLayer:
         self.ws = Workspace()
         ws, es = self.ws, x.t.element_size()
         self.x, self.w, self.b, self.g = x, w, b, g
-        z = self.z = Slab(torch.empty((n, cout, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
+        # fuse_pool: convolution, activation and average pooling in one call; the unpooled activation is not stored, a
+        # sign mask (one bit per voxel) stands in for it in the pooling backward (first-layer shapes, bf16)
+        fused = self.fused = bool(fuse_pool and pool and not split and dtype == torch.bfloat16 and cin <= 4 and cout <= 32
+                                  and d % 2 == 0 and hw % 16 == 0)
+        z = self.z = None if fused else Slab(torch.empty((n, cout, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
         dx = self.dx = Slab(torch.empty((n, cin, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
         self.dw = torch.empty((cout, cin, 3, 3, 3), device=dev)
         self.db = torch.empty((cout,), device=dev)
@@ -460,7 +465,13 @@ class SingleLayer:
 
         op("halo_pack_x", lambda: (halo_pack(x, FACE_D_LO, 1, faces[0]), halo_pack(x, FACE_D_HI, 1, faces[1])), 0, 4 * faces[0].numel() * es)
         op("halo_unpack_x", lambda: (halo_unpack(faces[1], x, FACE_D_LO, 1), halo_unpack(faces[0], x, FACE_D_HI, 1)), 0, 4 * faces[0].numel() * es)
-        op("conv_fwd", lambda: conv3d_fwd(x, w, b, z, act, alpha, ws), fl, (x.t.numel() + z.t.numel() + w.numel()) * es)
+        if fused:
+            p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
+            mask = self.mask = torch.empty((n * cout * d * hw * hw // 8,), dtype=torch.uint8, device=dev)
+            op("conv_fwd_pool", lambda: conv3d_fwd_pool(x, w, b, (n, cout, d, hw, hw), p, mask, act, alpha, ws), fl,
+               (x.t.numel() + p.t.numel() + w.numel()) * es + mask.numel())
+        else:
+            op("conv_fwd", lambda: conv3d_fwd(x, w, b, z, act, alpha, ws), fl, (x.t.numel() + z.t.numel() + w.numel()) * es)
         if split and d >= 3:
             # the same forward as main planes (no halo needed) + the two one-plane strips (Sec. III-C), on plane-run views
             pl = n * hw * hw
@@ -469,7 +480,10 @@ class SingleLayer:
             op("conv_fwd_strips", lambda: (conv3d_fwd(x.planes(0, 1, 1, 1), w, b, z.planes(0, 1), act, alpha, ws),
                                            conv3d_fwd(x.planes(d - 1, d, 1, 1), w, b, z.planes(d - 1, d), act, alpha, ws)),
                fl * 2 // d, (pl * 2 * (3 * cin + cout) + 2 * w.numel()) * es)
-        if pool:
+        if pool and fused:
+            self.dp = dp
+            op("pool_bwd_mask", lambda: pool3d_bwd_mask(dp, mask, g, act, alpha), 0, (dp.t.numel() + vox * cout) * es + mask.numel())
+        elif pool:
             p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
             self.dp = dp
             op("pool_fwd", lambda: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)

@@ -310,6 +310,45 @@ def test_cfg3_pool_and_halo_at_full_size():
         assert np.array_equal(from_dev(t.t), o.a)
 
 
+def test_cfg3_fused_first_layer_full_size():
+    """The first layer of the shard as `bench.py --workload shard512` runs it: convolution + leaky-ReLU + 2x2x2 average
+    pooling in ONE call that stores no unpooled activation but its sign mask, and the pooling backward that reads the mask.
+    Sampled pooled planes against the oracle's composition conv -> store as bf16 -> pool (Sec. III-C FP; Table I shapes)."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    n, cin, cout, d, hw, off, dg, alpha = 1, 4, 16, 64, 512, 64, 512, 0.01
+    bnd = np.sqrt(3.0 / (27 * cin))
+    w = quantize(synth.flat("uniform", SEED, 111, (cout, cin, 3, 3, 3), -bnd, bnd), BF)
+    bias = synth.round_f32(synth.flat("uniform", SEED, 112, (cout,), -0.1, 0.1)).astype(np.float64)
+    x = h3d.Slab(_noise((n, cin, d + 2, hw, hw), 21), 1, 1, off, dg)
+    qs, xs = (0, 17, 31), {}
+    for q in qs:                                   # pooled plane q <- output planes 2q, 2q+1 <- input planes 2q-1 .. 2q+2
+        xs[q] = _planes("cosmo", 113, (n, cin, dg, hw, hw), off + 2 * q - 1, off + 2 * q + 3)
+        _put(x.t, 2 * q, xs[q])
+    y = h3d.Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=torch.bfloat16, device="cuda"), 0, 0, off // 2, dg // 2)
+    mask = torch.full((n * cout * d * hw * hw // 8,), 0xAA, dtype=torch.uint8, device="cuda")
+    h3d.conv3d_fwd_pool(x, to_dev(w, BF), to_dev(bias, "f32"), (n, cout, d, hw, hw), y, mask, h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel().startswith("conv3d_fwd_c4_roll"), h3d.h3d_last_kernel()
+    mk = mask.cpu().numpy().reshape(n, cout, d, hw, hw // 8)
+    for q in qs:
+        zo = orc.conv3d_fwd(orc.Slab(xs[q], 1, 1, off + 2 * q, dg), w, bias, act=orc.ACT_LEAKY, alpha=alpha)
+        zq = orc.Slab(quantize(zo.a, BF), 0, 0, off + 2 * q, dg)
+        close(from_dev(y.t[:, :, q]), orc.pool3d_fwd(zq, orc.POOL_AVG).a[:, :, 0], 4e-3, f"pooled plane {q}")
+        # the mask is the sign of the activation; the two sides may differ where it is within rounding of zero
+        diff = np.unpackbits((mk[:, :, 2 * q:2 * q + 2] ^ orc.act_mask(zq))[..., None], axis=-1, bitorder="little")
+        diff = diff.reshape(zo.a.shape).astype(bool)
+        assert np.all(np.abs(zo.a[diff]) <= 1e-2 * np.abs(zo.a).max()) and diff.mean() < 1e-3, f"mask of planes {2 * q}, {2 * q + 1}"
+    # pooling backward from the mask: g = pool'(dp) * act'(z), the sign taken from the stored mask on both sides
+    dp = h3d.Slab(_noise((n, cout, d // 2, hw // 2, hw // 2), 22), 0, 0, off // 2, dg // 2)
+    g = h3d.Slab(torch.full((n, cout, d + 2, hw, hw), 7.0, dtype=torch.bfloat16, device="cuda"), 1, 1, off, dg)
+    h3d.pool3d_bwd_mask(dp, mask, g, h3d.ACT_LEAKY, alpha)
+    for q in qs:
+        up = orc.pool3d_bwd(orc.Slab(from_dev(dp.t[:, :, q:q + 1])), None, orc.POOL_AVG).a
+        pos = np.unpackbits(mk[:, :, 2 * q:2 * q + 2][..., None], axis=-1, bitorder="little").reshape(up.shape).astype(bool)
+        close(from_dev(g.t[:, :, 1 + 2 * q:3 + 2 * q]), up * np.where(pos, 1.0, alpha), 4e-3, f"g planes {2 * q}, {2 * q + 1}")
+    assert torch.all(g.t[:, :, 0] == 7.0) and torch.all(g.t[:, :, -1] == 7.0)        # halo planes are the neighbours': untouched
+
+
 # ---------------------------------------------------------------- configuration 4 (layers at full shape)
 @pytest.mark.parametrize("name,cin,cout,d,hw,halo_in,halo_out,dg,planes", [
     ("c1", 1, 32, 64, 256, 2, 1, 256, [-1, 30, 64]),
