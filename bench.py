@@ -171,6 +171,14 @@ def _cosmo_field(gen, shape, dtype):
     return torch.log1p(torch.poisson(torch.exp(g), generator=gen)).to(dtype)
 
 
+def _adjacent(lo, hi):
+    """The two face buffers of a tensor as halves of one allocation (LO first): the library then packs / unpacks both
+    faces in one call."""
+    import torch
+    both = torch.cat([lo.reshape(-1), hi.reshape(-1)])
+    return both[:lo.numel()].view_as(lo), both[lo.numel():].view_as(hi)
+
+
 def _single_layer(seed, n, cin, cout, d, hw, d_offset, d_global, dtype, field="normal", pool=True, **kw):
     """Harness inputs of one layer on a shard (seeded, drawn on the GPU): x with one halo plane per side, weights
     U[+-sqrt(3/fan_in)], bias U[+-0.1], the gradient slab g ~ N(0,1) with one halo plane per side, pooled gradient."""
@@ -212,7 +220,7 @@ def build_workload(name, args, seed):
         faces = {}
         for k, (c, width, level, nonneg) in spec.items():
             pair = [_randn(gen, (1, c, width, 256 // level, 256 // level), bf) for _ in range(2)]
-            faces[k] = tuple(torch.relu(f) if nonneg else f for f in pair)
+            faces[k] = _adjacent(*(torch.relu(f) if nonneg else f for f in pair))
         net = nets.UNetLevel(h3d.Slab(x, 2, 2, 64, 256), {k: (dev(w), dev(b, torch.float32)) for k, (w, b) in P.items()}, dout, faces)
         return net, ("U-Net-shaped level on an interior 64x256x256 shard of a 1-channel 256^3 volume (2-voxel halo), bf16: conv 1-32-64, "
                      "max-pool, conv 64-64-128, transposed conv 128-64, concat, conv 128-64, ReLU; fwd+bwd"), 64 * 256 * 256, "bf16"
@@ -264,7 +272,7 @@ def build_workload(name, args, seed):
     if name == "chain512":
         x, conv, dout, faces = recipes.shard_chain_inputs(seed, 512, 64, 64, 512, n=args.batch)
         net = nets.CosmoFlowShardChain(h3d.Slab(dev(x), 1, 1, 64, 512), [(dev(w), None) for w, _ in conv], dev(dout),
-                                       {k: (dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
+                                       {k: _adjacent(dev(lo), dev(hi)) for k, (lo, hi) in faces.items()}, fuse_pool=not args.unfused)
         return net, (f"conv1-pool1 .. conv3-pool3 of Table I's 512^3 network on one interior shard of an 8-way depth partition "
                      f"(N={args.batch} x 4x(64+2)x512x512 bf16), halo faces packed and unpacked per stage, fwd+bwd"), args.batch * 64 * 512 * 512, "bf16"
     if name == "k5":

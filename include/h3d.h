@@ -54,7 +54,9 @@ typedef enum {
 
 typedef enum { H3D_ACT_NONE = 0, H3D_ACT_RELU = 1, H3D_ACT_LEAKY = 2 } h3d_act;
 typedef enum { H3D_POOL_AVG = 0, H3D_POOL_MAX = 1 } h3d_pool;
-typedef enum { H3D_FACE_D_LO = 0, H3D_FACE_D_HI = 1 } h3d_face;
+/* D_BOTH: the two depth faces in one call (one launch instead of two: the faces of a shard are small, and a call costs a
+ * kernel launch whatever its size); the buffer then holds the LO face followed by the HI face, h3d_halo_bytes each. */
+typedef enum { H3D_FACE_D_LO = 0, H3D_FACE_D_HI = 1, H3D_FACE_D_BOTH = 2 } h3d_face;
 typedef enum { H3D_OP_FWD = 0, H3D_OP_BWD_DATA = 1, H3D_OP_BWD_FILTER = 2 } h3d_conv_op;
 
 typedef struct {
@@ -251,10 +253,12 @@ h3d_status h3d_pool3d_bwd_mask(void* handle, const h3d_tensor* dy, const void* m
  *      neighbour communication of boundary regions) ---- bit-exact copies.
  * Face buffer layout: [n][c][width][h][w] packed, same dtype as t. */
 size_t h3d_halo_bytes(const h3d_tensor* t, int width);
-/* pack: copy the `width` outermost INTERIOR planes at `face` into buf (what the neighbour needs). */
+/* pack: copy the `width` outermost INTERIOR planes at `face` into buf (what the neighbour needs).
+ * face D_BOTH: buf = [LO face][HI face], 2 * h3d_halo_bytes(t, width) bytes. */
 h3d_status h3d_halo_pack(void* handle, const h3d_tensor* t, int face, int width, void* buf, void* stream);
 /* unpack: write buf into the `width` HALO planes adjacent to the interior at `face`
- * (width <= that halo); buf == NULL zero-fills them (global boundary). */
+ * (width <= that halo); buf == NULL zero-fills them (global boundary).
+ * face D_BOTH: buf = [planes for the LO halo][planes for the HI halo] (width <= both halos); NULL zero-fills both. */
 h3d_status h3d_halo_unpack(void* handle, const void* buf, h3d_tensor* t, int face, int width, void* stream);
 
 /* ---- general faces (Sec. II-B: the spatial domain may be partitioned in any of its three dimensions;

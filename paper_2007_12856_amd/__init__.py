@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libh3d.so")
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_LEAKY = 0, 1, 2
 POOL_AVG, POOL_MAX = 0, 1
-FACE_D_LO, FACE_D_HI = 0, 1
+FACE_D_LO, FACE_D_HI, FACE_D_BOTH = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 STATUS = {0: "H3D_OK", -1: "H3D_EINVAL", -2: "H3D_EUNSUPPORTED", -3: "H3D_EWORKSPACE", -4: "H3D_EHALO", -5: "H3D_EHIP"}
 

@@ -98,30 +98,35 @@ extern "C" size_t h3d_halo_bytes(const h3d_tensor* t, int width) {
 
 static h3d_status face_args(void* handle, const h3d_tensor* t, int face, int width, bool pack, RunCopy* a) {
   H3D_TRY(check_tensor_packed(handle, t, "t"));
-  if (face != H3D_FACE_D_LO && face != H3D_FACE_D_HI) return fail(handle, H3D_EINVAL, "halo: bad face %d", face);
+  if (face != H3D_FACE_D_LO && face != H3D_FACE_D_HI && face != H3D_FACE_D_BOTH) return fail(handle, H3D_EINVAL, "halo: bad face %d", face);
   if (width <= 0) return fail(handle, H3D_EINVAL, "halo: width must be positive");
-  int64_t first;  // first stored plane of the face region
+  const bool both = face == H3D_FACE_D_BOTH;
+  int64_t first, first_hi;  // first stored plane of the face region (of the LO region and of the HI region for D_BOTH)
   if (pack) {
     if (width > t->d) return fail(handle, H3D_EINVAL, "halo_pack: width %d exceeds interior depth %d", width, t->d);
-    first = face == H3D_FACE_D_LO ? t->halo_lo : t->halo_lo + t->d - width;
+    first_hi = t->halo_lo + t->d - width;
+    first = face == H3D_FACE_D_HI ? first_hi : t->halo_lo;
   } else {
-    int have = face == H3D_FACE_D_LO ? t->halo_lo : t->halo_hi;
+    int have = both ? (t->halo_lo < t->halo_hi ? t->halo_lo : t->halo_hi) : (face == H3D_FACE_D_LO ? t->halo_lo : t->halo_hi);
     if (width > have) return fail(handle, H3D_EHALO, "halo_unpack: width %d exceeds stored halo %d", width, have);
-    first = face == H3D_FACE_D_LO ? t->halo_lo - width : t->halo_lo + t->d;
+    first_hi = t->halo_lo + t->d;
+    first = face == H3D_FACE_D_HI ? first_hi : t->halo_lo - width;
   }
   Geo g = make_geo(t);
   const int64_t es = elt_size(t->dtype);
-  a->nruns = (int64_t)t->n * t->c;
-  a->inner = a->nruns;  // single-level: i = 0
+  const int64_t nc = (int64_t)t->n * t->c;
+  a->nruns = both ? 2 * nc : nc;
+  a->inner = nc;            // run r = (face i = r / inner, (n, c) j = r % inner); one face: i = 0
   a->run_bytes = (int64_t)width * g.plane * es;
-  // slab side
-  int64_t slab_off = first * g.plane * es, slab_stride = g.cstride * es;
+  // slab side: the HI region starts (first_hi - first) planes above the LO region; buffer side: the HI face follows the LO face
+  const int64_t slab_off = first * g.plane * es, slab_stride = g.cstride * es;
+  const int64_t slab_outer = both ? (first_hi - first) * g.plane * es : 0, buf_outer = both ? nc * a->run_bytes : 0;
   if (pack) {
-    a->src = (const char*)t->data + slab_off; a->src_outer = 0; a->src_inner = slab_stride;
-    a->dst_outer = 0; a->dst_inner = a->run_bytes;
+    a->src = (const char*)t->data + slab_off; a->src_outer = slab_outer; a->src_inner = slab_stride;
+    a->dst_outer = buf_outer; a->dst_inner = a->run_bytes;
   } else {
-    a->dst = (char*)t->data + slab_off; a->dst_outer = 0; a->dst_inner = slab_stride;
-    a->src_outer = 0; a->src_inner = a->run_bytes;
+    a->dst = (char*)t->data + slab_off; a->dst_outer = slab_outer; a->dst_inner = slab_stride;
+    a->src_outer = buf_outer; a->src_inner = a->run_bytes;
   }
   return H3D_OK;
 }
@@ -140,7 +145,7 @@ extern "C" h3d_status h3d_halo_unpack(void* handle, const void* buf, h3d_tensor*
   RunCopy a{};
   H3D_TRY(face_args(handle, t, face, width, false, &a));
   a.src = (const char*)buf;  // nullptr => zero fill
-  if (!buf) { a.src_inner = 0; }
+  if (!buf) { a.src_inner = 0; a.src_outer = 0; }
   return copy_runs(handle, a, (hipStream_t)stream, "halo_unpack");
 }
 

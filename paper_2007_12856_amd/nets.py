@@ -13,6 +13,41 @@ from . import (ACT_LEAKY, ACT_NONE, POOL_AVG, Slab, Workspace, conv3d_bwd_data, 
                conv3d_fwd_pool, conv3d_s2_bwd_data, conv3d_s2_bwd_filter, conv3d_s2_fwd, dense_bwd, dense_fwd, mse_fwd_bwd, pool3d_bwd, pool3d_bwd_act, pool3d_bwd_mask, pool3d_fwd, pool3d_fwd_mask)
 
 
+def face_pair(t: "Slab", width: int):
+    """Two face buffers of `t` (LO, HI) that are the halves of ONE allocation, so that both faces can go through a single
+    halo_pack / halo_unpack call (FACE_D_BOTH)."""
+    from . import halo_bytes
+    k = halo_bytes(t, width) // t.t.element_size()
+    both = torch.empty(2 * k, dtype=t.t.dtype, device=t.t.device)
+    return both[:k], both[k:]
+
+
+def _adjacent(lo, hi) -> bool:
+    return (lo is not None and hi is not None and lo.is_contiguous() and hi.is_contiguous() and lo.numel() == hi.numel()
+            and lo.data_ptr() + lo.numel() * lo.element_size() == hi.data_ptr())
+
+
+def pack_faces(t: "Slab", width: int, lo, hi):
+    """The two depth faces of t's interior into lo / hi: one call when the two buffers are adjacent in memory."""
+    from . import FACE_D_BOTH, FACE_D_HI, FACE_D_LO, halo_pack
+    if _adjacent(lo, hi):
+        halo_pack(t, FACE_D_BOTH, width, lo)
+    else:
+        halo_pack(t, FACE_D_LO, width, lo)
+        halo_pack(t, FACE_D_HI, width, hi)
+
+
+def unpack_faces(lo, hi, t: "Slab", width: int):
+    """lo / hi (None: zero fill, the global boundary) into the two halos of t: one call when the two buffers are adjacent
+    in memory, or both are None."""
+    from . import FACE_D_BOTH, FACE_D_HI, FACE_D_LO, halo_unpack
+    if _adjacent(lo, hi) or (lo is None and hi is None):
+        halo_unpack(lo, t, FACE_D_BOTH, width)
+    else:
+        halo_unpack(lo, t, FACE_D_LO, width)
+        halo_unpack(hi, t, FACE_D_HI, width)
+
+
 class CosmoFlowStack:
     def __init__(self, x: torch.Tensor, target: torch.Tensor, conv_params, fc_params, alpha: float = 0.01, fuse_pool: bool = False,
                  strides=None, pools=None):
@@ -271,7 +306,7 @@ class UNetLevel:
         def exchange(name, t, width):
             lo, hi = faces[name]
             io = [f for f in (lo, hi) if f is not None] * 2
-            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, width), halo_unpack(hi, t, FACE_D_HI, width)), 0, io)
+            op(f"halo_unpack_{name}", lambda: unpack_faces(lo, hi, t, width), 0, io)
 
         P = params
         W = {k: v[0] for k, v in params.items()}
@@ -369,7 +404,7 @@ class CosmoFlowShardChain:
         self.da[0] = Slab(torch.empty((n, x.t.shape[1], x.d, x.t.shape[3], x.t.shape[4]), dtype=dt, device=dev), 0, 0, x.d_offset, x.d_global)
         self.dconv = [(torch.empty(w.shape, dtype=torch.float32, device=dev),
                        None if b is None else torch.empty(b.shape, dtype=torch.float32, device=dev)) for w, b in conv_params]
-        send = lambda t: [torch.empty(halo_bytes(t, 1) // es, dtype=dt, device=dev) for _ in range(2)]
+        send = lambda t: list(face_pair(t, 1))
         self.sent = {}
         self.ops = []
 
@@ -378,11 +413,11 @@ class CosmoFlowShardChain:
 
         def unpack(name, t):
             lo, hi = faces[name]
-            op(f"halo_unpack_{name}", lambda: (halo_unpack(lo, t, FACE_D_LO, 1), halo_unpack(hi, t, FACE_D_HI, 1)), 0, 4 * halo_bytes(t, 1))
+            op(f"halo_unpack_{name}", lambda: unpack_faces(lo, hi, t, 1), 0, 4 * halo_bytes(t, 1))
 
         def pack(name, t):
             bufs = self.sent[name] = send(t)
-            op(f"halo_pack_{name}", lambda: (halo_pack(t, FACE_D_LO, 1, bufs[0]), halo_pack(t, FACE_D_HI, 1, bufs[1])), 0, 4 * halo_bytes(t, 1))
+            op(f"halo_pack_{name}", lambda: pack_faces(t, 1, bufs[0], bufs[1]), 0, 4 * halo_bytes(t, 1))
 
         for i, (w, b) in enumerate(conv_params):
             cur, nxt, z, mask, g = a[i], a[i + 1], self.z[i], self.mask[i], self.g[i]
@@ -454,8 +489,7 @@ class SingleLayer:
         dx = self.dx = Slab(torch.empty((n, cin, d, hw, hw), dtype=dtype, device=dev), 0, 0, d_offset, d_global)
         self.dw = torch.empty((cout, cin, 3, 3, 3), device=dev)
         self.db = torch.empty((cout,), device=dev)
-        faces = [torch.empty(halo_bytes(x, 1) // es, dtype=dtype, device=dev) for _ in range(2)]
-        gfaces = [torch.empty(halo_bytes(g, 1) // es, dtype=dtype, device=dev) for _ in range(2)]
+        faces, gfaces = face_pair(x, 1), face_pair(g, 1)      # (what goes out to the neighbours comes back in: a stand-in for theirs)
         self.ops = []
         fl = 2 * 27 * cin * cout * n * d * hw * hw
         vox = n * d * hw * hw
@@ -463,8 +497,8 @@ class SingleLayer:
         def op(name, fn, flops=0, nbytes=0):
             self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": int(nbytes)})
 
-        op("halo_pack_x", lambda: (halo_pack(x, FACE_D_LO, 1, faces[0]), halo_pack(x, FACE_D_HI, 1, faces[1])), 0, 4 * faces[0].numel() * es)
-        op("halo_unpack_x", lambda: (halo_unpack(faces[1], x, FACE_D_LO, 1), halo_unpack(faces[0], x, FACE_D_HI, 1)), 0, 4 * faces[0].numel() * es)
+        op("halo_pack_x", lambda: pack_faces(x, 1, faces[0], faces[1]), 0, 4 * faces[0].numel() * es)
+        op("halo_unpack_x", lambda: unpack_faces(faces[0], faces[1], x, 1), 0, 4 * faces[0].numel() * es)
         if fused:
             p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
             mask = self.mask = torch.empty((n * cout * d * hw * hw // 8,), dtype=torch.uint8, device=dev)
@@ -488,8 +522,8 @@ class SingleLayer:
             self.dp = dp
             op("pool_fwd", lambda: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
             op("pool_bwd_act", lambda: pool3d_bwd_act(dp, None, z, g, POOL_AVG, act, alpha), 0, (dp.t.numel() + 2 * z.t.numel()) * es)
-        op("halo_pack_g", lambda: (halo_pack(g, FACE_D_LO, 1, gfaces[0]), halo_pack(g, FACE_D_HI, 1, gfaces[1])), 0, 4 * gfaces[0].numel() * es)
-        op("halo_unpack_g", lambda: (halo_unpack(gfaces[1], g, FACE_D_LO, 1), halo_unpack(gfaces[0], g, FACE_D_HI, 1)), 0, 4 * gfaces[0].numel() * es)
+        op("halo_pack_g", lambda: pack_faces(g, 1, gfaces[0], gfaces[1]), 0, 4 * gfaces[0].numel() * es)
+        op("halo_unpack_g", lambda: unpack_faces(gfaces[0], gfaces[1], g, 1), 0, 4 * gfaces[0].numel() * es)
         if faces_hw:
             # H and W faces of the activation gradient (a partitioning in H or W as well, Sec. II-B): one and two
             # voxels wide, pack and unpack of both ends; bytes = face read + face written

@@ -94,6 +94,46 @@ def test_halo_exchange_is_bit_exact(shape, dtype):
             assert np.array_equal(from_dev(shards_g[s].t), shards_o[s].a)   # canaries included
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,halo", [((2, 3, 4, 4, 5), (2, 2)), ((1, 4, 6, 16, 32), (1, 2)), ((1, 1, 2, 3, 3), (2, 1)),
+                                        ((2, 16, 8, 32, 64), (1, 1))])
+def test_both_faces_in_one_call_equal_the_two_calls(shape, halo, dtype):
+    """FACE_D_BOTH packs / unpacks the two depth faces with one launch: the buffer is the LO face followed by the HI
+    face, each bit for bit what the oracle's per-face call gives; NULL zero-fills both halos; canary planes stay."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, C, d, H, W = shape
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    a = synth.flat("normal", SEED, 23, (N, C, halo[0] + d + halo[1], H, W))
+    for width in (1, 2):
+        if width > d:
+            continue
+        o, g = slab_pair(a, dtype, halo, 8, 8 + d + 8)
+        k = h3d.halo_bytes(g, width) // (4 if dtype == "f32" else 2)
+        buf = torch.full((2 * k,), 5.0, dtype=tdt, device="cuda")
+        h3d.halo_pack(g, h3d.FACE_D_BOTH, width, buf)
+        lo, hi = orc.halo_pack(o, orc.FACE_D_LO, width), orc.halo_pack(o, orc.FACE_D_HI, width)
+        assert np.array_equal(from_dev(buf[:k]).reshape(lo.shape), lo) and np.array_equal(from_dev(buf[k:]).reshape(hi.shape), hi)
+        if width > min(halo):
+            with pytest.raises(h3d.H3DError) as e:
+                h3d.halo_unpack(buf, g, h3d.FACE_D_BOTH, width)
+            assert e.value.status == -4
+            continue
+        # unpack what was packed, swapped as two neighbours of the same content would send it
+        sw = torch.cat([buf[k:], buf[:k]])
+        h3d.halo_unpack(sw, g, h3d.FACE_D_BOTH, width)
+        orc.halo_unpack(hi, o, orc.FACE_D_LO, width)
+        orc.halo_unpack(lo, o, orc.FACE_D_HI, width)
+        assert np.array_equal(from_dev(g.t), o.a)
+        h3d.halo_unpack(None, g, h3d.FACE_D_BOTH, width)
+        orc.halo_unpack(None, o, orc.FACE_D_LO, width)
+        orc.halo_unpack(None, o, orc.FACE_D_HI, width)
+        assert np.array_equal(from_dev(g.t), o.a)
+    with pytest.raises(h3d.H3DError) as e:
+        h3d.halo_pack(g, 3, 1, buf)
+    assert e.value.status == -1
+
+
 # (N, C, D, H, W) stored extents and boxes (d0, h0, w0, bd, bh, bw): D, H and W faces one and two voxels wide, at both
 # ends, aligned and unaligned, a whole-tensor box, a single element, an empty box
 BOX_CASES = [
