@@ -5,7 +5,7 @@ A "step" is one pass of the whole hot path of a configuration over one synthetic
   unet      (configuration 4, the headline: the largest single-GPU configuration, 8.2 TFlop per step) the U-Net-shaped
             level on a 64x256x256 shard of a 256^3 volume, bf16, forward + backward;
   cosmoflow (configuration 2) the CosmoFlow-shaped stack, N=4 x 4x128^3, bf16, forward + backward;
-  shard512  (configuration 3) conv 4->16 + leaky-ReLU + avg-pool + halo faces on one 8-way depth shard of a 4x512^3 sample;
+  shard512  (configuration 3) conv 4->16 + leaky-ReLU + avg-pool + the D halo faces on one 8-way depth shard of a 4x512^3 sample;
   late256   (configuration 5) the weight-gradient-bound late layer, N=8, 256->256 channels on 16^3;
   single32  (configuration 1) one fp32 layer, 4->16 channels on 32^3 (the correctness-sized case).
 For each: W warm-up steps, then EXACTLY K timed steps between two device synchronisations (wall clock), then P >= 10
@@ -38,7 +38,7 @@ PEAK_FP32_VALU_TFLOPS = 157.3
 PEAK_MFMA_F32_TFLOPS = 157.3          # fp32 tensors: v_mfma_f32_16x16x4_f32
 RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
 ALL = ["unet", "cosmoflow", "shard512", "late256", "single32"]
-OTHERS = ["table1", "chain512", "k5", "split256", "bn", "layer_f32"]
+OTHERS = ["table1", "chain512", "k5", "split256", "bn", "layer_f32", "faces512"]
 
 
 # ----------------------------------------------------------------------------------------------- CPU baseline
@@ -237,10 +237,16 @@ def build_workload(name, args, seed):
         return net, (f"CosmoFlow-shaped stack: N={args.batch} x 4x{args.width}^3, conv 16-32-64-128-256 + leaky-ReLU + avg-pool, "
                      f"dense 2048-256-4, MSE; fwd+bwd; {2 if net.overlap else 1} streams"), args.batch * args.width ** 3, args.dtype
     if name == "shard512":
-        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", faces_hw=True, fuse_pool=not args.unfused)
+        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", fuse_pool=not args.unfused)
         return net, ("one interior 8-way depth shard of a 4x512^3 sample: 4x66x512x512 bf16, conv 4->16 + leaky-ReLU + avg-pool "
                      + ("(three separate passes)" if args.unfused else "(one fused call, sign mask for the backward pass)") +
-                     ", bwd-data / bwd-filter, D halo faces packed and unpacked; H and W faces of g"), 64 * 512 * 512, "bf16"
+                     ", bwd-data / bwd-filter, D halo faces packed and unpacked"), 64 * 512 * 512, "bf16"
+    if name == "faces512":
+        # the H and W faces (1 and 2 voxels wide, both ends) of the same shard's 16-channel activation gradient
+        net = _single_layer(seed, 1, 4, 16, 64, 512, 64, 512, bf, field="cosmo", faces_hw=True)
+        net.ops = [o for o in net.ops if o["name"].startswith("face_")]
+        return net, ("H and W faces of a 16x66x512x512 bf16 activation gradient (a partitioning in H or W as well): pack and unpack, "
+                     "1 and 2 voxels wide, both ends"), 64 * 512 * 512, "bf16"
     if name == "late256":
         net = _single_layer(seed, 8, 256, 256, 16, 16, 0, 16, bf, pool=False)
         return net, "weight-gradient-bound late layer: N=8, 256->256 channels, 16^3, bf16, fwd / bwd-data / bwd-filter", 8 * 16 ** 3, "bf16"
