@@ -248,13 +248,13 @@ def build_workload(name, args, seed):
         return net, ("H and W faces of a 16x66x512x512 bf16 activation gradient (a partitioning in H or W as well): pack and unpack, "
                      "1 and 2 voxels wide, both ends"), 64 * 512 * 512, "bf16"
     if name == "late256":
-        net = _single_layer(seed, 8, 256, 256, 16, 16, 0, 16, bf, pool=False)
+        net = _single_layer(seed, 8, 256, 256, 16, 16, 0, 16, bf, pool=False, halo_ops=False)       # whole 16^3 volumes: no faces
         return net, "weight-gradient-bound late layer: N=8, 256->256 channels, 16^3, bf16, fwd / bwd-data / bwd-filter", 8 * 16 ** 3, "bf16"
     if name == "single32":
-        net = _single_layer(seed, 1, 4, 16, 32, 32, 0, 32, torch.float32, pool=False)
+        net = _single_layer(seed, 1, 4, 16, 32, 32, 0, 32, torch.float32, pool=False, halo_ops=False)
         return net, "single layer, fp32: N=1, 4->16 channels, 32^3, bias + leaky-ReLU, fwd / bwd-data / bwd-filter", 32 ** 3, "f32"
     if name == "layer_f32":
-        net = _single_layer(seed, 1, 32, 64, 32, 128, 0, 32, torch.float32, pool=False)
+        net = _single_layer(seed, 1, 32, 64, 32, 128, 0, 32, torch.float32, pool=False, halo_ops=False)
         return net, "one layer in the paper's precision: fp32 storage and arithmetic, 32->64 channels on 32x128x128, fwd / bwd-data / bwd-filter", 32 * 128 * 128, "f32"
     if name == "split256":
         net = _single_layer(seed, 1, 64, 64, 32, 256, 32, 256, bf, pool=False, split=True)

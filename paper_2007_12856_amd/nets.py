@@ -473,7 +473,7 @@ class SingleLayer:
     plane per side, the pooled gradient dp when pooling is on); buffers that are only written are made here."""
 
     def __init__(self, x: Slab, w, b, g: Slab, dp: Slab | None = None, pool=True, act=ACT_LEAKY, alpha=0.01, split=False, faces_hw=False,
-                 fuse_pool=False):
+                 fuse_pool=False, halo_ops=True):
         from . import FACE_D_HI, FACE_D_LO, halo_bytes, halo_pack, halo_unpack
         dev, dtype = x.t.device, x.t.dtype
         n, cin, _, hw, _ = x.t.shape
@@ -497,8 +497,10 @@ class SingleLayer:
         def op(name, fn, flops=0, nbytes=0):
             self.ops.append({"name": name, "fn": fn, "flops": int(flops), "bytes": int(nbytes)})
 
-        op("halo_pack_x", lambda: pack_faces(x, 1, faces[0], faces[1]), 0, 4 * faces[0].numel() * es)
-        op("halo_unpack_x", lambda: unpack_faces(faces[0], faces[1], x, 1), 0, 4 * faces[0].numel() * es)
+        # halo_ops=False: an unsharded volume (d_offset 0, d_global = d) has no neighbours and no face traffic
+        if halo_ops:
+            op("halo_pack_x", lambda: pack_faces(x, 1, faces[0], faces[1]), 0, 4 * faces[0].numel() * es)
+            op("halo_unpack_x", lambda: unpack_faces(faces[0], faces[1], x, 1), 0, 4 * faces[0].numel() * es)
         if fused:
             p = self.p = Slab(torch.empty((n, cout, d // 2, hw // 2, hw // 2), dtype=dtype, device=dev), 0, 0, d_offset // 2, d_global // 2)
             mask = self.mask = torch.empty((n * cout * d * hw * hw // 8,), dtype=torch.uint8, device=dev)
@@ -522,8 +524,9 @@ class SingleLayer:
             self.dp = dp
             op("pool_fwd", lambda: pool3d_fwd(z, p, POOL_AVG), 0, (z.t.numel() + p.t.numel()) * es)
             op("pool_bwd_act", lambda: pool3d_bwd_act(dp, None, z, g, POOL_AVG, act, alpha), 0, (dp.t.numel() + 2 * z.t.numel()) * es)
-        op("halo_pack_g", lambda: pack_faces(g, 1, gfaces[0], gfaces[1]), 0, 4 * gfaces[0].numel() * es)
-        op("halo_unpack_g", lambda: unpack_faces(gfaces[0], gfaces[1], g, 1), 0, 4 * gfaces[0].numel() * es)
+        if halo_ops:
+            op("halo_pack_g", lambda: pack_faces(g, 1, gfaces[0], gfaces[1]), 0, 4 * gfaces[0].numel() * es)
+            op("halo_unpack_g", lambda: unpack_faces(gfaces[0], gfaces[1], g, 1), 0, 4 * gfaces[0].numel() * es)
         if faces_hw:
             # H and W faces of the activation gradient (a partitioning in H or W as well, Sec. II-B): one and two
             # voxels wide, pack and unpack of both ends; bytes = face read + face written
