@@ -17,47 +17,53 @@ SEED = synth.BASE_SEED + 77
 BF = "bf16"
 
 
-def _noise(shape, seed):
+def _tdt(dtype):
+    import torch
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def _noise(shape, seed, dtype=BF):
     import torch
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
-    return torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    return torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(_tdt(dtype))
 
 
-def _planes(kind, stream, full_shape, g_lo, g_hi):
-    """bf16-rounded float64 global planes [g_lo, g_hi) of the seeded virtual tensor (zero outside the volume)."""
-    return quantize(synth.slab(kind, SEED, stream, full_shape, g_lo, g_hi), BF)
+def _planes(kind, stream, full_shape, g_lo, g_hi, dtype=BF):
+    """storage-rounded float64 global planes [g_lo, g_hi) of the seeded virtual tensor (zero outside the volume)."""
+    return quantize(synth.slab(kind, SEED, stream, full_shape, g_lo, g_hi), dtype)
 
 
-def _put(t, stored_lo, a):
+def _put(t, stored_lo, a, dtype=BF):
     """upload planes `a` into stored planes [stored_lo, ...) of device tensor t, clipped to what is stored"""
     lo, hi = max(stored_lo, 0), min(stored_lo + a.shape[2], t.shape[2])
     if hi > lo:
-        t[:, :, lo:hi] = to_dev(a[:, :, lo - stored_lo:hi - stored_lo], BF)
+        t[:, :, lo:hi] = to_dev(a[:, :, lo - stored_lo:hi - stored_lo], dtype)
 
 
 def sampled_conv_case(cin, cout, n, d, hw, halo_in, halo_out, d_offset, d_global, planes, nsub=8, kinds=("cosmo", "normal"),
-                      act=orc.ACT_LEAKY, alpha=0.01, stream=0):
+                      act=orc.ACT_LEAKY, alpha=0.01, stream=0, dtype=BF):
     """fwd / bwd-data / bwd-filter of one conv layer at full shape against sampled oracle outputs."""
     import torch
     import paper_2007_12856_amd as h3d
     H = W = hw
     b = np.sqrt(3.0 / (27 * cin))
-    w = quantize(synth.flat("uniform", SEED, stream + 1, (cout, cin, 3, 3, 3), -b, b), BF)
+    w = quantize(synth.flat("uniform", SEED, stream + 1, (cout, cin, 3, 3, 3), -b, b), dtype)
     bias = synth.round_f32(synth.flat("uniform", SEED, stream + 2, (cout,), -0.1, 0.1)).astype(np.float64)
-    wd, bd = to_dev(w, BF), to_dev(bias, "f32")
+    wd, bd = to_dev(w, dtype), to_dev(bias, "f32")
+    tdt, tol_w = _tdt(dtype), (1e-5 if dtype == "f32" else 2e-4)
     cos = np.unique(np.linspace(0, cout - 1, min(nsub, cout)).astype(int))
     cis = np.unique(np.linspace(0, cin - 1, min(nsub, cin)).astype(int))
     xfull, zfull = (n, cin, d_global, H, W), (n, cout, d_global, H, W)
 
     # ---------------- forward
-    x = h3d.Slab(_noise((n, cin, d + 2 * halo_in, H, W), 1), halo_in, halo_in, d_offset, d_global)
+    x = h3d.Slab(_noise((n, cin, d + 2 * halo_in, H, W), 1, dtype), halo_in, halo_in, d_offset, d_global)
     subs = {}
     for p in planes:      # local output plane index (may be a halo plane of z)
-        a = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2)
-        _put(x.t, p - 1 + halo_in, a)
+        a = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2, dtype)
+        _put(x.t, p - 1 + halo_in, a, dtype)
         subs[p] = orc.Slab(a, 1, 1, d_offset + p, d_global) if 0 <= d_offset + p < d_global else None
-    z = h3d.Slab(torch.empty((n, cout, d + 2 * halo_out, H, W), dtype=torch.bfloat16, device="cuda"), halo_out, halo_out,
+    z = h3d.Slab(torch.empty((n, cout, d + 2 * halo_out, H, W), dtype=tdt, device="cuda"), halo_out, halo_out,
                  d_offset, d_global)
     h3d.conv3d_fwd(x, wd, bd, z, act, alpha)
     for p in planes:
@@ -66,33 +72,33 @@ def sampled_conv_case(cin, cout, n, d, hw, halo_in, halo_out, d_offset, d_global
             assert not got.any()          # beyond the global boundary: zero padding of the next layer
             continue
         ref = orc.conv3d_fwd(subs[p], w[cos], bias[cos], act=act, alpha=alpha).a[:, :, 0]
-        close(got, ref, TOL[BF], f"fwd plane {p}")
+        close(got, ref, TOL[dtype], f"fwd plane {p}")
 
     # ---------------- backward-data (dz and the saved output z carry a 1-plane exchanged halo)
     ip = [p for p in planes if 0 <= p < d]
-    dz = h3d.Slab(_noise((n, cout, d + 2, H, W), 2), 1, 1, d_offset, d_global)
-    zs = h3d.Slab(_noise((n, cout, d + 2, H, W), 3), 1, 1, d_offset, d_global)
+    dz = h3d.Slab(_noise((n, cout, d + 2, H, W), 2, dtype), 1, 1, d_offset, d_global)
+    zs = h3d.Slab(_noise((n, cout, d + 2, H, W), 3, dtype), 1, 1, d_offset, d_global)
     dzp, zp = {}, {}
     for p in ip:
-        dzp[p] = _planes(kinds[1], stream + 4, zfull, d_offset + p - 1, d_offset + p + 2)
-        zp[p] = _planes("normal", stream + 5, zfull, d_offset + p - 1, d_offset + p + 2)
-        _put(dz.t, p, dzp[p])
-        _put(zs.t, p, zp[p])
-    dx = h3d.Slab(torch.empty((n, cin, d, H, W), dtype=torch.bfloat16, device="cuda"), 0, 0, d_offset, d_global)
+        dzp[p] = _planes(kinds[1], stream + 4, zfull, d_offset + p - 1, d_offset + p + 2, dtype)
+        zp[p] = _planes("normal", stream + 5, zfull, d_offset + p - 1, d_offset + p + 2, dtype)
+        _put(dz.t, p, dzp[p], dtype)
+        _put(zs.t, p, zp[p], dtype)
+    dx = h3d.Slab(torch.empty((n, cin, d, H, W), dtype=tdt, device="cuda"), 0, 0, d_offset, d_global)
     h3d.conv3d_bwd_data(dz, zs, wd, dx, act, alpha)
     for p in ip:
         ref = orc.conv3d_bwd_data(orc.Slab(dzp[p], 1, 1, d_offset + p, d_global), orc.Slab(zp[p], 1, 1, d_offset + p, d_global),
                                   w[:, cis], act=act, alpha=alpha).a[:, :, 0]
-        close(from_dev(dx.t[:, cis, p]), ref, TOL[BF], f"bwd_data plane {p}")
+        close(from_dev(dx.t[:, cis, p]), ref, TOL[dtype], f"bwd_data plane {p}")
 
     # ---------------- backward-filter: dz is zero outside the sampled planes on both sides
-    dz0 = h3d.Slab(torch.zeros((n, cout, d, H, W), dtype=torch.bfloat16, device="cuda"), 0, 0, d_offset, d_global)
+    dz0 = h3d.Slab(torch.zeros((n, cout, d, H, W), dtype=tdt, device="cuda"), 0, 0, d_offset, d_global)
     z0 = h3d.Slab(zs.t[:, :, 1:-1].contiguous(), 0, 0, d_offset, d_global)
     dw_ref, db_ref = 0.0, 0.0
     for p in ip:
-        _put(dz0.t, p, dzp[p][:, :, 1:2])
-        xa = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2)
-        _put(x.t, p - 1 + halo_in, xa)
+        _put(dz0.t, p, dzp[p][:, :, 1:2], dtype)
+        xa = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2, dtype)
+        _put(x.t, p - 1 + halo_in, xa, dtype)
         a, bq = orc.conv3d_bwd_filter(orc.Slab(xa[:, cis], 1, 1, d_offset + p, d_global),
                                       orc.Slab(dzp[p][:, cos, 1:2], 0, 0, d_offset + p, d_global),
                                       orc.Slab(zp[p][:, cos, 1:2], 0, 0, d_offset + p, d_global), act=act, alpha=alpha)
@@ -101,8 +107,8 @@ def sampled_conv_case(cin, cout, n, d, hw, halo_in, halo_out, d_offset, d_global
     db = torch.empty((cout,), device="cuda")
     h3d.conv3d_bwd_filter(x, dz0, z0, dw, db, act, alpha)
     got = from_dev(dw)[cos][:, cis]
-    close(got, dw_ref, 2e-4, "bwd_filter dw")
-    close(from_dev(db)[cos], db_ref, 2e-4, "bwd_filter db")
+    close(got, dw_ref, tol_w, "bwd_filter dw")
+    close(from_dev(db)[cos], db_ref, tol_w, "bwd_filter db")
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
     h3d.conv3d_bwd_filter(x, dz0, z0, dw2, db2, act, alpha)
     assert torch.equal(dw, dw2) and torch.equal(db, db2)      # deterministic split-spatial reduction
@@ -110,13 +116,13 @@ def sampled_conv_case(cin, cout, n, d, hw, halo_in, halo_out, d_offset, d_global
     # steps do it): at full shape this is the route to the unmasked kernels and their many-strip chunks
     dwu_ref, dbu_ref = 0.0, 0.0
     for p in ip:
-        xa = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2)
+        xa = _planes(kinds[0], stream + 3, xfull, d_offset + p - 1, d_offset + p + 2, dtype)
         a, bq = orc.conv3d_bwd_filter(orc.Slab(xa[:, cis], 1, 1, d_offset + p, d_global),
                                       orc.Slab(dzp[p][:, cos, 1:2], 0, 0, d_offset + p, d_global), None, act=orc.ACT_NONE)
         dwu_ref, dbu_ref = dwu_ref + a, dbu_ref + bq
     h3d.conv3d_bwd_filter(x, dz0, None, dw, db, h3d.ACT_NONE, 0.0)
-    close(from_dev(dw)[cos][:, cis], dwu_ref, 2e-4, "unmasked bwd_filter dw")
-    close(from_dev(db)[cos], dbu_ref, 2e-4, "unmasked bwd_filter db")
+    close(from_dev(dw)[cos][:, cis], dwu_ref, tol_w, "unmasked bwd_filter dw")
+    close(from_dev(db)[cos], dbu_ref, tol_w, "unmasked bwd_filter db")
     h3d.conv3d_bwd_filter(x, dz0, None, dw2, db2, h3d.ACT_NONE, 0.0)
     assert torch.equal(dw, dw2) and torch.equal(db, db2)
     return z
@@ -275,6 +281,12 @@ def test_cfg2_cosmoflow_stack_full_size():
         dxi = orc.conv3d_bwd_data(gq, None, w)
         close(from_dev((net.dx if i == 0 else net.dout[i - 1]).t), dxi.a, tol, f"stage {i + 1} dx")
         del g, gq, dw, db, dxi, zq, dpq, xin
+
+
+def test_fp32_layer_of_the_bench_full_size():
+    """The fp32 layer that `bench.py --workload layer_f32` times (32->64 channels on a whole 32x128x128 volume): the fp32
+    matrix-core kernels at their 8-row, two-half tiles, against sampled oracle planes at the fp32 bar."""
+    sampled_conv_case(32, 64, 1, 32, 128, 1, 0, 0, 32, [0, 15, 31], kinds=("normal", "normal"), stream=400, dtype="f32")
 
 
 # ---------------------------------------------------------------- configuration 3
