@@ -14,6 +14,12 @@
 //    one row of the tile and keeps 27 accumulator tiles (one per tap) plus one for the bias gradient (the product of g
 //    with a column of ones).  The four wavefronts' sums are added in wavefront order, the chunks' partial sums in
 //    chunk order by a second kernel: the same bits on every run.
+//  * tile variants, chosen by shape alone (so a shard, a plane-run view and the whole slab sum every voxel in the same
+//    order): 2-row tiles when the 8-row tiles would leave most of the chip idle; 16-column tiles for volumes at most 16
+//    voxels wide; thin forms for a side with at most 4 channels (a first layer's BD and BF), where three taps share one
+//    product in the rows / columns of the 16 x 16 tile that would otherwise be padding.
+//  * every load goes through a buffer resource: an element outside the volume, or of a channel the tensor does not
+//    have, gets an offset beyond the resource and reads as zero without a branch.
 #include <algorithm>
 
 #include "common.h"
