@@ -1091,7 +1091,9 @@ static BfPlan bf_plan_mfma(const h3d_tensor* x, int cout, bool roll) {
     if (p.cib == 1 && cout > 16 && cout <= 32) { p.rbw = 2; p.nrg = 1; p.th = 6; }   // one 3-wavefront row group, taller tiles
     if (x->c <= 4) {    // first-layer kernel: one wavefront covers all taps, 8 wavefronts split the tile's rows
       p.smallci = false;
-      p.rbw = cout > 16 ? 2 : 1;
+      // wide volumes: 16 output channels per workgroup whatever Cout is (every group reads its own channels of g once;
+      // only the few input channels are read once per group), so that the 64-column form below serves them all
+      p.rbw = (cout > 16 && x->w < 64) ? 2 : 1;
       p.nrg = 1;
       p.th = p.rbw == 2 ? 16 : 32;
       if (p.rbw == 1 && x->w >= 64) { p.tw = 64; p.th = 8; }     // whole 128-byte lines per tile row; 4 wavefronts, two workgroups per CU
