@@ -7,7 +7,8 @@ A "step" is one pass of the whole hot path of a configuration over one synthetic
   cosmoflow (configuration 2) the CosmoFlow-shaped stack, N=4 x 4x128^3, bf16, forward + backward;
   shard512  (configuration 3) conv 4->16 + leaky-ReLU + avg-pool + the D halo faces on one 8-way depth shard of a 4x512^3 sample;
   late256   (configuration 5) the weight-gradient-bound late layer, N=8, 256->256 channels on 16^3;
-  single32  (configuration 1) one fp32 layer, 4->16 channels on 32^3 (the correctness-sized case).
+  single32  (configuration 1) one fp32 layer, 4->16 channels on 32^3 (the correctness-sized case);
+  layer_f32 (beside the five) one fp32 layer of 32->64 channels on 32x128x128: the fp32 matrix-core kernels under load.
 For each: W warm-up steps, then EXACTLY K timed steps between two device synchronisations (wall clock), then P >= 10
 passes with one HIP-event pair per library call (recorded on the launch stream) whose medians fill the per-call table.
 
@@ -38,6 +39,9 @@ PEAK_FP32_VALU_TFLOPS = 157.3
 PEAK_MFMA_F32_TFLOPS = 157.3          # fp32 tensors: v_mfma_f32_16x16x4_f32
 RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
 ALL = ["unet", "cosmoflow", "shard512", "late256", "single32"]
+# measured in the default run beside the five configurations: an fp32 layer large enough to load the fp32 matrix cores
+# (configuration 1, the only fp32 one, is launch-latency-sized)
+EXTRA = ["layer_f32"]
 OTHERS = ["table1", "chain512", "k5", "split256", "bn", "layer_f32", "faces512"]
 
 
@@ -562,7 +566,7 @@ def main():
         halo_rate = {"call": "halo_pack, 2 planes of 8 x 32 x 512 x 512 bf16", "bytes_read_plus_written": nbytes, "ms": round(ms, 4),
                      "gbs": round(nbytes / ms / 1e6, 1), "hbm_frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
         del t, buf
-    names = ALL if args.workload == "all" else [args.workload]
+    names = ALL + EXTRA if args.workload == "all" else [args.workload]
     head = names[0]
     passes = max(args.passes, 10)
     results = {}
