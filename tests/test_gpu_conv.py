@@ -402,6 +402,50 @@ def test_conv3d_fp32_matrix_core_kernels(shape):
     close(from_dev(dw2), dwo_n, 1e-5)
 
 
+def _f32_random_shapes(k=12):
+    rng = np.random.default_rng(SEED + 99)
+    out = []
+    for _ in range(k):
+        ci = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 17, 24, 33]))
+        co = int(rng.choice([1, 3, 4, 5, 9, 16, 17, 20, 32, 35]))
+        d, halo = int(rng.integers(1, 8)), int(rng.integers(0, 2))
+        out.append((int(rng.integers(1, 3)), ci, co, d, int(rng.integers(1, 23)), int(rng.choice([3, 8, 12, 16, 17, 31, 32, 40, 66])), halo,
+                    int(rng.choice([0, 4])) if halo else 0))
+    return out
+
+
+@pytest.mark.parametrize("shape", _f32_random_shapes())
+def test_conv3d_fp32_random_shapes(shape):
+    """Seeded random shapes for the fp32 matrix-core kernels: channel counts on either side of the thin / one-block /
+    two-block forms, widths on either side of the 16-column tiles, ragged rows, planes and halos in combinations nobody
+    picked by hand; all three passes with the fused activation derivative, against the oracle at the fp32 bar."""
+    import torch
+    import paper_2007_12856_amd as h3d
+    N, Ci, Co, D, H, W, halo, off = shape
+    Dg = off + D + (4 if halo else 0)
+    alpha = 0.01
+    w, bias = _weights(Ci, Co, "f32", 70)
+    wd, bd = to_dev(w, "f32"), to_dev(bias, "f32")
+    hl = (halo, halo)
+    xo, xg = slab_pair(synth.flat("normal", SEED, 71, (N, Ci, D + 2 * halo, H, W)), "f32", hl, off, Dg)
+    zo = orc.conv3d_fwd(xo, w, bias, act=orc.ACT_LEAKY, alpha=alpha)
+    zg = h3d.conv3d_fwd(xg, wd, bd, dev_like(zo, "f32"), h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel().startswith("conv3d_f32_mfma_kernel"), h3d.h3d_last_kernel()
+    close(from_dev(zg.t), zo.a, 1e-5, f"fwd {shape}")
+    zso, zsg = slab_pair(synth.flat("normal", SEED, 73, (N, Co, D + 2 * halo, H, W)), "f32", hl, off, Dg)
+    dzo, dzg = slab_pair(synth.flat("normal", SEED, 72, (N, Co, D + 2 * halo, H, W)), "f32", hl, off, Dg)
+    dxo = orc.conv3d_bwd_data(dzo, zso, w, act=orc.ACT_LEAKY, alpha=alpha)
+    dxg = h3d.conv3d_bwd_data(dzg, zsg, wd, dev_like(dxo, "f32"), h3d.ACT_LEAKY, alpha)
+    close(from_dev(dxg.t), dxo.a, 1e-5, f"bwd_data {shape}")
+    dwo, dbo = orc.conv3d_bwd_filter(xo, dzo, zso, act=orc.ACT_LEAKY, alpha=alpha)
+    dw = torch.full((Co, Ci, 3, 3, 3), 777.0, device="cuda")
+    db = torch.full((Co,), 777.0, device="cuda")
+    h3d.conv3d_bwd_filter(xg, dzg, zsg, dw, db, h3d.ACT_LEAKY, alpha)
+    assert h3d.h3d_last_kernel().startswith("bwd_filter_f32_mfma_kernel"), h3d.h3d_last_kernel()
+    close(from_dev(dw), dwo, 1e-5, f"dw {shape}")
+    close(from_dev(db), dbo, 1e-5, f"db {shape}")
+
+
 def test_conv3d_fp32_every_instance_was_run():
     """The shapes above reach the instances of the fp32 forward / backward-data kernel (channel-block form x tile rows x
     tile halves) (collected from the library's
